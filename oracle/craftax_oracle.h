@@ -1,0 +1,116 @@
+/*
+ * CPU oracle for the Craftax-Classic reset/step/observe path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is a plain, single-threaded, deliberately slow
+ * simulator used to check the GPU library.  It shares no code, header, table or
+ * constant generator with the HIP implementation, and nothing in the product path
+ * may call it.
+ *
+ * What the paper fixes (and this oracle follows): the 17-entry action table and
+ * the 22 achievements with ids 0..21 (appendix "Action Space" / "Achievements"),
+ * block ids 2..16 (appendix "Block Types"), creature health/damage (appendix
+ * "Creatures": zombie 5/2, skeleton 3/2, cow 3), fixed-capacity masked creature
+ * and plant tables (appendix "Differences between Craftax-Classic and Crafter"),
+ * a 7x9 symbolic view and a flat length of 1345 (section "RL Environment
+ * Interface", appendix "Observation Space"), +1 reward per first-time
+ * achievement and +-0.1 per health point (section "RL Environment Interface"),
+ * and auto-reset on done (appendix "Optimistic Environment Resets").
+ *
+ * The paper does not print the game rules themselves ("mimic Crafter").  Every
+ * rule below that the paper is silent on is this build's own frozen reading; such
+ * functions are marked "parity unpinned" beyond the invariants the tests check.
+ */
+#ifndef CRAFTAX_ORACLE_H
+#define CRAFTAX_ORACLE_H
+
+#include <stdint.h>
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ORC_MAP 64
+#define ORC_NMOB 12   /* slots 0-2 zombie, 3-5 cow, 6-8 skeleton, 9-11 arrow */
+#define ORC_NPLANT 10
+#define ORC_VIEW_ROWS 7
+#define ORC_VIEW_COLS 9
+#define ORC_NBLOCK 17
+#define ORC_NCHAN 21  /* 17 block channels + zombie, cow, skeleton, arrow */
+#define ORC_NVEC 22
+
+typedef struct {
+    uint32_t max_episode_steps;
+    uint32_t day_length;     /* even, 2..1024 */
+    uint32_t cap_zombie, cap_cow, cap_skeleton, cap_arrow; /* each 0..3 */
+    uint32_t cap_plant;      /* 0..10 */
+    uint64_t atlas_seed;     /* pixel observations only */
+} orc_config;
+
+typedef struct {
+    uint8_t alive, x, y, dir;
+    int8_t hp;
+    uint8_t cd;
+    uint8_t pad[2];
+} orc_mob;
+
+typedef struct {
+    uint8_t alive, x, y, pad;
+    uint16_t age;
+} orc_plant;
+
+/* One environment, canonical layout (4304 bytes, little endian, no hidden padding).
+ * Dead mob / plant slots hold all-zero fields. */
+typedef struct {
+    uint8_t map[ORC_MAP * ORC_MAP];  /* row-major, index y*64+x, block ids */
+    uint8_t px, py, dir, sleeping;   /* dir: 1 LEFT 2 RIGHT 3 UP 4 DOWN */
+    uint8_t inv[12];  /* wood stone coal iron diamond sapling, wood/stone/iron pickaxe, wood/stone/iron sword */
+    int8_t vit[4];    /* health food drink energy */
+    int16_t cnt[4];   /* hunger thirst fatigue recover */
+    uint32_t ach;     /* bit i = achievement id i */
+    uint32_t t;       /* steps taken in this episode */
+    uint32_t episode; /* resets since orc_reset */
+    uint64_t seed;
+    orc_mob mob[ORC_NMOB];
+    orc_plant plant[ORC_NPLANT];
+    uint32_t env;     /* environment index, part of every Philox counter */
+} orc_env;
+
+enum { ORC_OBS_SYM_U8_I8 = 0, ORC_OBS_SYM_U8_F32 = 1, ORC_OBS_SYM_F32 = 2, ORC_OBS_PIXELS_F32 = 3 };
+
+size_t orc_env_bytes(void);
+size_t orc_obs_bytes(int obs_mode);
+
+/* Philox4x32-10 (Salmon et al., SC'11). */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+/* One inverse round and one forward round, exposed for the bijection test. */
+void orc_philox_round(uint32_t c[4], const uint32_t k[2]);
+void orc_philox_round_inv(uint32_t c[4], const uint32_t k[2]);
+void orc_philox_batch(const uint32_t *ctrs, const uint32_t *keys, uint32_t *out, int n);
+
+void orc_default_config(orc_config *cfg);
+void orc_worldgen(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode);
+void orc_reset(orc_env *e, const orc_config *cfg, uint64_t seed, uint32_t env);
+/* Rules only: no auto-reset.  Returns reward/done of the step just taken. */
+void orc_step_rules(orc_env *e, const orc_config *cfg, int32_t action, float *reward, uint8_t *done);
+/* Rules, then auto-reset to a fresh episode if done. */
+void orc_step(orc_env *e, const orc_config *cfg, int32_t action, float *reward, uint8_t *done);
+void orc_observe(const orc_env *e, const orc_config *cfg, int obs_mode, void *obs);
+
+/* Batched helpers: loop the above over n environments, serially. */
+void orc_reset_batch(orc_env *envs, const orc_config *cfg, const uint64_t *seeds,
+                     const uint32_t *env_ids, int n);
+void orc_step_batch(orc_env *envs, const orc_config *cfg, const int32_t *actions, int obs_mode,
+                    void *obs, float *reward, uint8_t *done, int n);
+void orc_observe_batch(const orc_env *envs, const orc_config *cfg, int obs_mode, void *obs, int n);
+
+/* Small accessors for tests. */
+float orc_daylight(const orc_config *cfg, uint32_t t);
+uint32_t orc_zombie_spawn_threshold(const orc_config *cfg, uint32_t t);
+uint32_t orc_step_draw(const orc_env *e, uint32_t block, uint32_t word);
+uint32_t orc_value_noise(const uint16_t *lattice, int width, int spacing, int x, int y);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,151 @@
+"""ctypes loader for the CPU oracle (liboracle.so).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+cpu_baseline leg.  The GPU library never touches this.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SOURCES = ["philox.c", "classic.c"]
+LIB_PATH = os.path.join(_HERE, "liboracle.so")
+
+OBS_SYM_U8_I8, OBS_SYM_U8_F32, OBS_SYM_F32, OBS_PIXELS_F32 = 0, 1, 2, 3
+OBS_BYTES = {0: 1360, 1: 1424, 2: 5392, 3: 47632}
+
+MOB_DTYPE = np.dtype([("alive", "u1"), ("x", "u1"), ("y", "u1"), ("dir", "u1"), ("hp", "i1"),
+                      ("cd", "u1"), ("pad", "u1", (2,))])
+PLANT_DTYPE = np.dtype([("alive", "u1"), ("x", "u1"), ("y", "u1"), ("pad", "u1"), ("age", "<u2")])
+ENV_DTYPE = np.dtype([
+    ("map", "u1", (64, 64)),
+    ("px", "u1"), ("py", "u1"), ("dir", "u1"), ("sleeping", "u1"),
+    ("inv", "u1", (12,)),
+    ("vit", "i1", (4,)),
+    ("cnt", "<i2", (4,)),
+    ("ach", "<u4"), ("t", "<u4"), ("episode", "<u4"),
+    ("seed", "<u8"),
+    ("mob", MOB_DTYPE, (12,)),
+    ("plant", PLANT_DTYPE, (10,)),
+    ("env", "<u4"),
+])
+assert ENV_DTYPE.itemsize == 4304
+
+
+class Config(ctypes.Structure):
+    _fields_ = [("max_episode_steps", ctypes.c_uint32), ("day_length", ctypes.c_uint32),
+                ("cap_zombie", ctypes.c_uint32), ("cap_cow", ctypes.c_uint32),
+                ("cap_skeleton", ctypes.c_uint32), ("cap_arrow", ctypes.c_uint32),
+                ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64)]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C11, contraction off so floats are single IEEE ops)."""
+    srcs = [os.path.join(_HERE, s) for s in _SOURCES]
+    deps = srcs + [os.path.join(_HERE, "craftax_oracle.h")]
+    if not force and os.path.exists(LIB_PATH) and all(
+            os.path.getmtime(LIB_PATH) >= os.path.getmtime(d) for d in deps):
+        return LIB_PATH
+    cmd = ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-ffp-contract=off", "-fPIC", "-shared",
+           "-o", LIB_PATH] + srcs + ["-lm"]
+    subprocess.run(cmd, check=True)
+    return LIB_PATH
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(LIB_PATH)
+        L.orc_env_bytes.restype = ctypes.c_size_t
+        L.orc_obs_bytes.restype = ctypes.c_size_t
+        L.orc_daylight.restype = ctypes.c_float
+        L.orc_zombie_spawn_threshold.restype = ctypes.c_uint32
+        L.orc_step_draw.restype = ctypes.c_uint32
+        L.orc_value_noise.restype = ctypes.c_uint32
+        assert L.orc_env_bytes() == ENV_DTYPE.itemsize
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def default_config(**overrides) -> Config:
+    cfg = Config()
+    lib().orc_default_config(ctypes.byref(cfg))
+    for k, v in overrides.items():
+        setattr(cfg, k, v)
+    return cfg
+
+
+def philox(ctr, key):
+    c = (ctypes.c_uint32 * 4)(*[int(x) for x in ctr])
+    k = (ctypes.c_uint32 * 2)(*[int(x) for x in key])
+    o = (ctypes.c_uint32 * 4)()
+    lib().orc_philox4x32_10(c, k, o)
+    return [int(x) for x in o]
+
+
+def worldgen(seed: int, env: int, episode: int = 0) -> np.ndarray:
+    m = np.zeros((64, 64), np.uint8)
+    lib().orc_worldgen(_p(m), ctypes.c_uint64(seed), ctypes.c_uint32(env), ctypes.c_uint32(episode))
+    return m
+
+
+class Oracle:
+    """n independent environments stepped serially on the host."""
+
+    def __init__(self, n: int, cfg: Config | None = None, obs_mode: int = OBS_SYM_U8_F32):
+        self.n = n
+        self.cfg = cfg if cfg is not None else default_config()
+        self.obs_mode = obs_mode
+        self.envs = np.zeros(n, dtype=ENV_DTYPE)
+        self.obs = np.zeros((n, OBS_BYTES[obs_mode]), np.uint8)
+        self.reward = np.zeros(n, np.float32)
+        self.done = np.zeros(n, np.uint8)
+
+    def reset(self, seeds, env_ids=None):
+        seeds = np.ascontiguousarray(seeds, dtype=np.uint64)
+        ids = None if env_ids is None else np.ascontiguousarray(env_ids, dtype=np.uint32)
+        lib().orc_reset_batch(_p(self.envs), ctypes.byref(self.cfg), _p(seeds),
+                              None if ids is None else _p(ids), self.n)
+        return self.observe()
+
+    def observe(self):
+        lib().orc_observe_batch(_p(self.envs), ctypes.byref(self.cfg), self.obs_mode, _p(self.obs), self.n)
+        return self.obs
+
+    def step(self, actions, render: bool = True):
+        a = np.ascontiguousarray(actions, dtype=np.int32)
+        assert a.shape == (self.n,)
+        lib().orc_step_batch(_p(self.envs), ctypes.byref(self.cfg), _p(a), self.obs_mode,
+                             _p(self.obs) if render else None, _p(self.reward), _p(self.done), self.n)
+        return self.obs, self.reward, self.done
+
+    def step_rules_one(self, i: int, action: int):
+        """Rules without auto-reset on environment i; returns (reward, done)."""
+        r = ctypes.c_float()
+        d = ctypes.c_uint8()
+        ptr = ctypes.c_void_p(self.envs.ctypes.data + i * ENV_DTYPE.itemsize)
+        lib().orc_step_rules(ptr, ctypes.byref(self.cfg), ctypes.c_int32(action), ctypes.byref(r), ctypes.byref(d))
+        return r.value, d.value
+
+    def observe_one(self, i: int, mode: int | None = None) -> np.ndarray:
+        mode = self.obs_mode if mode is None else mode
+        out = np.zeros(OBS_BYTES[mode], np.uint8)
+        ptr = ctypes.c_void_p(self.envs.ctypes.data + i * ENV_DTYPE.itemsize)
+        lib().orc_observe(ptr, ctypes.byref(self.cfg), mode, _p(out))
+        return out
+
+    def draw(self, i: int, block: int, word: int) -> int:
+        ptr = ctypes.c_void_p(self.envs.ctypes.data + i * ENV_DTYPE.itemsize)
+        return int(lib().orc_step_draw(ptr, ctypes.c_uint32(block), ctypes.c_uint32(word)))

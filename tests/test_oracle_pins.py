@@ -1,0 +1,895 @@
+"""Pins for the CPU oracle: things the paper and the mathematics fix, checked without any
+reference to the GPU path.  A plausible slip in the oracle (dropped term, wrong sign or
+index, transposed operand) should fail at least one of these."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from oracle import pyoracle as po
+from paper_2402_16801_amd import synth
+
+L = po.lib()
+
+GRASS, WATER, STONE, TREE, WOOD, PATH, COAL, IRON, DIAMOND, TABLE, FURNACE, SAND, LAVA, PLANT, RIPE = range(2, 17)
+(NOOP, LEFT, RIGHT, UP, DOWN, DO, SLEEP, PLACE_STONE, PLACE_TABLE, PLACE_FURNACE, PLACE_PLANT,
+ MK_WP, MK_SP, MK_IP, MK_WS, MK_SS, MK_IS) = range(17)
+I_WOOD, I_STONE, I_COAL, I_IRON, I_DIAMOND, I_SAPLING, I_WP, I_SP, I_IP, I_WS, I_SS, I_IS = range(12)
+HEALTH, FOOD, DRINK, ENERGY = range(4)
+HUNGER, THIRST, FATIGUE, RECOVER = range(4)
+
+
+# ---------------------------------------------------------------- Philox ----
+def test_philox_two_implementations_agree():
+    rng = np.random.default_rng(1)
+    n = 1_000_000
+    ctrs = rng.integers(0, 2**32, size=(n, 4), dtype=np.uint64).astype(np.uint32)
+    keys = rng.integers(0, 2**32, size=(n, 2), dtype=np.uint64).astype(np.uint32)
+    keys[:] = keys[0]  # the numpy version takes one key per call
+    out = np.zeros((n, 4), np.uint32)
+    L.orc_philox_batch(ctrs.ctypes.data_as(ctypes.c_void_p), keys.ctypes.data_as(ctypes.c_void_p),
+                       out.ctypes.data_as(ctypes.c_void_p), n)
+    ref = synth.philox4x32_10(ctrs[:, 0], ctrs[:, 1], ctrs[:, 2], ctrs[:, 3], int(keys[0, 0]), int(keys[0, 1]))
+    for w in range(4):
+        assert np.array_equal(out[:, w], ref[w])
+
+
+def _philox_bigint(ctr, key):
+    """Third, independent writing of the definition with python integers."""
+    c = list(ctr)
+    k = list(key)
+    for r in range(10):
+        p0 = 0xD2511F53 * c[0]
+        p1 = 0xCD9E8D57 * c[2]
+        c = [(p1 >> 32) ^ c[1] ^ k[0], p1 & 0xFFFFFFFF, (p0 >> 32) ^ c[3] ^ k[1], p0 & 0xFFFFFFFF]
+        k = [(k[0] + 0x9E3779B9) & 0xFFFFFFFF, (k[1] + 0xBB67AE85) & 0xFFFFFFFF]
+    return c
+
+
+def test_philox_matches_bigint_definition():
+    rng = np.random.default_rng(2)
+    cases = [([0, 0, 0, 0], [0, 0]), ([0xFFFFFFFF] * 4, [0xFFFFFFFF] * 2)]
+    cases += [([int(v) for v in rng.integers(0, 2**32, 4)], [int(v) for v in rng.integers(0, 2**32, 2)])
+              for _ in range(200)]
+    for c, k in cases:
+        assert po.philox(c, k) == _philox_bigint(c, k)
+
+
+def test_philox_round_is_a_bijection():
+    rng = np.random.default_rng(3)
+    for _ in range(500):
+        c0 = [int(v) for v in rng.integers(0, 2**32, 4)]
+        k = (ctypes.c_uint32 * 2)(*[int(v) for v in rng.integers(0, 2**32, 2)])
+        c = (ctypes.c_uint32 * 4)(*c0)
+        L.orc_philox_round(c, k)
+        assert list(c) != c0
+        L.orc_philox_round_inv(c, k)
+        assert list(c) == c0
+
+
+def test_philox_output_is_roughly_uniform():
+    n = 200_000
+    w = synth.philox4x32_10(np.arange(n), 7, 9, 11, 123, 456)
+    allw = np.concatenate(w)
+    bits = np.unpackbits(allw.view(np.uint8))
+    assert abs(bits.mean() - 0.5) < 0.002
+    counts = np.bincount(allw.view(np.uint8), minlength=256)
+    expected = counts.sum() / 256
+    chi2 = ((counts - expected) ** 2 / expected).sum()
+    assert chi2 < 400  # 255 dof; 400 is far in the tail
+    # neighbouring counters are uncorrelated
+    a = w[0].astype(np.float64)
+    assert abs(np.corrcoef(a[:-1], a[1:])[0, 1]) < 0.01
+
+
+def test_choice_rule():
+    assert synth.choice(np.uint32(0), 17) == 0
+    assert synth.choice(np.uint32(0xFFFFFFFF), 17) == 16
+    u = np.arange(0, 2**32, 2**20, dtype=np.uint64).astype(np.uint32)
+    c = synth.choice(u, 5)
+    assert c.min() == 0 and c.max() == 4 and np.all(np.diff(c) >= 0)
+
+
+# ------------------------------------------------------------ day / night ----
+def test_daylight_closed_form():
+    cfg = po.default_config()
+    d = [L.orc_daylight(ctypes.byref(cfg), ctypes.c_uint32(t)) for t in range(600)]
+    assert d[0] == 1.0 and d[150] == 0.0 and d[300] == 1.0
+    assert d[75] == 0.5 and d[225] == 0.5            # smoothstep(1/2) = 1/2
+    assert d[:300] == d[300:]                        # period 300
+    assert all(d[t] == d[300 - t] for t in range(1, 150))
+    assert all(d[t] > d[t + 1] for t in range(0, 150))
+    # smoothstep(1/3) = 7/27
+    assert d[100] == np.float32(7.0 / 27.0)
+    # a different day length keeps the shape
+    cfg2 = po.default_config(day_length=40)
+    assert L.orc_daylight(ctypes.byref(cfg2), ctypes.c_uint32(10)) == 0.5
+
+
+def test_zombie_spawn_threshold_endpoints():
+    cfg = po.default_config()
+    assert L.orc_zombie_spawn_threshold(ctypes.byref(cfg), ctypes.c_uint32(0)) == 40 << 20
+    assert L.orc_zombie_spawn_threshold(ctypes.byref(cfg), ctypes.c_uint32(150)) == (40 + 3 * 255) << 20
+    th = [L.orc_zombie_spawn_threshold(ctypes.byref(cfg), ctypes.c_uint32(t)) for t in range(151)]
+    assert all(a <= b for a, b in zip(th, th[1:]))
+
+
+# ------------------------------------------------------------ value noise ----
+def _noise(lat, width, spacing, x, y):
+    lat = np.ascontiguousarray(lat, dtype=np.uint16)
+    return L.orc_value_noise(lat.ctypes.data_as(ctypes.c_void_p), width, spacing, x, y)
+
+
+@pytest.mark.parametrize("spacing,width", [(8, 9), (16, 5)])
+def test_value_noise_special_cases(spacing, width):
+    rng = np.random.default_rng(5)
+    lat = rng.integers(0, 65536, size=(width, width)).astype(np.uint16)
+    # lattice points reproduce the lattice exactly
+    for j in range(width - 1):
+        for i in range(width - 1):
+            assert _noise(lat, width, spacing, i * spacing, j * spacing) == lat[j, i]
+    # a constant lattice gives a constant field
+    const = np.full((width, width), 12345, np.uint16)
+    assert {_noise(const, width, spacing, x, y) for x in range(0, 64, 3) for y in range(0, 64, 5)} == {12345}
+    # half way between two lattice points the smooth weight is exactly 1/2
+    h = spacing // 2
+    a, b = int(lat[0, 0]), int(lat[0, 1])
+    assert _noise(lat, width, spacing, h, 0) == (a * 128 + b * 128) * 256 >> 16
+    # transposing the lattice transposes the field (x and y are not mixed up)
+    for x, y in [(3, 17), (40, 9), (63, 63), (0, 55)]:
+        assert _noise(lat, width, spacing, x, y) == _noise(lat.T.copy(), width, spacing, y, x)
+    # values stay between the four corner values
+    for x, y in [(5, 6), (21, 43), (62, 1)]:
+        i, j = x // spacing, y // spacing
+        corners = lat[j:j + 2, i:i + 2]
+        assert corners.min() <= _noise(lat, width, spacing, x, y) <= corners.max()
+
+
+# -------------------------------------------------------- world generation ----
+def test_worldgen_is_a_pure_function_and_varies():
+    a = po.worldgen(11, 3, 0)
+    assert np.array_equal(a, po.worldgen(11, 3, 0))
+    assert not np.array_equal(a, po.worldgen(12, 3, 0))
+    assert not np.array_equal(a, po.worldgen(11, 4, 0))
+    assert not np.array_equal(a, po.worldgen(11, 3, 1))
+
+
+def test_worldgen_histogram_and_start_area():
+    hist = np.zeros(17, np.int64)
+    for s in range(300):
+        m = po.worldgen(s, s, 0)
+        hist += np.bincount(m.ravel(), minlength=17)
+        assert np.all(m[30:35, 30:35] == GRASS)
+    natural = [GRASS, WATER, STONE, TREE, PATH, COAL, IRON, DIAMOND, SAND, LAVA]
+    assert all(hist[b] > 0 for b in natural)
+    placed_only = [0, 1, WOOD, TABLE, FURNACE, PLANT, RIPE]
+    assert all(hist[b] == 0 for b in placed_only)
+    frac = hist / hist.sum()
+    assert 0.25 < frac[GRASS] < 0.6 and 0.05 < frac[WATER] < 0.3 and 0.05 < frac[STONE] < 0.3
+    assert frac[DIAMOND] < frac[IRON] < frac[COAL] < frac[STONE]
+
+
+# ------------------------------------------------------------ helpers ----
+def blank(n=1, block=GRASS, caps=0, **cfgkw):
+    """Environments with a uniform map and, by default, spawning switched off."""
+    cfg = po.default_config(cap_zombie=caps, cap_cow=caps, cap_skeleton=caps, **cfgkw)
+    o = po.Oracle(n, cfg)
+    o.reset(synth.seeds_for(n))
+    o.envs["map"][:] = block
+    return o
+
+
+def step(o, a, i=0):
+    return o.step_rules_one(i, a)
+
+
+def snapshot(o, i=0):
+    return o.envs[i:i + 1].copy()
+
+
+# ------------------------------------------------------- hand-traced worlds ----
+def test_reset_state():
+    o = po.Oracle(3)
+    o.reset([5, 6, 7])
+    e = o.envs
+    assert list(e["px"]) == [32] * 3 and list(e["py"]) == [32] * 3 and list(e["dir"]) == [4] * 3
+    assert np.all(e["vit"] == 9) and np.all(e["inv"] == 0) and np.all(e["cnt"] == 0)
+    assert np.all(e["ach"] == 0) and np.all(e["t"] == 0) and np.all(e["episode"] == 0)
+    assert np.all(e["mob"]["alive"] == 0) and np.all(e["plant"]["alive"] == 0)
+    assert list(e["seed"]) == [5, 6, 7] and list(e["env"]) == [0, 1, 2]
+    assert np.array_equal(e["map"][1], po.worldgen(6, 1, 0))
+
+
+def test_movement_and_blocking():
+    o = blank()
+    e = o.envs[0]
+    assert step(o, LEFT) == (0.0, 0) and (e["px"], e["py"], e["dir"]) == (31, 32, 1)
+    step(o, UP); assert (e["px"], e["py"], e["dir"]) == (31, 31, 3)
+    step(o, RIGHT); assert (e["px"], e["py"], e["dir"]) == (32, 31, 2)
+    step(o, DOWN); assert (e["px"], e["py"], e["dir"]) == (32, 32, 4)
+    for b in (WATER, STONE, TREE, TABLE, FURNACE, COAL, IRON, DIAMOND, PLANT, RIPE):
+        e["map"][32, 33] = b
+        step(o, RIGHT)
+        assert (e["px"], e["py"], e["dir"]) == (32, 32, 2)
+    for b in (SAND, PATH):
+        e["map"][32, 33] = b
+        step(o, RIGHT); assert e["px"] == 33
+        step(o, LEFT); assert e["px"] == 32
+    # a mob blocks; the facing still turns
+    e["mob"][3] = (1, 32, 31, 0, 3, 0, (0, 0))
+    o.cfg.cap_cow = 0
+    before = (e["px"], e["py"])
+    step(o, UP)
+    assert (e["px"], e["py"]) == before and e["dir"] == 3
+    # map edges block
+    e["mob"][3] = (0, 0, 0, 0, 0, 0, (0, 0))
+    e["px"], e["py"] = 0, 0
+    step(o, LEFT); step(o, UP)
+    assert (e["px"], e["py"]) == (0, 0)
+    e["px"], e["py"] = 63, 63
+    step(o, RIGHT); step(o, DOWN)
+    assert (e["px"], e["py"]) == (63, 63)
+
+
+def test_lava_kills():
+    o = blank()
+    e = o.envs[0]
+    e["map"][33, 32] = LAVA
+    r, d = step(o, DOWN)
+    assert d == 1 and e["vit"][HEALTH] == 0 and (e["px"], e["py"]) == (32, 33)
+    assert r == np.float32(-9) * np.float32(0.1)
+
+
+def test_collect_wood_table_pickaxe_stone_chain():
+    o = blank()
+    e = o.envs[0]
+    e["map"][33, 32] = TREE
+    r, _ = step(o, DO)
+    assert r == np.float32(10) * np.float32(0.1) and e["inv"][I_WOOD] == 1 and e["ach"] == 1 << 0
+    for k in range(2, 10):
+        r, _ = step(o, DO)
+        assert r == 0.0 and e["inv"][I_WOOD] == k
+    step(o, DO)
+    assert e["inv"][I_WOOD] == 9 and e["map"][33, 32] == TREE      # saturates, tree stays
+    # table needs a free ground cell in front
+    r, _ = step(o, PLACE_TABLE)
+    assert r == 0.0 and e["inv"][I_WOOD] == 9                       # facing a tree: no-op
+    step(o, LEFT)                                                   # now at (31,32) facing left
+    r, _ = step(o, PLACE_TABLE)
+    assert r == np.float32(1.0) and e["map"][32, 30] == TABLE and e["inv"][I_WOOD] == 8
+    r, _ = step(o, MK_WP)
+    assert r == np.float32(1.0) and e["inv"][I_WP] == 1 and e["inv"][I_WOOD] == 7
+    r, _ = step(o, MK_WP)
+    assert r == 0.0 and e["inv"][I_WOOD] == 7                       # tools are made once
+    r, _ = step(o, MK_WS)
+    assert r == np.float32(1.0) and e["inv"][I_WS] == 1 and e["inv"][I_WOOD] == 6
+    # stone: gate on the wood pickaxe
+    e["map"][31, 31] = STONE
+    step(o, UP)
+    e["inv"][I_WP] = 0
+    r, _ = step(o, DO)
+    assert r == 0.0 and e["inv"][I_STONE] == 0 and e["map"][31, 31] == STONE
+    e["inv"][I_WP] = 1
+    r, _ = step(o, DO)
+    assert r == np.float32(1.0) and e["inv"][I_STONE] == 1 and e["map"][31, 31] == PATH
+    # stone pickaxe: 1 wood + 1 stone by the table (table at (30,32) is diagonal-adjacent? no: player at (31,32))
+    r, _ = step(o, MK_SP)
+    assert r == np.float32(1.0) and e["inv"][I_SP] == 1 and e["inv"][I_STONE] == 0 and e["inv"][I_WOOD] == 5
+    # away from the table nothing can be made
+    e["px"] = 40
+    e["inv"][I_STONE] = 3
+    r, _ = step(o, MK_SS)
+    assert r == 0.0 and e["inv"][I_SS] == 0 and e["inv"][I_STONE] == 3
+
+
+def test_ore_gates_and_iron_tools():
+    o = blank()
+    e = o.envs[0]
+    gates = [(COAL, I_COAL, I_WP, 17), (IRON, I_IRON, I_SP, 18), (DIAMOND, I_DIAMOND, I_IP, 19)]
+    for block, item, tool, ach in gates:
+        e["map"][33, 32] = block
+        r, _ = step(o, DO)
+        assert r == 0.0 and e["inv"][item] == 0 and e["map"][33, 32] == block
+        e["inv"][tool] = 1
+        r, _ = step(o, DO)
+        assert r == np.float32(1.0) and e["inv"][item] == 1 and e["map"][33, 32] == PATH
+        assert e["ach"] >> ach & 1
+    # iron tools need table AND furnace, and wood + coal + iron
+    e["inv"][I_WOOD] = 2
+    e["map"][31, 31] = TABLE
+    r, _ = step(o, MK_IP)
+    assert r == 0.0
+    e["map"][31, 33] = FURNACE
+    e["inv"][I_IP] = 0
+    r, _ = step(o, MK_IP)
+    assert r == np.float32(1.0) and e["inv"][I_IP] == 1
+    assert (e["inv"][I_WOOD], e["inv"][I_COAL], e["inv"][I_IRON]) == (1, 0, 0)
+    r, _ = step(o, MK_IS)
+    assert r == 0.0 and e["inv"][I_IS] == 0                         # no coal / iron left
+    e["inv"][I_COAL] = e["inv"][I_IRON] = 1
+    r, _ = step(o, MK_IS)
+    assert r == np.float32(1.0) and e["inv"][I_IS] == 1 and e["inv"][I_WOOD] == 0
+
+
+def test_place_stone_furnace_plant():
+    o = blank()
+    e = o.envs[0]
+    for target in (GRASS, SAND, PATH, WATER, LAVA):
+        e["inv"][I_STONE] = 1
+        e["map"][33, 32] = target
+        step(o, PLACE_STONE)
+        assert e["map"][33, 32] == STONE and e["inv"][I_STONE] == 0
+    assert e["ach"] == 1 << 10
+    e["inv"][I_STONE] = 1
+    e["map"][33, 32] = TREE
+    step(o, PLACE_STONE)
+    assert e["map"][33, 32] == TREE and e["inv"][I_STONE] == 1
+    # furnace needs a table nearby
+    e["map"][33, 32] = GRASS
+    step(o, PLACE_FURNACE)
+    assert e["map"][33, 32] == GRASS
+    e["map"][31, 33] = TABLE
+    r, _ = step(o, PLACE_FURNACE)
+    assert e["map"][33, 32] == FURNACE and e["inv"][I_STONE] == 0 and r == np.float32(1.0)
+    # plant: only on grass, needs a sapling; tracked in the plant table
+    step(o, LEFT)
+    e["inv"][I_SAPLING] = 2
+    e["map"][32, 30] = SAND
+    step(o, PLACE_PLANT)
+    assert e["map"][32, 30] == SAND and e["inv"][I_SAPLING] == 2
+    e["map"][32, 30] = GRASS
+    r, _ = step(o, PLACE_PLANT)
+    assert r == np.float32(1.0) and e["map"][32, 30] == PLANT and e["inv"][I_SAPLING] == 1
+    p = e["plant"][0]
+    assert (p["alive"], p["x"], p["y"]) == (1, 30, 32) and p["age"] == 1   # aged once by this step
+
+
+def test_plant_ripens_and_is_eaten_by_player():
+    o = blank()
+    e = o.envs[0]
+    e["inv"][I_SAPLING] = 1
+    step(o, PLACE_PLANT)
+    for _ in range(298):
+        step(o, NOOP)
+    assert e["plant"][0]["age"] == 299 and e["map"][33, 32] == PLANT
+    step(o, NOOP)
+    assert e["plant"][0]["age"] == 300 and e["map"][33, 32] == RIPE
+    e["vit"][FOOD] = 3
+    e["cnt"][HUNGER] = 20
+    r, _ = step(o, DO)
+    assert e["vit"][FOOD] == 7 and e["map"][33, 32] == PLANT and e["ach"] >> 11 & 1
+    assert e["plant"][0]["age"] == 1 and e["cnt"][HUNGER] == 2      # hunger reset, then this step's +2
+    # DO on an unripe plant does nothing
+    before = snapshot(o)
+    step(o, DO)
+    after = snapshot(o)
+    step_noop = blank()
+    assert after["inv"].tolist() == before["inv"].tolist() and after["map"].tolist() == before["map"].tolist()
+
+
+def test_zombie_eats_plant_with_probability_one_eighth():
+    eaten = 0
+    trials = 400
+    for s in range(trials):
+        o = blank()
+        o.envs["seed"][0] = 1000 + s
+        e = o.envs[0]
+        e["map"][40, 40] = PLANT
+        e["plant"][2] = (1, 40, 40, 0, 5)
+        e["mob"][1] = (1, 41, 40, 0, 5, 3, (0, 0))   # zombie right of the plant, far from the player
+        pred = o.draw(0, 2, 2) < 0x20000000
+        # freeze the zombie: surround by stone so it cannot leave
+        for (x, y) in [(42, 40), (41, 39), (41, 41)]:
+            e["map"][y, x] = STONE
+        step(o, NOOP)
+        gone = e["plant"][2]["alive"] == 0
+        assert gone == pred
+        if gone:
+            assert e["map"][40, 40] == GRASS
+        eaten += gone
+    assert 25 <= eaten <= 80   # about 1/8 of 400
+
+
+def test_drink_and_sapling_probability():
+    o = blank()
+    e = o.envs[0]
+    e["map"][33, 32] = WATER
+    e["vit"][DRINK] = 5
+    e["cnt"][THIRST] = 30
+    r, _ = step(o, DO)
+    assert e["vit"][DRINK] == 6 and e["cnt"][THIRST] == 2 and r == np.float32(1.0)
+    # sapling from grass follows draw misc[9] < 10 %
+    e["map"][33, 32] = GRASS
+    got = 0
+    for _ in range(300):
+        pred = o.draw(0, 9, 3) < 429496730
+        n0 = e["inv"][I_SAPLING]
+        e["inv"][I_SAPLING] = 0
+        step(o, DO)
+        assert (e["inv"][I_SAPLING] == 1) == pred
+        got += pred
+    assert 12 <= got <= 55
+
+
+def test_zombie_attack_cadence_and_sleep_damage():
+    o = blank()
+    e = o.envs[0]
+    e["mob"][0] = (1, 33, 32, 0, 5, 0, (0, 0))
+    healths = []
+    for _ in range(11):
+        r, d = step(o, NOOP)
+        healths.append(int(e["vit"][HEALTH]))
+    assert healths == [7, 7, 7, 7, 7, 5, 5, 5, 5, 5, 3]
+    assert (e["mob"][0]["x"], e["mob"][0]["y"]) == (33, 32)        # adjacent zombies do not move
+    # asleep: 7 damage, and the hit wakes the player
+    o = blank()
+    e = o.envs[0]
+    e["mob"][0] = (1, 32, 31, 0, 5, 0, (0, 0))
+    e["vit"][ENERGY] = 3
+    step(o, SLEEP)   # falls asleep and is hit in the same step while already flagged asleep
+    assert e["vit"][HEALTH] == 2 and e["sleeping"] == 0 and e["ach"] >> 15 & 1
+
+
+def test_reward_health_term():
+    o = blank()
+    e = o.envs[0]
+    e["mob"][0] = (1, 33, 32, 0, 5, 0, (0, 0))
+    r, _ = step(o, NOOP)
+    assert r == np.float32(-2) * np.float32(0.1)
+    # achievement and damage in the same step add up before the single multiply
+    e["mob"][0]["cd"] = 1
+    e["map"][33, 32] = TREE
+    r, _ = step(o, DO)
+    assert r == np.float32(10 - 2) * np.float32(0.1)
+
+
+def test_fight_mobs():
+    o = blank()
+    e = o.envs[0]
+    e["mob"][0] = (1, 32, 33, 0, 5, 3, (0, 0))     # zombie below, cooling down
+    for hp in (4, 3, 2, 1):
+        step(o, DO); assert e["mob"][0]["hp"] == hp
+        e["mob"][0]["cd"] = 3
+    r, _ = step(o, DO)
+    assert e["mob"][0]["alive"] == 0 and r == np.float32(1.0) and e["ach"] >> 8 & 1
+    assert e["mob"][0].tobytes() == bytes(8)
+    # sword damage 2 / 3 / 5
+    for tool, dmg in ((I_WS, 2), (I_SS, 3), (I_IS, 5)):
+        e["inv"][tool] = 1
+        e["mob"][6] = (1, 32, 33, 0, 3, 3, (0, 0))   # skeleton, hp 3
+        e["map"][33, 32] = PATH
+        step(o, DO)
+        if dmg >= 3:
+            assert e["mob"][6]["alive"] == 0 and e["ach"] >> 12 & 1
+        else:
+            assert e["mob"][6]["hp"] == 3 - dmg
+    # cow: 3 hp, eaten for +6 food
+    e["inv"][I_WS] = e["inv"][I_SS] = e["inv"][I_IS] = 0
+    e["mob"][6] = (0, 0, 0, 0, 0, 0, (0, 0))
+    e["mob"][4] = (1, 32, 33, 0, 3, 0, (0, 0))
+    e["map"][32, 31] = e["map"][32, 33] = e["map"][34, 32] = STONE  # keep the scene still
+    e["vit"][FOOD] = 2
+    hits = 0
+    while e["mob"][4]["alive"]:
+        # the cow may wander off; put it back in front
+        e["mob"][4]["x"], e["mob"][4]["y"] = 32, 33
+        step(o, DO); hits += 1
+    assert hits == 3 and e["vit"][FOOD] == 8 and e["ach"] >> 2 & 1
+
+
+def test_cow_moves_by_its_draw():
+    o = blank()
+    e = o.envs[0]
+    e["mob"][3] = (1, 10, 10, 0, 3, 0, (0, 0))
+    for _ in range(60):
+        x, y = int(e["mob"][3]["x"]), int(e["mob"][3]["y"])
+        m = (o.draw(0, 3, 0) * 8) >> 32
+        dx, dy = {0: (-1, 0), 1: (1, 0), 2: (0, -1), 3: (0, 1)}.get(m, (0, 0))
+        e["px"], e["py"] = x + 3, y + 3     # keep the player close enough that it does not despawn
+        step(o, NOOP)
+        assert (int(e["mob"][3]["x"]), int(e["mob"][3]["y"])) == (x + dx, y + dy)
+
+
+def test_zombie_chases():
+    o = blank()
+    e = o.envs[0]
+    e["mob"][2] = (1, 37, 30, 0, 5, 0, (0, 0))      # dx = -5, dy = 2 -> chase goes LEFT
+    for _ in range(40):
+        e["mob"][2]["x"], e["mob"][2]["y"] = 37, 30
+        chase = o.draw(0, 2, 1) < 3435973836
+        m = (o.draw(0, 2, 0) * 8) >> 32
+        step(o, NOOP)
+        pos = (int(e["mob"][2]["x"]), int(e["mob"][2]["y"]))
+        if chase:
+            assert pos == (36, 30)
+        else:
+            dx, dy = {0: (-1, 0), 1: (1, 0), 2: (0, -1), 3: (0, 1)}.get(m, (0, 0))
+            assert pos == (37 + dx, 30 + dy)
+
+
+def test_skeleton_shoots_and_arrow_flies():
+    o = blank(block=PATH)
+    e = o.envs[0]
+    shot = 0
+    for trial in range(40):
+        e["mob"][:] = 0
+        e["vit"][HEALTH] = 9
+        e["mob"][7] = (1, 32, 29, 0, 3, 0, (0, 0))  # three cells above the player
+        will_shoot = o.draw(0, 7, 1) < 0x80000000
+        step(o, NOOP)
+        if will_shoot:
+            shot += 1
+            a = e["mob"][9]
+            assert (a["alive"], a["x"], a["y"], a["dir"]) == (1, 32, 30, 4)
+            assert e["mob"][7]["cd"] == 4 and (e["mob"][7]["x"], e["mob"][7]["y"]) == (32, 29)
+            e["mob"][7] = 0                          # remove the archer; watch the arrow alone
+            step(o, NOOP)
+            assert (e["mob"][9]["x"], e["mob"][9]["y"]) == (32, 31) and e["vit"][HEALTH] == 9
+            r, _ = step(o, NOOP)
+            assert e["mob"][9]["alive"] == 0 and e["vit"][HEALTH] == 7
+            assert r == np.float32(-2) * np.float32(0.1)
+        else:
+            assert e["mob"][9]["alive"] == 0
+    assert 8 <= shot <= 32
+
+
+def test_arrow_breaks_on_obstacles_and_mobs():
+    o = blank()
+    e = o.envs[0]
+    e["mob"][9] = (1, 10, 40, 2, 0, 0, (0, 0))      # flying right
+    e["px"], e["py"] = 12, 45
+    e["map"][40, 12] = TREE
+    step(o, NOOP); assert (e["mob"][9]["alive"], e["mob"][9]["x"]) == (1, 11)
+    step(o, NOOP); assert e["mob"][9]["alive"] == 0
+    e["map"][40, 12] = WATER                         # arrows fly over water
+    e["mob"][9] = (1, 11, 40, 2, 0, 0, (0, 0))
+    step(o, NOOP); assert (e["mob"][9]["alive"], e["mob"][9]["x"]) == (1, 12)
+    e["mob"][4] = (1, 13, 40, 0, 3, 0, (0, 0))       # a cow in the way, boxed in by water
+    e["map"][39, 13] = e["map"][41, 13] = e["map"][40, 14] = WATER
+    step(o, NOOP)
+    assert e["mob"][9]["alive"] == 0 and e["mob"][4]["hp"] == 3
+    e["mob"][9] = (1, 63, 5, 2, 0, 0, (0, 0))        # leaves the map
+    e["px"], e["py"] = 60, 5
+    step(o, NOOP); assert e["mob"][9]["alive"] == 0
+
+
+def test_mobs_do_not_stack_and_later_mobs_see_earlier_moves():
+    # two cows boxed into a 1x3 corridor: whatever the draws, they never share a cell
+    o = blank(block=STONE)
+    e = o.envs[0]
+    e["map"][20, 20:23] = GRASS
+    e["map"][25, 25] = GRASS
+    e["px"], e["py"] = 25, 25
+    e["mob"][3] = (1, 20, 20, 0, 3, 0, (0, 0))
+    e["mob"][4] = (1, 22, 20, 0, 3, 0, (0, 0))
+    for _ in range(300):
+        step(o, NOOP)
+        a, b = e["mob"][3], e["mob"][4]
+        assert (a["x"], a["y"]) != (b["x"], b["y"])
+        assert a["y"] == 20 and b["y"] == 20 and 20 <= a["x"] <= 22 and 20 <= b["x"] <= 22
+
+
+def test_despawn_and_spawn_rules():
+    o = blank()
+    e = o.envs[0]
+    e["mob"][3] = (1, 48, 32, 0, 3, 0, (0, 0))      # 16 away: despawns
+    e["mob"][4] = (1, 47, 32, 0, 3, 0, (0, 0))      # 15 away: stays (may move 1 closer/further first)
+    e["map"][:, 46] = STONE; e["map"][:, 48:] = STONE; e["map"][31, 47] = e["map"][33, 47] = STONE
+    e["map"][32, 48] = GRASS
+    step(o, NOOP)
+    assert e["mob"][4]["alive"] == 1
+    # spawn: replay the rule from the draws
+    cfg = po.default_config()
+    o = po.Oracle(1, cfg); o.reset([77])
+    e = o.envs[0]
+    e["map"][:] = GRASS
+    e["map"][:, 40:] = PATH
+    spawned = np.zeros(3, int)
+    for _ in range(3000):
+        e["mob"][:] = 0
+        e["vit"][:] = 9
+        e["cnt"][:] = 0
+        t = int(e["t"])
+        preds = []
+        for j, (want, thr) in enumerate([(GRASS, L.orc_zombie_spawn_threshold(ctypes.byref(cfg), ctypes.c_uint32(t))),
+                                         (GRASS, 0x08000000), (PATH, 0x19999999)]):
+            dx = ((o.draw(0, 3 * j, 3) * 31) >> 32) - 15
+            dy = ((o.draw(0, 3 * j + 1, 3) * 31) >> 32) - 15
+            rp = o.draw(0, 3 * j + 2, 3)
+            x, y = 32 + dx, 32 + dy
+            ok = max(abs(dx), abs(dy)) >= 5 and 0 <= x < 64 and 0 <= y < 64 and e["map"][y, x] == want and rp < thr
+            ok = ok and not any(p == (x, y) for p in preds)
+            preds.append((x, y) if ok else None)
+        step(o, NOOP)
+        for j in range(3):
+            m = e["mob"][3 * j]
+            assert bool(m["alive"]) == (preds[j] is not None)
+            if preds[j]:
+                assert (m["x"], m["y"]) == preds[j] and m["hp"] == (5, 3, 3)[j] and m["cd"] == 0
+                spawned[j] += 1
+    assert spawned.min() > 5
+
+
+def test_needs_counters():
+    o = blank()
+    e = o.envs[0]
+    for s in range(1, 26):
+        step(o, NOOP)
+        assert e["cnt"][HUNGER] == 2 * s and e["vit"][FOOD] == 9
+    step(o, NOOP)
+    assert e["cnt"][HUNGER] == 0 and e["vit"][FOOD] == 8            # 52 > 50
+    assert e["cnt"][THIRST] == 10 and e["vit"][DRINK] == 8          # tripped at step 21 (42 > 40)
+    assert e["cnt"][FATIGUE] == 26 and e["vit"][ENERGY] == 9
+    for _ in range(5):
+        step(o, NOOP)
+    assert e["cnt"][FATIGUE] == 0 and e["vit"][ENERGY] == 8         # 31 > 30 at step 31
+    # recovery: +2 per step awake when fed, health +1 past 50
+    o = blank(); e = o.envs[0]
+    e["vit"][HEALTH] = 5
+    for _ in range(25):
+        step(o, NOOP)
+    assert e["vit"][HEALTH] == 5 and e["cnt"][RECOVER] == 50
+    r, _ = step(o, NOOP)
+    assert e["vit"][HEALTH] == 6 and e["cnt"][RECOVER] == 0 and r == np.float32(1) * np.float32(0.1)
+    # starving: -2 per step, health -1 below -30
+    o = blank(); e = o.envs[0]
+    e["vit"][FOOD] = 0
+    for _ in range(15):
+        step(o, NOOP)
+    assert e["vit"][HEALTH] == 9 and e["cnt"][RECOVER] == -30
+    r, _ = step(o, NOOP)
+    assert e["vit"][HEALTH] == 8 and e["cnt"][RECOVER] == 0 and r == np.float32(-1) * np.float32(0.1)
+
+
+def test_sleep_cycle_and_wake_up():
+    o = blank()
+    e = o.envs[0]
+    step(o, SLEEP)
+    assert e["sleeping"] == 0                                      # energy full: no sleep
+    e["vit"][ENERGY] = 7
+    e["cnt"][FATIGUE] = 0
+    step(o, SLEEP)
+    assert e["sleeping"] == 1 and e["cnt"][FATIGUE] == -1
+    x = int(e["px"])
+    step(o, LEFT)                                                  # asleep: actions are ignored
+    assert e["px"] == x and e["dir"] == 4
+    steps = 2
+    while e["sleeping"]:
+        r, _ = step(o, RIGHT)
+        steps += 1
+        assert steps < 100
+    assert e["vit"][ENERGY] == 9 and e["ach"] >> 15 & 1 and r == np.float32(1.0)
+    assert steps == 22   # fatigue -1 per step, +1 energy each time it passes -10: 11 + 11 steps
+
+
+def test_invalid_action_ids_are_noop_and_done_by_time_limit():
+    for bad in (-1, 17, 99, 2**31 - 1, -2**31):
+        a, b = blank(), blank()
+        step(a, bad); step(b, NOOP)
+        assert a.envs.tobytes() == b.envs.tobytes()
+    o = blank(max_episode_steps=5)
+    flags = [step(o, NOOP)[1] for _ in range(5)]
+    assert flags == [0, 0, 0, 0, 1]
+
+
+def test_unmet_prerequisites_equal_noop():
+    """Section "RL Environment Interface": an action without its prerequisites is a no-op
+    that still advances time, so the whole state must equal the NOOP successor."""
+    def scene():
+        o = blank(block=STONE, caps=3)      # boxed in by stone, empty inventory, live mobs around
+        e = o.envs[0]
+        e["map"][32, 32] = GRASS
+        e["map"][20:25, 20:25] = GRASS
+        e["mob"][0] = (1, 21, 21, 0, 5, 0, (0, 0))
+        e["mob"][4] = (1, 23, 23, 0, 3, 0, (0, 0))
+        e["t"] = 160
+        return o
+    ref = scene(); step(ref, NOOP)
+    for a in (DO, PLACE_STONE, PLACE_TABLE, PLACE_FURNACE, PLACE_PLANT, MK_WP, MK_SP, MK_IP, MK_WS, MK_SS, MK_IS):
+        o = scene(); step(o, a)
+        assert o.envs.tobytes() == ref.envs.tobytes(), a
+    # SLEEP with full energy
+    o = scene(); step(o, SLEEP)
+    assert o.envs.tobytes() == ref.envs.tobytes()
+    # moving into a wall only turns the player
+    o = scene(); step(o, DOWN)
+    assert o.envs.tobytes() == ref.envs.tobytes()
+
+
+def test_auto_reset():
+    cfg = po.default_config(max_episode_steps=3)
+    o = po.Oracle(2, cfg)
+    o.reset([9, 9], env_ids=[4, 5])
+    first = o.envs["map"].copy()
+    for s in range(3):
+        obs, r, d = o.step([NOOP, NOOP])
+        assert list(d) == ([0, 0] if s < 2 else [1, 1])
+    e = o.envs
+    assert list(e["episode"]) == [1, 1] and list(e["t"]) == [0, 0] and np.all(e["vit"] == 9)
+    assert np.array_equal(e["map"][0], po.worldgen(9, 4, 1)) and np.array_equal(e["map"][1], po.worldgen(9, 5, 1))
+    assert not np.array_equal(e["map"][0], first[0])
+    # the observation returned with done is the new episode's first observation
+    assert np.array_equal(obs[0], o.observe_one(0))
+    fresh = po.Oracle(1, cfg); fresh.reset([9], env_ids=[4])
+    fresh.envs["map"][0] = po.worldgen(9, 4, 1); fresh.envs["episode"] = 1
+    assert np.array_equal(obs[0], fresh.observe_one(0))
+
+
+# ------------------------------------------------------------ observations ----
+def test_symbolic_observation_layout():
+    assert 7 * 9 * (17 + 4) + 22 == 1345          # flat length printed in the paper
+    o = blank()
+    e = o.envs[0]
+    e["px"], e["py"] = 2, 1                        # near the top-left corner
+    e["map"][1, 3] = TREE
+    e["map"][0, 0] = WATER
+    e["mob"][0] = (1, 3, 2, 0, 5, 0, (0, 0))       # zombie
+    e["mob"][4] = (1, 1, 1, 0, 3, 0, (0, 0))       # cow
+    e["mob"][8] = (1, 6, 4, 0, 3, 0, (0, 0))       # skeleton
+    e["mob"][10] = (1, 2, 3, 4, 0, 0, (0, 0))      # arrow
+    e["mob"][5] = (1, 7, 1, 0, 3, 0, (0, 0))       # cow just outside the view (col +5)
+    e["inv"][:] = [4, 9, 1, 0, 2, 3, 1, 0, 1, 0, 1, 0]
+    e["vit"][:] = [7, 5, 3, 1]
+    e["dir"] = 2
+    e["t"] = 75
+    e["sleeping"] = 1
+    raw = o.observe_one(0, po.OBS_SYM_U8_F32)
+    cells = raw[:1323].reshape(7, 9, 21)
+    assert np.all(cells[:, :, :17].sum(-1) == 1) and np.all(cells[:, :, 17:].sum(-1) <= 1)
+    # rows -3..+3 around y=1 -> rows 0,1 are out of bounds; cols -4..+4 around x=2 -> cols 0,1 out
+    block = cells[:, :, :17].argmax(-1)
+    assert np.all(block[:2, :] == 1) and np.all(block[:, :2] == 1)
+    assert block[2, 2] == WATER                     # (x=0,y=0) sits at row 2, col 2
+    assert block[3, 5] == TREE                      # (3,1): row 3, col 5
+    assert block[3, 4] == GRASS                     # the player's own cell
+    mobs = {(r, c): ch for r, c, ch in zip(*np.nonzero(cells[:, :, 17:]))}
+    assert mobs == {(4, 5): 0, (3, 3): 1, (6, 8): 2, (5, 4): 3}
+    assert np.all(raw[1323:1328] == 0) and np.all(raw[1416:] == 0)
+    v = raw[1328:1416].view(np.float32)
+    exp = [np.float32(np.sqrt(float(n)) / 10.0) for n in (4, 9, 1, 0, 2, 3)] + [1, 0, 1, 0, 1, 0]
+    exp += [np.float32(x / 10.0) for x in (7, 5, 3, 1)] + [0, 1, 0, 0] + [0.5, 1]
+    assert v.tolist() == [float(np.float32(x)) for x in exp]
+    # int8 flavour holds the raw integers
+    raw8 = o.observe_one(0, po.OBS_SYM_U8_I8)
+    assert np.array_equal(raw8[:1323], raw[:1323])
+    assert raw8[1328:1350].view(np.int8).tolist() == [4, 9, 1, 0, 2, 3, 1, 0, 1, 0, 1, 0, 7, 5, 3, 1, 0, 1, 0, 0, 63, 1]
+    # paper-shaped float vector of length 1345
+    f = o.observe_one(0, po.OBS_SYM_F32)[:5380].view(np.float32)
+    assert np.array_equal(f[:1323], raw[:1323].astype(np.float32)) and np.array_equal(f[1323:], v)
+
+
+def test_pixel_observation_structure():
+    o = blank()
+    e = o.envs[0]
+    e["t"] = 75                                     # daylight exactly 0.5
+    e["map"][32, 36] = STONE
+    e["mob"][3] = (1, 30, 30, 0, 3, 0, (0, 0))
+    img = o.observe_one(0, po.OBS_PIXELS_F32)[:63 * 63 * 3 * 4].view(np.float32).reshape(63, 63, 3)
+    assert img.min() >= 0 and img.max() <= 0.5
+    tiles = img.reshape(9, 7, 9, 7, 3).transpose(0, 2, 1, 3, 4)
+    grass = tiles[0, 0]
+    assert np.array_equal(tiles[8, 8], grass) and np.array_equal(tiles[3, 7], grass)
+    assert not np.array_equal(tiles[4, 8], grass)             # the stone tile
+    assert not np.array_equal(tiles[4, 4], grass)             # the player sprite
+    assert not np.array_equal(tiles[2, 2], grass)             # the cow sprite
+    covered = (tiles[2, 2] != grass).any(-1).mean()
+    assert 0.2 < covered < 0.8                                 # the sprite mask covers about half
+    # light scales every pixel by one multiply: full daylight is exactly twice as bright
+    e["t"] = 0
+    img1 = o.observe_one(0, po.OBS_PIXELS_F32)[:63 * 63 * 3 * 4].view(np.float32).reshape(63, 63, 3)
+    assert np.array_equal(img1 * np.float32(0.5), img)
+    # texels are multiples of 2^-24 in [0,1)
+    q = img1 * np.float32(2 ** 24)
+    assert np.array_equal(q, np.round(q)) and img1.max() < 1.0
+    # another atlas seed gives another picture
+    o.cfg.atlas_seed = 1
+    assert not np.array_equal(o.observe_one(0, po.OBS_PIXELS_F32), img1.tobytes())
+
+
+# --------------------------------------------------- invariants on rollouts ----
+RECIPES = {
+    PLACE_STONE: {I_STONE: -1}, PLACE_TABLE: {I_WOOD: -1}, PLACE_FURNACE: {I_STONE: -1},
+    PLACE_PLANT: {I_SAPLING: -1},
+    MK_WP: {I_WOOD: -1, I_WP: 1}, MK_WS: {I_WOOD: -1, I_WS: 1},
+    MK_SP: {I_WOOD: -1, I_STONE: -1, I_SP: 1}, MK_SS: {I_WOOD: -1, I_STONE: -1, I_SS: 1},
+    MK_IP: {I_WOOD: -1, I_COAL: -1, I_IRON: -1, I_IP: 1}, MK_IS: {I_WOOD: -1, I_COAL: -1, I_IRON: -1, I_IS: 1},
+}
+
+
+@pytest.mark.parametrize("kind", ["uniform", "skewed"])
+def test_rollout_invariants(kind):
+    n, T = 48, 600
+    cfg = po.default_config(max_episode_steps=400)
+    o = po.Oracle(n, cfg)
+    o.reset(synth.seeds_for(n, 100))
+    # hand out materials so that crafting actually happens under random play
+    o.envs["inv"][:, :6] = 5
+    ach_before = o.envs["ach"].copy()
+    ep_return_int = np.zeros(n)
+    finished = 0
+    for s in range(T):
+        a = synth.actions(np.arange(n), s, kind, action_seed=5)
+        prev = o.envs.copy()
+        for i in range(n):
+            r, d = o.step_rules_one(i, int(a[i]))
+            e, p = o.envs[i], prev[i]
+            # map / table bounds and occupancy
+            live = e["mob"][e["mob"]["alive"] == 1]
+            cells = [(int(e["px"]), int(e["py"]))] + [(int(m["x"]), int(m["y"])) for m in live]
+            assert all(0 <= x < 64 and 0 <= y < 64 for x, y in cells)
+            assert len(set(cells)) == len(cells)
+            for k in range(6, 9):
+                m = e["mob"][k]
+                if m["alive"]:
+                    assert e["map"][m["y"], m["x"]] == PATH
+            for k in range(0, 6):
+                m = e["mob"][k]
+                if m["alive"]:
+                    assert e["map"][m["y"], m["x"]] in (GRASS, SAND, PATH)
+            for pl in e["plant"]:
+                if pl["alive"]:
+                    assert e["map"][pl["y"], pl["x"]] in (PLANT, RIPE)
+            assert (e["map"] >= 2).all() and (e["map"] <= 16).all()
+            assert e["inv"].max() <= 9 and e["vit"].min() >= 0 and e["vit"].max() <= 9
+            # achievements only grow; reward = popcount(new) + 0.1 * health change
+            assert p["ach"] & ~e["ach"] == 0
+            new = bin(int(e["ach"] & ~p["ach"])).count("1")
+            dh = int(e["vit"][0]) - int(p["vit"][0])
+            assert r == np.float32(10 * new + dh) * np.float32(0.1)
+            assert d == (e["vit"][0] <= 0 or e["t"] >= 400)
+            # crafting conserves inventory
+            dinv = e["inv"].astype(int) - p["inv"].astype(int)
+            act = int(a[i]) if not p["sleeping"] else NOOP
+            if act in RECIPES:
+                want = np.zeros(12, int)
+                for k, v in RECIPES[act].items():
+                    want[k] = v
+                assert np.array_equal(dinv, want) or not dinv.any()
+            elif act != DO:
+                assert not dinv.any()
+            else:
+                assert dinv.sum() in (0, 1) and dinv.min() >= 0
+            if d:
+                finished += 1
+                o.envs[i:i + 1] = _fresh(cfg, int(e["seed"]), int(e["env"]), int(e["episode"]) + 1)
+                o.envs["inv"][i, :6] = 5
+    assert finished > 20
+
+
+def _fresh(cfg, seed, env, episode):
+    f = po.Oracle(1, cfg)
+    f.reset([seed], env_ids=[env])
+    f.envs["episode"] = episode
+    f.envs["map"][0] = po.worldgen(seed, env, episode)
+    return f.envs
+
+
+def test_determinism_and_save_restore():
+    n, T = 16, 300
+    acts = synth.action_block(n, T, "uniform", 3)
+    a = po.Oracle(n); a.reset(synth.seeds_for(n))
+    b = po.Oracle(n); b.reset(synth.seeds_for(n))
+    trace_a = []
+    for s in range(T):
+        obs, r, d = a.step(acts[s])
+        trace_a.append((obs.copy(), r.copy(), d.copy()))
+    for s in range(T // 2):
+        b.step(acts[s])
+    saved = b.envs.copy()
+    c = po.Oracle(n); c.envs[:] = saved
+    for s in range(T // 2, T):
+        obs, r, d = c.step(acts[s])
+        assert np.array_equal(obs, trace_a[s][0]) and np.array_equal(r, trace_a[s][1]) and np.array_equal(d, trace_a[s][2])
+    assert c.envs.tobytes() == a.envs.tobytes()
+
+
+def test_envs_are_independent_of_batch_position():
+    """Environment i depends only on (seed, env index): run it alone or inside a batch."""
+    n, T = 8, 200
+    acts = synth.action_block(n, T, "skewed", 1)
+    full = po.Oracle(n); full.reset(synth.seeds_for(n))
+    solo = po.Oracle(1); solo.reset([5], env_ids=[5])
+    for s in range(T):
+        full.step(acts[s])
+        solo.step(acts[s, 5:6])
+    assert full.envs[5].tobytes() == solo.envs[0].tobytes()
