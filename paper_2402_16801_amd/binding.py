@@ -1,0 +1,195 @@
+"""Thin ctypes binding of libcraftax_hip.so (see include/craftax.h).
+
+Argument marshalling only: every step of the simulator runs in the HIP kernels.  PyTorch is
+used for device memory and streams.  There is no CPU fallback: if the library is missing or
+no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcraftax_hip.so")
+
+OBS_SYM_U8_I8, OBS_SYM_U8_F32, OBS_SYM_F32, OBS_PIXELS_F32 = 0, 1, 2, 3
+
+EXPORTS = [
+    "craftax_default_config", "craftax_state_bytes", "craftax_obs_bytes", "craftax_env_dump_bytes",
+    "craftax_state_init", "craftax_state_release", "craftax_reset", "craftax_step", "craftax_observe",
+    "craftax_export_envs", "craftax_import_envs", "craftax_synth_actions", "craftax_last_error",
+]
+
+
+class Config(ctypes.Structure):
+    _fields_ = [("abi_version", ctypes.c_uint32), ("variant", ctypes.c_uint32), ("obs_mode", ctypes.c_uint32),
+                ("max_episode_steps", ctypes.c_uint32), ("day_length", ctypes.c_uint32),
+                ("cap_zombie", ctypes.c_uint32), ("cap_cow", ctypes.c_uint32), ("cap_skeleton", ctypes.c_uint32),
+                ("cap_arrow", ctypes.c_uint32), ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64)]
+
+
+class CraftaxError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Loads the built library; raises if it has not been built (run __graft_entry__.build())."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise CraftaxError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64
+    L.craftax_default_config.argtypes = [ctypes.POINTER(Config)]
+    L.craftax_default_config.restype = None
+    L.craftax_state_bytes.argtypes = [ctypes.POINTER(Config), i32]
+    L.craftax_state_bytes.restype = ctypes.c_size_t
+    L.craftax_obs_bytes.argtypes = [ctypes.POINTER(Config)]
+    L.craftax_obs_bytes.restype = ctypes.c_size_t
+    L.craftax_env_dump_bytes.argtypes = []
+    L.craftax_env_dump_bytes.restype = ctypes.c_size_t
+    L.craftax_state_init.argtypes = [vp, ctypes.POINTER(Config), i32, vp]
+    L.craftax_state_release.argtypes = [vp]
+    L.craftax_reset.argtypes = [vp, vp, i32, vp]
+    L.craftax_step.argtypes = [vp, vp, vp, vp, vp, i32, vp]
+    L.craftax_observe.argtypes = [vp, vp, i32, vp]
+    L.craftax_export_envs.argtypes = [vp, i32, i32, vp, vp]
+    L.craftax_import_envs.argtypes = [vp, i32, i32, vp, vp]
+    L.craftax_synth_actions.argtypes = [vp, i32, i32, i32, u64, i32, vp]
+    L.craftax_last_error.argtypes = []
+    L.craftax_last_error.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise CraftaxError(f"{what} failed ({rc}): {load().craftax_last_error().decode()}")
+
+
+def default_config(**overrides) -> Config:
+    cfg = Config()
+    load().craftax_default_config(ctypes.byref(cfg))
+    for k, v in overrides.items():
+        setattr(cfg, k, v)
+    return cfg
+
+
+def craftax_state_bytes(cfg: Config, n: int) -> int:
+    return int(load().craftax_state_bytes(ctypes.byref(cfg), n))
+
+
+def craftax_obs_bytes(cfg: Config) -> int:
+    return int(load().craftax_obs_bytes(ctypes.byref(cfg)))
+
+
+def craftax_env_dump_bytes() -> int:
+    return int(load().craftax_env_dump_bytes())
+
+
+def _stream_ptr(stream) -> int:
+    return 0 if stream is None else int(stream.cuda_stream)
+
+
+def craftax_state_init(state, cfg: Config, n: int, stream=None):
+    _check(load().craftax_state_init(state.data_ptr(), ctypes.byref(cfg), n, _stream_ptr(stream)), "craftax_state_init")
+
+
+def craftax_state_release(state):
+    load().craftax_state_release(state.data_ptr())
+
+
+def craftax_reset(state, seeds, n: int, stream=None):
+    _check(load().craftax_reset(state.data_ptr(), seeds.data_ptr(), n, _stream_ptr(stream)), "craftax_reset")
+
+
+def craftax_step(state, actions, obs, reward, done, n: int, stream=None):
+    _check(load().craftax_step(state.data_ptr(), actions.data_ptr(), 0 if obs is None else obs.data_ptr(),
+                               reward.data_ptr(), done.data_ptr(), n, _stream_ptr(stream)), "craftax_step")
+
+
+def craftax_observe(state, obs, n: int, stream=None):
+    _check(load().craftax_observe(state.data_ptr(), obs.data_ptr(), n, _stream_ptr(stream)), "craftax_observe")
+
+
+def craftax_export_envs(state, first: int, count: int, dumps, stream=None):
+    _check(load().craftax_export_envs(state.data_ptr(), first, count, dumps.data_ptr(), _stream_ptr(stream)),
+           "craftax_export_envs")
+
+
+def craftax_import_envs(state, first: int, count: int, dumps, stream=None):
+    _check(load().craftax_import_envs(state.data_ptr(), first, count, dumps.data_ptr(), _stream_ptr(stream)),
+           "craftax_import_envs")
+
+
+def craftax_synth_actions(actions, n: int, step0: int, steps: int, action_seed: int, kind: int, stream=None):
+    _check(load().craftax_synth_actions(actions.data_ptr(), n, step0, steps, action_seed, kind, _stream_ptr(stream)),
+           "craftax_synth_actions")
+
+
+class Craftax:
+    """Owns the device buffers of n environments and forwards to the C ABI."""
+
+    def __init__(self, n: int, cfg: Config | None = None, device: str = "cuda:0"):
+        import torch
+
+        if not torch.cuda.is_available():
+            raise CraftaxError("no GPU visible: the simulator has no CPU path")
+        self.torch = torch
+        self.n = n
+        self.cfg = cfg if cfg is not None else default_config()
+        self.device = torch.device(device)
+        nbytes = craftax_state_bytes(self.cfg, n)
+        if nbytes == 0:
+            raise CraftaxError("invalid configuration")
+        self.obs_bytes = craftax_obs_bytes(self.cfg)
+        self.state = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.obs = torch.zeros((n, self.obs_bytes), dtype=torch.uint8, device=self.device)
+        self.reward = torch.zeros(n, dtype=torch.float32, device=self.device)
+        self.done = torch.zeros(n, dtype=torch.uint8, device=self.device)
+        self.stream = torch.cuda.current_stream(self.device)
+        craftax_state_init(self.state, self.cfg, n, self.stream)
+
+    def close(self):
+        if self.state is not None:
+            craftax_state_release(self.state)
+            self.state = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def reset(self, seeds):
+        torch = self.torch
+        s = torch.as_tensor(np.ascontiguousarray(seeds, dtype=np.uint64).view(np.int64), device=self.device)
+        craftax_reset(self.state, s, self.n, self.stream)
+        craftax_observe(self.state, self.obs, self.n, self.stream)
+        return self.obs
+
+    def step(self, actions):
+        """actions: int32 device tensor [n]."""
+        craftax_step(self.state, actions, self.obs, self.reward, self.done, self.n, self.stream)
+        return self.obs, self.reward, self.done
+
+    def export_envs(self, first: int = 0, count: int | None = None) -> np.ndarray:
+        torch = self.torch
+        count = self.n - first if count is None else count
+        size = craftax_env_dump_bytes()
+        buf = torch.empty((count, size), dtype=torch.uint8, device=self.device)
+        craftax_export_envs(self.state, first, count, buf, self.stream)
+        return buf.cpu().numpy()
+
+    def import_envs(self, dumps: np.ndarray, first: int = 0):
+        torch = self.torch
+        raw = np.ascontiguousarray(dumps).view(np.uint8).reshape(-1, craftax_env_dump_bytes())
+        buf = torch.as_tensor(raw, device=self.device)
+        craftax_import_envs(self.state, first, raw.shape[0], buf, self.stream)
+        self.torch.cuda.synchronize(self.device)

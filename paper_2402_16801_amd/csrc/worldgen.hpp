@@ -1,0 +1,126 @@
+// Block-cooperative generation of one 64x64 Craftax-Classic world (appendix "World
+// Generation" of the paper: noise thresholds carve grassland, forest, lakes, mountains with
+// caves, tunnels, ores and lava).  The paper uses Perlin noise in floating point; this
+// library uses seeded integer value noise so that every cell is a pure integer function of
+// (seed, env, episode).  All 256 threads of the block take part.
+#pragma once
+
+#include "common.hpp"
+
+namespace cx {
+
+constexpr int LAT16_N = 25;   // 5x5 lattice points at spacing 16
+constexpr int LAT8_N = 81;    // 9x9 lattice points at spacing 8
+constexpr int LAT_TOTAL = 2 * LAT16_N + 4 * LAT8_N;   // 374 u16 values
+constexpr int LAT_BLOCKS = (LAT_TOTAL + 7) / 8;       // Philox blocks holding them (8 u16 each)
+
+// terrain thresholds on 0..65535 scales
+constexpr int TH_MOUNTAIN = 39500, TH_CAVE_M = 41000, TH_CAVE_C = 43000;
+constexpr int TH_TUNNEL_CENTER = 30000, TH_TUNNEL_HALF = 1300;
+constexpr int TH_LAVA_M = 43000, TH_LAVA_F = 44000, TH_DIAMOND_M = 42000;
+constexpr int U_DIAMOND = 500, U_IRON = 3000, TH_IRON_F = 33000, U_COAL = 8000;
+constexpr int TH_WATER = 39500, TH_SAND = 37800, TH_FOREST_F = 33500;
+constexpr int U_TREE_FOREST = 26000, U_TREE_SPARSE = 1300;
+constexpr int START_CLEAR = 2, START_BIAS_R = 10, START_BIAS = 2500;
+
+// smoothstep(k/S) in 1/256 units for S = 8 and S = 16
+__device__ inline uint32_t smooth8(int k) { return (uint32_t)(12 * k * k - k * k * k); }
+__device__ inline uint32_t smooth16(int k) { return (uint32_t)((24 * k * k - k * k * k + 4) >> 3); }
+
+// One row's worth of bilinear interpolation: lattice rows j and j+1 blended with weight wy.
+__device__ inline uint32_t bilerp(const uint16_t* lat, int width, int ix, int iy, uint32_t wx, uint32_t wy)
+{
+    const uint32_t a = lat[iy * width + ix], b = lat[iy * width + ix + 1];
+    const uint32_t c = lat[(iy + 1) * width + ix], d = lat[(iy + 1) * width + ix + 1];
+    const uint32_t top = a * (256u - wx) + b * wx;
+    const uint32_t bot = c * (256u - wx) + d * wx;
+    return (top * (256u - wy) + bot * wy) >> 16;
+}
+
+__device__ inline int terrain_cell(const uint16_t* lat, int x, int y, int u)
+{
+    const uint16_t* w16 = lat;
+    const uint16_t* m16 = lat + LAT16_N;
+    const uint16_t* w8 = lat + 2 * LAT16_N;
+    const uint16_t* m8 = w8 + LAT8_N;
+    const uint16_t* c8 = m8 + LAT8_N;
+    const uint16_t* f8 = c8 + LAT8_N;
+    const int ix16 = x >> 4, iy16 = y >> 4, ix8 = x >> 3, iy8 = y >> 3;
+    const uint32_t wx16 = smooth16(x & 15), wy16 = smooth16(y & 15);
+    const uint32_t wx8 = smooth8(x & 7), wy8 = smooth8(y & 7);
+    int W = (int)((3u * bilerp(w16, 5, ix16, iy16, wx16, wy16) + bilerp(w8, 9, ix8, iy8, wx8, wy8)) >> 2);
+    int M = (int)((3u * bilerp(m16, 5, ix16, iy16, wx16, wy16) + bilerp(m8, 9, ix8, iy8, wx8, wy8)) >> 2);
+    const int C = (int)bilerp(c8, 9, ix8, iy8, wx8, wy8);
+    const int F = (int)bilerp(f8, 9, ix8, iy8, wx8, wy8);
+    const int d = max(iabs(x - MAPW / 2), iabs(y - MAPW / 2));
+    if (d < START_BIAS_R) {
+        const int bias = (START_BIAS_R - d) * START_BIAS;
+        W = max(0, W - bias);
+        M = max(0, M - bias);
+    }
+    if (d <= START_CLEAR) return BK_GRASS;
+    if (M > TH_MOUNTAIN) {
+        if (C > TH_CAVE_C && M > TH_CAVE_M) return BK_PATH;
+        if (iabs(C - TH_TUNNEL_CENTER) < TH_TUNNEL_HALF) return BK_PATH;
+        if (M > TH_LAVA_M && F > TH_LAVA_F) return BK_LAVA;
+        if (M > TH_DIAMOND_M && u < U_DIAMOND) return BK_DIAMOND;
+        if (F < TH_IRON_F && u >= U_DIAMOND && u < U_IRON) return BK_IRON;
+        if (u >= U_IRON && u < U_COAL) return BK_COAL;
+        return BK_STONE;
+    }
+    if (W > TH_WATER) return BK_WATER;
+    if (W > TH_SAND) return BK_SAND;
+    if (F > TH_FOREST_F && u < U_TREE_FOREST) return BK_TREE;
+    if (u < U_TREE_SPARSE) return BK_TREE;
+    return BK_GRASS;
+}
+
+// Generates the map of one environment with the 256 threads of the calling block.
+// s_lat: LDS scratch of at least LAT_BLOCKS*8 u16.  Ends with every thread's stores issued;
+// the caller synchronises before anyone reads the map.
+__device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat, uint32_t seed_lo, uint32_t seed_hi,
+                                      uint32_t env, uint32_t episode)
+{
+    const int tid = threadIdx.x;
+    if (tid < LAT_BLOCKS) {
+        const U4 r = philox4x32_10(env, 0u, episode, (DOM_WORLDGEN << 16) | (uint32_t)tid, seed_lo, seed_hi);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            s_lat[tid * 8 + 2 * w] = (uint16_t)(r.w[w] & 0xFFFFu);
+            s_lat[tid * 8 + 2 * w + 1] = (uint16_t)(r.w[w] >> 16);
+        }
+    }
+    __syncthreads();
+    // thread tid owns the 16 cells [16 tid, 16 tid + 16): one quarter of row tid/4
+    const int y = tid >> 2, x0 = (tid & 3) << 4;
+    uint32_t packed[4];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const U4 r = philox4x32_10(env, 1u, episode, (DOM_WORLDGEN << 16) | (uint32_t)(2 * tid + half), seed_lo, seed_hi);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const int xa = x0 + half * 8 + 2 * w;
+            const uint32_t ba = (uint32_t)terrain_cell(s_lat, xa, y, (int)(r.w[w] & 0xFFFFu));
+            const uint32_t bb = (uint32_t)terrain_cell(s_lat, xa + 1, y, (int)(r.w[w] >> 16));
+            const int cell = half * 8 + 2 * w;            // 0..15 within this thread's run
+            const int shift = (cell & 3) * 8;
+            if ((cell & 3) == 0) packed[cell >> 2] = 0;
+            packed[cell >> 2] |= (ba << shift) | (bb << (shift + 8));
+        }
+    }
+    reinterpret_cast<uint4*>(map)[tid] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+    __syncthreads();   // s_lat may be reused by the caller
+}
+
+// A fresh record for a new episode: full vitals, empty tables, player in the middle facing down.
+__device__ inline void fresh_record(EnvRec* r, uint32_t seed_lo, uint32_t seed_hi, uint32_t episode)
+{
+    uint32_t* w = reinterpret_cast<uint32_t*>(r);
+    for (int i = 0; i < 64; ++i) w[i] = 0;
+    r->px = MAPW / 2; r->py = MAPW / 2; r->dir = 4;
+    r->vit[0] = r->vit[1] = r->vit[2] = r->vit[3] = MAX_COUNT;
+    r->episode = episode;
+    r->seed_lo = seed_lo; r->seed_hi = seed_hi;
+}
+
+}  // namespace cx

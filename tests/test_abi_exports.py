@@ -1,0 +1,56 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header
+declares, and its size queries agree with the documented layouts.  No kernel is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2402_16801_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__ as g
+        g.build()
+    return binding.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "craftax.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(craftax_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_sizes_and_defaults(lib):
+    cfg = binding.default_config()
+    assert (cfg.abi_version, cfg.variant, cfg.obs_mode) == (1, 0, 1)
+    assert (cfg.max_episode_steps, cfg.day_length) == (10000, 300)
+    assert (cfg.cap_zombie, cfg.cap_cow, cfg.cap_skeleton, cfg.cap_arrow, cfg.cap_plant) == (3, 3, 3, 3, 10)
+    assert binding.craftax_env_dump_bytes() == 4304
+    strides = {0: 1360, 1: 1424, 2: 5392, 3: 47632}
+    for mode, stride in strides.items():
+        cfg.obs_mode = mode
+        assert binding.craftax_obs_bytes(cfg) == stride and stride % 16 == 0
+    assert 1345 * 4 <= strides[2] and 63 * 63 * 3 * 4 <= strides[3]
+    cfg.obs_mode = 1
+    b1, b2 = binding.craftax_state_bytes(cfg, 1), binding.craftax_state_bytes(cfg, 1001)
+    assert b2 - b1 == 1000 * (4096 + 256) and b1 % 256 == 0
+    assert binding.craftax_state_bytes(cfg, 0) == 0 and binding.craftax_state_bytes(cfg, -3) == 0
+    cfg.day_length = 7
+    assert binding.craftax_state_bytes(cfg, 4) == 0
+
+
+def test_host_side_argument_errors(lib):
+    cfg = binding.default_config()
+    assert lib.craftax_state_init(None, ctypes.byref(cfg), 4, None) == -1
+    assert lib.craftax_step(None, None, None, None, None, 4, None) == -1
+    assert lib.craftax_step(ctypes.c_void_p(4096), None, None, None, None, 4, None) == -4
+    assert lib.craftax_last_error() != b""
+    assert lib.craftax_state_release(ctypes.c_void_p(4096)) == -4
