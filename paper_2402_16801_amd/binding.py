@@ -44,6 +44,10 @@ def load() -> ctypes.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise CraftaxError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    # PyTorch ships its own HIP runtime; import it first so that this library binds to the
+    # same runtime instance (same SONAME) instead of bringing a second one into the process.
+    import torch  # noqa: F401
+
     L = ctypes.CDLL(LIB_PATH)
     vp, i32, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64
     L.craftax_default_config.argtypes = [ctypes.POINTER(Config)]
