@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the Craftax-Classic hot path on one MI355X.
+
+A "step" is one craftax_step call over all environments of the workload: rules, mob update,
+auto-reset of finished episodes and the symbolic observation write, with every input already
+resident in HBM.  Prints ONE JSON line (see the design doc for the field definitions).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--envs N] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+OBS_ALG_BYTES = 1323 + 22 * 4  # uint8 cells + fp32 scalars actually produced per env-step
+
+
+def algorithmic_bytes_per_env_step(mean_episode_len: float) -> dict:
+    """What the method itself has to move per environment step (not what cache lines carry)."""
+    parts = {
+        "obs_write": OBS_ALG_BYTES,
+        "action_reward_done": 4 + 4 + 1,
+        "player_record_rw": 52 + 40,          # pos/dir/sleep 4, inventory 12, vitals 4, counters 8,
+                                              # achievements 4, t 4, phase 4 read+written; episode 4, seed 8 read
+        "mob_table_rw": 12 * 6 * 2,           # alive,x,y,dir,hp,cd per slot, read + write
+        "plant_table_rw": 10 * 5 * 2,         # alive,x,y,age(2) per slot, read + write
+        "map_reads": 63 + 9 + 12 + 3 + 10,    # view, 3x3 neighbourhood, mob targets, spawn probes, plant cells
+        "map_writes": 2,
+        "reset_amortised": (4096 + 256) / max(mean_episode_len, 1.0),
+    }
+    parts["total"] = float(sum(parts.values()))
+    return parts
+
+
+def read_profile_traffic(name: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), taken from
+    the committed summary; None if that summary is absent."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+    return float(m.group(1)) if m else None
+
+
+def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3):
+    import torch
+    from paper_2402_16801_amd import binding as cx, synth
+
+    dev = torch.device("cuda:0")
+    cfg = cx.default_config(obs_mode=cx.OBS_SYM_U8_F32, max_episode_steps=10000)
+    sim = cx.Craftax(n, cfg)
+    sim.reset(synth.seeds_for(n))
+    total_steps = warmup + repeats * steps
+    kind_id = {"uniform": 0, "skewed": 1}[kind]
+    actions = torch.empty((total_steps, n), dtype=torch.int32, device=dev)
+    cx.craftax_synth_actions(actions, n, 0, total_steps, 0, kind_id, sim.stream)
+    torch.cuda.synchronize()
+
+    # the launches go to torch's current stream, so torch events bracket exactly that stream
+    state, obs, rew, done, stream = sim.state, sim.obs, sim.reward, sim.done, sim.stream
+    s = 0
+    for _ in range(warmup):
+        cx.craftax_step(state, actions[s], obs, rew, done, n, stream)
+        s += 1
+    torch.cuda.synchronize()
+    wall, evt = [], []
+    for _ in range(repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(steps):
+            cx.craftax_step(state, actions[s], obs, rew, done, n, stream)
+            s += 1
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall.append(time.perf_counter() - t0)
+        evt.append(e0.elapsed_time(e1) * 1e-3)
+    # episodes finished so far -> mean episode length (drives the amortised reset bytes)
+    episodes = 0
+    chunk = 8192
+    for first in range(0, n, chunk):
+        d = sim.export_envs(first, min(chunk, n - first))
+        episodes += int(d[:, 4132:4136].copy().view(np.uint32).sum())
+    mean_len = (n * total_steps) / max(episodes, 1)
+    sim.close()
+    med = int(np.argsort(wall)[len(wall) // 2])
+    return {"wall_s": wall[med], "event_s": evt[med], "all_wall_s": wall, "episodes": episodes, "mean_episode_len": mean_len}
+
+
+def cpu_baseline(n_sample: int, steps: int, kind: str):
+    """The CPU oracle, as it stands, on the first n_sample environments of the same workload."""
+    from oracle import pyoracle as po
+    from paper_2402_16801_amd import synth
+
+    acts = synth.action_block(n_sample, steps, kind, 0)
+    orc = po.Oracle(n_sample, po.default_config(max_episode_steps=10000), po.OBS_SYM_U8_F32)
+    orc.reset(synth.seeds_for(n_sample))
+    t0 = time.perf_counter()
+    for s in range(steps):
+        orc.step(acts[s])
+    dt = time.perf_counter() - t0
+    return {"value": n_sample * steps / dt, "unit": "env_steps/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {n_sample} envs x {steps} steps of the same workload, single thread, "
+                      f"including the symbolic observation ({dt:.1f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--envs", type=int, default=65536)
+    ap.add_argument("--kind", default="skewed", choices=["uniform", "skewed"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-small", action="store_true", help="skip the secondary 4096-env measurement")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run one plain 256 MiB device-to-device copy kernel (reference for rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; environments are independent and would shard "
+              "without communication, but no multi-GPU path is built or measured (--gpus must be 1).",
+              file=sys.stderr)
+        sys.exit(2)
+
+    if args.calibrate_copy:
+        import torch
+        src = torch.full((256 << 20,), 7, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    n, K, W = args.envs, args.steps, args.warmup
+    main_run = gpu_run(n, K, W, args.kind)
+    alg = algorithmic_bytes_per_env_step(main_run["mean_episode_len"])
+    per_launch_bytes = alg["total"] * n
+    launch_s = main_run["event_s"] / K             # average per-launch time from HIP events
+    achieved = per_launch_bytes / launch_s / 1e9
+    value = n * K / main_run["wall_s"]
+
+    out = {
+        "metric": "env steps/sec at 1 GPU (4096 / 65536 envs, symbolic obs) + % HBM roofline",
+        "value": value,
+        "unit": "env_steps/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": main_run["wall_s"] / K * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {
+            "workload": f"configs[2]: Craftax-Classic symbolic step, {n} envs, 64x64 map, fixed-seed action stream "
+                        f"skewed 50% toward move/do, episode cap 10000, auto-reset regenerating terrain, "
+                        f"obs uint8[1323]+fp32[22]",
+            "envs": n, "obs_mode": "SYM_U8_F32", "actions": args.kind,
+            "mean_episode_len": round(main_run["mean_episode_len"], 1),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": read_profile_traffic("k_step_sym_u8_f32_65536env.txt"),
+            "kernel": "k_step<SYM_U8_F32>",
+            "alg_bytes_per_env_step": round(alg["total"], 1),
+            "alg_bytes_per_launch": per_launch_bytes,
+            "avg_launch_us": launch_s * 1e6,
+        },
+    }
+    if not args.no_small:
+        small = gpu_run(4096, K, W, "uniform")
+        out["also"] = {"workload": "configs[1]: 4096 envs, uniform actions", "value": 4096 * K / small["wall_s"],
+                       "unit": "env_steps/s", "ms_per_step": small["wall_s"] / K * 1e3}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(2048, min(K, 1000), args.kind)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

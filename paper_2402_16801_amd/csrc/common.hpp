@@ -79,26 +79,45 @@ __host__ __device__ inline U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c
 __host__ __device__ inline uint32_t choice(uint32_t u, uint32_t n) { return (uint32_t)(((uint64_t)u * n) >> 32); }
 
 // ---- in-HBM layout ----------------------------------------------------------------------------
-// One 256-byte record per environment (two 128-byte lines, read and written as 16 x uint4 by
-// the 16 lanes that own the environment), plus a 4096-byte row-major map.
-struct Mob { uint8_t alive, x, y, dir; int8_t hp; uint8_t cd; uint8_t pad[2]; };          // 8 B
-struct Plant { uint8_t alive, x, y, pad; uint16_t age; uint16_t pad2; };                   // 8 B
-struct __attribute__((aligned(16))) EnvRec {
-    uint8_t px, py, dir, sleeping;   //   0
-    uint8_t inv[12];                 //   4
-    int8_t vit[4];                   //  16
-    int16_t cnt[4];                  //  20
-    uint32_t ach;                    //  28
-    uint32_t t;                      //  32
-    uint32_t episode;                //  36
-    uint32_t seed_lo, seed_hi;       //  40
-    uint32_t phase;                  //  48  t mod day_length, kept incrementally
-    uint32_t pad0[3];                //  52
-    Mob mob[NMOB];                   //  64
-    Plant plant[NPLANT];             // 160
-    uint32_t pad1[4];                // 240
-};
-static_assert(sizeof(EnvRec) == 256, "record must be 256 bytes");
+// One 128-byte record (one HBM/L2 line) per environment, 32 dwords, plus a 4096-byte
+// row-major map.  Everything that changes every step lives in the record.
+//   w0  px | py<<8 | dir<<16 | sleeping<<24
+//   w1  six 4-bit item counts (wood stone coal iron diamond sapling) | six tool flags at bit 24
+//   w2  four 4-bit vitals (health food drink energy) | phase<<16 (t mod day_length)
+//   w3  four signed 8-bit counters (hunger thirst fatigue recover)
+//   w4  achievement bits   w5 t   w6 episode   w7,w8 seed   w9 spare
+//   w10..w21 mob slots     w22..w31 plant slots
+// mob word:   alive | x<<1 | y<<7 | dir<<13 | hp<<16 | cd<<20   (0 when the slot is empty)
+// plant word: alive | x<<1 | y<<7 | age<<16                     (0 when the slot is empty)
+constexpr int REC_DWORDS = 32;
+constexpr int RW_POS = 0, RW_INV = 1, RW_VIT = 2, RW_CNT = 3, RW_ACH = 4, RW_T = 5, RW_EPISODE = 6,
+              RW_SEED_LO = 7, RW_SEED_HI = 8, RW_MOB = 10, RW_PLANT = 22;
+
+struct Mob { int alive, x, y, dir, hp, cd; };
+struct Plant { int alive, x, y, age; };
+
+__host__ __device__ inline Mob unpack_mob(uint32_t w)
+{
+    Mob m;
+    m.alive = w & 1u; m.x = (w >> 1) & 63u; m.y = (w >> 7) & 63u; m.dir = (w >> 13) & 7u;
+    m.hp = (w >> 16) & 15u; m.cd = (w >> 20) & 15u;
+    return m;
+}
+__host__ __device__ inline uint32_t pack_mob(const Mob& m)
+{
+    return m.alive ? (1u | ((uint32_t)m.x << 1) | ((uint32_t)m.y << 7) | ((uint32_t)m.dir << 13) |
+                      ((uint32_t)m.hp << 16) | ((uint32_t)m.cd << 20)) : 0u;
+}
+__host__ __device__ inline Plant unpack_plant(uint32_t w)
+{
+    Plant q;
+    q.alive = w & 1u; q.x = (w >> 1) & 63u; q.y = (w >> 7) & 63u; q.age = (int)(w >> 16);
+    return q;
+}
+__host__ __device__ inline uint32_t pack_plant(const Plant& q)
+{
+    return q.alive ? (1u | ((uint32_t)q.x << 1) | ((uint32_t)q.y << 7) | ((uint32_t)q.age << 16)) : 0u;
+}
 
 // Lookup tables built once on the host (craftax_state_init) and kept in the state blob, so
 // no float is ever computed on the device beyond single IEEE operations.
@@ -131,19 +150,29 @@ struct Params {
 };
 
 // ---- lane groups --------------------------------------------------------------------------------
-// An environment is owned by G = 16 consecutive lanes of a wavefront (four environments per
-// wave64).  Per-environment scalars are held redundantly by all 16 lanes; per-mob and
-// per-plant work is spread over lanes 0..11 / 0..9; cross-lane traffic is a ballot or a
-// bpermute restricted to the group.
-constexpr int G = 16;
+// An environment is owned by G consecutive lanes of a wavefront (G = 4, 8 or 16, so 16, 8 or
+// 4 environments per wave64).  Per-environment scalars are held redundantly by all G lanes
+// (same inputs, same arithmetic, no exchange needed); mob slot k, plant slot k and Philox
+// block k belong to lane k mod G (sub-slot k / G); cross-lane traffic is a ballot or a
+// bpermute restricted to the group.  Few lanes per environment amortise the scalar rules
+// over more environments per wave (best at tens of thousands of environments); many lanes
+// per environment give more waves and shorter per-wave loops (best at a few thousand).
+template <int G>
+struct Grp {
+    static constexpr int EPB = 256 / G;                    // environments per 256-thread block
+    static constexpr int NS_MOB = (NMOB + G - 1) / G;      // mob sub-slots per lane
+    static constexpr int NS_PLANT = (NPLANT + G - 1) / G;  // plant sub-slots per lane
 
-__device__ inline uint32_t gballot(bool pred)
-{
-    const uint64_t m = __ballot(pred);
-    const int shift = (threadIdx.x & 63) & ~(G - 1);
-    return (uint32_t)(m >> shift) & 0xFFFFu;
-}
-__device__ inline int gshfl(int v, int src_lane_in_group) { return __shfl(v, src_lane_in_group, G); }
+    // bit i of the result = predicate of lane i of this group
+    __device__ static inline uint32_t ballot(bool pred)
+    {
+        const uint64_t m = __ballot(pred);
+        const uint32_t lane = threadIdx.x & 63u;
+        const uint32_t half = (lane & 32u) ? (uint32_t)(m >> 32) : (uint32_t)m;
+        return __builtin_amdgcn_ubfe(half, lane & 31u & ~(uint32_t)(G - 1), (uint32_t)G);
+    }
+    __device__ static inline int shfl(int v, int src_lane_in_group) { return __shfl(v, src_lane_in_group, G); }
+};
 
 // LDS traffic inside one wave is executed in order, so a group only needs the compiler kept
 // from moving LDS accesses across the hand-over point.
@@ -154,11 +183,25 @@ __device__ inline void group_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__device__ inline bool in_map(int x, int y) { return (unsigned)x < (unsigned)MAPW && (unsigned)y < (unsigned)MAPW; }
-__device__ inline bool walkable_ground(int b) { return b == BK_GRASS || b == BK_SAND || b == BK_PATH; }
-__device__ inline bool arrow_flyable(int b) { return walkable_ground(b) || b == BK_WATER || b == BK_LAVA; }
+__device__ inline bool in_map(int x, int y) { return ((unsigned)x | (unsigned)y) < (unsigned)MAPW; }
+// block-id sets as bit masks
+constexpr uint32_t WALKABLE_MASK = (1u << BK_GRASS) | (1u << BK_SAND) | (1u << BK_PATH);
+constexpr uint32_t FLYABLE_MASK = WALKABLE_MASK | (1u << BK_WATER) | (1u << BK_LAVA);
+__device__ inline bool walkable_ground(int b) { return (WALKABLE_MASK >> b) & 1u; }
+__device__ inline bool arrow_flyable(int b) { return (FLYABLE_MASK >> b) & 1u; }
 __device__ inline int dir_dx(int d) { return d == 1 ? -1 : (d == 2 ? 1 : 0); }
 __device__ inline int dir_dy(int d) { return d == 3 ? -1 : (d == 4 ? 1 : 0); }
 __device__ inline int iabs(int v) { return v < 0 ? -v : v; }
+
+// Per-environment LDS area: record, 9x11 map window, one-hot bit staging, scalar vector.
+// The stride is 130 dwords: consecutive environments start two banks apart, so the 4..16
+// groups of a wave never collide on a bank when they touch the same field.
+constexpr int WIN_ROWS = 9, WIN_COLS = 11, WIN_CELLS = WIN_ROWS * WIN_COLS;   // 99
+constexpr int LDS_REC = 0;                       // 32 dwords
+constexpr int LDS_WIN = 32;                      // 99 bytes in 25 dwords
+constexpr int LDS_BITS = 57;                     // 1328 bits = 41.5 dwords -> 42
+constexpr int LDS_VEC = 99;                      // 24 dwords (22 scalars + padding)
+constexpr int LDS_ENV_DWORDS = 130;
+static_assert(LDS_VEC + 24 <= LDS_ENV_DWORDS, "per-environment LDS area overflows");
 
 }  // namespace cx

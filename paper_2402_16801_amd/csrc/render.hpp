@@ -10,75 +10,125 @@
 namespace cx {
 
 constexpr int OBS_STRIDE_U8_I8 = 1360, OBS_STRIDE_U8_F32 = 1424, OBS_STRIDE_F32 = 5392, OBS_STRIDE_PIXELS = 47632;
-constexpr int STAGE_CHUNKS = OBS_STRIDE_U8_F32 / 16;   // 89 uint4 of LDS staging per environment
+constexpr int CELL_CHUNKS = VEC_OFFSET / 16;   // 83 sixteen-byte chunks hold the 1323 one-hot bytes (+5 zero)
 
 __host__ __device__ constexpr int obs_stride(int mode)
 {
     return mode == 0 ? OBS_STRIDE_U8_I8 : mode == 1 ? OBS_STRIDE_U8_F32 : mode == 2 ? OBS_STRIDE_F32 : OBS_STRIDE_PIXELS;
 }
 
-// Renders one environment's symbolic observation with the 16 lanes of its group.
-// r: the environment's record in LDS (current).  stage: 89 uint4 of LDS owned by the group.
-// The one-hot bytes are assembled in LDS (zero fill, then one byte store per set channel) and
-// leave as 16-byte stores, so the HBM write is fully coalesced.
-template <int OBS_MODE>
-__device__ inline void render_symbolic(int l, const EnvRec* r, const uint8_t* __restrict__ map,
-                                       const Luts* __restrict__ luts, uint4* stage, uint8_t* __restrict__ obs_out)
+// four bits -> four 0/1 bytes (bit i -> byte i)
+__device__ inline uint32_t spread4(uint32_t nibble) { return (nibble * 0x00204081u) & 0x01010101u; }
+
+// Renders one environment's symbolic observation with the G lanes of its group.
+// e: the environment's LDS area; its record is current and its window holds the map around
+// (window centre) with the player displaced by (mvx, mvy) from that centre.
+// The one-hot channels are collected as single bits in LDS (one atomic OR per set channel),
+// then each lane expands 16 bits into a 16-byte store, so the HBM write is fully coalesced
+// and the staging costs 166 bytes of LDS per environment instead of 1323.
+template <int G, int OBS_MODE>
+__device__ inline void render_symbolic(int l, uint32_t* e, int mvx, int mvy, const Luts* __restrict__ luts,
+                                       uint8_t* __restrict__ obs_out)
 {
-    uint8_t* sb = reinterpret_cast<uint8_t*>(stage);
+    const uint32_t* rec = e + LDS_REC;
+    const uint8_t* win = reinterpret_cast<const uint8_t*>(e + LDS_WIN);
+    uint32_t* bits = e + LDS_BITS;
+    uint32_t* vec = e + LDS_VEC;
 #pragma unroll
-    for (int i = l; i < STAGE_CHUNKS; i += G) stage[i] = make_uint4(0, 0, 0, 0);
+    for (int it = 0; it < (42 + G - 1) / G; ++it) if (l + it * G < 42) bits[l + it * G] = 0u;
     group_sync();
-    const int px = r->px, py = r->py;
+    const uint32_t w_pos = rec[RW_POS];
+    const int px = w_pos & 0xFF, py = (w_pos >> 8) & 0xFF;
 #pragma unroll
-    for (int c = l; c < VIEW_ROWS * VIEW_COLS; c += G) {
+    for (int it_c = 0; it_c < ((VIEW_ROWS * VIEW_COLS) + G - 1) / G; ++it_c) {
+        const int c = l + it_c * G;
+        if (c >= (VIEW_ROWS * VIEW_COLS)) break;
         const int row = c / VIEW_COLS, col = c - row * VIEW_COLS;
-        const int x = px + col - VIEW_COLS / 2, y = py + row - VIEW_ROWS / 2;
-        const int b = in_map(x, y) ? (int)map[y * MAPW + x] : (int)BK_OOB;
-        sb[c * NCHAN + b] = 1;
-    }
-    if (l < NMOB) {
-        const Mob m = r->mob[l];
-        const int col = (int)m.x - px + VIEW_COLS / 2, row = (int)m.y - py + VIEW_ROWS / 2;
-        if (m.alive && (unsigned)col < (unsigned)VIEW_COLS && (unsigned)row < (unsigned)VIEW_ROWS)
-            sb[(row * VIEW_COLS + col) * NCHAN + 17 + l / 3] = 1;
+        const int b = win[(row + 1 + mvy) * WIN_COLS + col + 1 + mvx];
+        const int bit = c * NCHAN + b;
+        atomicOr(&bits[bit >> 5], 1u << (bit & 31));
     }
 #pragma unroll
-    for (int i = l; i < NVEC; i += G) {
-        int raw;
-        if (i < 12) raw = r->inv[i];
-        else if (i < 16) raw = r->vit[i - 12];
-        else if (i < 20) raw = (r->dir == i - 15) ? 1 : 0;
-        else if (i == 20) raw = 0;
-        else raw = r->sleeping;
-        if (OBS_MODE == 0) {
-            if (i == 20) raw = luts->light_q7[r->phase];
-            reinterpret_cast<int8_t*>(sb + VEC_OFFSET)[i] = (int8_t)raw;
-        } else {
-            float v;
-            if (i < 6) v = luts->sqrt10[raw];
-            else if (i < 12) v = (float)raw;
-            else if (i < 16) v = luts->tenth[raw];
-            else if (i == 20) v = luts->daylight[r->phase];
-            else v = (float)raw;
-            reinterpret_cast<float*>(sb + VEC_OFFSET)[i] = v;
+    for (int it_k = 0; it_k < ((NMOB) + G - 1) / G; ++it_k) {
+        const int k = l + it_k * G;
+        if (k >= (NMOB)) break;
+        const Mob m = unpack_mob(rec[RW_MOB + k]);
+        const int col = m.x - px + VIEW_COLS / 2, row = m.y - py + VIEW_ROWS / 2;
+        if (m.alive && (unsigned)col < (unsigned)VIEW_COLS && (unsigned)row < (unsigned)VIEW_ROWS) {
+            const int bit = (row * VIEW_COLS + col) * NCHAN + 17 + ((k * 11) >> 5);
+            atomicOr(&bits[bit >> 5], 1u << (bit & 31));
+        }
+    }
+    // the 22 scalars; int8 flavour packs four per dword
+    const uint32_t w_inv = rec[RW_INV], w_vit = rec[RW_VIT];
+    const int dir = (w_pos >> 16) & 0xFF, sleeping = (w_pos >> 24) & 0xFF;
+    const uint32_t phase = w_vit >> 16;
+    auto raw_of = [&](int i) -> int {
+        if (i < 6) return (w_inv >> (4 * i)) & 15;
+        if (i < 12) return (w_inv >> (18 + i)) & 1;
+        if (i < 16) return (w_vit >> (4 * (i - 12))) & 15;
+        if (i < 20) return dir == i - 15 ? 1 : 0;
+        if (i == 20) return (int)luts->light_q7[phase];
+        if (i == 21) return sleeping;
+        return 0;
+    };
+    if (OBS_MODE == 0) {
+#pragma unroll
+        for (int it_i = 0; it_i < ((8) + G - 1) / G; ++it_i) {
+        const int i = l + it_i * G;
+        if (i >= (8)) break;
+            uint32_t w = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w |= ((uint32_t)raw_of(4 * i + j) & 0xFFu) << (8 * j);
+            vec[i] = w;
+        }
+    } else {
+#pragma unroll
+        for (int it_i = 0; it_i < ((24) + G - 1) / G; ++it_i) {
+        const int i = l + it_i * G;
+        if (i >= (24)) break;
+            float v = 0.0f;
+            if (i < NVEC) {
+                const int raw = raw_of(i);
+                if (i < 6) v = luts->sqrt10[raw];
+                else if (i >= 12 && i < 16) v = luts->tenth[raw];
+                else if (i == 20) v = luts->daylight[phase];
+                else v = (float)raw;
+            }
+            vec[i] = __float_as_uint(v);
         }
     }
     group_sync();
     if (OBS_MODE == 0 || OBS_MODE == 1) {
         uint4* out = reinterpret_cast<uint4*>(obs_out);
+        const uint16_t* hb = reinterpret_cast<const uint16_t*>(bits);
 #pragma unroll
-        for (int i = l; i < obs_stride(OBS_MODE) / 16; i += G) out[i] = stage[i];
+        for (int it_i = 0; it_i < ((obs_stride(OBS_MODE) / 16) + G - 1) / G; ++it_i) {
+        const int i = l + it_i * G;
+        if (i >= (obs_stride(OBS_MODE) / 16)) break;
+            uint4 v;
+            if (i < CELL_CHUNKS) {
+                const uint32_t h = hb[i];
+                v = make_uint4(spread4(h & 15u), spread4((h >> 4) & 15u), spread4((h >> 8) & 15u), spread4(h >> 12));
+            } else {
+                const int j = (i - CELL_CHUNKS) * 4;
+                v = make_uint4(vec[j], vec[j + 1], vec[j + 2], vec[j + 3]);
+            }
+            out[i] = v;
+        }
     } else {
-        // float[1345]: expand four staged bytes (or copy four staged floats) per 16-byte store
+        // float[1345]: four values per 16-byte store
         float4* out = reinterpret_cast<float4*>(obs_out);
-        const float* sv = reinterpret_cast<const float*>(sb + VEC_OFFSET);
-        for (int i = l; i < OBS_STRIDE_F32 / 16; i += G) {
+        for (int it_i = 0; it_i < ((OBS_STRIDE_F32 / 16) + G - 1) / G; ++it_i) {
+        const int i = l + it_i * G;
+        if (i >= (OBS_STRIDE_F32 / 16)) break;
             float v[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int idx = 4 * i + j;
-                v[j] = idx < CELL_BYTES ? (float)sb[idx] : (idx < CELL_BYTES + NVEC ? sv[idx - CELL_BYTES] : 0.0f);
+                if (idx < CELL_BYTES) v[j] = (float)((bits[idx >> 5] >> (idx & 31)) & 1u);
+                else if (idx < CELL_BYTES + NVEC) v[j] = __uint_as_float(vec[idx - CELL_BYTES]);
+                else v[j] = 0.0f;
             }
             out[i] = make_float4(v[0], v[1], v[2], v[3]);
         }
@@ -88,12 +138,13 @@ __device__ inline void render_symbolic(int l, const EnvRec* r, const uint8_t* __
 
 // Pixel observation of one environment by a whole block (256 threads): 63x63x3 floats.
 // Each texel is one table value times the daylight value (a single IEEE multiply).
-__device__ inline void render_pixels_block(const EnvRec* __restrict__ rec, const uint8_t* __restrict__ map,
+__device__ inline void render_pixels_block(const uint32_t* __restrict__ rec, const uint8_t* __restrict__ map,
                                            const Luts* __restrict__ luts, float* __restrict__ out,
                                            int* s_tile /* 81 */, int* s_ent /* 81 */)
 {
     const int tid = threadIdx.x;
-    const int px = rec->px, py = rec->py;
+    const uint32_t w_pos = rec[RW_POS];
+    const int px = w_pos & 0xFF, py = (w_pos >> 8) & 0xFF;
     if (tid < 81) {
         const int tr = tid / 9, tc = tid - tr * 9;
         const int x = px + tc - 4, y = py + tr - 4;
@@ -102,12 +153,12 @@ __device__ inline void render_pixels_block(const EnvRec* __restrict__ rec, const
     }
     __syncthreads();
     if (tid < NMOB) {
-        const Mob m = rec->mob[tid];
-        const int tc = (int)m.x - px + 4, tr = (int)m.y - py + 4;
+        const Mob m = unpack_mob(rec[RW_MOB + tid]);
+        const int tc = m.x - px + 4, tr = m.y - py + 4;
         if (m.alive && (unsigned)tc < 9u && (unsigned)tr < 9u) s_ent[tr * 9 + tc] = 1 + tid / 3;
     }
     __syncthreads();
-    const float light = luts->daylight[rec->phase];
+    const float light = luts->daylight[rec[RW_VIT] >> 16];
     for (int i = tid; i < 63 * 63 * 3; i += 256) {
         const int ch = i % 3, pix = i / 3;
         const int gx = pix % 63, gy = pix / 63;

@@ -93,19 +93,20 @@ __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat
     __syncthreads();
     // thread tid owns the 16 cells [16 tid, 16 tid + 16): one quarter of row tid/4
     const int y = tid >> 2, x0 = (tid & 3) << 4;
-    uint32_t packed[4];
-#pragma unroll
+    uint32_t packed[4] = { 0u, 0u, 0u, 0u };
+#pragma unroll 1
     for (int half = 0; half < 2; ++half) {
         const U4 r = philox4x32_10(env, 1u, episode, (DOM_WORLDGEN << 16) | (uint32_t)(2 * tid + half), seed_lo, seed_hi);
-#pragma unroll
+#pragma unroll 1
         for (int w = 0; w < 4; ++w) {
+            const uint32_t rw = w == 0 ? r.w[0] : (w == 1 ? r.w[1] : (w == 2 ? r.w[2] : r.w[3]));
             const int xa = x0 + half * 8 + 2 * w;
-            const uint32_t ba = (uint32_t)terrain_cell(s_lat, xa, y, (int)(r.w[w] & 0xFFFFu));
-            const uint32_t bb = (uint32_t)terrain_cell(s_lat, xa + 1, y, (int)(r.w[w] >> 16));
-            const int cell = half * 8 + 2 * w;            // 0..15 within this thread's run
-            const int shift = (cell & 3) * 8;
-            if ((cell & 3) == 0) packed[cell >> 2] = 0;
-            packed[cell >> 2] |= (ba << shift) | (bb << (shift + 8));
+            const uint32_t ba = (uint32_t)terrain_cell(s_lat, xa, y, (int)(rw & 0xFFFFu));
+            const uint32_t bb = (uint32_t)terrain_cell(s_lat, xa + 1, y, (int)(rw >> 16));
+            const uint32_t pair = ba | (bb << 8);          // cells 2w, 2w+1 of this half
+            const uint32_t word = pair << ((w & 1) * 16);
+            if (half == 0) { if (w < 2) packed[0] |= word; else packed[1] |= word; }
+            else           { if (w < 2) packed[2] |= word; else packed[3] |= word; }
         }
     }
     reinterpret_cast<uint4*>(map)[tid] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
@@ -113,14 +114,14 @@ __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat
 }
 
 // A fresh record for a new episode: full vitals, empty tables, player in the middle facing down.
-__device__ inline void fresh_record(EnvRec* r, uint32_t seed_lo, uint32_t seed_hi, uint32_t episode)
+__device__ inline void fresh_record(uint32_t* rec, uint32_t seed_lo, uint32_t seed_hi, uint32_t episode)
 {
-    uint32_t* w = reinterpret_cast<uint32_t*>(r);
-    for (int i = 0; i < 64; ++i) w[i] = 0;
-    r->px = MAPW / 2; r->py = MAPW / 2; r->dir = 4;
-    r->vit[0] = r->vit[1] = r->vit[2] = r->vit[3] = MAX_COUNT;
-    r->episode = episode;
-    r->seed_lo = seed_lo; r->seed_hi = seed_hi;
+    for (int i = 0; i < REC_DWORDS; ++i) rec[i] = 0;
+    rec[RW_POS] = (uint32_t)(MAPW / 2) | ((uint32_t)(MAPW / 2) << 8) | (4u << 16);
+    rec[RW_VIT] = (uint32_t)MAX_COUNT * 0x1111u;
+    rec[RW_EPISODE] = episode;
+    rec[RW_SEED_LO] = seed_lo;
+    rec[RW_SEED_HI] = seed_hi;
 }
 
 }  // namespace cx

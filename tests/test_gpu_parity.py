@@ -27,12 +27,25 @@ def _cfgs(cx, obs_mode, **kw):
     return g, o
 
 
+def _make_sim(cx, n, gcfg, lanes=None):
+    """lanes: lanes per environment of the step kernel (4, 8, 16) or None for the default."""
+    import os
+    if lanes is None:
+        os.environ.pop("CRAFTAX_GROUP_LANES", None)
+    else:
+        os.environ["CRAFTAX_GROUP_LANES"] = str(lanes)
+    try:
+        return cx.Craftax(n, gcfg)
+    finally:
+        os.environ.pop("CRAFTAX_GROUP_LANES", None)
+
+
 def run_parity(cx, n, T, obs_mode, kind, sample=None, action_seed=0, state_every=0, obs_every=1,
-               seed_base=0, device_actions=False, progress=None, **cfgkw):
+               seed_base=0, device_actions=False, progress=None, lanes=None, **cfgkw):
     """Steps n GPU environments and the oracle on `sample` (default: all) and compares."""
     import torch
     gcfg, ocfg = _cfgs(cx, obs_mode, **cfgkw)
-    sim = cx.Craftax(n, gcfg)
+    sim = _make_sim(cx, n, gcfg, lanes)
     ids = np.arange(n) if sample is None else np.asarray(sample)
     idx_dev = torch.as_tensor(ids, device=sim.device, dtype=torch.long)
     orc = po.Oracle(len(ids), ocfg, obs_mode)
@@ -121,15 +134,27 @@ def test_config5_pixels_1024_envs_sampled(cx):
 
 
 # ---- shapes and edge cases ----------------------------------------------------------------------
-@pytest.mark.parametrize("n", [1, 5, 16, 17, 33, 250])
-def test_ragged_counts(cx, n):
-    run_parity(cx, n, 120, po.OBS_SYM_U8_F32, "skewed", state_every=40, max_episode_steps=50)
+@pytest.mark.parametrize("lanes", [4, 8, 16])
+@pytest.mark.parametrize("n", [1, 5, 16, 17, 33, 65, 250])
+def test_ragged_counts(cx, n, lanes):
+    run_parity(cx, n, 120, po.OBS_SYM_U8_F32, "skewed", state_every=40, max_episode_steps=50, lanes=lanes)
 
 
-def test_many_resets_in_one_block(cx):
+@pytest.mark.parametrize("lanes", [4, 8, 16])
+def test_every_group_width_full_compare(cx, lanes):
+    """The step kernel exists for 4, 8 and 16 lanes per environment; each is checked on every
+    output and the whole state, with frequent resets, for every observation layout."""
+    run_parity(cx, 96, 400, po.OBS_SYM_U8_F32, "uniform", state_every=1, max_episode_steps=90, lanes=lanes)
+    run_parity(cx, 70, 150, po.OBS_SYM_U8_I8, "skewed", state_every=5, max_episode_steps=40, lanes=lanes)
+    run_parity(cx, 70, 100, po.OBS_SYM_F32, "skewed", state_every=5, max_episode_steps=40, lanes=lanes)
+    run_parity(cx, 70, 100, po.OBS_PIXELS_F32, "uniform", state_every=5, obs_every=10, max_episode_steps=40, lanes=lanes)
+
+
+@pytest.mark.parametrize("lanes", [4, 8, 16])
+def test_many_resets_in_one_block(cx, lanes):
     """Episodes of 3 steps: every environment of a block finishes in the same step."""
-    run_parity(cx, 48, 40, po.OBS_SYM_U8_F32, "uniform", state_every=1, max_episode_steps=3)
-    run_parity(cx, 37, 30, po.OBS_SYM_U8_I8, "uniform", state_every=1, max_episode_steps=1)
+    run_parity(cx, 80, 40, po.OBS_SYM_U8_F32, "uniform", state_every=1, max_episode_steps=3, lanes=lanes)
+    run_parity(cx, 37, 30, po.OBS_SYM_U8_I8, "uniform", state_every=1, max_episode_steps=1, lanes=lanes)
 
 
 def test_paper_float_layout(cx):
@@ -166,12 +191,13 @@ def test_out_of_range_actions_are_noop(cx):
     assert sim.export_envs().tobytes() == orc.envs.tobytes()
 
 
-def test_import_export_round_trip_and_scripted_scene(cx):
+@pytest.mark.parametrize("lanes", [4, 8, 16])
+def test_import_export_round_trip_and_scripted_scene(cx, lanes):
     """State editing: push hand-made oracle states to the GPU, step both, compare."""
     import torch
     n = 20
     gcfg, ocfg = _cfgs(cx, po.OBS_SYM_U8_F32)
-    sim = cx.Craftax(n, gcfg)
+    sim = _make_sim(cx, n, gcfg, lanes)
     orc = po.Oracle(n, ocfg)
     seeds = synth.seeds_for(n, 50)
     sim.reset(seeds); orc.reset(seeds)
@@ -193,7 +219,6 @@ def test_import_export_round_trip_and_scripted_scene(cx):
     e["mob"][:, 10] = (1, 32, 36, 3, 0, 0, (0, 0))
     sim.import_envs(e.copy())
     assert sim.export_envs().tobytes() == e.tobytes()
-    assert np.array_equal(sim.obs.cpu().numpy() * 0, sim.obs.cpu().numpy() * 0)
     for s in range(80):
         a = synth.actions(np.arange(n), s, "uniform", action_seed=77)
         a[s % n] = s % 17            # make sure every action id is exercised in this scene
