@@ -138,8 +138,11 @@ struct Header {
     uint32_t obs_mode, max_episode_steps, day_length;
     uint32_t cap_zombie, cap_cow, cap_skeleton, cap_arrow, cap_plant;
     uint64_t atlas_seed;
-    uint64_t off_luts, off_recs, off_maps, total;
+    uint64_t off_luts, off_recs, off_maps, off_done, total;
 };
+// two device-side counters of the done list live in the first 256 bytes of the state blob
+constexpr uint64_t DONE_COUNT_OFFSET = 192;
+static_assert(sizeof(Header) <= DONE_COUNT_OFFSET, "header overlaps the done-list counters");
 constexpr uint64_t MAGIC = 0x43524146544158ull;  // "CRAFTAX"
 
 // Scalars every kernel needs, passed by value.

@@ -52,8 +52,10 @@ __device__ inline void store_record(int l, uint4* __restrict__ grec, const uint3
 // reset: one block per environment (appendix "Optimistic Environment Resets" explains why
 // world generation is the expensive part; here it is spread over 256 threads).
 __global__ __launch_bounds__(BLOCK) void k_reset(uint4* __restrict__ recs, uint8_t* __restrict__ maps,
-                                                 const uint64_t* __restrict__ seeds, Params p)
+                                                 const uint64_t* __restrict__ seeds, uint32_t* done_count,
+                                                 uint32_t* done_finished, Params p)
 {
+    if (blockIdx.x == 0 && threadIdx.x == 0) { *done_count = 0u; *done_finished = 0u; }
     __shared__ uint16_t s_lat[LAT_BLOCKS * 8];
     __shared__ uint32_t s_rec[REC_DWORDS];
     const uint32_t env = blockIdx.x;
@@ -66,60 +68,90 @@ __global__ __launch_bounds__(BLOCK) void k_reset(uint4* __restrict__ recs, uint8
 }
 
 // ---------------------------------------------------------------------------------------------
-// step: G lanes per environment, 256/G environments per block.  Finished episodes are
-// regenerated by the whole block before their first observation is rendered.
+// step: G lanes per environment, 256/G environments per block.  Environments whose episode
+// ended are not written back; their indices are appended to the state's done list, which
+// k_reset_list consumes right after (same stream), spreading world generation over the
+// whole chip instead of stretching the tail of a few step blocks.
+struct DoneList { uint32_t* count; uint32_t* finished; uint32_t* list; };
+
 template <int G, int OBS_MODE>
 __global__ __launch_bounds__(BLOCK, 4) void k_step(uint4* __restrict__ recs, uint8_t* __restrict__ maps,
-                                                const Luts* __restrict__ luts, const int32_t* __restrict__ actions,
-                                                uint8_t* __restrict__ obs, float* __restrict__ reward,
-                                                uint8_t* __restrict__ done, Params p)
+                                                   const Luts* __restrict__ luts, const int32_t* __restrict__ actions,
+                                                   uint8_t* __restrict__ obs, float* __restrict__ reward,
+                                                   uint8_t* __restrict__ done, DoneList dl, Params p)
 {
     constexpr int EPB = Grp<G>::EPB;
     __shared__ uint32_t s_env[EPB * LDS_ENV_DWORDS];
-    __shared__ uint16_t s_lat[LAT_BLOCKS * 8];
     __shared__ int s_ndone;
+    __shared__ uint32_t s_base;
     __shared__ int s_list[EPB];
 
     const int tid = threadIdx.x, g = tid / G, l = tid % G;
     const int env = blockIdx.x * EPB + g;
     const bool active = env < p.n;
     if (tid == 0) s_ndone = 0;
+    __syncthreads();
     uint32_t* e = s_env + g * LDS_ENV_DWORDS;
     uint8_t* map = maps + (size_t)(active ? env : 0) * (MAPW * MAPW);
     constexpr bool kSymbolic = OBS_MODE != CRAFTAX_OBS_PIXELS_F32;
-    bool finished = false;
     if (active) {
         load_record<G>(l, recs + (size_t)env * 8, e);
         group_sync();
         const StepOut o = step_env<G>(l, (uint32_t)env, e, map, luts, actions[env], p);
-        finished = o.done;
         if (l == 0) { reward[env] = o.reward; done[env] = o.done ? 1 : 0; }
-        if (!finished) {
+        if (!o.done) {
             store_record<G>(l, recs + (size_t)env * 8, e);
             if (kSymbolic && obs != nullptr)
                 render_symbolic<G, OBS_MODE>(l, e, o.mvx, o.mvy, luts, obs + (size_t)env * obs_stride(OBS_MODE));
+        } else if (l == 0) {
+            s_list[atomicAdd(&s_ndone, 1)] = env;
         }
     }
-    // a group-uniform vote keeps the common case (nobody finished) free of LDS atomics
-    if (finished && l == 0) s_list[atomicAdd(&s_ndone, 1)] = g;
     __syncthreads();
     const int nd = s_ndone;
     if (nd == 0) return;
-    for (int i = 0; i < nd; ++i) {
-        const int gg = s_list[i];
-        const uint32_t e2 = (uint32_t)(blockIdx.x * EPB + gg);
-        uint32_t* rr = s_env + gg * LDS_ENV_DWORDS + LDS_REC;
-        const uint32_t lo = rr[RW_SEED_LO], hi = rr[RW_SEED_HI], ep = rr[RW_EPISODE] + 1u;
-        worldgen_block(maps + (size_t)e2 * (MAPW * MAPW), s_lat, lo, hi, e2, ep);
-        if (tid == 0) fresh_record(rr, lo, hi, ep);
+    if (tid == 0) s_base = atomicAdd(dl.count, (uint32_t)nd);
+    __syncthreads();
+    if (tid < nd) dl.list[s_base + tid] = (uint32_t)s_list[tid];
+}
+
+// Regenerates every environment on the done list (one block each, looping if the list is
+// longer than the grid), renders its first observation, and clears the list for the next step.
+template <int OBS_MODE>
+__global__ __launch_bounds__(BLOCK) void k_reset_list(uint4* __restrict__ recs, uint8_t* __restrict__ maps,
+                                                      const Luts* __restrict__ luts, uint8_t* __restrict__ obs,
+                                                      DoneList dl, Params p)
+{
+    constexpr int G = 16;
+    __shared__ uint16_t s_lat[LAT_BLOCKS * 8];
+    __shared__ uint32_t s_env[LDS_ENV_DWORDS];
+    const uint32_t count = *dl.count;
+    if (blockIdx.x >= count) return;
+    const int tid = threadIdx.x;
+    constexpr bool kSymbolic = OBS_MODE != CRAFTAX_OBS_PIXELS_F32;
+    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
+        const uint32_t env = dl.list[i];
+        uint32_t* grec = reinterpret_cast<uint32_t*>(recs + (size_t)env * 8);
+        const uint32_t lo = grec[RW_SEED_LO], hi = grec[RW_SEED_HI], ep = grec[RW_EPISODE] + 1u;
+        uint8_t* map = maps + (size_t)env * (MAPW * MAPW);
+        worldgen_block(map, s_lat, lo, hi, env, ep);           // ends with a block barrier
+        if (tid == 0) fresh_record(s_env + LDS_REC, lo, hi, ep);
         __syncthreads();
-        if (tid < REC_DWORDS) reinterpret_cast<uint32_t*>(recs + (size_t)e2 * 8)[tid] = rr[tid];
+        if (tid < REC_DWORDS) grec[tid] = s_env[LDS_REC + tid];
+        if (kSymbolic && obs != nullptr && tid < G) {
+            load_window<G>(tid, MAPW / 2, MAPW / 2, map, reinterpret_cast<uint8_t*>(s_env + LDS_WIN));
+            group_sync();
+            render_symbolic<G, OBS_MODE>(tid, s_env, 0, 0, luts, obs + (size_t)env * obs_stride(OBS_MODE));
+        }
+        __syncthreads();
     }
-    __syncthreads();   // the new maps are visible to the whole block
-    if (finished && kSymbolic && obs != nullptr) {
-        load_window<G>(l, MAPW / 2, MAPW / 2, map, reinterpret_cast<uint8_t*>(e + LDS_WIN));
-        group_sync();
-        render_symbolic<G, OBS_MODE>(l, e, 0, 0, luts, obs + (size_t)env * obs_stride(OBS_MODE));
+    // the last working block clears the list; blocks beyond the list never touched it
+    __shared__ bool s_last;
+    if (tid == 0) {
+        const uint32_t workers = count < gridDim.x ? count : gridDim.x;
+        __threadfence();
+        s_last = atomicAdd(dl.finished, 1u) == workers - 1u;
+        if (s_last) { *dl.count = 0u; *dl.finished = 0u; }
     }
 }
 
@@ -287,7 +319,8 @@ static Header make_header(const craftax_config* c, int n)
     h.off_luts = 256;
     h.off_recs = round_up(h.off_luts + sizeof(Luts), 256);
     h.off_maps = h.off_recs + (uint64_t)n * (REC_DWORDS * 4);
-    h.total = h.off_maps + (uint64_t)n * (MAPW * MAPW);
+    h.off_done = h.off_maps + (uint64_t)n * (MAPW * MAPW);
+    h.total = round_up(h.off_done + (uint64_t)n * 4, 256);
     return h;
 }
 
@@ -348,7 +381,7 @@ static int check_launch(const char* what)
     return CRAFTAX_OK;
 }
 
-struct Ptrs { uint4* recs; uint8_t* maps; const Luts* luts; };
+struct Ptrs { uint4* recs; uint8_t* maps; const Luts* luts; DoneList dl; };
 static Ptrs pointers(const void* state, const HostState& s)
 {
     uint8_t* base = const_cast<uint8_t*>(static_cast<const uint8_t*>(state));
@@ -356,6 +389,9 @@ static Ptrs pointers(const void* state, const HostState& s)
     q.luts = reinterpret_cast<const Luts*>(base + s.hdr.off_luts);
     q.recs = reinterpret_cast<uint4*>(base + s.hdr.off_recs);
     q.maps = base + s.hdr.off_maps;
+    q.dl.count = reinterpret_cast<uint32_t*>(base + DONE_COUNT_OFFSET);
+    q.dl.finished = q.dl.count + 1;
+    q.dl.list = reinterpret_cast<uint32_t*>(base + s.hdr.off_done);
     return q;
 }
 
@@ -371,14 +407,17 @@ static int group_lanes(int n)
     return n >= 32768 ? 4 : (n >= 8192 ? 8 : 16);
 }
 
+constexpr int RESET_GRID = 1024;   // blocks of k_reset_list; those beyond the list exit at once
+
 template <int OBS_MODE>
 static void launch_step(int G, int n, hipStream_t st, const Ptrs& q, const int32_t* actions, uint8_t* o, float* reward,
                         uint8_t* done, const Params& p)
 {
     const dim3 block(BLOCK);
-    if (G == 4) hipLaunchKernelGGL((k_step<4, OBS_MODE>), dim3((n + 63) / 64), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, p);
-    else if (G == 8) hipLaunchKernelGGL((k_step<8, OBS_MODE>), dim3((n + 31) / 32), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, p);
-    else hipLaunchKernelGGL((k_step<16, OBS_MODE>), dim3((n + 15) / 16), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, p);
+    if (G == 4) hipLaunchKernelGGL((k_step<4, OBS_MODE>), dim3((n + 63) / 64), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.dl, p);
+    else if (G == 8) hipLaunchKernelGGL((k_step<8, OBS_MODE>), dim3((n + 31) / 32), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.dl, p);
+    else hipLaunchKernelGGL((k_step<16, OBS_MODE>), dim3((n + 15) / 16), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.dl, p);
+    hipLaunchKernelGGL((k_reset_list<OBS_MODE>), dim3(n < RESET_GRID ? n : RESET_GRID), block, 0, st, q.recs, q.maps, q.luts, o, q.dl, p);
 }
 
 }  // namespace cx
@@ -448,7 +487,8 @@ int craftax_reset(void* state, const uint64_t* seeds, int n, void* stream)
     if (int rc = lookup(state, n, true, &s)) return rc;
     if (!seeds) return fail(CRAFTAX_E_NULL, "seeds is NULL");
     const Ptrs q = pointers(state, s);
-    hipLaunchKernelGGL(k_reset, dim3(n), dim3(BLOCK), 0, (hipStream_t)stream, q.recs, q.maps, seeds, make_params(s));
+    hipLaunchKernelGGL(k_reset, dim3(n), dim3(BLOCK), 0, (hipStream_t)stream, q.recs, q.maps, seeds, q.dl.count, q.dl.finished,
+                       make_params(s));
     return check_launch("craftax_reset");
 }
 

@@ -27,31 +27,22 @@ constexpr int START_CLEAR = 2, START_BIAS_R = 10, START_BIAS = 2500;
 __device__ inline uint32_t smooth8(int k) { return (uint32_t)(12 * k * k - k * k * k); }
 __device__ inline uint32_t smooth16(int k) { return (uint32_t)((24 * k * k - k * k * k + 4) >> 3); }
 
-// One row's worth of bilinear interpolation: lattice rows j and j+1 blended with weight wy.
-__device__ inline uint32_t bilerp(const uint16_t* lat, int width, int ix, int iy, uint32_t wx, uint32_t wy)
+// Bilinear value noise, evaluated column-first: the caller blends the two lattice rows once
+// per lattice column (vertical weight wy), then every cell of the run blends two columns
+// (horizontal weight wx).  The integer result equals the row-first formula
+// ((a(256-wx)+b wx)(256-wy) + (c(256-wx)+d wx) wy) >> 16 because nothing is rounded before
+// the final shift and every intermediate fits in 32 bits.
+__device__ inline uint32_t column(const uint16_t* lat, int width, int ix, int iy, uint32_t wy)
 {
-    const uint32_t a = lat[iy * width + ix], b = lat[iy * width + ix + 1];
-    const uint32_t c = lat[(iy + 1) * width + ix], d = lat[(iy + 1) * width + ix + 1];
-    const uint32_t top = a * (256u - wx) + b * wx;
-    const uint32_t bot = c * (256u - wx) + d * wx;
-    return (top * (256u - wy) + bot * wy) >> 16;
+    return (uint32_t)lat[iy * width + ix] * (256u - wy) + (uint32_t)lat[(iy + 1) * width + ix] * wy;
+}
+__device__ inline uint32_t across(uint32_t left, uint32_t right, uint32_t wx)
+{
+    return (left * (256u - wx) + right * wx) >> 16;
 }
 
-__device__ inline int terrain_cell(const uint16_t* lat, int x, int y, int u)
+__device__ inline int classify(int W, int M, int C, int F, int x, int y, int u)
 {
-    const uint16_t* w16 = lat;
-    const uint16_t* m16 = lat + LAT16_N;
-    const uint16_t* w8 = lat + 2 * LAT16_N;
-    const uint16_t* m8 = w8 + LAT8_N;
-    const uint16_t* c8 = m8 + LAT8_N;
-    const uint16_t* f8 = c8 + LAT8_N;
-    const int ix16 = x >> 4, iy16 = y >> 4, ix8 = x >> 3, iy8 = y >> 3;
-    const uint32_t wx16 = smooth16(x & 15), wy16 = smooth16(y & 15);
-    const uint32_t wx8 = smooth8(x & 7), wy8 = smooth8(y & 7);
-    int W = (int)((3u * bilerp(w16, 5, ix16, iy16, wx16, wy16) + bilerp(w8, 9, ix8, iy8, wx8, wy8)) >> 2);
-    int M = (int)((3u * bilerp(m16, 5, ix16, iy16, wx16, wy16) + bilerp(m8, 9, ix8, iy8, wx8, wy8)) >> 2);
-    const int C = (int)bilerp(c8, 9, ix8, iy8, wx8, wy8);
-    const int F = (int)bilerp(f8, 9, ix8, iy8, wx8, wy8);
     const int d = max(iabs(x - MAPW / 2), iabs(y - MAPW / 2));
     if (d < START_BIAS_R) {
         const int bias = (START_BIAS_R - d) * START_BIAS;
@@ -91,22 +82,45 @@ __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat
         }
     }
     __syncthreads();
-    // thread tid owns the 16 cells [16 tid, 16 tid + 16): one quarter of row tid/4
+    // thread tid owns the 16 cells [16 tid, 16 tid + 16): one quarter of row tid/4.  Its run
+    // spans one spacing-16 lattice cell and two spacing-8 lattice cells.
     const int y = tid >> 2, x0 = (tid & 3) << 4;
+    const uint16_t* w16 = s_lat;
+    const uint16_t* m16 = s_lat + LAT16_N;
+    const uint16_t* w8 = s_lat + 2 * LAT16_N;
+    const uint16_t* m8 = w8 + LAT8_N;
+    const uint16_t* c8 = m8 + LAT8_N;
+    const uint16_t* f8 = c8 + LAT8_N;
+    const int iy16 = y >> 4, iy8 = y >> 3, ix16 = x0 >> 4, ix8 = x0 >> 3;
+    const uint32_t wy16 = smooth16(y & 15), wy8 = smooth8(y & 7);
+    const uint32_t W16a = column(w16, 5, ix16, iy16, wy16), W16b = column(w16, 5, ix16 + 1, iy16, wy16);
+    const uint32_t M16a = column(m16, 5, ix16, iy16, wy16), M16b = column(m16, 5, ix16 + 1, iy16, wy16);
+    uint32_t W8[3], M8[3], C8[3], F8[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        W8[i] = column(w8, 9, ix8 + i, iy8, wy8);
+        M8[i] = column(m8, 9, ix8 + i, iy8, wy8);
+        C8[i] = column(c8, 9, ix8 + i, iy8, wy8);
+        F8[i] = column(f8, 9, ix8 + i, iy8, wy8);
+    }
     uint32_t packed[4] = { 0u, 0u, 0u, 0u };
-#pragma unroll 1
+#pragma unroll
     for (int half = 0; half < 2; ++half) {
         const U4 r = philox4x32_10(env, 1u, episode, (DOM_WORLDGEN << 16) | (uint32_t)(2 * tid + half), seed_lo, seed_hi);
+        const uint32_t Wl = W8[half], Wr = W8[half + 1], Ml = M8[half], Mr = M8[half + 1];
+        const uint32_t Cl = C8[half], Cr = C8[half + 1], Fl = F8[half], Fr = F8[half + 1];
 #pragma unroll 1
-        for (int w = 0; w < 4; ++w) {
+        for (int j = 0; j < 8; ++j) {
+            const int w = j >> 1;
             const uint32_t rw = w == 0 ? r.w[0] : (w == 1 ? r.w[1] : (w == 2 ? r.w[2] : r.w[3]));
-            const int xa = x0 + half * 8 + 2 * w;
-            const uint32_t ba = (uint32_t)terrain_cell(s_lat, xa, y, (int)(rw & 0xFFFFu));
-            const uint32_t bb = (uint32_t)terrain_cell(s_lat, xa + 1, y, (int)(rw >> 16));
-            const uint32_t pair = ba | (bb << 8);          // cells 2w, 2w+1 of this half
-            const uint32_t word = pair << ((w & 1) * 16);
-            if (half == 0) { if (w < 2) packed[0] |= word; else packed[1] |= word; }
-            else           { if (w < 2) packed[2] |= word; else packed[3] |= word; }
+            const int u = (int)((j & 1) ? (rw >> 16) : (rw & 0xFFFFu));
+            const uint32_t wx8 = smooth8(j), wx16 = smooth16(half * 8 + j);
+            const int W = (int)((3u * across(W16a, W16b, wx16) + across(Wl, Wr, wx8)) >> 2);
+            const int M = (int)((3u * across(M16a, M16b, wx16) + across(Ml, Mr, wx8)) >> 2);
+            const int C = (int)across(Cl, Cr, wx8), F = (int)across(Fl, Fr, wx8);
+            const uint32_t b = (uint32_t)classify(W, M, C, F, x0 + half * 8 + j, y, u);
+            const uint32_t word = b << ((j & 3) * 8);
+            if (j < 4) packed[2 * half] |= word; else packed[2 * half + 1] |= word;
         }
     }
     reinterpret_cast<uint4*>(map)[tid] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
