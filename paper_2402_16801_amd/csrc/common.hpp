@@ -196,15 +196,19 @@ __device__ inline int dir_dx(int d) { return d == 1 ? -1 : (d == 2 ? 1 : 0); }
 __device__ inline int dir_dy(int d) { return d == 3 ? -1 : (d == 4 ? 1 : 0); }
 __device__ inline int iabs(int v) { return v < 0 ? -v : v; }
 
-// Per-environment LDS area: record, 9x11 map window, one-hot bit staging, scalar vector.
-// The stride is 130 dwords: consecutive environments start two banks apart, so the 4..16
-// groups of a wave never collide on a bank when they touch the same field.
-constexpr int WIN_ROWS = 9, WIN_COLS = 11, WIN_CELLS = WIN_ROWS * WIN_COLS;   // 99
+// Per-environment LDS area: record, map window, one-hot bit staging, scalar vector.
+// The window is 9 rows of 16 bytes: row r holds the map bytes of row (py-4+r) from the
+// 4-byte-aligned column xa = (px-5) & ~3 on, so it is filled with aligned dword loads; window
+// column c (map column px-5+c) sits at byte (px-5 & 3) + c of the row.  Cells outside the map
+// read as BK_OOB.  The per-environment stride is 142 dwords: the 4..16 environments of a wave
+// start on distinct even banks, so they never collide when they touch the same field.
+constexpr int WIN_ROWS = 9, WIN_COLS = 11, WIN_PITCH = 16;
+constexpr int WIN_DWORDS = WIN_ROWS * WIN_PITCH / 4;   // 36
 constexpr int LDS_REC = 0;                       // 32 dwords
-constexpr int LDS_WIN = 32;                      // 99 bytes in 25 dwords
-constexpr int LDS_BITS = 57;                     // 1328 bits = 41.5 dwords -> 42
-constexpr int LDS_VEC = 99;                      // 24 dwords (22 scalars + padding)
-constexpr int LDS_ENV_DWORDS = 130;
+constexpr int LDS_WIN = 32;                      // 36 dwords
+constexpr int LDS_BITS = 68;                     // 1328 bits -> 42 dwords
+constexpr int LDS_VEC = 110;                     // 24 dwords (22 scalars + padding)
+constexpr int LDS_ENV_DWORDS = 142;
 static_assert(LDS_VEC + 24 <= LDS_ENV_DWORDS, "per-environment LDS area overflows");
 
 }  // namespace cx

@@ -50,21 +50,19 @@ __device__ inline void store_record(int l, uint4* __restrict__ grec, const uint3
 
 // ---------------------------------------------------------------------------------------------
 // reset: one block per environment (appendix "Optimistic Environment Resets" explains why
-// world generation is the expensive part; here it is spread over 256 threads).
-__global__ __launch_bounds__(BLOCK) void k_reset(uint4* __restrict__ recs, uint8_t* __restrict__ maps,
+// world generation is the expensive part; here it is spread over 512 threads).
+__global__ __launch_bounds__(WG_THREADS) void k_reset(uint4* __restrict__ recs, uint8_t* __restrict__ maps,
                                                  const uint64_t* __restrict__ seeds, uint32_t* done_count,
                                                  uint32_t* done_finished, Params p)
 {
     if (blockIdx.x == 0 && threadIdx.x == 0) { *done_count = 0u; *done_finished = 0u; }
     __shared__ uint16_t s_lat[LAT_BLOCKS * 8];
-    __shared__ uint32_t s_rec[REC_DWORDS];
     const uint32_t env = blockIdx.x;
     const uint64_t seed = seeds[env];
     const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
     worldgen_block(maps + (size_t)env * (MAPW * MAPW), s_lat, lo, hi, env, 0u);
-    if (threadIdx.x == 0) fresh_record(s_rec, lo, hi, 0u);
-    __syncthreads();
-    if (threadIdx.x < REC_DWORDS) reinterpret_cast<uint32_t*>(recs + (size_t)env * 8)[threadIdx.x] = s_rec[threadIdx.x];
+    if (threadIdx.x < REC_DWORDS)
+        reinterpret_cast<uint32_t*>(recs + (size_t)env * 8)[threadIdx.x] = fresh_record_word(threadIdx.x, lo, hi, 0u);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -72,7 +70,8 @@ __global__ __launch_bounds__(BLOCK) void k_reset(uint4* __restrict__ recs, uint8
 // ended are not written back; their indices are appended to the state's done list, which
 // k_reset_list consumes right after (same stream), spreading world generation over the
 // whole chip instead of stretching the tail of a few step blocks.
-struct DoneList { uint32_t* count; uint32_t* finished; uint32_t* list; };
+// a list entry carries what the reset needs: (env, seed low, seed high, next episode index)
+struct DoneList { uint32_t* count; uint32_t* finished; uint4* list; };
 
 template <int G, int OBS_MODE>
 __global__ __launch_bounds__(BLOCK, 4) void k_step(uint4* __restrict__ recs, uint8_t* __restrict__ maps,
@@ -84,7 +83,7 @@ __global__ __launch_bounds__(BLOCK, 4) void k_step(uint4* __restrict__ recs, uin
     __shared__ uint32_t s_env[EPB * LDS_ENV_DWORDS];
     __shared__ int s_ndone;
     __shared__ uint32_t s_base;
-    __shared__ int s_list[EPB];
+    __shared__ uint4 s_list[EPB];
 
     const int tid = threadIdx.x, g = tid / G, l = tid % G;
     const int env = blockIdx.x * EPB + g;
@@ -102,9 +101,10 @@ __global__ __launch_bounds__(BLOCK, 4) void k_step(uint4* __restrict__ recs, uin
         if (!o.done) {
             store_record<G>(l, recs + (size_t)env * 8, e);
             if (kSymbolic && obs != nullptr)
-                render_symbolic<G, OBS_MODE>(l, e, o.mvx, o.mvy, luts, obs + (size_t)env * obs_stride(OBS_MODE));
+                render_symbolic<G, OBS_MODE>(l, e, o.mvx, o.mvy, o.woff, luts, obs + (size_t)env * obs_stride(OBS_MODE));
         } else if (l == 0) {
-            s_list[atomicAdd(&s_ndone, 1)] = env;
+            const uint32_t* rec = e + LDS_REC;   // not written back: still the episode that just ended
+            s_list[atomicAdd(&s_ndone, 1)] = make_uint4((uint32_t)env, rec[RW_SEED_LO], rec[RW_SEED_HI], rec[RW_EPISODE] + 1u);
         }
     }
     __syncthreads();
@@ -112,13 +112,13 @@ __global__ __launch_bounds__(BLOCK, 4) void k_step(uint4* __restrict__ recs, uin
     if (nd == 0) return;
     if (tid == 0) s_base = atomicAdd(dl.count, (uint32_t)nd);
     __syncthreads();
-    if (tid < nd) dl.list[s_base + tid] = (uint32_t)s_list[tid];
+    if (tid < nd) dl.list[s_base + tid] = s_list[tid];
 }
 
 // Regenerates every environment on the done list (one block each, looping if the list is
 // longer than the grid), renders its first observation, and clears the list for the next step.
 template <int OBS_MODE>
-__global__ __launch_bounds__(BLOCK) void k_reset_list(uint4* __restrict__ recs, uint8_t* __restrict__ maps,
+__global__ __launch_bounds__(WG_THREADS) void k_reset_list(uint4* __restrict__ recs, uint8_t* __restrict__ maps,
                                                       const Luts* __restrict__ luts, uint8_t* __restrict__ obs,
                                                       DoneList dl, Params p)
 {
@@ -128,30 +128,30 @@ __global__ __launch_bounds__(BLOCK) void k_reset_list(uint4* __restrict__ recs, 
     const uint32_t count = *dl.count;
     if (blockIdx.x >= count) return;
     const int tid = threadIdx.x;
-    constexpr bool kSymbolic = OBS_MODE != CRAFTAX_OBS_PIXELS_F32;
-    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
-        const uint32_t env = dl.list[i];
-        uint32_t* grec = reinterpret_cast<uint32_t*>(recs + (size_t)env * 8);
-        const uint32_t lo = grec[RW_SEED_LO], hi = grec[RW_SEED_HI], ep = grec[RW_EPISODE] + 1u;
-        uint8_t* map = maps + (size_t)env * (MAPW * MAPW);
-        worldgen_block(map, s_lat, lo, hi, env, ep);           // ends with a block barrier
-        if (tid == 0) fresh_record(s_env + LDS_REC, lo, hi, ep);
-        __syncthreads();
-        if (tid < REC_DWORDS) grec[tid] = s_env[LDS_REC + tid];
-        if (kSymbolic && obs != nullptr && tid < G) {
-            load_window<G>(tid, MAPW / 2, MAPW / 2, map, reinterpret_cast<uint8_t*>(s_env + LDS_WIN));
-            group_sync();
-            render_symbolic<G, OBS_MODE>(tid, s_env, 0, 0, luts, obs + (size_t)env * obs_stride(OBS_MODE));
-        }
-        __syncthreads();
-    }
-    // the last working block clears the list; blocks beyond the list never touched it
-    __shared__ bool s_last;
+    // Every working block has now read the count; the last one to say so clears the list for
+    // the next step (entries are only appended by the next step kernel, after this one ends).
     if (tid == 0) {
         const uint32_t workers = count < gridDim.x ? count : gridDim.x;
-        __threadfence();
-        s_last = atomicAdd(dl.finished, 1u) == workers - 1u;
-        if (s_last) { *dl.count = 0u; *dl.finished = 0u; }
+        if (atomicAdd(dl.finished, 1u) == workers - 1u) { *dl.count = 0u; *dl.finished = 0u; }
+    }
+    constexpr bool kSymbolic = OBS_MODE != CRAFTAX_OBS_PIXELS_F32;
+    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
+        const uint4 entry = dl.list[i];
+        const uint32_t env = entry.x, lo = entry.y, hi = entry.z, ep = entry.w;
+        uint32_t* grec = reinterpret_cast<uint32_t*>(recs + (size_t)env * 8);
+        uint8_t* map = maps + (size_t)env * (MAPW * MAPW);
+        if (tid >= 64 && tid < 64 + REC_DWORDS) {              // wave 1 writes the record, wave 0 will render
+            const uint32_t w = fresh_record_word(tid - 64, lo, hi, ep);
+            grec[tid - 64] = w;
+            s_env[LDS_REC + tid - 64] = w;
+        }
+        worldgen_block(map, s_lat, lo, hi, env, ep);           // ends with a block barrier
+        if (kSymbolic && obs != nullptr && tid < G) {
+            load_window<G>(tid, MAPW / 2, MAPW / 2, map, s_env + LDS_WIN);
+            group_sync();
+            render_symbolic<G, OBS_MODE>(tid, s_env, 0, 0, (MAPW / 2 - WIN_COLS / 2) & 3, luts, obs + (size_t)env * obs_stride(OBS_MODE));
+        }
+        __syncthreads();
     }
 }
 
@@ -168,10 +168,10 @@ __global__ __launch_bounds__(BLOCK) void k_observe(const uint4* __restrict__ rec
     load_record<G>(l, recs + (size_t)env * 8, e);
     group_sync();
     const uint32_t w_pos = e[LDS_REC + RW_POS];
-    load_window<G>(l, w_pos & 0xFF, (w_pos >> 8) & 0xFF, maps + (size_t)env * (MAPW * MAPW),
-                   reinterpret_cast<uint8_t*>(e + LDS_WIN));
+    const int px = w_pos & 0xFF;
+    load_window<G>(l, px, (w_pos >> 8) & 0xFF, maps + (size_t)env * (MAPW * MAPW), e + LDS_WIN);
     group_sync();
-    render_symbolic<G, OBS_MODE>(l, e, 0, 0, luts, obs + (size_t)env * obs_stride(OBS_MODE));
+    render_symbolic<G, OBS_MODE>(l, e, 0, 0, (px - WIN_COLS / 2) & 3, luts, obs + (size_t)env * obs_stride(OBS_MODE));
 }
 
 __global__ __launch_bounds__(BLOCK) void k_pixels(const uint4* __restrict__ recs, const uint8_t* __restrict__ maps,
@@ -320,7 +320,7 @@ static Header make_header(const craftax_config* c, int n)
     h.off_recs = round_up(h.off_luts + sizeof(Luts), 256);
     h.off_maps = h.off_recs + (uint64_t)n * (REC_DWORDS * 4);
     h.off_done = h.off_maps + (uint64_t)n * (MAPW * MAPW);
-    h.total = round_up(h.off_done + (uint64_t)n * 4, 256);
+    h.total = round_up(h.off_done + (uint64_t)n * 16, 256);
     return h;
 }
 
@@ -391,7 +391,7 @@ static Ptrs pointers(const void* state, const HostState& s)
     q.maps = base + s.hdr.off_maps;
     q.dl.count = reinterpret_cast<uint32_t*>(base + DONE_COUNT_OFFSET);
     q.dl.finished = q.dl.count + 1;
-    q.dl.list = reinterpret_cast<uint32_t*>(base + s.hdr.off_done);
+    q.dl.list = reinterpret_cast<uint4*>(base + s.hdr.off_done);
     return q;
 }
 
@@ -407,7 +407,7 @@ static int group_lanes(int n)
     return n >= 32768 ? 4 : (n >= 8192 ? 8 : 16);
 }
 
-constexpr int RESET_GRID = 1024;   // blocks of k_reset_list; those beyond the list exit at once
+constexpr int RESET_GRID = 512;   // blocks of k_reset_list; those beyond the list exit at once
 
 template <int OBS_MODE>
 static void launch_step(int G, int n, hipStream_t st, const Ptrs& q, const int32_t* actions, uint8_t* o, float* reward,
@@ -417,7 +417,7 @@ static void launch_step(int G, int n, hipStream_t st, const Ptrs& q, const int32
     if (G == 4) hipLaunchKernelGGL((k_step<4, OBS_MODE>), dim3((n + 63) / 64), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.dl, p);
     else if (G == 8) hipLaunchKernelGGL((k_step<8, OBS_MODE>), dim3((n + 31) / 32), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.dl, p);
     else hipLaunchKernelGGL((k_step<16, OBS_MODE>), dim3((n + 15) / 16), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.dl, p);
-    hipLaunchKernelGGL((k_reset_list<OBS_MODE>), dim3(n < RESET_GRID ? n : RESET_GRID), block, 0, st, q.recs, q.maps, q.luts, o, q.dl, p);
+    hipLaunchKernelGGL((k_reset_list<OBS_MODE>), dim3(n < RESET_GRID ? n : RESET_GRID), dim3(WG_THREADS), 0, st, q.recs, q.maps, q.luts, o, q.dl, p);
 }
 
 }  // namespace cx
@@ -487,7 +487,7 @@ int craftax_reset(void* state, const uint64_t* seeds, int n, void* stream)
     if (int rc = lookup(state, n, true, &s)) return rc;
     if (!seeds) return fail(CRAFTAX_E_NULL, "seeds is NULL");
     const Ptrs q = pointers(state, s);
-    hipLaunchKernelGGL(k_reset, dim3(n), dim3(BLOCK), 0, (hipStream_t)stream, q.recs, q.maps, seeds, q.dl.count, q.dl.finished,
+    hipLaunchKernelGGL(k_reset, dim3(n), dim3(WG_THREADS), 0, (hipStream_t)stream, q.recs, q.maps, seeds, q.dl.count, q.dl.finished,
                        make_params(s));
     return check_launch("craftax_reset");
 }

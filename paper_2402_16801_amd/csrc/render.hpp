@@ -22,12 +22,13 @@ __device__ inline uint32_t spread4(uint32_t nibble) { return (nibble * 0x0020408
 
 // Renders one environment's symbolic observation with the G lanes of its group.
 // e: the environment's LDS area; its record is current and its window holds the map around
-// (window centre) with the player displaced by (mvx, mvy) from that centre.
+// the window centre, with the player displaced by (mvx, mvy) from that centre and window
+// column 0 at byte woff of each 16-byte row.
 // The one-hot channels are collected as single bits in LDS (one atomic OR per set channel),
 // then each lane expands 16 bits into a 16-byte store, so the HBM write is fully coalesced
 // and the staging costs 166 bytes of LDS per environment instead of 1323.
 template <int G, int OBS_MODE>
-__device__ inline void render_symbolic(int l, uint32_t* e, int mvx, int mvy, const Luts* __restrict__ luts,
+__device__ inline void render_symbolic(int l, uint32_t* e, int mvx, int mvy, int woff, const Luts* __restrict__ luts,
                                        uint8_t* __restrict__ obs_out)
 {
     const uint32_t* rec = e + LDS_REC;
@@ -44,7 +45,7 @@ __device__ inline void render_symbolic(int l, uint32_t* e, int mvx, int mvy, con
         const int c = l + it_c * G;
         if (c >= (VIEW_ROWS * VIEW_COLS)) break;
         const int row = c / VIEW_COLS, col = c - row * VIEW_COLS;
-        const int b = win[(row + 1 + mvy) * WIN_COLS + col + 1 + mvx];
+        const int b = win[(row + 1 + mvy) * WIN_PITCH + woff + col + 1 + mvx];
         const int bit = c * NCHAN + b;
         atomicOr(&bits[bit >> 5], 1u << (bit & 31));
     }

@@ -22,21 +22,45 @@ namespace cx {
 
 enum Intent : int { K_NONE = 0, K_MOVE = 1, K_MOVE_PATH = 2, K_ATTACK = 3, K_SHOOT = 4, K_FLY = 5 };
 
-struct StepOut { bool done; float reward; int mvx, mvy; };
+struct StepOut { bool done; float reward; int mvx, mvy, woff; };
 
-// Loads the 9x11 window centred on (px, py) into LDS; cells outside the map read as BK_OOB.
+// Loads the map window around (px, py) into LDS with aligned dword loads: lane l takes dwords
+// l, l+G, ... of the 36; the four dwords of a window row are 16 contiguous map bytes, so the
+// lanes of one environment read whole rows and a wave touches few cache lines per load.
 template <int G>
-__device__ inline void load_window(int l, int px, int py, const uint8_t* __restrict__ map, uint8_t* win)
+__device__ inline void load_window(int l, int px, int py, const uint8_t* __restrict__ map, uint32_t* win)
 {
+    const int xa = (px - WIN_COLS / 2) & ~3, y0 = py - WIN_ROWS / 2;
 #pragma unroll
-    for (int it_i = 0; it_i < ((WIN_CELLS) + G - 1) / G; ++it_i) {
-        const int i = l + it_i * G;
-        if (i >= (WIN_CELLS)) break;
-        const int r = i / WIN_COLS, c = i - r * WIN_COLS;
-        const int x = px - WIN_COLS / 2 + c, y = py - WIN_ROWS / 2 + r;
-        win[i] = in_map(x, y) ? map[y * MAPW + x] : (uint8_t)BK_OOB;
+    for (int it = 0; it < (WIN_DWORDS + G - 1) / G; ++it) {
+        const int d = l + it * G;
+        if (d >= WIN_DWORDS) break;
+        const int r = d >> 2, x = xa + ((d & 3) << 2), y = y0 + r;
+        const bool inside = (unsigned)y < (unsigned)MAPW && (unsigned)x < (unsigned)MAPW;
+        win[d] = inside ? *reinterpret_cast<const uint32_t*>(map + y * MAPW + x) : 0x01010101u * (uint32_t)BK_OOB;
     }
 }
+
+// Mob and plant slots stay in their packed record form while the step runs: bit 0 alive,
+// bits 1..12 the cell (x | y<<6), so "is this live slot on cell c" is one AND and one compare
+// against key(c) = 1 | x<<1 | y<<7, a move is one bit-field insert and a kill is "= 0".
+constexpr uint32_t KEY_MASK = 0x1FFFu;
+__device__ inline uint32_t cell_key(int x, int y) { return 1u | ((uint32_t)x << 1) | ((uint32_t)y << 7); }
+__device__ inline int mob_x(uint32_t w) { return (int)__builtin_amdgcn_ubfe(w, 1, 6); }
+__device__ inline int mob_y(uint32_t w) { return (int)__builtin_amdgcn_ubfe(w, 7, 6); }
+__device__ inline uint32_t mob_moved(uint32_t w, uint32_t key) { return (w & ~KEY_MASK) | key; }
+
+// Small per-block-id tables of the DO action, packed into 64-bit constants (ids 0..10):
+// item picked up (+1, 0 = none), pickaxe needed (0 none, 1 wood, 2 stone, 3 iron), achievement.
+constexpr uint64_t DO_ITEM = (6ull << (4 * BK_GRASS)) | (2ull << (4 * BK_STONE)) | (1ull << (4 * BK_TREE)) |
+                             (3ull << (4 * BK_COAL)) | (4ull << (4 * BK_IRON)) | (5ull << (4 * BK_DIAMOND));
+constexpr uint64_t DO_GATE = (1ull << (2 * BK_STONE)) | (1ull << (2 * BK_COAL)) | (2ull << (2 * BK_IRON)) | (3ull << (2 * BK_DIAMOND));
+constexpr uint64_t DO_ACH = ((uint64_t)ACH_COLLECT_SAPLING << (5 * BK_GRASS)) | ((uint64_t)ACH_COLLECT_STONE << (5 * BK_STONE)) |
+                            ((uint64_t)ACH_COLLECT_WOOD << (5 * BK_TREE)) | ((uint64_t)ACH_COLLECT_COAL << (5 * BK_COAL)) |
+                            ((uint64_t)ACH_COLLECT_IRON << (5 * BK_IRON)) | ((uint64_t)ACH_COLLECT_DIAMOND << (5 * BK_DIAMOND));
+constexpr uint32_t MINED_MASK = (1u << BK_STONE) | (1u << BK_COAL) | (1u << BK_IRON) | (1u << BK_DIAMOND);  // leave a path
+constexpr uint32_t MAKE_ACH = ACH_MAKE_WOOD_PICKAXE | (ACH_MAKE_STONE_PICKAXE << 5) | (ACH_MAKE_IRON_PICKAXE << 10) |
+                              (ACH_MAKE_WOOD_SWORD << 15) | (ACH_MAKE_STONE_SWORD << 20) | (ACH_MAKE_IRON_SWORD << 25);
 
 // e: the environment's LDS area (record already loaded).  Returns with the record in LDS
 // updated (unless the episode ended) and the window patched with this step's map edits;
@@ -51,37 +75,36 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     uint8_t* win = reinterpret_cast<uint8_t*>(e + LDS_WIN);
 
     // ---- unpack -----------------------------------------------------------------------------
-    const uint32_t w_pos = rec[RW_POS], w_inv = rec[RW_INV], w_vit = rec[RW_VIT], w_cnt = rec[RW_CNT];
+    const uint32_t w_pos = rec[RW_POS], w_vit = rec[RW_VIT], w_cnt = rec[RW_CNT];
+    uint32_t w_inv = rec[RW_INV];    // six 4-bit counts, six tool flags from bit 24: stays packed
     const int px0 = w_pos & 0xFF, py0 = (w_pos >> 8) & 0xFF;
     int px = px0, py = py0, dir = (w_pos >> 16) & 0xFF, sleeping = (w_pos >> 24) & 0xFF;
-    int inv[12], vit[4], cnt[4];
-#pragma unroll
-    for (int i = 0; i < 6; ++i) { inv[i] = (w_inv >> (4 * i)) & 15; inv[6 + i] = (w_inv >> (24 + i)) & 1; }
+    load_window<G>(l, px0, py0, map, e + LDS_WIN);
+    const int woff = (px0 - WIN_COLS / 2) & 3;      // where window column 0 sits in a row
+    int vit[4], cnt[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) { vit[i] = (w_vit >> (4 * i)) & 15; cnt[i] = (int)(int8_t)(w_cnt >> (8 * i)); }
     uint32_t phase = w_vit >> 16;
     uint32_t ach = rec[RW_ACH];
     const uint32_t t = rec[RW_T], episode = rec[RW_EPISODE], seed_lo = rec[RW_SEED_LO], seed_hi = rec[RW_SEED_HI];
-    Mob m[NSM];
+    uint32_t mw[NSM];                // mob words of the slots this lane owns
     U4 dr[NSM];
 #pragma unroll
     for (int s = 0; s < NSM; ++s) {
         const int k = l + s * G;
-        m[s] = unpack_mob(k < NMOB ? rec[RW_MOB + k] : 0u);
+        mw[s] = k < NMOB ? rec[RW_MOB + k] : 0u;
         dr[s] = philox4x32_10(env, t, episode, (DOM_STEP << 16) | (uint32_t)k, seed_lo, seed_hi);
     }
-    Plant q[NSP];
+    uint32_t qw[NSP];                // plant words
     int q_block[NSP];
 #pragma unroll
     for (int s = 0; s < NSP; ++s) {
         const int k = l + s * G;
-        q[s] = unpack_plant(k < NPLANT ? rec[RW_PLANT + k] : 0u);
-        q_block[s] = q[s].alive ? (int)map[q[s].y * MAPW + q[s].x] : (int)BK_INVALID;
+        qw[s] = k < NPLANT ? rec[RW_PLANT + k] : 0u;
+        q_block[s] = (qw[s] & 1u) ? (int)map[mob_y(qw[s]) * MAPW + mob_x(qw[s])] : (int)BK_INVALID;
     }
     const int health0 = vit[0];
     const uint32_t ach0 = ach;
-
-    load_window<G>(l, px0, py0, map, win);
     const uint32_t sapling_draw = (uint32_t)Gr::shfl((int)dr[9 / G].w[3], 9 % G);
 
     int a = ((unsigned)action < (unsigned)AC_COUNT) ? action : (int)AC_NOOP;
@@ -91,40 +114,38 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     // ---- phase 1: the player's action ----------------------------------------------------------
     bool l_table = false, l_furnace = false;
 #pragma unroll
-    for (int it_j = 0; it_j < ((9) + G - 1) / G; ++it_j) {
-        const int j = l + it_j * G;
-        if (j >= (9)) break;
-        const int b = win[(3 + j / 3) * WIN_COLS + 4 + j % 3];
+    for (int it = 0; it < (9 + G - 1) / G; ++it) {
+        const int j = l + it * G;
+        if (j >= 9) break;
+        const int b = win[(3 + j / 3) * WIN_PITCH + woff + 4 + j % 3];
         l_table = l_table || b == BK_TABLE;
         l_furnace = l_furnace || b == BK_FURNACE;
     }
-    const bool near_table = Gr::ballot(l_table) != 0, near_furnace = Gr::ballot(l_furnace) != 0;
-
-    if (a >= AC_LEFT && a <= AC_DOWN) dir = a;
+    const bool is_move = a >= AC_LEFT && a <= AC_DOWN;
+    if (is_move) dir = a;
     const int ddx = dir_dx(dir), ddy = dir_dy(dir);
     const int fx = px + ddx, fy = py + ddy;
     const bool f_in = in_map(fx, fy);
-    const int f_win = (WIN_ROWS / 2 + ddy) * WIN_COLS + WIN_COLS / 2 + ddx;
+    const uint32_t fkey = cell_key(fx, fy);
+    const int f_win = (WIN_ROWS / 2 + ddy) * WIN_PITCH + woff + WIN_COLS / 2 + ddx;
     const int fb = win[f_win];
-    // which mob (if any) stands on the facing cell: owner lane and sub-slot
+    // which mob (if any) stands on the facing cell: owner lane, sub-slot and hp
     int my_hit = -1;
+    uint32_t plant_alive = 0;
 #pragma unroll
     for (int s = 0; s < NSM; ++s)
-        if (m[s].alive && m[s].x == fx && m[s].y == fy) my_hit = s | (m[s].hp << 4);
+        if ((mw[s] & KEY_MASK) == fkey) my_hit = s | (int)(__builtin_amdgcn_ubfe(mw[s], 16, 4) << 4);
     const uint32_t hit_lanes = Gr::ballot(my_hit >= 0);
-    const int hit_lane = hit_lanes ? (__ffs((int)hit_lanes) - 1) : -1;
-    const int hit_info = Gr::shfl(my_hit, hit_lane < 0 ? 0 : hit_lane);
-    const int hit = hit_lane < 0 ? -1 : hit_lane + G * (hit_info & 15);   // mob slot index
+    const int hit_lane = hit_lanes ? (__ffs((int)hit_lanes) - 1) : 0;
+    const int hit_info = Gr::shfl(my_hit, hit_lane);
+    const int hit = hit_lanes ? hit_lane + G * (hit_info & 15) : -1;   // mob slot index
     const int hit_hp = hit_info >> 4;
-    uint32_t plant_mask = 0;
-#pragma unroll
-    for (int s = 0; s < NSP; ++s) plant_mask |= Gr::ballot(q[s].alive != 0) << (s * G);
 
     int modval = -1;                 // new block of the facing cell, if the action edits it
     bool ate_ripe = false;
     int new_plant_slot = -1;
 
-    if (a >= AC_LEFT && a <= AC_DOWN) {
+    if (is_move) {
         if (f_in && hit < 0) {
             if (walkable_ground(fb)) { px = fx; py = fy; }
             else if (fb == BK_LAVA) { px = fx; py = fy; vit[0] = 0; }
@@ -134,11 +155,11 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
             if (hit >= 0) {
                 const int type = (hit * 11) >> 5;
                 if (type != MT_ARROW) {
-                    const int dmg = inv[IV_IRON_SWORD] ? 5 : (inv[IV_STONE_SWORD] ? 3 : (inv[IV_WOOD_SWORD] ? 2 : 1));
+                    const int dmg = (w_inv & (1u << 29)) ? 5 : ((w_inv & (1u << 28)) ? 3 : ((w_inv & (1u << 27)) ? 2 : 1));
                     const int hp = hit_hp - dmg;
 #pragma unroll
                     for (int s = 0; s < NSM; ++s)
-                        if (l + s * G == hit) { m[s].hp = hp; if (hp <= 0) m[s].alive = 0; }
+                        if (l + s * G == hit) mw[s] = hp > 0 ? ((mw[s] & ~(15u << 16)) | ((uint32_t)hp << 16)) : 0u;
                     if (hp <= 0) {
                         if (type == MT_ZOMBIE) ach |= 1u << ACH_DEFEAT_ZOMBIE;
                         if (type == MT_SKELETON) ach |= 1u << ACH_DEFEAT_SKELETON;
@@ -149,34 +170,21 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
                         }
                     }
                 }
-            } else {
-                int item = -1, leaves = fb, achv = 0;
-                bool gate = true;
-                switch (fb) {
-                case BK_TREE: item = IV_WOOD; achv = ACH_COLLECT_WOOD; break;
-                case BK_STONE: item = IV_STONE; gate = inv[IV_WOOD_PICKAXE]; leaves = BK_PATH; achv = ACH_COLLECT_STONE; break;
-                case BK_COAL: item = IV_COAL; gate = inv[IV_WOOD_PICKAXE]; leaves = BK_PATH; achv = ACH_COLLECT_COAL; break;
-                case BK_IRON: item = IV_IRON; gate = inv[IV_STONE_PICKAXE]; leaves = BK_PATH; achv = ACH_COLLECT_IRON; break;
-                case BK_DIAMOND: item = IV_DIAMOND; gate = inv[IV_IRON_PICKAXE]; leaves = BK_PATH; achv = ACH_COLLECT_DIAMOND; break;
-                case BK_GRASS: item = IV_SAPLING; gate = sapling_draw < P_SAPLING; achv = ACH_COLLECT_SAPLING; break;
-                case BK_WATER:
-                    vit[2] = min(MAX_COUNT, vit[2] + 1); cnt[1] = 0; ach |= 1u << ACH_COLLECT_DRINK;
-                    break;
-                case BK_RIPE:
-                    vit[1] = min(MAX_COUNT, vit[1] + FOOD_PLANT); cnt[0] = 0; ach |= 1u << ACH_EAT_PLANT;
-                    modval = BK_PLANT;
-                    ate_ripe = true;
-                    break;
-                default: break;
-                }
-                if (item >= 0 && gate) {
-#pragma unroll
-                    for (int i = 0; i < 6; ++i)
-                        if (i == item && inv[i] < MAX_COUNT) {
-                            inv[i]++;
-                            ach |= 1u << achv;
-                            if (leaves != fb) modval = leaves;
-                        }
+            } else if (fb == BK_WATER) {
+                vit[2] = min(MAX_COUNT, vit[2] + 1); cnt[1] = 0; ach |= 1u << ACH_COLLECT_DRINK;
+            } else if (fb == BK_RIPE) {
+                vit[1] = min(MAX_COUNT, vit[1] + FOOD_PLANT); cnt[0] = 0; ach |= 1u << ACH_EAT_PLANT;
+                modval = BK_PLANT;
+                ate_ripe = true;
+            } else if (fb <= BK_DIAMOND) {
+                const int item1 = (int)((DO_ITEM >> (4 * fb)) & 15u);        // item + 1
+                const int tool = (int)((DO_GATE >> (2 * fb)) & 3u);
+                const bool gate = tool ? ((w_inv >> (23 + tool)) & 1u) : (fb != BK_GRASS || sapling_draw < P_SAPLING);
+                const int sh = item1 ? 4 * (item1 - 1) : 0;
+                if (item1 && gate && ((w_inv >> sh) & 15u) < (uint32_t)MAX_COUNT) {
+                    w_inv += 1u << sh;
+                    ach |= 1u << (uint32_t)((DO_ACH >> (5 * fb)) & 31u);
+                    if ((MINED_MASK >> fb) & 1u) modval = BK_PATH;
                 }
             }
         }
@@ -184,22 +192,23 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
         if (vit[3] < MAX_COUNT) sleeping = 1;
     } else if (a >= AC_PLACE_STONE && a <= AC_PLACE_PLANT) {
         if (f_in && hit < 0) {
+            const bool ground = walkable_ground(fb);
             if (a == AC_PLACE_STONE) {
-                if (inv[IV_STONE] >= 1 && (walkable_ground(fb) || fb == BK_WATER || fb == BK_LAVA)) {
-                    inv[IV_STONE]--; modval = BK_STONE; ach |= 1u << ACH_PLACE_STONE;
+                if ((w_inv & 0xF0u) && (ground || fb == BK_WATER || fb == BK_LAVA)) {
+                    w_inv -= 0x10u; modval = BK_STONE; ach |= 1u << ACH_PLACE_STONE;
                 }
             } else if (a == AC_PLACE_TABLE) {
-                if (inv[IV_WOOD] >= 1 && walkable_ground(fb)) {
-                    inv[IV_WOOD]--; modval = BK_TABLE; ach |= 1u << ACH_PLACE_TABLE;
-                }
+                if ((w_inv & 0xFu) && ground) { w_inv -= 0x1u; modval = BK_TABLE; ach |= 1u << ACH_PLACE_TABLE; }
             } else if (a == AC_PLACE_FURNACE) {
-                if (inv[IV_STONE] >= 1 && walkable_ground(fb) && near_table) {
-                    inv[IV_STONE]--; modval = BK_FURNACE; ach |= 1u << ACH_PLACE_FURNACE;
+                if ((w_inv & 0xF0u) && ground && Gr::ballot(l_table) != 0) {
+                    w_inv -= 0x10u; modval = BK_FURNACE; ach |= 1u << ACH_PLACE_FURNACE;
                 }
             } else {
-                const uint32_t free_slots = ~plant_mask & ((1u << p.cap_plant) - 1u);
-                if (inv[IV_SAPLING] >= 1 && fb == BK_GRASS && free_slots) {
-                    inv[IV_SAPLING]--; modval = BK_PLANT; ach |= 1u << ACH_PLACE_PLANT;
+#pragma unroll
+                for (int s = 0; s < NSP; ++s) plant_alive |= Gr::ballot(qw[s] & 1u) << (s * G);
+                const uint32_t free_slots = ~plant_alive & ((1u << p.cap_plant) - 1u);
+                if ((w_inv & 0xF00000u) && fb == BK_GRASS && free_slots) {
+                    w_inv -= 0x100000u; modval = BK_PLANT; ach |= 1u << ACH_PLACE_PLANT;
                     new_plant_slot = __ffs((int)free_slots) - 1;
                 }
             }
@@ -207,18 +216,14 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     } else if (a >= AC_MAKE_WOOD_PICKAXE) {
         const int which = a - AC_MAKE_WOOD_PICKAXE;               // 0..5: pickaxes then swords
         const int tier = which >= 3 ? which - 3 : which;          // 0 wood, 1 stone, 2 iron
-        const int need_stone = tier == 1, need_ci = tier == 2;
-        const int have = (w_inv >> (24 + which)) & 1;             // tools are made once
-        const bool ok = !have && near_table && (!need_ci || near_furnace) && inv[IV_WOOD] >= 1 &&
-                        inv[IV_STONE] >= need_stone && inv[IV_COAL] >= need_ci && inv[IV_IRON] >= need_ci;
+        // cost in the inventory's nibble layout: wood | stone<<4 | coal<<8 | iron<<12
+        const uint32_t cost = tier == 0 ? 0x0001u : (tier == 1 ? 0x0011u : 0x1101u);
+        const uint32_t nonzero = (w_inv | (w_inv >> 1) | (w_inv >> 2) | (w_inv >> 3)) & 0x1111u;
+        const bool near_table = Gr::ballot(l_table) != 0, near_furnace = Gr::ballot(l_furnace) != 0;
+        const bool ok = !((w_inv >> (24 + which)) & 1u) && near_table && (tier != 2 || near_furnace) && (nonzero & cost) == cost;
         if (ok) {
-            inv[IV_WOOD]--; inv[IV_STONE] -= need_stone; inv[IV_COAL] -= need_ci; inv[IV_IRON] -= need_ci;
-#pragma unroll
-            for (int i = 0; i < 6; ++i) if (i == which) inv[6 + i] = 1;
-            // achievement ids of the six tools: 5, 13, 20 (pickaxes), 6, 14, 21 (swords)
-            const int achv = which >= 3 ? (tier == 0 ? ACH_MAKE_WOOD_SWORD : tier == 1 ? ACH_MAKE_STONE_SWORD : ACH_MAKE_IRON_SWORD)
-                                        : (tier == 0 ? ACH_MAKE_WOOD_PICKAXE : tier == 1 ? ACH_MAKE_STONE_PICKAXE : ACH_MAKE_IRON_PICKAXE);
-            ach |= 1u << achv;
+            w_inv = (w_inv - cost) | (1u << (24 + which));
+            ach |= 1u << ((MAKE_ACH >> (5 * which)) & 31u);
         }
     }
     const int modcell = modval >= 0 ? fy * MAPW + fx : -1;
@@ -227,32 +232,36 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
 #pragma unroll
         for (int s = 0; s < NSP; ++s) {
             const int k = l + s * G;
-            if (k == new_plant_slot) { q[s].alive = 1; q[s].x = fx; q[s].y = fy; q[s].age = 0; q_block[s] = BK_PLANT; }
-            else if (q[s].alive && q[s].x == fx && q[s].y == fy) { q_block[s] = modval; if (ate_ripe) q[s].age = 0; }
+            if (k == new_plant_slot) { qw[s] = fkey; q_block[s] = BK_PLANT; }
+            else if ((qw[s] & KEY_MASK) == fkey) { q_block[s] = modval; if (ate_ripe) qw[s] &= 0xFFFFu; }
         }
     }
     const int mvx = px - px0, mvy = py - py0;
+    const uint32_t pkey = cell_key(px, py);
 
     // ---- phase 2: mobs.  Intent of each slot from its own state, the player and its draws ----
+    // packed intent: kind | ok<<3 | at_player<<4 | target key<<8 | direction<<24
     int packed[NSM];
-    bool l_attack = false, l_arrow_hit = false;
     int n_attack = 0, n_arrow = 0;
 #pragma unroll
     for (int s = 0; s < NSM; ++s) {
         const int k = l + s * G;
         int kind = K_NONE, ndir = 0;
-        if (m[s].alive) {
+        const int mx = mob_x(mw[s]), my = mob_y(mw[s]);
+        if (mw[s] & 1u) {
             const int type = (k * 11) >> 5;
-            const int dx = px - m[s].x, dy = py - m[s].y;
+            const int dx = px - mx, dy = py - my;
             const int adx = iabs(dx), ady = iabs(dy), cheb = max(adx, ady);
             const uint32_t m8 = dr[s].w[0] >> 29;                 // choice(draw, 8)
             const uint32_t r_act = dr[s].w[1];
             const int toward = adx >= ady ? (dx < 0 ? 1 : 2) : (dy < 0 ? 3 : 4);
             const int wander = m8 < 4 ? (int)m8 + 1 : 0;
+            const int cd = (int)__builtin_amdgcn_ubfe(mw[s], 20, 4);
+            if (type == MT_ZOMBIE || type == MT_SKELETON) { if (cd > 0) mw[s] -= 1u << 20; }
+            const bool ready = cd <= 1;                            // cooldown is zero after the decrement
             if (type == MT_ZOMBIE) {
-                if (m[s].cd > 0) m[s].cd--;
                 if (adx + ady == 1) {
-                    if (m[s].cd == 0) { kind = K_ATTACK; m[s].cd = CD_ZOMBIE; }
+                    if (ready) { kind = K_ATTACK; mw[s] = (mw[s] & ~(15u << 20)) | ((uint32_t)CD_ZOMBIE << 20); }
                 } else {
                     ndir = (cheb < CHASE_RANGE && r_act < P_CHASE) ? toward : wander;
                     if (ndir) kind = K_MOVE;
@@ -261,35 +270,36 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
                 ndir = wander;
                 if (ndir) kind = K_MOVE;
             } else if (type == MT_SKELETON) {
-                if (m[s].cd > 0) m[s].cd--;
                 const bool aligned = (dx == 0 || dy == 0) && cheb <= SHOOT_RANGE;
-                if (aligned && m[s].cd == 0 && r_act < P_SHOOT) { kind = K_SHOOT; ndir = toward; m[s].cd = CD_SKELETON; }
-                else {
+                if (aligned && ready && r_act < P_SHOOT) {
+                    kind = K_SHOOT; ndir = toward; mw[s] = (mw[s] & ~(15u << 20)) | ((uint32_t)CD_SKELETON << 20);
+                } else {
                     ndir = wander ? wander : (cheb <= SHOOT_RANGE ? toward : 0);
                     if (ndir) kind = K_MOVE_PATH;
                 }
             } else {
-                kind = K_FLY; ndir = m[s].dir;
+                kind = K_FLY; ndir = (int)__builtin_amdgcn_ubfe(mw[s], 13, 3);
             }
         }
-        const int tx = m[s].x + dir_dx(ndir), ty = m[s].y + dir_dy(ndir);
+        const int tx = mx + dir_dx(ndir), ty = my + dir_dy(ndir);
         const bool t_in = in_map(tx, ty);
         int tb = BK_OOB;
         if (kind != K_NONE && kind != K_ATTACK && t_in) {
             tb = map[ty * MAPW + tx];
             if (ty * MAPW + tx == modcell) tb = modval;
         }
-        const bool at_player = (tx == px && ty == py);
+        const uint32_t tkey = cell_key(tx & 63, ty & 63);
+        const bool at_player = t_in && tkey == pkey;
         const bool t_ok = t_in && (kind == K_MOVE ? walkable_ground(tb) : (kind == K_MOVE_PATH ? tb == BK_PATH : arrow_flyable(tb)));
-        packed[s] = kind | ((int)t_ok << 3) | ((int)at_player << 4) | ((tx + 1) << 8) | ((ty + 1) << 16) | (ndir << 24);
+        packed[s] = kind | ((int)t_ok << 3) | ((int)at_player << 4) | (int)(tkey << 8) | (ndir << 24);
         n_attack += __popc(Gr::ballot(kind == K_ATTACK));
         n_arrow += __popc(Gr::ballot((kind == K_SHOOT || kind == K_FLY) && at_player));
     }
-    (void)l_attack; (void)l_arrow_hit;
 
     // spawn candidates (phase 3) are fixed by the draws and the player's position: read their
     // terrain now so the loads overlap the mob resolution below
-    int sp_x[3], sp_y[3], sp_b[3];
+    uint32_t sp_key[3];
+    int sp_b[3];
     bool sp_cand[3];
     uint32_t sp_p[3];
 #pragma unroll
@@ -297,51 +307,45 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
         const int dx = (int)choice((uint32_t)Gr::shfl((int)dr[(3 * j) / G].w[3], (3 * j) % G), 31) - 15;
         const int dy = (int)choice((uint32_t)Gr::shfl((int)dr[(3 * j + 1) / G].w[3], (3 * j + 1) % G), 31) - 15;
         sp_p[j] = (uint32_t)Gr::shfl((int)dr[(3 * j + 2) / G].w[3], (3 * j + 2) % G);
-        sp_x[j] = px + dx; sp_y[j] = py + dy;
-        sp_cand[j] = max(iabs(dx), iabs(dy)) >= SPAWN_MIN_DIST && in_map(sp_x[j], sp_y[j]);
-        sp_b[j] = sp_cand[j] ? (int)map[sp_y[j] * MAPW + sp_x[j]] : (int)BK_OOB;
+        const int sx = px + dx, sy = py + dy;
+        sp_cand[j] = max(iabs(dx), iabs(dy)) >= SPAWN_MIN_DIST && in_map(sx, sy);
+        sp_key[j] = cell_key(sx & 63, sy & 63);
+        sp_b[j] = sp_cand[j] ? (int)map[sy * MAPW + sx] : (int)BK_OOB;
     }
 
     const int damage = n_attack * (sleeping ? DMG_ZOMBIE_SLEEP : DMG_ZOMBIE) + n_arrow * DMG_ARROW;
 
     // Moves resolve one slot at a time in the order zombies, cows, arrows, skeletons; each sees
     // the positions left by the slots before it.  An arrow shot now first flies next step.
+    // The slot index is a compile-time constant here, so each iteration only carries the code
+    // of its own mob type, and a wave-wide vote skips slots that are idle in all its groups.
     constexpr int ORDER[NMOB] = { 0, 1, 2, 3, 4, 5, 9, 10, 11, 6, 7, 8 };
 #pragma unroll
     for (int i = 0; i < NMOB; ++i) {
-        constexpr int dummy = 0; (void)dummy;
         const int k = ORDER[i];
         const int ks = k / G, kl = k % G;           // owner sub-slot and lane (compile-time)
         const int ik = Gr::shfl(packed[ks], kl);
         const int kk = ik & 7;
-        if (Gr::ballot(kk != K_NONE && kk != K_ATTACK) == 0) continue;   // uniform per group
+        if (!__any(kk != K_NONE && kk != K_ATTACK)) continue;
         const bool k_ok = (ik >> 3) & 1, k_at = (ik >> 4) & 1;
-        const int kx = ((ik >> 8) & 0xFF) - 1, ky = ((ik >> 16) & 0xFF) - 1;
+        const uint32_t tkey = ((uint32_t)ik >> 8) & KEY_MASK;
         bool l_occ = false;
 #pragma unroll
-        for (int s = 0; s < NSM; ++s) l_occ = l_occ || (m[s].alive && m[s].x == kx && m[s].y == ky);
-        const bool occ = Gr::ballot(l_occ) != 0 || (kx == px && ky == py);
-        if (kk == K_MOVE || kk == K_MOVE_PATH) {
-            if (k_ok && !occ && l == kl) { m[ks].x = kx; m[ks].y = ky; }
-        } else if (kk == K_SHOOT) {
-            uint32_t arrows = 0;                     // bit j = arrow slot 9+j alive
-#pragma unroll
-            for (int j = 0; j < 3; ++j) {
-                const int as = (9 + j) / G, al = (9 + j) % G;
-                arrows |= ((Gr::ballot(m[as].alive != 0) >> al) & 1u) << j;
+        for (int s = 0; s < NSM; ++s) l_occ = l_occ || (mw[s] & KEY_MASK) == tkey;
+        const bool blocked = Gr::ballot(l_occ) != 0 || k_at || !k_ok;
+        if (k < 6 || (k < 9 && kk == K_MOVE_PATH)) {
+            if ((kk == K_MOVE || kk == K_MOVE_PATH) && !blocked && l == kl) mw[ks] = mob_moved(mw[ks], tkey);
+        } else if (k < 9) {
+            if (kk == K_SHOOT && !blocked) {
+                const uint32_t arrows = (Gr::ballot(mw[9 / G] & 1u) >> (9 % G)) & 7u;   // bit j = arrow slot 9+j alive
+                const uint32_t free_arrows = ~arrows & ((1u << p.cap_arrow) - 1u) & 7u;
+                if (free_arrows) {
+                    const int ka = 9 + __ffs((int)free_arrows) - 1;
+                    if (l == ka % G) mw[9 / G] = tkey | ((uint32_t)((ik >> 24) & 7) << 13);
+                }
             }
-            const uint32_t free_arrows = ~arrows & ((1u << p.cap_arrow) - 1u) & 7u;
-            if (!k_at && free_arrows && k_ok && !occ) {
-                const int ka = 9 + __ffs((int)free_arrows) - 1;
-#pragma unroll
-                for (int s = 0; s < NSM; ++s)
-                    if (l + s * G == ka) { m[s].alive = 1; m[s].x = kx; m[s].y = ky; m[s].dir = (ik >> 24) & 7; m[s].hp = 0; m[s].cd = 0; }
-            }
-        } else if (kk == K_FLY) {
-            if (l == kl) {
-                if (k_at || !k_ok || occ) m[ks].alive = 0;
-                else { m[ks].x = kx; m[ks].y = ky; }
-            }
+        } else {
+            if (kk == K_FLY && l == kl) mw[ks] = blocked ? 0u : mob_moved(mw[ks], tkey);
         }
     }
     vit[0] = max(0, vit[0] - damage);
@@ -349,17 +353,17 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     // ---- phase 3: despawn far mobs, then one spawn attempt per type -----------------------------
 #pragma unroll
     for (int s = 0; s < NSM; ++s)
-        if (m[s].alive && max(iabs(m[s].x - px), iabs(m[s].y - py)) > DESPAWN_DIST) m[s].alive = 0;
+        if ((mw[s] & 1u) && max(iabs(mob_x(mw[s]) - px), iabs(mob_y(mw[s]) - py)) > DESPAWN_DIST) mw[s] = 0u;
 #pragma unroll
     for (int j = 0; j < 3; ++j) {
         uint32_t taken = 0;                          // bit i = slot 3j+i alive
         bool l_occ = false;
 #pragma unroll
-        for (int s = 0; s < NSM; ++s) l_occ = l_occ || (m[s].alive && m[s].x == sp_x[j] && m[s].y == sp_y[j]);
+        for (int s = 0; s < NSM; ++s) l_occ = l_occ || (mw[s] & KEY_MASK) == sp_key[j];
 #pragma unroll
         for (int i = 0; i < 3; ++i) {
             const int ss = (3 * j + i) / G, sl = (3 * j + i) % G;
-            taken |= ((Gr::ballot(m[ss].alive != 0) >> sl) & 1u) << i;
+            taken |= ((Gr::ballot(mw[ss] & 1u) >> sl) & 1u) << i;
         }
         const bool occ = Gr::ballot(l_occ) != 0;
         const uint32_t cap = j == 0 ? p.cap_zombie : (j == 1 ? p.cap_cow : p.cap_skeleton);
@@ -368,40 +372,39 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
         const int want = j == 2 ? BK_PATH : BK_GRASS;
         if (sp_cand[j] && free_slots && !occ && sp_b[j] == want && sp_p[j] < thr) {
             const int kn = 3 * j + __ffs((int)free_slots) - 1;
+            const uint32_t hp = j == 0 ? HP_ZOMBIE : (j == 1 ? HP_COW : HP_SKELETON);
 #pragma unroll
             for (int s = 0; s < NSM; ++s)
-                if (l + s * G == kn) {
-                    m[s].alive = 1; m[s].x = sp_x[j]; m[s].y = sp_y[j]; m[s].dir = 0;
-                    m[s].hp = j == 0 ? HP_ZOMBIE : (j == 1 ? HP_COW : HP_SKELETON); m[s].cd = 0;
-                }
+                if (l + s * G == kn) mw[s] = sp_key[j] | (hp << 16);
         }
     }
 
     // ---- phase 4: plants ----------------------------------------------------------------------------
-    if (plant_mask != 0 || new_plant_slot >= 0) {    // uniform per group
-        int zinfo[3];
+    bool any_plant = false;
 #pragma unroll
-        for (int z = 0; z < 3; ++z) {
-            const int zs = z / G, zl = z % G;
-            zinfo[z] = Gr::shfl((m[zs].alive ? 1 : 0) | (m[zs].x << 8) | (m[zs].y << 16), zl);
-        }
+    for (int s = 0; s < NSP; ++s) any_plant = any_plant || (qw[s] & 1u);
+    if (__any(any_plant)) {                          // skipped by waves that track no plant at all
+        uint32_t zw[3];
+#pragma unroll
+        for (int z = 0; z < 3; ++z) zw[z] = (uint32_t)Gr::shfl((int)mw[z / G], z % G);
 #pragma unroll
         for (int s = 0; s < NSP; ++s) {
-            if (!q[s].alive) continue;
+            if (!(qw[s] & 1u)) continue;
+            const int qx = mob_x(qw[s]), qy = mob_y(qw[s]);
             bool zombie_near = false;
 #pragma unroll
             for (int z = 0; z < 3; ++z)
-                zombie_near = zombie_near || ((zinfo[z] & 1) && iabs(((zinfo[z] >> 8) & 0xFF) - q[s].x) + iabs(((zinfo[z] >> 16) & 0xFF) - q[s].y) == 1);
-            if (q[s].age < 65535) q[s].age++;
+                zombie_near = zombie_near || ((zw[z] & 1u) && iabs(mob_x(zw[z]) - qx) + iabs(mob_y(zw[z]) - qy) == 1);
+            if ((qw[s] >> 16) < 65535u) qw[s] += 1u << 16;
             int nb = q_block[s];
-            if (nb == BK_PLANT && q[s].age >= RIPE_AGE) nb = BK_RIPE;
+            if (nb == BK_PLANT && (qw[s] >> 16) >= (uint32_t)RIPE_AGE) nb = BK_RIPE;
             if (zombie_near && dr[s].w[2] < P_PLANT_EATEN) nb = BK_GRASS;
             if (nb != q_block[s]) {
-                map[q[s].y * MAPW + q[s].x] = (uint8_t)nb;
-                const int wx = q[s].x - (px0 - WIN_COLS / 2), wy = q[s].y - (py0 - WIN_ROWS / 2);
-                if ((unsigned)wx < (unsigned)WIN_COLS && (unsigned)wy < (unsigned)WIN_ROWS) win[wy * WIN_COLS + wx] = (uint8_t)nb;
+                map[qy * MAPW + qx] = (uint8_t)nb;
+                const int wx = qx - (px0 - WIN_COLS / 2), wy = qy - (py0 - WIN_ROWS / 2);
+                if ((unsigned)wx < (unsigned)WIN_COLS && (unsigned)wy < (unsigned)WIN_ROWS) win[wy * WIN_PITCH + woff + wx] = (uint8_t)nb;
             }
-            if (nb == BK_GRASS) q[s].alive = 0;
+            if (nb == BK_GRASS) qw[s] = 0u;
         }
     }
 
@@ -430,7 +433,7 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
 
     // ---- reward, time, done ---------------------------------------------------------------------------
     StepOut out;
-    out.mvx = mvx; out.mvy = mvy;
+    out.mvx = mvx; out.mvy = mvy; out.woff = woff;
     const int gained = __popc(ach & ~ach0);
     out.reward = (float)(10 * gained + (vit[0] - health0)) * 0.1f;
     const uint32_t t1 = t + 1;
@@ -439,12 +442,10 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     if (out.done) return out;
 
     // ---- pack the record back into LDS ------------------------------------------------------------------
+    group_sync();
     if (l == 0) {
-        uint32_t wi = 0;
-#pragma unroll
-        for (int i = 0; i < 6; ++i) wi |= ((uint32_t)inv[i] << (4 * i)) | ((uint32_t)inv[6 + i] << (24 + i));
         rec[RW_POS] = (uint32_t)px | ((uint32_t)py << 8) | ((uint32_t)dir << 16) | ((uint32_t)sleeping << 24);
-        rec[RW_INV] = wi;
+        rec[RW_INV] = w_inv;
         rec[RW_VIT] = (uint32_t)vit[0] | ((uint32_t)vit[1] << 4) | ((uint32_t)vit[2] << 8) | ((uint32_t)vit[3] << 12) | (phase << 16);
         rec[RW_CNT] = (uint32_t)(cnt[0] & 0xFF) | ((uint32_t)(cnt[1] & 0xFF) << 8) | ((uint32_t)(cnt[2] & 0xFF) << 16) | ((uint32_t)(cnt[3] & 0xFF) << 24);
         rec[RW_ACH] = ach;
@@ -453,12 +454,12 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
 #pragma unroll
     for (int s = 0; s < NSM; ++s) {
         const int k = l + s * G;
-        if (k < NMOB) rec[RW_MOB + k] = pack_mob(m[s]);
+        if (k < NMOB) rec[RW_MOB + k] = mw[s];
     }
 #pragma unroll
     for (int s = 0; s < NSP; ++s) {
         const int k = l + s * G;
-        if (k < NPLANT) rec[RW_PLANT + k] = pack_plant(q[s]);
+        if (k < NPLANT) rec[RW_PLANT + k] = qw[s];
     }
     group_sync();
     return out;

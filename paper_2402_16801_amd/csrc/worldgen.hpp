@@ -2,7 +2,7 @@
 // Generation" of the paper: noise thresholds carve grassland, forest, lakes, mountains with
 // caves, tunnels, ores and lava).  The paper uses Perlin noise in floating point; this
 // library uses seeded integer value noise so that every cell is a pure integer function of
-// (seed, env, episode).  All 256 threads of the block take part.
+// (seed, env, episode).  All 512 threads of the block take part.
 #pragma once
 
 #include "common.hpp"
@@ -66,9 +66,15 @@ __device__ inline int classify(int W, int M, int C, int F, int x, int y, int u)
     return BK_GRASS;
 }
 
-// Generates the map of one environment with the 256 threads of the calling block.
-// s_lat: LDS scratch of at least LAT_BLOCKS*8 u16.  Ends with every thread's stores issued;
-// the caller synchronises before anyone reads the map.
+// Generates the map of one environment with the WG_THREADS = 512 threads of the calling
+// block: thread t owns the 8 cells [8t, 8t+8) of row t/8, which are exactly one spacing-8
+// lattice cell wide (and inside one spacing-16 cell), and whose per-cell uniforms are
+// exactly Philox block t of stream 1.  A reset is latency-bound, so the work is cut into
+// many short threads and two such blocks fit on a compute unit.
+// s_lat: LDS scratch of at least LAT_BLOCKS*8 u16.  Ends with a block barrier, after which
+// the map is visible to the whole block.
+constexpr int WG_THREADS = 512;
+
 __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat, uint32_t seed_lo, uint32_t seed_hi,
                                       uint32_t env, uint32_t episode)
 {
@@ -81,10 +87,9 @@ __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat
             s_lat[tid * 8 + 2 * w + 1] = (uint16_t)(r.w[w] >> 16);
         }
     }
+    const U4 r = philox4x32_10(env, 1u, episode, (DOM_WORLDGEN << 16) | (uint32_t)tid, seed_lo, seed_hi);
     __syncthreads();
-    // thread tid owns the 16 cells [16 tid, 16 tid + 16): one quarter of row tid/4.  Its run
-    // spans one spacing-16 lattice cell and two spacing-8 lattice cells.
-    const int y = tid >> 2, x0 = (tid & 3) << 4;
+    const int y = tid >> 3, x0 = (tid & 7) << 3;
     const uint16_t* w16 = s_lat;
     const uint16_t* m16 = s_lat + LAT16_N;
     const uint16_t* w8 = s_lat + 2 * LAT16_N;
@@ -95,47 +100,37 @@ __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat
     const uint32_t wy16 = smooth16(y & 15), wy8 = smooth8(y & 7);
     const uint32_t W16a = column(w16, 5, ix16, iy16, wy16), W16b = column(w16, 5, ix16 + 1, iy16, wy16);
     const uint32_t M16a = column(m16, 5, ix16, iy16, wy16), M16b = column(m16, 5, ix16 + 1, iy16, wy16);
-    uint32_t W8[3], M8[3], C8[3], F8[3];
+    const uint32_t Wl = column(w8, 9, ix8, iy8, wy8), Wr = column(w8, 9, ix8 + 1, iy8, wy8);
+    const uint32_t Ml = column(m8, 9, ix8, iy8, wy8), Mr = column(m8, 9, ix8 + 1, iy8, wy8);
+    const uint32_t Cl = column(c8, 9, ix8, iy8, wy8), Cr = column(c8, 9, ix8 + 1, iy8, wy8);
+    const uint32_t Fl = column(f8, 9, ix8, iy8, wy8), Fr = column(f8, 9, ix8 + 1, iy8, wy8);
+    uint32_t packed[2] = { 0u, 0u };
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        W8[i] = column(w8, 9, ix8 + i, iy8, wy8);
-        M8[i] = column(m8, 9, ix8 + i, iy8, wy8);
-        C8[i] = column(c8, 9, ix8 + i, iy8, wy8);
-        F8[i] = column(f8, 9, ix8 + i, iy8, wy8);
+    for (int j = 0; j < 8; ++j) {
+        const int x = x0 + j;
+        const uint32_t rw = r.w[j >> 1];
+        const int u = (int)((j & 1) ? (rw >> 16) : (rw & 0xFFFFu));
+        const uint32_t wx8 = smooth8(j), wx16 = smooth16(x & 15);
+        const int W = (int)((3u * across(W16a, W16b, wx16) + across(Wl, Wr, wx8)) >> 2);
+        const int M = (int)((3u * across(M16a, M16b, wx16) + across(Ml, Mr, wx8)) >> 2);
+        const int C = (int)across(Cl, Cr, wx8), F = (int)across(Fl, Fr, wx8);
+        packed[j >> 2] |= (uint32_t)classify(W, M, C, F, x, y, u) << (8 * (j & 3));
     }
-    uint32_t packed[4] = { 0u, 0u, 0u, 0u };
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        const U4 r = philox4x32_10(env, 1u, episode, (DOM_WORLDGEN << 16) | (uint32_t)(2 * tid + half), seed_lo, seed_hi);
-        const uint32_t Wl = W8[half], Wr = W8[half + 1], Ml = M8[half], Mr = M8[half + 1];
-        const uint32_t Cl = C8[half], Cr = C8[half + 1], Fl = F8[half], Fr = F8[half + 1];
-#pragma unroll 1
-        for (int j = 0; j < 8; ++j) {
-            const int w = j >> 1;
-            const uint32_t rw = w == 0 ? r.w[0] : (w == 1 ? r.w[1] : (w == 2 ? r.w[2] : r.w[3]));
-            const int u = (int)((j & 1) ? (rw >> 16) : (rw & 0xFFFFu));
-            const uint32_t wx8 = smooth8(j), wx16 = smooth16(half * 8 + j);
-            const int W = (int)((3u * across(W16a, W16b, wx16) + across(Wl, Wr, wx8)) >> 2);
-            const int M = (int)((3u * across(M16a, M16b, wx16) + across(Ml, Mr, wx8)) >> 2);
-            const int C = (int)across(Cl, Cr, wx8), F = (int)across(Fl, Fr, wx8);
-            const uint32_t b = (uint32_t)classify(W, M, C, F, x0 + half * 8 + j, y, u);
-            const uint32_t word = b << ((j & 3) * 8);
-            if (j < 4) packed[2 * half] |= word; else packed[2 * half + 1] |= word;
-        }
-    }
-    reinterpret_cast<uint4*>(map)[tid] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
-    __syncthreads();   // s_lat may be reused by the caller
+    reinterpret_cast<uint2*>(map)[tid] = make_uint2(packed[0], packed[1]);
+    __syncthreads();
 }
 
-// A fresh record for a new episode: full vitals, empty tables, player in the middle facing down.
-__device__ inline void fresh_record(uint32_t* rec, uint32_t seed_lo, uint32_t seed_hi, uint32_t episode)
+// Word i of a fresh record: full vitals, empty tables, player in the middle facing down.
+__device__ inline uint32_t fresh_record_word(int i, uint32_t seed_lo, uint32_t seed_hi, uint32_t episode)
 {
-    for (int i = 0; i < REC_DWORDS; ++i) rec[i] = 0;
-    rec[RW_POS] = (uint32_t)(MAPW / 2) | ((uint32_t)(MAPW / 2) << 8) | (4u << 16);
-    rec[RW_VIT] = (uint32_t)MAX_COUNT * 0x1111u;
-    rec[RW_EPISODE] = episode;
-    rec[RW_SEED_LO] = seed_lo;
-    rec[RW_SEED_HI] = seed_hi;
+    switch (i) {
+    case RW_POS: return (uint32_t)(MAPW / 2) | ((uint32_t)(MAPW / 2) << 8) | (4u << 16);
+    case RW_VIT: return (uint32_t)MAX_COUNT * 0x1111u;
+    case RW_EPISODE: return episode;
+    case RW_SEED_LO: return seed_lo;
+    case RW_SEED_HI: return seed_hi;
+    default: return 0u;
+    }
 }
 
 }  // namespace cx

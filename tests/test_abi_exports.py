@@ -41,7 +41,7 @@ def test_sizes_and_defaults(lib):
     assert 1345 * 4 <= strides[2] and 63 * 63 * 3 * 4 <= strides[3]
     cfg.obs_mode = 1
     b1, b2 = binding.craftax_state_bytes(cfg, 1), binding.craftax_state_bytes(cfg, 1001)
-    assert abs((b2 - b1) - 1000 * (4096 + 128 + 4)) < 256 and b1 % 256 == 0   # map + record + done-list entry
+    assert abs((b2 - b1) - 1000 * (4096 + 128 + 16)) < 256 and b1 % 256 == 0   # map + record + done-list entry
     assert binding.craftax_state_bytes(cfg, 0) == 0 and binding.craftax_state_bytes(cfg, -3) == 0
     cfg.day_length = 7
     assert binding.craftax_state_bytes(cfg, 4) == 0
