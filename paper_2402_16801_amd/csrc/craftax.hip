@@ -125,6 +125,10 @@ __global__ __launch_bounds__(WG_THREADS) void k_reset_list(uint4* __restrict__ r
     constexpr int G = 16;
     __shared__ uint16_t s_lat[LAT_BLOCKS * 8];
     __shared__ uint32_t s_env[LDS_ENV_DWORDS];
+    uint4 entry = dl.list[blockIdx.x];   // fetched together with the count; ignored if beyond it
+    // the scalars of a fresh episode are constants: fetch their table entries before anything else
+    const float fresh_tenth = luts->tenth[MAX_COUNT], fresh_day = luts->daylight[0];
+    const uint32_t fresh_q7 = luts->light_q7[0];
     const uint32_t count = *dl.count;
     if (blockIdx.x >= count) return;
     const int tid = threadIdx.x;
@@ -136,7 +140,7 @@ __global__ __launch_bounds__(WG_THREADS) void k_reset_list(uint4* __restrict__ r
     }
     constexpr bool kSymbolic = OBS_MODE != CRAFTAX_OBS_PIXELS_F32;
     for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
-        const uint4 entry = dl.list[i];
+        if (i != blockIdx.x) entry = dl.list[i];
         const uint32_t env = entry.x, lo = entry.y, hi = entry.z, ep = entry.w;
         uint32_t* grec = reinterpret_cast<uint32_t*>(recs + (size_t)env * 8);
         uint8_t* map = maps + (size_t)env * (MAPW * MAPW);
@@ -145,11 +149,24 @@ __global__ __launch_bounds__(WG_THREADS) void k_reset_list(uint4* __restrict__ r
             grec[tid - 64] = w;
             s_env[LDS_REC + tid - 64] = w;
         }
-        worldgen_block(map, s_lat, lo, hi, env, ep);           // ends with a block barrier
+        worldgen_block(map, s_lat, lo, hi, env, ep, s_env + LDS_WIN);   // ends with a block barrier
         if (kSymbolic && obs != nullptr && tid < G) {
-            load_window<G>(tid, MAPW / 2, MAPW / 2, map, s_env + LDS_WIN);
-            group_sync();
-            render_symbolic<G, OBS_MODE>(tid, s_env, 0, 0, (MAPW / 2 - WIN_COLS / 2) & 3, luts, obs + (size_t)env * obs_stride(OBS_MODE));
+            // scalars of a fresh episode: empty inventory, vitals 9, facing down, noon, awake
+            uint32_t* vec = s_env + LDS_VEC;
+            for (int i = tid; i < 24; i += G) {
+                uint32_t w = 0;
+                if (OBS_MODE == CRAFTAX_OBS_SYM_U8_I8) {
+                    if (i == 3) w = 0x09090909u;                       // bytes 12..15: the four vitals
+                    if (i == 4) w = 1u << 24;                          // byte 19: facing down
+                    if (i == 5) w = fresh_q7;                          // byte 20: daylight
+                } else {
+                    if (i >= 12 && i < 16) w = __float_as_uint(fresh_tenth);
+                    if (i == 19) w = __float_as_uint(1.0f);
+                    if (i == 20) w = __float_as_uint(fresh_day);
+                }
+                vec[i] = w;
+            }
+            render_symbolic<G, OBS_MODE, false>(tid, s_env, 0, 0, (MAPW / 2 - WIN_COLS / 2) & 3, luts, obs + (size_t)env * obs_stride(OBS_MODE));
         }
         __syncthreads();
     }

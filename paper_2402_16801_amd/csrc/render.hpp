@@ -27,7 +27,8 @@ __device__ inline uint32_t spread4(uint32_t nibble) { return (nibble * 0x0020408
 // The one-hot channels are collected as single bits in LDS (one atomic OR per set channel),
 // then each lane expands 16 bits into a 16-byte store, so the HBM write is fully coalesced
 // and the staging costs 166 bytes of LDS per environment instead of 1323.
-template <int G, int OBS_MODE>
+// FILL_VEC = false: the caller has already put the 22 scalars into the LDS vector area.
+template <int G, int OBS_MODE, bool FILL_VEC = true>
 __device__ inline void render_symbolic(int l, uint32_t* e, int mvx, int mvy, int woff, const Luts* __restrict__ luts,
                                        uint8_t* __restrict__ obs_out)
 {
@@ -73,7 +74,8 @@ __device__ inline void render_symbolic(int l, uint32_t* e, int mvx, int mvy, int
         if (i == 21) return sleeping;
         return 0;
     };
-    if (OBS_MODE == 0) {
+    if (!FILL_VEC) {
+    } else if (OBS_MODE == 0) {
 #pragma unroll
         for (int it_i = 0; it_i < ((8) + G - 1) / G; ++it_i) {
         const int i = l + it_i * G;

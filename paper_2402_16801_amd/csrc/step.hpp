@@ -30,14 +30,23 @@ struct StepOut { bool done; float reward; int mvx, mvy, woff; };
 template <int G>
 __device__ inline void load_window(int l, int px, int py, const uint8_t* __restrict__ map, uint32_t* win)
 {
+    constexpr int NIT = (WIN_DWORDS + G - 1) / G;
     const int xa = (px - WIN_COLS / 2) & ~3, y0 = py - WIN_ROWS / 2;
+    uint32_t v[NIT];
+    bool inside[NIT];
+    // all loads are issued unconditionally (outside cells read offset 0 and are replaced
+    // afterwards), so they go out back to back and are waited for once
 #pragma unroll
-    for (int it = 0; it < (WIN_DWORDS + G - 1) / G; ++it) {
+    for (int it = 0; it < NIT; ++it) {
         const int d = l + it * G;
-        if (d >= WIN_DWORDS) break;
         const int r = d >> 2, x = xa + ((d & 3) << 2), y = y0 + r;
-        const bool inside = (unsigned)y < (unsigned)MAPW && (unsigned)x < (unsigned)MAPW;
-        win[d] = inside ? *reinterpret_cast<const uint32_t*>(map + y * MAPW + x) : 0x01010101u * (uint32_t)BK_OOB;
+        inside[it] = d < WIN_DWORDS && (unsigned)y < (unsigned)MAPW && (unsigned)x < (unsigned)MAPW;
+        v[it] = *reinterpret_cast<const uint32_t*>(map + (inside[it] ? y * MAPW + x : 0));
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int d = l + it * G;
+        if (d < WIN_DWORDS) win[d] = inside[it] ? v[it] : 0x01010101u * (uint32_t)BK_OOB;
     }
 }
 
@@ -101,7 +110,8 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     for (int s = 0; s < NSP; ++s) {
         const int k = l + s * G;
         qw[s] = k < NPLANT ? rec[RW_PLANT + k] : 0u;
-        q_block[s] = (qw[s] & 1u) ? (int)map[mob_y(qw[s]) * MAPW + mob_x(qw[s])] : (int)BK_INVALID;
+        q_block[s] = (int)map[(qw[s] & 1u) ? mob_y(qw[s]) * MAPW + mob_x(qw[s]) : 0];   // unconditional load
+        if (!(qw[s] & 1u)) q_block[s] = BK_INVALID;
     }
     const int health0 = vit[0];
     const uint32_t ach0 = ach;
@@ -243,6 +253,7 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     // packed intent: kind | ok<<3 | at_player<<4 | target key<<8 | direction<<24
     int packed[NSM];
     int n_attack = 0, n_arrow = 0;
+    int kind_[NSM], ndir_[NSM], tx_[NSM], ty_[NSM], tb_[NSM];
 #pragma unroll
     for (int s = 0; s < NSM; ++s) {
         const int k = l + s * G;
@@ -281,21 +292,12 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
                 kind = K_FLY; ndir = (int)__builtin_amdgcn_ubfe(mw[s], 13, 3);
             }
         }
-        const int tx = mx + dir_dx(ndir), ty = my + dir_dy(ndir);
-        const bool t_in = in_map(tx, ty);
-        int tb = BK_OOB;
-        if (kind != K_NONE && kind != K_ATTACK && t_in) {
-            tb = map[ty * MAPW + tx];
-            if (ty * MAPW + tx == modcell) tb = modval;
-        }
-        const uint32_t tkey = cell_key(tx & 63, ty & 63);
-        const bool at_player = t_in && tkey == pkey;
-        const bool t_ok = t_in && (kind == K_MOVE ? walkable_ground(tb) : (kind == K_MOVE_PATH ? tb == BK_PATH : arrow_flyable(tb)));
-        packed[s] = kind | ((int)t_ok << 3) | ((int)at_player << 4) | (int)(tkey << 8) | (ndir << 24);
-        n_attack += __popc(Gr::ballot(kind == K_ATTACK));
-        n_arrow += __popc(Gr::ballot((kind == K_SHOOT || kind == K_FLY) && at_player));
+        kind_[s] = kind; ndir_[s] = ndir;
+        tx_[s] = mx + dir_dx(ndir); ty_[s] = my + dir_dy(ndir);
+        // terrain of the target cell: loaded unconditionally (cell 0 when there is no target)
+        const bool need = kind != K_NONE && kind != K_ATTACK && in_map(tx_[s], ty_[s]);
+        tb_[s] = (int)map[need ? ty_[s] * MAPW + tx_[s] : 0];
     }
-
     // spawn candidates (phase 3) are fixed by the draws and the player's position: read their
     // terrain now so the loads overlap the mob resolution below
     uint32_t sp_key[3];
@@ -310,7 +312,21 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
         const int sx = px + dx, sy = py + dy;
         sp_cand[j] = max(iabs(dx), iabs(dy)) >= SPAWN_MIN_DIST && in_map(sx, sy);
         sp_key[j] = cell_key(sx & 63, sy & 63);
-        sp_b[j] = sp_cand[j] ? (int)map[sy * MAPW + sx] : (int)BK_OOB;
+        sp_b[j] = (int)map[sp_cand[j] ? sy * MAPW + sx : 0];
+        if (!sp_cand[j]) sp_b[j] = BK_OOB;
+    }
+#pragma unroll
+    for (int s = 0; s < NSM; ++s) {
+        const int kind = kind_[s], tx = tx_[s], ty = ty_[s];
+        const bool t_in = in_map(tx, ty);
+        int tb = (kind != K_NONE && kind != K_ATTACK && t_in) ? tb_[s] : (int)BK_OOB;
+        if (ty * MAPW + tx == modcell && t_in) tb = modval;
+        const uint32_t tkey = cell_key(tx & 63, ty & 63);
+        const bool at_player = t_in && tkey == pkey;
+        const bool t_ok = t_in && (kind == K_MOVE ? walkable_ground(tb) : (kind == K_MOVE_PATH ? tb == BK_PATH : arrow_flyable(tb)));
+        packed[s] = kind | ((int)t_ok << 3) | ((int)at_player << 4) | (int)(tkey << 8) | (ndir_[s] << 24);
+        n_attack += __popc(Gr::ballot(kind == K_ATTACK));
+        n_arrow += __popc(Gr::ballot((kind == K_SHOOT || kind == K_FLY) && at_player));
     }
 
     const int damage = n_attack * (sleeping ? DMG_ZOMBIE_SLEEP : DMG_ZOMBIE) + n_arrow * DMG_ARROW;

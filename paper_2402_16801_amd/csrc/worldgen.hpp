@@ -75,8 +75,11 @@ __device__ inline int classify(int W, int M, int C, int F, int x, int y, int u)
 // the map is visible to the whole block.
 constexpr int WG_THREADS = 512;
 
+// start_win (may be null): LDS window (9 rows x 4 dwords) of the start position (32, 32); the
+// threads that own those cells drop them there, so the first observation of the new episode
+// can be rendered without reading the map back.
 __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat, uint32_t seed_lo, uint32_t seed_hi,
-                                      uint32_t env, uint32_t episode)
+                                      uint32_t env, uint32_t episode, uint32_t* start_win = nullptr)
 {
     const int tid = threadIdx.x;
     if (tid < LAT_BLOCKS) {
@@ -117,6 +120,15 @@ __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat
         packed[j >> 2] |= (uint32_t)classify(W, M, C, F, x, y, u) << (8 * (j & 3));
     }
     reinterpret_cast<uint2*>(map)[tid] = make_uint2(packed[0], packed[1]);
+    {
+        // window of the start cell: rows 28..36, columns 24..39 (aligned start of 32-5)
+        constexpr int WY0 = MAPW / 2 - WIN_ROWS / 2, WX0 = (MAPW / 2 - WIN_COLS / 2) & ~3;
+        const int wr = y - WY0, wc = x0 - WX0;
+        if (start_win != nullptr && (unsigned)wr < (unsigned)WIN_ROWS && (unsigned)wc < (unsigned)WIN_PITCH) {
+            start_win[wr * (WIN_PITCH / 4) + wc / 4] = packed[0];
+            start_win[wr * (WIN_PITCH / 4) + wc / 4 + 1] = packed[1];
+        }
+    }
     __syncthreads();
 }
 
