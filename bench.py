@@ -31,13 +31,10 @@ def algorithmic_bytes_per_env_step(mean_episode_len: float) -> dict:
     parts = {
         "obs_write": OBS_ALG_BYTES,
         "action_reward_done": 4 + 4 + 1,
-        "player_record_rw": 52 + 40,          # pos/dir/sleep 4, inventory 12, vitals 4, counters 8,
-                                              # achievements 4, t 4, phase 4 read+written; episode 4, seed 8 read
-        "mob_table_rw": 12 * 6 * 2,           # alive,x,y,dir,hp,cd per slot, read + write
-        "plant_table_rw": 10 * 5 * 2,         # alive,x,y,age(2) per slot, read + write
+        "record_rw": 128 + 128,               # packed record (player 40 B, 12 mob words, 10 plant words), read + write
         "map_reads": 63 + 9 + 12 + 3 + 10,    # view, 3x3 neighbourhood, mob targets, spawn probes, plant cells
         "map_writes": 2,
-        "reset_amortised": (4096 + 256) / max(mean_episode_len, 1.0),
+        "reset_amortised": (4096 + 128 + 16) / max(mean_episode_len, 1.0),   # new map + record + done-list entry
     }
     parts["total"] = float(sum(parts.values()))
     return parts
@@ -126,8 +123,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-small", action="store_true", help="skip the secondary 4096-env measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="first run one plain 256 MiB device-to-device copy kernel (reference for rocprofv3 "
-                         "FETCH_SIZE / WRITE_SIZE readings)")
+                    help="first run one plain elementwise kernel that reads and writes 256 MiB (reference for "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; environments are independent and would shard "
@@ -137,10 +134,11 @@ def main():
 
     if args.calibrate_copy:
         import torch
-        src = torch.full((256 << 20,), 7, dtype=torch.uint8, device="cuda:0")
+        # one elementwise kernel that reads 256 MiB and writes 256 MiB
+        src = torch.full((64 << 20,), 7, dtype=torch.int32, device="cuda:0")
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        dst.copy_(src)
+        torch.add(src, 1, out=dst)
         torch.cuda.synchronize()
         del src, dst
 
@@ -178,8 +176,8 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": read_profile_traffic("k_step_sym_u8_f32_65536env.txt"),
-            "kernel": "k_step<SYM_U8_F32>",
+            "traffic": read_profile_traffic("craftax_step_sym_u8_f32_65536env.txt"),
+            "kernel": "k_step<4 lanes, SYM_U8_F32> + k_reset_list (one craftax_step call)",
             "alg_bytes_per_env_step": round(alg["total"], 1),
             "alg_bytes_per_launch": per_launch_bytes,
             "avg_launch_us": launch_s * 1e6,
@@ -190,7 +188,7 @@ def main():
         out["also"] = {"workload": "configs[1]: 4096 envs, uniform actions", "value": 4096 * K / small["wall_s"],
                        "unit": "env_steps/s", "ms_per_step": small["wall_s"] / K * 1e3}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(2048, min(K, 1000), args.kind)
+        out["cpu_baseline"] = cpu_baseline(8192, min(K, 1000), args.kind)
     print(json.dumps(out))
 
 
