@@ -211,7 +211,10 @@ __global__ __launch_bounds__(BLOCK) void k_export(const uint4* __restrict__ recs
 {
     const int env = first + blockIdx.x, tid = threadIdx.x;
     craftax_env_dump* d = dumps + blockIdx.x;
-    reinterpret_cast<uint4*>(d->map)[tid] = reinterpret_cast<const uint4*>(maps + (size_t)env * (MAPW * MAPW))[tid];
+    {   // 16-byte piece tid of the tiled map = row (tid & 7) of tile (tid >> 3) -> row-major dump
+        const int tile = tid >> 3, y = ((tile >> 2) << 3) + (tid & 7), x = (tile & 3) << 4;
+        *reinterpret_cast<uint4*>(d->map + y * MAPW + x) = reinterpret_cast<const uint4*>(maps + (size_t)env * (MAPW * MAPW))[tid];
+    }
     __shared__ uint32_t r[REC_DWORDS];
     if (tid < REC_DWORDS) r[tid] = reinterpret_cast<const uint32_t*>(recs + (size_t)env * 8)[tid];
     __syncthreads();
@@ -244,7 +247,10 @@ __global__ __launch_bounds__(BLOCK) void k_import(uint4* __restrict__ recs, uint
 {
     const int env = first + blockIdx.x, tid = threadIdx.x;
     const craftax_env_dump* d = dumps + blockIdx.x;
-    reinterpret_cast<uint4*>(maps + (size_t)env * (MAPW * MAPW))[tid] = reinterpret_cast<const uint4*>(d->map)[tid];
+    {
+        const int tile = tid >> 3, y = ((tile >> 2) << 3) + (tid & 7), x = (tile & 3) << 4;
+        reinterpret_cast<uint4*>(maps + (size_t)env * (MAPW * MAPW))[tid] = *reinterpret_cast<const uint4*>(d->map + y * MAPW + x);
+    }
     __shared__ uint32_t r[REC_DWORDS];
     if (tid < REC_DWORDS) r[tid] = 0;
     __syncthreads();

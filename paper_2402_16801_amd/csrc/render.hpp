@@ -151,7 +151,7 @@ __device__ inline void render_pixels_block(const uint32_t* __restrict__ rec, con
     if (tid < 81) {
         const int tr = tid / 9, tc = tid - tr * 9;
         const int x = px + tc - 4, y = py + tr - 4;
-        s_tile[tid] = in_map(x, y) ? (int)map[y * MAPW + x] : (int)BK_OOB;
+        s_tile[tid] = in_map(x, y) ? (int)map[map_index(x, y)] : (int)BK_OOB;
         s_ent[tid] = (tid == 40) ? 0 : -1;
     }
     __syncthreads();

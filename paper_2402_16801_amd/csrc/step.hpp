@@ -25,8 +25,8 @@ enum Intent : int { K_NONE = 0, K_MOVE = 1, K_MOVE_PATH = 2, K_ATTACK = 3, K_SHO
 struct StepOut { bool done; float reward; int mvx, mvy, woff; };
 
 // Loads the map window around (px, py) into LDS with aligned dword loads: lane l takes dwords
-// l, l+G, ... of the 36; the four dwords of a window row are 16 contiguous map bytes, so the
-// lanes of one environment read whole rows and a wave touches few cache lines per load.
+// l, l+G, ... of the 36 (four per window row).  A dword never straddles a map tile, and the
+// whole window lies in at most four tiles (cache lines).
 template <int G>
 __device__ inline void load_window(int l, int px, int py, const uint8_t* __restrict__ map, uint32_t* win)
 {
@@ -41,7 +41,7 @@ __device__ inline void load_window(int l, int px, int py, const uint8_t* __restr
         const int d = l + it * G;
         const int r = d >> 2, x = xa + ((d & 3) << 2), y = y0 + r;
         inside[it] = d < WIN_DWORDS && (unsigned)y < (unsigned)MAPW && (unsigned)x < (unsigned)MAPW;
-        v[it] = *reinterpret_cast<const uint32_t*>(map + (inside[it] ? y * MAPW + x : 0));
+        v[it] = *reinterpret_cast<const uint32_t*>(map + (inside[it] ? map_index(x, y) : 0));
     }
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
@@ -110,7 +110,7 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     for (int s = 0; s < NSP; ++s) {
         const int k = l + s * G;
         qw[s] = k < NPLANT ? rec[RW_PLANT + k] : 0u;
-        q_block[s] = (int)map[(qw[s] & 1u) ? mob_y(qw[s]) * MAPW + mob_x(qw[s]) : 0];   // unconditional load
+        q_block[s] = (int)map[(qw[s] & 1u) ? map_index(mob_x(qw[s]), mob_y(qw[s])) : 0];   // unconditional load
         if (!(qw[s] & 1u)) q_block[s] = BK_INVALID;
     }
     const int health0 = vit[0];
@@ -238,7 +238,7 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     }
     const int modcell = modval >= 0 ? fy * MAPW + fx : -1;
     if (modval >= 0) {
-        if (l == 0) { map[modcell] = (uint8_t)modval; win[f_win] = (uint8_t)modval; }
+        if (l == 0) { map[map_index(fx, fy)] = (uint8_t)modval; win[f_win] = (uint8_t)modval; }
 #pragma unroll
         for (int s = 0; s < NSP; ++s) {
             const int k = l + s * G;
@@ -296,7 +296,7 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
         tx_[s] = mx + dir_dx(ndir); ty_[s] = my + dir_dy(ndir);
         // terrain of the target cell: loaded unconditionally (cell 0 when there is no target)
         const bool need = kind != K_NONE && kind != K_ATTACK && in_map(tx_[s], ty_[s]);
-        tb_[s] = (int)map[need ? ty_[s] * MAPW + tx_[s] : 0];
+        tb_[s] = (int)map[need ? map_index(tx_[s], ty_[s]) : 0];
     }
     // spawn candidates (phase 3) are fixed by the draws and the player's position: read their
     // terrain now so the loads overlap the mob resolution below
@@ -312,7 +312,7 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
         const int sx = px + dx, sy = py + dy;
         sp_cand[j] = max(iabs(dx), iabs(dy)) >= SPAWN_MIN_DIST && in_map(sx, sy);
         sp_key[j] = cell_key(sx & 63, sy & 63);
-        sp_b[j] = (int)map[sp_cand[j] ? sy * MAPW + sx : 0];
+        sp_b[j] = (int)map[sp_cand[j] ? map_index(sx, sy) : 0];
         if (!sp_cand[j]) sp_b[j] = BK_OOB;
     }
 #pragma unroll
@@ -416,7 +416,7 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
             if (nb == BK_PLANT && (qw[s] >> 16) >= (uint32_t)RIPE_AGE) nb = BK_RIPE;
             if (zombie_near && dr[s].w[2] < P_PLANT_EATEN) nb = BK_GRASS;
             if (nb != q_block[s]) {
-                map[qy * MAPW + qx] = (uint8_t)nb;
+                map[map_index(qx, qy)] = (uint8_t)nb;
                 const int wx = qx - (px0 - WIN_COLS / 2), wy = qy - (py0 - WIN_ROWS / 2);
                 if ((unsigned)wx < (unsigned)WIN_COLS && (unsigned)wy < (unsigned)WIN_ROWS) win[wy * WIN_PITCH + woff + wx] = (uint8_t)nb;
             }

@@ -119,7 +119,7 @@ __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat
         const int C = (int)across(Cl, Cr, wx8), F = (int)across(Fl, Fr, wx8);
         packed[j >> 2] |= (uint32_t)classify(W, M, C, F, x, y, u) << (8 * (j & 3));
     }
-    reinterpret_cast<uint2*>(map)[tid] = make_uint2(packed[0], packed[1]);
+    *reinterpret_cast<uint2*>(map + map_index(x0, y)) = make_uint2(packed[0], packed[1]);   // 8 cells inside one tile row
     {
         // window of the start cell: rows 28..36, columns 24..39 (aligned start of 32-5)
         constexpr int WY0 = MAPW / 2 - WIN_ROWS / 2, WX0 = (MAPW / 2 - WIN_COLS / 2) & ~3;
