@@ -45,8 +45,8 @@ enum { CRAFTAX_VARIANT_CLASSIC = 0 };
 /* Observation layouts (per environment, stride = craftax_obs_bytes()):
  *  SYM_U8_I8  : bytes [0,1323) 7x9 cells x 21 channels (17-way block one-hot, then zombie,
  *               cow, skeleton, arrow bits), row-major (row, col, channel); int8[22] raw
- *               scalars at byte 1328; stride 1360.
- *  SYM_U8_F32 : same cell bytes; float[22] scaled scalars at byte 1328; stride 1424.
+ *               scalars at byte 1328; stride 1408 (11 cache lines).
+ *  SYM_U8_F32 : same cell bytes; float[22] scaled scalars at byte 1328; stride 1536 (12 cache lines).
  *  SYM_F32    : float[1345] = the cell bytes as 0.0/1.0 followed by the 22 scaled scalars
  *               (the flat layout of the paper, section "RL Environment Interface"); stride 5392.
  *  PIXELS_F32 : float[63][63][3] RGB in [0,1]; stride 47632.

@@ -116,8 +116,8 @@ size_t orc_env_bytes(void) { return sizeof(orc_env); }
 size_t orc_obs_bytes(int mode)
 {
     switch (mode) {
-    case ORC_OBS_SYM_U8_I8: return 1360;
-    case ORC_OBS_SYM_U8_F32: return 1424;
+    case ORC_OBS_SYM_U8_I8: return 1408;   /* 11 cache lines of 128 bytes */
+    case ORC_OBS_SYM_U8_F32: return 1536;  /* 12 cache lines */
     case ORC_OBS_SYM_F32: return 5392;
     case ORC_OBS_PIXELS_F32: return 47632;
     }

@@ -16,7 +16,7 @@ _SOURCES = ["philox.c", "classic.c"]
 LIB_PATH = os.path.join(_HERE, "liboracle.so")
 
 OBS_SYM_U8_I8, OBS_SYM_U8_F32, OBS_SYM_F32, OBS_PIXELS_F32 = 0, 1, 2, 3
-OBS_BYTES = {0: 1360, 1: 1424, 2: 5392, 3: 47632}
+OBS_BYTES = {0: 1408, 1: 1536, 2: 5392, 3: 47632}
 
 MOB_DTYPE = np.dtype([("alive", "u1"), ("x", "u1"), ("y", "u1"), ("dir", "u1"), ("hp", "i1"),
                       ("cd", "u1"), ("pad", "u1", (2,))])

@@ -93,6 +93,8 @@ __global__ __launch_bounds__(BLOCK, 4) void k_step(uint4* __restrict__ recs, uin
     uint32_t* e = s_env + g * LDS_ENV_DWORDS;
     uint8_t* map = maps + (size_t)(active ? env : 0) * (MAPW * MAPW);
     constexpr bool kSymbolic = OBS_MODE != CRAFTAX_OBS_PIXELS_F32;
+    constexpr bool kBytes = OBS_MODE == CRAFTAX_OBS_SYM_U8_I8 || OBS_MODE == CRAFTAX_OBS_SYM_U8_F32;
+    bool staged = false;
     if (active) {
         load_record<G>(l, recs + (size_t)env * 8, e);
         group_sync();
@@ -100,12 +102,22 @@ __global__ __launch_bounds__(BLOCK, 4) void k_step(uint4* __restrict__ recs, uin
         if (l == 0) { reward[env] = o.reward; done[env] = o.done ? 1 : 0; }
         if (!o.done) {
             store_record<G>(l, recs + (size_t)env * 8, e);
-            if (kSymbolic && obs != nullptr)
-                render_symbolic<G, OBS_MODE>(l, e, o.mvx, o.mvy, o.woff, luts, obs + (size_t)env * obs_stride(OBS_MODE));
+            if (kSymbolic && obs != nullptr) {
+                // byte layouts are staged in LDS here and written by the whole wave below
+                render_symbolic<G, OBS_MODE, true, !kBytes>(l, e, o.mvx, o.mvy, o.woff, luts, obs + (size_t)env * obs_stride(OBS_MODE));
+                staged = kBytes;
+            }
         } else if (l == 0) {
             const uint32_t* rec = e + LDS_REC;   // not written back: still the episode that just ended
             s_list[atomicAdd(&s_ndone, 1)] = make_uint4((uint32_t)env, rec[RW_SEED_LO], rec[RW_SEED_HI], rec[RW_EPISODE] + 1u);
         }
+    }
+    if (kBytes && obs != nullptr) {
+        if (l == 0) e[LDS_FLAG] = staged ? 1u : 0u;
+        group_sync();
+        const int first = (tid & ~63) / G;                         // first environment of this wave within the block
+        flush_wave_observations<G, OBS_MODE>(s_env + first * LDS_ENV_DWORDS,
+                                             obs + (size_t)(blockIdx.x * EPB + first) * obs_stride(OBS_MODE));
     }
     __syncthreads();
     const int nd = s_ndone;

@@ -9,7 +9,10 @@
 
 namespace cx {
 
-constexpr int OBS_STRIDE_U8_I8 = 1360, OBS_STRIDE_U8_F32 = 1424, OBS_STRIDE_F32 = 5392, OBS_STRIDE_PIXELS = 47632;
+// The two byte layouts use strides that are multiples of 128 so that every observation starts on
+// a cache-line boundary and can be written as whole lines.
+constexpr int OBS_STRIDE_U8_I8 = 1408, OBS_STRIDE_U8_F32 = 1536, OBS_STRIDE_F32 = 5392, OBS_STRIDE_PIXELS = 47632;
+constexpr int VEC_CHUNKS_I8 = 2, VEC_CHUNKS_F32 = 6;   // 16-byte chunks that hold the 22 scalars
 constexpr int CELL_CHUNKS = VEC_OFFSET / 16;   // 83 sixteen-byte chunks hold the 1323 one-hot bytes (+5 zero)
 
 __host__ __device__ constexpr int obs_stride(int mode)
@@ -27,8 +30,56 @@ __device__ inline uint32_t spread4(uint32_t nibble) { return (nibble * 0x0020408
 // The one-hot channels are collected as single bits in LDS (one atomic OR per set channel),
 // then each lane expands 16 bits into a 16-byte store, so the HBM write is fully coalesced
 // and the staging costs 166 bytes of LDS per environment instead of 1323.
+// One 16-byte chunk of a staged observation (byte layouts): chunks 0..82 expand 16 staged bits
+// each, the next 2 or 6 hold the scalars, the rest of the stride is zero.
+template <int OBS_MODE>
+__device__ inline uint4 staged_chunk(const uint32_t* e, int c)
+{
+    constexpr int NV = OBS_MODE == 0 ? VEC_CHUNKS_I8 : VEC_CHUNKS_F32;
+    if (c < CELL_CHUNKS) {
+        const uint32_t h = reinterpret_cast<const uint16_t*>(e + LDS_BITS)[c];
+        return make_uint4(spread4(h & 15u), spread4((h >> 4) & 15u), spread4((h >> 8) & 15u), spread4(h >> 12));
+    }
+    if (c < CELL_CHUNKS + NV) {
+        const uint32_t* v = e + LDS_VEC + (c - CELL_CHUNKS) * 4;
+        return make_uint4(v[0], v[1], v[2], v[3]);
+    }
+    return make_uint4(0u, 0u, 0u, 0u);
+}
+
+// Writes the staged observations of all environments of the calling wave (byte layouts).
+// Lanes regroup into runs of max(G, 8): a run writes 128 or 256 contiguous, line-aligned bytes
+// of one environment per store instruction, i.e. whole cache lines, as streaming stores (the
+// observation is not read again by this kernel).  With G = 4 a run serves two environments in
+// turn.  wave_env: LDS area of the wave's first environment; wave_obs: its observation.
+template <int G, int OBS_MODE>
+__device__ inline void flush_wave_observations(uint32_t* wave_env, uint8_t* __restrict__ wave_obs)
+{
+    constexpr int RUN = G < 8 ? 8 : G, PASSES = RUN / G, STRIDE = obs_stride(OBS_MODE), NCHUNK = STRIDE / 16;
+    const int w = threadIdx.x & 63, run = w / RUN, j = w % RUN;
+#pragma unroll
+    for (int pass = 0; pass < PASSES; ++pass) {
+        const int ei = run * PASSES + pass;                       // environment within the wave
+        const uint32_t* e = wave_env + ei * LDS_ENV_DWORDS;
+        if (!e[LDS_FLAG]) continue;
+        uint32_t* out = reinterpret_cast<uint32_t*>(wave_obs + (size_t)ei * STRIDE);
+#pragma unroll
+        for (int it = 0; it < (NCHUNK + RUN - 1) / RUN; ++it) {
+            const int c = it * RUN + j;
+            if (c >= NCHUNK) break;
+            const uint4 v = staged_chunk<OBS_MODE>(e, c);
+            __builtin_nontemporal_store(v.x, out + 4 * c);
+            __builtin_nontemporal_store(v.y, out + 4 * c + 1);
+            __builtin_nontemporal_store(v.z, out + 4 * c + 2);
+            __builtin_nontemporal_store(v.w, out + 4 * c + 3);
+        }
+    }
+}
+
 // FILL_VEC = false: the caller has already put the 22 scalars into the LDS vector area.
-template <int G, int OBS_MODE, bool FILL_VEC = true>
+// FLUSH = false: stop after staging (bits and scalars in LDS); the caller writes them out with
+// flush_wave_observations.
+template <int G, int OBS_MODE, bool FILL_VEC = true, bool FLUSH = true>
 __device__ inline void render_symbolic(int l, uint32_t* e, int mvx, int mvy, int woff, const Luts* __restrict__ luts,
                                        uint8_t* __restrict__ obs_out)
 {
@@ -102,22 +153,14 @@ __device__ inline void render_symbolic(int l, uint32_t* e, int mvx, int mvy, int
         }
     }
     group_sync();
+    if (!FLUSH) return;
     if (OBS_MODE == 0 || OBS_MODE == 1) {
         uint4* out = reinterpret_cast<uint4*>(obs_out);
-        const uint16_t* hb = reinterpret_cast<const uint16_t*>(bits);
 #pragma unroll
         for (int it_i = 0; it_i < ((obs_stride(OBS_MODE) / 16) + G - 1) / G; ++it_i) {
-        const int i = l + it_i * G;
-        if (i >= (obs_stride(OBS_MODE) / 16)) break;
-            uint4 v;
-            if (i < CELL_CHUNKS) {
-                const uint32_t h = hb[i];
-                v = make_uint4(spread4(h & 15u), spread4((h >> 4) & 15u), spread4((h >> 8) & 15u), spread4(h >> 12));
-            } else {
-                const int j = (i - CELL_CHUNKS) * 4;
-                v = make_uint4(vec[j], vec[j + 1], vec[j + 2], vec[j + 3]);
-            }
-            out[i] = v;
+            const int i = l + it_i * G;
+            if (i >= (obs_stride(OBS_MODE) / 16)) break;
+            out[i] = staged_chunk<OBS_MODE>(e, i);
         }
     } else {
         // float[1345]: four values per 16-byte store

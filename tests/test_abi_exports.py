@@ -34,7 +34,7 @@ def test_sizes_and_defaults(lib):
     assert (cfg.max_episode_steps, cfg.day_length) == (10000, 300)
     assert (cfg.cap_zombie, cfg.cap_cow, cfg.cap_skeleton, cfg.cap_arrow, cfg.cap_plant) == (3, 3, 3, 3, 10)
     assert binding.craftax_env_dump_bytes() == 4304
-    strides = {0: 1360, 1: 1424, 2: 5392, 3: 47632}
+    strides = {0: 1408, 1: 1536, 2: 5392, 3: 47632}
     for mode, stride in strides.items():
         cfg.obs_mode = mode
         assert binding.craftax_obs_bytes(cfg) == stride and stride % 16 == 0
