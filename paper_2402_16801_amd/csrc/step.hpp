@@ -303,14 +303,16 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     uint32_t sp_key[3];
     int sp_b[3];
     bool sp_cand[3];
-    uint32_t sp_p[3];
 #pragma unroll
     for (int j = 0; j < 3; ++j) {
         const int dx = (int)choice((uint32_t)Gr::shfl((int)dr[(3 * j) / G].w[3], (3 * j) % G), 31) - 15;
         const int dy = (int)choice((uint32_t)Gr::shfl((int)dr[(3 * j + 1) / G].w[3], (3 * j + 1) % G), 31) - 15;
-        sp_p[j] = (uint32_t)Gr::shfl((int)dr[(3 * j + 2) / G].w[3], (3 * j + 2) % G);
+        const uint32_t sp_p = (uint32_t)Gr::shfl((int)dr[(3 * j + 2) / G].w[3], (3 * j + 2) % G);
+        const uint32_t thr = j == 0 ? luts->zombie_thr[phase] : (j == 1 ? P_COW_SPAWN : P_SKELETON_SPAWN);
         const int sx = px + dx, sy = py + dy;
-        sp_cand[j] = max(iabs(dx), iabs(dy)) >= SPAWN_MIN_DIST && in_map(sx, sy);
+        // a candidate only if the probability draw passes too: most attempts end here, and the
+        // terrain byte (a whole cache line of traffic) is then not fetched at all
+        sp_cand[j] = max(iabs(dx), iabs(dy)) >= SPAWN_MIN_DIST && in_map(sx, sy) && sp_p < thr;
         sp_key[j] = cell_key(sx & 63, sy & 63);
         sp_b[j] = (int)map[sp_cand[j] ? map_index(sx, sy) : 0];
         if (!sp_cand[j]) sp_b[j] = BK_OOB;
@@ -384,9 +386,8 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
         const bool occ = Gr::ballot(l_occ) != 0;
         const uint32_t cap = j == 0 ? p.cap_zombie : (j == 1 ? p.cap_cow : p.cap_skeleton);
         const uint32_t free_slots = ~taken & ((1u << cap) - 1u) & 7u;
-        const uint32_t thr = j == 0 ? luts->zombie_thr[phase] : (j == 1 ? P_COW_SPAWN : P_SKELETON_SPAWN);
         const int want = j == 2 ? BK_PATH : BK_GRASS;
-        if (sp_cand[j] && free_slots && !occ && sp_b[j] == want && sp_p[j] < thr) {
+        if (sp_cand[j] && free_slots && !occ && sp_b[j] == want) {
             const int kn = 3 * j + __ffs((int)free_slots) - 1;
             const uint32_t hp = j == 0 ? HP_ZOMBIE : (j == 1 ? HP_COW : HP_SKELETON);
 #pragma unroll
