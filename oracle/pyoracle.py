@@ -12,7 +12,8 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SOURCES = ["philox.c", "classic.c"]
+_SOURCES = ["philox.c", "classic.c", "craftax_full.c"]
+_HEADERS = ["craftax_oracle.h", "craftax_full.h"]
 LIB_PATH = os.path.join(_HERE, "liboracle.so")
 
 OBS_SYM_U8_I8, OBS_SYM_U8_F32, OBS_SYM_F32, OBS_PIXELS_F32 = 0, 1, 2, 3
@@ -36,6 +37,44 @@ ENV_DTYPE = np.dtype([
 assert ENV_DTYPE.itemsize == 4304
 
 
+# ---- full Craftax ------------------------------------------------------------------------
+FULL_OBS_U8_F32, FULL_OBS_F32 = 0, 1
+FULL_OBS_BYTES = {0: 8448, 1: 33152}
+FULL_MOB_DTYPE = np.dtype([("alive", "u1"), ("x", "u1"), ("y", "u1"), ("dir", "u1"), ("hp", "i1"),
+                           ("cd", "u1"), ("type", "u1"), ("pad", "u1")])
+FULL_ENV_DTYPE = np.dtype([
+    ("block", "u1", (9, 48, 48)), ("item", "u1", (9, 48, 48)), ("light", "u1", (9, 48, 48)),
+    ("px", "u1"), ("py", "u1"), ("dir", "u1"), ("floor", "u1"),
+    ("sleeping", "u1"), ("resting", "u1"), ("learned_fireball", "u1"), ("learned_iceball", "u1"),
+    ("inv", "u1", (10,)), ("potion", "u1", (6,)),
+    ("book", "u1"), ("pickaxe", "u1"), ("sword", "u1"), ("sword_ench", "u1"), ("bow", "u1"), ("bow_ench", "u1"),
+    ("armour", "u1", (4,)), ("armour_ench", "u1", (4,)),
+    ("vit", "i1", (5,)),
+    ("xp", "u1"), ("dex", "u1"), ("str", "u1"), ("intel", "u1"),
+    ("pad_a", "u1"),
+    ("cnt", "<i2", (5,)),
+    ("potion_effect", "u1", (6,)), ("kills", "u1", (9,)),
+    ("boss_hits", "u1"), ("boss_vulnerable", "u1"),
+    ("pad_b", "u1"),
+    ("visited", "<u2"),
+    ("ladder_up", "u1", (9, 2)), ("ladder_down", "u1", (9, 2)),
+    ("pad_c", "u1", (2,)),
+    ("ach", "<u4", (3,)),
+    ("t", "<u4"), ("episode", "<u4"), ("env", "<u4"), ("pad0", "<u4"),
+    ("seed", "<u8"),
+    ("mob", FULL_MOB_DTYPE, (9, 14)),
+    ("plant", PLANT_DTYPE, (10,)),
+    ("pad1", "u1", (4,)),
+])
+assert FULL_ENV_DTYPE.itemsize == 63432
+
+
+class FullConfig(ctypes.Structure):
+    _fields_ = [("max_episode_steps", ctypes.c_uint32), ("day_length", ctypes.c_uint32),
+                ("cap_melee", ctypes.c_uint32), ("cap_ranged", ctypes.c_uint32),
+                ("cap_passive", ctypes.c_uint32), ("cap_plant", ctypes.c_uint32)]
+
+
 class Config(ctypes.Structure):
     _fields_ = [("max_episode_steps", ctypes.c_uint32), ("day_length", ctypes.c_uint32),
                 ("cap_zombie", ctypes.c_uint32), ("cap_cow", ctypes.c_uint32),
@@ -46,7 +85,7 @@ class Config(ctypes.Structure):
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain C11, contraction off so floats are single IEEE ops)."""
     srcs = [os.path.join(_HERE, s) for s in _SOURCES]
-    deps = srcs + [os.path.join(_HERE, "craftax_oracle.h")]
+    deps = srcs + [os.path.join(_HERE, h) for h in _HEADERS]
     if not force and os.path.exists(LIB_PATH) and all(
             os.path.getmtime(LIB_PATH) >= os.path.getmtime(d) for d in deps):
         return LIB_PATH
@@ -71,6 +110,10 @@ def lib() -> ctypes.CDLL:
         L.orc_step_draw.restype = ctypes.c_uint32
         L.orc_value_noise.restype = ctypes.c_uint32
         assert L.orc_env_bytes() == ENV_DTYPE.itemsize
+        L.cf_env_bytes.restype = ctypes.c_size_t
+        L.cf_obs_bytes.restype = ctypes.c_size_t
+        L.cf_step_draw.restype = ctypes.c_uint32
+        assert L.cf_env_bytes() == FULL_ENV_DTYPE.itemsize
         _lib = L
     return _lib
 
@@ -149,3 +192,61 @@ class Oracle:
     def draw(self, i: int, block: int, word: int) -> int:
         ptr = ctypes.c_void_p(self.envs.ctypes.data + i * ENV_DTYPE.itemsize)
         return int(lib().orc_step_draw(ptr, ctypes.c_uint32(block), ctypes.c_uint32(word)))
+
+
+def full_default_config(**overrides) -> FullConfig:
+    cfg = FullConfig()
+    lib().cf_default_config(ctypes.byref(cfg))
+    for k, v in overrides.items():
+        setattr(cfg, k, v)
+    return cfg
+
+
+class FullOracle:
+    """n independent full-Craftax environments stepped serially on the host."""
+
+    def __init__(self, n: int, cfg: FullConfig | None = None, obs_mode: int = FULL_OBS_U8_F32):
+        self.n = n
+        self.cfg = cfg if cfg is not None else full_default_config()
+        self.obs_mode = obs_mode
+        self.envs = np.zeros(n, dtype=FULL_ENV_DTYPE)
+        self.obs = np.zeros((n, FULL_OBS_BYTES[obs_mode]), np.uint8)
+        self.reward = np.zeros(n, np.float32)
+        self.done = np.zeros(n, np.uint8)
+
+    def _ptr(self, i: int):
+        return ctypes.c_void_p(self.envs.ctypes.data + i * FULL_ENV_DTYPE.itemsize)
+
+    def reset(self, seeds, env_ids=None):
+        seeds = np.ascontiguousarray(seeds, dtype=np.uint64)
+        ids = None if env_ids is None else np.ascontiguousarray(env_ids, dtype=np.uint32)
+        lib().cf_reset_batch(_p(self.envs), ctypes.byref(self.cfg), _p(seeds),
+                             None if ids is None else _p(ids), self.n)
+        return self.observe()
+
+    def observe(self):
+        lib().cf_observe_batch(_p(self.envs), ctypes.byref(self.cfg), self.obs_mode, _p(self.obs), self.n)
+        return self.obs
+
+    def step(self, actions, render: bool = True):
+        a = np.ascontiguousarray(actions, dtype=np.int32)
+        assert a.shape == (self.n,)
+        lib().cf_step_batch(_p(self.envs), ctypes.byref(self.cfg), _p(a), self.obs_mode,
+                            _p(self.obs) if render else None, _p(self.reward), _p(self.done), self.n)
+        return self.obs, self.reward, self.done
+
+    def step_rules_one(self, i: int, action: int):
+        r = ctypes.c_float()
+        d = ctypes.c_uint8()
+        lib().cf_step_rules(self._ptr(i), ctypes.byref(self.cfg), ctypes.c_int32(action),
+                            ctypes.byref(r), ctypes.byref(d))
+        return r.value, d.value
+
+    def observe_one(self, i: int, mode: int | None = None) -> np.ndarray:
+        mode = self.obs_mode if mode is None else mode
+        out = np.zeros(FULL_OBS_BYTES[mode], np.uint8)
+        lib().cf_observe(self._ptr(i), ctypes.byref(self.cfg), mode, _p(out))
+        return out
+
+    def draw(self, i: int, block: int, word: int) -> int:
+        return int(lib().cf_step_draw(self._ptr(i), ctypes.c_uint32(block), ctypes.c_uint32(word)))

@@ -1,0 +1,751 @@
+"""Pins for the full-Craftax CPU oracle: the paper's tables, closed forms, invariants and
+hand-traced scenes.  None of these call the GPU library."""
+from __future__ import annotations
+
+import collections
+import os
+
+import numpy as np
+import pytest
+
+from oracle import pyoracle as po
+from paper_2402_16801_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+# ids of the paper's tables (appendix "Action Space", "Block Types"), typed here independently
+A = {n: i for i, n in enumerate(
+    "NOOP LEFT RIGHT UP DOWN DO SLEEP PLACE_STONE PLACE_TABLE PLACE_FURNACE PLACE_PLANT MAKE_WOOD_PICKAXE "
+    "MAKE_STONE_PICKAXE MAKE_IRON_PICKAXE MAKE_WOOD_SWORD MAKE_STONE_SWORD MAKE_IRON_SWORD REST DESCEND ASCEND "
+    "MAKE_DIAMOND_PICKAXE MAKE_DIAMOND_SWORD MAKE_IRON_ARMOUR MAKE_DIAMOND_ARMOUR SHOOT_ARROW MAKE_ARROW "
+    "CAST_FIREBALL CAST_ICEBALL PLACE_TORCH DRINK_POTION_RED DRINK_POTION_GREEN DRINK_POTION_BLUE "
+    "DRINK_POTION_PINK DRINK_POTION_CYAN DRINK_POTION_YELLOW READ_BOOK ENCHANT_SWORD ENCHANT_ARMOUR MAKE_TORCH "
+    "LEVEL_UP_DEXTERITY LEVEL_UP_STRENGTH LEVEL_UP_INTELLIGENCE ENCHANT_BOW".split())}
+B = {n: i for i, n in enumerate(
+    "INVALID OOB GRASS WATER STONE TREE WOOD PATH COAL IRON DIAMOND TABLE FURNACE SAND LAVA PLANT RIPE WALL "
+    "DARKNESS WALL_MOSS STALAGMITE SAPPHIRE RUBY CHEST FOUNTAIN FIRE_GRASS ICE_GRASS GRAVEL FIRE_TREE ICE_SHRUB "
+    "ENCH_FIRE ENCH_ICE NECROMANCER GRAVE1 GRAVE2 GRAVE3 NECRO_VULN".split())}
+WALKABLE = {B["GRASS"], B["SAND"], B["PATH"], B["FIRE_GRASS"], B["ICE_GRASS"], B["GRAVEL"]}
+I_WOOD, I_STONE, I_COAL, I_IRON, I_DIAMOND, I_SAPPHIRE, I_RUBY, I_SAPLING, I_TORCH, I_ARROW = range(10)
+HEALTH, FOOD, DRINK, ENERGY, MANA = range(5)
+CREATURES = ("Zombie Skeleton Cow Orc_Soldier Orc_Mage Snail Gnome_Warrior Gnome_Archer Bat Lizard Kobold Knight "
+             "Archer Troll Deep_Thing Pig_Man Fire_Elemental Frost_Troll Ice_Elemental").split()
+C = {n: i for i, n in enumerate(CREATURES)}
+
+
+def read_golden(name):
+    rows = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                rows.append(line.split())
+    return rows
+
+
+ACH = {r[1]: int(r[0]) for r in read_golden("craftax_achievements.txt")}
+
+
+def has(env, name):
+    i = ACH[name]
+    return bool(int(env["ach"][i >> 5]) >> (i & 31) & 1)
+
+
+QUIET = dict(cap_melee=0, cap_ranged=0, cap_passive=0)      # no spawning: scenes place their own mobs
+
+
+def fresh(n=1, seed=7, **cfg):
+    o = po.FullOracle(n, po.full_default_config(**cfg))
+    o.reset(synth.seeds_for(n, seed))
+    return o
+
+
+def arena(o, i=0, floor=0, fill="PATH", light=20):
+    """Flatten one floor of env i to a single walkable block, remove mobs, centre the player."""
+    e = o.envs[i]
+    e["block"][floor] = B[fill]
+    e["item"][floor] = 0
+    e["light"][floor] = light
+    e["mob"][floor] = np.zeros(14, po.FULL_MOB_DTYPE)
+    e["floor"] = floor
+    e["px"], e["py"], e["dir"] = 24, 24, 2          # facing right: target cell (25, 24)
+    return e
+
+
+def put_mob(e, floor, slot, x, y, creature, hp=None, cd=0, direction=0):
+    m = e["mob"][floor][slot]
+    m["alive"], m["x"], m["y"], m["dir"], m["cd"], m["type"] = 1, x, y, direction, cd, creature
+    m["hp"] = po.lib().cf_creature(creature, 0) if hp is None else hp
+
+
+# ---- the paper's tables ----------------------------------------------------------------------
+def test_achievement_rewards_match_table_and_sum_to_226():
+    rows = read_golden("craftax_achievements.txt")
+    assert [int(r[0]) for r in rows] == list(range(67))
+    for i, _, rew in rows:
+        assert po.lib().cf_achievement_reward(int(i)) == int(rew)
+    assert sum(po.lib().cf_achievement_reward(i) for i in range(67)) == 226      # section "Craftax-1B"
+    assert po.lib().cf_achievement_reward(67) == 0 and po.lib().cf_achievement_reward(-1) == 0
+    assert collections.Counter(int(r[2]) for r in rows) == {1: 25, 3: 18, 5: 15, 8: 9}
+
+
+def test_creature_table_matches_paper():
+    rows = read_golden("craftax_creatures.txt")
+    assert [r[0] for r in rows] == CREATURES
+    col = {"ground": 0, "flying": 1, "amphibian": 2, "aquatic": 3}
+    for i, r in enumerate(rows):
+        want = [int(v) for v in r[2:9]] + [col[r[9]]]
+        got = [po.lib().cf_creature(i, f) for f in range(8)]
+        assert got == want, r[0]
+    assert po.lib().cf_creature(19, 0) == -1
+
+
+def test_observation_length_is_8268():
+    assert 9 * 11 * (37 + 5 + 40 + 1) + 51 == 8268            # section "RL Environment Interface"
+    assert po.FULL_OBS_BYTES[po.FULL_OBS_F32] >= 8268 * 4
+    assert po.FULL_OBS_BYTES[po.FULL_OBS_U8_F32] >= 99 * 83 + 51 * 4
+    assert all(v % 128 == 0 for v in po.FULL_OBS_BYTES.values())
+
+
+# ---- observation --------------------------------------------------------------------------------
+def split_f32(obs_bytes):
+    v = obs_bytes[: 8268 * 4].view(np.float32)
+    return v[: 99 * 83].reshape(9, 11, 83), v[99 * 83:]
+
+
+def test_fresh_observation_structure_and_scalars():
+    o = fresh(3)
+    for i in range(3):
+        cells, vec = split_f32(o.observe_one(i, po.FULL_OBS_F32))
+        assert np.all(cells[..., :37].sum(-1) == 1) and np.all(cells[..., 37:42].sum(-1) == 1)
+        assert np.all(cells[..., 42:82] == 0)
+        assert np.all(cells[..., 82] == 1.0)
+        assert cells[4, 5, B["GRASS"]] == 1                    # cleared start area under the player
+        want = np.zeros(51, np.float32)
+        want[30:35] = np.float32(0.9)                          # health food drink energy mana = 9
+        want[36:39] = np.float32(0.1)                          # dexterity strength intelligence = 1
+        want[42] = 1                                           # facing down
+        want[43] = 1                                           # noon
+        want[49] = 1                                           # floor 0 counts as cleared
+        want[50] = 1                                           # boss vulnerable
+        assert np.array_equal(vec, want)
+        # byte layout carries the same information
+        u8 = o.observe_one(i, po.FULL_OBS_U8_F32)
+        c8 = u8[: 99 * 83].reshape(9, 11, 83)
+        assert np.array_equal(c8[..., :82].astype(np.float32), cells[..., :82])
+        assert np.all(c8[..., 82] == 20)
+        assert np.array_equal(u8[8224: 8224 + 204].view(np.float32), vec)
+        assert not u8[8217:8224].any() and not u8[8428:].any()
+
+
+def test_scalar_scalings_follow_the_inventory_table():
+    o = fresh()
+    e = o.envs[0]
+    e["inv"] = [4, 9, 16, 25, 36, 49, 64, 81, 99, 1]
+    e["potion"] = [0, 1, 2, 3, 4, 5]
+    e["book"], e["pickaxe"], e["sword"], e["sword_ench"], e["bow"], e["bow_ench"] = 1, 3, 4, 2, 1, 1
+    e["armour"], e["armour_ench"] = [0, 1, 2, 2], [0, 1, 2, 0]
+    e["vit"] = [14, 17, 3, 0, 21]
+    e["xp"], e["dex"], e["str"], e["intel"] = 8, 5, 2, 3
+    e["dir"], e["sleeping"], e["resting"], e["learned_fireball"], e["learned_iceball"] = 1, 1, 0, 1, 0
+    e["floor"], e["boss_vulnerable"] = 0, 0
+    _, vec = split_f32(o.observe_one(0, po.FULL_OBS_F32))
+    f = np.float32
+    want = [f(np.sqrt(float(n)) / 10.0) for n in [4, 9, 16, 25, 36, 49, 64, 81, 99, 1]]
+    want += [f(np.sqrt(float(n)) / 10.0) for n in range(6)]
+    want += [f(0.5), f(0.75), f(1.0), f(2), f(1), f(1)]
+    want += [f(0), f(0.5), f(1), f(1)] + [f(0), f(1), f(2), f(0)]
+    want += [f(1.4), f(1.7), f(0.3), f(0.0), f(2.1)]
+    want += [f(0.8), f(0.5), f(0.2), f(0.3)]
+    want += [f(1), f(0), f(0), f(0)] + [f(1.0), f(1), f(0), f(1), f(0), f(0.0), f(1), f(0)]
+    assert np.array_equal(vec, np.array(want, np.float32))
+
+
+def test_dark_cells_are_masked_and_torches_light_them():
+    o = fresh()
+    e = arena(o, floor=2, light=0)
+    e["inv"][I_TORCH] = 2
+    cells, _ = split_f32(o.observe_one(0, po.FULL_OBS_F32))
+    assert not cells.any()                                    # everything below light 0.05 is hidden
+    r, d = o.step_rules_one(0, A["PLACE_TORCH"])
+    assert e["item"][2][24, 25] == 1 and e["inv"][I_TORCH] == 1 and has(e, "PLACE_TORCH") and r == pytest.approx(1.0)
+    yy, xx = np.mgrid[0:48, 0:48]
+    want = np.maximum(0, 20 - 4 * np.maximum(abs(xx - 25), abs(yy - 24)))
+    assert np.array_equal(e["light"][2], want)
+    cells, _ = split_f32(o.observe_one(0, po.FULL_OBS_F32))
+    vis = want[20:29, 19:30] > 0
+    assert np.array_equal(cells[..., 82], (want[20:29, 19:30] / 20.0).astype(np.float32))
+    assert np.array_equal(cells[..., :37].sum(-1) == 1, vis) and np.array_equal(cells[..., 37:42].sum(-1) == 1, vis)
+    assert cells[4, 6, 38] == 1                               # the torch item in front of the player
+    # a second torch two cells further only ever raises light
+    e["px"] = 27
+    o.step_rules_one(0, A["PLACE_TORCH"])
+    want2 = np.maximum(want, np.maximum(0, 20 - 4 * np.maximum(abs(xx - 28), abs(yy - 24))))
+    assert np.array_equal(e["light"][2], want2)
+
+
+def test_creature_channels_and_view_edges():
+    o = fresh()
+    e = arena(o, floor=0, fill="GRASS")
+    e["px"], e["py"] = 2, 1
+    put_mob(e, 0, 0, 3, 1, C["Zombie"])
+    put_mob(e, 0, 3, 2, 3, C["Skeleton"])
+    put_mob(e, 0, 5, 4, 2, C["Cow"])
+    put_mob(e, 0, 8, 5, 1, C["Skeleton"], hp=0, direction=2)
+    put_mob(e, 0, 11, 1, 1, 1, hp=0, direction=1)               # a fireball of the player
+    cells, _ = split_f32(o.observe_one(0, po.FULL_OBS_F32))
+    # view rows are y-4..y+4, columns x-5..x+5
+    assert np.all(cells[:3, :, B["OOB"]] == 1) and np.all(cells[:, :3, B["OOB"]] == 1)
+    assert cells[3, 3, B["GRASS"]] == 1                        # map cell (0, 0)
+    assert cells[4, 6, 42 + 0] == 1                            # zombie: melee class, type slot 0
+    assert cells[6, 5, 42 + 16 + 0] == 1                       # skeleton: ranged class
+    assert cells[5, 7, 42 + 8 + 0] == 1                        # cow: passive class
+    assert cells[4, 8, 42 + 24 + 0] == 1                       # physical mob projectile
+    assert cells[4, 4, 42 + 32 + 1] == 1                       # fireball
+    assert cells[..., 42:82].sum() == 5
+
+
+# ---- world generation ---------------------------------------------------------------------------
+def reachable(block, start):
+    seen = np.zeros((48, 48), bool)
+    todo = [start]
+    seen[start[1], start[0]] = True
+    while todo:
+        x, y = todo.pop()
+        for dx, dy in ((1, 0), (-1, 0), (0, 1), (0, -1)):
+            nx, ny = x + dx, y + dy
+            if 0 <= nx < 48 and 0 <= ny < 48 and not seen[ny, nx] and int(block[ny, nx]) in WALKABLE:
+                seen[ny, nx] = True
+                todo.append((nx, ny))
+    return seen
+
+
+def test_worldgen_floors_structure_and_ladder_connectivity():
+    n = 48
+    o = fresh(n, seed=100)
+    allowed = {
+        0: {"GRASS", "WATER", "STONE", "TREE", "PATH", "COAL", "IRON", "DIAMOND", "SAND", "LAVA"},
+        1: {"WALL", "PATH", "CHEST", "FOUNTAIN"},
+        2: {"PATH", "STONE", "STALAGMITE", "COAL", "IRON", "DIAMOND", "SAPPHIRE", "RUBY"},
+        3: {"WALL_MOSS", "PATH", "WATER", "CHEST"},
+        4: {"WALL", "PATH", "CHEST", "ENCH_FIRE", "ENCH_ICE"},
+        5: {"PATH", "STONE", "WATER", "COAL", "IRON", "DIAMOND", "SAPPHIRE", "RUBY"},
+        6: {"FIRE_GRASS", "STONE", "LAVA", "FIRE_TREE", "RUBY", "COAL", "PATH"},
+        7: {"ICE_GRASS", "STONE", "WATER", "ICE_SHRUB", "SAPPHIRE", "DIAMOND", "PATH"},
+        8: {"WALL", "PATH", "GRAVE1", "GRAVE2", "GRAVE3", "NECRO_VULN"},
+    }
+    seen_blocks = collections.defaultdict(set)
+    for i in range(n):
+        e = o.envs[i]
+        for f in range(9):
+            blk, item, light = e["block"][f], e["item"][f], e["light"][f]
+            ids = set(np.unique(blk).tolist())
+            assert ids <= {B[k] for k in allowed[f]}, (i, f, ids)
+            seen_blocks[f] |= ids
+            assert np.all(light == (0 if f in (2, 5, 7, 8) else 20))          # dark floors 2, 5, 7, 8
+            counts = np.bincount(item.ravel(), minlength=5)
+            assert counts[1] == 0
+            assert counts[3] == (1 if f > 0 else 0)
+            assert counts[2] == (1 if f == 0 else 0) and counts[4] == (1 if 0 < f < 8 else 0)
+            if f > 0:
+                ux, uy = e["ladder_up"][f]
+                assert item[uy, ux] == 3 and blk[uy, ux] == B["PATH"]
+            if f < 8:
+                dx, dy = e["ladder_down"][f]
+                assert item[dy, dx] == (2 if f == 0 else 4) and blk[dy, dx] == B["PATH"]
+            if 0 < f < 8:
+                assert reachable(blk, (int(ux), int(uy)))[dy, dx], (i, f)
+        assert np.all(e["block"][0][22:27, 22:27] == B["GRASS"])
+        assert (e["px"], e["py"], e["floor"]) == (24, 24, 0)
+        assert e["block"][8][6, 24] == B["NECRO_VULN"] and (e["block"][8] >= B["GRAVE1"]).sum() == 16
+        assert (e["block"][4] == B["ENCH_FIRE"]).sum() <= 1 and (e["block"][1] == B["CHEST"]).sum() >= 1
+    for f in range(9):
+        assert seen_blocks[f] == {B[k] for k in allowed[f]} - ({B["PATH"]} if f in (6, 7) and B["PATH"] not in seen_blocks[f] else set()), f
+
+
+def test_worldgen_is_a_pure_function_of_seed_env_episode():
+    o = fresh(4, seed=5)
+    p = fresh(4, seed=5)
+    assert o.envs.tobytes() == p.envs.tobytes()
+    q = po.FullOracle(1)
+    q.reset(np.array([6], np.uint64), env_ids=np.array([1], np.uint32))       # same (seed, env) as o.envs[1]
+    assert q.envs[0].tobytes() == o.envs[1].tobytes()
+    r = po.FullOracle(1)
+    r.reset(np.array([6], np.uint64), env_ids=np.array([2], np.uint32))
+    assert not np.array_equal(r.envs[0]["block"], o.envs[1]["block"])
+    # episode index re-draws the world and the potion map
+    e = o.envs[0]
+    before = e["block"].copy()
+    e["vit"][HEALTH] = 1
+    e["cnt"][3] = -30
+    e["vit"][FOOD] = 0
+    _, _, d = o.step(np.zeros(4, np.int32))
+    assert d[0] == 1 and e["episode"] == 1 and e["t"] == 0 and not np.array_equal(before, e["block"])
+
+
+def test_potion_map_is_a_permutation_that_varies():
+    o = fresh(64, seed=11)
+    perms = {tuple(e["potion_effect"].tolist()) for e in o.envs}
+    assert all(sorted(p) == list(range(6)) for p in perms) and len(perms) > 20
+
+
+# ---- rules: hand-traced scenes -----------------------------------------------------------------
+def test_every_unmet_prerequisite_is_a_noop():
+    o = fresh(2, seed=3)
+    base = o.envs[0].copy()
+    ref = o.envs[0:1].copy()
+    tmp = po.FullOracle(1)
+    tmp.envs[:] = ref
+    tmp.step_rules_one(0, A["NOOP"])
+    want = tmp.envs[0].tobytes()
+    idle = [a for n, a in A.items() if n.startswith(("PLACE_", "MAKE_", "DRINK_", "ENCHANT_", "LEVEL_UP", "CAST_"))]
+    idle += [A["SHOOT_ARROW"], A["READ_BOOK"], A["DESCEND"], A["ASCEND"], A["SLEEP"], A["REST"], 43, -1, 1000]
+    for a in idle:
+        tmp.envs[0] = base
+        r, d = tmp.step_rules_one(0, a)
+        assert tmp.envs[0].tobytes() == want, a
+        assert r == 0.0 and d == 0
+
+
+def test_ladders_experience_and_floor_achievements():
+    o = fresh(**QUIET)
+    e = o.envs[0]
+    e["px"], e["py"] = e["ladder_down"][0]
+    r, _ = o.step_rules_one(0, A["DESCEND"])
+    assert e["floor"] == 1 and (e["px"], e["py"]) == tuple(e["ladder_up"][1]) and e["xp"] == 1
+    assert has(e, "ENTER_DUNGEON") and r == pytest.approx(3.0)
+    r, _ = o.step_rules_one(0, A["DESCEND"])                   # not on a ladder down
+    assert e["floor"] == 1 and r == 0.0
+    r, _ = o.step_rules_one(0, A["ASCEND"])
+    assert e["floor"] == 0 and (e["px"], e["py"]) == tuple(e["ladder_down"][0]) and e["xp"] == 1 and r == 0.0
+    o.step_rules_one(0, A["DESCEND"])
+    assert e["floor"] == 1 and e["xp"] == 1                    # experience only the first time
+    # the way further down is blocked until 8 kills on this floor
+    e["mob"][1] = np.zeros(14, po.FULL_MOB_DTYPE)
+    e["px"], e["py"] = e["ladder_down"][1]
+    o.step_rules_one(0, A["DESCEND"])
+    assert e["floor"] == 1
+    e["kills"][1] = 7
+    e["px"], e["py"], e["dir"] = e["ladder_up"][1][0], e["ladder_up"][1][1], 2
+    e["block"][1][e["py"], e["px"] + 1] = B["PATH"]
+    put_mob(e, 1, 0, e["px"] + 1, e["py"], C["Orc_Soldier"], hp=1, cd=5)
+    r, _ = o.step_rules_one(0, A["DO"])
+    dx, dy = e["ladder_down"][1]
+    assert e["kills"][1] == 8 and e["item"][1][dy, dx] == 2 and has(e, "DEFEAT_ORC_SOLIDER") and r == pytest.approx(3.0)
+    e["mob"][1] = np.zeros(14, po.FULL_MOB_DTYPE)
+    e["px"], e["py"] = dx, dy
+    r, _ = o.step_rules_one(0, A["DESCEND"])
+    assert e["floor"] == 2 and e["xp"] == 2 and has(e, "ENTER_GNOMISH_MINES") and r == pytest.approx(3.0)
+    # a mob on the far end of the ladder blocks the way back
+    ux, uy = e["ladder_down"][1]
+    put_mob(e, 1, 6, ux, uy, C["Snail"])
+    e["mob"][2] = np.zeros(14, po.FULL_MOB_DTYPE)
+    o.step_rules_one(0, A["ASCEND"])
+    assert e["floor"] == 2
+    # spending experience
+    for name, fld in (("LEVEL_UP_DEXTERITY", "dex"), ("LEVEL_UP_STRENGTH", "str")):
+        o.step_rules_one(0, A[name])
+        assert e[fld] == 2
+    o.step_rules_one(0, A["LEVEL_UP_INTELLIGENCE"])
+    assert e["intel"] == 1 and e["xp"] == 0
+
+
+def hit(o, e, creature, **player):
+    """hp left on a fresh creature in front of the player after one DO"""
+    e["mob"][e["floor"]] = np.zeros(14, po.FULL_MOB_DTYPE)
+    for k, v in player.items():
+        e[k] = v
+    put_mob(e, int(e["floor"]), 0, 25, 24, creature, cd=5)
+    o.step_rules_one(0, A["DO"])
+    m = e["mob"][e["floor"]][0]
+    return int(m["hp"]) if m["alive"] else 0
+
+
+def test_three_element_damage_against_creature_defence():
+    o = fresh(**QUIET)
+    e = arena(o, floor=4)
+    e["cnt"][:] = 0
+    assert hit(o, e, C["Knight"], sword=0) == 12               # 1 * 50 % = 0
+    assert hit(o, e, C["Knight"], sword=3) == 10               # 5 * 50 % = 2
+    assert hit(o, e, C["Knight"], sword=4) == 8                # 8 * 50 % = 4
+    assert hit(o, e, C["Knight"], sword=3, str=5) == 8         # (5 + 4) * 50 % = 4
+    assert hit(o, e, C["Knight"], sword=3, str=1, sword_ench=1) == 6   # + 4 fire, no fire defence
+    assert hit(o, e, C["Pig_Man"], sword=4, sword_ench=1) == 20        # 8 * 10 % = 0, fire immune
+    assert hit(o, e, C["Pig_Man"], sword=4, sword_ench=2) == 16        # 4 ice
+    assert hit(o, e, C["Frost_Troll"], sword=4, sword_ench=2) == 24
+    assert hit(o, e, C["Troll"], sword=2, sword_ench=0) == 18          # 3 * 80 % = 2
+    assert hit(o, e, C["Zombie"], sword=1) == 3
+
+
+def test_damage_to_player_through_armour():
+    o = fresh(**QUIET)
+    e = arena(o, floor=5)
+
+    def taken(creature, sleeping=0, **player):
+        e["mob"][5] = np.zeros(14, po.FULL_MOB_DTYPE)
+        e["vit"] = [14, 9, 9, 9, 9]
+        e["str"] = 5
+        e["cnt"][:] = 0
+        e["sleeping"] = sleeping
+        for k, v in player.items():
+            e[k] = v
+        put_mob(e, 5, 0, 25, 24, creature)
+        r, _ = o.step_rules_one(0, A["NOOP"])
+        assert e["mob"][5][0]["cd"] == 5
+        woke = 1.0 if sleeping else 0.0                          # WAKE_UP is a basic achievement
+        assert r == pytest.approx(woke - 0.1 * (14 - e["vit"][HEALTH]))
+        return 14 - int(e["vit"][HEALTH])
+
+    assert taken(C["Troll"], armour=[0, 0, 0, 0], armour_ench=[0, 0, 0, 0]) == 8          # 6 + 1 + 1
+    assert taken(C["Troll"], armour=[2, 2, 2, 2]) == 3                                    # 6 * 20 % = 1, + 1 + 1
+    assert taken(C["Troll"], armour=[1, 1, 0, 0]) == 6                                    # 6 * 80 % = 4
+    assert taken(C["Troll"], armour=[2, 2, 2, 2], armour_ench=[1, 1, 1, 1, ]) == 2        # fire 1 * 20 % = 0
+    assert taken(C["Troll"], armour=[0, 0, 0, 0], armour_ench=[0, 0, 0, 0], sleeping=1) == 14   # doubled, clamped at 0
+    assert e["sleeping"] == 0 and has(e, "WAKE_UP")
+    assert taken(C["Frost_Troll"], armour=[2, 2, 2, 2], armour_ench=[2, 2, 2, 0]) == 2    # 4 * 20 % = 0, 5 * 40 % = 2
+
+
+def test_crafting_recipes_and_conservation():
+    o = fresh(**QUIET)
+    e = arena(o, floor=0, fill="GRASS")
+    e["block"][0][23, 23], e["block"][0][25, 25] = B["TABLE"], B["FURNACE"]
+    e["inv"] = [20, 20, 20, 20, 20, 0, 0, 0, 0, 0]
+    steps = [("MAKE_ARROW", {I_WOOD: -1, I_STONE: -1, I_ARROW: +2}, "MAKE_ARROW"),
+             ("MAKE_TORCH", {I_WOOD: -1, I_COAL: -1, I_TORCH: +4}, "MAKE_TORCH"),
+             ("MAKE_IRON_ARMOUR", {I_IRON: -3, I_COAL: -3}, "MAKE_IRON_ARMOUR"),
+             ("MAKE_DIAMOND_ARMOUR", {I_DIAMOND: -3}, "MAKE_DIAMOND_ARMOUR"),
+             ("MAKE_DIAMOND_PICKAXE", {I_WOOD: -1, I_DIAMOND: -3}, "MAKE_DIAMOND_PICKAXE"),
+             ("MAKE_DIAMOND_SWORD", {I_WOOD: -1, I_DIAMOND: -2}, "MAKE_DIAMOND_SWORD"),
+             ("MAKE_IRON_PICKAXE", {}, None),                     # already better than iron: nothing happens
+             ("MAKE_WOOD_SWORD", {}, None)]
+    for name, delta, ach in steps:
+        before = e["inv"].astype(int).copy()
+        r, _ = o.step_rules_one(0, A[name])
+        want = before.copy()
+        for k, v in delta.items():
+            want[k] += v
+        assert np.array_equal(e["inv"], want), name
+        if ach:
+            assert has(e, ach) and r == pytest.approx(float(po.lib().cf_achievement_reward(ACH[ach]))), name
+        else:
+            assert r == 0.0
+    assert e["pickaxe"] == 4 and e["sword"] == 4
+    assert e["armour"].tolist() == [2, 0, 0, 0]                 # iron piece 0, then diamond upgrades the first piece below 2
+    for _ in range(5):
+        o.step_rules_one(0, A["MAKE_IRON_ARMOUR"])
+    assert e["armour"].tolist() == [2, 1, 1, 1] and e["inv"][I_IRON] == 20 - 3 * 4
+    # without the furnace nothing that needs one works
+    e["block"][0][25, 25] = B["GRASS"]
+    before = e.copy()
+    o.step_rules_one(0, A["MAKE_DIAMOND_ARMOUR"])
+    assert np.array_equal(e["inv"], before["inv"]) and np.array_equal(e["armour"], before["armour"])
+
+
+def test_mining_needs_the_pickaxe_level():
+    o = fresh(**QUIET)
+    e = arena(o, floor=2)
+    gates = [("STONE", 1, I_STONE, "COLLECT_STONE"), ("STALAGMITE", 1, I_STONE, None), ("COAL", 1, I_COAL, "COLLECT_COAL"),
+             ("IRON", 2, I_IRON, "COLLECT_IRON"), ("DIAMOND", 3, I_DIAMOND, "COLLECT_DIAMOND"),
+             ("SAPPHIRE", 4, I_SAPPHIRE, "COLLECT_SAPPHIRE"), ("RUBY", 4, I_RUBY, "COLLECT_RUBY")]
+    for name, level, item, ach in gates:
+        for have in range(5):
+            e["block"][2][24, 25] = B[name]
+            e["pickaxe"] = have
+            e["inv"][:] = 0
+            e["ach"][:] = 0
+            e["mob"][2] = np.zeros(14, po.FULL_MOB_DTYPE)        # nothing spawned earlier may interfere
+            e["vit"][:] = 9
+            e["cnt"][:] = 0
+            r, _ = o.step_rules_one(0, A["DO"])
+            if have >= level:
+                assert e["inv"][item] == 1 and e["block"][2][24, 25] == B["PATH"], (name, have)
+                if ach:
+                    assert has(e, ach) and r == pytest.approx(float(po.lib().cf_achievement_reward(ACH[ach])))
+            else:
+                assert e["inv"][item] == 0 and e["block"][2][24, 25] == B[name] and r == 0.0, (name, have)
+    e["block"][2][24, 25] = B["STONE"]
+    e["inv"][I_STONE] = 99
+    o.step_rules_one(0, A["DO"])
+    assert e["inv"][I_STONE] == 99 and e["block"][2][24, 25] == B["STONE"]     # a full stack leaves the block
+
+
+def test_chest_bow_potions_books_and_spells():
+    o = fresh(**QUIET)
+    e = arena(o, floor=1)
+    e["block"][1][24, 25] = B["CHEST"]
+    r, _ = o.step_rules_one(0, A["DO"])
+    assert e["bow"] == 1 and has(e, "OPEN_CHEST") and has(e, "FIND_BOW") and r == pytest.approx(6.0)
+    assert e["block"][1][24, 25] == B["PATH"] and e["potion"].sum() == 0
+    got_books = 0
+    for _ in range(40):                                        # later chests: always a potion, sometimes more
+        e["block"][1][24, 25] = B["CHEST"]
+        before = (e["potion"].astype(int).sum(), int(e["book"]), int(e["inv"][I_ARROW]), int(e["inv"][I_TORCH]))
+        u0, u1 = o.draw(0, 10, 3), o.draw(0, 11, 3)
+        o.step_rules_one(0, A["DO"])
+        assert e["potion"].astype(int).sum() == before[0] + 1
+        kind = (u1 * 4) >> 32
+        assert e["potion"][(u0 * 6) >> 32] >= 1
+        assert e["inv"][I_ARROW] == before[2] + (4 if kind == 0 else 0)
+        assert e["inv"][I_TORCH] == before[3] + (4 if kind == 1 else 0)
+        assert e["book"] == min(2, before[1] + (1 if kind == 2 else 0))
+        got_books = int(e["book"])
+    assert got_books == 2
+    r, _ = o.step_rules_one(0, A["READ_BOOK"])
+    assert e["learned_fireball"] == 1 and e["learned_iceball"] == 0 and e["book"] == 1 and r == pytest.approx(5.0)
+    r, _ = o.step_rules_one(0, A["READ_BOOK"])
+    assert e["learned_iceball"] == 1 and e["book"] == 0 and has(e, "LEARN_ICEBALL")
+    # fireball: costs 2 mana, flies one cell per step, hurts by 4 + 2 (INT - 1) fire
+    e["mob"][1] = np.zeros(14, po.FULL_MOB_DTYPE)
+    e["vit"][MANA] = 9
+    e["cnt"][:] = 0
+    # a snail that cannot move: water in front (projectiles cross it), stone elsewhere
+    e["block"][1][24, 27] = B["WATER"]
+    e["block"][1][24, 29] = e["block"][1][23, 28] = e["block"][1][25, 28] = B["STONE"]
+    put_mob(e, 1, 5, 28, 24, C["Snail"])                         # 6 hp
+    r, _ = o.step_rules_one(0, A["CAST_FIREBALL"])
+    assert e["vit"][MANA] == 7 and has(e, "CAST_FIREBALL") and r == pytest.approx(5.0)
+    p = e["mob"][1][11]
+    assert p["alive"] == 1 and p["type"] == 1 and p["dir"] == 2 and (p["x"], p["y"]) == (26, 24)   # flew one cell already
+    o.step_rules_one(0, A["NOOP"])
+    assert (e["mob"][1][11]["x"], e["mob"][1][5]["hp"]) == (27, 6)
+    o.step_rules_one(0, A["NOOP"])
+    m = e["mob"][1][5]
+    assert (m["alive"] == 1 and m["hp"] == 2) and e["mob"][1][11]["alive"] == 0
+    e["intel"] = 3                                               # 4 + 2 * 2 = 8 fire kills it; eating a snail
+    e["vit"][FOOD] = 3
+    o.step_rules_one(0, A["CAST_FIREBALL"])
+    o.step_rules_one(0, A["NOOP"])
+    r, _ = o.step_rules_one(0, A["NOOP"])
+    assert e["mob"][1][5]["alive"] == 0 and has(e, "EAT_SNAIL") and e["vit"][FOOD] == 9 and r == pytest.approx(3.0)
+    assert e["kills"][1] == 0                                    # passive creatures do not count as kills
+    e["vit"][MANA] = 1
+    r, _ = o.step_rules_one(0, A["CAST_ICEBALL"])
+    assert e["vit"][MANA] >= 1 and not has(e, "CAST_ICEBALL")    # not enough mana
+
+
+def test_bow_and_arrows():
+    o = fresh(**QUIET)
+    e = arena(o, floor=0, fill="GRASS")
+    e["bow"], e["dex"] = 1, 3
+    e["inv"][I_ARROW] = 2
+    put_mob(e, 0, 5, 25, 24, C["Cow"])                          # adjacent: hit at once, 2 + (DEX - 1) = 4 >= 3 hp
+    r, _ = o.step_rules_one(0, A["SHOOT_ARROW"])
+    assert e["inv"][I_ARROW] == 1 and has(e, "FIRE_BOW") and has(e, "EAT_COW") and r == pytest.approx(4.0)
+    assert e["mob"][0][5]["alive"] == 0
+    e["block"][0][24, 25] = B["STONE"]                           # blocked: no arrow is spent
+    o.step_rules_one(0, A["SHOOT_ARROW"])
+    assert e["inv"][I_ARROW] == 1 and e["mob"][0][11:14]["alive"].sum() == 0
+    e["block"][0][24, 25] = B["WATER"]                           # arrows fly over water
+    o.step_rules_one(0, A["SHOOT_ARROW"])
+    assert e["inv"][I_ARROW] == 0
+
+
+def test_potions_apply_the_episode_permutation():
+    o = fresh(**QUIET)
+    e = arena(o)
+    caps = {0: (HEALTH, 9), 1: (MANA, 9), 2: (ENERGY, 9)}
+    for colour in range(6):
+        e["potion"][:] = 1
+        e["vit"] = [5, 9, 9, 5, 5]
+        e["cnt"][:] = 0
+        eff = int(e["potion_effect"][colour])
+        r, _ = o.step_rules_one(0, A["DRINK_POTION_RED"] + colour)
+        vit, cap = caps[eff >> 1]
+        want = min(cap, 5 + 8) if eff % 2 == 0 else 2
+        assert e["vit"][vit] == want and e["potion"][colour] == 0 and has(e, "DRINK_POTION")
+        others = [v for v in (HEALTH, MANA, ENERGY) if v != vit]
+        assert all(e["vit"][v] == 5 for v in others)
+
+
+def test_enchanting_needs_table_mana_and_gem():
+    o = fresh(**QUIET)
+    e = arena(o, floor=4)
+    e["block"][4][24, 25] = B["ENCH_FIRE"]
+    e["sword"], e["bow"] = 2, 1
+    e["armour"] = [1, 0, 2, 0]
+    e["vit"][MANA] = 21
+    e["intel"] = 5
+    e["inv"][I_RUBY], e["inv"][I_SAPPHIRE] = 2, 5
+
+    def act(name):
+        e["cnt"][:] = 0                                          # keep mana regeneration out of the picture
+        return o.step_rules_one(0, A[name])
+
+    r, _ = act("ENCHANT_SWORD")
+    assert e["sword_ench"] == 1 and e["vit"][MANA] == 12 and e["inv"][I_RUBY] == 1 and r == pytest.approx(5.0)
+    r, _ = act("ENCHANT_SWORD")               # same element again: nothing
+    assert e["vit"][MANA] == 12 and e["inv"][I_RUBY] == 1 and r == 0.0
+    r, _ = act("ENCHANT_ARMOUR")
+    assert e["armour_ench"].tolist() == [1, 0, 0, 0] and e["vit"][MANA] == 3 and e["inv"][I_RUBY] == 0 and r == pytest.approx(5.0)
+    e["vit"][MANA] = 21
+    act("ENCHANT_BOW")                        # no ruby left
+    assert e["bow_ench"] == 0 and e["vit"][MANA] == 21
+    e["block"][4][24, 25] = B["ENCH_ICE"]
+    act("ENCHANT_BOW")
+    assert e["bow_ench"] == 2 and e["inv"][I_SAPPHIRE] == 4 and e["vit"][MANA] == 12
+    act("ENCHANT_ARMOUR")
+    assert e["armour_ench"].tolist() == [2, 0, 0, 0] and e["vit"][MANA] == 3
+    act("ENCHANT_ARMOUR")                     # mana below 9
+    assert e["armour_ench"].tolist() == [2, 0, 0, 0]
+
+
+def test_boss_fight_takes_eight_hits_with_waves_between():
+    o = fresh(**QUIET)
+    e = o.envs[0]
+    e["floor"], e["px"], e["py"], e["dir"] = 8, 24, 7, 3         # below the necromancer, facing up
+    e["light"][8] = 20
+    total = 0.0
+    for hitno in range(1, 9):
+        assert e["boss_vulnerable"] == 1 and e["block"][8][6, 24] == B["NECRO_VULN"]
+        r, _ = o.step_rules_one(0, A["DO"])
+        total += r + 0.1 * 0
+        assert e["boss_hits"] == hitno
+        if hitno < 8:
+            assert e["boss_vulnerable"] == 0 and e["block"][8][6, 24] == B["NECROMANCER"]
+            wave = e["mob"][8]
+            assert wave["alive"][:5].sum() >= 4                 # three melee, two ranged (a cell may be taken)
+            want_m = [C["Zombie"], C["Orc_Soldier"], C["Gnome_Warrior"], C["Lizard"], C["Knight"], C["Troll"], C["Pig_Man"]][hitno - 1]
+            assert all(m["type"] == want_m for m in wave[:3] if m["alive"])
+            r2, _ = o.step_rules_one(0, A["DO"])                # invulnerable while the wave lives
+            assert e["boss_hits"] == hitno
+            e["mob"][8] = np.zeros(14, po.FULL_MOB_DTYPE)       # wave gone
+            e["vit"][HEALTH] = 9
+            o.step_rules_one(0, A["NOOP"])
+    assert has(e, "DAMAGE_NECROMANCER") and has(e, "DEFEAT_NECROMANCER") and e["block"][8][6, 24] == B["PATH"]
+    assert e["boss_vulnerable"] == 0
+
+
+def test_ranged_mob_shoots_and_projectile_hits_next_steps():
+    o = fresh(**QUIET)
+    e = arena(o, floor=3)
+    e["cnt"][:] = 0
+    put_mob(e, 3, 3, 27, 24, C["Kobold"])
+    shot = False
+    for _ in range(40):
+        h0 = int(e["vit"][HEALTH])
+        o.step_rules_one(0, A["NOOP"])
+        if e["mob"][3][8:11]["alive"].any():
+            shot = True
+            p = e["mob"][3][8:11][e["mob"][3][8:11]["alive"] == 1][0]
+            assert p["type"] == C["Kobold"] and (p["x"] == e["px"] or p["y"] == e["py"])
+        if int(e["vit"][HEALTH]) < h0:
+            assert h0 - int(e["vit"][HEALTH]) == 4 and shot
+            break
+    else:
+        raise AssertionError("the kobold never hit")
+
+
+def test_collision_types_keep_mobs_on_their_terrain():
+    o = fresh(**QUIET)
+    e = arena(o, floor=5, fill="WATER")
+    e["block"][5][20:29, 20:29] = B["PATH"]
+    e["block"][5][24, 30:40] = B["PATH"]
+    put_mob(e, 5, 3, 10, 10, C["Deep_Thing"])                    # aquatic, in the water
+    put_mob(e, 5, 0, 35, 24, C["Troll"])                         # ground, on a 1-wide causeway
+    put_mob(e, 5, 5, 12, 30, C["Bat"])                           # flying
+    e["vit"][:] = 9
+    for _ in range(300):
+        e["vit"][:] = 9
+        e["cnt"][:] = 0
+        o.step_rules_one(0, A["NOOP"])
+        for s in range(8):
+            m = e["mob"][5][s]
+            if not m["alive"]:
+                continue
+            b = int(e["block"][5][m["y"], m["x"]])
+            col = po.lib().cf_creature(int(m["type"]), 7)
+            if col == 0:
+                assert b in WALKABLE
+            elif col == 3:
+                assert b == B["WATER"]
+            elif col == 2:
+                assert b in WALKABLE or b == B["WATER"]
+
+
+# ---- invariants over random rollouts -----------------------------------------------------------
+def test_random_rollout_invariants():
+    n, steps = 48, 1500
+    o = fresh(n, seed=900)
+    # give some environments a head start underground so that every floor is exercised
+    for i in range(n):
+        e = o.envs[i]
+        f = i % 9
+        if f:
+            e["floor"], e["px"], e["py"] = f, e["ladder_up"][f][0], e["ladder_up"][f][1]
+            e["visited"] = (1 << (f + 1)) - 1
+            e["inv"][:] = 30
+            e["pickaxe"], e["sword"], e["bow"] = 4, 4, 1
+            e["learned_fireball"] = 1
+            e["book"] = 1
+            e["potion"][:] = 3
+            e["armour"] = [2, 2, 1, 1]
+            e["xp"] = 2
+    ach_prev = o.envs["ach"].copy()
+    ep_prev = o.envs["episode"].copy()
+    health_prev = o.envs["vit"][:, HEALTH].astype(int)
+    floors_seen = set()
+    for s in range(steps):
+        a = synth.actions(np.arange(n), s, "skewed", 5, 43)
+        before_xp = o.envs["xp"].astype(int) + o.envs["dex"] + o.envs["str"] + o.envs["intel"]
+        before_vis = np.array([bin(int(v)).count("1") for v in o.envs["visited"]])
+        for i in range(n):
+            r, d = o.step_rules_one(i, int(a[i]))
+            e = o.envs[i]
+            new = [int(e["ach"][w]) & ~int(ach_prev[i][w]) for w in range(3)]
+            assert all(int(ach_prev[i][w]) & ~int(e["ach"][w]) == 0 for w in range(3))     # monotone
+            gained = sum(po.lib().cf_achievement_reward(b) for b in range(67) if new[b >> 5] >> (b & 31) & 1)
+            dh = int(e["vit"][HEALTH]) - health_prev[i]
+            assert r == np.float32(np.float32(10 * gained + dh) * np.float32(0.1))
+            f = int(e["floor"])
+            floors_seen.add(f)
+            assert 0 <= e["px"] < 48 and 0 <= e["py"] < 48 and 1 <= e["dir"] <= 4
+            cells = [(int(e["px"]), int(e["py"]))]
+            mobs = e["mob"][f]
+            for k in range(14):
+                m = mobs[k]
+                if not m["alive"]:
+                    assert m.tobytes() == bytes(8)
+                    continue
+                assert 0 <= m["x"] < 48 and 0 <= m["y"] < 48
+                cells.append((int(m["x"]), int(m["y"])))
+                if k < 8:
+                    assert 0 < m["hp"] <= po.lib().cf_creature(int(m["type"]), 0)
+            assert len(set(cells)) == len(cells), (s, i, cells)
+            assert e["inv"].max() <= 99 and e["potion"].max() <= 99 and e["book"] <= 2
+            assert 0 <= e["vit"][HEALTH] <= 14 and 0 <= e["vit"][MANA] <= 21 and max(e["vit"][1:4]) <= 17 and min(e["vit"]) >= 0
+            vis = bin(int(e["visited"])).count("1")
+            assert int(e["xp"]) + e["dex"] + e["str"] + e["intel"] - before_xp[i] == vis - before_vis[i]
+            assert d == (1 if e["vit"][HEALTH] <= 0 or e["t"] >= 100000 else 0)
+            if d:
+                o.envs[i:i + 1] = _reset_like(o, i)
+        ach_prev = o.envs["ach"].copy()
+        health_prev = o.envs["vit"][:, HEALTH].astype(int)
+    assert floors_seen == set(range(9))
+    assert (o.envs["episode"] > ep_prev).any()
+
+
+def _reset_like(o, i):
+    """what cf_step does after a terminal step: the next episode of the same (seed, env)"""
+    e = o.envs[i]
+    tmp = po.FullOracle(1, o.cfg)
+    tmp.envs[0] = e
+    tmp.envs[0]["vit"][HEALTH] = 0
+    tmp.envs[0]["t"] = 5
+    ep = int(e["episode"])
+    # force a terminal step through the public step (auto-reset)
+    tmp.step(np.zeros(1, np.int32))
+    assert tmp.done[0] == 1 and tmp.envs[0]["episode"] == ep + 1
+    return tmp.envs
+
+
+def test_step_is_rules_plus_reset_and_deterministic():
+    n = 16
+    a = fresh(n, seed=40)
+    b = fresh(n, seed=40)
+    for s in range(400):
+        act = synth.actions(np.arange(n), s, "uniform", 1, 43)
+        _, ra, da = a.step(act)
+        _, rb, db = b.step(act, render=False)
+        assert np.array_equal(ra, rb) and np.array_equal(da, db)
+    assert a.envs.tobytes() == b.envs.tobytes()
+    assert a.envs["episode"].sum() > 0
+    assert np.array_equal(a.obs, b.observe())
