@@ -1,5 +1,5 @@
 /*
- * craftax.h - C ABI of the MI355X (gfx950) batched Craftax-Classic simulator.
+ * craftax.h - C ABI of the MI355X (gfx950) batched Craftax-Classic and Craftax simulator.
  *
  * The library implements the environment interface the paper describes in section
  * "RL Environment Interface" (Gymnax-style reset/step with the whole state exposed as one
@@ -40,7 +40,9 @@ enum {
     CRAFTAX_E_CONFIG = -6      /* unsupported configuration value */
 };
 
-enum { CRAFTAX_VARIANT_CLASSIC = 0 };
+/* Variants (section "Craftax: An Extension of Crafter ..."): Classic = the Crafter rules on a
+ * 64x64 map; CRAFTAX = the full game with nine 48x48 floors, 43 actions, 67 achievements. */
+enum { CRAFTAX_VARIANT_CLASSIC = 0, CRAFTAX_VARIANT_CRAFTAX = 1 };
 
 /* Observation layouts (per environment, stride = craftax_obs_bytes()):
  *  SYM_U8_I8  : bytes [0,1323) 7x9 cells x 21 channels (17-way block one-hot, then zombie,
@@ -53,7 +55,26 @@ enum { CRAFTAX_VARIANT_CLASSIC = 0 };
  * The 22 scalars: wood, stone, coal, iron, diamond, sapling, wood/stone/iron pickaxe,
  * wood/stone/iron sword, health, food, drink, energy, facing one-hot (left, right, up,
  * down), daylight, sleeping.  Scaled form follows appendix "Observation Space":
- * counts sqrt(n)/10, vitals x/10, flags 0/1.  Unused bytes of the stride are zero. */
+ * counts sqrt(n)/10, vitals x/10, flags 0/1.  Unused bytes of the stride are zero.
+ *
+ * Variant CRAFTAX supports two of the layouts (appendix "Observation Space": 9x11 cells, per
+ * cell 37-way block, 5-way item and 40-way creature one-hots plus a light level, cells darker
+ * than 0.05 blank; then 51 scalars; 99*83 + 51 = 8268):
+ *  SYM_U8_F32 : bytes [0,8217) 9x11 cells x 83 channels, row-major (row, col, channel), channel
+ *               82 = light level 0..20; float[51] scalars at byte 8224; stride 8448 (66 lines).
+ *  SYM_F32    : float[8268] = the cell bytes as floats (light as level/20) followed by the 51
+ *               scalars (the flat layout of the paper); stride 33152.
+ * Channels: 0..36 block id; 37..41 item (none, torch, ladder down, ladder up, blocked ladder
+ * down); 42..81 creature = 42 + 8*class + type slot, classes melee, passive, ranged, mob
+ * projectile, player projectile; melee and ranged type slot = the floor the creature lives on
+ * (appendix "Creatures"), passive cow/snail/bat = 0/1/2, mob projectile plain/fire/ice/both =
+ * 0/1/2/3, player projectile arrow/fireball/iceball = 0/1/2.
+ * The 51 scalars follow the inventory table of that appendix: wood, stone, coal, iron, diamond,
+ * sapphire, ruby, sapling, torch, arrow, 6 potions (sqrt(n)/10); book n/2; pickaxe, sword
+ * level/4; sword enchantment; bow; bow enchantment; 4 armour level/2; 4 armour enchantments;
+ * health, food, drink, energy, mana, experience, dexterity, strength, intelligence (x/10);
+ * facing one-hot; daylight; sleeping; resting; learned fireball; learned iceball; floor/10;
+ * floor cleared; boss vulnerable. */
 enum {
     CRAFTAX_OBS_SYM_U8_I8 = 0,
     CRAFTAX_OBS_SYM_U8_F32 = 1,
@@ -68,7 +89,10 @@ typedef struct craftax_config {
     uint32_t max_episode_steps;  /* episode is cut (done = 1) when this many steps were taken */
     uint32_t day_length;         /* even, 2..1024 */
     uint32_t cap_zombie, cap_cow, cap_skeleton, cap_arrow;  /* 0..3 each (appendix "Differences
-                                    between Craftax-Classic and Crafter": fixed, masked slots) */
+                                    between Craftax-Classic and Crafter": fixed, masked slots).
+                                    Variant CRAFTAX reads them as the per-floor caps of melee
+                                    (cap_zombie, 0..3), passive (cap_cow, 0..3) and ranged
+                                    (cap_skeleton, 0..2) creatures; projectiles are always 3+3 */
     uint32_t cap_plant;          /* 0..10 */
     uint64_t atlas_seed;         /* seed of the synthetic tile atlas (pixel observations) */
 } craftax_config;
@@ -92,8 +116,49 @@ typedef struct craftax_env_dump {
     uint32_t env;
 } craftax_env_dump;
 
+/* One full-Craftax environment in canonical form (63432 bytes, little endian).  Maps are
+ * [floor][y][x].  Mob slots per floor: 0-2 melee, 3-4 ranged, 5-7 passive, 8-10 mob
+ * projectiles, 11-13 player projectiles; `type` is the creature's row in appendix "Creatures"
+ * (0 zombie, 1 skeleton, 2 cow, 3 orc soldier, 4 orc mage, 5 snail, 6 gnome warrior, 7 gnome
+ * archer, 8 bat, 9 lizard, 10 kobold, 11 knight, 12 archer, 13 troll, 14 deep thing, 15 pig man,
+ * 16 fire elemental, 17 frost troll, 18 ice elemental), for a mob projectile its shooter's, for
+ * a player projectile 0 arrow, 1 fireball, 2 iceball.  Dead slots are all zero. */
+typedef struct craftax_full_mob { uint8_t alive, x, y, dir; int8_t hp; uint8_t cd, type, pad; } craftax_full_mob;
+typedef struct craftax_full_env_dump {
+    uint8_t block[9][48 * 48];  /* appendix "Block Types" */
+    uint8_t item[9][48 * 48];   /* 0 none, 1 torch, 2 ladder down, 3 ladder up, 4 ladder down (blocked) */
+    uint8_t light[9][48 * 48];  /* 0..20 */
+    uint8_t px, py, dir, floor;
+    uint8_t sleeping, resting, learned_fireball, learned_iceball;
+    uint8_t inv[10];            /* wood stone coal iron diamond sapphire ruby sapling torch arrow */
+    uint8_t potion[6];          /* red green blue pink cyan yellow */
+    uint8_t book, pickaxe, sword, sword_ench, bow, bow_ench;   /* levels 0..4; enchantment 0 none, 1 fire, 2 ice */
+    uint8_t armour[4], armour_ench[4];
+    int8_t vit[5];              /* health food drink energy mana */
+    uint8_t xp, dex, str, intel;
+    uint8_t pad_a;
+    int16_t cnt[5];             /* hunger thirst fatigue recover mana */
+    uint8_t potion_effect[6];   /* colour -> effect of this episode: 0/1 health +/-, 2/3 mana, 4/5 energy */
+    uint8_t kills[9];
+    uint8_t boss_hits, boss_vulnerable;
+    uint8_t pad_b;
+    uint16_t visited;           /* bit f = floor f was entered */
+    uint8_t ladder_up[9][2], ladder_down[9][2];   /* x, y per floor */
+    uint8_t pad_c[2];
+    uint32_t ach[3];            /* bit i of word i/32 = achievement id i (appendix "Achievements") */
+    uint32_t t, episode, env;
+    uint32_t pad0;
+    uint64_t seed;
+    craftax_full_mob mob[9][14];
+    craftax_plant plant[10];
+    uint8_t pad1[4];
+} craftax_full_env_dump;
+
 /* Fills *cfg (HOST) with the defaults: Classic, SYM_U8_F32, 10000 steps, day 300, caps 3/3/3/3/10. */
 void craftax_default_config(craftax_config *cfg);
+/* Defaults of a variant: CLASSIC as above; CRAFTAX: SYM_U8_F32, 100000 steps (appendix
+ * "Further Environment Details"), day 300, caps melee 3 / passive 3 / ranged 2, 10 plants. */
+void craftax_default_config_for(craftax_config *cfg, uint32_t variant);
 
 /* Bytes of device memory the caller must provide for n environments (0 on a bad config). */
 size_t craftax_state_bytes(const craftax_config *cfg, int n);
@@ -101,6 +166,8 @@ size_t craftax_state_bytes(const craftax_config *cfg, int n);
 size_t craftax_obs_bytes(const craftax_config *cfg);
 /* sizeof(craftax_env_dump). */
 size_t craftax_env_dump_bytes(void);
+/* Size of one canonical dump for cfg->variant: craftax_env_dump or craftax_full_env_dump. */
+size_t craftax_env_dump_bytes_for(const craftax_config *cfg);
 
 /* Writes the header, lookup tables and tile atlas into `state` (DEVICE, 256-byte aligned,
  * craftax_state_bytes() long) and registers it with the library.  Environments hold no
@@ -113,7 +180,8 @@ int craftax_state_release(void *state);
  * Philox key for all later episodes, a generated 64x64 world, full vitals, empty tables. */
 int craftax_reset(void *state, const uint64_t *seeds, int n, void *stream);
 
-/* One step of every environment.  actions: DEVICE int32[n]; ids outside 0..16 act as NOOP.
+/* One step of every environment.  actions: DEVICE int32[n]; ids outside the variant's action
+ * table (0..16 Classic, 0..42 Craftax: appendix "Action Space") act as NOOP.
  * Outputs (all DEVICE): obs (n x craftax_obs_bytes(), 16-byte aligned), reward float[n],
  * done uint8[n].  When done[i] = 1 the reward belongs to the episode that just ended and
  * state and obs already hold the first state of the next episode.  obs may be NULL to skip
@@ -125,14 +193,15 @@ int craftax_step(void *state, const int32_t *actions, void *obs, float *reward, 
 int craftax_observe(void *state, void *obs, int n, void *stream);
 
 /* Copies environments [first, first+count) to / from canonical dumps in DEVICE memory
- * (count x craftax_env_dump).  Import is the state-editing hook: the paper notes that the
+ * (count x craftax_env_dump, or craftax_full_env_dump for variant CRAFTAX).  Import is the state-editing hook: the paper notes that the
  * whole environment state is one object that level editors can modify. */
 int craftax_export_envs(const void *state, int first, int count, void *dumps, void *stream);
 int craftax_import_envs(void *state, int first, int count, const void *dumps, void *stream);
 
 /* Fills actions (DEVICE int32[steps][n]) with the synthetic action stream used by the
  * benchmark: kind 0 = uniform over 17 actions, kind 1 = half of the draws restricted to
- * ids 1..5.  Input generation only; not part of the simulator. */
+ * ids 1..5, kinds 2 and 3 = the same two over the 43 actions of full Craftax.  Input generation
+ * only; not part of the simulator. */
 int craftax_synth_actions(int32_t *actions, int n, int step0, int steps, uint64_t action_seed,
                           int kind, void *stream);
 

@@ -15,9 +15,11 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libcraftax_hip.so")
 
 OBS_SYM_U8_I8, OBS_SYM_U8_F32, OBS_SYM_F32, OBS_PIXELS_F32 = 0, 1, 2, 3
+VARIANT_CLASSIC, VARIANT_CRAFTAX = 0, 1
 
 EXPORTS = [
-    "craftax_default_config", "craftax_state_bytes", "craftax_obs_bytes", "craftax_env_dump_bytes",
+    "craftax_default_config", "craftax_default_config_for", "craftax_state_bytes", "craftax_obs_bytes",
+    "craftax_env_dump_bytes", "craftax_env_dump_bytes_for",
     "craftax_state_init", "craftax_state_release", "craftax_reset", "craftax_step", "craftax_observe",
     "craftax_export_envs", "craftax_import_envs", "craftax_synth_actions", "craftax_last_error",
 ]
@@ -52,6 +54,10 @@ def load() -> ctypes.CDLL:
     vp, i32, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64
     L.craftax_default_config.argtypes = [ctypes.POINTER(Config)]
     L.craftax_default_config.restype = None
+    L.craftax_default_config_for.argtypes = [ctypes.POINTER(Config), ctypes.c_uint32]
+    L.craftax_default_config_for.restype = None
+    L.craftax_env_dump_bytes_for.argtypes = [ctypes.POINTER(Config)]
+    L.craftax_env_dump_bytes_for.restype = ctypes.c_size_t
     L.craftax_state_bytes.argtypes = [ctypes.POINTER(Config), i32]
     L.craftax_state_bytes.restype = ctypes.c_size_t
     L.craftax_obs_bytes.argtypes = [ctypes.POINTER(Config)]
@@ -77,9 +83,9 @@ def _check(rc: int, what: str):
         raise CraftaxError(f"{what} failed ({rc}): {load().craftax_last_error().decode()}")
 
 
-def default_config(**overrides) -> Config:
+def default_config(variant: int = VARIANT_CLASSIC, **overrides) -> Config:
     cfg = Config()
-    load().craftax_default_config(ctypes.byref(cfg))
+    load().craftax_default_config_for(ctypes.byref(cfg), variant)
     for k, v in overrides.items():
         setattr(cfg, k, v)
     return cfg
@@ -95,6 +101,10 @@ def craftax_obs_bytes(cfg: Config) -> int:
 
 def craftax_env_dump_bytes() -> int:
     return int(load().craftax_env_dump_bytes())
+
+
+def craftax_env_dump_bytes_for(cfg: Config) -> int:
+    return int(load().craftax_env_dump_bytes_for(ctypes.byref(cfg)))
 
 
 def _stream_ptr(stream) -> int:
@@ -186,14 +196,14 @@ class Craftax:
     def export_envs(self, first: int = 0, count: int | None = None) -> np.ndarray:
         torch = self.torch
         count = self.n - first if count is None else count
-        size = craftax_env_dump_bytes()
+        size = craftax_env_dump_bytes_for(self.cfg)
         buf = torch.empty((count, size), dtype=torch.uint8, device=self.device)
         craftax_export_envs(self.state, first, count, buf, self.stream)
         return buf.cpu().numpy()
 
     def import_envs(self, dumps: np.ndarray, first: int = 0):
         torch = self.torch
-        raw = np.ascontiguousarray(dumps).view(np.uint8).reshape(-1, craftax_env_dump_bytes())
+        raw = np.ascontiguousarray(dumps).view(np.uint8).reshape(-1, craftax_env_dump_bytes_for(self.cfg))
         buf = torch.as_tensor(raw, device=self.device)
         craftax_import_envs(self.state, first, raw.shape[0], buf, self.stream)
         self.torch.cuda.synchronize(self.device)

@@ -5,7 +5,7 @@ import os
 import subprocess
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(_PKG, "csrc", "craftax.hip")
+SRCS = [os.path.join(_PKG, "csrc", f) for f in ("craftax.hip", "full.hip")]
 OUT = os.path.join(_PKG, "libcraftax_hip.so")
 
 HIPCC_FLAGS = [
@@ -17,7 +17,7 @@ HIPCC_FLAGS = [
 
 def build_library(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", OUT, SRC]
+    cmd = [hipcc] + HIPCC_FLAGS + ["-o", OUT] + SRCS
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stderr)

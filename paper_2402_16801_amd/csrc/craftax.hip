@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "common.hpp"
+#include "full_api.hpp"
 #include "render.hpp"
 #include "step.hpp"
 #include "worldgen.hpp"
@@ -304,9 +305,10 @@ __global__ void k_synth_actions(int32_t* __restrict__ actions, int n, int step0,
     if (i >= (size_t)n * (size_t)steps) return;
     const uint32_t s = (uint32_t)(i / (size_t)n), env = (uint32_t)(i % (size_t)n);
     const U4 r = philox4x32_10(env, (uint32_t)step0 + s, 0u, DOM_ACTIONS << 16, k0, k1);
+    const uint32_t count = kind >= 2 ? 43u : (uint32_t)AC_COUNT;   // appendix "Action Space": 17 Classic, 43 Craftax
     int a;
-    if (kind == 0) a = (int)choice(r.w[0], AC_COUNT);
-    else a = r.w[0] < 0x80000000u ? 1 + (int)choice(r.w[1], 5) : (int)choice(r.w[1], AC_COUNT);
+    if ((kind & 1) == 0) a = (int)choice(r.w[0], count);
+    else a = r.w[0] < 0x80000000u ? 1 + (int)choice(r.w[1], 5) : (int)choice(r.w[1], count);
     actions[i] = a;
 }
 
@@ -331,8 +333,9 @@ static int fail(int code, const std::string& msg)
 
 static bool config_ok(const craftax_config* c, std::string* why)
 {
+    if (c->variant == CRAFTAX_VARIANT_CRAFTAX) return cf::host::config_ok(c, why);
     if (c->abi_version != CRAFTAX_ABI_VERSION) { *why = "abi_version mismatch"; return false; }
-    if (c->variant != CRAFTAX_VARIANT_CLASSIC) { *why = "only the Classic variant is implemented"; return false; }
+    if (c->variant != CRAFTAX_VARIANT_CLASSIC) { *why = "unknown variant"; return false; }
     if (c->obs_mode > CRAFTAX_OBS_PIXELS_F32) { *why = "unknown obs_mode"; return false; }
     if (c->day_length < 2 || c->day_length > MAX_DAY || (c->day_length & 1)) { *why = "day_length must be even and in 2..1024"; return false; }
     if (c->cap_zombie > 3 || c->cap_cow > 3 || c->cap_skeleton > 3 || c->cap_arrow > 3) { *why = "mob caps must be 0..3"; return false; }
@@ -461,34 +464,47 @@ using namespace cx;
 
 extern "C" {
 
-void craftax_default_config(craftax_config* cfg)
+void craftax_default_config_for(craftax_config* cfg, uint32_t variant)
 {
     if (!cfg) return;
     std::memset(cfg, 0, sizeof(*cfg));
     cfg->abi_version = CRAFTAX_ABI_VERSION;
-    cfg->variant = CRAFTAX_VARIANT_CLASSIC;
+    cfg->variant = variant;
     cfg->obs_mode = CRAFTAX_OBS_SYM_U8_F32;
-    cfg->max_episode_steps = 10000;
+    cfg->max_episode_steps = variant == CRAFTAX_VARIANT_CRAFTAX ? 100000 : 10000;
     cfg->day_length = 300;
     cfg->cap_zombie = cfg->cap_cow = cfg->cap_skeleton = cfg->cap_arrow = 3;
+    if (variant == CRAFTAX_VARIANT_CRAFTAX) cfg->cap_skeleton = 2;
     cfg->cap_plant = 10;
     cfg->atlas_seed = 0;
 }
+
+void craftax_default_config(craftax_config* cfg) { craftax_default_config_for(cfg, CRAFTAX_VARIANT_CLASSIC); }
 
 size_t craftax_state_bytes(const craftax_config* cfg, int n)
 {
     std::string why;
     if (!cfg || n <= 0 || !config_ok(cfg, &why)) return 0;
+    if (cfg->variant == CRAFTAX_VARIANT_CRAFTAX) return cf::host::state_bytes(cfg, n);
     return (size_t)make_header(cfg, n).total;
 }
 
 size_t craftax_obs_bytes(const craftax_config* cfg)
 {
     if (!cfg || cfg->obs_mode > CRAFTAX_OBS_PIXELS_F32) return 0;
+    if (cfg->variant == CRAFTAX_VARIANT_CRAFTAX) {
+        std::string why;
+        return cf::host::config_ok(cfg, &why) ? cf::host::obs_bytes(cfg) : 0;
+    }
     return (size_t)obs_stride((int)cfg->obs_mode);
 }
 
 size_t craftax_env_dump_bytes(void) { return sizeof(craftax_env_dump); }
+size_t craftax_env_dump_bytes_for(const craftax_config* cfg)
+{
+    if (!cfg) return 0;
+    return cfg->variant == CRAFTAX_VARIANT_CRAFTAX ? sizeof(craftax_full_env_dump) : sizeof(craftax_env_dump);
+}
 
 int craftax_state_init(void* state, const craftax_config* cfg, int n, void* stream)
 {
@@ -498,7 +514,17 @@ int craftax_state_init(void* state, const craftax_config* cfg, int n, void* stre
     std::string why;
     if (!config_ok(cfg, &why)) return fail(CRAFTAX_E_CONFIG, why);
     HostState s;
-    s.cfg = *cfg; s.n = n; s.hdr = make_header(cfg, n); s.lanes = group_lanes(n);
+    s.cfg = *cfg; s.n = n;
+    if (cfg->variant == CRAFTAX_VARIANT_CRAFTAX) {
+        std::memset(&s.hdr, 0, sizeof(s.hdr));
+        s.lanes = 64;
+        std::string err;
+        if (int rc = cf::host::state_init(state, cfg, n, stream, &err)) return fail(rc, err);
+        std::lock_guard<std::mutex> lock(g_mutex);
+        g_states[state] = s;
+        return CRAFTAX_OK;
+    }
+    s.hdr = make_header(cfg, n); s.lanes = group_lanes(n);
     std::vector<uint8_t> staging((size_t)s.hdr.off_recs, 0);
     std::memcpy(staging.data(), &s.hdr, sizeof(Header));
     build_luts(cfg, reinterpret_cast<Luts*>(staging.data() + s.hdr.off_luts));
@@ -521,6 +547,11 @@ int craftax_reset(void* state, const uint64_t* seeds, int n, void* stream)
     HostState s;
     if (int rc = lookup(state, n, true, &s)) return rc;
     if (!seeds) return fail(CRAFTAX_E_NULL, "seeds is NULL");
+    if (s.cfg.variant == CRAFTAX_VARIANT_CRAFTAX) {
+        std::string err;
+        const int rc = cf::host::reset(state, &s.cfg, n, seeds, stream, &err);
+        return rc ? fail(rc, err) : rc;
+    }
     const Ptrs q = pointers(state, s);
     hipLaunchKernelGGL(k_reset, dim3(n), dim3(WG_THREADS), 0, (hipStream_t)stream, q.recs, q.maps, seeds, q.dl.count, q.dl.finished,
                        make_params(s));
@@ -533,6 +564,11 @@ int craftax_step(void* state, const int32_t* actions, void* obs, float* reward, 
     if (int rc = lookup(state, n, true, &s)) return rc;
     if (!actions || !reward || !done) return fail(CRAFTAX_E_NULL, "actions, reward or done is NULL");
     if ((uintptr_t)obs % 16) return fail(CRAFTAX_E_ALIGN, "obs must be 16-byte aligned");
+    if (s.cfg.variant == CRAFTAX_VARIANT_CRAFTAX) {
+        std::string err;
+        const int rc = cf::host::step(state, &s.cfg, n, actions, obs, reward, done, stream, &err);
+        return rc ? fail(rc, err) : rc;
+    }
     const Ptrs q = pointers(state, s);
     const Params p = make_params(s);
     hipStream_t st = (hipStream_t)stream;
@@ -556,6 +592,11 @@ int craftax_observe(void* state, void* obs, int n, void* stream)
     if (int rc = lookup(state, n, true, &s)) return rc;
     if (!obs) return fail(CRAFTAX_E_NULL, "obs is NULL");
     if ((uintptr_t)obs % 16) return fail(CRAFTAX_E_ALIGN, "obs must be 16-byte aligned");
+    if (s.cfg.variant == CRAFTAX_VARIANT_CRAFTAX) {
+        std::string err;
+        const int rc = cf::host::observe(state, &s.cfg, n, obs, stream, &err);
+        return rc ? fail(rc, err) : rc;
+    }
     const Ptrs q = pointers(state, s);
     const Params p = make_params(s);
     const dim3 grid((n + 15) / 16), block(BLOCK);
@@ -577,6 +618,11 @@ int craftax_export_envs(const void* state, int first, int count, void* dumps, vo
     if (!dumps) return fail(CRAFTAX_E_NULL, "dumps is NULL");
     if (first < 0 || count <= 0 || first + count > s.n) return fail(CRAFTAX_E_COUNT, "range outside the state");
     if ((uintptr_t)dumps % 16) return fail(CRAFTAX_E_ALIGN, "dumps must be 16-byte aligned");
+    if (s.cfg.variant == CRAFTAX_VARIANT_CRAFTAX) {
+        std::string err;
+        const int rc = cf::host::export_envs(state, &s.cfg, s.n, first, count, dumps, stream, &err);
+        return rc ? fail(rc, err) : rc;
+    }
     const Ptrs q = pointers(state, s);
     hipLaunchKernelGGL(k_export, dim3(count), dim3(BLOCK), 0, (hipStream_t)stream, q.recs, q.maps,
                        static_cast<craftax_env_dump*>(dumps), first);
@@ -590,6 +636,11 @@ int craftax_import_envs(void* state, int first, int count, const void* dumps, vo
     if (!dumps) return fail(CRAFTAX_E_NULL, "dumps is NULL");
     if (first < 0 || count <= 0 || first + count > s.n) return fail(CRAFTAX_E_COUNT, "range outside the state");
     if ((uintptr_t)dumps % 16) return fail(CRAFTAX_E_ALIGN, "dumps must be 16-byte aligned");
+    if (s.cfg.variant == CRAFTAX_VARIANT_CRAFTAX) {
+        std::string err;
+        const int rc = cf::host::import_envs(state, &s.cfg, s.n, first, count, dumps, stream, &err);
+        return rc ? fail(rc, err) : rc;
+    }
     const Ptrs q = pointers(state, s);
     hipLaunchKernelGGL(k_import, dim3(count), dim3(BLOCK), 0, (hipStream_t)stream, q.recs, q.maps,
                        static_cast<const craftax_env_dump*>(dumps), first, make_params(s));
@@ -599,7 +650,7 @@ int craftax_import_envs(void* state, int first, int count, const void* dumps, vo
 int craftax_synth_actions(int32_t* actions, int n, int step0, int steps, uint64_t action_seed, int kind, void* stream)
 {
     if (!actions) return fail(CRAFTAX_E_NULL, "actions is NULL");
-    if (n <= 0 || steps <= 0 || step0 < 0 || kind < 0 || kind > 1) return fail(CRAFTAX_E_COUNT, "bad n, steps, step0 or kind");
+    if (n <= 0 || steps <= 0 || step0 < 0 || kind < 0 || kind > 3) return fail(CRAFTAX_E_COUNT, "bad n, steps, step0 or kind");
     const size_t total = (size_t)n * (size_t)steps;
     hipLaunchKernelGGL(k_synth_actions, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, actions, n,
                        step0, steps, (uint32_t)action_seed, (uint32_t)(action_seed >> 32), kind);

@@ -1,0 +1,27 @@
+// Host entry points of the full-Craftax variant, called by the C ABI in craftax.hip once the
+// state's variant is known.  Every function returns 0 or a negative CRAFTAX_E_* code and, on
+// error, a message in *err.  Nothing here synchronises except state_init.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <string>
+
+#include "../../include/craftax.h"
+
+namespace cf {
+namespace host {
+
+bool config_ok(const craftax_config* cfg, std::string* why);
+size_t state_bytes(const craftax_config* cfg, int n);
+size_t obs_bytes(const craftax_config* cfg);
+int state_init(void* state, const craftax_config* cfg, int n, void* stream, std::string* err);
+int reset(void* state, const craftax_config* cfg, int n, const uint64_t* seeds, void* stream, std::string* err);
+int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, void* obs, float* reward, uint8_t* done,
+         void* stream, std::string* err);
+int observe(void* state, const craftax_config* cfg, int n, void* obs, void* stream, std::string* err);
+int export_envs(const void* state, const craftax_config* cfg, int n, int first, int count, void* dumps, void* stream, std::string* err);
+int import_envs(void* state, const craftax_config* cfg, int n, int first, int count, const void* dumps, void* stream, std::string* err);
+
+}  // namespace host
+}  // namespace cf

@@ -47,6 +47,27 @@ def test_sizes_and_defaults(lib):
     assert binding.craftax_state_bytes(cfg, 4) == 0
 
 
+def test_full_variant_sizes_and_defaults(lib):
+    cfg = binding.default_config(binding.VARIANT_CRAFTAX)
+    assert (cfg.abi_version, cfg.variant, cfg.obs_mode) == (1, 1, 1)
+    assert (cfg.max_episode_steps, cfg.day_length) == (100000, 300)
+    assert (cfg.cap_zombie, cfg.cap_cow, cfg.cap_skeleton, cfg.cap_plant) == (3, 3, 2, 10)
+    assert binding.craftax_env_dump_bytes_for(cfg) == 63432
+    assert binding.craftax_env_dump_bytes_for(binding.default_config()) == 4304
+    assert binding.craftax_obs_bytes(cfg) == 8448 >= 99 * 83 + 51 * 4
+    cfg.obs_mode = binding.OBS_SYM_F32
+    assert binding.craftax_obs_bytes(cfg) == 33152 >= 8268 * 4
+    for bad in (binding.OBS_SYM_U8_I8, binding.OBS_PIXELS_F32):
+        cfg.obs_mode = bad
+        assert binding.craftax_obs_bytes(cfg) == 0 and binding.craftax_state_bytes(cfg, 8) == 0
+    cfg.obs_mode = binding.OBS_SYM_U8_F32
+    b1, b2 = binding.craftax_state_bytes(cfg, 1), binding.craftax_state_bytes(cfg, 1001)
+    # per environment: 1024-byte record + mob tables, 9 floors x 2 maps x 2304 bytes, done-list entry
+    assert abs((b2 - b1) - 1000 * (1024 + 9 * 2 * 2304 + 16)) < 512 and b1 % 256 == 0
+    cfg.cap_skeleton = 3
+    assert binding.craftax_state_bytes(cfg, 8) == 0
+
+
 def test_host_side_argument_errors(lib):
     cfg = binding.default_config()
     assert lib.craftax_state_init(None, ctypes.byref(cfg), 4, None) == -1
