@@ -1,11 +1,14 @@
 #!/usr/bin/env python3
-"""Benchmark of the Craftax-Classic hot path on one MI355X.
+"""Benchmark of the Craftax hot path on one MI355X.
 
 A "step" is one craftax_step call over all environments of the workload: rules, mob update,
 auto-reset of finished episodes and the symbolic observation write, with every input already
-resident in HBM.  Prints ONE JSON line (see the design doc for the field definitions).
+resident in HBM.  Prints ONE JSON line (see the design doc for the field definitions).  The headline
+workload is the 65,536-environment Craftax-Classic step; the 4,096-environment Classic step and
+the 4,096-environment full-Craftax step are measured next to it ("also", "also_craftax"), or
+alone with --workload craftax.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--envs N] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--envs N] [--workload classic|craftax] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -40,6 +43,23 @@ def algorithmic_bytes_per_env_step(mean_episode_len: float) -> dict:
     return parts
 
 
+FULL_OBS_ALG_BYTES = 99 * 83 + 51 * 4   # uint8 cells + fp32 scalars of the full game
+
+
+def full_algorithmic_bytes_per_env_step(mean_episode_len: float) -> dict:
+    parts = {
+        "obs_write": FULL_OBS_ALG_BYTES,
+        "action_reward_done": 4 + 4 + 1,
+        "record_rw": 256 + 256,               # packed record incl. ladders and plants, read + write
+        "mob_table_rw": 56 + 56,              # 14 slots of the current floor
+        "map_reads": 2 * 99 + 14 + 3 + 10,    # view in both maps, mob targets, spawn probes, plant cells
+        "map_writes": 2,
+        "reset_amortised": (9 * 2 * 2304 + 1024 + 16) / max(mean_episode_len, 1.0),
+    }
+    parts["total"] = float(sum(parts.values()))
+    return parts
+
+
 def read_profile_traffic(name: str):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), taken from
     the committed summary; None if that summary is absent."""
@@ -50,16 +70,19 @@ def read_profile_traffic(name: str):
     return float(m.group(1)) if m else None
 
 
-def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3):
+def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, variant: str = "classic"):
     import torch
     from paper_2402_16801_amd import binding as cx, synth
 
     dev = torch.device("cuda:0")
-    cfg = cx.default_config(obs_mode=cx.OBS_SYM_U8_F32, max_episode_steps=10000)
+    if variant == "craftax":
+        cfg = cx.default_config(cx.VARIANT_CRAFTAX, obs_mode=cx.OBS_SYM_U8_F32)
+    else:
+        cfg = cx.default_config(obs_mode=cx.OBS_SYM_U8_F32, max_episode_steps=10000)
     sim = cx.Craftax(n, cfg)
     sim.reset(synth.seeds_for(n))
     total_steps = warmup + repeats * steps
-    kind_id = {"uniform": 0, "skewed": 1}[kind]
+    kind_id = {"uniform": 0, "skewed": 1}[kind] + (2 if variant == "craftax" else 0)
     actions = torch.empty((total_steps, n), dtype=torch.int32, device=dev)
     cx.craftax_synth_actions(actions, n, 0, total_steps, 0, kind_id, sim.stream)
     torch.cuda.synchronize()
@@ -86,23 +109,27 @@ def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3):
         evt.append(e0.elapsed_time(e1) * 1e-3)
     # episodes finished so far -> mean episode length (drives the amortised reset bytes)
     episodes = 0
-    chunk = 8192
+    chunk = 512 if variant == "craftax" else 8192
     for first in range(0, n, chunk):
         d = sim.export_envs(first, min(chunk, n - first))
-        episodes += int(d[:, 4132:4136].copy().view(np.uint32).sum())
+        episodes += int(d.view(sim.dump_dtype)["episode"].sum())
     mean_len = (n * total_steps) / max(episodes, 1)
     sim.close()
     med = int(np.argsort(wall)[len(wall) // 2])
     return {"wall_s": wall[med], "event_s": evt[med], "all_wall_s": wall, "episodes": episodes, "mean_episode_len": mean_len}
 
 
-def cpu_baseline(n_sample: int, steps: int, kind: str):
+def cpu_baseline(n_sample: int, steps: int, kind: str, variant: str = "classic"):
     """The CPU oracle, as it stands, on the first n_sample environments of the same workload."""
     from oracle import pyoracle as po
     from paper_2402_16801_amd import synth
 
-    acts = synth.action_block(n_sample, steps, kind, 0)
-    orc = po.Oracle(n_sample, po.default_config(max_episode_steps=10000), po.OBS_SYM_U8_F32)
+    if variant == "craftax":
+        acts = synth.action_block(n_sample, steps, kind, 0, n_actions=43)
+        orc = po.FullOracle(n_sample, po.full_default_config(), po.FULL_OBS_U8_F32)
+    else:
+        acts = synth.action_block(n_sample, steps, kind, 0)
+        orc = po.Oracle(n_sample, po.default_config(max_episode_steps=10000), po.OBS_SYM_U8_F32)
     orc.reset(synth.seeds_for(n_sample))
     t0 = time.perf_counter()
     for s in range(steps):
@@ -118,8 +145,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--envs", type=int, default=65536)
-    ap.add_argument("--kind", default="skewed", choices=["uniform", "skewed"])
+    ap.add_argument("--workload", default="classic", choices=["classic", "craftax"])
+    ap.add_argument("--envs", type=int, default=None, help="default 65536 (classic) or 4096 (craftax)")
+    ap.add_argument("--kind", default=None, choices=["uniform", "skewed"], help="default skewed (classic) or uniform (craftax)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-small", action="store_true", help="skip the secondary 4096-env measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -142,6 +170,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.workload == "craftax":
+        print(json.dumps(craftax_line(args)))
+        return
+    args.envs = 65536 if args.envs is None else args.envs
+    args.kind = "skewed" if args.kind is None else args.kind
     n, K, W = args.envs, args.steps, args.warmup
     main_run = gpu_run(n, K, W, args.kind)
     alg = algorithmic_bytes_per_env_step(main_run["mean_episode_len"])
@@ -187,9 +220,44 @@ def main():
         small = gpu_run(4096, K, W, "uniform")
         out["also"] = {"workload": "configs[1]: 4096 envs, uniform actions", "value": 4096 * K / small["wall_s"],
                        "unit": "env_steps/s", "ms_per_step": small["wall_s"] / K * 1e3}
+        full = craftax_line(args, with_cpu=False)
+        out["also_craftax"] = {"workload": full["config"]["workload"], "value": full["value"], "unit": "env_steps/s",
+                               "ms_per_step": full["ms_per_step"], "roofline": full["roofline"]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(8192, min(K, 1000), args.kind)
     print(json.dumps(out))
+
+
+def craftax_line(args, with_cpu: bool = True) -> dict:
+    """configs[3]: the full game, 4096 environments, 43 uniform actions."""
+    n = 4096 if (args.envs is None or args.workload != "craftax") else args.envs
+    kind = "uniform" if (args.kind is None or args.workload != "craftax") else args.kind
+    K, W = args.steps, args.warmup
+    run = gpu_run(n, K, W, kind, variant="craftax")
+    alg = full_algorithmic_bytes_per_env_step(run["mean_episode_len"])
+    launch_s = run["event_s"] / K
+    achieved = alg["total"] * n / launch_s / 1e9
+    out = {
+        "metric": "env steps/sec at 1 GPU (4096 / 65536 envs, symbolic obs) + % HBM roofline",
+        "value": n * K / run["wall_s"], "unit": "env_steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": run["wall_s"] / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {
+            "workload": f"configs[3]: full Craftax step, {n} envs, 9 floors x 48x48 block + item/light maps, 43 actions "
+                        f"{kind}, per-floor mob tables 3/2/3/3/3, episode cap 100000, obs uint8[8217]+fp32[51]",
+            "envs": n, "obs_mode": "SYM_U8_F32", "actions": kind, "mean_episode_len": round(run["mean_episode_len"], 1),
+        },
+        "roofline": {
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": read_profile_traffic("craftax_full_step_sym_u8_f32_4096env.txt"),
+            "kernel": "kf_step<SYM_U8_F32> + kf_reset_list (one craftax_step call)",
+            "alg_bytes_per_env_step": round(alg["total"], 1), "alg_bytes_per_launch": alg["total"] * n,
+            "avg_launch_us": launch_s * 1e6,
+        },
+    }
+    if with_cpu and not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(1024, min(K, 1000), kind, variant="craftax")
+    return out
 
 
 if __name__ == "__main__":

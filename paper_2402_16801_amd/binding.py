@@ -32,6 +32,29 @@ class Config(ctypes.Structure):
                 ("cap_arrow", ctypes.c_uint32), ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64)]
 
 
+# numpy views of the canonical dumps declared in include/craftax.h
+_MOB = np.dtype([("alive", "u1"), ("x", "u1"), ("y", "u1"), ("dir", "u1"), ("hp", "i1"), ("cd", "u1"), ("pad", "u1", (2,))])
+_PLANT = np.dtype([("alive", "u1"), ("x", "u1"), ("y", "u1"), ("pad", "u1"), ("age", "<u2")])
+ENV_DUMP_DTYPE = np.dtype([
+    ("map", "u1", (64, 64)), ("px", "u1"), ("py", "u1"), ("dir", "u1"), ("sleeping", "u1"), ("inv", "u1", (12,)),
+    ("vit", "i1", (4,)), ("cnt", "<i2", (4,)), ("ach", "<u4"), ("t", "<u4"), ("episode", "<u4"), ("seed", "<u8"),
+    ("mob", _MOB, (12,)), ("plant", _PLANT, (10,)), ("env", "<u4")])
+_FULL_MOB = np.dtype([("alive", "u1"), ("x", "u1"), ("y", "u1"), ("dir", "u1"), ("hp", "i1"), ("cd", "u1"), ("type", "u1"), ("pad", "u1")])
+FULL_ENV_DUMP_DTYPE = np.dtype([
+    ("block", "u1", (9, 48, 48)), ("item", "u1", (9, 48, 48)), ("light", "u1", (9, 48, 48)),
+    ("px", "u1"), ("py", "u1"), ("dir", "u1"), ("floor", "u1"),
+    ("sleeping", "u1"), ("resting", "u1"), ("learned_fireball", "u1"), ("learned_iceball", "u1"),
+    ("inv", "u1", (10,)), ("potion", "u1", (6,)),
+    ("book", "u1"), ("pickaxe", "u1"), ("sword", "u1"), ("sword_ench", "u1"), ("bow", "u1"), ("bow_ench", "u1"),
+    ("armour", "u1", (4,)), ("armour_ench", "u1", (4,)), ("vit", "i1", (5,)),
+    ("xp", "u1"), ("dex", "u1"), ("str", "u1"), ("intel", "u1"), ("pad_a", "u1"), ("cnt", "<i2", (5,)),
+    ("potion_effect", "u1", (6,)), ("kills", "u1", (9,)), ("boss_hits", "u1"), ("boss_vulnerable", "u1"), ("pad_b", "u1"),
+    ("visited", "<u2"), ("ladder_up", "u1", (9, 2)), ("ladder_down", "u1", (9, 2)), ("pad_c", "u1", (2,)),
+    ("ach", "<u4", (3,)), ("t", "<u4"), ("episode", "<u4"), ("env", "<u4"), ("pad0", "<u4"), ("seed", "<u8"),
+    ("mob", _FULL_MOB, (9, 14)), ("plant", _PLANT, (10,)), ("pad1", "u1", (4,))])
+assert ENV_DUMP_DTYPE.itemsize == 4304 and FULL_ENV_DUMP_DTYPE.itemsize == 63432
+
+
 class CraftaxError(RuntimeError):
     pass
 
@@ -192,6 +215,10 @@ class Craftax:
         """actions: int32 device tensor [n]."""
         craftax_step(self.state, actions, self.obs, self.reward, self.done, self.n, self.stream)
         return self.obs, self.reward, self.done
+
+    @property
+    def dump_dtype(self) -> np.dtype:
+        return FULL_ENV_DUMP_DTYPE if self.cfg.variant == VARIANT_CRAFTAX else ENV_DUMP_DTYPE
 
     def export_envs(self, first: int = 0, count: int | None = None) -> np.ndarray:
         torch = self.torch

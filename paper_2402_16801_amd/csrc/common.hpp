@@ -79,8 +79,11 @@ __host__ __device__ inline U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c
 __host__ __device__ inline uint32_t choice(uint32_t u, uint32_t n) { return (uint32_t)(((uint64_t)u * n) >> 32); }
 
 // ---- in-HBM layout ----------------------------------------------------------------------------
-// One 128-byte record (one HBM/L2 line) per environment, 32 dwords, plus a 4096-byte
-// tiled map (see map_index).  Everything that changes every step lives in the record.
+// One 128-byte record (one HBM/L2 line) per environment, 32 dwords, plus two 4096-byte
+// tiled maps (see map_index): the world of episode e lives in map slot e & 1, the other slot
+// holds (or is being filled with) the world of episode e + 1, generated ahead of time so that
+// a finished episode only has to switch slots.  Everything that changes every step lives in
+// the record.
 //   w0  px | py<<8 | dir<<16 | sleeping<<24
 //   w1  six 4-bit item counts (wood stone coal iron diamond sapling) | six tool flags at bit 24
 //   w2  four 4-bit vitals (health food drink energy) | phase<<16 (t mod day_length)
@@ -138,9 +141,20 @@ struct Header {
     uint32_t obs_mode, max_episode_steps, day_length;
     uint32_t cap_zombie, cap_cow, cap_skeleton, cap_arrow, cap_plant;
     uint64_t atlas_seed;
-    uint64_t off_luts, off_recs, off_maps, off_done, total;
+    uint64_t off_ctrs, off_luts, off_recs, off_maps, off_tags, off_regen0, off_regen1, off_slow, total;
 };
-// two device-side counters of the done list live in the first 256 bytes of the state blob
+// Device-side counters of the Classic variant: one uint32 per 256 bytes (counters hit by atomics
+// from many blocks must not share a memory channel), in their own area of the state blob.
+//   SEQ     number of step launches so far + 1
+//   TOP     groups of blocks of the current step launch that have all started
+//   SLOW    entries in the slow list; SLOW_FINISHED: slow-list blocks finished
+//   GROUP+g blocks of group g of the current step launch that have started (64 groups)
+//   REGEN+p*16+s entries in sub-list s of regeneration list p
+constexpr int CTR_STRIDE = 64;   // dwords between counters
+constexpr int NGROUP = 64, NSUB = 16;
+enum Counter : int { CT_SEQ = 0, CT_TOP = 1, CT_SLOW = 2, CT_SLOW_FINISHED = 3, CT_GROUP = 4, CT_REGEN = CT_GROUP + NGROUP,
+                     CT_COUNT = CT_REGEN + 2 * NSUB };
+// the done-list counters of the full-Craftax variant live in the first 256 bytes of its state blob
 constexpr uint64_t DONE_COUNT_OFFSET = 192;
 static_assert(sizeof(Header) <= DONE_COUNT_OFFSET, "header overlaps the done-list counters");
 constexpr uint64_t MAGIC = 0x43524146544158ull;  // "CRAFTAX"
@@ -192,6 +206,12 @@ __device__ inline void group_sync()
 __device__ inline int map_index(int x, int y)
 {
     return (((y >> 3) << 2) + (x >> 4)) * 128 + ((y & 7) << 4) + (x & 15);
+}
+
+// byte offset of the map of `episode` of environment `env` inside the maps area
+__host__ __device__ inline size_t map_offset(uint32_t env, uint32_t episode)
+{
+    return ((size_t)env * 2 + (episode & 1u)) * (size_t)(MAPW * MAPW);
 }
 
 __device__ inline bool in_map(int x, int y) { return ((unsigned)x | (unsigned)y) < (unsigned)MAPW; }

@@ -50,67 +50,148 @@ __device__ inline void store_record(int l, uint4* __restrict__ grec, const uint3
 }
 
 // ---------------------------------------------------------------------------------------------
-// reset: one block per environment (appendix "Optimistic Environment Resets" explains why
-// world generation is the expensive part; here it is spread over 512 threads).
+// Worlds are generated ahead of time (appendix "Optimistic Environment Resets" explains why
+// world generation is the expensive part of a reset): map slot e & 1 holds the world of
+// episode e, the other slot the world of episode e + 1.  An episode that ends switches slots
+// inside the step kernel and puts the environment on a regeneration list; extra blocks of the
+// NEXT step launch fill the freed slot with the world after next, in the shadow of the step
+// blocks.  A tag per environment says which episode its spare slot holds and which launch wrote
+// it; a spare is only trusted when an earlier launch wrote it.  The spare of an episode is
+// generated during that episode's first step, so only an episode that ends at its first step
+// finds it missing; a fresh episode cannot (full vitals, cleared start area, no mobs) unless the
+// episode cap is 1.  Such episodes go on the slow list, which k_reset_list serves right after
+// the step kernel; it is launched only for an episode cap of 1.  craftax_reset and
+// craftax_import_envs generate the spare themselves.
+// A list entry carries what world generation needs: (env, seed low, seed high, episode index);
+// env = ENTRY_VOID marks an entry cancelled by an import.
+// Each regeneration list is cut into NSUB sub-lists with their own counters (blocks append to
+// sub-list blockIdx mod NSUB), so that the appending atomics do not queue up on one address;
+// sub_cap is the capacity of a sub-list.
+struct Lists { uint32_t* ctr; uint4* regen[2]; uint4* slow; uint2* tags; uint32_t sub_cap; };
+__device__ inline uint32_t* counter(const Lists& ls, int i) { return ls.ctr + (size_t)i * CTR_STRIDE; }
+constexpr uint32_t TAG_NONE = 0xFFFFFFFFu, ENTRY_VOID = 0xFFFFFFFFu;
+
+// reset: two blocks per environment, for the worlds of episodes 0 and 1
 __global__ __launch_bounds__(WG_THREADS) void k_reset(uint4* __restrict__ recs, uint8_t* __restrict__ maps,
-                                                 const uint64_t* __restrict__ seeds, uint32_t* done_count,
-                                                 uint32_t* done_finished, Params p)
+                                                 const uint64_t* __restrict__ seeds, Lists ls)
 {
-    if (blockIdx.x == 0 && threadIdx.x == 0) { *done_count = 0u; *done_finished = 0u; }
+    if (blockIdx.x == 0 && threadIdx.x < CT_COUNT) *counter(ls, threadIdx.x) = threadIdx.x == CT_SEQ ? 1u : 0u;
     __shared__ uint16_t s_lat[LAT_BLOCKS * 8];
-    const uint32_t env = blockIdx.x;
+    const uint32_t env = blockIdx.x >> 1, ep = blockIdx.x & 1u;
     const uint64_t seed = seeds[env];
     const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
-    worldgen_block(maps + (size_t)env * (MAPW * MAPW), s_lat, lo, hi, env, 0u);
-    if (threadIdx.x < REC_DWORDS)
-        reinterpret_cast<uint32_t*>(recs + (size_t)env * 8)[threadIdx.x] = fresh_record_word(threadIdx.x, lo, hi, 0u);
+    worldgen_block(maps + map_offset(env, ep), s_lat, lo, hi, env, ep);
+    if (ep == 0) {
+        if (threadIdx.x < REC_DWORDS)
+            reinterpret_cast<uint32_t*>(recs + (size_t)env * 8)[threadIdx.x] = fresh_record_word(threadIdx.x, lo, hi, 0u);
+    } else if (threadIdx.x == 0) ls.tags[env] = make_uint2(1u, 0u);
+}
+
+// A regeneration block of the step grid: worlds for the episodes after next of the episodes that
+// ended in the previous launch.
+__device__ __forceinline__ void regeneration_block(uint8_t* __restrict__ maps, const Lists& ls, uint32_t seq, uint32_t count,
+                                                   uint32_t rb, uint32_t nrb, uint16_t* s_lat)
+{
+    const uint32_t which = (seq & 1u) ^ 1u, sub = rb % NSUB;
+    const uint4* list = ls.regen[which] + (size_t)sub * ls.sub_cap;
+    for (uint32_t i = rb / NSUB; i < count; i += nrb / NSUB) {
+        const uint4 entry = list[i];
+        if (entry.x == ENTRY_VOID) continue;
+        worldgen_block<BLOCK>(maps + map_offset(entry.x, entry.w), s_lat, entry.y, entry.z, entry.x, entry.w);
+        if (threadIdx.x == 0) ls.tags[entry.x] = make_uint2(entry.w, seq);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
-// step: G lanes per environment, 256/G environments per block.  Environments whose episode
-// ended are not written back; their indices are appended to the state's done list, which
-// k_reset_list consumes right after (same stream), spreading world generation over the
-// whole chip instead of stretching the tail of a few step blocks.
-// a list entry carries what the reset needs: (env, seed low, seed high, next episode index)
-struct DoneList { uint32_t* count; uint32_t* finished; uint4* list; };
-
+// step: G lanes per environment, 256/G environments per block, followed in the same grid by
+// the regeneration blocks for the episodes that ended in the previous launch.
 template <int G, int OBS_MODE>
 __global__ __launch_bounds__(BLOCK, 4) void k_step(uint4* __restrict__ recs, uint8_t* __restrict__ maps,
                                                    const Luts* __restrict__ luts, const int32_t* __restrict__ actions,
                                                    uint8_t* __restrict__ obs, float* __restrict__ reward,
-                                                   uint8_t* __restrict__ done, DoneList dl, Params p)
+                                                   uint8_t* __restrict__ done, Lists ls, Params p, int step_blocks)
 {
     constexpr int EPB = Grp<G>::EPB;
     __shared__ uint32_t s_env[EPB * LDS_ENV_DWORDS];
     __shared__ int s_ndone;
     __shared__ uint32_t s_base;
     __shared__ uint4 s_list[EPB];
+    const int tid = threadIdx.x;
+    // Launch number.  Every block reads it (and, as a regeneration block, the length of its
+    // sub-list) and then counts itself in; once all blocks of the launch have done so, one thread
+    // advances the number and empties the lists this launch consumes.  Counting is in two levels
+    // (NGROUP group counters, then one on top) so that no counter sees more than a few dozen atomics.
+    const uint32_t seq = *counter(ls, CT_SEQ);
+    const bool regen_role = (int)blockIdx.x >= step_blocks;
+    const uint32_t rb = blockIdx.x - (uint32_t)step_blocks, nrb = gridDim.x - (uint32_t)step_blocks;
+    uint32_t regen_count = 0u;
+    if (regen_role) regen_count = *counter(ls, CT_REGEN + (int)(((seq & 1u) ^ 1u) * NSUB + rb % NSUB));
+    const uint32_t gsize = (gridDim.x + NGROUP - 1) / NGROUP, grp = blockIdx.x / gsize;
+    uint32_t started = 0u;
+    asm volatile("" :: "v"(seq), "v"(regen_count) : "memory");   // both values have arrived before this block counts itself in
+    if (tid == 0) started = atomicAdd(counter(ls, CT_GROUP + (int)grp), 1u);
+    auto leave = [&]() {
+        if (tid != 0) return;
+        const uint32_t members = min(gsize, gridDim.x - grp * gsize), ngroups = (gridDim.x + gsize - 1) / gsize;
+        if (started != members - 1u) return;
+        *counter(ls, CT_GROUP + (int)grp) = 0u;
+        if (atomicAdd(counter(ls, CT_TOP), 1u) != ngroups - 1u) return;
+        *counter(ls, CT_TOP) = 0u;
+        for (int sub = 0; sub < NSUB; ++sub) *counter(ls, CT_REGEN + (int)(((seq & 1u) ^ 1u) * NSUB) + sub) = 0u;
+        *counter(ls, CT_SEQ) = seq + 1u;
+    };
 
-    const int tid = threadIdx.x, g = tid / G, l = tid % G;
+    if (regen_role) {
+        if (rb / NSUB < regen_count)
+            regeneration_block(maps, ls, seq, regen_count, rb, nrb, reinterpret_cast<uint16_t*>(s_env));
+        leave();
+        return;
+    }
+
+    const int g = tid / G, l = tid % G;
     const int env = blockIdx.x * EPB + g;
     const bool active = env < p.n;
     if (tid == 0) s_ndone = 0;
     __syncthreads();
     uint32_t* e = s_env + g * LDS_ENV_DWORDS;
-    uint8_t* map = maps + (size_t)(active ? env : 0) * (MAPW * MAPW);
     constexpr bool kSymbolic = OBS_MODE != CRAFTAX_OBS_PIXELS_F32;
     constexpr bool kBytes = OBS_MODE == CRAFTAX_OBS_SYM_U8_I8 || OBS_MODE == CRAFTAX_OBS_SYM_U8_F32;
     bool staged = false;
     if (active) {
         load_record<G>(l, recs + (size_t)env * 8, e);
         group_sync();
-        const StepOut o = step_env<G>(l, (uint32_t)env, e, map, luts, actions[env], p);
+        const uint32_t* rec = e + LDS_REC;
+        const uint32_t ep = rec[RW_EPISODE], lo = rec[RW_SEED_LO], hi = rec[RW_SEED_HI];
+        StepOut o = step_env<G>(l, (uint32_t)env, e, maps + map_offset((uint32_t)env, ep), luts, actions[env], p);
         if (l == 0) { reward[env] = o.reward; done[env] = o.done ? 1 : 0; }
-        if (!o.done) {
+        bool write_back = !o.done;
+        if (o.done) {
+            // the record in LDS is still the episode that just ended
+            const uint2 tag = ls.tags[env];
+            if (tag.x == ep + 1u && tag.y < seq) {
+                // the next world is waiting in the other slot: start the new episode right here
+                group_sync();
+#pragma unroll
+                for (int it = 0; it < (REC_DWORDS + G - 1) / G; ++it) {
+                    const int i = l + it * G;
+                    if (i < REC_DWORDS) e[LDS_REC + i] = fresh_record_word(i, lo, hi, ep + 1u);
+                }
+                load_window<G>(l, MAPW / 2, MAPW / 2, maps + map_offset((uint32_t)env, ep + 1u), e + LDS_WIN);
+                group_sync();
+                o.mvx = 0; o.mvy = 0; o.woff = (MAPW / 2 - WIN_COLS / 2) & 3;
+                write_back = true;
+                if (l == 0) s_list[atomicAdd(&s_ndone, 1)] = make_uint4((uint32_t)env, lo, hi, ep + 2u);
+            } else if (l == 0) {
+                ls.slow[atomicAdd(counter(ls, CT_SLOW), 1u)] = make_uint4((uint32_t)env, lo, hi, ep + 1u);
+            }
+        }
+        if (write_back) {
             store_record<G>(l, recs + (size_t)env * 8, e);
             if (kSymbolic && obs != nullptr) {
                 // byte layouts are staged in LDS here and written by the whole wave below
                 render_symbolic<G, OBS_MODE, true, !kBytes>(l, e, o.mvx, o.mvy, o.woff, luts, obs + (size_t)env * obs_stride(OBS_MODE));
                 staged = kBytes;
             }
-        } else if (l == 0) {
-            const uint32_t* rec = e + LDS_REC;   // not written back: still the episode that just ended
-            s_list[atomicAdd(&s_ndone, 1)] = make_uint4((uint32_t)env, rec[RW_SEED_LO], rec[RW_SEED_HI], rec[RW_EPISODE] + 1u);
         }
     }
     if (kBytes && obs != nullptr) {
@@ -121,48 +202,51 @@ __global__ __launch_bounds__(BLOCK, 4) void k_step(uint4* __restrict__ recs, uin
                                              obs + (size_t)(blockIdx.x * EPB + first) * obs_stride(OBS_MODE));
     }
     __syncthreads();
+    leave();
     const int nd = s_ndone;
     if (nd == 0) return;
-    if (tid == 0) s_base = atomicAdd(dl.count, (uint32_t)nd);
+    const uint32_t sub = blockIdx.x % NSUB;
+    if (tid == 0) s_base = atomicAdd(counter(ls, CT_REGEN + (int)((seq & 1u) * NSUB + sub)), (uint32_t)nd);
     __syncthreads();
-    if (tid < nd) dl.list[s_base + tid] = s_list[tid];
+    if (tid < nd) ls.regen[seq & 1u][(size_t)sub * ls.sub_cap + s_base + tid] = s_list[tid];
 }
 
-// Regenerates every environment on the done list (one block each, looping if the list is
-// longer than the grid), renders its first observation, and clears the list for the next step.
+// Serves the slow list: generates the world of the new episode in place (one block each, looping
+// if the list is longer than the grid), writes the fresh record, renders the first observation,
+// and asks the next step launch to generate the world after it.  Runs after the step kernel (which
+// has already advanced the launch number), and only when the episode cap is 1.
 template <int OBS_MODE>
 __global__ __launch_bounds__(WG_THREADS) void k_reset_list(uint4* __restrict__ recs, uint8_t* __restrict__ maps,
                                                       const Luts* __restrict__ luts, uint8_t* __restrict__ obs,
-                                                      DoneList dl, Params p)
+                                                      Lists ls, Params p, int envs_per_step_block)
 {
     constexpr int G = 16;
     __shared__ uint16_t s_lat[LAT_BLOCKS * 8];
     __shared__ uint32_t s_env[LDS_ENV_DWORDS];
-    uint4 entry = dl.list[blockIdx.x];   // fetched together with the count; ignored if beyond it
+    const int tid = threadIdx.x;
+    const uint32_t count = *counter(ls, CT_SLOW);
+    if (blockIdx.x >= count) return;
+    const uint32_t next = (*counter(ls, CT_SEQ) & 1u) ^ 1u;      // the list the next launch's regeneration blocks will read
     // the scalars of a fresh episode are constants: fetch their table entries before anything else
     const float fresh_tenth = luts->tenth[MAX_COUNT], fresh_day = luts->daylight[0];
     const uint32_t fresh_q7 = luts->light_q7[0];
-    const uint32_t count = *dl.count;
-    if (blockIdx.x >= count) return;
-    const int tid = threadIdx.x;
-    // Every working block has now read the count; the last one to say so clears the list for
-    // the next step (entries are only appended by the next step kernel, after this one ends).
-    if (tid == 0) {
-        const uint32_t workers = count < gridDim.x ? count : gridDim.x;
-        if (atomicAdd(dl.finished, 1u) == workers - 1u) { *dl.count = 0u; *dl.finished = 0u; }
-    }
     constexpr bool kSymbolic = OBS_MODE != CRAFTAX_OBS_PIXELS_F32;
     for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
-        if (i != blockIdx.x) entry = dl.list[i];
+        const uint4 entry = ls.slow[i];
+        if (entry.x == ENTRY_VOID) continue;
         const uint32_t env = entry.x, lo = entry.y, hi = entry.z, ep = entry.w;
         uint32_t* grec = reinterpret_cast<uint32_t*>(recs + (size_t)env * 8);
-        uint8_t* map = maps + (size_t)env * (MAPW * MAPW);
         if (tid >= 64 && tid < 64 + REC_DWORDS) {              // wave 1 writes the record, wave 0 will render
             const uint32_t w = fresh_record_word(tid - 64, lo, hi, ep);
             grec[tid - 64] = w;
             s_env[LDS_REC + tid - 64] = w;
         }
-        worldgen_block(map, s_lat, lo, hi, env, ep, s_env + LDS_WIN);   // ends with a block barrier
+        if (tid == 96) {   // same sub-list as the environment's step block uses, so that no sub-list can overflow
+            const uint32_t sub = (env / (uint32_t)envs_per_step_block) % NSUB;
+            const uint32_t at = atomicAdd(counter(ls, CT_REGEN + (int)(next * NSUB + sub)), 1u);
+            ls.regen[next][(size_t)sub * ls.sub_cap + at] = make_uint4(env, lo, hi, ep + 1u);
+        }
+        worldgen_block(maps + map_offset(env, ep), s_lat, lo, hi, env, ep, s_env + LDS_WIN);   // ends with a block barrier
         if (kSymbolic && obs != nullptr && tid < G) {
             // scalars of a fresh episode: empty inventory, vitals 9, facing down, noon, awake
             uint32_t* vec = s_env + LDS_VEC;
@@ -183,6 +267,11 @@ __global__ __launch_bounds__(WG_THREADS) void k_reset_list(uint4* __restrict__ r
         }
         __syncthreads();
     }
+    // the last working block empties the list
+    if (tid == 0) {
+        const uint32_t workers = count < gridDim.x ? count : gridDim.x;
+        if (atomicAdd(counter(ls, CT_SLOW_FINISHED), 1u) == workers - 1u) { *counter(ls, CT_SLOW) = 0u; *counter(ls, CT_SLOW_FINISHED) = 0u; }
+    }
 }
 
 template <int OBS_MODE>
@@ -199,7 +288,7 @@ __global__ __launch_bounds__(BLOCK) void k_observe(const uint4* __restrict__ rec
     group_sync();
     const uint32_t w_pos = e[LDS_REC + RW_POS];
     const int px = w_pos & 0xFF;
-    load_window<G>(l, px, (w_pos >> 8) & 0xFF, maps + (size_t)env * (MAPW * MAPW), e + LDS_WIN);
+    load_window<G>(l, px, (w_pos >> 8) & 0xFF, maps + map_offset((uint32_t)env, e[LDS_REC + RW_EPISODE]), e + LDS_WIN);
     group_sync();
     render_symbolic<G, OBS_MODE>(l, e, 0, 0, (px - WIN_COLS / 2) & 3, luts, obs + (size_t)env * obs_stride(OBS_MODE));
 }
@@ -213,7 +302,7 @@ __global__ __launch_bounds__(BLOCK) void k_pixels(const uint4* __restrict__ recs
     if (threadIdx.x < REC_DWORDS) s_rec[threadIdx.x] = reinterpret_cast<const uint32_t*>(recs + (size_t)env * 8)[threadIdx.x];
     __syncthreads();
     float* out = reinterpret_cast<float*>(obs + (size_t)env * OBS_STRIDE_PIXELS);
-    render_pixels_block(s_rec, maps + (size_t)env * (MAPW * MAPW), luts, out, s_tile, s_ent);
+    render_pixels_block(s_rec, maps + map_offset((uint32_t)env, s_rec[RW_EPISODE]), luts, out, s_tile, s_ent);
     if (threadIdx.x == 0) out[63 * 63 * 3] = 0.0f;   // the stride's padding word
 }
 
@@ -224,13 +313,13 @@ __global__ __launch_bounds__(BLOCK) void k_export(const uint4* __restrict__ recs
 {
     const int env = first + blockIdx.x, tid = threadIdx.x;
     craftax_env_dump* d = dumps + blockIdx.x;
-    {   // 16-byte piece tid of the tiled map = row (tid & 7) of tile (tid >> 3) -> row-major dump
-        const int tile = tid >> 3, y = ((tile >> 2) << 3) + (tid & 7), x = (tile & 3) << 4;
-        *reinterpret_cast<uint4*>(d->map + y * MAPW + x) = reinterpret_cast<const uint4*>(maps + (size_t)env * (MAPW * MAPW))[tid];
-    }
     __shared__ uint32_t r[REC_DWORDS];
     if (tid < REC_DWORDS) r[tid] = reinterpret_cast<const uint32_t*>(recs + (size_t)env * 8)[tid];
     __syncthreads();
+    {   // 16-byte piece tid of the tiled map = row (tid & 7) of tile (tid >> 3) -> row-major dump
+        const int tile = tid >> 3, y = ((tile >> 2) << 3) + (tid & 7), x = (tile & 3) << 4;
+        *reinterpret_cast<uint4*>(d->map + y * MAPW + x) = reinterpret_cast<const uint4*>(maps + map_offset((uint32_t)env, r[RW_EPISODE]))[tid];
+    }
     if (tid == 0) {
         d->px = r[RW_POS] & 0xFF; d->py = (r[RW_POS] >> 8) & 0xFF; d->dir = (r[RW_POS] >> 16) & 0xFF; d->sleeping = r[RW_POS] >> 24;
         for (int i = 0; i < 6; ++i) { d->inv[i] = (r[RW_INV] >> (4 * i)) & 15; d->inv[6 + i] = (r[RW_INV] >> (24 + i)) & 1; }
@@ -255,14 +344,20 @@ __global__ __launch_bounds__(BLOCK) void k_export(const uint4* __restrict__ recs
 
 // Import packs into the record's bit fields: counts and vitals must be 0..15, counters
 // -128..127, mob hp and cooldown 0..15, coordinates 0..63 (every state the rules can reach is).
-__global__ __launch_bounds__(BLOCK) void k_import(uint4* __restrict__ recs, uint8_t* __restrict__ maps,
+__global__ __launch_bounds__(BLOCK) void k_import(uint4* __restrict__ recs, uint8_t* __restrict__ maps, Lists ls,
                                                   const craftax_env_dump* __restrict__ dumps, int first, Params p)
 {
     const int env = first + blockIdx.x, tid = threadIdx.x;
     const craftax_env_dump* d = dumps + blockIdx.x;
     {
         const int tile = tid >> 3, y = ((tile >> 2) << 3) + (tid & 7), x = (tile & 3) << 4;
-        reinterpret_cast<uint4*>(maps + (size_t)env * (MAPW * MAPW))[tid] = *reinterpret_cast<const uint4*>(d->map + y * MAPW + x);
+        reinterpret_cast<uint4*>(maps + map_offset((uint32_t)env, d->episode))[tid] = *reinterpret_cast<const uint4*>(d->map + y * MAPW + x);
+    }
+    // whatever was queued for this environment belongs to the episode that is being replaced
+    for (int li = 0; li < 2 * NSUB + 1; ++li) {
+        uint4* list = li < 2 * NSUB ? ls.regen[li / NSUB] + (size_t)(li % NSUB) * ls.sub_cap : ls.slow;
+        const uint32_t cnt = *counter(ls, li < 2 * NSUB ? CT_REGEN + li : CT_SLOW);
+        for (uint32_t i = tid; i < cnt; i += BLOCK) if (list[i].x == (uint32_t)env) list[i].x = ENTRY_VOID;
     }
     __shared__ uint32_t r[REC_DWORDS];
     if (tid < REC_DWORDS) r[tid] = 0;
@@ -296,6 +391,17 @@ __global__ __launch_bounds__(BLOCK) void k_import(uint4* __restrict__ recs, uint
     }
     __syncthreads();
     if (tid < REC_DWORDS) reinterpret_cast<uint32_t*>(recs + (size_t)env * 8)[tid] = r[tid];
+}
+
+// after an import: the world of the episode after the imported one, into the spare slot
+__global__ __launch_bounds__(WG_THREADS) void k_import_spare(const uint4* __restrict__ recs, uint8_t* __restrict__ maps, Lists ls, int first)
+{
+    __shared__ uint16_t s_lat[LAT_BLOCKS * 8];
+    const uint32_t env = (uint32_t)first + blockIdx.x;
+    const uint32_t* r = reinterpret_cast<const uint32_t*>(recs + (size_t)env * 8);
+    const uint32_t ep = r[RW_EPISODE] + 1u, lo = r[RW_SEED_LO], hi = r[RW_SEED_HI];
+    worldgen_block(maps + map_offset(env, ep), s_lat, lo, hi, env, ep);
+    if (threadIdx.x == 0) ls.tags[env] = make_uint2(ep, 0u);
 }
 
 // synthetic action stream (input generation for benchmarks; not part of the simulator)
@@ -346,6 +452,14 @@ static bool config_ok(const craftax_config* c, std::string* why)
 
 static uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
+// Entries a regeneration sub-list must hold: every environment of the step blocks that append to
+// it, for the narrowest lane group (most environments per block).
+static uint64_t sub_list_capacity(int n)
+{
+    const uint64_t epb = 64, blocks = ((uint64_t)n + epb - 1) / epb;
+    return ((blocks + NSUB - 1) / NSUB) * epb + epb;
+}
+
 static Header make_header(const craftax_config* c, int n)
 {
     Header h;
@@ -354,11 +468,16 @@ static Header make_header(const craftax_config* c, int n)
     h.obs_mode = c->obs_mode; h.max_episode_steps = c->max_episode_steps; h.day_length = c->day_length;
     h.cap_zombie = c->cap_zombie; h.cap_cow = c->cap_cow; h.cap_skeleton = c->cap_skeleton;
     h.cap_arrow = c->cap_arrow; h.cap_plant = c->cap_plant; h.atlas_seed = c->atlas_seed;
-    h.off_luts = 256;
+    h.off_ctrs = 256;
+    h.off_luts = h.off_ctrs + (uint64_t)CT_COUNT * CTR_STRIDE * 4;
     h.off_recs = round_up(h.off_luts + sizeof(Luts), 256);
     h.off_maps = h.off_recs + (uint64_t)n * (REC_DWORDS * 4);
-    h.off_done = h.off_maps + (uint64_t)n * (MAPW * MAPW);
-    h.total = round_up(h.off_done + (uint64_t)n * 16, 256);
+    h.off_tags = h.off_maps + (uint64_t)n * 2 * (MAPW * MAPW);     // two map slots per environment
+    h.off_regen0 = round_up(h.off_tags + (uint64_t)n * 8, 256);
+    const uint64_t list_bytes = (uint64_t)NSUB * sub_list_capacity(n) * 16;
+    h.off_regen1 = h.off_regen0 + list_bytes;
+    h.off_slow = h.off_regen1 + list_bytes;
+    h.total = round_up(h.off_slow + (uint64_t)n * 16, 256);
     return h;
 }
 
@@ -419,7 +538,7 @@ static int check_launch(const char* what)
     return CRAFTAX_OK;
 }
 
-struct Ptrs { uint4* recs; uint8_t* maps; const Luts* luts; DoneList dl; };
+struct Ptrs { uint4* recs; uint8_t* maps; const Luts* luts; Lists ls; };
 static Ptrs pointers(const void* state, const HostState& s)
 {
     uint8_t* base = const_cast<uint8_t*>(static_cast<const uint8_t*>(state));
@@ -427,9 +546,12 @@ static Ptrs pointers(const void* state, const HostState& s)
     q.luts = reinterpret_cast<const Luts*>(base + s.hdr.off_luts);
     q.recs = reinterpret_cast<uint4*>(base + s.hdr.off_recs);
     q.maps = base + s.hdr.off_maps;
-    q.dl.count = reinterpret_cast<uint32_t*>(base + DONE_COUNT_OFFSET);
-    q.dl.finished = q.dl.count + 1;
-    q.dl.list = reinterpret_cast<uint4*>(base + s.hdr.off_done);
+    q.ls.ctr = reinterpret_cast<uint32_t*>(base + s.hdr.off_ctrs);
+    q.ls.sub_cap = (uint32_t)sub_list_capacity(s.n);
+    q.ls.regen[0] = reinterpret_cast<uint4*>(base + s.hdr.off_regen0);
+    q.ls.regen[1] = reinterpret_cast<uint4*>(base + s.hdr.off_regen1);
+    q.ls.slow = reinterpret_cast<uint4*>(base + s.hdr.off_slow);
+    q.ls.tags = reinterpret_cast<uint2*>(base + s.hdr.off_tags);
     return q;
 }
 
@@ -445,17 +567,21 @@ static int group_lanes(int n)
     return n >= 32768 ? 4 : (n >= 8192 ? 8 : 16);
 }
 
-constexpr int RESET_GRID = 512;   // blocks of k_reset_list; those beyond the list exit at once
+constexpr int RESET_GRID = 64;    // blocks of k_reset_list (the slow list is nearly always empty); each loops over the list
+constexpr int REGEN_BLOCKS = 512; // regeneration blocks appended to the step grid; those beyond the list exit at once
 
 template <int OBS_MODE>
 static void launch_step(int G, int n, hipStream_t st, const Ptrs& q, const int32_t* actions, uint8_t* o, float* reward,
                         uint8_t* done, const Params& p)
 {
     const dim3 block(BLOCK);
-    if (G == 4) hipLaunchKernelGGL((k_step<4, OBS_MODE>), dim3((n + 63) / 64), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.dl, p);
-    else if (G == 8) hipLaunchKernelGGL((k_step<8, OBS_MODE>), dim3((n + 31) / 32), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.dl, p);
-    else hipLaunchKernelGGL((k_step<16, OBS_MODE>), dim3((n + 15) / 16), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.dl, p);
-    hipLaunchKernelGGL((k_reset_list<OBS_MODE>), dim3(n < RESET_GRID ? n : RESET_GRID), dim3(WG_THREADS), 0, st, q.recs, q.maps, q.luts, o, q.dl, p);
+    const int regen = ((n < REGEN_BLOCKS ? n : REGEN_BLOCKS) + NSUB - 1) / NSUB * NSUB;   // a multiple of the sub-list count
+    const int sb = (n + 256 / G - 1) / (256 / G);
+    if (G == 4) hipLaunchKernelGGL((k_step<4, OBS_MODE>), dim3(sb + regen), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.ls, p, sb);
+    else if (G == 8) hipLaunchKernelGGL((k_step<8, OBS_MODE>), dim3(sb + regen), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.ls, p, sb);
+    else hipLaunchKernelGGL((k_step<16, OBS_MODE>), dim3(sb + regen), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.ls, p, sb);
+    if (p.max_episode_steps == 1u)   // the only way an episode can end before its spare world exists
+        hipLaunchKernelGGL((k_reset_list<OBS_MODE>), dim3(n < RESET_GRID ? n : RESET_GRID), dim3(WG_THREADS), 0, st, q.recs, q.maps, q.luts, o, q.ls, p, 256 / G);
 }
 
 }  // namespace cx
@@ -553,8 +679,7 @@ int craftax_reset(void* state, const uint64_t* seeds, int n, void* stream)
         return rc ? fail(rc, err) : rc;
     }
     const Ptrs q = pointers(state, s);
-    hipLaunchKernelGGL(k_reset, dim3(n), dim3(WG_THREADS), 0, (hipStream_t)stream, q.recs, q.maps, seeds, q.dl.count, q.dl.finished,
-                       make_params(s));
+    hipLaunchKernelGGL(k_reset, dim3(2u * (unsigned)n), dim3(WG_THREADS), 0, (hipStream_t)stream, q.recs, q.maps, seeds, q.ls);
     return check_launch("craftax_reset");
 }
 
@@ -642,8 +767,9 @@ int craftax_import_envs(void* state, int first, int count, const void* dumps, vo
         return rc ? fail(rc, err) : rc;
     }
     const Ptrs q = pointers(state, s);
-    hipLaunchKernelGGL(k_import, dim3(count), dim3(BLOCK), 0, (hipStream_t)stream, q.recs, q.maps,
+    hipLaunchKernelGGL(k_import, dim3(count), dim3(BLOCK), 0, (hipStream_t)stream, q.recs, q.maps, q.ls,
                        static_cast<const craftax_env_dump*>(dumps), first, make_params(s));
+    hipLaunchKernelGGL(k_import_spare, dim3(count), dim3(WG_THREADS), 0, (hipStream_t)stream, q.recs, q.maps, q.ls, first);
     return check_launch("craftax_import_envs");
 }
 

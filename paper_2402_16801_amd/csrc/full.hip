@@ -19,7 +19,7 @@ static_assert(sizeof(craftax_full_env_dump) == 63432, "canonical dump layout");
 
 // a list entry carries what the reset needs: (env, seed low, seed high, next episode index)
 struct DoneList { uint32_t* count; uint32_t* finished; uint4* list; };
-constexpr int RESET_GRID = 512;
+constexpr int RESET_SLOTS = 64;   // environments regenerated at once by kf_reset_list (nine blocks each)
 
 __device__ inline uint32_t pack_regs(const MobRegs& m)
 {
@@ -29,7 +29,8 @@ __device__ inline uint32_t pack_regs(const MobRegs& m)
 }
 
 // ---------------------------------------------------------------------------------------------
-// reset of every environment: one block each
+// reset of every environment: one block per (environment, floor); the block of floor 0 also
+// writes the fresh record and the empty mob tables
 __global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
                                                        const uint64_t* __restrict__ seeds, uint32_t* done_count,
                                                        uint32_t* done_finished)
@@ -37,12 +38,14 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ e
     if (blockIdx.x == 0 && threadIdx.x == 0) { *done_count = 0u; *done_finished = 0u; }
     __shared__ uint16_t s_lat[LAT_TOTAL];
     __shared__ GenLayout s_layout;
-    const uint32_t env = blockIdx.x;
+    const uint32_t env = blockIdx.x / FLOORS;
+    const int f = blockIdx.x % FLOORS;
     const uint64_t seed = seeds[env];
     const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
-    worldgen_block(maps + (size_t)env * MAP_BYTES, s_lat, s_layout, lo, hi, env, 0u);
+    worldgen_floor_block(maps + (size_t)env * MAP_BYTES, s_lat, s_layout, lo, hi, env, 0u, f);
     const int tid = threadIdx.x;
-    if (tid < ENV_DWORDS) envs[(size_t)env * ENV_DWORDS + tid] = tid < REC_DWORDS ? fresh_record_word(tid, s_layout, lo, hi, 0u) : 0u;
+    if (f == 0 && tid < ENV_DWORDS)
+        envs[(size_t)env * ENV_DWORDS + tid] = tid < REC_DWORDS ? fresh_record_word(tid, s_layout, lo, hi, 0u) : 0u;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -85,8 +88,9 @@ __global__ __launch_bounds__(BLOCK) void kf_step(uint32_t* __restrict__ envs, ui
         render_env<F32>(l, e, o.wx0, o.wy0, m.alive, m.x, m.y, m.type, luts, obs + (size_t)env * (F32 ? STRIDE_F32 : STRIDE_U8));
 }
 
-// Regenerates every environment on the done list (one block each, looping if the list is longer
-// than the grid), renders its first observation, and clears the list for the next step.
+// Regenerates every environment on the done list, nine blocks (one per floor) each, looping if
+// the list is longer than the grid; the block of floor 0 also writes the fresh record and renders
+// the first observation.  The last working block clears the list for the next step.
 template <bool F32>
 __global__ __launch_bounds__(GEN_THREADS) void kf_reset_list(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
                                                             const Luts* __restrict__ luts, uint8_t* __restrict__ obs, DoneList dl)
@@ -95,28 +99,32 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_reset_list(uint32_t* __restric
     __shared__ GenLayout s_layout;
     __shared__ uint32_t s_env[L_ENV_DWORDS];
     const uint32_t count = *dl.count;
-    if (blockIdx.x >= count) return;
+    const uint32_t slot = blockIdx.x / FLOORS, slots = gridDim.x / FLOORS;
+    const int f = blockIdx.x % FLOORS;
+    if (slot >= count) return;
     const int tid = threadIdx.x;
     // every working block has read the count; the last one to say so clears the list for the
     // next step (entries are only appended by the next step kernel, after this one ends)
     if (tid == 0) {
-        const uint32_t workers = count < gridDim.x ? count : gridDim.x;
+        const uint32_t workers = (count < slots ? count : slots) * FLOORS;
         if (atomicAdd(dl.finished, 1u) == workers - 1u) { *dl.count = 0u; *dl.finished = 0u; }
     }
-    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
+    for (uint32_t i = slot; i < count; i += slots) {
         const uint4 entry = dl.list[i];
         const uint32_t env = entry.x, lo = entry.y, hi = entry.z, ep = entry.w;
-        worldgen_block(maps + (size_t)env * MAP_BYTES, s_lat, s_layout, lo, hi, env, ep,
-                       reinterpret_cast<uint8_t*>(s_env + L_WB), reinterpret_cast<uint8_t*>(s_env + L_WI));
-        if (tid < ENV_DWORDS) {
-            const uint32_t w = tid < REC_DWORDS ? fresh_record_word(tid, s_layout, lo, hi, ep) : 0u;
-            envs[(size_t)env * ENV_DWORDS + tid] = w;
-            if (tid < REC_DWORDS) s_env[L_REC + tid] = w;
+        worldgen_floor_block(maps + (size_t)env * MAP_BYTES, s_lat, s_layout, lo, hi, env, ep, f,
+                             reinterpret_cast<uint8_t*>(s_env + L_WB), reinterpret_cast<uint8_t*>(s_env + L_WI));
+        if (f == 0) {
+            if (tid < ENV_DWORDS) {
+                const uint32_t w = tid < REC_DWORDS ? fresh_record_word(tid, s_layout, lo, hi, ep) : 0u;
+                envs[(size_t)env * ENV_DWORDS + tid] = w;
+                if (tid < REC_DWORDS) s_env[L_REC + tid] = w;
+            }
+            __syncthreads();
+            if (obs != nullptr && tid < 64)
+                render_env<F32>(tid, s_env, W / 2 - WIN_COLS / 2, W / 2 - WIN_ROWS / 2, 0, 0, 0, 0, luts,
+                                obs + (size_t)env * (F32 ? STRIDE_F32 : STRIDE_U8));
         }
-        __syncthreads();
-        if (obs != nullptr && tid < 64)
-            render_env<F32>(tid, s_env, W / 2 - WIN_COLS / 2, W / 2 - WIN_ROWS / 2, 0, 0, 0, 0, luts,
-                            obs + (size_t)env * (F32 ? STRIDE_F32 : STRIDE_U8));
         __syncthreads();
     }
 }
@@ -358,7 +366,7 @@ int state_init(void* state, const craftax_config* cfg, int n, void* stream, std:
 int reset(void* state, const craftax_config* cfg, int n, const uint64_t* seeds, void* stream, std::string* err)
 {
     const Ptrs q = pointers(state, make_header(cfg, n));
-    hipLaunchKernelGGL(kf_reset, dim3(n), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, seeds, q.dl.count, q.dl.finished);
+    hipLaunchKernelGGL(kf_reset, dim3((unsigned)n * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, seeds, q.dl.count, q.dl.finished);
     return check_launch("craftax_reset", err);
 }
 
@@ -369,7 +377,7 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
     const Params p = make_params(cfg, n);
     hipStream_t st = (hipStream_t)stream;
     uint8_t* o = static_cast<uint8_t*>(obs);
-    const dim3 grid((n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK), rgrid(n < RESET_GRID ? n : RESET_GRID);
+    const dim3 grid((n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK), rgrid((unsigned)(n < RESET_SLOTS ? n : RESET_SLOTS) * FLOORS);
     if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) {
         hipLaunchKernelGGL(kf_step<true>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.dl, p);
         hipLaunchKernelGGL(kf_reset_list<true>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.dl);

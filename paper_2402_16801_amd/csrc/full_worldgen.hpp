@@ -3,20 +3,20 @@
 // sewers, vault, troll mines, fire realm, ice realm, graveyard).  The paper does not print its
 // generators; here every cell of every floor is a pure integer function of (seed, env, episode,
 // floor, x, y): value-noise thresholds for the open floors, eight seeded rooms joined by
-// L-shaped corridors for the built ones.  512 threads, each owning runs of 8 cells.
+// L-shaped corridors for the built ones.  One block of 576 threads per (environment, floor),
+// each thread owning a run of 4 cells, so that a reset is nine short blocks instead of one long one.
 #pragma once
 
 #include "full_common.hpp"
 
 namespace cf {
 
-constexpr int GEN_THREADS = 512;
+constexpr int GEN_THREADS = CELLS / 4;                    // 576: one thread per run of 4 cells of a floor
 constexpr int LAT0_U16 = 2 * 16 + 4 * 49;                 // overworld lattices: two 4x4 (spacing 16), four 7x7 (spacing 8)
 constexpr int LAT0_BLOCKS = (LAT0_U16 + 7) / 8;           // 29
 constexpr int LATC_U16 = 2 * 49, LATC_BLOCKS = (LATC_U16 + 7) / 8;   // cave floors: two 7x7 lattices, 13 blocks
 constexpr int LAT_STRIDE0 = LAT0_BLOCKS * 8, LAT_STRIDEC = LATC_BLOCKS * 8;
-constexpr int LAT_TOTAL = LAT_STRIDE0 + 4 * LAT_STRIDEC;
-constexpr int OCTETS_PER_FLOOR = CELLS / 8;               // 288
+constexpr int LAT_TOTAL = LAT_STRIDE0;                    // a block generates one floor: the largest lattice set
 
 struct Room { int x, y, w, h, cx, cy; };
 struct GenLayout {
@@ -53,82 +53,92 @@ __device__ inline bool on_corridor(int x, int y, int x0, int y0, int x1, int y1)
     return h | v;
 }
 
-// block id | item << 8 of one cell (a real call: inlined four times it exhausts the registers)
-__device__ __noinline__ int gen_cell(const GenLayout& L, const uint16_t* lat, int f, int x, int y, int u)
+// Cell functions, one per kind of floor: block id | item << 8.
+__device__ inline int cell_overworld(const GenLayout& L, const uint16_t* lat, int x, int y, int u)
 {
-    int b, it = IT_NONE;
-    if (f == 0) {
-        const uint16_t *w16 = lat, *m16 = lat + 16, *w8 = lat + 32, *m8 = w8 + 49, *c8 = m8 + 49, *f8 = c8 + 49;
-        int Wn = (int)((3u * noise16(w16, x, y) + noise8(w8, x, y)) >> 2);
-        int Mn = (int)((3u * noise16(m16, x, y) + noise8(m8, x, y)) >> 2);
-        const int Cn = (int)noise8(c8, x, y), Fn = (int)noise8(f8, x, y);
-        const int d = max(iabs(x - W / 2), iabs(y - W / 2));
-        if (d < 10) { const int bias = (10 - d) * 2500; Wn = max(0, Wn - bias); Mn = max(0, Mn - bias); }
-        if (d <= 2) b = B_GRASS;
-        else if (Mn > 39500) {
-            if (Cn > 43000 && Mn > 41000) b = B_PATH;
-            else if (iabs(Cn - 30000) < 1300) b = B_PATH;
-            else if (Mn > 43000 && Fn > 44000) b = B_LAVA;
-            else if (Mn > 42000 && u < 500) b = B_DIAMOND;
-            else if (Fn < 33000 && u >= 500 && u < 3000) b = B_IRON;
-            else if (u >= 3000 && u < 8000) b = B_COAL;
-            else b = B_STONE;
-        } else if (Wn > 39500) b = B_WATER;
-        else if (Wn > 37800) b = B_SAND;
-        else if (Fn > 33500 && u < 26000) b = B_TREE;
-        else if (u < 1300) b = B_TREE;
-        else b = B_GRASS;
-        if (x == L.down[0][0] && y == L.down[0][1]) { b = B_PATH; it = IT_LADDER_DOWN; }
-    } else if (is_dungeon(f)) {
-        const Room* R = L.room[dungeon_index(f)];
-        bool inside = false;
+    const uint16_t *w16 = lat, *m16 = lat + 16, *w8 = lat + 32, *m8 = w8 + 49, *c8 = m8 + 49, *f8 = c8 + 49;
+    int Wn = (int)((3u * noise16(w16, x, y) + noise8(w8, x, y)) >> 2);
+    int Mn = (int)((3u * noise16(m16, x, y) + noise8(m8, x, y)) >> 2);
+    const int Cn = (int)noise8(c8, x, y), Fn = (int)noise8(f8, x, y);
+    const int d = max(iabs(x - W / 2), iabs(y - W / 2));
+    if (d < 10) { const int bias = (10 - d) * 2500; Wn = max(0, Wn - bias); Mn = max(0, Mn - bias); }
+    int b;
+    if (d <= 2) b = B_GRASS;
+    else if (Mn > 39500) {
+        if (Cn > 43000 && Mn > 41000) b = B_PATH;
+        else if (iabs(Cn - 30000) < 1300) b = B_PATH;
+        else if (Mn > 43000 && Fn > 44000) b = B_LAVA;
+        else if (Mn > 42000 && u < 500) b = B_DIAMOND;
+        else if (Fn < 33000 && u >= 500 && u < 3000) b = B_IRON;
+        else if (u >= 3000 && u < 8000) b = B_COAL;
+        else b = B_STONE;
+    } else if (Wn > 39500) b = B_WATER;
+    else if (Wn > 37800) b = B_SAND;
+    else if (Fn > 33500 && u < 26000) b = B_TREE;
+    else if (u < 1300) b = B_TREE;
+    else b = B_GRASS;
+    if (x == L.down[0][0] && y == L.down[0][1]) return B_PATH | (IT_LADDER_DOWN << 8);
+    return b;
+}
+__device__ inline int cell_dungeon(const GenLayout& L, int f, int x, int y, int u)
+{
+    const Room* R = L.room[dungeon_index(f)];
+    bool inside = false;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) inside |= (unsigned)(x - R[i].x) < (unsigned)R[i].w && (unsigned)(y - R[i].y) < (unsigned)R[i].h;
-        b = f == 3 ? B_WALL_MOSS : B_WALL;
-        if (inside) b = (f == 3 && u < 12000) ? B_WATER : B_PATH;
+    for (int i = 0; i < 8; ++i) inside |= (unsigned)(x - R[i].x) < (unsigned)R[i].w && (unsigned)(y - R[i].y) < (unsigned)R[i].h;
+    int b = f == 3 ? B_WALL_MOSS : B_WALL;
+    if (inside) b = (f == 3 && u < 12000) ? B_WATER : B_PATH;
 #pragma unroll
-        for (int i = 1; i <= 6; ++i) if (x == R[i].cx + 1 && y == R[i].cy + 1) b = B_CHEST;
-        if (f == 1 && x == R[2].cx - 1 && y == R[2].cy - 1) b = B_FOUNTAIN;
-        if (f == 4 && x == R[3].cx - 1 && y == R[3].cy - 1) b = B_ENCH_FIRE;
-        if (f == 4 && x == R[4].cx - 1 && y == R[4].cy - 1) b = B_ENCH_ICE;
-        bool corridor = false;
+    for (int i = 1; i <= 6; ++i) if (x == R[i].cx + 1 && y == R[i].cy + 1) b = B_CHEST;
+    if (f == 1 && x == R[2].cx - 1 && y == R[2].cy - 1) b = B_FOUNTAIN;
+    if (f == 4 && x == R[3].cx - 1 && y == R[3].cy - 1) b = B_ENCH_FIRE;
+    if (f == 4 && x == R[4].cx - 1 && y == R[4].cy - 1) b = B_ENCH_ICE;
+    bool corridor = false;
 #pragma unroll
-        for (int i = 0; i < 7; ++i) corridor |= on_corridor(x, y, R[i].cx, R[i].cy, R[i + 1].cx, R[i + 1].cy);
-        if (corridor) b = B_PATH;
-        if (x == R[0].cx && y == R[0].cy) { b = B_PATH; it = IT_LADDER_UP; }
-        if (x == R[7].cx && y == R[7].cy) { b = B_PATH; it = IT_LADDER_DOWN_BLOCKED; }
-    } else if (f == 8) {
-        b = (x == 0 || y == 0 || x == W - 1 || y == W - 1) ? B_WALL : B_PATH;
-        if ((x & 7) == 0 && x >= 8 && x <= 40 && (y == 12 || y == 24 || y == 36)) b = B_GRAVE1 + ((x - 8) / 8 + (y - 12) / 12) % 3;
-        if (x == BOSS_X && y == BOSS_Y) b = B_NECRO_VULN;
-        if (x == 24 && y == 42) { b = B_PATH; it = IT_LADDER_UP; }
+    for (int i = 0; i < 7; ++i) corridor |= on_corridor(x, y, R[i].cx, R[i].cy, R[i + 1].cx, R[i + 1].cy);
+    if (corridor) b = B_PATH;       // corridors last: room centre 0 (ladder up) always reaches room centre 7 (ladder down)
+    int it = IT_NONE;
+    if (x == R[0].cx && y == R[0].cy) { b = B_PATH; it = IT_LADDER_UP; }
+    if (x == R[7].cx && y == R[7].cy) { b = B_PATH; it = IT_LADDER_DOWN_BLOCKED; }
+    return b | (it << 8);
+}
+__device__ inline int cell_graveyard(int x, int y)
+{
+    int b = (x == 0 || y == 0 || x == W - 1 || y == W - 1) ? B_WALL : B_PATH;
+    if ((x & 7) == 0 && x >= 8 && x <= 40 && (y == 12 || y == 24 || y == 36)) b = B_GRAVE1 + ((x - 8) / 8 + (y - 12) / 12) % 3;
+    if (x == BOSS_X && y == BOSS_Y) b = B_NECRO_VULN;
+    if (x == 24 && y == 42) return B_PATH | (IT_LADDER_UP << 8);
+    return b;
+}
+__device__ inline int cell_cave(const GenLayout& L, const uint16_t* lat, int f, int x, int y, int u)
+{
+    const uint16_t *c8 = lat, *f8 = lat + 49;
+    const int Cn = (int)noise8(c8, x, y), Fn = (int)noise8(f8, x, y);
+    const int open = f == 6 ? B_FIRE_GRASS : (f == 7 ? B_ICE_GRASS : B_PATH);
+    int b;
+    if (Cn > 31000) {
+        b = open;
+        if (f == 2 && u < 1500) b = B_STALAGMITE;
+        if (f == 5 && Fn > 44000) b = B_WATER;
+        if (f == 6) { if (Fn > 43000) b = B_LAVA; else if (u < 3000) b = B_FIRE_TREE; }
+        if (f == 7) { if (Fn > 43000) b = B_WATER; else if (u < 3000) b = B_ICE_SHRUB; }
     } else {
-        const uint16_t *c8 = lat, *f8 = lat + 49;
-        const int Cn = (int)noise8(c8, x, y), Fn = (int)noise8(f8, x, y);
-        const int open = f == 6 ? B_FIRE_GRASS : (f == 7 ? B_ICE_GRASS : B_PATH);
-        if (Cn > 31000) {
-            b = open;
-            if (f == 2 && u < 1500) b = B_STALAGMITE;
-            if (f == 5 && Fn > 44000) b = B_WATER;
-            if (f == 6) { if (Fn > 43000) b = B_LAVA; else if (u < 3000) b = B_FIRE_TREE; }
-            if (f == 7) { if (Fn > 43000) b = B_WATER; else if (u < 3000) b = B_ICE_SHRUB; }
-        } else {
-            b = B_STONE;
-            if (f == 2 || f == 5) {
-                if (u < 5000) b = B_COAL;
-                else if (u < 7500) b = B_IRON;
-                else if (u < 8000) b = B_DIAMOND;
-                else if (u < (f == 2 ? 8600 : 9000)) b = B_SAPPHIRE;
-                else if (u < (f == 2 ? 9200 : 10000)) b = B_RUBY;
-            } else if (f == 6) { if (u < 2500) b = B_RUBY; else if (u < 6000) b = B_COAL; }
-            else { if (u < 2500) b = B_SAPPHIRE; else if (u < 5000) b = B_DIAMOND; }
-        }
-        const int ux = L.up[f][0], uy = L.up[f][1], dx = L.down[f][0], dy = L.down[f][1];
-        if (max(iabs(x - ux), iabs(y - uy)) <= 1 || max(iabs(x - dx), iabs(y - dy)) <= 1) b = open;
-        if (on_corridor(x, y, ux, uy, dx, dy)) b = open;      // the two ladders are always connected
-        if (x == ux && y == uy) { b = B_PATH; it = IT_LADDER_UP; }
-        if (x == dx && y == dy) { b = B_PATH; it = IT_LADDER_DOWN_BLOCKED; }
+        b = B_STONE;
+        if (f == 2 || f == 5) {
+            if (u < 5000) b = B_COAL;
+            else if (u < 7500) b = B_IRON;
+            else if (u < 8000) b = B_DIAMOND;
+            else if (u < (f == 2 ? 8600 : 9000)) b = B_SAPPHIRE;
+            else if (u < (f == 2 ? 9200 : 10000)) b = B_RUBY;
+        } else if (f == 6) { if (u < 2500) b = B_RUBY; else if (u < 6000) b = B_COAL; }
+        else { if (u < 2500) b = B_SAPPHIRE; else if (u < 5000) b = B_DIAMOND; }
     }
+    const int ux = L.up[f][0], uy = L.up[f][1], dx = L.down[f][0], dy = L.down[f][1];
+    if (max(iabs(x - ux), iabs(y - uy)) <= 1 || max(iabs(x - dx), iabs(y - dy)) <= 1) b = open;
+    if (on_corridor(x, y, ux, uy, dx, dy)) b = open;      // the two ladders are always connected
+    int it = IT_NONE;
+    if (x == ux && y == uy) { b = B_PATH; it = IT_LADDER_UP; }
+    if (x == dx && y == dy) { b = B_PATH; it = IT_LADDER_DOWN_BLOCKED; }
     return b | (it << 8);
 }
 
@@ -139,107 +149,121 @@ __device__ inline U4 wg_block(uint32_t lo, uint32_t hi, uint32_t env, uint32_t e
     return philox4x32_10(env, stream, episode, (cx::DOM_WORLDGEN << 16) | block, lo, hi);
 }
 
-// Generates all floors of one environment.  maps: this environment's 41472 bytes.  s_lat and
-// L are LDS scratch.  start_wb / start_wi (may be null): LDS windows (11 x 16 bytes) of the
-// start position on floor 0, filled by the threads that own those cells.  Ends with a barrier;
-// L then holds the ladders and the potion permutation for the fresh record.
-__device__ inline void worldgen_block(uint8_t* __restrict__ maps, uint16_t* s_lat, GenLayout& L, uint32_t lo, uint32_t hi,
-                                      uint32_t env, uint32_t episode, uint8_t* start_wb = nullptr, uint8_t* start_wi = nullptr)
+__device__ inline void put_lattice(uint16_t* dst, const U4& r)
+{
+#pragma unroll
+    for (int w = 0; w < 4; ++w) { dst[2 * w] = (uint16_t)(r.w[w] & 0xFFFFu); dst[2 * w + 1] = (uint16_t)(r.w[w] >> 16); }
+}
+__device__ inline void make_room(GenLayout& L, int f, int i, const U4& r)
+{
+    Room R;
+    R.w = 5 + (int)choice(r.w[0], 5);
+    R.h = 5 + (int)choice(r.w[1], 5);
+    R.x = 1 + (int)choice(r.w[2], (uint32_t)(46 - R.w));
+    R.y = 1 + (int)choice(r.w[3], (uint32_t)(46 - R.h));
+    R.cx = R.x + R.w / 2;
+    R.cy = R.y + R.h / 2;
+    L.room[dungeon_index(f)][i] = R;
+    if (i == 0) { L.up[f][0] = R.cx; L.up[f][1] = R.cy; }
+    if (i == 7) { L.down[f][0] = R.cx; L.down[f][1] = R.cy; }
+}
+__device__ inline void make_cave_ladders(GenLayout& L, int f, const U4& r)
+{
+    L.up[f][0] = 10 + (int)choice(r.w[0], 6); L.up[f][1] = 10 + (int)choice(r.w[1], 6);
+    L.down[f][0] = 32 + (int)choice(r.w[2], 6); L.down[f][1] = 32 + (int)choice(r.w[3], 6);
+}
+
+// Generates floor f of one environment with the GEN_THREADS threads of the calling block: thread
+// t owns the 4 cells [4t, 4t+4) of the floor (row t/12).  The block of floor 0 also derives the
+// ladders of every floor and the potion permutation (whole_layout), which the fresh record
+// needs, and may drop the cells around the start position into an LDS window (start_wb /
+// start_wi, 11 x 16 bytes each) for the first observation.  maps: this environment's 41472
+// bytes.  s_lat, L: LDS scratch.  Ends with a block barrier.
+__device__ inline void worldgen_floor_block(uint8_t* __restrict__ maps, uint16_t* s_lat, GenLayout& L, uint32_t lo, uint32_t hi,
+                                            uint32_t env, uint32_t episode, int f, uint8_t* start_wb = nullptr,
+                                            uint8_t* start_wi = nullptr)
 {
     const int tid = threadIdx.x;
-    if (tid < LAT0_BLOCKS + 4 * LATC_BLOCKS) {
-        int f, blk, base;
-        if (tid < LAT0_BLOCKS) { f = 0; blk = tid; base = 0; }
-        else {
-            const int c = (tid - LAT0_BLOCKS) / LATC_BLOCKS;
-            blk = (tid - LAT0_BLOCKS) % LATC_BLOCKS;
-            f = c == 0 ? 2 : (c == 1 ? 5 : (c == 2 ? 6 : 7));
-            base = LAT_STRIDE0 + c * LAT_STRIDEC;
-        }
-        const U4 r = wg_block(lo, hi, env, episode, (uint32_t)f * 4u, (uint32_t)blk);
+    if (f == 0) {
+        if (tid < LAT0_BLOCKS) put_lattice(s_lat + tid * 8, wg_block(lo, hi, env, episode, 0u, (uint32_t)tid));
+        else if (tid >= 64 && tid < 88) {
+            const int d = (tid - 64) >> 3, i = (tid - 64) & 7, ff = d == 0 ? 1 : (d == 1 ? 3 : 4);
+            make_room(L, ff, i, wg_block(lo, hi, env, episode, (uint32_t)ff * 4u + 2u, (uint32_t)i));
+        } else if (tid >= 96 && tid < 100) {
+            const int c = tid - 96, ff = c == 0 ? 2 : (c == 1 ? 5 : (c == 2 ? 6 : 7));
+            make_cave_ladders(L, ff, wg_block(lo, hi, env, episode, (uint32_t)ff * 4u + 2u, 0u));
+        } else if (tid == 100) {
+            const U4 r = wg_block(lo, hi, env, episode, 2u, 0u);
+            int dx = (int)choice(r.w[0], 13) - 6;
+            const int dy = (int)choice(r.w[1], 13) - 6;
+            if (max(iabs(dx), iabs(dy)) < 3) dx = 3;
+            L.up[0][0] = 0; L.up[0][1] = 0; L.down[0][0] = W / 2 + dx; L.down[0][1] = W / 2 + dy;
+            L.up[8][0] = 24; L.up[8][1] = 42; L.down[8][0] = 0; L.down[8][1] = 0;
+        } else if (tid == 101) {
+            // section "Potions and Enchantments": a fresh colour -> effect permutation per episode
+            const U4 r0 = wg_block(lo, hi, env, episode, 63u, 0u), r1 = wg_block(lo, hi, env, episode, 63u, 1u);
+            const uint32_t draws[5] = { r0.w[0], r0.w[1], r0.w[2], r0.w[3], r1.w[0] };
+            uint32_t perm = 0u;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            s_lat[base + blk * 8 + 2 * w] = (uint16_t)(r.w[w] & 0xFFFFu);
-            s_lat[base + blk * 8 + 2 * w + 1] = (uint16_t)(r.w[w] >> 16);
+            for (int i = 0; i < 6; ++i) perm |= (uint32_t)i << (3 * i);
+#pragma unroll
+            for (int i = 5; i >= 1; --i) {
+                const int j = (int)choice(draws[5 - i], (uint32_t)(i + 1));
+                const uint32_t a = (perm >> (3 * i)) & 7u, b = (perm >> (3 * j)) & 7u;
+                perm &= ~((7u << (3 * i)) | (7u << (3 * j)));
+                perm |= (b << (3 * i)) | (a << (3 * j));
+            }
+            L.perm = perm;
         }
-    } else if (tid >= 128 && tid < 152) {
-        const int d = (tid - 128) >> 3, i = (tid - 128) & 7, f = d == 0 ? 1 : (d == 1 ? 3 : 4);
-        const U4 r = wg_block(lo, hi, env, episode, (uint32_t)f * 4u + 2u, (uint32_t)i);
-        Room R;
-        R.w = 5 + (int)choice(r.w[0], 5);
-        R.h = 5 + (int)choice(r.w[1], 5);
-        R.x = 1 + (int)choice(r.w[2], (uint32_t)(46 - R.w));
-        R.y = 1 + (int)choice(r.w[3], (uint32_t)(46 - R.h));
-        R.cx = R.x + R.w / 2;
-        R.cy = R.y + R.h / 2;
-        L.room[d][i] = R;
-        if (i == 0) { L.up[f][0] = R.cx; L.up[f][1] = R.cy; }
-        if (i == 7) { L.down[f][0] = R.cx; L.down[f][1] = R.cy; }
-    } else if (tid >= 160 && tid < 164) {
-        const int c = tid - 160, f = c == 0 ? 2 : (c == 1 ? 5 : (c == 2 ? 6 : 7));
-        const U4 r = wg_block(lo, hi, env, episode, (uint32_t)f * 4u + 2u, 0u);
-        L.up[f][0] = 10 + (int)choice(r.w[0], 6); L.up[f][1] = 10 + (int)choice(r.w[1], 6);
-        L.down[f][0] = 32 + (int)choice(r.w[2], 6); L.down[f][1] = 32 + (int)choice(r.w[3], 6);
-    } else if (tid == 164) {
-        const U4 r = wg_block(lo, hi, env, episode, 2u, 0u);
-        int dx = (int)choice(r.w[0], 13) - 6;
-        const int dy = (int)choice(r.w[1], 13) - 6;
-        if (max(iabs(dx), iabs(dy)) < 3) dx = 3;
-        L.up[0][0] = 0; L.up[0][1] = 0; L.down[0][0] = W / 2 + dx; L.down[0][1] = W / 2 + dy;
-        L.up[8][0] = 24; L.up[8][1] = 42; L.down[8][0] = 0; L.down[8][1] = 0;
-    } else if (tid == 165) {
-        // section "Potions and Enchantments": a fresh colour -> effect permutation per episode
-        const U4 r0 = wg_block(lo, hi, env, episode, 63u, 0u), r1 = wg_block(lo, hi, env, episode, 63u, 1u);
-        const uint32_t draws[5] = { r0.w[0], r0.w[1], r0.w[2], r0.w[3], r1.w[0] };
-        uint32_t perm = 0u;
-        for (int i = 0; i < 6; ++i) perm |= (uint32_t)i << (3 * i);
-        for (int i = 5; i >= 1; --i) {
-            const int j = (int)choice(draws[5 - i], (uint32_t)(i + 1));
-            const uint32_t a = (perm >> (3 * i)) & 7u, b = (perm >> (3 * j)) & 7u;
-            perm &= ~((7u << (3 * i)) | (7u << (3 * j)));
-            perm |= (b << (3 * i)) | (a << (3 * j));
-        }
-        L.perm = perm;
+    } else if (is_dungeon(f)) {
+        if (tid < 8) make_room(L, f, tid, wg_block(lo, hi, env, episode, (uint32_t)f * 4u + 2u, (uint32_t)tid));
+    } else if (is_cave(f)) {
+        if (tid < LATC_BLOCKS) put_lattice(s_lat + tid * 8, wg_block(lo, hi, env, episode, (uint32_t)f * 4u, (uint32_t)tid));
+        else if (tid == 32) make_cave_ladders(L, f, wg_block(lo, hi, env, episode, (uint32_t)f * 4u + 2u, 0u));
+    }
+    const int y = tid / 12, x = (tid - y * 12) * 4;
+    const bool needs_u = !(f == 1 || f == 4 || f == 8);
+    uint32_t rw0 = 0u, rw1 = 0u;
+    if (needs_u) {
+        // per-cell draws: Philox block (cell / 8) holds eight u16, this thread uses one half of it
+        const U4 r = wg_block(lo, hi, env, episode, (uint32_t)f * 4u + 1u, (uint32_t)(tid >> 1));
+        rw0 = (tid & 1) ? r.w[2] : r.w[0];
+        rw1 = (tid & 1) ? r.w[3] : r.w[1];
     }
     __syncthreads();
+    const uint32_t light = lit_floor(f) ? (uint32_t)MAX_LIGHT << 3 : 0u;
+    uint32_t pb = 0u, pi = 0u;
+    auto put = [&](int j, int cell) {
+        pb |= (uint32_t)(cell & 0xFF) << (8 * j);
+        pi |= ((uint32_t)(cell >> 8) | light) << (8 * j);
+    };
+    auto draw = [&](int j) { const uint32_t rw = j < 2 ? rw0 : rw1; return (int)((j & 1) ? (rw >> 16) : (rw & 0xFFFFu)); };
+    // the floor is the same for the whole block: one kind of cell function per block
+    if (f == 0) {
 #pragma unroll 1
-    for (int o = tid; o < FLOORS * OCTETS_PER_FLOOR; o += GEN_THREADS) {
-        const int f = o / OCTETS_PER_FLOOR, oo = o - f * OCTETS_PER_FLOOR;
-        const int y = oo / 6, x0 = (oo - y * 6) * 8;
-        const bool needs_u = !(f == 1 || f == 4 || f == 8);
-        U4 r;
-        r.w[0] = r.w[1] = r.w[2] = r.w[3] = 0u;
-        if (needs_u) r = wg_block(lo, hi, env, episode, (uint32_t)f * 4u + 1u, (uint32_t)oo);
-        const uint16_t* lat = f == 0 ? s_lat : s_lat + LAT_STRIDE0 + cave_index(f) * LAT_STRIDEC;
-        const uint32_t light = lit_floor(f) ? (uint32_t)MAX_LIGHT << 3 : 0u;
-        // two halves of four cells each (kept rolled: the cell function is large)
+        for (int j = 0; j < 4; ++j) put(j, cell_overworld(L, s_lat, x + j, y, draw(j)));
+    } else if (is_dungeon(f)) {
 #pragma unroll 1
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t rw0 = h ? r.w[2] : r.w[0], rw1 = h ? r.w[3] : r.w[1];
-            uint32_t pb = 0u, pi = 0u;
+        for (int j = 0; j < 4; ++j) put(j, cell_dungeon(L, f, x + j, y, draw(j)));
+    } else if (f == 8) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) put(j, cell_graveyard(x + j, y));
+    } else {
+#pragma unroll 1
+        for (int j = 0; j < 4; ++j) put(j, cell_cave(L, s_lat, f, x + j, y, draw(j)));
+    }
+    *reinterpret_cast<uint32_t*>(maps + block_off(f, x, y)) = pb;
+    *reinterpret_cast<uint32_t*>(maps + il_off(f, x, y)) = pi;
+    if (start_wb != nullptr && f == 0) {
+        // window of the start cell (24, 24): rows 19..29, columns 18..30
+        const int wr = y - (W / 2 - WIN_ROWS / 2);
+        if ((unsigned)wr < (unsigned)WIN_ROWS) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const uint32_t rw = j < 2 ? rw0 : rw1;
-                const int u = (int)((j & 1) ? (rw >> 16) : (rw & 0xFFFFu));
-                const int cell = gen_cell(L, lat, f, x0 + 4 * h + j, y, u);
-                pb |= (uint32_t)(cell & 0xFF) << (8 * j);
-                pi |= ((uint32_t)(cell >> 8) | light) << (8 * j);
-            }
-            const int x = x0 + 4 * h;
-            *reinterpret_cast<uint32_t*>(maps + block_off(f, x, y)) = pb;
-            *reinterpret_cast<uint32_t*>(maps + il_off(f, x, y)) = pi;
-            if (start_wb != nullptr && f == 0) {
-                // window of the start cell (24, 24): rows 19..29, columns 18..30
-                const int wr = y - (W / 2 - WIN_ROWS / 2);
-                if ((unsigned)wr < (unsigned)WIN_ROWS) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int wc = x + j - (W / 2 - WIN_COLS / 2);
-                        if ((unsigned)wc < (unsigned)WIN_COLS) {
-                            start_wb[wr * WIN_PITCH + wc] = (uint8_t)(pb >> (8 * j));
-                            start_wi[wr * WIN_PITCH + wc] = (uint8_t)(pi >> (8 * j));
-                        }
-                    }
+                const int wc = x + j - (W / 2 - WIN_COLS / 2);
+                if ((unsigned)wc < (unsigned)WIN_COLS) {
+                    start_wb[wr * WIN_PITCH + wc] = (uint8_t)(pb >> (8 * j));
+                    start_wi[wr * WIN_PITCH + wc] = (uint8_t)(pi >> (8 * j));
                 }
             }
         }

@@ -66,8 +66,8 @@ __device__ inline int classify(int W, int M, int C, int F, int x, int y, int u)
     return BK_GRASS;
 }
 
-// Generates the map of one environment with the WG_THREADS = 512 threads of the calling
-// block: thread t owns the 8 cells [8t, 8t+8) of row t/8, which are exactly one spacing-8
+// Generates the map of one environment with the NT threads of the calling block (512, or
+// fewer with each thread taking several runs): run t owns the 8 cells [8t, 8t+8) of row t/8, which are exactly one spacing-8
 // lattice cell wide (and inside one spacing-16 cell), and whose per-cell uniforms are
 // exactly Philox block t of stream 1.  A reset is latency-bound, so the work is cut into
 // many short threads and two such blocks fit on a compute unit.
@@ -78,10 +78,13 @@ constexpr int WG_THREADS = 512;
 // start_win (may be null): LDS window (9 rows x 4 dwords) of the start position (32, 32); the
 // threads that own those cells drop them there, so the first observation of the new episode
 // can be rendered without reading the map back.
+template <int NT = WG_THREADS>
 __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat, uint32_t seed_lo, uint32_t seed_hi,
                                       uint32_t env, uint32_t episode, uint32_t* start_win = nullptr)
 {
-    const int tid = threadIdx.x;
+    static_assert(WG_THREADS % NT == 0 && NT >= 64, "block size must divide 512");
+    const int tid0 = threadIdx.x;
+    const int tid = tid0;
     if (tid < LAT_BLOCKS) {
         const U4 r = philox4x32_10(env, 0u, episode, (DOM_WORLDGEN << 16) | (uint32_t)tid, seed_lo, seed_hi);
 #pragma unroll
@@ -90,8 +93,10 @@ __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat
             s_lat[tid * 8 + 2 * w + 1] = (uint16_t)(r.w[w] >> 16);
         }
     }
-    const U4 r = philox4x32_10(env, 1u, episode, (DOM_WORLDGEN << 16) | (uint32_t)tid, seed_lo, seed_hi);
     __syncthreads();
+#pragma unroll 1
+    for (int tid = tid0; tid < WG_THREADS; tid += NT) {   // a block smaller than 512 takes several runs per thread
+    const U4 r = philox4x32_10(env, 1u, episode, (DOM_WORLDGEN << 16) | (uint32_t)tid, seed_lo, seed_hi);
     const int y = tid >> 3, x0 = (tid & 7) << 3;
     const uint16_t* w16 = s_lat;
     const uint16_t* m16 = s_lat + LAT16_N;
@@ -128,6 +133,7 @@ __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat
             start_win[wr * (WIN_PITCH / 4) + wc / 4] = packed[0];
             start_win[wr * (WIN_PITCH / 4) + wc / 4 + 1] = packed[1];
         }
+    }
     }
     __syncthreads();
 }

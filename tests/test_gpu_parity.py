@@ -155,6 +155,7 @@ def test_many_resets_in_one_block(cx, lanes):
     """Episodes of 3 steps: every environment of a block finishes in the same step."""
     run_parity(cx, 80, 40, po.OBS_SYM_U8_F32, "uniform", state_every=1, max_episode_steps=3, lanes=lanes)
     run_parity(cx, 37, 30, po.OBS_SYM_U8_I8, "uniform", state_every=1, max_episode_steps=1, lanes=lanes)
+    run_parity(cx, 53, 30, po.OBS_SYM_U8_F32, "skewed", state_every=1, max_episode_steps=2, lanes=lanes)
 
 
 def test_paper_float_layout(cx):
@@ -228,6 +229,49 @@ def test_import_export_round_trip_and_scripted_scene(cx, lanes):
         assert np.array_equal(rew.cpu().numpy().view(np.uint32), orew.view(np.uint32)), s
         assert np.array_equal(obs.cpu().numpy(), oobs), s
         assert sim.export_envs().tobytes() == orc.envs.tobytes(), s
+
+
+@pytest.mark.parametrize("lanes", [4, 16])
+def test_episode_ends_on_the_first_step_after_an_import(cx, lanes):
+    """Edited states that die or run out of time at once: the next world has to be there already,
+    also when an import lands between two steps while older worlds are still being prepared."""
+    import torch
+    n = 48
+    gcfg, ocfg = _cfgs(cx, po.OBS_SYM_U8_F32, max_episode_steps=500)
+    sim = _make_sim(cx, n, gcfg, lanes)
+    orc = po.Oracle(n, ocfg)
+    seeds = synth.seeds_for(n, 300)
+    sim.reset(seeds); orc.reset(seeds)
+
+    def both(a):
+        obs, rew, done = sim.step(torch.as_tensor(a, device=sim.device))
+        oobs, orew, odone = orc.step(a)
+        assert np.array_equal(done.cpu().numpy(), odone)
+        assert np.array_equal(rew.cpu().numpy().view(np.uint32), orew.view(np.uint32))
+        assert np.array_equal(obs.cpu().numpy(), oobs)
+        assert sim.export_envs().tobytes() == orc.envs.tobytes()
+        return odone
+
+    for s in range(5):
+        both(synth.actions(np.arange(n), s, "skewed", 9))
+    for round_ in range(3):
+        e = orc.envs
+        e["t"][0::3] = 499                      # out of time at the next step
+        e["vit"][1::3] = [1, 0, 0, 0]           # starving: the recover counter takes the last health point
+        e["cnt"][1::3] = [0, 0, 0, -30]
+        e["episode"][2::3] += 5 + round_        # other episode index: other map slot, other worlds ahead
+        sim.import_envs(e.copy())
+        d = both(np.zeros(n, np.int32))
+        assert d[0::3].all() and d[1::3].all() and not d[2::3].any()
+        for s in range(4):
+            both(synth.actions(np.arange(n), 10 * round_ + s, "uniform", 4))
+    # finish the episodes that were given other indices, so that their prepared worlds are used too
+    orc.envs["t"][:] = 499
+    sim.import_envs(orc.envs.copy())
+    assert both(np.zeros(n, np.int32)).all()
+    for s in range(6):
+        both(synth.actions(np.arange(n), 50 + s, "uniform", 4))
+    sim.close()
 
 
 def test_run_to_run_determinism(cx):
