@@ -55,7 +55,7 @@ __device__ inline void store_record(int l, uint4* __restrict__ grec, const uint3
 // episode e, the other slot the world of episode e + 1.  An episode that ends switches slots
 // inside the step kernel and puts the environment on a regeneration list; extra blocks of the
 // NEXT step launch fill the freed slot with the world after next, in the shadow of the step
-// blocks.  A tag per environment says which episode its spare slot holds and which launch wrote
+// blocks.  Two tags per environment (one per half of the map) say which episode its spare slot holds and which launch wrote
 // it; a spare is only trusted when an earlier launch wrote it.  The spare of an episode is
 // generated during that episode's first step, so only an episode that ends at its first step
 // finds it missing; a fresh episode cannot (full vitals, cleared start area, no mobs) unless the
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(WG_THREADS) void k_reset(uint4* __restrict__ recs, 
     if (ep == 0) {
         if (threadIdx.x < REC_DWORDS)
             reinterpret_cast<uint32_t*>(recs + (size_t)env * 8)[threadIdx.x] = fresh_record_word(threadIdx.x, lo, hi, 0u);
-    } else if (threadIdx.x == 0) ls.tags[env] = make_uint2(1u, 0u);
+    } else if (threadIdx.x < 2) ls.tags[2 * env + threadIdx.x] = make_uint2(1u, 0u);
 }
 
 // A regeneration block of the step grid: worlds for the episodes after next of the episodes that
@@ -94,11 +94,15 @@ __device__ __forceinline__ void regeneration_block(uint8_t* __restrict__ maps, c
 {
     const uint32_t which = (seq & 1u) ^ 1u, sub = rb % NSUB;
     const uint4* list = ls.regen[which] + (size_t)sub * ls.sub_cap;
-    for (uint32_t i = rb / NSUB; i < count; i += nrb / NSUB) {
+    // two blocks per world, one half each: a regeneration block is then as short as it can be with
+    // one run of 8 cells per thread, and the tail it adds to the launch is half as long
+    const uint32_t pair = rb / NSUB, half = pair & 1u;
+    for (uint32_t i = pair >> 1; i < count; i += nrb / NSUB / 2) {
         const uint4 entry = list[i];
         if (entry.x == ENTRY_VOID) continue;
-        worldgen_block<BLOCK>(maps + map_offset(entry.x, entry.w), s_lat, entry.y, entry.z, entry.x, entry.w);
-        if (threadIdx.x == 0) ls.tags[entry.x] = make_uint2(entry.w, seq);
+        worldgen_block<BLOCK>(maps + map_offset(entry.x, entry.w), s_lat, entry.y, entry.z, entry.x, entry.w, nullptr,
+                              (int)half * (WG_THREADS / 2), WG_THREADS / 2);
+        if (threadIdx.x == 0) ls.tags[2 * entry.x + half] = make_uint2(entry.w, seq);
     }
 }
 
@@ -142,7 +146,7 @@ __global__ __launch_bounds__(BLOCK, 4) void k_step(uint4* __restrict__ recs, uin
     };
 
     if (regen_role) {
-        if (rb / NSUB < regen_count)
+        if (rb / NSUB / 2 < regen_count)
             regeneration_block(maps, ls, seq, regen_count, rb, nrb, reinterpret_cast<uint16_t*>(s_env));
         leave();
         return;
@@ -167,8 +171,8 @@ __global__ __launch_bounds__(BLOCK, 4) void k_step(uint4* __restrict__ recs, uin
         bool write_back = !o.done;
         if (o.done) {
             // the record in LDS is still the episode that just ended
-            const uint2 tag = ls.tags[env];
-            if (tag.x == ep + 1u && tag.y < seq) {
+            const uint4 tag = reinterpret_cast<const uint4*>(ls.tags)[env];   // (episode, launch) of the two halves of the spare world
+            if (tag.x == ep + 1u && tag.y < seq && tag.z == ep + 1u && tag.w < seq) {
                 // the next world is waiting in the other slot: start the new episode right here
                 group_sync();
 #pragma unroll
@@ -401,7 +405,7 @@ __global__ __launch_bounds__(WG_THREADS) void k_import_spare(const uint4* __rest
     const uint32_t* r = reinterpret_cast<const uint32_t*>(recs + (size_t)env * 8);
     const uint32_t ep = r[RW_EPISODE] + 1u, lo = r[RW_SEED_LO], hi = r[RW_SEED_HI];
     worldgen_block(maps + map_offset(env, ep), s_lat, lo, hi, env, ep);
-    if (threadIdx.x == 0) ls.tags[env] = make_uint2(ep, 0u);
+    if (threadIdx.x < 2) ls.tags[2 * env + threadIdx.x] = make_uint2(ep, 0u);
 }
 
 // synthetic action stream (input generation for benchmarks; not part of the simulator)
@@ -473,7 +477,7 @@ static Header make_header(const craftax_config* c, int n)
     h.off_recs = round_up(h.off_luts + sizeof(Luts), 256);
     h.off_maps = h.off_recs + (uint64_t)n * (REC_DWORDS * 4);
     h.off_tags = h.off_maps + (uint64_t)n * 2 * (MAPW * MAPW);     // two map slots per environment
-    h.off_regen0 = round_up(h.off_tags + (uint64_t)n * 8, 256);
+    h.off_regen0 = round_up(h.off_tags + (uint64_t)n * 16, 256);
     const uint64_t list_bytes = (uint64_t)NSUB * sub_list_capacity(n) * 16;
     h.off_regen1 = h.off_regen0 + list_bytes;
     h.off_slow = h.off_regen1 + list_bytes;
@@ -568,14 +572,14 @@ static int group_lanes(int n)
 }
 
 constexpr int RESET_GRID = 64;    // blocks of k_reset_list (the slow list is nearly always empty); each loops over the list
-constexpr int REGEN_BLOCKS = 512; // regeneration blocks appended to the step grid; those beyond the list exit at once
+constexpr int REGEN_BLOCKS = 1024; // regeneration blocks appended to the step grid (two per world); those beyond the list exit at once
 
 template <int OBS_MODE>
 static void launch_step(int G, int n, hipStream_t st, const Ptrs& q, const int32_t* actions, uint8_t* o, float* reward,
                         uint8_t* done, const Params& p)
 {
     const dim3 block(BLOCK);
-    const int regen = ((n < REGEN_BLOCKS ? n : REGEN_BLOCKS) + NSUB - 1) / NSUB * NSUB;   // a multiple of the sub-list count
+    const int regen = ((2 * n < REGEN_BLOCKS ? 2 * n : REGEN_BLOCKS) + 2 * NSUB - 1) / (2 * NSUB) * (2 * NSUB);   // a multiple of twice the sub-list count
     const int sb = (n + 256 / G - 1) / (256 / G);
     if (G == 4) hipLaunchKernelGGL((k_step<4, OBS_MODE>), dim3(sb + regen), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.ls, p, sb);
     else if (G == 8) hipLaunchKernelGGL((k_step<8, OBS_MODE>), dim3(sb + regen), block, 0, st, q.recs, q.maps, q.luts, actions, o, reward, done, q.ls, p, sb);

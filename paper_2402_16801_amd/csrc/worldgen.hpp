@@ -78,9 +78,12 @@ constexpr int WG_THREADS = 512;
 // start_win (may be null): LDS window (9 rows x 4 dwords) of the start position (32, 32); the
 // threads that own those cells drop them there, so the first observation of the new episode
 // can be rendered without reading the map back.
+// first_run, runs: the part of the world this call generates (runs first_run .. first_run + runs - 1
+// of the 512; a world may be split over several blocks).
 template <int NT = WG_THREADS>
 __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat, uint32_t seed_lo, uint32_t seed_hi,
-                                      uint32_t env, uint32_t episode, uint32_t* start_win = nullptr)
+                                      uint32_t env, uint32_t episode, uint32_t* start_win = nullptr, int first_run = 0,
+                                      int runs = WG_THREADS)
 {
     static_assert(WG_THREADS % NT == 0 && NT >= 64, "block size must divide 512");
     const int tid0 = threadIdx.x;
@@ -95,7 +98,7 @@ __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat
     }
     __syncthreads();
 #pragma unroll 1
-    for (int tid = tid0; tid < WG_THREADS; tid += NT) {   // a block smaller than 512 takes several runs per thread
+    for (int tid = first_run + tid0; tid < first_run + runs; tid += NT) {   // a block smaller than its share takes several runs per thread
     const U4 r = philox4x32_10(env, 1u, episode, (DOM_WORLDGEN << 16) | (uint32_t)tid, seed_lo, seed_hi);
     const int y = tid >> 3, x0 = (tid & 7) << 3;
     const uint16_t* w16 = s_lat;

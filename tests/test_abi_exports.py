@@ -41,7 +41,7 @@ def test_sizes_and_defaults(lib):
     assert 1345 * 4 <= strides[2] and 63 * 63 * 3 * 4 <= strides[3]
     cfg.obs_mode = 1
     b1, b2 = binding.craftax_state_bytes(cfg, 1), binding.craftax_state_bytes(cfg, 1001)
-    per_env = 2 * 4096 + 128 + 8 + 3 * 16          # two map slots, record, spare tag, three list entries
+    per_env = 2 * 4096 + 128 + 16 + 3 * 16         # two map slots, record, two spare tags, three list entries
     assert abs((b2 - b1) - 1000 * per_env) < 70000 and b1 % 256 == 0   # sub-lists round their capacity up
     assert binding.craftax_state_bytes(cfg, 0) == 0 and binding.craftax_state_bytes(cfg, -3) == 0
     cfg.day_length = 7

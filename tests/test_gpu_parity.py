@@ -274,6 +274,47 @@ def test_episode_ends_on_the_first_step_after_an_import(cx, lanes):
     sim.close()
 
 
+def test_step_captured_in_a_graph_and_replayed(cx):
+    """One craftax_step call captured in a HIP graph and replayed 120 times (an odd-length graph:
+    the launch bookkeeping must live on the device), actions refilled between replays; every replay
+    is checked against the oracle, with eager work and synchronisation in between."""
+    import torch
+    n = 700
+    gcfg, ocfg = _cfgs(cx, po.OBS_SYM_U8_F32, max_episode_steps=40)
+    sim = _make_sim(cx, n, gcfg, None)
+    orc = po.Oracle(n, ocfg)
+    seeds = synth.seeds_for(n, 21)
+    sim.reset(seeds); orc.reset(seeds)
+    a_buf = torch.zeros(n, dtype=torch.int32, device=sim.device)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        # warm-up launch outside capture is not needed: nothing here allocates; capture one step
+        with torch.cuda.graph(graph, stream=side):
+            cx.craftax_step(sim.state, a_buf, sim.obs, sim.reward, sim.done, n, torch.cuda.current_stream())
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    # the capture itself does not execute the step: the state is still the reset state
+    assert sim.export_envs().tobytes() == orc.envs.tobytes()
+    finished = 0
+    for s in range(120):
+        a = synth.actions(np.arange(n), s, "skewed", 6)
+        a_buf.copy_(torch.as_tensor(a, device=sim.device))
+        graph.replay()
+        torch.cuda.synchronize()
+        oobs, orew, odone = orc.step(a)
+        finished += int(odone.sum())
+        assert np.array_equal(sim.done.cpu().numpy(), odone), s
+        assert np.array_equal(sim.reward.cpu().numpy().view(np.uint32), orew.view(np.uint32)), s
+        assert np.array_equal(sim.obs.cpu().numpy(), oobs), s
+        if s % 10 == 9:
+            assert sim.export_envs().tobytes() == orc.envs.tobytes(), s
+    assert finished > 2 * n
+    sim.close()
+
+
 def test_run_to_run_determinism(cx):
     import torch
     outs = []
