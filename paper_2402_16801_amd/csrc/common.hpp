@@ -143,20 +143,8 @@ struct Header {
     uint64_t atlas_seed;
     uint64_t off_ctrs, off_luts, off_recs, off_maps, off_tags, off_regen0, off_regen1, off_slow, total;
 };
-// Device-side counters of the Classic variant: one uint32 per 256 bytes (counters hit by atomics
-// from many blocks must not share a memory channel), in their own area of the state blob.
-//   SEQ     number of step launches so far + 1
-//   TOP     groups of blocks of the current step launch that have all started
-//   SLOW    entries in the slow list; SLOW_FINISHED: slow-list blocks finished
-//   GROUP+g blocks of group g of the current step launch that have started (64 groups)
-//   REGEN+p*16+s entries in sub-list s of regeneration list p
-constexpr int CTR_STRIDE = 64;   // dwords between counters
-constexpr int NGROUP = 64, NSUB = 16;
-enum Counter : int { CT_SEQ = 0, CT_TOP = 1, CT_SLOW = 2, CT_SLOW_FINISHED = 3, CT_GROUP = 4, CT_REGEN = CT_GROUP + NGROUP,
-                     CT_COUNT = CT_REGEN + 2 * NSUB };
-// the done-list counters of the full-Craftax variant live in the first 256 bytes of its state blob
-constexpr uint64_t DONE_COUNT_OFFSET = 192;
-static_assert(sizeof(Header) <= DONE_COUNT_OFFSET, "header overlaps the done-list counters");
+constexpr uint64_t HEADER_BYTES = 256;   // the header sits alone in the first 256 bytes of the state blob
+static_assert(sizeof(Header) <= HEADER_BYTES, "header outgrew its area");
 constexpr uint64_t MAGIC = 0x43524146544158ull;  // "CRAFTAX"
 
 // Scalars every kernel needs, passed by value.

@@ -17,9 +17,13 @@ namespace cf {
 
 static_assert(sizeof(craftax_full_env_dump) == 63432, "canonical dump layout");
 
-// a list entry carries what the reset needs: (env, seed low, seed high, next episode index)
-struct DoneList { uint32_t* count; uint32_t* finished; uint4* list; };
-constexpr int RESET_SLOTS = 64;   // environments regenerated at once by kf_reset_list (nine blocks each)
+using la::Lists;
+using la::counter;
+using la::ENTRY_VOID;
+using la::NSUB;
+
+constexpr int RESET_SLOTS = 64;    // environments served at once by kf_reset_list (nine blocks each)
+constexpr int REGEN_BLOCKS = 1296; // regeneration blocks appended to the step grid: 3 worlds per sub-list at once, 27 blocks per world
 
 __device__ inline uint32_t pack_regs(const MobRegs& m)
 {
@@ -28,104 +32,213 @@ __device__ inline uint32_t pack_regs(const MobRegs& m)
     return pack_mob(o);
 }
 
-// ---------------------------------------------------------------------------------------------
-// reset of every environment: one block per (environment, floor); the block of floor 0 also
-// writes the fresh record and the empty mob tables
-__global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
-                                                       const uint64_t* __restrict__ seeds, uint32_t* done_count,
-                                                       uint32_t* done_finished)
+// What the block that generated floor 0 of a world leaves behind for the environment: as the
+// current world (fresh record, empty mob tables) or as the spare world (its ladders and potion map).
+__device__ inline void publish_world(uint32_t* __restrict__ genv, const GenLayout& L, uint32_t lo, uint32_t hi, uint32_t ep,
+                                     bool current, uint32_t* s_layout_words)
 {
-    if (blockIdx.x == 0 && threadIdx.x == 0) { *done_count = 0u; *done_finished = 0u; }
+    const int tid = threadIdx.x;
+    if (tid < FLOORS + 1) s_layout_words[tid] = layout_word(L, tid);
+    __syncthreads();
+    if (current) {
+        if (tid < SPARE_LADDER) genv[tid] = tid < REC_DWORDS ? fresh_record_word(tid, s_layout_words, lo, hi, ep) : 0u;
+    } else if (tid < FLOORS + 1) genv[SPARE_LADDER + tid] = s_layout_words[tid];
+}
+
+// ---------------------------------------------------------------------------------------------
+// reset of every environment: one block per (environment, episode 0 or 1, floor)
+__global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
+                                                       const uint64_t* __restrict__ seeds, Lists ls)
+{
+    if (blockIdx.x == 0) la::reset_counters(ls);
     __shared__ uint16_t s_lat[LAT_TOTAL];
     __shared__ GenLayout s_layout;
-    const uint32_t env = blockIdx.x / FLOORS;
+    __shared__ uint32_t s_words[FLOORS + 1];
+    const uint32_t env = blockIdx.x / (2 * FLOORS), ep = (blockIdx.x / FLOORS) & 1u;
     const int f = blockIdx.x % FLOORS;
     const uint64_t seed = seeds[env];
     const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
-    worldgen_floor_block(maps + (size_t)env * MAP_BYTES, s_lat, s_layout, lo, hi, env, 0u, f);
-    const int tid = threadIdx.x;
-    if (f == 0 && tid < ENV_DWORDS)
-        envs[(size_t)env * ENV_DWORDS + tid] = tid < REC_DWORDS ? fresh_record_word(tid, s_layout, lo, hi, 0u) : 0u;
+    worldgen_floor_block(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f);
+    if (f == 0) publish_world(envs + (size_t)env * ENV_DWORDS, s_layout, lo, hi, ep, ep == 0u, s_words);
+    if (ep == 1u && threadIdx.x < FLOOR_PARTS) ls.tags[(size_t)env * NTAG + f * FLOOR_PARTS + threadIdx.x] = make_uint2(1u, 0u);
 }
+
+// A regeneration block of the step grid: a third of one floor of the world after next of an
+// episode that ended in the previous launch (27 short blocks per world fit into the gaps the
+// step blocks leave; one long block per world would outlast them).
+__device__ __forceinline__ void regeneration_block(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, const Lists& ls,
+                                                   uint32_t seq, uint32_t count, uint32_t rb, uint32_t nrb, uint32_t* lds)
+{
+    uint16_t* s_lat = reinterpret_cast<uint16_t*>(lds);
+    GenLayout& L = *reinterpret_cast<GenLayout*>(lds + 128);
+    uint32_t* s_words = lds + 512;
+    const uint4* list = la::consumed_sub_list(ls, seq, rb);
+    const uint32_t k = rb / NSUB, unit = k % NTAG, f = unit / FLOOR_PARTS, part = unit % FLOOR_PARTS;
+    for (uint32_t i = k / NTAG; i < count; i += nrb / NSUB / NTAG) {
+        const uint4 entry = list[i];
+        if (entry.x == ENTRY_VOID) continue;
+        worldgen_floor_block<BLOCK>(maps + map_offset(entry.x, entry.w), s_lat, L, entry.y, entry.z, entry.x, entry.w, (int)f,
+                                    nullptr, nullptr, (int)part * (GEN_THREADS / FLOOR_PARTS), GEN_THREADS / FLOOR_PARTS);
+        if (unit == 0) publish_world(envs + (size_t)entry.x * ENV_DWORDS, L, entry.y, entry.z, entry.w, false, s_words);
+        if (threadIdx.x == 0) ls.tags[(size_t)entry.x * NTAG + unit] = make_uint2(entry.w, seq);
+        __syncthreads();
+    }
+}
+static_assert(LAT_TOTAL * 2 <= 128 * 4 && sizeof(GenLayout) <= (512 - 128) * 4, "regeneration scratch overlaps");
 
 // ---------------------------------------------------------------------------------------------
-// step: one wavefront per environment, four environments per block.  Finished episodes are not
-// written back; they go on the done list that kf_reset_list consumes right after.
+// step: one wavefront per environment, four environments per block, followed in the same grid by
+// the regeneration blocks for the episodes that ended in the previous launch.
 template <bool F32>
-__global__ __launch_bounds__(BLOCK) void kf_step(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
+__global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
                                                 const Luts* __restrict__ luts, const int32_t* __restrict__ actions,
                                                 uint8_t* __restrict__ obs, float* __restrict__ reward,
-                                                uint8_t* __restrict__ done, DoneList dl, Params p)
+                                                uint8_t* __restrict__ done, Lists ls, Params p, int step_blocks)
 {
     __shared__ uint32_t s_env[ENVS_PER_BLOCK * L_ENV_DWORDS];
+    __shared__ int s_ndone;
+    __shared__ uint32_t s_base;
+    __shared__ uint4 s_list[ENVS_PER_BLOCK];
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
-    const int env = blockIdx.x * ENVS_PER_BLOCK + w;
-    if (env >= p.n) return;                                     // whole waves leave; the kernel has no block barrier
-    uint32_t* e = s_env + w * L_ENV_DWORDS;
-    uint32_t* genv = envs + (size_t)env * ENV_DWORDS;
-    uint8_t* emaps = maps + (size_t)env * MAP_BYTES;
-    e[L_REC + l] = genv[l];
-    const int action = uni(actions[env]);
-    wave_sync();
-    MobRegs m;
-    uint32_t qw;
-    Player P;
-    const StepOut o = step_env(l, (uint32_t)env, e, genv, emaps, luts, action, p, m, qw, P);
-    if (l == 0) { reward[env] = o.reward; done[env] = o.done ? 1 : 0; }
-    if (o.done) {
-        if (l == 0) {
-            const uint32_t idx = atomicAdd(dl.count, 1u);
-            dl.list[idx] = make_uint4((uint32_t)env, e[L_REC + R_SEED_LO], e[L_REC + R_SEED_HI], P.episode + 1u);
-        }
+    const bool regen_role = (int)blockIdx.x >= step_blocks;
+    const uint32_t rb = blockIdx.x - (uint32_t)step_blocks, nrb = gridDim.x - (uint32_t)step_blocks;
+    const la::Ticket ticket = la::enter_launch(ls, regen_role, rb);
+    const uint32_t seq = ticket.seq;
+    if (regen_role) {
+        if (rb / NSUB / NTAG < ticket.regen_count) regeneration_block(envs, maps, ls, seq, ticket.regen_count, rb, nrb, s_env);
+        la::leave_launch(ls, ticket);
         return;
     }
-    if (l == 0) pack_player(e + L_REC, P);
-    if (l < NPLANT) e[L_REC + R_PLANT + l] = qw;
-    wave_sync();
-    genv[l] = e[L_REC + l];
-    if (l < MOBTAB_DWORDS) genv[REC_DWORDS + P.floor * MOBTAB_DWORDS + l] = l < NSLOT ? pack_regs(m) : 0u;
-    if (obs != nullptr)
-        render_env<F32>(l, e, o.wx0, o.wy0, m.alive, m.x, m.y, m.type, luts, obs + (size_t)env * (F32 ? STRIDE_F32 : STRIDE_U8));
+    if (tid == 0) s_ndone = 0;
+    __syncthreads();
+    const int env = blockIdx.x * ENVS_PER_BLOCK + w;
+    if (env < p.n) {
+        uint32_t* e = s_env + w * L_ENV_DWORDS;
+        uint32_t* genv = envs + (size_t)env * ENV_DWORDS;
+        e[L_REC + l] = genv[l];
+        const int action = uni(actions[env]);
+        wave_sync();
+        const uint32_t ep = uniu(e[L_REC + R_EPISODE]), lo = uniu(e[L_REC + R_SEED_LO]), hi = uniu(e[L_REC + R_SEED_HI]);
+        MobRegs m;
+        uint32_t qw;
+        Player P;
+        // What a finished episode needs from the spare world is fetched now, together with the
+        // current window, so that switching worlds costs no further trip to memory: its tags, its
+        // ladders and potion map, and the window of its start position.
+        uint2 tag = make_uint2(0u, 0u);
+        if (l < NTAG) tag = ls.tags[(size_t)env * NTAG + l];
+        const uint32_t hdr = l < FLOORS + 1 ? genv[SPARE_LADDER + l] : 0u;
+        const uint8_t* spare = maps + map_offset((uint32_t)env, ep + 1u);
+        uint32_t sw[3];
+#pragma unroll
+        for (int it = 0; it < 3; ++it) {
+            const int i = l + 64 * it;
+            sw[it] = 0u;
+            if (i < WIN_ROWS * WIN_COLS) {
+                const int r = i / WIN_COLS, c = i - r * WIN_COLS;
+                const int x = W / 2 - WIN_COLS / 2 + c, y = W / 2 - WIN_ROWS / 2 + r;
+                sw[it] = (uint32_t)spare[block_off(0, x, y)] | ((uint32_t)spare[il_off(0, x, y)] << 8);
+            }
+        }
+        auto park = [&]() {
+            if (l < NTAG) { e[L_SPARE_TAG + 2 * l] = tag.x; e[L_SPARE_TAG + 2 * l + 1] = tag.y; }
+            if (l < FLOORS + 1) e[L_SPARE_HDR + l] = hdr;
+#pragma unroll
+            for (int it = 0; it < 3; ++it) {
+                const int i = l + 64 * it;
+                if (i < WIN_ROWS * WIN_COLS) {
+                    const int r = i / WIN_COLS, c = i - r * WIN_COLS;
+                    reinterpret_cast<uint8_t*>(e + L_SPARE_WB)[r * WIN_PITCH + c] = (uint8_t)sw[it];
+                    reinterpret_cast<uint8_t*>(e + L_SPARE_WI)[r * WIN_PITCH + c] = (uint8_t)(sw[it] >> 8);
+                }
+            }
+        };
+        StepOut o = step_env(l, (uint32_t)env, e, genv, maps + map_offset((uint32_t)env, ep), luts, action, p, m, qw, P, park);
+        if (l == 0) { reward[env] = o.reward; done[env] = o.done ? 1 : 0; }
+        bool write_back = !o.done;
+        int floor_now = P.floor;
+        if (!o.done) {
+            if (l == 0) pack_player(e + L_REC, P);
+            if (l < NPLANT) e[L_REC + R_PLANT + l] = qw;
+            wave_sync();
+        } else {
+            // every part of the next world must have been written by an earlier launch
+            constexpr uint64_t ALL = (1ull << NTAG) - 1ull;
+            const bool ready = (__ballot(l < NTAG && e[L_SPARE_TAG + 2 * (l < NTAG ? l : 0)] == ep + 1u &&
+                                         e[L_SPARE_TAG + 2 * (l < NTAG ? l : 0) + 1] < seq) & ALL) == ALL;
+            if (ready) {
+                // start the new episode right here: fresh record from the spare world's ladders and
+                // potion map, all mob tables empty, window of the start position from the other slot
+                wave_sync();
+                e[L_REC + l] = fresh_record_word(l, e + L_SPARE_HDR, lo, hi, ep + 1u);
+                if (l < WIN_ROWS * WIN_PITCH / 4) { e[L_WB + l] = e[L_SPARE_WB + l]; e[L_WI + l] = e[L_SPARE_WI + l]; }
+#pragma unroll
+                for (int it = 0; it < (FLOORS * MOBTAB_DWORDS + 63) / 64; ++it) {
+                    const int i = l + 64 * it;
+                    if (i < FLOORS * MOBTAB_DWORDS) genv[REC_DWORDS + i] = 0u;
+                }
+                clear_mob(m);
+                floor_now = 0;
+                o.wx0 = W / 2 - WIN_COLS / 2; o.wy0 = W / 2 - WIN_ROWS / 2;
+                wave_sync();
+                write_back = true;
+                if (l == 0) s_list[atomicAdd(&s_ndone, 1)] = make_uint4((uint32_t)env, lo, hi, ep + 2u);
+            } else if (l == 0) {
+                la::append_slow(ls, (uint32_t)p.n, make_uint4((uint32_t)env, lo, hi, ep + 1u));
+            }
+        }
+        if (write_back) {
+            genv[l] = e[L_REC + l];
+            if (l < MOBTAB_DWORDS) genv[REC_DWORDS + floor_now * MOBTAB_DWORDS + l] = l < NSLOT ? pack_regs(m) : 0u;
+            if (obs != nullptr)
+                render_env<F32>(l, e, o.wx0, o.wy0, m.alive, m.x, m.y, m.type, luts, obs + (size_t)env * (F32 ? STRIDE_F32 : STRIDE_U8));
+        }
+    }
+    __syncthreads();
+    la::leave_launch(ls, ticket);
+    const int nd = s_ndone;
+    if (nd == 0) return;
+    la::append_block_entries(ls, seq, s_list, nd, &s_base);
 }
 
-// Regenerates every environment on the done list, nine blocks (one per floor) each, looping if
-// the list is longer than the grid; the block of floor 0 also writes the fresh record and renders
-// the first observation.  The last working block clears the list for the next step.
+// Serves the slow list: generates the world of the new episode in place (nine blocks each, looping
+// if the list is longer than the grid); the block of floor 0 writes the fresh record, renders the
+// first observation and asks the next step launch for the world after it.  Runs after the step
+// kernel, and only when the episode cap is 1.
 template <bool F32>
 __global__ __launch_bounds__(GEN_THREADS) void kf_reset_list(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
-                                                            const Luts* __restrict__ luts, uint8_t* __restrict__ obs, DoneList dl)
+                                                            const Luts* __restrict__ luts, uint8_t* __restrict__ obs, Lists ls)
 {
     __shared__ uint16_t s_lat[LAT_TOTAL];
     __shared__ GenLayout s_layout;
+    __shared__ uint32_t s_words[FLOORS + 1];
     __shared__ uint32_t s_env[L_ENV_DWORDS];
-    const uint32_t count = *dl.count;
+    const uint32_t count = la::slow_count(ls, ls.slow_cap);
     const uint32_t slot = blockIdx.x / FLOORS, slots = gridDim.x / FLOORS;
     const int f = blockIdx.x % FLOORS;
     if (slot >= count) return;
     const int tid = threadIdx.x;
-    // every working block has read the count; the last one to say so clears the list for the
-    // next step (entries are only appended by the next step kernel, after this one ends)
-    if (tid == 0) {
-        const uint32_t workers = (count < slots ? count : slots) * FLOORS;
-        if (atomicAdd(dl.finished, 1u) == workers - 1u) { *dl.count = 0u; *dl.finished = 0u; }
-    }
     for (uint32_t i = slot; i < count; i += slots) {
-        const uint4 entry = dl.list[i];
+        const uint4 entry = ls.slow[i];
+        if (entry.x == ENTRY_VOID) continue;
         const uint32_t env = entry.x, lo = entry.y, hi = entry.z, ep = entry.w;
-        worldgen_floor_block(maps + (size_t)env * MAP_BYTES, s_lat, s_layout, lo, hi, env, ep, f,
+        worldgen_floor_block(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f,
                              reinterpret_cast<uint8_t*>(s_env + L_WB), reinterpret_cast<uint8_t*>(s_env + L_WI));
         if (f == 0) {
-            if (tid < ENV_DWORDS) {
-                const uint32_t w = tid < REC_DWORDS ? fresh_record_word(tid, s_layout, lo, hi, ep) : 0u;
-                envs[(size_t)env * ENV_DWORDS + tid] = w;
-                if (tid < REC_DWORDS) s_env[L_REC + tid] = w;
-            }
+            publish_world(envs + (size_t)env * ENV_DWORDS, s_layout, lo, hi, ep, true, s_words);
+            if (tid < REC_DWORDS) s_env[L_REC + tid] = fresh_record_word(tid, s_words, lo, hi, ep);
+            if (tid == 96) la::append_after_step(ls, env / ENVS_PER_BLOCK, make_uint4(env, lo, hi, ep + 1u));
             __syncthreads();
             if (obs != nullptr && tid < 64)
                 render_env<F32>(tid, s_env, W / 2 - WIN_COLS / 2, W / 2 - WIN_ROWS / 2, 0, 0, 0, 0, luts,
                                 obs + (size_t)env * (F32 ? STRIDE_F32 : STRIDE_U8));
         }
         __syncthreads();
+    }
+    // the last working block empties the list (nine blocks per served slot)
+    if (tid == 0) {
+        const uint32_t workers = (count < slots ? count : slots) * FLOORS;
+        if (atomicAdd(counter(ls, la::CT_SLOW_FINISHED), 1u) == workers - 1u) { *counter(ls, la::CT_SLOW) = 0u; *counter(ls, la::CT_SLOW_FINISHED) = 0u; }
     }
 }
 
@@ -141,13 +254,28 @@ __global__ __launch_bounds__(BLOCK) void kf_observe(const uint32_t* __restrict__
     const uint32_t* genv = envs + (size_t)env * ENV_DWORDS;
     e[L_REC + l] = genv[l];
     wave_sync();
-    const uint32_t pos = uniu(e[L_REC + R_POS]);
+    const uint32_t pos = uniu(e[L_REC + R_POS]), ep = uniu(e[L_REC + R_EPISODE]);
     const int px = pos & 0xFF, py = (pos >> 8) & 0xFF, f = (pos >> 24) & 0xF;
     const Mob u = unpack_mob(l < NSLOT ? genv[REC_DWORDS + f * MOBTAB_DWORDS + l] : 0u);
-    load_window(l, maps + (size_t)env * MAP_BYTES, f, px, py, reinterpret_cast<uint8_t*>(e + L_WB), reinterpret_cast<uint8_t*>(e + L_WI));
+    load_window(l, maps + map_offset((uint32_t)env, ep), f, px, py, reinterpret_cast<uint8_t*>(e + L_WB), reinterpret_cast<uint8_t*>(e + L_WI));
     wave_sync();
     render_env<F32>(l, e, px - WIN_COLS / 2, py - WIN_ROWS / 2, u.alive, u.x, u.y, u.type, luts,
                     obs + (size_t)env * (F32 ? STRIDE_F32 : STRIDE_U8));
+}
+
+// after an import: the world of the episode after the imported one, into the spare slot
+__global__ __launch_bounds__(GEN_THREADS) void kf_import_spare(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, Lists ls, int first)
+{
+    __shared__ uint16_t s_lat[LAT_TOTAL];
+    __shared__ GenLayout s_layout;
+    __shared__ uint32_t s_words[FLOORS + 1];
+    const uint32_t env = (uint32_t)first + blockIdx.x / FLOORS;
+    const int f = blockIdx.x % FLOORS;
+    uint32_t* genv = envs + (size_t)env * ENV_DWORDS;
+    const uint32_t ep = genv[R_EPISODE] + 1u, lo = genv[R_SEED_LO], hi = genv[R_SEED_HI];
+    worldgen_floor_block(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f);
+    if (f == 0) publish_world(genv, s_layout, lo, hi, ep, false, s_words);
+    if (threadIdx.x < FLOOR_PARTS) ls.tags[(size_t)env * NTAG + f * FLOOR_PARTS + threadIdx.x] = make_uint2(ep, 0u);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -157,8 +285,8 @@ __global__ __launch_bounds__(BLOCK) void kf_export(const uint32_t* __restrict__ 
 {
     const int env = first + blockIdx.x, tid = threadIdx.x;
     craftax_full_env_dump* d = dumps + blockIdx.x;
-    const uint8_t* em = maps + (size_t)env * MAP_BYTES;
     const uint32_t* r = envs + (size_t)env * ENV_DWORDS;
+    const uint8_t* em = maps + map_offset((uint32_t)env, r[R_EPISODE]);
     for (int i = tid; i < FLOORS * CELLS; i += BLOCK) {
         const int f = i / CELLS, c = i - f * CELLS;
         const uint32_t il = em[(size_t)f * 2 * CELLS + CELLS + c];
@@ -210,12 +338,13 @@ __global__ __launch_bounds__(BLOCK) void kf_export(const uint32_t* __restrict__ 
 // Import packs into the record's bit fields: counts 0..255, counters -128..127, mob hp 0..31,
 // cooldown 0..15, experience 0..15, coordinates 0..47, floor 0..8 (every state the rules can
 // reach is); values outside are clamped so that no kernel ever indexes beyond its buffers.
-__global__ __launch_bounds__(BLOCK) void kf_import(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
+__global__ __launch_bounds__(BLOCK) void kf_import(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, Lists ls,
                                                   const craftax_full_env_dump* __restrict__ dumps, int first, Params p)
 {
     const int env = first + blockIdx.x, tid = threadIdx.x;
     const craftax_full_env_dump* d = dumps + blockIdx.x;
-    uint8_t* em = maps + (size_t)env * MAP_BYTES;
+    uint8_t* em = maps + map_offset((uint32_t)env, d->episode);
+    la::cancel_entries(ls, (uint32_t)env);   // whatever was queued for this environment belongs to the episode that is being replaced
     uint32_t* r = envs + (size_t)env * ENV_DWORDS;
     for (int i = tid; i < FLOORS * CELLS; i += BLOCK) {
         const int f = i / CELLS, c = i - f * CELLS;
@@ -270,7 +399,7 @@ __global__ __launch_bounds__(BLOCK) void kf_import(uint32_t* __restrict__ envs, 
         s[R_PLANT + tid - 128] = (u.alive & 1) ? (1u | ((uint32_t)min((int)u.x, W - 1) << 1) | ((uint32_t)min((int)u.y, W - 1) << 7) | ((uint32_t)u.age << 16)) : 0u;
     }
     __syncthreads();
-    r[tid] = s[tid];
+    if (tid < SPARE_LADDER) r[tid] = s[tid];   // the spare world's description is written by kf_import_spare
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -296,11 +425,16 @@ static Header make_header(const craftax_config* c, int n)
     h.magic = MAGIC; h.version = CRAFTAX_ABI_VERSION; h.n = (uint32_t)n; h.variant = c->variant;
     h.obs_mode = c->obs_mode; h.max_episode_steps = c->max_episode_steps; h.day_length = c->day_length;
     h.cap_melee = c->cap_zombie; h.cap_ranged = c->cap_skeleton; h.cap_passive = c->cap_cow; h.cap_plant = c->cap_plant;
-    h.off_luts = 256;
+    h.off_ctrs = cx::HEADER_BYTES;
+    h.off_luts = h.off_ctrs + la::COUNTER_BYTES;
     h.off_envs = round_up(h.off_luts + sizeof(Luts), 256);
     h.off_maps = h.off_envs + (uint64_t)n * (ENV_DWORDS * 4);
-    h.off_done = round_up(h.off_maps + (uint64_t)n * MAP_BYTES, 256);
-    h.total = round_up(h.off_done + (uint64_t)n * 16, 256);
+    h.off_tags = round_up(h.off_maps + (uint64_t)n * 2 * MAP_BYTES, 256);     // two map slots per environment
+    h.off_regen0 = round_up(h.off_tags + (uint64_t)n * NTAG * 8, 256);
+    const uint64_t list_bytes = (uint64_t)NSUB * la::sub_list_capacity((uint64_t)n, ENVS_PER_BLOCK) * 16;
+    h.off_regen1 = h.off_regen0 + list_bytes;
+    h.off_slow = h.off_regen1 + list_bytes;
+    h.total = round_up(h.off_slow + (uint64_t)n * 16, 256);
     return h;
 }
 
@@ -321,7 +455,7 @@ static void build_luts(const craftax_config* c, Luts* L)
     for (int i = 0; i < 32; ++i) L->light20[i] = (float)((double)i / 20.0);
 }
 
-struct Ptrs { uint32_t* envs; uint8_t* maps; const Luts* luts; DoneList dl; };
+struct Ptrs { uint32_t* envs; uint8_t* maps; const Luts* luts; Lists ls; };
 static Ptrs pointers(const void* state, const Header& h)
 {
     uint8_t* base = const_cast<uint8_t*>(static_cast<const uint8_t*>(state));
@@ -329,9 +463,13 @@ static Ptrs pointers(const void* state, const Header& h)
     q.luts = reinterpret_cast<const Luts*>(base + h.off_luts);
     q.envs = reinterpret_cast<uint32_t*>(base + h.off_envs);
     q.maps = base + h.off_maps;
-    q.dl.count = reinterpret_cast<uint32_t*>(base + cx::DONE_COUNT_OFFSET);
-    q.dl.finished = q.dl.count + 1;
-    q.dl.list = reinterpret_cast<uint4*>(base + h.off_done);
+    q.ls.ctr = reinterpret_cast<uint32_t*>(base + h.off_ctrs);
+    q.ls.regen[0] = reinterpret_cast<uint4*>(base + h.off_regen0);
+    q.ls.regen[1] = reinterpret_cast<uint4*>(base + h.off_regen1);
+    q.ls.slow = reinterpret_cast<uint4*>(base + h.off_slow);
+    q.ls.tags = reinterpret_cast<uint2*>(base + h.off_tags);
+    q.ls.sub_cap = (uint32_t)la::sub_list_capacity((uint64_t)h.n, ENVS_PER_BLOCK);
+    q.ls.slow_cap = h.n;
     return q;
 }
 static Params make_params(const craftax_config* c, int n)
@@ -366,7 +504,7 @@ int state_init(void* state, const craftax_config* cfg, int n, void* stream, std:
 int reset(void* state, const craftax_config* cfg, int n, const uint64_t* seeds, void* stream, std::string* err)
 {
     const Ptrs q = pointers(state, make_header(cfg, n));
-    hipLaunchKernelGGL(kf_reset, dim3((unsigned)n * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, seeds, q.dl.count, q.dl.finished);
+    hipLaunchKernelGGL(kf_reset, dim3((unsigned)n * 2 * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, seeds, q.ls);
     return check_launch("craftax_reset", err);
 }
 
@@ -377,13 +515,17 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
     const Params p = make_params(cfg, n);
     hipStream_t st = (hipStream_t)stream;
     uint8_t* o = static_cast<uint8_t*>(obs);
-    const dim3 grid((n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK), rgrid((unsigned)(n < RESET_SLOTS ? n : RESET_SLOTS) * FLOORS);
+    const int sb = (n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK;
+    const int unit = NSUB * NTAG;                                            // regeneration blocks come in multiples of this
+    const int want = NTAG * n < REGEN_BLOCKS ? NTAG * n : REGEN_BLOCKS;
+    const dim3 grid((unsigned)(sb + (want + unit - 1) / unit * unit)), rgrid((unsigned)(n < RESET_SLOTS ? n : RESET_SLOTS) * FLOORS);
+    const bool slow = p.max_episode_steps == 1u;   // the only way an episode can end before its spare world exists
     if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) {
-        hipLaunchKernelGGL(kf_step<true>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.dl, p);
-        hipLaunchKernelGGL(kf_reset_list<true>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.dl);
+        hipLaunchKernelGGL(kf_step<true>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, sb);
+        if (slow) hipLaunchKernelGGL(kf_reset_list<true>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls);
     } else {
-        hipLaunchKernelGGL(kf_step<false>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.dl, p);
-        hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.dl);
+        hipLaunchKernelGGL(kf_step<false>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, sb);
+        if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls);
     }
     return check_launch("craftax_step", err);
 }
@@ -409,8 +551,9 @@ int export_envs(const void* state, const craftax_config* cfg, int n, int first, 
 int import_envs(void* state, const craftax_config* cfg, int n, int first, int count, const void* dumps, void* stream, std::string* err)
 {
     const Ptrs q = pointers(state, make_header(cfg, n));
-    hipLaunchKernelGGL(kf_import, dim3(count), dim3(BLOCK), 0, (hipStream_t)stream, q.envs, q.maps,
+    hipLaunchKernelGGL(kf_import, dim3(count), dim3(BLOCK), 0, (hipStream_t)stream, q.envs, q.maps, q.ls,
                        static_cast<const craftax_full_env_dump*>(dumps), first, make_params(cfg, n));
+    hipLaunchKernelGGL(kf_import_spare, dim3((unsigned)count * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, q.ls, first);
     return check_launch("craftax_import_envs", err);
 }
 

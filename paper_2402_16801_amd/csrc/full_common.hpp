@@ -7,6 +7,7 @@
 #include <stdint.h>
 
 #include "common.hpp"
+#include "lookahead.hpp"
 
 namespace cf {
 
@@ -124,8 +125,10 @@ __device__ inline bool passable_for(int col, int b)
 __device__ inline bool inb(int x, int y) { return ((unsigned)x < (unsigned)W) & ((unsigned)y < (unsigned)W); }
 
 // ---- in-HBM layout ----------------------------------------------------------------------------
-// Per environment: a 1024-byte block = a 64-dword record followed by nine 16-dword mob tables
-// (one 64-byte table per floor, slots 0..13 used), and 9 floors x (block map 2304 B + item/light
+// Per environment: a 1024-byte block = a 64-dword record, nine 16-dword mob tables (one 64-byte
+// table per floor, slots 0..13 used) and, from dword 208 on, the ladders and the potion map of
+// the world waiting in the spare map slot; and two map slots (the world of episode e in slot
+// e & 1, the world of episode e + 1 in the other) of 9 floors x (block map 2304 B + item/light
 // map 2304 B), row-major 48-byte rows.  The second map holds item | light << 3 per cell.
 //   r0  px | py<<8 | dir<<16 | floor<<24
 //   r1  sleeping | resting<<1 | fireball<<2 | iceball<<3 | book<<4 | pickaxe<<6 | sword<<9 | sword_ench<<12 |
@@ -141,9 +144,13 @@ __device__ inline bool inb(int x, int y) { return ((unsigned)x < (unsigned)W) & 
 // mob word:   alive | x<<1 | y<<7 | dir<<13 | hp<<16 | cd<<21 | type<<25      (0 when the slot is empty)
 // plant word: alive | x<<1 | y<<7 | age<<16
 constexpr int ENV_DWORDS = 256, REC_DWORDS = 64, MOBTAB_DWORDS = 16;
+constexpr int SPARE_LADDER = 208, SPARE_PERM = 217;   // dwords of the environment block describing the spare world
+constexpr int FLOOR_PARTS = 3;                        // a regenerated floor is split over this many blocks
+constexpr int NTAG = 9 * FLOOR_PARTS;                 // spare-world tags per environment: one per part of a floor
 constexpr int R_POS = 0, R_FLAGS = 1, R_ATTR = 2, R_INV = 3, R_POT = 6, R_VIT = 7, R_MANA = 8, R_CNT = 9, R_PERM = 10,
               R_KILLS = 11, R_LADDER = 14, R_ACH = 23, R_T = 26, R_EPISODE = 27, R_SEED_LO = 28, R_SEED_HI = 29, R_PLANT = 32;
-constexpr size_t MAP_BYTES = (size_t)FLOORS * 2 * CELLS;          // 41472 per environment
+constexpr size_t MAP_BYTES = (size_t)FLOORS * 2 * CELLS;          // 41472 per map slot
+__host__ __device__ inline size_t map_offset(uint32_t env, uint32_t episode) { return ((size_t)env * 2 + (episode & 1u)) * MAP_BYTES; }
 __device__ inline size_t block_off(int f, int x, int y) { return (size_t)f * (2 * CELLS) + (size_t)(y * W + x); }
 __device__ inline size_t il_off(int f, int x, int y) { return (size_t)f * (2 * CELLS) + CELLS + (size_t)(y * W + x); }
 
@@ -174,9 +181,9 @@ struct Header {
     uint32_t version, n;
     uint32_t variant, obs_mode, max_episode_steps, day_length;
     uint32_t cap_melee, cap_ranged, cap_passive, cap_plant;
-    uint64_t off_luts, off_envs, off_maps, off_done, total;
+    uint64_t off_ctrs, off_luts, off_envs, off_maps, off_tags, off_regen0, off_regen1, off_slow, total;
 };
-static_assert(sizeof(Header) <= cx::DONE_COUNT_OFFSET, "header overlaps the done-list counters");
+static_assert(sizeof(Header) <= cx::HEADER_BYTES, "header outgrew its area");
 constexpr uint64_t MAGIC = 0x46554C4C43524158ull;
 
 struct Params {
@@ -194,8 +201,14 @@ constexpr int L_REC = 0;                         // 64 dwords
 constexpr int L_WB = 64;                         // 44 dwords: block window
 constexpr int L_WI = 108;                        // 44 dwords: item/light window
 constexpr int L_CRE = 152;                       // 100 dwords: creature channel per view cell
-constexpr int L_STAGE = 256;                     // 2112 dwords: the byte layout of the observation
-constexpr int L_ENV_DWORDS = L_STAGE + STRIDE_U8 / 4;   // 2368
+constexpr int L_BITS = 252;                      // 260 dwords: one bit per cell byte of the observation (8217 bits)
+constexpr int L_LIGHT = 512;                     // 28 dwords: light level per view cell (bytes)
+constexpr int L_VEC = 540;                       // 52 dwords: the 51 scalars and a zero
+constexpr int L_SPARE_WB = 592;                  // 44 dwords: block window of the start position of the spare world
+constexpr int L_SPARE_WI = 636;                  // 44 dwords: its item/light window
+constexpr int L_SPARE_TAG = 680;                 // 54 dwords: the 27 (episode, launch) tags of the spare world
+constexpr int L_SPARE_HDR = 734;                 // 10 dwords: ladders and potion map of the spare world
+constexpr int L_ENV_DWORDS = 744;
 constexpr int ENVS_PER_BLOCK = 4, BLOCK = 256;
 
 __device__ inline void wave_sync()

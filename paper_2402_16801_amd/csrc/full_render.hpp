@@ -1,15 +1,13 @@
 // Symbolic observation of full Craftax (appendix "Observation Space"): 9 x 11 cells around the
 // player, per cell one-hot block (37) + item (5) + creature (40: five slot classes of eight
 // types) + light; cells darker than 0.05 are blank; then the 51 scalars of the inventory table.
-// The wave first builds the byte layout in LDS (zero fill, then a few byte stores per cell),
-// then streams it out as whole cache lines, or expands it to floats for the flat layout.
+// The wave stages the one-hot bytes as bits in LDS and expands them while streaming out whole
+// cache lines (byte layout) or floats (flat layout).
 #pragma once
 
 #include "full_common.hpp"
 
 namespace cf {
-
-constexpr int LIGHT_TAG = 0x80;    // marks the light byte of a cell while the float layout is expanded
 
 // Where scalar i of the observation comes from: record word, shift, mask, and how the raw
 // integer becomes a float.  Direction, daylight and "floor cleared" are handled apart.
@@ -75,9 +73,15 @@ __device__ inline int creature_channel(int k, int type)
     return 42 + 32 + type;
 }
 
+// one-hot nibble -> four bytes of 0/1
+__device__ inline uint32_t spread4(uint32_t nibble) { return (nibble * 0x00204081u) & 0x01010101u; }
+
 // e: the wave's LDS area holding the packed record (current), the two windows with origin
 // (wx0, wy0) on the current floor; m_*: this lane's mob slot.  F32 = false: writes the
 // 8448-byte layout; F32 = true: writes float[8268] (+ zero padding to 33152 bytes).
+// The one-hot bytes are staged as single bits (a few LDS atomics per cell) next to a light level
+// per cell; every lane then expands 16 bits at a time into one 16-byte piece of the output, so
+// that a wavefront writes whole cache lines.
 template <bool F32>
 __device__ inline void render_env(const int l, uint32_t* e, const int wx0, const int wy0, const int m_alive, const int m_x,
                                   const int m_y, const int m_type, const Luts* __restrict__ luts, uint8_t* __restrict__ out)
@@ -86,90 +90,105 @@ __device__ inline void render_env(const int l, uint32_t* e, const int wx0, const
     const uint8_t* wb = reinterpret_cast<const uint8_t*>(e + L_WB);
     const uint8_t* wi = reinterpret_cast<const uint8_t*>(e + L_WI);
     uint32_t* cre = e + L_CRE;
-    uint8_t* stage = reinterpret_cast<uint8_t*>(e + L_STAGE);
+    uint32_t* bits = e + L_BITS;
+    uint8_t* light = reinterpret_cast<uint8_t*>(e + L_LIGHT);
+    float* vec = reinterpret_cast<float*>(e + L_VEC);
     const uint32_t pos = uniu(rec[R_POS]);
     const int px = pos & 0xFF, py = (pos >> 8) & 0xFF;
-    {
-        uint4* z = reinterpret_cast<uint4*>(stage);
 #pragma unroll
-        for (int it = 0; it < 9; ++it) {
-            const int i = l + 64 * it;
-            if (i < STRIDE_U8 / 16) z[i] = make_uint4(0u, 0u, 0u, 0u);
-        }
-        cre[l] = 0xFFFFFFFFu;
-        if (l + 64 < NCELL + 1) cre[l + 64] = 0xFFFFFFFFu;
+    for (int it = 0; it < 5; ++it) {
+        const int i = l + 64 * it;
+        if (i < 260) bits[i] = 0u;
     }
+    cre[l] = 0xFFFFFFFFu;
+    if (l + 64 < NCELL + 1) cre[l + 64] = 0xFFFFFFFFu;
     wave_sync();
     if (l < NSLOT && m_alive) {
         const int vr = m_y - (py - VROWS / 2), vc = m_x - (px - VCOLS / 2);
         if ((unsigned)vr < (unsigned)VROWS && (unsigned)vc < (unsigned)VCOLS)
             atomicMin(&cre[vr * VCOLS + vc], ((uint32_t)l << 8) | (uint32_t)creature_channel(l, m_type));   // lowest slot wins
     }
-    if (l < NVEC) reinterpret_cast<float*>(stage + VEC_OFFSET)[l] = scalar_value(l, rec, luts);
+    if (l < NVEC + 1) vec[l] = l < NVEC ? scalar_value(l, rec, luts) : 0.0f;
     wave_sync();
+    auto set_bit = [&](int i) { atomicOr(&bits[i >> 5], 1u << (i & 31)); };
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const int cell = l + 64 * it;
         if (cell < NCELL) {
             const int r = cell / VCOLS, c = cell - r * VCOLS;
             const int x = px - VCOLS / 2 + c, y = py - VROWS / 2 + r;
-            uint8_t* ch = stage + cell * NCHAN;
+            int lv = 0;
             if (!inb(x, y)) {   // beyond the edge of the map: always visible
-                ch[B_OOB] = 1; ch[37 + IT_NONE] = 1; ch[82] = (uint8_t)(F32 ? (LIGHT_TAG | MAX_LIGHT) : MAX_LIGHT);
+                set_bit(cell * NCHAN + B_OOB); set_bit(cell * NCHAN + 37 + IT_NONE); lv = MAX_LIGHT;
             } else {
-                const int il = wi[(y - wy0) * WIN_PITCH + (x - wx0)], light = il >> 3;
-                if (light != 0) {
-                    ch[wb[(y - wy0) * WIN_PITCH + (x - wx0)]] = 1;
-                    ch[37 + (il & 7)] = 1;
+                const int il = wi[(y - wy0) * WIN_PITCH + (x - wx0)];
+                lv = il >> 3;
+                if (lv != 0) {      // cells darker than 0.05 stay blank
+                    set_bit(cell * NCHAN + (wb[(y - wy0) * WIN_PITCH + (x - wx0)] & 63));
+                    set_bit(cell * NCHAN + 37 + (il & 7));
                     const uint32_t cr = cre[cell];
-                    if (cr != 0xFFFFFFFFu) ch[cr & 0xFFu] = 1;
-                    ch[82] = (uint8_t)(F32 ? (LIGHT_TAG | light) : light);
+                    if (cr != 0xFFFFFFFFu) set_bit(cell * NCHAN + (int)(cr & 0xFFu));
                 }
             }
+            light[cell] = (uint8_t)lv;
         }
     }
     wave_sync();
+    // piece j covers bytes [16j, 16j+16) of the cell area; the one light byte inside it (cell c,
+    // byte 83c + 82) is patched in
+    auto light_in_piece = [&](int j, int* at, int* lv) {
+        *at = -1; *lv = 0;
+        if (16 * j + 15 >= 82) {
+            const int c = (16 * j + 15 - 82) / NCHAN, p = NCHAN * c + 82;
+            if (p >= 16 * j && c < NCELL) { *at = p - 16 * j; *lv = light[c]; }
+        }
+    };
     if (!F32) {
-        const uint4* src = reinterpret_cast<const uint4*>(stage);
         uint4* dst = reinterpret_cast<uint4*>(out);
 #pragma unroll
         for (int it = 0; it < 9; ++it) {
-            const int i = l + 64 * it;
-            if (i < STRIDE_U8 / 16) {
-                const uint4 v = src[i];
-                __builtin_nontemporal_store(v.x, &dst[i].x);
-                __builtin_nontemporal_store(v.y, &dst[i].y);
-                __builtin_nontemporal_store(v.z, &dst[i].z);
-                __builtin_nontemporal_store(v.w, &dst[i].w);
+            const int j = l + 64 * it;
+            if (j < STRIDE_U8 / 16) {
+                uint32_t v[4] = { 0u, 0u, 0u, 0u };
+                if (j < VEC_OFFSET / 16) {
+                    const uint32_t b16 = (bits[j >> 1] >> ((j & 1) * 16)) & 0xFFFFu;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) v[k] = spread4((b16 >> (4 * k)) & 15u);
+                    int at, lv;
+                    light_in_piece(j, &at, &lv);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) if ((at >> 2) == k) v[k] |= (uint32_t)lv << (8 * (at & 3));
+                } else if (j < VEC_OFFSET / 16 + (NVEC + 3) / 4) {
+                    const uint4 f = reinterpret_cast<const uint4*>(e + L_VEC)[j - VEC_OFFSET / 16];
+                    v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+                }
+                __builtin_nontemporal_store(v[0], &dst[j].x);
+                __builtin_nontemporal_store(v[1], &dst[j].y);
+                __builtin_nontemporal_store(v[2], &dst[j].z);
+                __builtin_nontemporal_store(v[3], &dst[j].w);
             }
         }
     } else {
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(stage);
-        const float* vec = reinterpret_cast<const float*>(stage + VEC_OFFSET);
         float4* dst = reinterpret_cast<float4*>(out);
 #pragma unroll 1
-        for (int q = l; q < STRIDE_F32 / 16; q += 64) {
-            float v[4];
-            if (4 * q + 3 < CELL_BYTES) {
-                const uint32_t w = src[q];
+        for (int j = l; j < STRIDE_F32 / 64; j += 64) {   // 16 floats per piece
+            const uint32_t b16 = j < 520 ? (bits[j >> 1] >> ((j & 1) * 16)) & 0xFFFFu : 0u;
+            int at, lv;
+            light_in_piece(j, &at, &lv);
+            const float lf = luts->light20[lv];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t b = (w >> (8 * j)) & 0xFFu;
-                    v[j] = (b & LIGHT_TAG) ? luts->light20[b & 31u] : (float)b;
-                }
-            } else {
+            for (int q = 0; q < 4; ++q) {
+                float v[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int idx = 4 * q + j;
+                for (int k = 0; k < 4; ++k) {
+                    const int idx = 16 * j + 4 * q + k;
                     float f = 0.0f;
-                    if (idx < CELL_BYTES) {
-                        const uint32_t b = stage[idx];
-                        f = (b & LIGHT_TAG) ? luts->light20[b & 31u] : (float)b;
-                    } else if (idx < CELL_BYTES + NVEC) f = vec[idx - CELL_BYTES];
-                    v[j] = f;
+                    if (idx < CELL_BYTES) f = (4 * q + k == at) ? lf : (float)((b16 >> (4 * q + k)) & 1u);
+                    else if (idx < CELL_BYTES + NVEC) f = vec[idx - CELL_BYTES];
+                    v[k] = f;
                 }
+                dst[4 * j + q] = make_float4(v[0], v[1], v[2], v[3]);
             }
-            dst[q] = make_float4(v[0], v[1], v[2], v[3]);
         }
     }
 }

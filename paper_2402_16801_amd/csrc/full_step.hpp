@@ -126,9 +126,12 @@ enum Intent : int { N_NONE = 0, N_DAMAGE, N_DAMAGE_DIE, N_DIE, N_MOVE, N_SHOOT, 
 
 // e: this wave's LDS area with the record loaded.  genv: the environment's 1024-byte block in
 // HBM.  maps: its floors.  m, qw: this lane's mob slot (current floor) and plant word.
+// after_load: called once the loads of the current window have been issued and stored, before the
+// wave waits for them (the caller parks data it fetched earlier there).
+template <typename AfterLoad>
 __device__ inline StepOut step_env(const int l, const uint32_t env, uint32_t* e, uint32_t* __restrict__ genv,
                                    uint8_t* __restrict__ maps, const Luts* __restrict__ luts, const int action_in,
-                                   const Params& p, MobRegs& m, uint32_t& qw, Player& P)
+                                   const Params& p, MobRegs& m, uint32_t& qw, Player& P, AfterLoad&& after_load)
 {
     uint32_t* rec = e + L_REC;
     uint8_t* wb = reinterpret_cast<uint8_t*>(e + L_WB);
@@ -155,6 +158,7 @@ __device__ inline StepOut step_env(const int l, const uint32_t env, uint32_t* e,
     if (q_alive) q_block = maps[block_off(0, q_x, q_y)];
     int wx0 = P.px - WIN_COLS / 2, wy0 = P.py - WIN_ROWS / 2;
     load_window(l, maps, P.floor, P.px, P.py, wb, wi);
+    after_load();
     wave_sync();
 
     auto win_b = [&](int x, int y) { return uni((int)wb[(y - wy0) * WIN_PITCH + (x - wx0)]); };

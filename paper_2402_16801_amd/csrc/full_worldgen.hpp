@@ -179,11 +179,16 @@ __device__ inline void make_cave_ladders(GenLayout& L, int f, const U4& r)
 // needs, and may drop the cells around the start position into an LDS window (start_wb /
 // start_wi, 11 x 16 bytes each) for the first observation.  maps: this environment's 41472
 // bytes.  s_lat, L: LDS scratch.  Ends with a block barrier.
+// first_run, runs: the part of the floor this call generates (a floor may be split over several
+// blocks); runs <= NT.
+template <int NT = GEN_THREADS>
 __device__ inline void worldgen_floor_block(uint8_t* __restrict__ maps, uint16_t* s_lat, GenLayout& L, uint32_t lo, uint32_t hi,
                                             uint32_t env, uint32_t episode, int f, uint8_t* start_wb = nullptr,
-                                            uint8_t* start_wi = nullptr)
+                                            uint8_t* start_wi = nullptr, int first_run = 0, int runs = GEN_THREADS)
 {
-    const int tid = threadIdx.x;
+    static_assert(NT >= 128, "the layout phase uses thread indices up to 101");
+    const int tid0 = threadIdx.x;
+    { const int tid = tid0;
     if (f == 0) {
         if (tid < LAT0_BLOCKS) put_lattice(s_lat + tid * 8, wg_block(lo, hi, env, episode, 0u, (uint32_t)tid));
         else if (tid >= 64 && tid < 88) {
@@ -221,6 +226,11 @@ __device__ inline void worldgen_floor_block(uint8_t* __restrict__ maps, uint16_t
         if (tid < LATC_BLOCKS) put_lattice(s_lat + tid * 8, wg_block(lo, hi, env, episode, (uint32_t)f * 4u, (uint32_t)tid));
         else if (tid == 32) make_cave_ladders(L, f, wg_block(lo, hi, env, episode, (uint32_t)f * 4u + 2u, 0u));
     }
+    }
+    __syncthreads();
+    // one run of 4 cells per thread (the callers give a block no more runs than it has threads)
+    if (tid0 < runs) {
+    const int tid = first_run + tid0;
     const int y = tid / 12, x = (tid - y * 12) * 4;
     const bool needs_u = !(f == 1 || f == 4 || f == 8);
     uint32_t rw0 = 0u, rw1 = 0u;
@@ -230,7 +240,6 @@ __device__ inline void worldgen_floor_block(uint8_t* __restrict__ maps, uint16_t
         rw0 = (tid & 1) ? r.w[2] : r.w[0];
         rw1 = (tid & 1) ? r.w[3] : r.w[1];
     }
-    __syncthreads();
     const uint32_t light = lit_floor(f) ? (uint32_t)MAX_LIGHT << 3 : 0u;
     uint32_t pb = 0u, pi = 0u;
     auto put = [&](int j, int cell) {
@@ -268,24 +277,31 @@ __device__ inline void worldgen_floor_block(uint8_t* __restrict__ maps, uint16_t
             }
         }
     }
+    }
     __syncthreads();
+}
+
+// The ten dwords that describe a generated world beyond its maps: ladders of the nine floors and
+// the potion permutation (valid in the block that generated floor 0).
+__device__ inline uint32_t layout_word(const GenLayout& L, int i)
+{
+    if (i < FLOORS) return (uint32_t)L.up[i][0] | ((uint32_t)L.up[i][1] << 8) | ((uint32_t)L.down[i][0] << 16) | ((uint32_t)L.down[i][1] << 24);
+    return L.perm;
 }
 
 // Word i (0..63) of the record of a fresh episode: player in the middle of the overworld
 // facing down, vitals 9, attributes 1, boss vulnerable, floor 0 visited.
-__device__ inline uint32_t fresh_record_word(int i, const GenLayout& L, uint32_t lo, uint32_t hi, uint32_t episode)
+// layout: the ten layout_word values of the world.
+__device__ inline uint32_t fresh_record_word(int i, const uint32_t* layout, uint32_t lo, uint32_t hi, uint32_t episode)
 {
-    if (i >= R_LADDER && i < R_LADDER + FLOORS) {
-        const int f = i - R_LADDER;
-        return (uint32_t)L.up[f][0] | ((uint32_t)L.up[f][1] << 8) | ((uint32_t)L.down[f][0] << 16) | ((uint32_t)L.down[f][1] << 24);
-    }
+    if (i >= R_LADDER && i < R_LADDER + FLOORS) return layout[i - R_LADDER];
     switch (i) {
     case R_POS: return (uint32_t)(W / 2) | ((uint32_t)(W / 2) << 8) | (4u << 16);
     case R_FLAGS: return 1u << 17;
     case R_ATTR: return (1u << 20) | (1u << 23) | (1u << 26);
     case R_VIT: return 0x09090909u;
     case R_MANA: return 9u;
-    case R_PERM: return L.perm | (1u << 18);
+    case R_PERM: return layout[FLOORS] | (1u << 18);
     case R_EPISODE: return episode;
     case R_SEED_LO: return lo;
     case R_SEED_HI: return hi;

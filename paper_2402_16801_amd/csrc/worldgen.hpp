@@ -66,8 +66,8 @@ __device__ inline int classify(int W, int M, int C, int F, int x, int y, int u)
     return BK_GRASS;
 }
 
-// Generates the map of one environment with the NT threads of the calling block (512, or
-// fewer with each thread taking several runs): run t owns the 8 cells [8t, 8t+8) of row t/8, which are exactly one spacing-8
+// Generates the map of one environment, or a part of it, with the NT threads of the calling
+// block: run t owns the 8 cells [8t, 8t+8) of row t/8, which are exactly one spacing-8
 // lattice cell wide (and inside one spacing-16 cell), and whose per-cell uniforms are
 // exactly Philox block t of stream 1.  A reset is latency-bound, so the work is cut into
 // many short threads and two such blocks fit on a compute unit.
@@ -79,7 +79,7 @@ constexpr int WG_THREADS = 512;
 // threads that own those cells drop them there, so the first observation of the new episode
 // can be rendered without reading the map back.
 // first_run, runs: the part of the world this call generates (runs first_run .. first_run + runs - 1
-// of the 512; a world may be split over several blocks).
+// of the 512; a world may be split over several blocks); runs <= NT.
 template <int NT = WG_THREADS>
 __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat, uint32_t seed_lo, uint32_t seed_hi,
                                       uint32_t env, uint32_t episode, uint32_t* start_win = nullptr, int first_run = 0,
@@ -97,8 +97,9 @@ __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat
         }
     }
     __syncthreads();
-#pragma unroll 1
-    for (int tid = first_run + tid0; tid < first_run + runs; tid += NT) {   // a block smaller than its share takes several runs per thread
+    // one run of 8 cells per thread (the callers give a block no more runs than it has threads)
+    if (tid0 < runs) {
+    const int tid = first_run + tid0;
     const U4 r = philox4x32_10(env, 1u, episode, (DOM_WORLDGEN << 16) | (uint32_t)tid, seed_lo, seed_hi);
     const int y = tid >> 3, x0 = (tid & 7) << 3;
     const uint16_t* w16 = s_lat;
