@@ -210,7 +210,7 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": read_profile_traffic("craftax_step_sym_u8_f32_65536env.txt"),
-            "kernel": "k_step<4 lanes, SYM_U8_F32> + k_reset_list (one craftax_step call)",
+            "kernel": "k_step<4 lanes, SYM_U8_F32>: step blocks + regeneration blocks, one launch per craftax_step call",
             "alg_bytes_per_env_step": round(alg["total"], 1),
             "alg_bytes_per_launch": per_launch_bytes,
             "avg_launch_us": launch_s * 1e6,
@@ -250,7 +250,7 @@ def craftax_line(args, with_cpu: bool = True) -> dict:
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": read_profile_traffic("craftax_full_step_sym_u8_f32_4096env.txt"),
-            "kernel": "kf_step<SYM_U8_F32> + kf_reset_list (one craftax_step call)",
+            "kernel": "kf_step<SYM_U8_F32>: step blocks + regeneration blocks, one launch per craftax_step call",
             "alg_bytes_per_env_step": round(alg["total"], 1), "alg_bytes_per_launch": alg["total"] * n,
             "avg_launch_us": launch_s * 1e6,
         },
