@@ -237,6 +237,92 @@ def test_full_null_observation_and_determinism(cx):
     assert outs[0] == outs[1]
 
 
+def test_full_episode_ends_on_the_first_step_after_an_import(cx):
+    """Edited states that die or run out of time at once: the next world has to be there already,
+    also when the import lands while older worlds are still being prepared."""
+    import torch
+    n = 30
+    gcfg, ocfg = _cfgs(cx, 1, max_episode_steps=300)
+    sim = cx.Craftax(n, gcfg)
+    orc = po.FullOracle(n, ocfg)
+    seeds = synth.seeds_for(n, 400)
+    sim.reset(seeds); orc.reset(seeds)
+
+    def both(a):
+        obs, rew, done = sim.step(torch.as_tensor(a, device=sim.device))
+        oobs, orew, odone = orc.step(a)
+        assert np.array_equal(done.cpu().numpy(), odone)
+        assert np.array_equal(rew.cpu().numpy().view(np.uint32), orew.view(np.uint32))
+        assert np.array_equal(obs.cpu().numpy(), oobs)
+        compare_state(sim, orc, np.arange(n), "a step")
+        return odone
+
+    for s in range(4):
+        both(synth.actions(np.arange(n), s, "skewed", 9, 43))
+    for round_ in range(3):
+        e = orc.envs
+        e["t"][0::3] = 299                          # out of time at the next step
+        e["vit"][1::3] = [1, 0, 0, 0, 5]            # starving: the recover counter takes the last health point
+        e["cnt"][1::3] = [0, 0, 0, -30, 0]
+        e["episode"][2::3] += 3 + round_            # other episode index: other map slot, other worlds ahead
+        sim.import_envs(e.copy())
+        d = both(np.zeros(n, np.int32))
+        assert d[0::3].all() and d[1::3].all() and not d[2::3].any()
+        for s in range(3):
+            both(synth.actions(np.arange(n), 10 * round_ + s, "uniform", 4, 43))
+    orc.envs["t"][:] = 299
+    sim.import_envs(orc.envs.copy())
+    assert both(np.zeros(n, np.int32)).all()
+    for s in range(5):
+        both(synth.actions(np.arange(n), 50 + s, "uniform", 4, 43))
+    sim.close()
+
+
+def test_full_one_step_episodes(cx):
+    """Episode cap 1: every step ends every episode, so the spare world is never ready in time and
+    the slow path (second kernel) alternates with the fast one; cap 2 for the fast path alone."""
+    run_full(cx, 21, 24, kind="uniform", state_every=1, max_episode_steps=1)
+    run_full(cx, 21, 30, kind="skewed", state_every=1, max_episode_steps=2)
+
+
+def test_full_step_captured_in_a_graph_and_replayed(cx):
+    """One craftax_step call captured in a HIP graph and replayed 90 times, actions refilled
+    between replays; every replay is checked against the oracle."""
+    import torch
+    n = 150
+    gcfg, ocfg = _cfgs(cx, 1, max_episode_steps=25)
+    sim = cx.Craftax(n, gcfg)
+    orc = po.FullOracle(n, ocfg)
+    seeds = synth.seeds_for(n, 31)
+    sim.reset(seeds); orc.reset(seeds)
+    a_buf = torch.zeros(n, dtype=torch.int32, device=sim.device)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            cx.craftax_step(sim.state, a_buf, sim.obs, sim.reward, sim.done, n, torch.cuda.current_stream())
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    compare_state(sim, orc, np.arange(n), "after capture")      # capturing executes nothing
+    finished = 0
+    for s in range(90):
+        a = synth.actions(np.arange(n), s, "skewed", 6, 43)
+        a_buf.copy_(torch.as_tensor(a, device=sim.device))
+        graph.replay()
+        torch.cuda.synchronize()
+        oobs, orew, odone = orc.step(a)
+        finished += int(odone.sum())
+        assert np.array_equal(sim.done.cpu().numpy(), odone), s
+        assert np.array_equal(sim.reward.cpu().numpy().view(np.uint32), orew.view(np.uint32)), s
+        assert np.array_equal(sim.obs.cpu().numpy(), oobs), s
+        if s % 10 == 9:
+            compare_state(sim, orc, np.arange(n), f"replay {s}")
+    assert finished >= 3 * n
+    sim.close()
+
+
 def test_full_config4_4096_envs_5000_steps(cx):
     """The benchmark shape of the full game: 4096 environments, 43 uniform actions generated on
     the device, 5000 steps; 128 sampled environments are checked against the oracle."""
