@@ -161,9 +161,15 @@ void cf_default_config(cf_config *cfg)
     cfg->day_length = 300;
     cfg->cap_melee = 3; cfg->cap_ranged = 2; cfg->cap_passive = 3;
     cfg->cap_plant = 10;
+    cfg->atlas_seed = 0;
 }
 size_t cf_env_bytes(void) { return sizeof(cf_env); }
-size_t cf_obs_bytes(int mode) { return mode == CF_OBS_U8_F32 ? 8448 : 33152; }   /* 66 and 259 cache lines */
+size_t cf_obs_bytes(int mode)
+{
+    if (mode == CF_OBS_U8_F32) return 8448;       /* 66 cache lines */
+    if (mode == CF_OBS_F32) return 33152;         /* 259 cache lines */
+    return 171648;                                /* 130 x 110 x 3 floats = 171600 bytes, padded to 1341 cache lines */
+}
 
 static void unlock(cf_env *e, int a) { e->ach[a >> 5] |= 1u << (a & 31); }
 
@@ -913,10 +919,73 @@ static void scalars(const cf_env *e, const cf_config *cfg, float v[CF_NVEC])
     v[i++] = (float)(e->floor == 0 || e->kills[e->floor] >= KILLS_TO_CLEAR);
     v[i++] = (float)e->boss_vulnerable;
 }
+/* ---- pixel observation (section "RL Environment Interface": 110 x 130 x 3 for Craftax, 10-pixel
+ * tiles per appendix "Observation Space").  Reading (the paper's textures are not available): the
+ * 9 x 11 view as tiles from a seeded atlas, then four rows of 11 inventory slots.
+ *   view cell: texel of its block tile; an item, then a creature, then the player (centre cell)
+ *   replace the pixels their 10x10 one-bit masks select; the result is multiplied by the cell's
+ *   light level / 20 (one multiply); cells of light 0 are black; cells beyond the map edge show
+ *   the tile of block 1 at full light.
+ *   inventory slot j (0..43), row 9 + j/11, column j%11: icon tile j times min(scalar j of the
+ *   symbolic observation, 1).
+ * Atlas: texel = (u >> 8) * 2^-24, u = Philox word (key = atlas seed, counter (0, stream, 0,
+ * ATLAS | idx/4), word idx%4); streams 8 block tiles [37][10][10][3], 9 item tiles [5], 10
+ * creature tiles [40] (by observation channel - 42), 11 the player tile, 12 icon tiles [44],
+ * 13 masks (top bit of word tile*100 + pixel; tiles: 5 items, 40 creatures, player). */
+enum { DOM_ATLAS = 3 };
+static float full_texel(uint64_t seed, uint32_t stream, uint32_t idx)
+{
+    uint32_t w = philox_word(seed, 0, stream, 0, DOM_ATLAS, idx >> 2, idx & 3u);
+    return (float)(w >> 8) * (1.0f / 16777216.0f);
+}
+static int full_mask(uint64_t seed, uint32_t tile, uint32_t pixel)
+{
+    uint32_t idx = tile * 100u + pixel;
+    return (int)(philox_word(seed, 0, 13, 0, DOM_ATLAS, idx >> 2, idx & 3u) >> 31);
+}
+static int creature_channel(const cf_env *e, int k);
+static void scalars(const cf_env *e, const cf_config *cfg, float v[CF_NVEC]);
+static void pixels(const cf_env *e, const cf_config *cfg, float *out)
+{
+    const int f = e->floor;
+    const uint64_t seed = cfg->atlas_seed;
+    float v[CF_NVEC];
+    scalars(e, cfg, v);
+    for (int y = 0; y < CF_PIX_ROWS; y++)
+        for (int x = 0; x < CF_PIX_COLS; x++) {
+            const int tr = y / 10, tc = x / 10, pix = (y % 10) * 10 + (x % 10);
+            for (int c = 0; c < 3; c++) {
+                const uint32_t in_tile = (uint32_t)(pix * 3 + c);
+                float px;
+                if (tr < CF_VIEW_ROWS) {
+                    const int mx = e->px + tc - CF_VIEW_COLS / 2, my = e->py + tr - CF_VIEW_ROWS / 2;
+                    int block = B_OOB, item = IT_NONE, light = MAX_LIGHT, k = -1;
+                    if (inb(mx, my)) {
+                        block = e->block[f][cell(mx, my)]; item = e->item[f][cell(mx, my)]; light = e->light[f][cell(mx, my)];
+                        k = mob_at(e, mx, my);
+                    }
+                    float texel = full_texel(seed, 8, (uint32_t)block * 300u + in_tile);
+                    if (item != IT_NONE && full_mask(seed, (uint32_t)item, (uint32_t)pix)) texel = full_texel(seed, 9, (uint32_t)item * 300u + in_tile);
+                    if (k >= 0) {
+                        const uint32_t ch = (uint32_t)creature_channel(e, k) - 42u;
+                        if (full_mask(seed, 5u + ch, (uint32_t)pix)) texel = full_texel(seed, 10, ch * 300u + in_tile);
+                    }
+                    if (mx == e->px && my == e->py && full_mask(seed, 45u, (uint32_t)pix)) texel = full_texel(seed, 11, in_tile);
+                    px = light == 0 ? 0.0f : texel * (float)((double)light / 20.0);
+                } else {
+                    const int j = (tr - CF_VIEW_ROWS) * 11 + tc;
+                    px = full_texel(seed, 12, (uint32_t)j * 300u + in_tile) * (v[j] < 1.0f ? v[j] : 1.0f);
+                }
+                out[(y * CF_PIX_COLS + x) * 3 + c] = px;
+            }
+        }
+}
+
 void cf_observe(const cf_env *e, const cf_config *cfg, int mode, void *obs)
 {
     uint8_t *o = (uint8_t *)obs;
     memset(o, 0, cf_obs_bytes(mode));
+    if (mode == CF_OBS_PIXELS_F32) { pixels(e, cfg, (float *)obs); return; }
     uint8_t cells[CF_VIEW_ROWS * CF_VIEW_COLS][CF_NCHAN];
     memset(cells, 0, sizeof(cells));
     const int f = e->floor;

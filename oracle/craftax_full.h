@@ -46,6 +46,7 @@ typedef struct {
     uint32_t day_length;
     uint32_t cap_melee, cap_ranged, cap_passive;   /* 3, 2, 3 */
     uint32_t cap_plant;
+    uint64_t atlas_seed;          /* seed of the synthetic tile atlas (pixel observations) */
 } cf_config;
 
 typedef struct {
@@ -83,7 +84,9 @@ typedef struct {
     uint8_t pad1[4];
 } cf_env;
 
-enum { CF_OBS_U8_F32 = 0, CF_OBS_F32 = 1 };
+enum { CF_OBS_U8_F32 = 0, CF_OBS_F32 = 1, CF_OBS_PIXELS_F32 = 2 };
+#define CF_PIX_ROWS 130   /* 9 view rows + 4 inventory rows of 10-pixel tiles */
+#define CF_PIX_COLS 110   /* 11 tile columns */
 
 size_t cf_env_bytes(void);
 size_t cf_obs_bytes(int mode);

@@ -38,8 +38,8 @@ assert ENV_DTYPE.itemsize == 4304
 
 
 # ---- full Craftax ------------------------------------------------------------------------
-FULL_OBS_U8_F32, FULL_OBS_F32 = 0, 1
-FULL_OBS_BYTES = {0: 8448, 1: 33152}
+FULL_OBS_U8_F32, FULL_OBS_F32, FULL_OBS_PIXELS_F32 = 0, 1, 2
+FULL_OBS_BYTES = {0: 8448, 1: 33152, 2: 171648}
 FULL_MOB_DTYPE = np.dtype([("alive", "u1"), ("x", "u1"), ("y", "u1"), ("dir", "u1"), ("hp", "i1"),
                            ("cd", "u1"), ("type", "u1"), ("pad", "u1")])
 FULL_ENV_DTYPE = np.dtype([
@@ -72,7 +72,7 @@ assert FULL_ENV_DTYPE.itemsize == 63432
 class FullConfig(ctypes.Structure):
     _fields_ = [("max_episode_steps", ctypes.c_uint32), ("day_length", ctypes.c_uint32),
                 ("cap_melee", ctypes.c_uint32), ("cap_ranged", ctypes.c_uint32),
-                ("cap_passive", ctypes.c_uint32), ("cap_plant", ctypes.c_uint32)]
+                ("cap_passive", ctypes.c_uint32), ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64)]
 
 
 class Config(ctypes.Structure):

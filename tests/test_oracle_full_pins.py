@@ -749,3 +749,91 @@ def test_step_is_rules_plus_reset_and_deterministic():
     assert a.envs.tobytes() == b.envs.tobytes()
     assert a.envs["episode"].sum() > 0
     assert np.array_equal(a.obs, b.observe())
+
+
+# ---- pixel observation ----------------------------------------------------------------------------
+def full_pixels(o, i=0):
+    return o.observe_one(i, po.FULL_OBS_PIXELS_F32)[:130 * 110 * 3 * 4].view(np.float32).reshape(130, 110, 3)
+
+
+def atlas_tile(seed, stream, tile):
+    """One 10x10x3 tile straight from the Philox known-answer-tested generator."""
+    out = np.zeros(300, np.float32)
+    for k in range(300):
+        idx = tile * 300 + k
+        w = po.philox([0, stream, 0, (3 << 16) | (idx >> 2)], [seed & 0xFFFFFFFF, seed >> 32])[idx & 3]
+        out[k] = np.float32(w >> 8) * np.float32(2.0 ** -24)
+    return out.reshape(10, 10, 3)
+
+
+def atlas_mask(seed, tile):
+    out = np.zeros(100, bool)
+    for k in range(100):
+        idx = tile * 100 + k
+        out[k] = po.philox([0, 13, 0, (3 << 16) | (idx >> 2)], [seed & 0xFFFFFFFF, seed >> 32])[idx & 3] >> 31
+    return out.reshape(10, 10)
+
+
+def test_pixel_observation_is_110_by_130_tiles_overlays_and_light():
+    assert po.FULL_OBS_BYTES[po.FULL_OBS_PIXELS_F32] >= 110 * 130 * 3 * 4      # section "RL Environment Interface"
+    seed = 0x1234567811
+    o = fresh(atlas_seed=seed)
+    e = arena(o, floor=1, fill="PATH")
+    e["px"], e["py"] = 3, 24                                   # two columns of the view hang over the map edge
+    e["block"][1][24, 5] = B["STONE"]
+    e["item"][1][24, 2] = 1                                    # a torch item left of the player
+    e["light"][1][24, 6] = 10
+    e["light"][1][23, 3] = 0
+    put_mob(e, 1, 0, 4, 25, C["Orc_Soldier"])                  # melee class, type slot 1
+    img = full_pixels(o)
+    tiles = img.reshape(13, 10, 11, 10, 3).transpose(0, 2, 1, 3, 4)
+    path, stone, oob = (atlas_tile(seed, 8, B[k]) for k in ("PATH", "STONE", "OOB"))
+    assert np.array_equal(tiles[0, 5], path) and np.array_equal(tiles[8, 10], path)
+    assert np.array_equal(tiles[4, 7], stone)
+    for r in range(9):
+        assert np.array_equal(tiles[r, 0], oob) and np.array_equal(tiles[r, 1], oob)   # beyond the edge, full light
+    assert np.array_equal(tiles[4, 8], path * np.float32(0.5))                 # light 10 of 20: one multiply
+    assert not tiles[3, 5].any()                                               # light 0 is black
+    # overlays replace exactly the pixels their masks select: torch (item tile 1), orc (creature tile 1), player
+    m = atlas_mask(seed, 1)
+    assert np.array_equal(tiles[4, 4], np.where(m[..., None], atlas_tile(seed, 9, 1), path))
+    m = atlas_mask(seed, 5 + 1)
+    assert np.array_equal(tiles[5, 6], np.where(m[..., None], atlas_tile(seed, 10, 1), path))
+    m = atlas_mask(seed, 45)
+    assert np.array_equal(tiles[4, 5], np.where(m[..., None], atlas_tile(seed, 11, 0), path))
+    assert 0.25 < m.mean() < 0.75
+    # a creature standing on an item shows over it; the item shows where the creature's mask is clear
+    put_mob(e, 1, 1, 2, 24, C["Orc_Soldier"])
+    both = full_pixels(o).reshape(13, 10, 11, 10, 3).transpose(0, 2, 1, 3, 4)[4, 4]
+    under = np.where(atlas_mask(seed, 1)[..., None], atlas_tile(seed, 9, 1), path)
+    assert np.array_equal(both, np.where(atlas_mask(seed, 6)[..., None], atlas_tile(seed, 10, 1), under))
+    # texels are multiples of 2^-24 below one
+    q = tiles[0, 5] * np.float32(2 ** 24)
+    assert np.array_equal(q, np.round(q)) and img.max() < 1.0 and img.min() >= 0.0
+
+
+def test_pixel_inventory_strip_follows_the_symbolic_scalars():
+    seed = 99
+    o = fresh(atlas_seed=seed)
+    e = arena(o, floor=0, fill="GRASS")
+    _, vec = split_f32(o.observe_one(0, po.FULL_OBS_F32))
+    strip = full_pixels(o)[90:].reshape(4, 10, 11, 10, 3).transpose(0, 2, 1, 3, 4).reshape(44, 10, 10, 3)
+    for j in range(44):
+        want = atlas_tile(seed, 12, j) * min(vec[j], np.float32(1.0))
+        assert np.array_equal(strip[j], want), j
+    assert not strip[0].any() and strip[30].any()              # no wood yet; the health slot is lit
+    # the strip changes with the inventory and only there
+    before = full_pixels(o).copy()
+    e["inv"][I_WOOD] = 25                                       # sqrt(25) / 10
+    e["xp"] = 15                                                # a scalar above one is clamped to full brightness
+    after = full_pixels(o)
+    assert np.array_equal(after[:90], before[:90])
+    strip = after[90:].reshape(4, 10, 11, 10, 3).transpose(0, 2, 1, 3, 4).reshape(44, 10, 10, 3)
+    _, vec = split_f32(o.observe_one(0, po.FULL_OBS_F32))
+    assert vec[0] == np.float32(0.5) and np.array_equal(strip[0], atlas_tile(seed, 12, 0) * np.float32(0.5))
+    j = int(np.flatnonzero(vec[:44] > 1)[0])
+    assert np.array_equal(strip[j], atlas_tile(seed, 12, j))
+    # another atlas seed gives another picture; the symbolic observation does not depend on it
+    o.cfg.atlas_seed = seed + 1
+    assert not np.array_equal(full_pixels(o), after)
+    assert np.array_equal(split_f32(o.observe_one(0, po.FULL_OBS_F32))[1], vec)
