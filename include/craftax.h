@@ -57,13 +57,22 @@ enum { CRAFTAX_VARIANT_CLASSIC = 0, CRAFTAX_VARIANT_CRAFTAX = 1 };
  * down), daylight, sleeping.  Scaled form follows appendix "Observation Space":
  * counts sqrt(n)/10, vitals x/10, flags 0/1.  Unused bytes of the stride are zero.
  *
- * Variant CRAFTAX supports two of the layouts (appendix "Observation Space": 9x11 cells, per
+ * Variant CRAFTAX supports three of the layouts (appendix "Observation Space": 9x11 cells, per
  * cell 37-way block, 5-way item and 40-way creature one-hots plus a light level, cells darker
  * than 0.05 blank; then 51 scalars; 99*83 + 51 = 8268):
  *  SYM_U8_F32 : bytes [0,8217) 9x11 cells x 83 channels, row-major (row, col, channel), channel
  *               82 = light level 0..20; float[51] scalars at byte 8224; stride 8448 (66 lines).
  *  SYM_F32    : float[8268] = the cell bytes as floats (light as level/20) followed by the 51
  *               scalars (the flat layout of the paper); stride 33152.
+ *  PIXELS_F32 : float[130][110][3] RGB in [0,1) (section "RL Environment Interface": 110 x 130 x 3;
+ *               10-pixel tiles): tile rows 0..8 are the 9x11 view, tile rows 9..12 hold inventory
+ *               slot j = 0..43 at row 9 + j/11, column j%11.  Tiles come from an atlas seeded by
+ *               cfg->atlas_seed (the paper's textures are not part of this library): a view cell
+ *               shows its block tile, overlaid by its item, creature and the player where their
+ *               one-bit masks are set, times light level / 20; cells beyond the map edge show
+ *               block 1 at full light; slot j shows icon j times min(scalar j, 1).  Stride 171648
+ *               (171600 bytes of pixels, zero padding).  craftax_step draws the picture in a
+ *               second kernel on the same stream.
  * Channels: 0..36 block id; 37..41 item (none, torch, ladder down, ladder up, blocked ladder
  * down); 42..81 creature = 42 + 8*class + type slot, classes melee, passive, ranged, mob
  * projectile, player projectile; melee and ranged type slot = the floor the creature lives on

@@ -10,6 +10,7 @@
 #include "worldgen.hpp"
 #include "full_common.hpp"
 #include "full_render.hpp"
+#include "full_pixels.hpp"
 #include "full_step.hpp"
 #include "full_worldgen.hpp"
 
@@ -410,7 +411,9 @@ static uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 bool config_ok(const craftax_config* c, std::string* why)
 {
     if (c->abi_version != CRAFTAX_ABI_VERSION) { *why = "abi_version mismatch"; return false; }
-    if (c->obs_mode != CRAFTAX_OBS_SYM_U8_F32 && c->obs_mode != CRAFTAX_OBS_SYM_F32) { *why = "the Craftax variant renders SYM_U8_F32 or SYM_F32"; return false; }
+    if (c->obs_mode != CRAFTAX_OBS_SYM_U8_F32 && c->obs_mode != CRAFTAX_OBS_SYM_F32 && c->obs_mode != CRAFTAX_OBS_PIXELS_F32) {
+        *why = "the Craftax variant renders SYM_U8_F32, SYM_F32 or PIXELS_F32"; return false;
+    }
     if (c->day_length < 2 || c->day_length > (uint32_t)MAX_DAY || (c->day_length & 1)) { *why = "day_length must be even and in 2..1024"; return false; }
     if (c->cap_zombie > 3 || c->cap_cow > 3 || c->cap_skeleton > 2) { *why = "caps: melee 0..3, passive 0..3, ranged 0..2"; return false; }
     if (c->cap_plant > (uint32_t)NPLANT) { *why = "cap_plant must be 0..10"; return false; }
@@ -453,6 +456,28 @@ static void build_luts(const craftax_config* c, Luts* L)
     for (int i = 0; i < 100; ++i) L->sqrt10[i] = (float)(std::sqrt((double)i) / 10.0);
     for (int i = 0; i < 32; ++i) L->tenth[i] = (float)((double)i / 10.0);
     for (int i = 0; i < 32; ++i) L->light20[i] = (float)((double)i / 20.0);
+    if (c->obs_mode != CRAFTAX_OBS_PIXELS_F32) return;
+    // tile atlas: word idx of stream s is word idx % 4 of Philox block (0, s, 0, ATLAS | idx / 4)
+    // under the atlas seed; streams 8 blocks, 9 items, 10 creatures, 11 player, 12 icons, 13 masks
+    const uint32_t k0 = (uint32_t)c->atlas_seed, k1 = (uint32_t)(c->atlas_seed >> 32);
+    auto fill = [&](uint32_t stream, uint32_t count, float* dst) {
+        for (uint32_t i = 0; i < count; i += 4) {
+            const cx::U4 r = cx::philox4x32_10(0u, stream, 0u, (cx::DOM_ATLAS << 16) | (i >> 2), k0, k1);
+            for (uint32_t k = 0; k < 4 && i + k < count; ++k) dst[i + k] = (float)(r.w[k] >> 8) * (1.0f / 16777216.0f);
+        }
+    };
+    fill(8, 37 * 300, L->atlas);
+    fill(9, 5 * 300, L->atlas + AT_ITEM * 300);
+    fill(10, 40 * 300, L->atlas + AT_CRE * 300);
+    fill(11, 300, L->atlas + AT_PLAYER * 300);
+    fill(12, 44 * 300, L->atlas + AT_ICON * 300);
+    for (uint32_t i = 0; i < 46 * 100; i += 4) {
+        const cx::U4 r = cx::philox4x32_10(0u, 13u, 0u, (cx::DOM_ATLAS << 16) | (i >> 2), k0, k1);
+        for (uint32_t k = 0; k < 4; ++k) {
+            const uint32_t t = (i + k) / 100, pix = (i + k) % 100;
+            if (r.w[k] >> 31) L->mask[t][pix / 10] |= (uint16_t)(1u << (pix % 10));
+        }
+    }
 }
 
 struct Ptrs { uint32_t* envs; uint8_t* maps; const Luts* luts; Lists ls; };
@@ -487,7 +512,10 @@ static int check_launch(const char* what, std::string* err)
 }
 
 size_t state_bytes(const craftax_config* cfg, int n) { return (size_t)make_header(cfg, n).total; }
-size_t obs_bytes(const craftax_config* cfg) { return cfg->obs_mode == CRAFTAX_OBS_SYM_F32 ? STRIDE_F32 : STRIDE_U8; }
+size_t obs_bytes(const craftax_config* cfg)
+{
+    return cfg->obs_mode == CRAFTAX_OBS_PIXELS_F32 ? STRIDE_PIXELS : cfg->obs_mode == CRAFTAX_OBS_SYM_F32 ? STRIDE_F32 : STRIDE_U8;
+}
 
 int state_init(void* state, const craftax_config* cfg, int n, void* stream, std::string* err)
 {
@@ -520,7 +548,12 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
     const int want = NTAG * n < REGEN_BLOCKS ? NTAG * n : REGEN_BLOCKS;
     const dim3 grid((unsigned)(sb + (want + unit - 1) / unit * unit)), rgrid((unsigned)(n < RESET_SLOTS ? n : RESET_SLOTS) * FLOORS);
     const bool slow = p.max_episode_steps == 1u;   // the only way an episode can end before its spare world exists
-    if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) {
+    if (cfg->obs_mode == CRAFTAX_OBS_PIXELS_F32) {
+        // the step runs without rendering; the picture is drawn from the state it leaves
+        hipLaunchKernelGGL(kf_step<false>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, (uint8_t*)nullptr, reward, done, q.ls, p, sb);
+        if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, (uint8_t*)nullptr, q.ls);
+        if (o != nullptr) hipLaunchKernelGGL(kf_pixels, dim3((unsigned)n), dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, o);
+    } else if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) {
         hipLaunchKernelGGL(kf_step<true>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, sb);
         if (slow) hipLaunchKernelGGL(kf_reset_list<true>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls);
     } else {
@@ -535,7 +568,8 @@ int observe(void* state, const craftax_config* cfg, int n, void* obs, void* stre
     const Ptrs q = pointers(state, make_header(cfg, n));
     const dim3 grid((n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK);
     uint8_t* o = static_cast<uint8_t*>(obs);
-    if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) hipLaunchKernelGGL(kf_observe<true>, grid, dim3(BLOCK), 0, (hipStream_t)stream, q.envs, q.maps, q.luts, o, n);
+    if (cfg->obs_mode == CRAFTAX_OBS_PIXELS_F32) hipLaunchKernelGGL(kf_pixels, dim3((unsigned)n), dim3(BLOCK), 0, (hipStream_t)stream, q.envs, q.maps, q.luts, o);
+    else if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) hipLaunchKernelGGL(kf_observe<true>, grid, dim3(BLOCK), 0, (hipStream_t)stream, q.envs, q.maps, q.luts, o, n);
     else hipLaunchKernelGGL(kf_observe<false>, grid, dim3(BLOCK), 0, (hipStream_t)stream, q.envs, q.maps, q.luts, o, n);
     return check_launch("craftax_observe", err);
 }

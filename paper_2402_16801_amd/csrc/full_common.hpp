@@ -174,7 +174,15 @@ struct Luts {
     float sqrt10[100];              // sqrt(n)/10
     float tenth[32];                // x/10
     float light20[32];              // light level / 20
+    // pixel observations: 10x10 RGB tiles, texel = (Philox word >> 8) * 2^-24 keyed by the atlas
+    // seed.  Tiles 0..36 blocks, 37..41 items, 42..81 creatures (observation channel - 42), 82
+    // the player, 83..126 inventory icons.  mask[t][row] bit x: overlay t covers that pixel
+    // (t: 0..4 items, 5..44 creatures, 45 the player).
+    float atlas[127 * 300];
+    uint16_t mask[46][10];
 };
+constexpr int AT_ITEM = 37, AT_CRE = 42, AT_PLAYER = 82, AT_ICON = 83, AT_TILES = 127;
+constexpr int MASK_CRE = 5, MASK_PLAYER = 45;
 
 struct Header {
     uint64_t magic;

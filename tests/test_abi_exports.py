@@ -58,7 +58,9 @@ def test_full_variant_sizes_and_defaults(lib):
     assert binding.craftax_obs_bytes(cfg) == 8448 >= 99 * 83 + 51 * 4
     cfg.obs_mode = binding.OBS_SYM_F32
     assert binding.craftax_obs_bytes(cfg) == 33152 >= 8268 * 4
-    for bad in (binding.OBS_SYM_U8_I8, binding.OBS_PIXELS_F32):
+    cfg.obs_mode = binding.OBS_PIXELS_F32
+    assert binding.craftax_obs_bytes(cfg) == 171648 >= 130 * 110 * 3 * 4
+    for bad in (binding.OBS_SYM_U8_I8, 4):
         cfg.obs_mode = bad
         assert binding.craftax_obs_bytes(cfg) == 0 and binding.craftax_state_bytes(cfg, 8) == 0
     cfg.obs_mode = binding.OBS_SYM_U8_F32

@@ -14,7 +14,7 @@ B_TABLE, B_FURNACE, B_PATH, B_CHEST, B_ENCH_FIRE, B_ENCH_ICE = 11, 12, 7, 23, 30
 ACH = {"PLACE_TORCH": 24, "ENTER_DUNGEON": 29, "OPEN_CHEST": 61, "DRINK_POTION": 62, "CAST_FIREBALL": 56,
        "FIRE_BOW": 53, "DAMAGE_NECROMANCER": 48, "ENCHANT_SWORD": 63, "MAKE_ARROW": 22, "MAKE_TORCH": 23,
        "LEARN_ICEBALL": 57, "MAKE_DIAMOND_ARMOUR": 27}
-ORACLE_MODE = {1: po.FULL_OBS_U8_F32, 2: po.FULL_OBS_F32}
+ORACLE_MODE = {1: po.FULL_OBS_U8_F32, 2: po.FULL_OBS_F32, 3: po.FULL_OBS_PIXELS_F32}
 
 
 @pytest.fixture(scope="module")
@@ -320,6 +320,52 @@ def test_full_step_captured_in_a_graph_and_replayed(cx):
         if s % 10 == 9:
             compare_state(sim, orc, np.arange(n), f"replay {s}")
     assert finished >= 3 * n
+    sim.close()
+
+
+def test_full_pixels_rollouts(cx):
+    """The 110 x 130 x 3 picture, every other step, on rich scenes of all floors (mobs, torches,
+    ladders, darkness) and on fresh worlds; one multiply per texel on both sides: bit-exact."""
+    run_full(cx, 18, 60, obs_mode=3, kind="skewed", prep=rich_scene, obs_every=2, state_every=30, atlas_seed=0xABCDEF0123)
+    run_full(cx, 10, 40, obs_mode=3, kind="uniform", obs_every=4, atlas_seed=5)
+    run_full(cx, 5, 6, obs_mode=3, kind="uniform", max_episode_steps=1, atlas_seed=5)       # every step ends an episode
+    run_full(cx, 6, 12, obs_mode=3, kind="skewed", max_episode_steps=3, obs_every=1, atlas_seed=6)
+
+
+def test_full_pixels_overlays_edges_and_strip(cx):
+    """A built scene: the view hangs over the map edge, creatures of every class stand on lit,
+    dim and dark cells and on items, the inventory is full."""
+    gcfg, ocfg = _cfgs(cx, 3, cap_melee=0, cap_ranged=0, cap_passive=0, atlas_seed=77)
+    n = 4
+    sim = cx.Craftax(n, gcfg)
+    orc = po.FullOracle(n, ocfg, po.FULL_OBS_PIXELS_F32)
+    seeds = synth.seeds_for(n, 9)
+    sim.reset(seeds)
+    orc.reset(seeds)
+    for i in range(n):
+        e = orc.envs[i]
+        f = (0, 2, 5, 8)[i]
+        e["floor"], e["px"], e["py"] = f, (2, 45, 24, 3)[i], (1, 46, 24, 44)[i]
+        x, y = int(e["px"]), int(e["py"])
+        e["light"][f][max(0, y - 4):y + 5, max(0, x - 5):x + 6] = np.arange(99).reshape(9, 11)[:min(48, y + 5) - max(0, y - 4), :min(48, x + 6) - max(0, x - 5)] % 21
+        e["item"][f][y, min(47, x + 1)] = 1
+        e["item"][f][min(47, y + 1), x] = 2
+        slots = ((0, 3), (3, 4), (5, 5), (8, 4), (11, 2), (12, 1), (1, 3))
+        spots = ((1, 0), (0, 1), (-1, 0), (0, -1), (1, 1), (-1, -1), (1, 0))         # the last shares a cell with slot 0
+        for (slot, typ), (dx, dy) in zip(slots, spots):
+            m = e["mob"][f][slot]
+            m["alive"], m["x"], m["y"], m["type"], m["hp"] = 1, min(47, max(0, x + dx)), min(47, max(0, y + dy)), typ, 3
+        e["inv"][:] = np.arange(10) * 9
+        e["potion"][:] = (0, 1, 4, 9, 16, 25)
+        e["xp"], e["vit"][0] = 14, 12
+        e["armour"] = (2, 1, 0, 2)
+    sim.import_envs(orc.envs)
+    cx.craftax_observe(sim.state, sim.obs, n, sim.stream)
+    got, want = sim.obs.cpu().numpy(), orc.observe()
+    assert got.shape == want.shape == (n, 171648)
+    assert np.array_equal(got, want)
+    img = got[:, :171600].view(np.float32).reshape(n, 130, 110, 3)
+    assert img.max() < 1.0 and img.min() >= 0.0 and (img[:, 90:] > 0).any()
     sim.close()
 
 
