@@ -8,7 +8,7 @@ workload is the 65,536-environment Craftax-Classic step; the 4,096-environment C
 the 4,096-environment full-Craftax step are measured next to it ("also", "also_craftax"), or
 alone with --workload craftax.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--envs N] [--workload classic|craftax] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--envs N] [--workload classic|craftax|craftax_pixels] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -70,13 +70,13 @@ def read_profile_traffic(name: str):
     return float(m.group(1)) if m else None
 
 
-def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, variant: str = "classic"):
+def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, variant: str = "classic", pixels: bool = False):
     import torch
     from paper_2402_16801_amd import binding as cx, synth
 
     dev = torch.device("cuda:0")
     if variant == "craftax":
-        cfg = cx.default_config(cx.VARIANT_CRAFTAX, obs_mode=cx.OBS_SYM_U8_F32)
+        cfg = cx.default_config(cx.VARIANT_CRAFTAX, obs_mode=cx.OBS_PIXELS_F32 if pixels else cx.OBS_SYM_U8_F32)
     else:
         cfg = cx.default_config(obs_mode=cx.OBS_SYM_U8_F32, max_episode_steps=10000)
     sim = cx.Craftax(n, cfg)
@@ -107,6 +107,17 @@ def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, varian
         torch.cuda.synchronize()
         wall.append(time.perf_counter() - t0)
         evt.append(e0.elapsed_time(e1) * 1e-3)
+    draw_s = None
+    if pixels:      # the drawing kernel alone: craftax_observe launches just that kernel
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(5):
+            cx.craftax_observe(state, obs, n, stream)
+        e0.record(stream)
+        for _ in range(steps):
+            cx.craftax_observe(state, obs, n, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        draw_s = e0.elapsed_time(e1) * 1e-3 / steps
     # episodes finished so far -> mean episode length (drives the amortised reset bytes)
     episodes = 0
     chunk = 512 if variant == "craftax" else 8192
@@ -116,7 +127,8 @@ def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, varian
     mean_len = (n * total_steps) / max(episodes, 1)
     sim.close()
     med = int(np.argsort(wall)[len(wall) // 2])
-    return {"wall_s": wall[med], "event_s": evt[med], "all_wall_s": wall, "episodes": episodes, "mean_episode_len": mean_len}
+    return {"wall_s": wall[med], "event_s": evt[med], "all_wall_s": wall, "episodes": episodes, "mean_episode_len": mean_len,
+            "draw_s": draw_s}
 
 
 def cpu_baseline(n_sample: int, steps: int, kind: str, variant: str = "classic"):
@@ -145,7 +157,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="classic", choices=["classic", "craftax"])
+    ap.add_argument("--workload", default="classic", choices=["classic", "craftax", "craftax_pixels"])
     ap.add_argument("--envs", type=int, default=None, help="default 65536 (classic) or 4096 (craftax)")
     ap.add_argument("--kind", default=None, choices=["uniform", "skewed"], help="default skewed (classic) or uniform (craftax)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -172,6 +184,9 @@ def main():
 
     if args.workload == "craftax":
         print(json.dumps(craftax_line(args)))
+        return
+    if args.workload == "craftax_pixels":
+        print(json.dumps(craftax_pixels_line(args)))
         return
     args.envs = 65536 if args.envs is None else args.envs
     args.kind = "skewed" if args.kind is None else args.kind
@@ -226,6 +241,36 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(8192, min(K, 1000), args.kind)
     print(json.dumps(out))
+
+
+PIXEL_BYTES_PER_ENV = 130 * 110 * 3 * 4 + 1024 + 2 * 99      # the picture + the record and mob table + the 99 view cells of two maps
+
+
+def craftax_pixels_line(args) -> dict:
+    """Full Craftax with the 110 x 130 x 3 pixel observation: step kernel + drawing kernel."""
+    n = 4096 if args.envs is None else args.envs
+    kind = "uniform" if args.kind is None else args.kind
+    K, W = args.steps, args.warmup
+    run = gpu_run(n, K, W, kind, variant="craftax", pixels=True)
+    achieved = PIXEL_BYTES_PER_ENV * n / run["draw_s"] / 1e9
+    return {
+        "metric": "env steps/sec at 1 GPU (pixel obs) + % HBM roofline",
+        "value": n * K / run["wall_s"], "unit": "env_steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": run["wall_s"] / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {
+            "workload": f"full Craftax step with pixel observation, {n} envs, 43 actions {kind}, obs fp32[130][110][3] "
+                        f"from a seeded 127-tile atlas",
+            "envs": n, "obs_mode": "PIXELS_F32", "actions": kind, "mean_episode_len": round(run["mean_episode_len"], 1),
+        },
+        "roofline": {
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": read_profile_traffic("craftax_full_pixels_4096env.txt"),
+            "kernel": "kf_pixels: one block per environment, launched after the step kernel",
+            "alg_bytes_per_env_step": PIXEL_BYTES_PER_ENV, "alg_bytes_per_launch": PIXEL_BYTES_PER_ENV * n,
+            "avg_launch_us": run["draw_s"] * 1e6,
+        },
+    }
 
 
 def craftax_line(args, with_cpu: bool = True) -> dict:

@@ -7,11 +7,12 @@
 //               multiplied once by light level / 20.  Cells beyond the map edge show block 1 at
 //               full light.
 //   slot j    : icon tile j times min(scalar j of the symbolic observation, 1), j = 0..43.
-// One block per environment.  Thread t < 220 owns pixel column t % 110 of the two image rows an
-// iteration covers, so one iteration writes 2640 contiguous bytes and everything that depends on
-// the column (tile column, offset inside the tile) is computed once.  The work per pixel is one
-// 12-byte atlas read (cache resident: the atlas is 152 KB), three multiplies and one 12-byte
-// store; the kernel is bound by its 171,600 bytes of output per environment.
+// One block per environment.  The picture is walked in linear pixel order, 1024 pixels (whole
+// cache lines) per block iteration, 256 per wave: every lane fetches the three texels of four
+// pixels (the atlas is 152 KB and stays in cache), scales them and parks them in a wave-private
+// LDS strip, from which every lane writes three aligned 16-byte pieces -- 12-byte stores at a
+// 12-byte lane stride reach only half the write bandwidth.  The kernel is bound by its 171,600
+// bytes of output per environment.
 #pragma once
 
 #include "full_render.hpp"
@@ -22,6 +23,9 @@ constexpr int PIX_ROWS = 130, PIX_COLS = 110, TILE_PX = 10, TILE_FLOATS = TILE_P
 constexpr int TILE_ROWS = 13, STRIP_SLOTS = 44;
 constexpr int STRIDE_PIXELS = 171648;                         // 171,600 bytes of pixels + padding to whole cache lines
 constexpr int NO_TILE = 0xFF;
+constexpr int PIX_UNROLL = 4, WAVE_PIXELS = 64 * PIX_UNROLL, GROUP_PIXELS = WAVE_PIXELS * (BLOCK / 64), WAVE_FLOATS = WAVE_PIXELS * 3;
+constexpr int FULL_GROUPS = STRIDE_PIXELS / 12 / GROUP_PIXELS;   // 13 whole groups of 1024 pixels, then a partial one
+static_assert((FULL_GROUPS + 1) * GROUP_PIXELS * 12 >= STRIDE_PIXELS && FULL_GROUPS * GROUP_PIXELS <= PIX_ROWS * PIX_COLS, "pixel groups");
 
 __global__ __launch_bounds__(BLOCK) void kf_pixels(const uint32_t* __restrict__ envs, const uint8_t* __restrict__ maps,
                                                    const Luts* __restrict__ luts, uint8_t* __restrict__ obs)
@@ -30,10 +34,13 @@ __global__ __launch_bounds__(BLOCK) void kf_pixels(const uint32_t* __restrict__ 
     __shared__ uint32_t s_cre[NCELL];
     __shared__ uint32_t s_tile[TILE_ROWS * VCOLS];            // base tile | item tile << 8 | creature tile << 16 | player << 24
     __shared__ float s_scale[TILE_ROWS * VCOLS];
+    __shared__ __attribute__((aligned(4))) uint16_t s_mask[46 * TILE_PX];
+    __shared__ __attribute__((aligned(16))) float s_strip[(BLOCK / 64) * WAVE_FLOATS];
     const int env = blockIdx.x, tid = threadIdx.x;
     const uint32_t* genv = envs + (size_t)env * ENV_DWORDS;
     if (tid < REC_DWORDS) s_rec[tid] = genv[tid];
-    else if (tid - REC_DWORDS < NCELL) s_cre[tid - REC_DWORDS] = 0xFFFFFFFFu;
+    if (tid < 46 * TILE_PX / 2) reinterpret_cast<uint32_t*>(s_mask)[tid] = reinterpret_cast<const uint32_t*>(&luts->mask[0][0])[tid];
+    if (tid < NCELL) s_cre[tid] = 0xFFFFFFFFu;
     __syncthreads();
     const uint32_t pos = s_rec[R_POS];
     const int px = pos & 0xFF, py = (pos >> 8) & 0xFF, f = (pos >> 24) & 0xF;
@@ -72,38 +79,81 @@ __global__ __launch_bounds__(BLOCK) void kf_pixels(const uint32_t* __restrict__ 
         s_scale[tid] = scale;
     }
     __syncthreads();
-    float* out = reinterpret_cast<float*>(obs + (size_t)env * STRIDE_PIXELS);
-    if (tid >= 2 * PIX_COLS) {      // the stride's padding
-        if (tid - 2 * PIX_COLS < (STRIDE_PIXELS - PIX_ROWS * PIX_COLS * 12) / 4) out[PIX_ROWS * PIX_COLS * 3 + tid - 2 * PIX_COLS] = 0.0f;
-        return;
-    }
-    const int half = tid >= PIX_COLS ? 1 : 0, x = tid - half * PIX_COLS;
-    const int tc = x / TILE_PX, xi = x - tc * TILE_PX;
+    float4* out = reinterpret_cast<float4*>(obs + (size_t)env * STRIDE_PIXELS);
+    const int w = tid >> 6, l = tid & 63;
     const float* atlas = luts->atlas;
-#pragma unroll 1
-    for (int tr = 0; tr < TILE_ROWS; ++tr) {
-        const uint32_t info = s_tile[tr * VCOLS + tc];
-        const float scale = s_scale[tr * VCOLS + tc];
-        const int base = info & 0xFF;
-        const bool plain = (info >> 8) == 0xFFFFu;            // no item, no creature, not the player's cell
+    float* strip = s_strip + w * WAVE_FLOATS;
+    auto covered = [&](int overlay, int yi, int xi) { return (s_mask[overlay * TILE_PX + yi] >> xi) & 1u; };
+    float v[PIX_UNROLL][3], scale[PIX_UNROLL];
+    // Group g of the picture is 1024 consecutive pixels, 256 per wave, 4 per lane (64 apart).
+    // fetch: the texels of this lane's four pixels of group g.
+    auto fetch = [&](int g) {
+        const int p0 = g * GROUP_PIXELS + w * WAVE_PIXELS + l;
+        int y = p0 / PIX_COLS, x = p0 - y * PIX_COLS;
 #pragma unroll
-        for (int k = 0; k < TILE_PX / 2; ++k) {
-            const int yi = 2 * k + half;
-            int tile = base;
-            if (!plain) {
+        for (int u = 0; u < PIX_UNROLL; ++u) {
+            // pixels beyond the picture (the stride's padding) read texel 0 at scale 0
+            const bool valid = y < PIX_ROWS;
+            const int yy = valid ? y : 0;
+            const int tr = yy / TILE_PX, yi = yy - tr * TILE_PX, tc = x / TILE_PX, xi = x - tc * TILE_PX;
+            const uint32_t info = s_tile[tr * VCOLS + tc];
+            scale[u] = valid ? s_scale[tr * VCOLS + tc] : 0.0f;
+            int tile = info & 0xFF;
+            if ((info >> 8) != 0xFFFFu) {                     // an item, a creature or the player on this cell
                 const int item = (info >> 8) & 0xFF, cre = (info >> 16) & 0xFF;
-                if (item != NO_TILE && ((luts->mask[item - AT_ITEM][yi] >> xi) & 1u)) tile = item;
-                if (cre != NO_TILE && ((luts->mask[MASK_CRE + cre - AT_CRE][yi] >> xi) & 1u)) tile = cre;
-                if ((info >> 24) && ((luts->mask[MASK_PLAYER][yi] >> xi) & 1u)) tile = AT_PLAYER;
+                if (item != NO_TILE && covered(item - AT_ITEM, yi, xi)) tile = item;
+                if (cre != NO_TILE && covered(MASK_CRE + cre - AT_CRE, yi, xi)) tile = cre;
+                if ((info >> 24) && covered(MASK_PLAYER, yi, xi)) tile = AT_PLAYER;
             }
-            const float* src = atlas + tile * TILE_FLOATS + yi * (TILE_PX * 3) + xi * 3;
-            float* dst = out + ((tr * TILE_PX + yi) * PIX_COLS + x) * 3;
-            const float r = src[0], g = src[1], b = src[2];
-            __builtin_nontemporal_store(r * scale, dst);
-            __builtin_nontemporal_store(g * scale, dst + 1);
-            __builtin_nontemporal_store(b * scale, dst + 2);
+            const float* src = atlas + (uint32_t)(tile * TILE_FLOATS + yi * (TILE_PX * 3) + xi * 3);
+            v[u][0] = src[0]; v[u][1] = src[1]; v[u][2] = src[2];
+            x += 64;
+            if (x >= PIX_COLS) { x -= PIX_COLS; ++y; }
         }
+    };
+    // turn: scales the fetched texels and regroups the wave's 768 floats through LDS so that
+    // lane l holds the 16-byte pieces l, l + 64 and l + 128 of the wave's part of the output
+    float4 piece[3];
+    auto turn = [&]() {
+#pragma unroll
+        for (int u = 0; u < PIX_UNROLL; ++u) {
+            strip[u * 192 + l * 3] = v[u][0] * scale[u];
+            strip[u * 192 + l * 3 + 1] = v[u][1] * scale[u];
+            strip[u * 192 + l * 3 + 2] = v[u][2] * scale[u];
+        }
+        wave_sync();
+#pragma unroll
+        for (int k = 0; k < 3; ++k) piece[k] = *reinterpret_cast<const float4*>(strip + (k * 64 + l) * 4);
+        wave_sync();
+    };
+    auto store = [&](int g, bool guarded) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            const int q = (g * GROUP_PIXELS + w * WAVE_PIXELS) * 3 / 4 + k * 64 + l;
+            if (!guarded || q < STRIDE_PIXELS / 16) {
+                __builtin_nontemporal_store(piece[k].x, &out[q].x);
+                __builtin_nontemporal_store(piece[k].y, &out[q].y);
+                __builtin_nontemporal_store(piece[k].z, &out[q].z);
+                __builtin_nontemporal_store(piece[k].w, &out[q].w);
+            }
+        }
+    };
+    // The fetches of the next group are issued before the stores of this one: the memory
+    // operations of a wave complete in order, so neither waits for the other's round trip.  The
+    // first group is peeled so that the loop is entered with the same operations in flight as
+    // its back edge has, and the last, partial group is stored under a bounds check.
+    fetch(0);
+    turn();
+    fetch(1);
+    store(0, false);
+#pragma unroll 1
+    for (int g = 1; g < FULL_GROUPS; ++g) {
+        turn();
+        fetch(g + 1);
+        store(g, false);
     }
+    turn();
+    store(FULL_GROUPS, true);
 }
 
 }  // namespace cf
