@@ -131,6 +131,24 @@ def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, varian
             "draw_s": draw_s}
 
 
+def copy_ceiling_gbs(mib: int = 1024, repeats: int = 10) -> float:
+    """Measured device-to-device copy rate (bytes read + bytes written per second), as context
+    for the nominal peak: a buffer larger than the last-level cache, copied `repeats` times."""
+    import torch
+
+    src = torch.empty(mib << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(repeats):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * (mib << 20) * repeats / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def cpu_baseline(n_sample: int, steps: int, kind: str, variant: str = "classic"):
     """The CPU oracle, as it stands, on the first n_sample environments of the same workload."""
     from oracle import pyoracle as po
@@ -229,6 +247,7 @@ def main():
             "alg_bytes_per_env_step": round(alg["total"], 1),
             "alg_bytes_per_launch": per_launch_bytes,
             "avg_launch_us": launch_s * 1e6,
+            "measured_copy_gbs": copy_ceiling_gbs(),
         },
     }
     if not args.no_small:
@@ -269,6 +288,7 @@ def craftax_pixels_line(args) -> dict:
             "kernel": "kf_pixels: one block per environment, launched after the step kernel",
             "alg_bytes_per_env_step": PIXEL_BYTES_PER_ENV, "alg_bytes_per_launch": PIXEL_BYTES_PER_ENV * n,
             "avg_launch_us": run["draw_s"] * 1e6,
+            "measured_copy_gbs": copy_ceiling_gbs(),
         },
     }
 

@@ -64,7 +64,7 @@ enum { DIR_NONE = 0, DIR_LEFT = 1, DIR_RIGHT = 2, DIR_UP = 3, DIR_DOWN = 4 };
 /* Philox counter layout (reading): key = 64-bit seed (low word, high word);
  * counter = (env, a, b, domain<<16 | block).  STEP: a = t, b = episode.
  * WORLDGEN: a = stream, b = episode.  ATLAS: a = stream, b = 0, env = 0. */
-enum { DOM_STEP = 0, DOM_WORLDGEN = 1, DOM_ACTIONS = 2, DOM_ATLAS = 3 };
+enum { DOM_STEP = 0, DOM_WORLDGEN = 1, DOM_ACTIONS = 2, DOM_ATLAS = 3, DOM_MUTATE = 4 };
 
 static uint32_t philox_word(uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t dom,
                             uint32_t block, uint32_t word)
@@ -762,4 +762,38 @@ void orc_step_batch(orc_env *envs, const orc_config *cfg, const int32_t *actions
         orc_step(&envs[i], cfg, actions[i], &reward[i], &done[i]);
         if (obs) orc_observe(&envs[i], cfg, mode, (uint8_t *)obs + stride * (size_t)i);
     }
+}
+
+/* ---- level mutations (section "Craftax-1B: UED") ------------------------------------------------
+ * "Swap" exchanges two tiles of different type, one of them inside the central 16x16 area of the
+ * map; "restricted swap" only exchanges tiles of one group: stone with the ores, grass with
+ * trees.  Reading (the paper gives no more than that): up to 32 tries; try k draws Philox block
+ * (env, round, 0, MUTATE | k) under the mutation seed: word 0 picks the central cell
+ * (choice of 256, row-major inside the area), word 1 the other cell (choice of all cells).  A try
+ * is refused if the two blocks are equal, if a cell holds the player or a live mob, if a block is
+ * a plant (plants are tracked in a table), or, restricted, if the blocks are not of one group.
+ * The first try that is not refused is carried out.  Returns that try's number + 1, or 0. */
+static int swap_group(uint8_t b)
+{
+    if (b == B_STONE || b == B_COAL || b == B_IRON || b == B_DIAMOND) return 1;
+    if (b == B_GRASS || b == B_TREE) return 2;
+    return 0;
+}
+int orc_mutate_swap(orc_env *e, uint64_t mutation_seed, uint32_t round, int restricted)
+{
+    const int c0 = (ORC_MAP - 16) / 2;
+    for (uint32_t k = 0; k < 32; k++) {
+        uint32_t a = choice(philox_word(mutation_seed, e->env, round, 0, DOM_MUTATE, k, 0), 256);
+        uint32_t b = choice(philox_word(mutation_seed, e->env, round, 0, DOM_MUTATE, k, 1), ORC_MAP * ORC_MAP);
+        int ax = c0 + (int)(a % 16), ay = c0 + (int)(a / 16), bx = (int)(b % ORC_MAP), by = (int)(b / ORC_MAP);
+        uint8_t ba = e->map[ay * ORC_MAP + ax], bb = e->map[by * ORC_MAP + bx];
+        if (ba == bb) continue;
+        if (occupied(e, ax, ay) || occupied(e, bx, by)) continue;
+        if (ba == B_PLANT || ba == B_RIPE || bb == B_PLANT || bb == B_RIPE) continue;
+        if (restricted && (swap_group(ba) == 0 || swap_group(ba) != swap_group(bb))) continue;
+        e->map[ay * ORC_MAP + ax] = bb;
+        e->map[by * ORC_MAP + bx] = ba;
+        return (int)k + 1;
+    }
+    return 0;
 }

@@ -116,7 +116,7 @@ enum { PP_ARROW = 0, PP_FIREBALL = 1, PP_ICEBALL = 2 };
 #define P_RANGED_SPAWN 0x0CCCCCCCu       /* 5 %  */
 #define P_MELEE_SPAWN 0x0CCCCCCCu        /* 5 % below the overworld */
 
-enum { DOM_STEP = 0, DOM_WORLDGEN = 1 };
+enum { DOM_STEP = 0, DOM_WORLDGEN = 1, DOM_MUTATE = 4 };
 
 static uint32_t philox_word(uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t dom, uint32_t block, uint32_t word)
 {
@@ -1032,4 +1032,37 @@ void cf_step_batch(cf_env *envs, const cf_config *cfg, const int32_t *actions, i
         cf_step(&envs[i], cfg, actions[i], &reward[i], &done[i]);
         if (obs) cf_observe(&envs[i], cfg, mode, (uint8_t *)obs + stride * (size_t)i);
     }
+}
+
+/* ---- level mutations (section "Craftax-1B: UED": applied to the overworld) ----------------------
+ * Same reading as for Classic, on floor 0: up to 32 tries, try k draws Philox block (env, round, 0,
+ * MUTATE | k) under the mutation seed, word 0 the cell inside the central 16x16 area, word 1 any
+ * cell; refused if the blocks are equal, a cell holds the player (when on floor 0), a live mob of
+ * floor 0 or an item (ladder, torch), a block is a plant, or, restricted, the blocks are not of
+ * one group (stone and the ores, gems included; grass and tree).  Returns the try + 1, or 0. */
+static int swap_group(uint8_t b)
+{
+    if (b == B_STONE || b == B_COAL || b == B_IRON || b == B_DIAMOND || b == B_SAPPHIRE || b == B_RUBY) return 1;
+    if (b == B_GRASS || b == B_TREE) return 2;
+    return 0;
+}
+int cf_mutate_swap(cf_env *e, uint64_t mutation_seed, uint32_t round, int restricted)
+{
+    const int c0 = (CF_W - 16) / 2;
+    for (uint32_t k = 0; k < 32; k++) {
+        uint32_t a = choice(philox_word(mutation_seed, e->env, round, 0, DOM_MUTATE, k, 0), 256);
+        uint32_t b = choice(philox_word(mutation_seed, e->env, round, 0, DOM_MUTATE, k, 1), CF_CELLS);
+        int ax = c0 + (int)(a % 16), ay = c0 + (int)(a / 16), bx = (int)(b % CF_W), by = (int)(b / CF_W);
+        uint8_t ba = e->block[0][cell(ax, ay)], bb = e->block[0][cell(bx, by)];
+        if (ba == bb) continue;
+        if (e->floor == 0 && ((e->px == ax && e->py == ay) || (e->px == bx && e->py == by))) continue;
+        if (mob_at_floor(e, 0, ax, ay) >= 0 || mob_at_floor(e, 0, bx, by) >= 0) continue;
+        if (e->item[0][cell(ax, ay)] != IT_NONE || e->item[0][cell(bx, by)] != IT_NONE) continue;
+        if (ba == B_PLANT || ba == B_RIPE || bb == B_PLANT || bb == B_RIPE) continue;
+        if (restricted && (swap_group(ba) == 0 || swap_group(ba) != swap_group(bb))) continue;
+        e->block[0][cell(ax, ay)] = bb;
+        e->block[0][cell(bx, by)] = ba;
+        return (int)k + 1;
+    }
+    return 0;
 }

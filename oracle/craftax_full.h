@@ -102,6 +102,8 @@ void cf_step_batch(cf_env *envs, const cf_config *cfg, const int32_t *actions, i
                    float *reward, uint8_t *done, int n);
 void cf_observe_batch(const cf_env *envs, const cf_config *cfg, int mode, void *obs, int n);
 uint32_t cf_step_draw(const cf_env *e, uint32_t block, uint32_t word);
+/* UED level mutation of the overworld (section "Craftax-1B: UED"), see orc_mutate_swap. */
+int cf_mutate_swap(cf_env *e, uint64_t mutation_seed, uint32_t round, int restricted);
 /* creature table accessors for tests: field 0 health, 1..3 damage phys/fire/ice, 4..6 defence %, 7 collision */
 int cf_creature(int index, int field);
 

@@ -104,6 +104,10 @@ void orc_step_batch(orc_env *envs, const orc_config *cfg, const int32_t *actions
                     void *obs, float *reward, uint8_t *done, int n);
 void orc_observe_batch(const orc_env *envs, const orc_config *cfg, int obs_mode, void *obs, int n);
 
+/* UED level mutation (section "Craftax-1B: UED"): swaps two tiles of different type, one inside
+ * the central 16x16 area; restricted != 0 keeps to stone <-> ores and grass <-> tree. */
+int orc_mutate_swap(orc_env *e, uint64_t mutation_seed, uint32_t round, int restricted);
+
 /* Small accessors for tests. */
 float orc_daylight(const orc_config *cfg, uint32_t t);
 uint32_t orc_zombie_spawn_threshold(const orc_config *cfg, uint32_t t);

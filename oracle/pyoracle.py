@@ -193,6 +193,14 @@ class Oracle:
         ptr = ctypes.c_void_p(self.envs.ctypes.data + i * ENV_DTYPE.itemsize)
         return int(lib().orc_step_draw(ptr, ctypes.c_uint32(block), ctypes.c_uint32(word)))
 
+    def mutate_swap(self, mutation_seed: int, round_: int, restricted: bool) -> np.ndarray:
+        """Swap mutation on every environment; returns the accepted try + 1 (0: no swap) per env."""
+        out = np.zeros(self.n, np.int32)
+        for i in range(self.n):
+            ptr = ctypes.c_void_p(self.envs.ctypes.data + i * ENV_DTYPE.itemsize)
+            out[i] = lib().orc_mutate_swap(ptr, ctypes.c_uint64(mutation_seed), ctypes.c_uint32(round_), int(restricted))
+        return out
+
 
 def full_default_config(**overrides) -> FullConfig:
     cfg = FullConfig()
@@ -250,3 +258,10 @@ class FullOracle:
 
     def draw(self, i: int, block: int, word: int) -> int:
         return int(lib().cf_step_draw(self._ptr(i), ctypes.c_uint32(block), ctypes.c_uint32(word)))
+
+    def mutate_swap(self, mutation_seed: int, round_: int, restricted: bool) -> np.ndarray:
+        """Swap mutation of the overworld of every environment; returns the accepted try + 1 per env."""
+        out = np.zeros(self.n, np.int32)
+        for i in range(self.n):
+            out[i] = lib().cf_mutate_swap(self._ptr(i), ctypes.c_uint64(mutation_seed), ctypes.c_uint32(round_), int(restricted))
+        return out

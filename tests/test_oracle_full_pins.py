@@ -837,3 +837,43 @@ def test_pixel_inventory_strip_follows_the_symbolic_scalars():
     o.cfg.atlas_seed = seed + 1
     assert not np.array_equal(full_pixels(o), after)
     assert np.array_equal(split_f32(o.observe_one(0, po.FULL_OBS_F32))[1], vec)
+
+
+# ---- level mutations (section "Craftax-1B: UED") ---------------------------------------------------
+@pytest.mark.parametrize("restricted", [False, True])
+def test_swap_mutation_of_the_overworld(restricted):
+    n = 48
+    o = fresh(n, seed=31)
+    for s in range(20):
+        o.step(synth.actions(np.arange(n), s, "skewed", 0, 43))
+    before = o.envs.copy()
+    tries = o.mutate_swap(77, 3, restricted)
+    assert (tries > 0).sum() > n * 0.8 and tries.max() <= 32
+    ores = {B[k] for k in ("STONE", "COAL", "IRON", "DIAMOND", "SAPPHIRE", "RUBY")}
+    green = {B["GRASS"], B["TREE"]}
+    for i in range(n):
+        a, b = before[i]["block"][0], o.envs[i]["block"][0]
+        ys, xs = np.nonzero(a != b)
+        assert len(ys) == (2 if tries[i] else 0)
+        assert np.array_equal(before[i]["block"][1:], o.envs[i]["block"][1:])      # only the overworld
+        for name in po.FULL_ENV_DTYPE.names:
+            if name != "block":
+                assert np.array_equal(before[i][name], o.envs[i][name])
+        if not tries[i]:
+            continue
+        (y0, y1), (x0, x1) = ys, xs
+        assert a[y0, x0] == b[y1, x1] and a[y1, x1] == b[y0, x0] and a[y0, x0] != a[y1, x1]
+        assert any(16 <= x < 32 and 16 <= y < 32 for x, y in ((x0, y0), (x1, y1)))
+        e = before[i]
+        taken = {(int(m["x"]), int(m["y"])) for m in e["mob"][0] if m["alive"]}
+        if e["floor"] == 0:
+            taken.add((int(e["px"]), int(e["py"])))
+        assert not taken & {(int(x0), int(y0)), (int(x1), int(y1))}
+        assert e["item"][0][y0, x0] == 0 and e["item"][0][y1, x1] == 0            # ladders and torches stay put
+        pair = {int(a[y0, x0]), int(a[y1, x1])}
+        assert not pair & {B["PLANT"], B["RIPE"]}
+        if restricted:
+            assert pair <= ores or pair <= green
+    again = po.FullOracle(n, po.full_default_config())
+    again.envs[:] = before
+    assert np.array_equal(again.mutate_swap(77, 3, restricted), tries) and again.envs.tobytes() == o.envs.tobytes()

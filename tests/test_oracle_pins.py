@@ -893,3 +893,68 @@ def test_envs_are_independent_of_batch_position():
         full.step(acts[s])
         solo.step(acts[s, 5:6])
     assert full.envs[5].tobytes() == solo.envs[0].tobytes()
+
+
+# --------------------------------------------------- level mutations (section "Craftax-1B: UED") ----
+GROUP = {STONE: 1, COAL: 1, IRON: 1, DIAMOND: 1, GRASS: 2, TREE: 2}
+
+
+@pytest.mark.parametrize("restricted", [False, True])
+def test_swap_mutation_exchanges_two_different_tiles_one_near_the_start(restricted):
+    n = 96
+    o = po.Oracle(n, po.default_config())
+    o.reset(synth.seeds_for(n, 21))
+    for s in range(30):                                        # some mobs and plants on the maps
+        o.step(synth.actions(np.arange(n), s, "skewed"))
+    before = o.envs.copy()
+    tries = o.mutate_swap(1234, 0, restricted)
+    assert (tries > 0).sum() > n * 0.8 and tries.max() <= 32
+    for i in range(n):
+        a, b = before[i]["map"].reshape(64, 64), o.envs[i]["map"].reshape(64, 64)
+        ys, xs = np.nonzero(a != b)
+        if tries[i] == 0:
+            assert len(ys) == 0
+            continue
+        assert len(ys) == 2                                     # exactly two cells change ...
+        (y0, y1), (x0, x1) = ys, xs
+        assert a[y0, x0] == b[y1, x1] and a[y1, x1] == b[y0, x0] and a[y0, x0] != a[y1, x1]   # ... and trade places
+        assert any(24 <= x < 40 and 24 <= y < 40 for x, y in ((x0, y0), (x1, y1)))             # the central 16x16 area
+        e = before[i]
+        taken = {(int(e["px"]), int(e["py"]))} | {(int(m["x"]), int(m["y"])) for m in e["mob"] if m["alive"]}
+        assert not taken & {(int(x0), int(y0)), (int(x1), int(y1))}
+        assert not {int(a[y0, x0]), int(a[y1, x1])} & {PLANT, RIPE}
+        if restricted:
+            assert GROUP.get(int(a[y0, x0]), 0) == GROUP.get(int(a[y1, x1]), -1)
+        # nothing but the map changes
+        for name in po.ENV_DTYPE.names:
+            if name != "map":
+                assert np.array_equal(before[i][name], o.envs[i][name])
+    # same seed and round: same mutation; another round: another one
+    again = po.Oracle(n, po.default_config())
+    again.envs[:] = before
+    assert np.array_equal(again.mutate_swap(1234, 0, restricted), tries) and again.envs.tobytes() == o.envs.tobytes()
+    again.envs[:] = before
+    again.mutate_swap(1234, 1, restricted)
+    assert again.envs.tobytes() != o.envs.tobytes()
+
+
+def test_swap_mutation_draws_follow_the_counter_layout():
+    """The first try: word 0 of Philox block (env, round, 0, MUTATE << 16 | 0) under the mutation
+    seed picks the central cell, word 1 the other one."""
+    o = blank()
+    e = o.envs[0]
+    e["env"] = 5
+    m = e["map"].reshape(64, 64)
+    m[:, :] = np.arange(64 * 64).reshape(64, 64) % 2 * (SAND - GRASS) + GRASS        # a checkerboard of grass and sand
+    e["px"], e["py"] = 0, 0
+    seed, rnd = 0xDEADBEEF12345, 9
+    for k in range(32):
+        w = po.philox([5, rnd, 0, (4 << 16) | k], [seed & 0xFFFFFFFF, seed >> 32])
+        a, b = (w[0] * 256) >> 32, (w[1] * 4096) >> 32
+        ax, ay, bx, by = 24 + a % 16, 24 + a // 16, b % 64, b // 64
+        if m[ay, ax] != m[by, bx] and (bx, by) != (0, 0):
+            break
+    want = m.copy()
+    want[ay, ax], want[by, bx] = m[by, bx], m[ay, ax]
+    assert o.mutate_swap(seed, rnd, False)[0] == k + 1
+    assert np.array_equal(e["map"].reshape(64, 64), want)
