@@ -207,6 +207,21 @@ int craftax_observe(void *state, void *obs, int n, void *stream);
 int craftax_export_envs(const void *state, int first, int count, void *dumps, void *stream);
 int craftax_import_envs(void *state, int first, int count, const void *dumps, void *stream);
 
+/* Level mutation for unsupervised environment design (section "Craftax-1B: UED", the "swap" and
+ * "restricted swap" operators): in each environment of [first, first+count) two tiles of
+ * different type trade places on the current map (variant CRAFTAX: on the overworld, floor 0), one
+ * of them inside the central 16x16 area; restricted != 0 only lets stone trade with ores (coal,
+ * iron, diamond; sapphire and ruby too in CRAFTAX) and grass with trees.  The paper says no more;
+ * this library's reading: up to 32 tries per call, try k drawing Philox block (env, round, 0,
+ * MUTATE << 16 | k) keyed by mutation_seed, word 0 -> the central cell ((u * 256) >> 32, row-major
+ * in the area), word 1 -> any cell ((u * cells) >> 32, row-major); a try is refused if the two
+ * blocks are equal, if a cell holds the player, a live mob, a plant or (CRAFTAX) an item, or,
+ * restricted, if the blocks are not of one group; the first try not refused is carried out.
+ * tries: DEVICE int32[count] or NULL; receives that try's number + 1, or 0 if all were refused.
+ * Nothing but the map changes.  Errors: CRAFTAX_E_COUNT for a range outside the state. */
+int craftax_mutate_swap(void *state, int first, int count, uint64_t mutation_seed, uint32_t round,
+                        int restricted, int32_t *tries, void *stream);
+
 /* Fills actions (DEVICE int32[steps][n]) with the synthetic action stream used by the
  * benchmark: kind 0 = uniform over 17 actions, kind 1 = half of the draws restricted to
  * ids 1..5, kinds 2 and 3 = the same two over the 43 actions of full Craftax.  Input generation

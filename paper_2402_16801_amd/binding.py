@@ -21,7 +21,7 @@ EXPORTS = [
     "craftax_default_config", "craftax_default_config_for", "craftax_state_bytes", "craftax_obs_bytes",
     "craftax_env_dump_bytes", "craftax_env_dump_bytes_for",
     "craftax_state_init", "craftax_state_release", "craftax_reset", "craftax_step", "craftax_observe",
-    "craftax_export_envs", "craftax_import_envs", "craftax_synth_actions", "craftax_last_error",
+    "craftax_export_envs", "craftax_import_envs", "craftax_mutate_swap", "craftax_synth_actions", "craftax_last_error",
 ]
 
 
@@ -94,6 +94,7 @@ def load() -> ctypes.CDLL:
     L.craftax_observe.argtypes = [vp, vp, i32, vp]
     L.craftax_export_envs.argtypes = [vp, i32, i32, vp, vp]
     L.craftax_import_envs.argtypes = [vp, i32, i32, vp, vp]
+    L.craftax_mutate_swap.argtypes = [vp, i32, i32, u64, ctypes.c_uint32, i32, vp, vp]
     L.craftax_synth_actions.argtypes = [vp, i32, i32, i32, u64, i32, vp]
     L.craftax_last_error.argtypes = []
     L.craftax_last_error.restype = ctypes.c_char_p
@@ -165,6 +166,11 @@ def craftax_import_envs(state, first: int, count: int, dumps, stream=None):
            "craftax_import_envs")
 
 
+def craftax_mutate_swap(state, first: int, count: int, mutation_seed: int, round_: int, restricted: bool, tries=None, stream=None):
+    _check(load().craftax_mutate_swap(state.data_ptr(), first, count, mutation_seed, round_, int(bool(restricted)),
+                                      None if tries is None else tries.data_ptr(), _stream_ptr(stream)), "craftax_mutate_swap")
+
+
 def craftax_synth_actions(actions, n: int, step0: int, steps: int, action_seed: int, kind: int, stream=None):
     _check(load().craftax_synth_actions(actions.data_ptr(), n, step0, steps, action_seed, kind, _stream_ptr(stream)),
            "craftax_synth_actions")
@@ -234,3 +240,10 @@ class Craftax:
         buf = torch.as_tensor(raw, device=self.device)
         craftax_import_envs(self.state, first, raw.shape[0], buf, self.stream)
         self.torch.cuda.synchronize(self.device)
+
+    def mutate_swap(self, mutation_seed: int, round_: int, restricted: bool, first: int = 0, count: int | None = None) -> np.ndarray:
+        """Swap mutation of the current maps; returns the accepted try + 1 (0: none) per environment."""
+        count = self.n - first if count is None else count
+        tries = self.torch.zeros(count, dtype=self.torch.int32, device=self.device)
+        craftax_mutate_swap(self.state, first, count, mutation_seed, round_, restricted, tries, self.stream)
+        return tries.cpu().numpy()

@@ -50,7 +50,8 @@ constexpr int VEC_OFFSET = 1328;
 constexpr int MAX_DAY = 1024;
 
 // Philox domains: counter = (env, a, b, domain<<16 | block), key = the env's 64-bit seed.
-enum Domain : uint32_t { DOM_STEP = 0, DOM_WORLDGEN = 1, DOM_ACTIONS = 2, DOM_ATLAS = 3 };
+enum Domain : uint32_t { DOM_STEP = 0, DOM_WORLDGEN = 1, DOM_ACTIONS = 2, DOM_ATLAS = 3, DOM_MUTATE = 4 };
+constexpr int MUTATE_TRIES = 32, MUTATE_AREA = 16;   // swap mutation: tries per call, side of the central area
 
 // ---- Philox4x32-10 (Salmon et al., SC'11) -------------------------------------------------
 struct U4 { uint32_t w[4]; };

@@ -403,6 +403,52 @@ __global__ __launch_bounds__(BLOCK) void kf_import(uint32_t* __restrict__ envs, 
     if (tid < SPARE_LADDER) r[tid] = s[tid];   // the spare world's description is written by kf_import_spare
 }
 
+// Level mutation of the overworld (section "Craftax-1B: UED"), as for Classic: up to 32 tries, try
+// k drawing Philox block (env, round, 0, MUTATE | k) under the mutation seed; refused if the blocks
+// are equal, a cell holds the player (when on floor 0), a live mob of floor 0 or an item, a block
+// is a plant, or, restricted, the blocks are not of one group (stone and ores, gems included;
+// grass and tree).  One thread per environment.
+__device__ inline int swap_group(int b)
+{
+    if (b == B_STONE || b == B_COAL || b == B_IRON || b == B_DIAMOND || b == B_SAPPHIRE || b == B_RUBY) return 1;
+    if (b == B_GRASS || b == B_TREE) return 2;
+    return 0;
+}
+__global__ void kf_mutate_swap(const uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, int first, int count, uint32_t k0,
+                               uint32_t k1, uint32_t round, int restricted, int32_t* __restrict__ tries)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    const uint32_t env = (uint32_t)(first + i);
+    const uint32_t* genv = envs + (size_t)env * ENV_DWORDS;
+    uint8_t* m = maps + map_offset(env, genv[R_EPISODE]);
+    const uint32_t pos = genv[R_POS];
+    const int px = pos & 0xFF, py = (pos >> 8) & 0xFF, floor = (pos >> 24) & 0xF;
+    auto taken = [&](int x, int y) {
+        bool t = floor == 0 && x == px && y == py;
+        for (int k = 0; k < NSLOT; ++k) {
+            const Mob u = unpack_mob(genv[REC_DWORDS + k]);
+            t |= u.alive && (int)u.x == x && (int)u.y == y;
+        }
+        return t || (m[il_off(0, x, y)] & 7) != IT_NONE;
+    };
+    int done = 0;
+    for (int k = 0; k < cx::MUTATE_TRIES && !done; ++k) {
+        const cx::U4 d = cx::philox4x32_10(env, round, 0u, (cx::DOM_MUTATE << 16) | (uint32_t)k, k0, k1);
+        const int a = (int)cx::choice(d.w[0], cx::MUTATE_AREA * cx::MUTATE_AREA), b = (int)cx::choice(d.w[1], CELLS);
+        const int c0 = (W - cx::MUTATE_AREA) / 2;
+        const int ax = c0 + a % cx::MUTATE_AREA, ay = c0 + a / cx::MUTATE_AREA, bx = b % W, by = b / W;
+        const int ba = m[block_off(0, ax, ay)], bb = m[block_off(0, bx, by)];
+        if (ba == bb || taken(ax, ay) || taken(bx, by)) continue;
+        if (ba == B_PLANT || ba == B_RIPE || bb == B_PLANT || bb == B_RIPE) continue;
+        if (restricted && (swap_group(ba) == 0 || swap_group(ba) != swap_group(bb))) continue;
+        m[block_off(0, ax, ay)] = (uint8_t)bb;
+        m[block_off(0, bx, by)] = (uint8_t)ba;
+        done = k + 1;
+    }
+    if (tries != nullptr) tries[i] = done;
+}
+
 // ---------------------------------------------------------------------------------------------
 namespace host {
 
@@ -589,6 +635,15 @@ int import_envs(void* state, const craftax_config* cfg, int n, int first, int co
                        static_cast<const craftax_full_env_dump*>(dumps), first, make_params(cfg, n));
     hipLaunchKernelGGL(kf_import_spare, dim3((unsigned)count * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, q.ls, first);
     return check_launch("craftax_import_envs", err);
+}
+
+int mutate_swap(void* state, const craftax_config* cfg, int n, int first, int count, uint64_t mutation_seed, uint32_t round,
+                int restricted, int32_t* tries, void* stream, std::string* err)
+{
+    const Ptrs q = pointers(state, make_header(cfg, n));
+    hipLaunchKernelGGL(kf_mutate_swap, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, (hipStream_t)stream, q.envs, q.maps, first,
+                       count, (uint32_t)mutation_seed, (uint32_t)(mutation_seed >> 32), round, restricted != 0 ? 1 : 0, tries);
+    return check_launch("craftax_mutate_swap", err);
 }
 
 }  // namespace host

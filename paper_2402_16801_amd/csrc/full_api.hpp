@@ -22,6 +22,8 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
 int observe(void* state, const craftax_config* cfg, int n, void* obs, void* stream, std::string* err);
 int export_envs(const void* state, const craftax_config* cfg, int n, int first, int count, void* dumps, void* stream, std::string* err);
 int import_envs(void* state, const craftax_config* cfg, int n, int first, int count, const void* dumps, void* stream, std::string* err);
+int mutate_swap(void* state, const craftax_config* cfg, int n, int first, int count, uint64_t mutation_seed, uint32_t round,
+                int restricted, int32_t* tries, void* stream, std::string* err);
 
 }  // namespace host
 }  // namespace cf

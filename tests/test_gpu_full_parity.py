@@ -375,3 +375,34 @@ def test_full_config4_4096_envs_5000_steps(cx):
     sample = np.arange(0, 4096, 32)
     finished, _, _ = run_full(cx, 4096, 5000, kind="uniform", sample=sample, device_actions=True, obs_every=10, progress=1000)
     assert finished > 128 * 10
+
+
+@pytest.mark.parametrize("restricted", [False, True])
+def test_full_swap_mutation_matches_the_oracle(cx, restricted):
+    """UED swap / restricted swap of the overworld, with some players below ground."""
+    import torch
+    n = 120
+    gcfg, ocfg = _cfgs(cx, 1)
+    sim = cx.Craftax(n, gcfg)
+    orc = po.FullOracle(n, ocfg)
+    seeds = synth.seeds_for(n, 41)
+    sim.reset(seeds)
+    orc.reset(seeds)
+    rich_scene(orc.envs)
+    sim.import_envs(orc.envs)
+    for s in range(25):
+        a = synth.actions(np.arange(n), s, "skewed", 0, 43)
+        sim.step(torch.as_tensor(a, device=sim.device))
+        orc.step(a)
+    for rnd in (0, 1):
+        got = sim.mutate_swap(99, rnd, restricted)
+        want = orc.mutate_swap(99, rnd, restricted)
+        assert np.array_equal(got, want) and (want > 0).sum() > n // 2
+        compare_state(sim, orc, np.arange(n), f"mutation round {rnd}")
+    for s in range(25, 40):
+        a = synth.actions(np.arange(n), s, "skewed", 0, 43)
+        obs, rew, done = sim.step(torch.as_tensor(a, device=sim.device))
+        oobs, orew, odone = orc.step(a)
+        assert np.array_equal(obs.cpu().numpy(), oobs) and np.array_equal(done.cpu().numpy(), odone)
+    compare_state(sim, orc, np.arange(n), "play after mutation")
+    sim.close()

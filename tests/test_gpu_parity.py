@@ -386,3 +386,41 @@ def test_error_codes(cx):
     sim.reset(synth.seeds_for(n))
     sim.step(act)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("restricted", [False, True])
+def test_swap_mutation_matches_the_oracle(cx, restricted):
+    """UED swap / restricted swap on maps with mobs and plants on them, two rounds, then the
+    mutated levels are played on: state and observations stay bit-exact."""
+    import torch
+    n = 300
+    gcfg, ocfg = cx.default_config(), po.default_config()
+    sim = cx.Craftax(n, gcfg)
+    orc = po.Oracle(n, ocfg, po.OBS_SYM_U8_F32)
+    seeds = synth.seeds_for(n, 77)
+    sim.reset(seeds)
+    orc.reset(seeds)
+    for s in range(40):
+        a = synth.actions(np.arange(n), s, "skewed")
+        sim.step(torch.as_tensor(a, device=sim.device))
+        orc.step(a)
+    for rnd in (0, 1):
+        got = sim.mutate_swap(0xABCDEF12345, rnd, restricted)
+        want = orc.mutate_swap(0xABCDEF12345, rnd, restricted)
+        assert np.array_equal(got, want) and (want > 0).sum() > n // 2
+        assert sim.export_envs().tobytes() == orc.envs.tobytes()
+    # a sub-range only touches its environments
+    got = sim.mutate_swap(5, 2, restricted, first=100, count=50)
+    before = orc.envs.copy()
+    want = orc.mutate_swap(5, 2, restricted)
+    orc.envs[:100], orc.envs[150:] = before[:100], before[150:]
+    assert np.array_equal(got, want[100:150]) and sim.export_envs().tobytes() == orc.envs.tobytes()
+    for s in range(40, 60):
+        a = synth.actions(np.arange(n), s, "skewed")
+        obs, rew, done = sim.step(torch.as_tensor(a, device=sim.device))
+        oobs, orew, odone = orc.step(a)
+        assert np.array_equal(obs.cpu().numpy(), oobs) and np.array_equal(done.cpu().numpy(), odone)
+    assert sim.export_envs().tobytes() == orc.envs.tobytes()
+    with pytest.raises(cx.CraftaxError):
+        cx.craftax_mutate_swap(sim.state, 290, 20, 1, 0, False, None, sim.stream)
+    sim.close()
