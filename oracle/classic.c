@@ -109,6 +109,8 @@ void orc_default_config(orc_config *cfg)
     cfg->cap_zombie = 3; cfg->cap_cow = 3; cfg->cap_skeleton = 3; cfg->cap_arrow = 3;
     cfg->cap_plant = 10;
     cfg->atlas_seed = 0;
+    cfg->worldgen = ORC_WORLDGEN_VALUE;
+    cfg->reserved = 0;
 }
 
 size_t orc_env_bytes(void) { return sizeof(orc_env); }
@@ -181,6 +183,56 @@ uint32_t orc_value_noise(const uint16_t *lattice, int width, int spacing, int x,
     return (top * (256u - wy) + bot * wy) >> 16;
 }
 
+/* Perlin gradient noise (appendix "World Generation": the paper generates worlds from Perlin
+ * noise after the perlin-numpy generator: unit gradients at random angles on a lattice, the four
+ * corner dot products blended with the fade curve 6t^5 - 15t^4 + 10t^3, the result times sqrt 2),
+ * here in integers so that the GPU can match it bit for bit:
+ *   angle index a = lattice u16 >> 6 (1024 directions), gradient (cos, sin)(2 pi a / 1024) in
+ *   Q14 (table from the C library, rounded to nearest);
+ *   offsets from the four corners in units of 1/S (S = lattice spacing), dot = gx dx + gy dy;
+ *   fade weight in Q16: (F 65536 + S^5 / 2) / S^5 with F = k^3 (6 k^2 - 15 k S + 10 S^2);
+ *   lerp(p, q, w) = p + floor((q - p) w / 65536), first along x, then along y;
+ *   the value n is then in units of 1 / (16384 S); it is returned on the 0..65535 scale of the
+ *   terrain thresholds as 32768 + floor(n GAIN / (1024 S)), clamped (reading: the gain makes its
+ *   spread about that of the value-noise fields, so that the same thresholds carve the terrain). */
+#define PERLIN_GAIN 3900
+static int16_t perlin_cos[1024], perlin_sin[1024];
+static int perlin_ready = 0;
+static void perlin_tables(void)
+{
+    if (perlin_ready) return;
+    for (int a = 0; a < 1024; a++) {
+        double th = 6.283185307179586476925286766559 * (double)a / 1024.0;
+        perlin_cos[a] = (int16_t)lround(cos(th) * 16384.0);
+        perlin_sin[a] = (int16_t)lround(sin(th) * 16384.0);
+    }
+    perlin_ready = 1;
+}
+static int64_t floor_div(int64_t v, int64_t d) { return v >= 0 ? v / d : -((-v + d - 1) / d); }
+static int64_t perlin_fade(int k, int spacing)
+{
+    int64_t S = spacing, S5 = S * S * S * S * S;
+    int64_t F = (int64_t)k * k * k * (6 * (int64_t)k * k - 15 * (int64_t)k * S + 10 * S * S);
+    return (F * 65536 + S5 / 2) / S5;
+}
+static int64_t perlin_lerp(int64_t p, int64_t q, int64_t w) { return p + floor_div((q - p) * w, 65536); }
+uint32_t orc_perlin_noise(const uint16_t *lattice, int width, int spacing, int x, int y)
+{
+    perlin_tables();
+    int ix = x / spacing, iy = y / spacing, kx = x % spacing, ky = y % spacing;
+    int64_t dot[2][2];
+    for (int cy = 0; cy < 2; cy++)
+        for (int cx = 0; cx < 2; cx++) {
+            int a = lattice[(iy + cy) * width + ix + cx] >> 6;
+            dot[cy][cx] = (int64_t)perlin_cos[a] * (kx - cx * spacing) + (int64_t)perlin_sin[a] * (ky - cy * spacing);
+        }
+    int64_t wx = perlin_fade(kx, spacing), wy = perlin_fade(ky, spacing);
+    int64_t top = perlin_lerp(dot[0][0], dot[0][1], wx), bot = perlin_lerp(dot[1][0], dot[1][1], wx);
+    int64_t n = perlin_lerp(top, bot, wy);
+    int64_t v = 32768 + floor_div(n * PERLIN_GAIN, 1024 * (int64_t)spacing);
+    return (uint32_t)(v < 0 ? 0 : (v > 65535 ? 65535 : v));
+}
+
 /* u16 number `idx` of a worldgen stream: numbers are packed two per Philox word, low half
  * first, four words per block. */
 static uint16_t worldgen_u16(uint64_t seed, uint32_t env, uint32_t episode, uint32_t stream, uint32_t idx)
@@ -218,6 +270,15 @@ static uint16_t worldgen_u16(uint64_t seed, uint32_t env, uint32_t episode, uint
 
 void orc_worldgen(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode)
 {
+    orc_worldgen_mode(map, seed, env, episode, ORC_WORLDGEN_VALUE);
+}
+
+/* mode ORC_WORLDGEN_VALUE: the fields are value noise; ORC_WORLDGEN_PERLIN: the same lattices read
+ * as gradient angles, the fields are Perlin noise.  Everything else (field mix, thresholds, start
+ * area) is shared. */
+void orc_worldgen_mode(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode, uint32_t mode)
+{
+    uint32_t (*noise)(const uint16_t *, int, int, int, int) = mode == ORC_WORLDGEN_PERLIN ? orc_perlin_noise : orc_value_noise;
     uint16_t lat[LAT_TOTAL];
     for (uint32_t i = 0; i < LAT_TOTAL; i++) lat[i] = worldgen_u16(seed, env, episode, 0, i);
     const uint16_t *w16 = lat, *m16 = lat + LAT16_N;
@@ -225,10 +286,10 @@ void orc_worldgen(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode)
 
     for (int y = 0; y < ORC_MAP; y++) {
         for (int x = 0; x < ORC_MAP; x++) {
-            int W = (int)((3u * orc_value_noise(w16, 5, 16, x, y) + orc_value_noise(w8, 9, 8, x, y)) >> 2);
-            int M = (int)((3u * orc_value_noise(m16, 5, 16, x, y) + orc_value_noise(m8, 9, 8, x, y)) >> 2);
-            int C = (int)orc_value_noise(c8, 9, 8, x, y);
-            int F = (int)orc_value_noise(f8, 9, 8, x, y);
+            int W = (int)((3u * noise(w16, 5, 16, x, y) + noise(w8, 9, 8, x, y)) >> 2);
+            int M = (int)((3u * noise(m16, 5, 16, x, y) + noise(m8, 9, 8, x, y)) >> 2);
+            int C = (int)noise(c8, 9, 8, x, y);
+            int F = (int)noise(f8, 9, 8, x, y);
             int u = worldgen_u16(seed, env, episode, 1, (uint32_t)(y * ORC_MAP + x));
             int d = imax(iabs(x - ORC_MAP / 2), iabs(y - ORC_MAP / 2));
             if (d < START_BIAS_R) {  /* keep the start in open country */
@@ -256,13 +317,13 @@ void orc_worldgen(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode)
     }
 }
 
-static void reset_episode(orc_env *e, uint32_t episode)
+static void reset_episode(orc_env *e, const orc_config *cfg, uint32_t episode)
 {
     uint64_t seed = e->seed;
     uint32_t env = e->env;
     memset(e, 0, sizeof(*e));
     e->seed = seed; e->env = env; e->episode = episode;
-    orc_worldgen(e->map, seed, env, episode);
+    orc_worldgen_mode(e->map, seed, env, episode, cfg->worldgen);
     e->px = ORC_MAP / 2; e->py = ORC_MAP / 2;
     e->dir = DIR_DOWN;
     e->vit[V_HEALTH] = e->vit[V_FOOD] = e->vit[V_DRINK] = e->vit[V_ENERGY] = MAX_COUNT;
@@ -270,10 +331,9 @@ static void reset_episode(orc_env *e, uint32_t episode)
 
 void orc_reset(orc_env *e, const orc_config *cfg, uint64_t seed, uint32_t env)
 {
-    (void)cfg;
     memset(e, 0, sizeof(*e));
     e->seed = seed; e->env = env;
-    reset_episode(e, 0);
+    reset_episode(e, cfg, 0);
 }
 
 /* ---- helpers over the mob table ------------------------------------------------------ */
@@ -638,7 +698,7 @@ void orc_step_rules(orc_env *e, const orc_config *cfg, int32_t action, float *re
 void orc_step(orc_env *e, const orc_config *cfg, int32_t action, float *reward, uint8_t *done)
 {
     orc_step_rules(e, cfg, action, reward, done);
-    if (*done) reset_episode(e, e->episode + 1);
+    if (*done) reset_episode(e, cfg, e->episode + 1);
 }
 
 /* ---- observations ------------------------------------------------------------------------- */

@@ -45,7 +45,10 @@ typedef struct {
     uint32_t cap_zombie, cap_cow, cap_skeleton, cap_arrow; /* each 0..3 */
     uint32_t cap_plant;      /* 0..10 */
     uint64_t atlas_seed;     /* pixel observations only */
+    uint32_t worldgen;       /* ORC_WORLDGEN_VALUE (benchmark configurations) or ORC_WORLDGEN_PERLIN (the paper's noise) */
+    uint32_t reserved;
 } orc_config;
+enum { ORC_WORLDGEN_VALUE = 0, ORC_WORLDGEN_PERLIN = 1 };
 
 typedef struct {
     uint8_t alive, x, y, dir;
@@ -90,6 +93,8 @@ void orc_philox_batch(const uint32_t *ctrs, const uint32_t *keys, uint32_t *out,
 
 void orc_default_config(orc_config *cfg);
 void orc_worldgen(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode);
+void orc_worldgen_mode(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode, uint32_t mode);
+uint32_t orc_perlin_noise(const uint16_t *lattice, int width, int spacing, int x, int y);
 void orc_reset(orc_env *e, const orc_config *cfg, uint64_t seed, uint32_t env);
 /* Rules only: no auto-reset.  Returns reward/done of the step just taken. */
 void orc_step_rules(orc_env *e, const orc_config *cfg, int32_t action, float *reward, uint8_t *done);

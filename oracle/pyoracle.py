@@ -79,7 +79,11 @@ class Config(ctypes.Structure):
     _fields_ = [("max_episode_steps", ctypes.c_uint32), ("day_length", ctypes.c_uint32),
                 ("cap_zombie", ctypes.c_uint32), ("cap_cow", ctypes.c_uint32),
                 ("cap_skeleton", ctypes.c_uint32), ("cap_arrow", ctypes.c_uint32),
-                ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64)]
+                ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64),
+                ("worldgen", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
+WORLDGEN_VALUE, WORLDGEN_PERLIN = 0, 1
 
 
 def build(force: bool = False) -> str:
@@ -109,6 +113,7 @@ def lib() -> ctypes.CDLL:
         L.orc_zombie_spawn_threshold.restype = ctypes.c_uint32
         L.orc_step_draw.restype = ctypes.c_uint32
         L.orc_value_noise.restype = ctypes.c_uint32
+        L.orc_perlin_noise.restype = ctypes.c_uint32
         assert L.orc_env_bytes() == ENV_DTYPE.itemsize
         L.cf_env_bytes.restype = ctypes.c_size_t
         L.cf_obs_bytes.restype = ctypes.c_size_t
@@ -138,10 +143,16 @@ def philox(ctr, key):
     return [int(x) for x in o]
 
 
-def worldgen(seed: int, env: int, episode: int = 0) -> np.ndarray:
+def worldgen(seed: int, env: int, episode: int = 0, mode: int = WORLDGEN_VALUE) -> np.ndarray:
     m = np.zeros((64, 64), np.uint8)
-    lib().orc_worldgen(_p(m), ctypes.c_uint64(seed), ctypes.c_uint32(env), ctypes.c_uint32(episode))
+    lib().orc_worldgen_mode(_p(m), ctypes.c_uint64(seed), ctypes.c_uint32(env), ctypes.c_uint32(episode), ctypes.c_uint32(mode))
     return m
+
+
+def perlin_noise(lattice: np.ndarray, spacing: int, x: int, y: int) -> int:
+    """Integer Perlin noise of the oracle over a square u16 lattice, on the 0..65535 scale."""
+    lat = np.ascontiguousarray(lattice, dtype=np.uint16)
+    return int(lib().orc_perlin_noise(_p(lat), lat.shape[1], spacing, x, y))
 
 
 class Oracle:

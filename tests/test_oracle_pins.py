@@ -958,3 +958,82 @@ def test_swap_mutation_draws_follow_the_counter_layout():
     want[ay, ax], want[by, bx] = m[by, bx], m[ay, ax]
     assert o.mutate_swap(seed, rnd, False)[0] == k + 1
     assert np.array_equal(e["map"].reshape(64, 64), want)
+
+
+# --------------------------------------------------- Perlin world generation (appendix "World Generation") ----
+def perlin_float(lat, S, x, y):
+    """Perlin noise from its definition, in double precision: unit gradients at the lattice
+    angles, corner dot products, fade 6t^5 - 15t^4 + 10t^3, blend along x then y."""
+    ix, iy, tx, ty = x // S, y // S, (x % S) / S, (y % S) / S
+    fade = lambda t: t * t * t * (t * (6 * t - 15) + 10)
+    dots = np.zeros((2, 2))
+    for cy in range(2):
+        for cx in range(2):
+            th = 2 * np.pi * (int(lat[iy + cy, ix + cx]) >> 6) / 1024
+            dots[cy, cx] = np.cos(th) * (tx - cx) + np.sin(th) * (ty - cy)
+    top = dots[0, 0] + fade(tx) * (dots[0, 1] - dots[0, 0])
+    bot = dots[1, 0] + fade(tx) * (dots[1, 1] - dots[1, 0])
+    return top + fade(ty) * (bot - top)
+
+
+@pytest.mark.parametrize("spacing,width", [(16, 5), (8, 9)])
+def test_perlin_noise_against_its_definition(spacing, width):
+    rng = np.random.default_rng(17)
+    lat = rng.integers(0, 65536, size=(width, width)).astype(np.uint16)
+    # zero at every lattice point: the middle of the 0..65535 scale
+    for j in range(width - 1):
+        for i in range(width - 1):
+            assert po.perlin_noise(lat, spacing, i * spacing, j * spacing) == 32768
+    # the definition in floating point, on the oracle's scale (gain 3900 / 1024 per unit of 1 / 16384)
+    worst = 0.0
+    for y in range(0, 64, 3):
+        for x in range(0, 64, 1):
+            want = 32768 + 16 * 3900 * perlin_float(lat, spacing, x, y)
+            got = po.perlin_noise(lat, spacing, x, y)
+            if 0 < got < 65535:
+                worst = max(worst, abs(got - want))
+            else:
+                assert want < 8 or want > 65527
+    assert worst < 8.0                                          # Q14 gradients and Q16 fade weights: a few units of 65536
+    # turning every gradient by half a turn mirrors the field about the middle
+    flipped = ((lat.astype(np.uint32) + (512 << 6)) & 0xFFFF).astype(np.uint16)
+    for x, y in [(3, 17), (40, 9), (62, 62), (1, 55), (33, 31)]:
+        a, b = po.perlin_noise(lat, spacing, x, y), po.perlin_noise(flipped, spacing, x, y)
+        if 0 < a < 65535 and 0 < b < 65535:
+            assert abs((a - 32768) + (b - 32768)) <= 3
+    # transposing the lattice and swapping cos and sin (angle -> quarter turn - angle) transposes the field
+    mirrored = (((256 - (lat.astype(np.int64) >> 6)) % 1024) << 6).astype(np.uint16).T.copy()
+    for x, y in [(3, 17), (40, 9), (62, 62), (1, 55)]:
+        assert abs(po.perlin_noise(lat, spacing, x, y) - po.perlin_noise(mirrored, spacing, y, x)) <= 3
+
+
+def test_perlin_worldgen_structure():
+    hist = np.zeros(17, np.int64)
+    for s in range(200):
+        m = po.worldgen(s, s, 0, po.WORLDGEN_PERLIN)
+        hist += np.bincount(m.ravel(), minlength=17)
+        assert np.all(m[30:35, 30:35] == GRASS)
+        assert not np.array_equal(m, po.worldgen(s, s, 0, po.WORLDGEN_VALUE))
+        if s < 20:
+            assert np.array_equal(m, po.worldgen(s, s, 0, po.WORLDGEN_PERLIN))
+            assert not np.array_equal(m, po.worldgen(s, s, 1, po.WORLDGEN_PERLIN))
+    natural = [GRASS, WATER, STONE, TREE, PATH, COAL, IRON, DIAMOND, SAND, LAVA]
+    assert all(hist[b] > 0 for b in natural)
+    assert all(hist[b] == 0 for b in [0, 1, WOOD, TABLE, FURNACE, PLANT, RIPE])
+    frac = hist / hist.sum()
+    assert 0.25 < frac[GRASS] < 0.6 and 0.05 < frac[WATER] < 0.3 and 0.05 < frac[STONE] < 0.3
+    assert frac[DIAMOND] < frac[IRON] < frac[COAL] < frac[STONE]
+
+
+def test_perlin_mode_is_used_by_reset_and_auto_reset():
+    cfg = po.default_config(worldgen=po.WORLDGEN_PERLIN, max_episode_steps=3)
+    o = po.Oracle(2, cfg)
+    seeds = synth.seeds_for(2, 9)
+    o.reset(seeds)
+    for i in range(2):
+        assert np.array_equal(o.envs[i]["map"].reshape(64, 64), po.worldgen(int(seeds[i]), i, 0, po.WORLDGEN_PERLIN))
+    for _ in range(3):
+        o.step(np.zeros(2, np.int32))
+    assert np.all(o.envs["episode"] == 1)
+    for i in range(2):
+        assert np.array_equal(o.envs[i]["map"].reshape(64, 64), po.worldgen(int(seeds[i]), i, 1, po.WORLDGEN_PERLIN))
