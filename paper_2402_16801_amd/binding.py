@@ -15,6 +15,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libcraftax_hip.so")
 
 OBS_SYM_U8_I8, OBS_SYM_U8_F32, OBS_SYM_F32, OBS_PIXELS_F32 = 0, 1, 2, 3
+WORLDGEN_VALUE, WORLDGEN_PERLIN = 0, 1
 VARIANT_CLASSIC, VARIANT_CRAFTAX = 0, 1
 
 EXPORTS = [
@@ -29,7 +30,8 @@ class Config(ctypes.Structure):
     _fields_ = [("abi_version", ctypes.c_uint32), ("variant", ctypes.c_uint32), ("obs_mode", ctypes.c_uint32),
                 ("max_episode_steps", ctypes.c_uint32), ("day_length", ctypes.c_uint32),
                 ("cap_zombie", ctypes.c_uint32), ("cap_cow", ctypes.c_uint32), ("cap_skeleton", ctypes.c_uint32),
-                ("cap_arrow", ctypes.c_uint32), ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64)]
+                ("cap_arrow", ctypes.c_uint32), ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64),
+                ("worldgen", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 # numpy views of the canonical dumps declared in include/craftax.h

@@ -134,6 +134,7 @@ struct Luts {
     float tile[16 * 147];           // tile atlas [block id - 1][7][7][3]
     float ent[5 * 147];             // entity atlas [player, zombie, cow, skeleton, arrow][7][7][3]
     uint8_t ent_mask[256];          // [5][49] 0/1
+    uint32_t perlin_cs[1024];       // unit gradient of direction a: cos (low half) and sin (high half) in Q14, as int16
 };
 
 struct Header {
@@ -153,6 +154,7 @@ struct Params {
     int n;
     uint32_t max_episode_steps, day_length;
     uint32_t cap_zombie, cap_cow, cap_skeleton, cap_arrow, cap_plant;
+    uint32_t worldgen;              // CRAFTAX_WORLDGEN_*
 };
 
 // ---- lane groups --------------------------------------------------------------------------------

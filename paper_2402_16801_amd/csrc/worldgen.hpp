@@ -1,8 +1,8 @@
 // Block-cooperative generation of one 64x64 Craftax-Classic world (appendix "World
 // Generation" of the paper: noise thresholds carve grassland, forest, lakes, mountains with
-// caves, tunnels, ores and lava).  The paper uses Perlin noise in floating point; this
-// library uses seeded integer value noise so that every cell is a pure integer function of
-// (seed, env, episode).  All 512 threads of the block take part.
+// caves, tunnels, ores and lava).  Two noises feed the same rule: seeded integer value noise
+// (the benchmark configurations) and Perlin gradient noise as the paper uses, evaluated in
+// integers; either way every cell is a pure integer function of (seed, env, episode).
 #pragma once
 
 #include "common.hpp"
@@ -39,6 +39,41 @@ __device__ inline uint32_t column(const uint16_t* lat, int width, int ix, int iy
 __device__ inline uint32_t across(uint32_t left, uint32_t right, uint32_t wx)
 {
     return (left * (256u - wx) + right * wx) >> 16;
+}
+
+// Perlin gradient noise (appendix "World Generation"): the lattice numbers are read as one of 1024
+// directions (top ten bits); cs[a] holds the unit gradient of direction a in Q14.  S is the
+// lattice spacing; offsets from the four corners are in units of 1/S; the fade weight
+// 6t^5 - 15t^4 + 10t^3 of t = k/S is (F 65536 + S^5 / 2) / S^5 in Q16 with
+// F = k^3 (6 k^2 - 15 k S + 10 S^2); blends are p + floor((q - p) w / 65536), along x then y; the
+// value, in units of 1 / (16384 S), lands on the 0..65535 scale of the thresholds as
+// 32768 + floor(n * 3900 / (1024 S)), clamped.  All divisors are powers of two: floors are shifts.
+constexpr int PERLIN_GAIN = 3900;
+template <int S>
+__device__ inline int64_t perlin_fade(int k)
+{
+    const int F = k * k * k * (6 * k * k - 15 * k * S + 10 * S * S);
+    return S == 16 ? (int64_t)((F + 8) >> 4) : (int64_t)(2 * F);
+}
+__device__ inline int64_t perlin_blend(int64_t p, int64_t q, int64_t w) { return p + (((q - p) * w) >> 16); }
+template <int S>
+__device__ inline uint32_t perlin(const uint16_t* lat, int width, const uint32_t* __restrict__ cs, int x, int y)
+{
+    static_assert(S == 8 || S == 16, "lattice spacing");
+    constexpr int SHIFT = S == 16 ? 4 : 3;
+    const int ix = x >> SHIFT, iy = y >> SHIFT, kx = x & (S - 1), ky = y & (S - 1);
+    int64_t dot[2][2];
+#pragma unroll
+    for (int cy = 0; cy < 2; ++cy)
+#pragma unroll
+        for (int cx = 0; cx < 2; ++cx) {
+            const uint32_t g = cs[lat[(iy + cy) * width + ix + cx] >> 6];
+            dot[cy][cx] = (int64_t)((int)(int16_t)(g & 0xFFFFu) * (kx - cx * S) + (int)(int16_t)(g >> 16) * (ky - cy * S));
+        }
+    const int64_t wx = perlin_fade<S>(kx), wy = perlin_fade<S>(ky);
+    const int64_t n = perlin_blend(perlin_blend(dot[0][0], dot[0][1], wx), perlin_blend(dot[1][0], dot[1][1], wx), wy);
+    const int64_t v = 32768 + ((n * PERLIN_GAIN) >> (10 + SHIFT));
+    return (uint32_t)(v < 0 ? 0 : (v > 65535 ? 65535 : v));
 }
 
 __device__ inline int classify(int W, int M, int C, int F, int x, int y, int u)
@@ -80,10 +115,11 @@ constexpr int WG_THREADS = 512;
 // can be rendered without reading the map back.
 // first_run, runs: the part of the world this call generates (runs first_run .. first_run + runs - 1
 // of the 512; a world may be split over several blocks); runs <= NT.
-template <int NT = WG_THREADS>
+// PERLIN: the fields are Perlin noise over the same lattices (perlin_cs: the gradient table).
+template <int NT = WG_THREADS, bool PERLIN = false>
 __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat, uint32_t seed_lo, uint32_t seed_hi,
                                       uint32_t env, uint32_t episode, uint32_t* start_win = nullptr, int first_run = 0,
-                                      int runs = WG_THREADS)
+                                      int runs = WG_THREADS, const uint32_t* __restrict__ perlin_cs = nullptr)
 {
     static_assert(WG_THREADS % NT == 0 && NT >= 64, "block size must divide 512");
     const int tid0 = threadIdx.x;
@@ -122,10 +158,19 @@ __device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat
         const int x = x0 + j;
         const uint32_t rw = r.w[j >> 1];
         const int u = (int)((j & 1) ? (rw >> 16) : (rw & 0xFFFFu));
-        const uint32_t wx8 = smooth8(j), wx16 = smooth16(x & 15);
-        const int W = (int)((3u * across(W16a, W16b, wx16) + across(Wl, Wr, wx8)) >> 2);
-        const int M = (int)((3u * across(M16a, M16b, wx16) + across(Ml, Mr, wx8)) >> 2);
-        const int C = (int)across(Cl, Cr, wx8), F = (int)across(Fl, Fr, wx8);
+        int W, M, C, F;
+        if (PERLIN) {
+            W = (int)((3u * perlin<16>(w16, 5, perlin_cs, x, y) + perlin<8>(w8, 9, perlin_cs, x, y)) >> 2);
+            M = (int)((3u * perlin<16>(m16, 5, perlin_cs, x, y) + perlin<8>(m8, 9, perlin_cs, x, y)) >> 2);
+            C = (int)perlin<8>(c8, 9, perlin_cs, x, y);
+            F = (int)perlin<8>(f8, 9, perlin_cs, x, y);
+        } else {
+            const uint32_t wx8 = smooth8(j), wx16 = smooth16(x & 15);
+            W = (int)((3u * across(W16a, W16b, wx16) + across(Wl, Wr, wx8)) >> 2);
+            M = (int)((3u * across(M16a, M16b, wx16) + across(Ml, Mr, wx8)) >> 2);
+            C = (int)across(Cl, Cr, wx8);
+            F = (int)across(Fl, Fr, wx8);
+        }
         packed[j >> 2] |= (uint32_t)classify(W, M, C, F, x, y, u) << (8 * (j & 3));
     }
     *reinterpret_cast<uint2*>(map + map_index(x0, y)) = make_uint2(packed[0], packed[1]);   // 8 cells inside one tile row

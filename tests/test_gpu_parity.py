@@ -424,3 +424,51 @@ def test_swap_mutation_matches_the_oracle(cx, restricted):
     with pytest.raises(cx.CraftaxError):
         cx.craftax_mutate_swap(sim.state, 290, 20, 1, 0, False, None, sim.stream)
     sim.close()
+
+
+@pytest.mark.parametrize("lanes", [4, 8, 16])
+def test_perlin_worldgen_mode(cx, lanes):
+    """The paper's Perlin-noise world generation: reset worlds, worlds regenerated one episode
+    ahead (short episodes), worlds generated in place (one-step episodes), and imports."""
+    import torch
+    P = po.WORLDGEN_PERLIN
+    # reset: the generated maps themselves
+    n = 70
+    gcfg, ocfg = _cfgs(cx, po.OBS_SYM_U8_F32, worldgen=P)
+    sim = _make_sim(cx, n, gcfg, lanes)
+    seeds = synth.seeds_for(n, 123)
+    sim.reset(seeds)
+    maps = sim.export_envs().view(po.ENV_DTYPE)["map"].reshape(n, 64, 64)
+    for i in range(n):
+        assert np.array_equal(maps[i], po.worldgen(int(seeds[i]), i, 0, P)), f"world of env {i}"
+    assert not np.array_equal(maps[0], po.worldgen(int(seeds[0]), 0, 0, po.WORLDGEN_VALUE))
+    sim.close()
+    run_parity(cx, 150, 200, po.OBS_SYM_U8_F32, "skewed", state_every=10, max_episode_steps=12, lanes=lanes, worldgen=P)
+    run_parity(cx, 37, 25, po.OBS_SYM_U8_I8, "uniform", state_every=1, max_episode_steps=1, lanes=lanes, worldgen=P)
+    run_parity(cx, 53, 30, po.OBS_SYM_U8_F32, "uniform", state_every=1, max_episode_steps=2, lanes=lanes, worldgen=P)
+    run_parity(cx, 20, 60, po.OBS_PIXELS_F32, "uniform", state_every=10, obs_every=5, max_episode_steps=25, lanes=lanes, worldgen=P)
+
+
+def test_perlin_worldgen_after_import_and_bad_mode(cx):
+    import torch
+    P = po.WORLDGEN_PERLIN
+    n = 24
+    gcfg, ocfg = _cfgs(cx, po.OBS_SYM_U8_F32, worldgen=P, max_episode_steps=500)
+    sim = _make_sim(cx, n, gcfg)
+    orc = po.Oracle(n, ocfg)
+    seeds = synth.seeds_for(n, 5)
+    sim.reset(seeds); orc.reset(seeds)
+    orc.envs["t"][:] = 499
+    orc.envs["episode"][::2] += 7
+    sim.import_envs(orc.envs.copy())
+    for s in range(3):
+        a = synth.actions(np.arange(n), s, "uniform")
+        obs, rew, done = sim.step(torch.as_tensor(a, device=sim.device))
+        oobs, orew, odone = orc.step(a)
+        assert np.array_equal(done.cpu().numpy(), odone) and np.array_equal(obs.cpu().numpy(), oobs)
+        assert sim.export_envs().tobytes() == orc.envs.tobytes()
+    sim.close()
+    bad = cx.default_config(worldgen=2)
+    assert cx.craftax_state_bytes(bad, 8) == 0
+    full = cx.default_config(cx.VARIANT_CRAFTAX, worldgen=P)
+    assert cx.craftax_state_bytes(full, 8) == 0
