@@ -83,7 +83,7 @@ __device__ inline uint32_t spread4(uint32_t nibble) { return (nibble * 0x0020408
 // per cell; every lane then expands 16 bits at a time into one 16-byte piece of the output, so
 // that a wavefront writes whole cache lines.
 template <bool F32>
-__device__ inline void render_env(const int l, uint32_t* e, const int wx0, const int wy0, const int m_alive, const int m_x,
+__device__ __forceinline__ void render_env(const int l, uint32_t* e, const int wx0, const int wy0, const int m_alive, const int m_x,
                                   const int m_y, const int m_type, const Luts* __restrict__ luts, uint8_t* __restrict__ out)
 {
     const uint32_t* rec = e + L_REC;

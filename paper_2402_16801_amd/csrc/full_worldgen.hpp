@@ -182,7 +182,7 @@ __device__ inline void make_cave_ladders(GenLayout& L, int f, const U4& r)
 // first_run, runs: the part of the floor this call generates (a floor may be split over several
 // blocks); runs <= NT.
 template <int NT = GEN_THREADS>
-__device__ inline void worldgen_floor_block(uint8_t* __restrict__ maps, uint16_t* s_lat, GenLayout& L, uint32_t lo, uint32_t hi,
+__device__ __forceinline__ void worldgen_floor_block(uint8_t* __restrict__ maps, uint16_t* s_lat, GenLayout& L, uint32_t lo, uint32_t hi,
                                             uint32_t env, uint32_t episode, int f, uint8_t* start_wb = nullptr,
                                             uint8_t* start_wi = nullptr, int first_run = 0, int runs = GEN_THREADS)
 {

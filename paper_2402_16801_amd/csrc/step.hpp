@@ -89,6 +89,9 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     const int px0 = w_pos & 0xFF, py0 = (w_pos >> 8) & 0xFF;
     int px = px0, py = py0, dir = (w_pos >> 16) & 0xFF, sleeping = (w_pos >> 24) & 0xFF;
     load_window<G>(l, px0, py0, map, e + LDS_WIN);
+    // where a lane with nothing to read points its load: the player's own cell, whose cache line
+    // the window load fetches anyway (any other fixed cell would cost a line of its own)
+    const int idle_cell = map_index(px0, py0);
     const int woff = (px0 - WIN_COLS / 2) & 3;      // where window column 0 sits in a row
     int vit[4], cnt[4];
 #pragma unroll
@@ -110,7 +113,7 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     for (int s = 0; s < NSP; ++s) {
         const int k = l + s * G;
         qw[s] = k < NPLANT ? rec[RW_PLANT + k] : 0u;
-        q_block[s] = (int)map[(qw[s] & 1u) ? map_index(mob_x(qw[s]), mob_y(qw[s])) : 0];   // unconditional load
+        q_block[s] = (int)map[(qw[s] & 1u) ? map_index(mob_x(qw[s]), mob_y(qw[s])) : idle_cell];   // unconditional load
         if (!(qw[s] & 1u)) q_block[s] = BK_INVALID;
     }
     const int health0 = vit[0];
@@ -294,9 +297,9 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
         }
         kind_[s] = kind; ndir_[s] = ndir;
         tx_[s] = mx + dir_dx(ndir); ty_[s] = my + dir_dy(ndir);
-        // terrain of the target cell: loaded unconditionally (cell 0 when there is no target)
+        // terrain of the target cell: loaded unconditionally (the idle cell when there is no target)
         const bool need = kind != K_NONE && kind != K_ATTACK && in_map(tx_[s], ty_[s]);
-        tb_[s] = (int)map[need ? map_index(tx_[s], ty_[s]) : 0];
+        tb_[s] = (int)map[need ? map_index(tx_[s], ty_[s]) : idle_cell];
     }
     // spawn candidates (phase 3) are fixed by the draws and the player's position: read their
     // terrain now so the loads overlap the mob resolution below
@@ -314,7 +317,7 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
         // terrain byte (a whole cache line of traffic) is then not fetched at all
         sp_cand[j] = max(iabs(dx), iabs(dy)) >= SPAWN_MIN_DIST && in_map(sx, sy) && sp_p < thr;
         sp_key[j] = cell_key(sx & 63, sy & 63);
-        sp_b[j] = (int)map[sp_cand[j] ? map_index(sx, sy) : 0];
+        sp_b[j] = (int)map[sp_cand[j] ? map_index(sx, sy) : idle_cell];
         if (!sp_cand[j]) sp_b[j] = BK_OOB;
     }
 #pragma unroll

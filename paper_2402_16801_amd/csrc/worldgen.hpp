@@ -117,7 +117,7 @@ constexpr int WG_THREADS = 512;
 // of the 512; a world may be split over several blocks); runs <= NT.
 // PERLIN: the fields are Perlin noise over the same lattices (perlin_cs: the gradient table).
 template <int NT = WG_THREADS, bool PERLIN = false>
-__device__ inline void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat, uint32_t seed_lo, uint32_t seed_hi,
+__device__ __forceinline__ void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat, uint32_t seed_lo, uint32_t seed_hi,
                                       uint32_t env, uint32_t episode, uint32_t* start_win = nullptr, int first_run = 0,
                                       int runs = WG_THREADS, const uint32_t* __restrict__ perlin_cs = nullptr)
 {
