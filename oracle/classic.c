@@ -55,11 +55,11 @@ enum { DIR_NONE = 0, DIR_LEFT = 1, DIR_RIGHT = 2, DIR_UP = 3, DIR_DOWN = 4 };
 #define FOOD_PLANT 4
 
 #define P_SAPLING 429496730u     /* 10 %  of 2^32 */
-#define P_CHASE 3435973836u      /* 80 % */
-#define P_SHOOT 0x80000000u      /* 50 % */
-#define P_PLANT_EATEN 0x20000000u /* 1/8 */
-#define P_COW_SPAWN 0x08000000u  /* 1/32 */
-#define P_SKELETON_SPAWN 0x19999999u /* 10 % */
+#define P_CHASE 52429u           /* 80 %  of 2^16 */
+#define P_SHOOT 32768u           /* 50 %  of 2^16 */
+#define P_PLANT_EATEN 32u        /* 1/8   of 2^8 */
+#define P_COW_SPAWN 128u         /* 1/32  of 2^12 */
+#define P_SKELETON_SPAWN 410u    /* 10 %  of 2^12 */
 
 /* Philox counter layout (reading): key = 64-bit seed (low word, high word);
  * counter = (env, a, b, domain<<16 | block).  STEP: a = t, b = episode.
@@ -76,16 +76,23 @@ static uint32_t philox_word(uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2
     return out[word];
 }
 
-/* Static draw slots of one step (reading): block k (k = 0..11) holds
- *   word 0  movement draw of mob slot k        word 1  decision draw of mob slot k
- *   word 2  "eaten" draw of plant slot k (k<10) word 3  misc[k]
- * misc[3j..3j+2] = (x, y, probability) draws of the spawn attempt of type j (zombie, cow,
- * skeleton); misc[9] = sapling draw of DO on grass.  A draw is the same number whether or
- * not control flow uses it, so an action whose prerequisites fail equals NOOP exactly. */
+/* Static draw slots of one step (reading): four Philox blocks b = 0..3 of four words each.
+ *   block b, word s (s = 0..2): the draws of mob slot k = b + 4 s and of plant slot k (k < 10):
+ *       bits 0..15   decision draw, compared with 16-bit thresholds
+ *       bits 16..18  movement choice: 0..3 a direction, 4..7 stay
+ *       bits 19..26  "eaten" draw of the plant, compared with an 8-bit threshold
+ *   block b, word 3: misc[b].  misc[j], j = 0..2, is the spawn attempt of type j (zombie, cow,
+ *       skeleton): bits 0..9 and 10..19 pick the x and y offsets as ((v * 31) >> 10) - 15, bits
+ *       20..31 are the probability draw (12 bits); misc[3] is the sapling draw of DO on grass
+ *       (all 32 bits).
+ * A draw is the same number whether or not control flow uses it, so an action whose
+ * prerequisites fail equals NOOP exactly. */
 uint32_t orc_step_draw(const orc_env *e, uint32_t block, uint32_t word)
 {
     return philox_word(e->seed, e->env, e->t, e->episode, DOM_STEP, block, word);
 }
+static uint32_t slot_draw(const orc_env *e, int k) { return orc_step_draw(e, (uint32_t)(k & 3), (uint32_t)(k >> 2)); }
+static uint32_t misc_draw(const orc_env *e, int j) { return orc_step_draw(e, (uint32_t)j, 3); }
 
 static uint32_t choice(uint32_t u, uint32_t n) { return (uint32_t)(((uint64_t)u * n) >> 32); }
 
@@ -465,7 +472,7 @@ static void player_action(orc_env *e, const orc_config *cfg, int a)
             unlock(e, ACH_COLLECT_DRINK);
             break;
         case B_GRASS:
-            if (orc_step_draw(e, 9, 3) < P_SAPLING)
+            if (misc_draw(e, 3) < P_SAPLING)
                 collect(e, cell, I_SAPLING, 1, B_GRASS, ACH_COLLECT_SAPLING);
             break;
         case B_RIPE: {
@@ -547,8 +554,8 @@ static void mob_update(orc_env *e, const orc_config *cfg, int k, int *damage)
     int type = mob_type(k);
     int dx = (int)e->px - m->x, dy = (int)e->py - m->y;
     int adx = iabs(dx), ady = iabs(dy), cheb = imax(adx, ady);
-    uint32_t r_move = orc_step_draw(e, (uint32_t)k, 0), r_act = orc_step_draw(e, (uint32_t)k, 1);
-    uint32_t m8 = choice(r_move, 8);     /* 0..3: a direction, 4..7: stay */
+    uint32_t r_act = slot_draw(e, k) & 0xFFFFu;
+    uint32_t m8 = (slot_draw(e, k) >> 16) & 7u;     /* 0..3: a direction, 4..7: stay */
 
     if (type == T_ZOMBIE) {
         if (m->cd > 0) m->cd--;
@@ -604,16 +611,17 @@ static void despawn_spawn(orc_env *e, const orc_config *cfg)
     const uint32_t caps[3] = { cfg->cap_zombie, cfg->cap_cow, cfg->cap_skeleton };
     const int8_t hp[3] = { HP_ZOMBIE, HP_COW, HP_SKELETON };
     for (int j = 0; j < 3; j++) {
-        int dx = (int)choice(orc_step_draw(e, (uint32_t)(3 * j), 3), 31) - 15;
-        int dy = (int)choice(orc_step_draw(e, (uint32_t)(3 * j + 1), 3), 31) - 15;
-        uint32_t rp = orc_step_draw(e, (uint32_t)(3 * j + 2), 3);
+        uint32_t w = misc_draw(e, j);
+        int dx = (int)(((w & 1023u) * 31u) >> 10) - 15;
+        int dy = (int)((((w >> 10) & 1023u) * 31u) >> 10) - 15;
+        uint32_t rp = w >> 20;
         int slot = -1;
         for (uint32_t s = 0; s < caps[j] && s < 3; s++)
             if (!e->mob[3 * j + s].alive) { slot = 3 * j + (int)s; break; }
         int x = e->px + dx, y = e->py + dy;
         if (slot < 0 || imax(iabs(dx), iabs(dy)) < SPAWN_MIN_DIST || !inb(x, y) || occupied(e, x, y)) continue;
         uint8_t b = e->map[y * ORC_MAP + x];
-        uint32_t thr = j == T_ZOMBIE ? orc_zombie_spawn_threshold(cfg, e->t)
+        uint32_t thr = j == T_ZOMBIE ? orc_zombie_spawn_threshold(cfg, e->t) >> 20   /* its top 12 bits */
                      : j == T_COW ? P_COW_SPAWN : P_SKELETON_SPAWN;
         uint8_t want = j == T_SKELETON ? B_PATH : B_GRASS;
         if (b != want || rp >= thr) continue;
@@ -636,7 +644,7 @@ static void plants(orc_env *e)
             const orc_mob *m = &e->mob[z];
             if (m->alive && iabs((int)m->x - p->x) + iabs((int)m->y - p->y) == 1) zombie_near = 1;
         }
-        if (zombie_near && orc_step_draw(e, (uint32_t)k, 2) < P_PLANT_EATEN) {
+        if (zombie_near && ((slot_draw(e, k) >> 19) & 0xFFu) < P_PLANT_EATEN) {
             e->map[cell] = B_GRASS;
             memset(p, 0, sizeof(*p));
         }

@@ -179,6 +179,12 @@ def blank(n=1, block=GRASS, caps=0, **cfgkw):
     return o
 
 
+def slot_draw(o, k, i=0):
+    """The packed draws of mob / plant slot k: word k // 4 of Philox block k % 4 of the step;
+    bits 0..15 decision, 16..18 movement choice, 19..26 the plant's "eaten" draw."""
+    return o.draw(i, k & 3, k >> 2)
+
+
 def step(o, a, i=0):
     return o.step_rules_one(i, a)
 
@@ -377,7 +383,7 @@ def test_zombie_eats_plant_with_probability_one_eighth():
         e["map"][40, 40] = PLANT
         e["plant"][2] = (1, 40, 40, 0, 5)
         e["mob"][1] = (1, 41, 40, 0, 5, 3, (0, 0))   # zombie right of the plant, far from the player
-        pred = o.draw(0, 2, 2) < 0x20000000
+        pred = ((slot_draw(o, 2) >> 19) & 0xFF) < 32
         # freeze the zombie: surround by stone so it cannot leave
         for (x, y) in [(42, 40), (41, 39), (41, 41)]:
             e["map"][y, x] = STONE
@@ -398,11 +404,11 @@ def test_drink_and_sapling_probability():
     e["cnt"][THIRST] = 30
     r, _ = step(o, DO)
     assert e["vit"][DRINK] == 6 and e["cnt"][THIRST] == 2 and r == np.float32(1.0)
-    # sapling from grass follows draw misc[9] < 10 %
+    # sapling from grass follows draw misc[3] < 10 %
     e["map"][33, 32] = GRASS
     got = 0
     for _ in range(300):
-        pred = o.draw(0, 9, 3) < 429496730
+        pred = o.draw(0, 3, 3) < 429496730
         n0 = e["inv"][I_SAPLING]
         e["inv"][I_SAPLING] = 0
         step(o, DO)
@@ -483,7 +489,7 @@ def test_cow_moves_by_its_draw():
     e["mob"][3] = (1, 10, 10, 0, 3, 0, (0, 0))
     for _ in range(60):
         x, y = int(e["mob"][3]["x"]), int(e["mob"][3]["y"])
-        m = (o.draw(0, 3, 0) * 8) >> 32
+        m = (slot_draw(o, 3) >> 16) & 7
         dx, dy = {0: (-1, 0), 1: (1, 0), 2: (0, -1), 3: (0, 1)}.get(m, (0, 0))
         e["px"], e["py"] = x + 3, y + 3     # keep the player close enough that it does not despawn
         step(o, NOOP)
@@ -496,8 +502,8 @@ def test_zombie_chases():
     e["mob"][2] = (1, 37, 30, 0, 5, 0, (0, 0))      # dx = -5, dy = 2 -> chase goes LEFT
     for _ in range(40):
         e["mob"][2]["x"], e["mob"][2]["y"] = 37, 30
-        chase = o.draw(0, 2, 1) < 3435973836
-        m = (o.draw(0, 2, 0) * 8) >> 32
+        chase = (slot_draw(o, 2) & 0xFFFF) < 52429
+        m = (slot_draw(o, 2) >> 16) & 7
         step(o, NOOP)
         pos = (int(e["mob"][2]["x"]), int(e["mob"][2]["y"]))
         if chase:
@@ -515,7 +521,7 @@ def test_skeleton_shoots_and_arrow_flies():
         e["mob"][:] = 0
         e["vit"][HEALTH] = 9
         e["mob"][7] = (1, 32, 29, 0, 3, 0, (0, 0))  # three cells above the player
-        will_shoot = o.draw(0, 7, 1) < 0x80000000
+        will_shoot = (slot_draw(o, 7) & 0xFFFF) < 32768
         step(o, NOOP)
         if will_shoot:
             shot += 1
@@ -591,11 +597,12 @@ def test_despawn_and_spawn_rules():
         e["cnt"][:] = 0
         t = int(e["t"])
         preds = []
-        for j, (want, thr) in enumerate([(GRASS, L.orc_zombie_spawn_threshold(ctypes.byref(cfg), ctypes.c_uint32(t))),
-                                         (GRASS, 0x08000000), (PATH, 0x19999999)]):
-            dx = ((o.draw(0, 3 * j, 3) * 31) >> 32) - 15
-            dy = ((o.draw(0, 3 * j + 1, 3) * 31) >> 32) - 15
-            rp = o.draw(0, 3 * j + 2, 3)
+        for j, (want, thr) in enumerate([(GRASS, L.orc_zombie_spawn_threshold(ctypes.byref(cfg), ctypes.c_uint32(t)) >> 20),
+                                         (GRASS, 128), (PATH, 410)]):
+            w = o.draw(0, j, 3)                       # misc[j]: x and y picks of 10 bits, a 12-bit probability draw
+            dx = (((w & 1023) * 31) >> 10) - 15
+            dy = ((((w >> 10) & 1023) * 31) >> 10) - 15
+            rp = w >> 20
             x, y = 32 + dx, 32 + dy
             ok = max(abs(dx), abs(dy)) >= 5 and 0 <= x < 64 and 0 <= y < 64 and e["map"][y, x] == want and rp < thr
             ok = ok and not any(p == (x, y) for p in preds)
