@@ -38,11 +38,11 @@ constexpr int CHASE_RANGE = 8, SHOOT_RANGE = 4, DESPAWN_DIST = 15, SPAWN_MIN_DIS
 constexpr int RIPE_AGE = 300;
 constexpr int FOOD_COW = 6, FOOD_PLANT = 4;
 constexpr uint32_t P_SAPLING = 429496730u;        // 10 %
-constexpr uint32_t P_CHASE = 3435973836u;         // 80 %
-constexpr uint32_t P_SHOOT = 0x80000000u;         // 50 %
-constexpr uint32_t P_PLANT_EATEN = 0x20000000u;   // 1/8
-constexpr uint32_t P_COW_SPAWN = 0x08000000u;     // 1/32
-constexpr uint32_t P_SKELETON_SPAWN = 0x19999999u;// 10 %
+constexpr uint32_t P_CHASE = 52429u;              // 80 % of 2^16
+constexpr uint32_t P_SHOOT = 32768u;              // 50 % of 2^16
+constexpr uint32_t P_PLANT_EATEN = 32u;           // 1/8 of 2^8
+constexpr uint32_t P_COW_SPAWN = 128u;            // 1/32 of 2^12
+constexpr uint32_t P_SKELETON_SPAWN = 410u;       // 10 % of 2^12
 
 constexpr int VIEW_ROWS = 7, VIEW_COLS = 9, NCHAN = 21, NVEC = 22;
 constexpr int CELL_BYTES = VIEW_ROWS * VIEW_COLS * NCHAN;  // 1323

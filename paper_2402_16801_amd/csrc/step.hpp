@@ -7,9 +7,12 @@
 // Crafter"), creature health and damage (appendix "Creatures").  The remaining rules
 // ("mimic Crafter") are this library's own frozen reading.
 //
-// Random draws have fixed slots: Philox block k (k = 0..11) of the step =
-// (move draw of mob k, decision draw of mob k, eaten draw of plant k, misc[k]);
-// misc[3j..3j+2] = (x, y, p) of the spawn attempt of type j; misc[9] = sapling draw.
+// Random draws have fixed slots in four Philox blocks per step: word s < 3 of block b holds the
+// draws of mob and plant slot b + 4s (bits 0..15 decision, 16..18 movement choice, 19..26 the
+// plant's "eaten" draw); word 3 of block b is misc[b]: spawn attempt of type b < 3 (two 10-bit
+// picks for x and y, a 12-bit probability draw) and, for b = 3, the sapling draw.  A lane owns
+// slots l, l + G, ... with G a multiple of four, so block l & 3 holds all its draws: one Philox
+// block per lane and step.
 //
 // Memory round trips of a step: record -> 9x11 map window around the player (kept in LDS,
 // patched with this step's edits, and reused for the observation) -> one terrain byte per
@@ -99,13 +102,16 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     uint32_t phase = w_vit >> 16;
     uint32_t ach = rec[RW_ACH];
     const uint32_t t = rec[RW_T], episode = rec[RW_EPISODE], seed_lo = rec[RW_SEED_LO], seed_hi = rec[RW_SEED_HI];
+    static_assert(G % 4 == 0, "a lane's slots must share one Philox block");
+    const U4 dr = philox4x32_10(env, t, episode, (DOM_STEP << 16) | (uint32_t)(l & 3), seed_lo, seed_hi);
     uint32_t mw[NSM];                // mob words of the slots this lane owns
-    U4 dr[NSM];
+    uint32_t sw[NSM];                // their packed draws
 #pragma unroll
     for (int s = 0; s < NSM; ++s) {
         const int k = l + s * G;
         mw[s] = k < NMOB ? rec[RW_MOB + k] : 0u;
-        dr[s] = philox4x32_10(env, t, episode, (DOM_STEP << 16) | (uint32_t)k, seed_lo, seed_hi);
+        const int w = k >> 2;
+        sw[s] = w == 0 ? dr.w[0] : (w == 1 ? dr.w[1] : (w == 2 ? dr.w[2] : 0u));
     }
     uint32_t qw[NSP];                // plant words
     int q_block[NSP];
@@ -118,7 +124,7 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     }
     const int health0 = vit[0];
     const uint32_t ach0 = ach;
-    const uint32_t sapling_draw = (uint32_t)Gr::shfl((int)dr[9 / G].w[3], 9 % G);
+    const uint32_t sapling_draw = (uint32_t)Gr::shfl((int)dr.w[3], 3);
 
     int a = ((unsigned)action < (unsigned)AC_COUNT) ? action : (int)AC_NOOP;
     if (sleeping) a = AC_NOOP;
@@ -266,8 +272,8 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
             const int type = (k * 11) >> 5;
             const int dx = px - mx, dy = py - my;
             const int adx = iabs(dx), ady = iabs(dy), cheb = max(adx, ady);
-            const uint32_t m8 = dr[s].w[0] >> 29;                 // choice(draw, 8)
-            const uint32_t r_act = dr[s].w[1];
+            const uint32_t m8 = (sw[s] >> 16) & 7u;               // movement choice
+            const uint32_t r_act = sw[s] & 0xFFFFu;               // decision draw
             const int toward = adx >= ady ? (dx < 0 ? 1 : 2) : (dy < 0 ? 3 : 4);
             const int wander = m8 < 4 ? (int)m8 + 1 : 0;
             const int cd = (int)__builtin_amdgcn_ubfe(mw[s], 20, 4);
@@ -308,10 +314,11 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
     bool sp_cand[3];
 #pragma unroll
     for (int j = 0; j < 3; ++j) {
-        const int dx = (int)choice((uint32_t)Gr::shfl((int)dr[(3 * j) / G].w[3], (3 * j) % G), 31) - 15;
-        const int dy = (int)choice((uint32_t)Gr::shfl((int)dr[(3 * j + 1) / G].w[3], (3 * j + 1) % G), 31) - 15;
-        const uint32_t sp_p = (uint32_t)Gr::shfl((int)dr[(3 * j + 2) / G].w[3], (3 * j + 2) % G);
-        const uint32_t thr = j == 0 ? luts->zombie_thr[phase] : (j == 1 ? P_COW_SPAWN : P_SKELETON_SPAWN);
+        const uint32_t sp_w = (uint32_t)Gr::shfl((int)dr.w[3], j);              // misc[j]
+        const int dx = (int)(((sp_w & 1023u) * 31u) >> 10) - 15;
+        const int dy = (int)((((sp_w >> 10) & 1023u) * 31u) >> 10) - 15;
+        const uint32_t sp_p = sp_w >> 20;
+        const uint32_t thr = j == 0 ? luts->zombie_thr[phase] >> 20 : (j == 1 ? P_COW_SPAWN : P_SKELETON_SPAWN);
         const int sx = px + dx, sy = py + dy;
         // a candidate only if the probability draw passes too: most attempts end here, and the
         // terrain byte (a whole cache line of traffic) is then not fetched at all
@@ -418,7 +425,7 @@ __device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __
             if ((qw[s] >> 16) < 65535u) qw[s] += 1u << 16;
             int nb = q_block[s];
             if (nb == BK_PLANT && (qw[s] >> 16) >= (uint32_t)RIPE_AGE) nb = BK_RIPE;
-            if (zombie_near && dr[s].w[2] < P_PLANT_EATEN) nb = BK_GRASS;
+            if (zombie_near && ((sw[s] >> 19) & 0xFFu) < P_PLANT_EATEN) nb = BK_GRASS;
             if (nb != q_block[s]) {
                 map[map_index(qx, qy)] = (uint8_t)nb;
                 const int wx = qx - (px0 - WIN_COLS / 2), wy = qy - (py0 - WIN_ROWS / 2);
