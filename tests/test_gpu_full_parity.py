@@ -377,6 +377,15 @@ def test_full_config4_4096_envs_5000_steps(cx):
     assert finished > 128 * 10
 
 
+def test_full_four_times_the_benchmark_size_sampled(cx):
+    """16,384 environments of the full game (1.4 GB of state) with a short episode cap, so that
+    the regeneration lists are long; a strided sample is followed by the oracle."""
+    sample = np.unique(np.concatenate([np.arange(0, 16384, 512), [16383, 8191]]))
+    finished, _, _ = run_full(cx, 16384, 60, kind="uniform", sample=sample, device_actions=True, obs_every=5,
+                              max_episode_steps=11)
+    assert finished > len(sample) * 4
+
+
 @pytest.mark.parametrize("restricted", [False, True])
 def test_full_swap_mutation_matches_the_oracle(cx, restricted):
     """UED swap / restricted swap of the overworld, with some players below ground."""

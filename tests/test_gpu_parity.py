@@ -133,6 +133,15 @@ def test_config5_pixels_1024_envs_sampled(cx):
                atlas_seed=0)
 
 
+def test_four_times_the_largest_config_sampled(cx):
+    """262,144 environments (2.2 GB of state), short episodes so that every list and every
+    regeneration block is busy; a strided sample is followed by the oracle."""
+    sample = np.unique(np.concatenate([np.arange(0, 262144, 4096), [262143, 131071, 65536]]))
+    finished = run_parity(cx, 262144, 60, po.OBS_SYM_U8_F32, "skewed", sample=sample, state_every=30,
+                          device_actions=True, max_episode_steps=9)
+    assert finished > len(sample) * 5
+
+
 # ---- shapes and edge cases ----------------------------------------------------------------------
 @pytest.mark.parametrize("lanes", [4, 8, 16])
 @pytest.mark.parametrize("n", [1, 5, 16, 17, 33, 65, 250])
