@@ -43,7 +43,7 @@ __device__ __constant__ const ScalarSpec SCALARS[NVEC] = {
 };
 
 // scalar `i` of the observation from the packed record in LDS
-__device__ inline float scalar_value(int i, const uint32_t* rec, const Luts* __restrict__ luts)
+__device__ __forceinline__ float scalar_value(int i, const uint32_t* rec, const Luts* __restrict__ luts)
 {
     const ScalarSpec s = SCALARS[i];
     const uint32_t raw = (rec[s.word] >> s.shift) & s.mask;

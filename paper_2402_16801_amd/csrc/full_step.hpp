@@ -33,7 +33,7 @@ struct Player {
 
 __device__ inline int sext8(uint32_t v) { return (int)(int8_t)(v & 0xFFu); }
 
-__device__ inline void unpack_player(const uint32_t* rec, Player& P)
+__device__ __forceinline__ void unpack_player(const uint32_t* rec, Player& P)
 {
     const uint32_t r0 = uniu(rec[R_POS]), r1 = uniu(rec[R_FLAGS]), r2 = uniu(rec[R_ATTR]);
     P.px = r0 & 0xFF; P.py = (r0 >> 8) & 0xFF; P.dir = (r0 >> 16) & 0xFF; P.floor = (r0 >> 24) & 0xF;
@@ -61,7 +61,7 @@ __device__ inline void unpack_player(const uint32_t* rec, Player& P)
 }
 
 // packs everything that can change back into the LDS copy of the record (one lane writes)
-__device__ inline void pack_player(uint32_t* rec, const Player& P)
+__device__ __forceinline__ void pack_player(uint32_t* rec, const Player& P)
 {
     rec[R_POS] = (uint32_t)P.px | ((uint32_t)P.py << 8) | ((uint32_t)P.dir << 16) | ((uint32_t)P.floor << 24);
     rec[R_FLAGS] = (uint32_t)P.sleeping | ((uint32_t)P.resting << 1) | ((uint32_t)P.fireball << 2) | ((uint32_t)P.iceball << 3) |
@@ -101,7 +101,7 @@ __device__ inline int through(int ap, int af, int ai, int dp, int df, int di)
 }
 
 // Loads the 11 x 13 window of floor f centred on (cx, cy) into LDS (both maps).
-__device__ inline void load_window(int l, const uint8_t* __restrict__ maps, int f, int cx_, int cy_, uint8_t* wb, uint8_t* wi)
+__device__ __forceinline__ void load_window(int l, const uint8_t* __restrict__ maps, int f, int cx_, int cy_, uint8_t* wb, uint8_t* wi)
 {
 #pragma unroll
     for (int it = 0; it < 3; ++it) {
@@ -129,7 +129,7 @@ enum Intent : int { N_NONE = 0, N_DAMAGE, N_DAMAGE_DIE, N_DIE, N_MOVE, N_SHOOT, 
 // after_load: called once the loads of the current window have been issued and stored, before the
 // wave waits for them (the caller parks data it fetched earlier there).
 template <typename AfterLoad>
-__device__ inline StepOut step_env(const int l, const uint32_t env, uint32_t* e, uint32_t* __restrict__ genv,
+__device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uint32_t* e, uint32_t* __restrict__ genv,
                                    uint8_t* __restrict__ maps, const Luts* __restrict__ luts, const int action_in,
                                    const Params& p, MobRegs& m, uint32_t& qw, Player& P, AfterLoad&& after_load)
 {

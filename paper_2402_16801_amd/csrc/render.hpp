@@ -33,7 +33,7 @@ __device__ inline uint32_t spread4(uint32_t nibble) { return (nibble * 0x0020408
 // One 16-byte chunk of a staged observation (byte layouts): chunks 0..82 expand 16 staged bits
 // each, the next 2 or 6 hold the scalars, the rest of the stride is zero.
 template <int OBS_MODE>
-__device__ inline uint4 staged_chunk(const uint32_t* e, int c)
+__device__ __forceinline__ uint4 staged_chunk(const uint32_t* e, int c)
 {
     constexpr int NV = OBS_MODE == 0 ? VEC_CHUNKS_I8 : VEC_CHUNKS_F32;
     if (c < CELL_CHUNKS) {
@@ -53,7 +53,7 @@ __device__ inline uint4 staged_chunk(const uint32_t* e, int c)
 // observation is not read again by this kernel).  With G = 4 a run serves two environments in
 // turn.  wave_env: LDS area of the wave's first environment; wave_obs: its observation.
 template <int G, int OBS_MODE>
-__device__ inline void flush_wave_observations(uint32_t* wave_env, uint8_t* __restrict__ wave_obs)
+__device__ __forceinline__ void flush_wave_observations(uint32_t* wave_env, uint8_t* __restrict__ wave_obs)
 {
     constexpr int RUN = G < 8 ? 8 : G, PASSES = RUN / G, STRIDE = obs_stride(OBS_MODE), NCHUNK = STRIDE / 16;
     const int w = threadIdx.x & 63, run = w / RUN, j = w % RUN;
@@ -80,7 +80,7 @@ __device__ inline void flush_wave_observations(uint32_t* wave_env, uint8_t* __re
 // FLUSH = false: stop after staging (bits and scalars in LDS); the caller writes them out with
 // flush_wave_observations.
 template <int G, int OBS_MODE, bool FILL_VEC = true, bool FLUSH = true>
-__device__ inline void render_symbolic(int l, uint32_t* e, int mvx, int mvy, int woff, const Luts* __restrict__ luts,
+__device__ __forceinline__ void render_symbolic(int l, uint32_t* e, int mvx, int mvy, int woff, const Luts* __restrict__ luts,
                                        uint8_t* __restrict__ obs_out)
 {
     const uint32_t* rec = e + LDS_REC;
@@ -184,7 +184,7 @@ __device__ inline void render_symbolic(int l, uint32_t* e, int mvx, int mvy, int
 
 // Pixel observation of one environment by a whole block (256 threads): 63x63x3 floats.
 // Each texel is one table value times the daylight value (a single IEEE multiply).
-__device__ inline void render_pixels_block(const uint32_t* __restrict__ rec, const uint8_t* __restrict__ map,
+__device__ __forceinline__ void render_pixels_block(const uint32_t* __restrict__ rec, const uint8_t* __restrict__ map,
                                            const Luts* __restrict__ luts, float* __restrict__ out,
                                            int* s_tile /* 81 */, int* s_ent /* 81 */)
 {

@@ -31,7 +31,7 @@ struct StepOut { bool done; float reward; int mvx, mvy, woff; };
 // l, l+G, ... of the 36 (four per window row).  A dword never straddles a map tile, and the
 // whole window lies in at most four tiles (cache lines).
 template <int G>
-__device__ inline void load_window(int l, int px, int py, const uint8_t* __restrict__ map, uint32_t* win)
+__device__ __forceinline__ void load_window(int l, int px, int py, const uint8_t* __restrict__ map, uint32_t* win)
 {
     constexpr int NIT = (WIN_DWORDS + G - 1) / G;
     const int xa = (px - WIN_COLS / 2) & ~3, y0 = py - WIN_ROWS / 2;
@@ -78,7 +78,7 @@ constexpr uint32_t MAKE_ACH = ACH_MAKE_WOOD_PICKAXE | (ACH_MAKE_STONE_PICKAXE <<
 // updated (unless the episode ended) and the window patched with this step's map edits;
 // (mvx, mvy) is how far the player moved, i.e. where the view sits inside the window.
 template <int G>
-__device__ inline StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __restrict__ map,
+__device__ __forceinline__ StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __restrict__ map,
                                    const Luts* __restrict__ luts, int action, const Params& p)
 {
     using Gr = Grp<G>;
