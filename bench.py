@@ -149,14 +149,14 @@ def copy_ceiling_gbs(mib: int = 1024, repeats: int = 10) -> float:
     return 2.0 * (mib << 20) * repeats / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
-def cpu_baseline(n_sample: int, steps: int, kind: str, variant: str = "classic"):
+def cpu_baseline(n_sample: int, steps: int, kind: str, variant: str = "classic", pixels: bool = False):
     """The CPU oracle, as it stands, on the first n_sample environments of the same workload."""
     from oracle import pyoracle as po
     from paper_2402_16801_amd import synth
 
     if variant == "craftax":
         acts = synth.action_block(n_sample, steps, kind, 0, n_actions=43)
-        orc = po.FullOracle(n_sample, po.full_default_config(), po.FULL_OBS_U8_F32)
+        orc = po.FullOracle(n_sample, po.full_default_config(), po.FULL_OBS_PIXELS_F32 if pixels else po.FULL_OBS_U8_F32)
     else:
         acts = synth.action_block(n_sample, steps, kind, 0)
         orc = po.Oracle(n_sample, po.default_config(max_episode_steps=10000), po.OBS_SYM_U8_F32)
@@ -167,7 +167,7 @@ def cpu_baseline(n_sample: int, steps: int, kind: str, variant: str = "classic")
     dt = time.perf_counter() - t0
     return {"value": n_sample * steps / dt, "unit": "env_steps/s", "cores": 1, "kind": "oracle",
             "sample": f"first {n_sample} envs x {steps} steps of the same workload, single thread, "
-                      f"including the symbolic observation ({dt:.1f} s)"}
+                      f"including the {'pixel' if pixels else 'symbolic'} observation ({dt:.1f} s)"}
 
 
 def main():
@@ -290,6 +290,7 @@ def craftax_pixels_line(args) -> dict:
             "avg_launch_us": run["draw_s"] * 1e6,
             "measured_copy_gbs": copy_ceiling_gbs(),
         },
+        **({} if args.no_cpu_baseline else {"cpu_baseline": cpu_baseline(64, 40, kind, variant="craftax", pixels=True)}),
     }
 
 
