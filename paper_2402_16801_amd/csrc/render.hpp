@@ -184,37 +184,100 @@ __device__ __forceinline__ void render_symbolic(int l, uint32_t* e, int mvx, int
 
 // Pixel observation of one environment by a whole block (256 threads): 63x63x3 floats.
 // Each texel is one table value times the daylight value (a single IEEE multiply).
+// The picture is walked in linear pixel order, 1024 pixels per block iteration, 256 per wave:
+// every lane fetches the three texels of four pixels (the atlas stays in cache), scales them and
+// parks them in a wave-private LDS strip, from which every lane writes three aligned 16-byte
+// pieces; 12-byte stores at a 12-byte lane stride reach only half the write bandwidth.  The
+// fetches of the next group are issued before the stores of the current one.
+constexpr int PIX_SIDE = 63, PIX_TILE = 7, PIX_TILE_FLOATS = PIX_TILE * PIX_TILE * 3, PIX_VIEW = 9;
+constexpr int PIX_GROUP = 1024, PIX_WAVE = 256, PIX_WAVE_FLOATS = PIX_WAVE * 3;
+constexpr int PIX_FULL_GROUPS = OBS_STRIDE_PIXELS / 12 / PIX_GROUP;   // 3 whole groups, then a partial one
+static_assert((PIX_FULL_GROUPS + 1) * PIX_GROUP * 12 >= OBS_STRIDE_PIXELS && PIX_FULL_GROUPS * PIX_GROUP <= PIX_SIDE * PIX_SIDE, "pixel groups");
+
+// s_tile, s_ent: 81 ints each; s_strip: 4 * 768 floats, 16-byte aligned.  Writes the whole stride
+// (the padding after the picture as zero).
 __device__ __forceinline__ void render_pixels_block(const uint32_t* __restrict__ rec, const uint8_t* __restrict__ map,
-                                           const Luts* __restrict__ luts, float* __restrict__ out,
-                                           int* s_tile /* 81 */, int* s_ent /* 81 */)
+                                                    const Luts* __restrict__ luts, uint8_t* __restrict__ obs_out,
+                                                    int* s_tile, int* s_ent, float* s_strip)
 {
     const int tid = threadIdx.x;
     const uint32_t w_pos = rec[RW_POS];
     const int px = w_pos & 0xFF, py = (w_pos >> 8) & 0xFF;
-    if (tid < 81) {
-        const int tr = tid / 9, tc = tid - tr * 9;
-        const int x = px + tc - 4, y = py + tr - 4;
+    if (tid < PIX_VIEW * PIX_VIEW) {
+        const int tr = tid / PIX_VIEW, tc = tid - tr * PIX_VIEW;
+        const int x = px + tc - PIX_VIEW / 2, y = py + tr - PIX_VIEW / 2;
         s_tile[tid] = in_map(x, y) ? (int)map[map_index(x, y)] : (int)BK_OOB;
-        s_ent[tid] = (tid == 40) ? 0 : -1;
+        s_ent[tid] = (tid == PIX_VIEW * PIX_VIEW / 2) ? 0 : -1;
     }
     __syncthreads();
     if (tid < NMOB) {
         const Mob m = unpack_mob(rec[RW_MOB + tid]);
-        const int tc = m.x - px + 4, tr = m.y - py + 4;
-        if (m.alive && (unsigned)tc < 9u && (unsigned)tr < 9u) s_ent[tr * 9 + tc] = 1 + tid / 3;
+        const int tc = m.x - px + PIX_VIEW / 2, tr = m.y - py + PIX_VIEW / 2;
+        if (m.alive && (unsigned)tc < (unsigned)PIX_VIEW && (unsigned)tr < (unsigned)PIX_VIEW) s_ent[tr * PIX_VIEW + tc] = 1 + tid / 3;
     }
     __syncthreads();
     const float light = luts->daylight[rec[RW_VIT] >> 16];
-    for (int i = tid; i < 63 * 63 * 3; i += 256) {
-        const int ch = i % 3, pix = i / 3;
-        const int gx = pix % 63, gy = pix / 63;
-        const int tc = gx / 7, tr = gy / 7, ix = gx - tc * 7, iy = gy - tr * 7;
-        const int tile = s_tile[tr * 9 + tc], ent = s_ent[tr * 9 + tc];
-        const int in_tile = (iy * 7 + ix) * 3 + ch;
-        float texel = luts->tile[(tile - 1) * 147 + in_tile];
-        if (ent >= 0 && luts->ent_mask[ent * 49 + iy * 7 + ix]) texel = luts->ent[ent * 147 + in_tile];
-        out[i] = texel * light;
+    float4* out = reinterpret_cast<float4*>(obs_out);
+    const int w = tid >> 6, l = tid & 63;
+    float* strip = s_strip + w * PIX_WAVE_FLOATS;
+    float v[4][3], scale[4];
+    auto fetch = [&](int g) {
+        const int p0 = g * PIX_GROUP + w * PIX_WAVE + l;
+        int y = p0 / PIX_SIDE, x = p0 - y * PIX_SIDE;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            // pixels beyond the picture (the stride's padding) read texel 0 at scale 0
+            const bool valid = y < PIX_SIDE;
+            const int yy = valid ? y : 0;
+            const int tr = yy / PIX_TILE, iy = yy - tr * PIX_TILE, tc = x / PIX_TILE, ix = x - tc * PIX_TILE;
+            const int tile = s_tile[tr * PIX_VIEW + tc], ent = s_ent[tr * PIX_VIEW + tc];
+            const int in_tile = (iy * PIX_TILE + ix) * 3;
+            const float* src = luts->tile + (tile - 1) * PIX_TILE_FLOATS + in_tile;
+            if (ent >= 0 && luts->ent_mask[ent * (PIX_TILE * PIX_TILE) + iy * PIX_TILE + ix]) src = luts->ent + ent * PIX_TILE_FLOATS + in_tile;
+            v[u][0] = src[0]; v[u][1] = src[1]; v[u][2] = src[2];
+            scale[u] = valid ? light : 0.0f;
+            x += 64;
+            if (x >= PIX_SIDE) { x -= PIX_SIDE; ++y; }
+            if (x >= PIX_SIDE) { x -= PIX_SIDE; ++y; }            // 64 pixels on is one row and one pixel further
+        }
+    };
+    float4 piece[3];
+    auto turn = [&]() {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            strip[u * 192 + l * 3] = v[u][0] * scale[u];
+            strip[u * 192 + l * 3 + 1] = v[u][1] * scale[u];
+            strip[u * 192 + l * 3 + 2] = v[u][2] * scale[u];
+        }
+        group_sync();
+#pragma unroll
+        for (int k = 0; k < 3; ++k) piece[k] = *reinterpret_cast<const float4*>(strip + (k * 64 + l) * 4);
+        group_sync();
+    };
+    auto store = [&](int g, bool guarded) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            const int q = (g * PIX_GROUP + w * PIX_WAVE) * 3 / 4 + k * 64 + l;
+            if (!guarded || q < OBS_STRIDE_PIXELS / 16) {
+                __builtin_nontemporal_store(piece[k].x, &out[q].x);
+                __builtin_nontemporal_store(piece[k].y, &out[q].y);
+                __builtin_nontemporal_store(piece[k].z, &out[q].z);
+                __builtin_nontemporal_store(piece[k].w, &out[q].w);
+            }
+        }
+    };
+    fetch(0);
+    turn();
+    fetch(1);
+    store(0, false);
+#pragma unroll 1
+    for (int g = 1; g < PIX_FULL_GROUPS; ++g) {
+        turn();
+        fetch(g + 1);
+        store(g, false);
     }
+    turn();
+    store(PIX_FULL_GROUPS, true);
 }
 
 }  // namespace cx
