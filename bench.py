@@ -131,6 +131,32 @@ def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, varian
             "draw_s": draw_s}
 
 
+def rollout_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3):
+    """craftax_rollout: the same steps, actions and outputs as `steps` craftax_step calls, in one launch."""
+    import torch
+    from paper_2402_16801_amd import binding as cx, synth
+
+    cfg = cx.default_config(obs_mode=cx.OBS_SYM_U8_F32, max_episode_steps=10000)
+    sim = cx.Craftax(n, cfg)
+    sim.reset(synth.seeds_for(n))
+    total = warmup + repeats * steps
+    actions = torch.empty((total, n), dtype=torch.int32, device=sim.device)
+    cx.craftax_synth_actions(actions, n, 0, total, 0, {"uniform": 0, "skewed": 1}[kind], sim.stream)
+    reward = torch.zeros((steps, n), dtype=torch.float32, device=sim.device)
+    done = torch.zeros((steps, n), dtype=torch.uint8, device=sim.device)
+    cx.craftax_rollout(sim.state, actions[:warmup], warmup, sim.obs, reward[:warmup], done[:warmup], n, sim.stream)
+    torch.cuda.synchronize()
+    wall = []
+    for r in range(repeats):
+        a = actions[warmup + r * steps: warmup + (r + 1) * steps]
+        t0 = time.perf_counter()
+        cx.craftax_rollout(sim.state, a, steps, sim.obs, reward, done, n, sim.stream)
+        torch.cuda.synchronize()
+        wall.append(time.perf_counter() - t0)
+    sim.close()
+    return sorted(wall)[len(wall) // 2]
+
+
 def copy_ceiling_gbs(mib: int = 1024, repeats: int = 10) -> float:
     """Measured device-to-device copy rate (bytes read + bytes written per second), as context
     for the nominal peak: a buffer larger than the last-level cache, copied `repeats` times."""
@@ -254,6 +280,11 @@ def main():
         small = gpu_run(4096, K, W, "uniform")
         out["also"] = {"workload": "configs[1]: 4096 envs, uniform actions", "value": 4096 * K / small["wall_s"],
                        "unit": "env_steps/s", "ms_per_step": small["wall_s"] / K * 1e3}
+        roll = rollout_run(n, K, W, args.kind)
+        out["also_rollout"] = {"workload": f"the same {n} environments and action stream through craftax_rollout: {K} steps per launch, "
+                                           "observation written after every step, reward and done of every step kept",
+                               "value": n * K / roll, "unit": "env_steps/s", "ms_per_step": roll / K * 1e3,
+                               "roofline_frac": alg["total"] * n / (roll / K) / 1e9 / HBM_PEAK_GBS}
         full = craftax_line(args, with_cpu=False)
         out["also_craftax"] = {"workload": full["config"]["workload"], "value": full["value"], "unit": "env_steps/s",
                                "ms_per_step": full["ms_per_step"], "roofline": full["roofline"]}

@@ -207,6 +207,18 @@ int craftax_reset(void *state, const uint64_t *seeds, int n, void *stream);
 int craftax_step(void *state, const int32_t *actions, void *obs, float *reward, uint8_t *done,
                  int n, void *stream);
 
+/* Several steps in one launch, for callers that hold the actions of all of them (a random or
+ * scripted policy; the paper's appendix "Optimistic Environment Resets" measures such rollouts):
+ * exactly the result of `steps` calls of craftax_step with actions[t] (DEVICE int32[steps][n]),
+ * with reward and done of every step (DEVICE float[steps][n], uint8[steps][n]) and the observation
+ * written after every step into the same buffer obs (DEVICE, n strides; it ends up holding the
+ * observation after the last step; NULL skips rendering).  A thread block keeps its environments
+ * on chip for the whole launch and blocks advance independently.  Variant CLASSIC with a symbolic
+ * observation only (CRAFTAX_E_CONFIG otherwise).  Other errors as for craftax_step;
+ * CRAFTAX_E_COUNT also for steps <= 0. */
+int craftax_rollout(void *state, const int32_t *actions, int steps, void *obs, float *reward,
+                    uint8_t *done, int n, void *stream);
+
 /* Renders the current observation of every environment (used after craftax_reset). */
 int craftax_observe(void *state, void *obs, int n, void *stream);
 

@@ -22,7 +22,7 @@ EXPORTS = [
     "craftax_default_config", "craftax_default_config_for", "craftax_state_bytes", "craftax_obs_bytes",
     "craftax_env_dump_bytes", "craftax_env_dump_bytes_for",
     "craftax_state_init", "craftax_state_release", "craftax_reset", "craftax_step", "craftax_observe",
-    "craftax_export_envs", "craftax_import_envs", "craftax_mutate_swap", "craftax_synth_actions", "craftax_last_error",
+    "craftax_rollout", "craftax_export_envs", "craftax_import_envs", "craftax_mutate_swap", "craftax_synth_actions", "craftax_last_error",
 ]
 
 
@@ -96,6 +96,7 @@ def load() -> ctypes.CDLL:
     L.craftax_observe.argtypes = [vp, vp, i32, vp]
     L.craftax_export_envs.argtypes = [vp, i32, i32, vp, vp]
     L.craftax_import_envs.argtypes = [vp, i32, i32, vp, vp]
+    L.craftax_rollout.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp]
     L.craftax_mutate_swap.argtypes = [vp, i32, i32, u64, ctypes.c_uint32, i32, vp, vp]
     L.craftax_synth_actions.argtypes = [vp, i32, i32, i32, u64, i32, vp]
     L.craftax_last_error.argtypes = []
@@ -152,6 +153,11 @@ def craftax_reset(state, seeds, n: int, stream=None):
 def craftax_step(state, actions, obs, reward, done, n: int, stream=None):
     _check(load().craftax_step(state.data_ptr(), actions.data_ptr(), 0 if obs is None else obs.data_ptr(),
                                reward.data_ptr(), done.data_ptr(), n, _stream_ptr(stream)), "craftax_step")
+
+
+def craftax_rollout(state, actions, steps: int, obs, reward, done, n: int, stream=None):
+    _check(load().craftax_rollout(state.data_ptr(), actions.data_ptr(), steps, 0 if obs is None else obs.data_ptr(),
+                                  reward.data_ptr(), done.data_ptr(), n, _stream_ptr(stream)), "craftax_rollout")
 
 
 def craftax_observe(state, obs, n: int, stream=None):

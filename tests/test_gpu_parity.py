@@ -481,3 +481,100 @@ def test_perlin_worldgen_after_import_and_bad_mode(cx):
     assert cx.craftax_state_bytes(bad, 8) == 0
     full = cx.default_config(cx.VARIANT_CRAFTAX, worldgen=P)
     assert cx.craftax_state_bytes(full, 8) == 0
+
+
+def _rollout_case(cx, n, obs_mode, kind, pre, steps, post, seed_base=0, **cfgkw):
+    """`pre` single steps, one rollout of `steps` steps, `post` single steps; every reward and
+    done, the observation after the rollout and after every single step, and the final state
+    are compared with the oracle stepping one step at a time."""
+    import torch
+    gcfg, ocfg = _cfgs(cx, obs_mode, **cfgkw)
+    sim = _make_sim(cx, n, gcfg)
+    orc = po.Oracle(n, ocfg, obs_mode)
+    seeds = synth.seeds_for(n, seed_base)
+    sim.reset(seeds); orc.reset(seeds)
+    t = 0
+
+    def single(k):
+        nonlocal t
+        for _ in range(k):
+            a = synth.actions(np.arange(n), t, kind, 5)
+            obs, rew, done = sim.step(torch.as_tensor(a, device=sim.device))
+            oobs, orew, odone = orc.step(a)
+            assert np.array_equal(done.cpu().numpy(), odone), f"done at step {t}"
+            assert np.array_equal(rew.cpu().numpy().view(np.uint32), orew.view(np.uint32)), f"reward at step {t}"
+            assert np.array_equal(obs.cpu().numpy(), oobs), f"observation at step {t}"
+            t += 1
+
+    single(pre)
+    acts = np.stack([synth.actions(np.arange(n), t + s, kind, 5) for s in range(steps)]).astype(np.int32)
+    d_acts = torch.as_tensor(acts, device=sim.device)
+    d_rew = torch.zeros((steps, n), dtype=torch.float32, device=sim.device)
+    d_done = torch.zeros((steps, n), dtype=torch.uint8, device=sim.device)
+    cx.craftax_rollout(sim.state, d_acts, steps, sim.obs, d_rew, d_done, n, sim.stream)
+    torch.cuda.synchronize()
+    g_rew, g_done = d_rew.cpu().numpy(), d_done.cpu().numpy()
+    finished = 0
+    for s in range(steps):
+        oobs, orew, odone = orc.step(acts[s])
+        assert np.array_equal(g_done[s], odone), f"done at rollout step {s}: envs {np.nonzero(g_done[s] != odone)[0][:8]}"
+        assert np.array_equal(g_rew[s].view(np.uint32), orew.view(np.uint32)), f"reward at rollout step {s}"
+        finished += int(odone.sum())
+    t += steps
+    assert np.array_equal(sim.obs.cpu().numpy(), orc.obs), "observation after the rollout"
+    assert sim.export_envs().tobytes() == orc.envs.tobytes(), "state after the rollout"
+    single(post)
+    assert sim.export_envs().tobytes() == orc.envs.tobytes(), "state at the end"
+    sim.close()
+    return finished
+
+
+@pytest.mark.parametrize("obs_mode", [po.OBS_SYM_U8_I8, po.OBS_SYM_U8_F32, po.OBS_SYM_F32])
+def test_rollout_equals_single_steps(cx, obs_mode):
+    """craftax_rollout = that many craftax_step calls: short episodes (most spare worlds are used and
+    regenerated inside the launch), single steps before (worlds still queued when the rollout starts)
+    and after (every spare world must be in place again)."""
+    finished = _rollout_case(cx, 200, obs_mode, "skewed", pre=12, steps=120, post=25, max_episode_steps=17)
+    assert finished > 200 * 5
+
+
+def test_rollout_edge_cases(cx):
+    # episodes of one and two steps: nearly every world is generated on the spot
+    _rollout_case(cx, 70, po.OBS_SYM_U8_F32, "uniform", pre=3, steps=20, post=5, max_episode_steps=1)
+    _rollout_case(cx, 70, po.OBS_SYM_U8_F32, "uniform", pre=0, steps=25, post=5, max_episode_steps=2, seed_base=9)
+    # ragged counts, one step, long episodes (no reset at all), the paper's noise
+    _rollout_case(cx, 1, po.OBS_SYM_U8_I8, "skewed", pre=0, steps=40, post=3, max_episode_steps=9)
+    _rollout_case(cx, 65, po.OBS_SYM_U8_F32, "skewed", pre=1, steps=1, post=1)
+    _rollout_case(cx, 130, po.OBS_SYM_U8_F32, "uniform", pre=0, steps=300, post=10)
+    _rollout_case(cx, 90, po.OBS_SYM_U8_F32, "skewed", pre=5, steps=60, post=10, max_episode_steps=11, worldgen=po.WORLDGEN_PERLIN)
+
+
+def test_rollout_null_obs_and_errors(cx):
+    import torch
+    n, steps = 64, 30
+    gcfg, ocfg = _cfgs(cx, po.OBS_SYM_U8_F32, max_episode_steps=13)
+    sim = _make_sim(cx, n, gcfg)
+    orc = po.Oracle(n, ocfg)
+    seeds = synth.seeds_for(n, 4)
+    sim.reset(seeds); orc.reset(seeds)
+    acts = np.stack([synth.actions(np.arange(n), s, "uniform", 1) for s in range(steps)]).astype(np.int32)
+    d_acts = torch.as_tensor(acts, device=sim.device)
+    d_rew = torch.zeros((steps, n), dtype=torch.float32, device=sim.device)
+    d_done = torch.zeros((steps, n), dtype=torch.uint8, device=sim.device)
+    cx.craftax_rollout(sim.state, d_acts, steps, None, d_rew, d_done, n, sim.stream)     # no rendering
+    for s in range(steps):
+        orc.step(acts[s], render=False)
+    assert sim.export_envs().tobytes() == orc.envs.tobytes()
+    cx.craftax_observe(sim.state, sim.obs, n, sim.stream)
+    assert np.array_equal(sim.obs.cpu().numpy(), orc.observe())
+    with pytest.raises(cx.CraftaxError):
+        cx.craftax_rollout(sim.state, d_acts, 0, sim.obs, d_rew, d_done, n, sim.stream)
+    with pytest.raises(cx.CraftaxError):
+        cx.craftax_rollout(sim.state, d_acts, steps, sim.obs, d_rew, d_done, n + 1, sim.stream)
+    sim.close()
+    for bad in (cx.default_config(obs_mode=cx.OBS_PIXELS_F32), cx.default_config(cx.VARIANT_CRAFTAX)):
+        other = cx.Craftax(8, bad)
+        other.reset(synth.seeds_for(8))
+        with pytest.raises(cx.CraftaxError):
+            cx.craftax_rollout(other.state, d_acts, 2, None, d_rew, d_done, 8, other.stream)
+        other.close()
