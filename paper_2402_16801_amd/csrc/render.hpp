@@ -49,8 +49,9 @@ __device__ __forceinline__ uint4 staged_chunk(const uint32_t* e, int c)
 
 // Writes the staged observations of all environments of the calling wave (byte layouts).
 // Lanes regroup into runs of max(G, 8): a run writes 128 or 256 contiguous, line-aligned bytes
-// of one environment per store instruction, i.e. whole cache lines, as streaming stores (the
-// observation is not read again by this kernel).  With G = 4 a run serves two environments in
+// of one environment per store instruction, i.e. whole cache lines.  Plain stores: measured
+// against streaming (non-temporal) ones they are 5 % faster here, the observation buffer being
+// rewritten every step.  With G = 4 a run serves two environments in
 // turn.  wave_env: LDS area of the wave's first environment; wave_obs: its observation.
 template <int G, int OBS_MODE>
 __device__ __forceinline__ void flush_wave_observations(uint32_t* wave_env, uint8_t* __restrict__ wave_obs)
@@ -68,10 +69,7 @@ __device__ __forceinline__ void flush_wave_observations(uint32_t* wave_env, uint
             const int c = it * RUN + j;
             if (c >= NCHUNK) break;
             const uint4 v = staged_chunk<OBS_MODE>(e, c);
-            __builtin_nontemporal_store(v.x, out + 4 * c);
-            __builtin_nontemporal_store(v.y, out + 4 * c + 1);
-            __builtin_nontemporal_store(v.z, out + 4 * c + 2);
-            __builtin_nontemporal_store(v.w, out + 4 * c + 3);
+            *reinterpret_cast<uint4*>(out + 4 * c) = v;
         }
     }
 }
