@@ -228,6 +228,7 @@ constexpr int LDS_WIN = 32;                      // 36 dwords
 constexpr int LDS_BITS = 68;                     // 1328 bits -> 42 dwords
 constexpr int LDS_VEC = 110;                     // 24 dwords (22 scalars + padding)
 constexpr int LDS_FLAG = 134;                    // 1 = this environment's staged observation is to be written
+constexpr int LDS_WINPOS = 135;                  // rollout: bit 31 | py << 8 | px of the position the window was loaded for, or 0
 constexpr int LDS_ENV_DWORDS = 142;
 static_assert(LDS_VEC + 24 <= LDS_ENV_DWORDS, "per-environment LDS area overflows");
 

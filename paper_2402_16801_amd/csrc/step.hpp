@@ -77,7 +77,10 @@ constexpr uint32_t MAKE_ACH = ACH_MAKE_WOOD_PICKAXE | (ACH_MAKE_STONE_PICKAXE <<
 // e: the environment's LDS area (record already loaded).  Returns with the record in LDS
 // updated (unless the episode ended) and the window patched with this step's map edits;
 // (mvx, mvy) is how far the player moved, i.e. where the view sits inside the window.
-template <int G>
+// KEEP_WIN (kernels that keep an environment in LDS from step to step): the window is only loaded
+// if the one in LDS was not loaded for the player's current position; every change the step makes
+// to the map inside the window is patched into it, so a kept window equals a fresh one.
+template <int G, bool KEEP_WIN = false>
 __device__ __forceinline__ StepOut step_env(int l, uint32_t env, uint32_t* e, uint8_t* __restrict__ map,
                                    const Luts* __restrict__ luts, int action, const Params& p)
 {
@@ -91,7 +94,8 @@ __device__ __forceinline__ StepOut step_env(int l, uint32_t env, uint32_t* e, ui
     uint32_t w_inv = rec[RW_INV];    // six 4-bit counts, six tool flags from bit 24: stays packed
     const int px0 = w_pos & 0xFF, py0 = (w_pos >> 8) & 0xFF;
     int px = px0, py = py0, dir = (w_pos >> 16) & 0xFF, sleeping = (w_pos >> 24) & 0xFF;
-    load_window<G>(l, px0, py0, map, e + LDS_WIN);
+    const uint32_t win_key = 0x80000000u | (w_pos & 0xFFFFu);
+    if (!KEEP_WIN || e[LDS_WINPOS] != win_key) load_window<G>(l, px0, py0, map, e + LDS_WIN);
     // where a lane with nothing to read points its load: the player's own cell, whose cache line
     // the window load fetches anyway (any other fixed cell would cost a line of its own)
     const int idle_cell = map_index(px0, py0);
@@ -129,6 +133,7 @@ __device__ __forceinline__ StepOut step_env(int l, uint32_t env, uint32_t* e, ui
     int a = ((unsigned)action < (unsigned)AC_COUNT) ? action : (int)AC_NOOP;
     if (sleeping) a = AC_NOOP;
     group_sync();   // the window is in LDS
+    if (KEEP_WIN && l == 0) e[LDS_WINPOS] = win_key;
 
     // ---- phase 1: the player's action ----------------------------------------------------------
     bool l_table = false, l_furnace = false;
