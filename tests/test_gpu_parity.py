@@ -578,3 +578,33 @@ def test_rollout_null_obs_and_errors(cx):
         with pytest.raises(cx.CraftaxError):
             cx.craftax_rollout(other.state, d_acts, 2, None, d_rew, d_done, 8, other.stream)
         other.close()
+
+
+def test_rollout_at_scale_sampled(cx):
+    """70,000 environments (more blocks than the chip holds at once, a ragged last block), short
+    episodes; a strided sample is followed by the oracle step by step."""
+    import torch
+    n, steps = 70000, 50
+    gcfg, ocfg = _cfgs(cx, po.OBS_SYM_U8_F32, max_episode_steps=9)
+    sim = _make_sim(cx, n, gcfg)
+    ids = np.unique(np.concatenate([np.arange(0, n, 1100), [n - 1, n - 2, 65535, 65536]]))
+    orc = po.Oracle(len(ids), ocfg)
+    seeds = synth.seeds_for(n, 31)
+    sim.reset(seeds)
+    orc.reset(seeds[ids], env_ids=ids)
+    d_acts = torch.empty((steps, n), dtype=torch.int32, device=sim.device)
+    cx.craftax_synth_actions(d_acts, n, 0, steps, 3, 1, sim.stream)
+    d_rew = torch.zeros((steps, n), dtype=torch.float32, device=sim.device)
+    d_done = torch.zeros((steps, n), dtype=torch.uint8, device=sim.device)
+    cx.craftax_rollout(sim.state, d_acts, steps, sim.obs, d_rew, d_done, n, sim.stream)
+    torch.cuda.synchronize()
+    g_rew, g_done = d_rew.cpu().numpy()[:, ids], d_done.cpu().numpy()[:, ids]
+    for s in range(steps):
+        a = synth.actions(ids, s, "skewed", 3)
+        oobs, orew, odone = orc.step(a)
+        assert np.array_equal(g_done[s], odone), f"done at step {s}"
+        assert np.array_equal(g_rew[s].view(np.uint32), orew.view(np.uint32)), f"reward at step {s}"
+    assert np.array_equal(sim.obs.cpu().numpy()[ids], orc.obs)
+    dumps = np.concatenate([sim.export_envs(int(i), 1) for i in ids])
+    assert dumps.tobytes() == orc.envs.tobytes()
+    sim.close()
