@@ -283,6 +283,9 @@ def main():
         small = gpu_run(4096, K, W, "uniform")
         out["also"] = {"workload": "configs[1]: 4096 envs, uniform actions", "value": 4096 * K / small["wall_s"],
                        "unit": "env_steps/s", "ms_per_step": small["wall_s"] / K * 1e3}
+        small_roll = rollout_run(4096, K, W, "uniform")
+        out["also"]["rollout_value"] = 4096 * K / small_roll
+        out["also"]["rollout_ms_per_step"] = small_roll / K * 1e3
         roll = rollout_run(n, K, W, args.kind)
         out["also_rollout"] = {"workload": f"the same {n} environments and action stream through craftax_rollout: {K} steps per launch, "
                                            "observation written after every step, reward and done of every step kept",

@@ -483,13 +483,13 @@ def test_perlin_worldgen_after_import_and_bad_mode(cx):
     assert cx.craftax_state_bytes(full, 8) == 0
 
 
-def _rollout_case(cx, n, obs_mode, kind, pre, steps, post, seed_base=0, **cfgkw):
+def _rollout_case(cx, n, obs_mode, kind, pre, steps, post, seed_base=0, lanes=None, **cfgkw):
     """`pre` single steps, one rollout of `steps` steps, `post` single steps; every reward and
     done, the observation after the rollout and after every single step, and the final state
     are compared with the oracle stepping one step at a time."""
     import torch
     gcfg, ocfg = _cfgs(cx, obs_mode, **cfgkw)
-    sim = _make_sim(cx, n, gcfg)
+    sim = _make_sim(cx, n, gcfg, lanes)          # 4 lanes: 64 environments per block; otherwise 16 per block
     orc = po.Oracle(n, ocfg, obs_mode)
     seeds = synth.seeds_for(n, seed_base)
     sim.reset(seeds); orc.reset(seeds)
@@ -529,24 +529,27 @@ def _rollout_case(cx, n, obs_mode, kind, pre, steps, post, seed_base=0, **cfgkw)
     return finished
 
 
+@pytest.mark.parametrize("lanes", [4, 16])
 @pytest.mark.parametrize("obs_mode", [po.OBS_SYM_U8_I8, po.OBS_SYM_U8_F32, po.OBS_SYM_F32])
-def test_rollout_equals_single_steps(cx, obs_mode):
+def test_rollout_equals_single_steps(cx, obs_mode, lanes):
     """craftax_rollout = that many craftax_step calls: short episodes (most spare worlds are used and
     regenerated inside the launch), single steps before (worlds still queued when the rollout starts)
     and after (every spare world must be in place again)."""
-    finished = _rollout_case(cx, 200, obs_mode, "skewed", pre=12, steps=120, post=25, max_episode_steps=17)
+    finished = _rollout_case(cx, 200, obs_mode, "skewed", pre=12, steps=120, post=25, max_episode_steps=17, lanes=lanes)
     assert finished > 200 * 5
 
 
-def test_rollout_edge_cases(cx):
+@pytest.mark.parametrize("lanes", [4, 16])
+def test_rollout_edge_cases(cx, lanes):
     # episodes of one and two steps: nearly every world is generated on the spot
-    _rollout_case(cx, 70, po.OBS_SYM_U8_F32, "uniform", pre=3, steps=20, post=5, max_episode_steps=1)
-    _rollout_case(cx, 70, po.OBS_SYM_U8_F32, "uniform", pre=0, steps=25, post=5, max_episode_steps=2, seed_base=9)
+    _rollout_case(cx, 70, po.OBS_SYM_U8_F32, "uniform", pre=3, steps=20, post=5, max_episode_steps=1, lanes=lanes)
+    _rollout_case(cx, 70, po.OBS_SYM_U8_F32, "uniform", pre=0, steps=25, post=5, max_episode_steps=2, seed_base=9, lanes=lanes)
     # ragged counts, one step, long episodes (no reset at all), the paper's noise
-    _rollout_case(cx, 1, po.OBS_SYM_U8_I8, "skewed", pre=0, steps=40, post=3, max_episode_steps=9)
-    _rollout_case(cx, 65, po.OBS_SYM_U8_F32, "skewed", pre=1, steps=1, post=1)
-    _rollout_case(cx, 130, po.OBS_SYM_U8_F32, "uniform", pre=0, steps=300, post=10)
-    _rollout_case(cx, 90, po.OBS_SYM_U8_F32, "skewed", pre=5, steps=60, post=10, max_episode_steps=11, worldgen=po.WORLDGEN_PERLIN)
+    _rollout_case(cx, 1, po.OBS_SYM_U8_I8, "skewed", pre=0, steps=40, post=3, max_episode_steps=9, lanes=lanes)
+    _rollout_case(cx, 65, po.OBS_SYM_U8_F32, "skewed", pre=1, steps=1, post=1, lanes=lanes)
+    _rollout_case(cx, 130, po.OBS_SYM_U8_F32, "uniform", pre=0, steps=300, post=10, lanes=lanes)
+    _rollout_case(cx, 90, po.OBS_SYM_U8_F32, "skewed", pre=5, steps=60, post=10, max_episode_steps=11, worldgen=po.WORLDGEN_PERLIN,
+                  lanes=lanes)
 
 
 def test_rollout_null_obs_and_errors(cx):
