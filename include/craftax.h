@@ -213,8 +213,8 @@ int craftax_step(void *state, const int32_t *actions, void *obs, float *reward, 
  * with reward and done of every step (DEVICE float[steps][n], uint8[steps][n]) and the observation
  * written after every step into the same buffer obs (DEVICE, n strides; it ends up holding the
  * observation after the last step; NULL skips rendering).  A thread block keeps its environments
- * on chip for the whole launch and blocks advance independently.  Variant CLASSIC with a symbolic
- * observation only (CRAFTAX_E_CONFIG otherwise).  Other errors as for craftax_step;
+ * on chip for the whole launch and blocks advance independently.  Both variants, symbolic
+ * observations only (CRAFTAX_E_CONFIG for a pixel mode).  Other errors as for craftax_step;
  * CRAFTAX_E_COUNT also for steps <= 0. */
 int craftax_rollout(void *state, const int32_t *actions, int steps, void *obs, float *reward,
                     uint8_t *done, int n, void *stream);

@@ -202,6 +202,145 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
     la::append_block_entries(ls, seq, s_list, nd, &s_base);
 }
 
+// ---------------------------------------------------------------------------------------------
+// rollout: several steps in one launch (see craftax_rollout).  A block keeps the records of its
+// four environments in LDS for the whole launch, every wavefront walks its environment through
+// the steps, and the block meets at a barrier once per step.  When episodes end in a step, the
+// whole block generates their next worlds on the spot, floor by floor (the other environments of
+// the block wait those few dozen microseconds; nothing is exchanged between blocks, so blocks
+// drift apart and the memory traffic of some overlaps the arithmetic of others).  At the end the
+// block writes the records back and generates, for every environment whose episode changed, the
+// spare world that the step kernel expects, tagged as written by launch 0.  Before the launch the
+// regeneration lists of the step kernel must be empty (the host runs a list-only launch first).
+template <bool F32>
+__global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
+                                                       const Luts* __restrict__ luts, const int32_t* __restrict__ actions,
+                                                       uint8_t* __restrict__ obs, float* __restrict__ reward,
+                                                       uint8_t* __restrict__ done, uint2* __restrict__ tags, Params p, int steps)
+{
+    __shared__ uint32_t s_env[ENVS_PER_BLOCK * L_ENV_DWORDS];
+    __shared__ uint16_t s_lat[LAT_TOTAL];
+    __shared__ GenLayout s_layout;
+    __shared__ uint32_t s_words[FLOORS + 1];
+    __shared__ int s_ended[ENVS_PER_BLOCK];          // this step ended the episode of environment w
+    __shared__ uint32_t s_first_ep[ENVS_PER_BLOCK];  // episode at the start of the launch, if its spare world was complete
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+    const int env = blockIdx.x * ENVS_PER_BLOCK + w;
+    const bool active = env < p.n;
+    uint32_t* e = s_env + w * L_ENV_DWORDS;
+    uint32_t* genv = envs + (size_t)(active ? env : 0) * ENV_DWORDS;
+    if (active) e[L_REC + l] = genv[l];
+    if (l == 0) { s_ended[w] = 0; s_first_ep[w] = 0xFFFFFFFFu; }
+    __syncthreads();
+    if (active) {
+        const uint32_t ep = uniu(e[L_REC + R_EPISODE]);
+        uint2 tag = make_uint2(0u, 0u);
+        if (l < NTAG) tag = tags[(size_t)env * NTAG + l];
+        constexpr uint64_t ALL = (1ull << NTAG) - 1ull;
+        const bool complete = (__ballot(l < NTAG && tag.x == ep + 1u) & ALL) == ALL;
+        if (l == 0 && complete) s_first_ep[w] = ep;
+    }
+
+    // Generates the world of episode `ep` of block-local environment ww into its map slot, all threads
+    // of the block; leaves the ten layout words in s_words.  start: drop the cells around the start
+    // position into that environment's LDS windows.
+    auto generate = [&](int ww, uint32_t ep, bool start) __attribute__((always_inline)) {
+        uint32_t* ew = s_env + ww * L_ENV_DWORDS;
+        const uint32_t wenv = (uint32_t)(blockIdx.x * ENVS_PER_BLOCK + ww), lo = ew[L_REC + R_SEED_LO], hi = ew[L_REC + R_SEED_HI];
+        uint8_t* slot = maps + map_offset(wenv, ep);
+#pragma unroll 1
+        for (int unit = 0; unit < NTAG; ++unit) {
+            const int f = unit / FLOOR_PARTS, part = unit % FLOOR_PARTS;
+            worldgen_floor_block<BLOCK>(slot, s_lat, s_layout, lo, hi, wenv, ep, f,
+                                        start ? reinterpret_cast<uint8_t*>(ew + L_WB) : nullptr,
+                                        start ? reinterpret_cast<uint8_t*>(ew + L_WI) : nullptr,
+                                        part * (GEN_THREADS / FLOOR_PARTS), GEN_THREADS / FLOOR_PARTS);
+            if (unit == FLOOR_PARTS - 1) {            // floor 0 is complete: its layout describes the whole world
+                if (tid < FLOORS + 1) s_words[tid] = layout_word(s_layout, tid);
+                __syncthreads();
+            }
+        }
+    };
+
+#pragma unroll 1
+    for (int t = 0; t < steps; ++t) {
+        // Everything a lane derives from its index is derived again in every turn: the compiler would
+        // otherwise keep dozens of such values alive across the whole loop and spill them.
+        int tid_t = threadIdx.x;
+        uint8_t* obs_t = obs;
+        asm volatile("" : "+v"(tid_t));
+        asm volatile("" : "+s"(obs_t));
+        const int tid = tid_t, w = tid >> 6, l = tid & 63;
+        const int env = blockIdx.x * ENVS_PER_BLOCK + w;
+        const bool active = env < p.n;
+        uint32_t* e = s_env + w * L_ENV_DWORDS;
+        uint32_t* genv = envs + (size_t)(active ? env : 0) * ENV_DWORDS;
+        uint8_t* obs = obs_t;
+        MobRegs m;
+        clear_mob(m);
+        StepOut o;
+        o.done = false; o.reward = 0.0f; o.wx0 = 0; o.wy0 = 0;
+        int floor_now = 0;
+        if (active) {
+            const int action = uni(actions[(size_t)t * p.n + env]);
+            const uint32_t ep = uniu(e[L_REC + R_EPISODE]);
+            uint32_t qw;
+            Player P;
+            o = step_env(l, (uint32_t)env, e, genv, maps + map_offset((uint32_t)env, ep), luts, action, p, m, qw, P, []() {});
+            if (l == 0) { reward[(size_t)t * p.n + env] = o.reward; done[(size_t)t * p.n + env] = o.done ? 1 : 0; }
+            floor_now = P.floor;
+            if (!o.done) {
+                if (l == 0) pack_player(e + L_REC, P);
+                if (l < NPLANT) e[L_REC + R_PLANT + l] = qw;
+                wave_sync();
+            } else if (l == 0) s_ended[w] = 1;
+        }
+        __syncthreads();
+        // the worlds of the episodes that start now
+#pragma unroll 1
+        for (int ww = 0; ww < ENVS_PER_BLOCK; ++ww) {
+            if (!s_ended[ww]) continue;
+            uint32_t* ew = s_env + ww * L_ENV_DWORDS;
+            const uint32_t ep1 = ew[L_REC + R_EPISODE] + 1u, lo = ew[L_REC + R_SEED_LO], hi = ew[L_REC + R_SEED_HI];
+            uint32_t* wgenv = envs + (size_t)(blockIdx.x * ENVS_PER_BLOCK + ww) * ENV_DWORDS;
+            __syncthreads();
+            generate(ww, ep1, true);
+            // fresh record in LDS, empty mob tables in memory
+            if (tid < REC_DWORDS) ew[L_REC + tid] = fresh_record_word(tid, s_words, lo, hi, ep1);
+            if (tid < FLOORS * MOBTAB_DWORDS) wgenv[REC_DWORDS + tid] = 0u;
+            __syncthreads();
+        }
+        if (active) {
+            if (o.done) {
+                clear_mob(m);
+                floor_now = 0;
+                o.wx0 = W / 2 - WIN_COLS / 2; o.wy0 = W / 2 - WIN_ROWS / 2;
+                if (l == 0) s_ended[w] = 0;
+            }
+            if (l < MOBTAB_DWORDS) genv[REC_DWORDS + floor_now * MOBTAB_DWORDS + l] = l < NSLOT ? pack_regs(m) : 0u;
+            if (obs != nullptr)
+                render_env<F32>(l, e, o.wx0, o.wy0, m.alive, m.x, m.y, m.type, luts, obs + (size_t)env * (F32 ? STRIDE_F32 : STRIDE_U8));
+        }
+        __syncthreads();
+    }
+    // records back; spare worlds for the step kernel
+    if (active) genv[l] = e[L_REC + l];
+#pragma unroll 1
+    for (int ww = 0; ww < ENVS_PER_BLOCK; ++ww) {
+        const int wenv = blockIdx.x * ENVS_PER_BLOCK + ww;
+        if (wenv >= p.n) continue;
+        uint32_t* ew = s_env + ww * L_ENV_DWORDS;
+        const uint32_t ep = ew[L_REC + R_EPISODE];
+        if (s_first_ep[ww] == ep) continue;                       // its spare world is still the right one
+        __syncthreads();
+        generate(ww, ep + 1u, false);
+        uint32_t* wgenv = envs + (size_t)wenv * ENV_DWORDS;
+        if (tid < FLOORS + 1) wgenv[SPARE_LADDER + tid] = s_words[tid];
+        if (tid < NTAG) tags[(size_t)wenv * NTAG + tid] = make_uint2(ep + 1u, 0u);
+        __syncthreads();
+    }
+}
+
 // Serves the slow list: generates the world of the new episode in place (nine blocks each, looping
 // if the list is longer than the grid); the block of floor 0 writes the fresh record, renders the
 // first observation and asks the next step launch for the world after it.  Runs after the step
@@ -608,6 +747,27 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
         if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls);
     }
     return check_launch("craftax_step", err);
+}
+
+int rollout(void* state, const craftax_config* cfg, int n, const int32_t* actions, int steps, void* obs, float* reward, uint8_t* done,
+            void* stream, std::string* err)
+{
+    if (cfg->obs_mode == CRAFTAX_OBS_PIXELS_F32) { *err = "craftax_rollout needs a symbolic observation"; return CRAFTAX_E_CONFIG; }
+    const Ptrs q = pointers(state, make_header(cfg, n));
+    const Params p = make_params(cfg, n);
+    hipStream_t st = (hipStream_t)stream;
+    uint8_t* o = static_cast<uint8_t*>(obs);
+    const int unit = NSUB * NTAG;
+    const int want = NTAG * n < REGEN_BLOCKS ? NTAG * n : REGEN_BLOCKS;
+    const dim3 drain((unsigned)((want + unit - 1) / unit * unit)), grid((unsigned)((n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK));
+    // a launch of regeneration blocks only empties the lists of the step kernel and completes every spare world
+    hipLaunchKernelGGL(kf_step<false>, drain, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, (const int32_t*)nullptr, (uint8_t*)nullptr,
+                       (float*)nullptr, (uint8_t*)nullptr, q.ls, p, 0);
+    if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32)
+        hipLaunchKernelGGL(kf_rollout<true>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls.tags, p, steps);
+    else
+        hipLaunchKernelGGL(kf_rollout<false>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls.tags, p, steps);
+    return check_launch("craftax_rollout", err);
 }
 
 int observe(void* state, const craftax_config* cfg, int n, void* obs, void* stream, std::string* err)

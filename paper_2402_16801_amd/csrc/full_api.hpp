@@ -19,6 +19,8 @@ int state_init(void* state, const craftax_config* cfg, int n, void* stream, std:
 int reset(void* state, const craftax_config* cfg, int n, const uint64_t* seeds, void* stream, std::string* err);
 int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, void* obs, float* reward, uint8_t* done,
          void* stream, std::string* err);
+int rollout(void* state, const craftax_config* cfg, int n, const int32_t* actions, int steps, void* obs, float* reward, uint8_t* done,
+            void* stream, std::string* err);
 int observe(void* state, const craftax_config* cfg, int n, void* obs, void* stream, std::string* err);
 int export_envs(const void* state, const craftax_config* cfg, int n, int first, int count, void* dumps, void* stream, std::string* err);
 int import_envs(void* state, const craftax_config* cfg, int n, int first, int count, const void* dumps, void* stream, std::string* err);

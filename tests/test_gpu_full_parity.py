@@ -415,3 +415,102 @@ def test_full_swap_mutation_matches_the_oracle(cx, restricted):
         assert np.array_equal(obs.cpu().numpy(), oobs) and np.array_equal(done.cpu().numpy(), odone)
     compare_state(sim, orc, np.arange(n), "play after mutation")
     sim.close()
+
+
+def _rollout_full(cx, n, obs_mode, kind, pre, steps, post, seed_base=0, prep=None, **cfgkw):
+    """`pre` single steps, one craftax_rollout of `steps` steps, `post` single steps, against the
+    oracle stepping one step at a time: every reward and done, the observation after the rollout
+    and after every single step, the state after the rollout and at the end."""
+    import torch
+    gcfg, ocfg = _cfgs(cx, obs_mode, **cfgkw)
+    sim = cx.Craftax(n, gcfg)
+    orc = po.FullOracle(n, ocfg, ORACLE_MODE[obs_mode])
+    seeds = synth.seeds_for(n, seed_base)
+    sim.reset(seeds); orc.reset(seeds)
+    ids = np.arange(n)
+    if prep is not None:
+        prep(orc.envs)
+        sim.import_envs(orc.envs)
+    t = 0
+
+    def single(k):
+        nonlocal t
+        for _ in range(k):
+            a = synth.actions(ids, t, kind, 7, 43)
+            obs, rew, done = sim.step(torch.as_tensor(a, device=sim.device))
+            oobs, orew, odone = orc.step(a)
+            assert np.array_equal(done.cpu().numpy(), odone), f"done at step {t}"
+            assert np.array_equal(rew.cpu().numpy().view(np.uint32), orew.view(np.uint32)), f"reward at step {t}"
+            assert np.array_equal(obs.cpu().numpy(), oobs), f"observation at step {t}"
+            t += 1
+
+    single(pre)
+    acts = np.stack([synth.actions(ids, t + s, kind, 7, 43) for s in range(steps)]).astype(np.int32)
+    d_acts = torch.as_tensor(acts, device=sim.device)
+    d_rew = torch.zeros((steps, n), dtype=torch.float32, device=sim.device)
+    d_done = torch.zeros((steps, n), dtype=torch.uint8, device=sim.device)
+    cx.craftax_rollout(sim.state, d_acts, steps, sim.obs, d_rew, d_done, n, sim.stream)
+    torch.cuda.synchronize()
+    g_rew, g_done = d_rew.cpu().numpy(), d_done.cpu().numpy()
+    finished = 0
+    for s in range(steps):
+        oobs, orew, odone = orc.step(acts[s], render=(s == steps - 1))
+        assert np.array_equal(g_done[s], odone), f"done at rollout step {s}: envs {np.nonzero(g_done[s] != odone)[0][:8]}"
+        assert np.array_equal(g_rew[s].view(np.uint32), orew.view(np.uint32)), f"reward at rollout step {s}"
+        finished += int(odone.sum())
+    t += steps
+    assert np.array_equal(sim.obs.cpu().numpy(), oobs), "observation after the rollout"
+    compare_state(sim, orc, ids, "the end of the rollout")
+    single(post)
+    compare_state(sim, orc, ids, "the end")
+    sim.close()
+    return finished
+
+
+@pytest.mark.parametrize("obs_mode", [1, 2])
+def test_rollout_equals_single_steps(cx, obs_mode):
+    """craftax_rollout = that many craftax_step calls.  Short episodes, so that most worlds are
+    generated inside the launch; single steps before it (spare worlds still queued when the rollout
+    starts) and after it (every spare world must be in place again, with its tags)."""
+    finished = _rollout_full(cx, 70, obs_mode, "skewed", pre=9, steps=60, post=14, max_episode_steps=13)
+    assert finished > 70 * 3
+
+
+def test_rollout_rich_scenes(cx):
+    """all nine floors, gear and spells: the rules behind the ladders inside a rollout"""
+    _rollout_full(cx, 90, 1, "uniform", pre=2, steps=150, post=10, prep=rich_scene)
+
+
+def test_rollout_edge_cases(cx):
+    # episodes of one and two steps, a single environment, a single step, a ragged last block
+    _rollout_full(cx, 10, 1, "uniform", pre=2, steps=6, post=3, max_episode_steps=1)
+    _rollout_full(cx, 9, 1, "uniform", pre=0, steps=9, post=3, max_episode_steps=2, seed_base=5)
+    _rollout_full(cx, 1, 2, "skewed", pre=0, steps=30, post=2, max_episode_steps=8)
+    _rollout_full(cx, 5, 1, "skewed", pre=1, steps=1, post=1)
+    _rollout_full(cx, 131, 1, "uniform", pre=0, steps=200, post=5)
+
+
+def test_rollout_without_observation_and_pixels_refused(cx):
+    import torch
+    n, steps = 12, 20
+    gcfg, ocfg = _cfgs(cx, 1, max_episode_steps=7)
+    sim = cx.Craftax(n, gcfg)
+    orc = po.FullOracle(n, ocfg, ORACLE_MODE[1])
+    seeds = synth.seeds_for(n, 2)
+    sim.reset(seeds); orc.reset(seeds)
+    acts = np.stack([synth.actions(np.arange(n), s, "uniform", 1, 43) for s in range(steps)]).astype(np.int32)
+    d_acts = torch.as_tensor(acts, device=sim.device)
+    d_rew = torch.zeros((steps, n), dtype=torch.float32, device=sim.device)
+    d_done = torch.zeros((steps, n), dtype=torch.uint8, device=sim.device)
+    cx.craftax_rollout(sim.state, d_acts, steps, None, d_rew, d_done, n, sim.stream)
+    for s in range(steps):
+        orc.step(acts[s], render=False)
+    compare_state(sim, orc, np.arange(n), "a rollout without rendering")
+    cx.craftax_observe(sim.state, sim.obs, n, sim.stream)
+    assert np.array_equal(sim.obs.cpu().numpy(), orc.observe())
+    sim.close()
+    pix = cx.Craftax(4, cx.default_config(cx.VARIANT_CRAFTAX, obs_mode=cx.OBS_PIXELS_F32))
+    pix.reset(synth.seeds_for(4))
+    with pytest.raises(cx.CraftaxError):
+        cx.craftax_rollout(pix.state, d_acts, 2, None, d_rew, d_done, 4, pix.stream)
+    pix.close()
