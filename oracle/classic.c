@@ -283,11 +283,30 @@ void orc_worldgen(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode)
 /* mode ORC_WORLDGEN_VALUE: the fields are value noise; ORC_WORLDGEN_PERLIN: the same lattices read
  * as gradient angles, the fields are Perlin noise.  Everything else (field mix, thresholds, start
  * area) is shared. */
+static void worldgen_fields(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode, uint32_t mode, const uint16_t *theta);
+
 void orc_worldgen_mode(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode, uint32_t mode)
+{
+    worldgen_fields(map, seed, env, episode, mode, NULL);
+}
+
+/* The level of the UED experiments (section "Craftax-1B: UED", noise mutation): the angle of every
+ * Perlin gradient.  theta[i], in 1024ths of a turn, is added to the angle that lattice number i
+ * stands for (order: the two spacing-16 lattices, then the four spacing-8 ones, row by row). */
+void orc_worldgen_theta(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode, const uint16_t *theta)
+{
+    worldgen_fields(map, seed, env, episode, ORC_WORLDGEN_PERLIN, theta);
+}
+
+static void worldgen_fields(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode, uint32_t mode, const uint16_t *theta)
 {
     uint32_t (*noise)(const uint16_t *, int, int, int, int) = mode == ORC_WORLDGEN_PERLIN ? orc_perlin_noise : orc_value_noise;
     uint16_t lat[LAT_TOTAL];
-    for (uint32_t i = 0; i < LAT_TOTAL; i++) lat[i] = worldgen_u16(seed, env, episode, 0, i);
+    for (uint32_t i = 0; i < LAT_TOTAL; i++) {
+        lat[i] = worldgen_u16(seed, env, episode, 0, i);
+        /* the angle is the upper ten bits of the lattice number */
+        if (theta) lat[i] = (uint16_t)(lat[i] + ((theta[i] & 1023u) << 6));
+    }
     const uint16_t *w16 = lat, *m16 = lat + LAT16_N;
     const uint16_t *w8 = lat + 2 * LAT16_N, *m8 = w8 + LAT8_N, *c8 = m8 + LAT8_N, *f8 = c8 + LAT8_N;
 
@@ -864,4 +883,27 @@ int orc_mutate_swap(orc_env *e, uint64_t mutation_seed, uint32_t round, int rest
         return (int)k + 1;
     }
     return 0;
+}
+
+/* Noise mutation (section "Craftax-1B: UED"): a uniform random number is added to every element
+ * of the level's angle vector theta (here an integer in [-amplitude, amplitude], in 1024ths of a
+ * turn, element i from u16 number i of a stream of its own), the world of the current episode is
+ * generated again from the new angles, and the episode starts over in it. */
+void orc_mutate_noise(orc_env *e, const orc_config *cfg, uint16_t *theta, uint64_t mutation_seed, uint32_t round, uint32_t amplitude)
+{
+    (void)cfg;
+    for (uint32_t i = 0; i < LAT_TOTAL; i++) {
+        uint32_t w = philox_word(mutation_seed, e->env, round, 1, DOM_MUTATE, i >> 3, (i >> 1) & 3u);
+        uint32_t d = (i & 1u) ? (w >> 16) : (w & 0xFFFFu);
+        int32_t u = (int32_t)((d * (2u * amplitude + 1u)) >> 16) - (int32_t)amplitude;
+        theta[i] = (uint16_t)(((int32_t)(theta[i] & 1023u) + u) & 1023);
+    }
+    uint64_t seed = e->seed;
+    uint32_t env = e->env, episode = e->episode;
+    memset(e, 0, sizeof(*e));
+    e->seed = seed; e->env = env; e->episode = episode;
+    orc_worldgen_theta(e->map, seed, env, episode, theta);
+    e->px = ORC_MAP / 2; e->py = ORC_MAP / 2;
+    e->dir = DIR_DOWN;
+    e->vit[V_HEALTH] = e->vit[V_FOOD] = e->vit[V_DRINK] = e->vit[V_ENERGY] = MAX_COUNT;
 }

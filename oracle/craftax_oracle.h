@@ -113,6 +113,12 @@ void orc_observe_batch(const orc_env *envs, const orc_config *cfg, int obs_mode,
  * the central 16x16 area; restricted != 0 keeps to stone <-> ores and grass <-> tree. */
 int orc_mutate_swap(orc_env *e, uint64_t mutation_seed, uint32_t round, int restricted);
 
+/* The noise mutation of the same section: the level is the vector of Perlin gradient angles.
+ * theta: ORC_THETA_LEN offsets in 1024ths of a turn (in/out); amplitude <= 511. */
+#define ORC_THETA_LEN 374
+void orc_worldgen_theta(uint8_t *map, uint64_t seed, uint32_t env, uint32_t episode, const uint16_t *theta);
+void orc_mutate_noise(orc_env *e, const orc_config *cfg, uint16_t *theta, uint64_t mutation_seed, uint32_t round, uint32_t amplitude);
+
 /* Small accessors for tests. */
 float orc_daylight(const orc_config *cfg, uint32_t t);
 uint32_t orc_zombie_spawn_threshold(const orc_config *cfg, uint32_t t);

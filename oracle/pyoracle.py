@@ -149,6 +149,18 @@ def worldgen(seed: int, env: int, episode: int = 0, mode: int = WORLDGEN_VALUE) 
     return m
 
 
+THETA_LEN = 374      # Perlin gradient angles of one Classic world: 2 x 25 + 4 x 81
+
+
+def worldgen_theta(seed: int, env: int, episode: int, theta: np.ndarray) -> np.ndarray:
+    """Perlin world whose gradient angles are turned by theta[i] / 1024 of a turn."""
+    th = np.ascontiguousarray(theta, dtype=np.uint16)
+    assert th.shape == (THETA_LEN,)
+    m = np.zeros((64, 64), np.uint8)
+    lib().orc_worldgen_theta(_p(m), ctypes.c_uint64(seed), ctypes.c_uint32(env), ctypes.c_uint32(episode), _p(th))
+    return m
+
+
 def perlin_noise(lattice: np.ndarray, spacing: int, x: int, y: int) -> int:
     """Integer Perlin noise of the oracle over a square u16 lattice, on the 0..65535 scale."""
     lat = np.ascontiguousarray(lattice, dtype=np.uint16)
@@ -211,6 +223,14 @@ class Oracle:
             ptr = ctypes.c_void_p(self.envs.ctypes.data + i * ENV_DTYPE.itemsize)
             out[i] = lib().orc_mutate_swap(ptr, ctypes.c_uint64(mutation_seed), ctypes.c_uint32(round_), int(restricted))
         return out
+
+    def mutate_noise(self, theta: np.ndarray, mutation_seed: int, round_: int, amplitude: int) -> None:
+        """Noise mutation on every environment; theta (uint16 [n][THETA_LEN]) is updated in place."""
+        assert theta.dtype == np.uint16 and theta.shape == (self.n, THETA_LEN) and theta.flags.c_contiguous
+        for i in range(self.n):
+            ptr = ctypes.c_void_p(self.envs.ctypes.data + i * ENV_DTYPE.itemsize)
+            lib().orc_mutate_noise(ptr, ctypes.byref(self.cfg), ctypes.c_void_p(theta.ctypes.data + i * THETA_LEN * 2),
+                                   ctypes.c_uint64(mutation_seed), ctypes.c_uint32(round_), ctypes.c_uint32(amplitude))
 
 
 def full_default_config(**overrides) -> FullConfig:

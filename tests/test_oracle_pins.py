@@ -1044,3 +1044,107 @@ def test_perlin_mode_is_used_by_reset_and_auto_reset():
     assert np.all(o.envs["episode"] == 1)
     for i in range(2):
         assert np.array_equal(o.envs[i]["map"].reshape(64, 64), po.worldgen(int(seeds[i]), i, 1, po.WORLDGEN_PERLIN))
+
+
+# --------------------------------------------------- noise mutation (section "Craftax-1B: UED") ----
+def _lattice_numbers(seed, env, episode):
+    """The 374 lattice numbers of a world, straight from Philox: stream 0 of the world generation
+    domain, two u16 per word, low half first."""
+    out = []
+    for block in range(47):
+        w = po.philox([env, 0, episode, (1 << 16) | block], [seed & 0xFFFFFFFF, seed >> 32])
+        for x in w:
+            out += [x & 0xFFFF, x >> 16]
+    return np.array(out[:po.THETA_LEN], np.uint16)
+
+
+def _fields(lat, x, y):
+    """W, M of the terrain rule (appendix "World Generation") from the oracle's noise function alone."""
+    w16, m16 = lat[0:25].reshape(5, 5), lat[25:50].reshape(5, 5)
+    w8, m8 = lat[50:131].reshape(9, 9), lat[131:212].reshape(9, 9)
+    W = (3 * po.perlin_noise(w16, 16, x, y) + po.perlin_noise(w8, 8, x, y)) >> 2
+    M = (3 * po.perlin_noise(m16, 16, x, y) + po.perlin_noise(m8, 8, x, y)) >> 2
+    return W, M
+
+
+def test_noise_mutation_turns_the_right_angles():
+    rng = np.random.default_rng(3)
+    seed, env, ep = 0x1234567890AB, 11, 2
+    zero = np.zeros(po.THETA_LEN, np.uint16)
+    assert np.array_equal(po.worldgen_theta(seed, env, ep, zero), po.worldgen(seed, env, ep, po.WORLDGEN_PERLIN))
+    base = _lattice_numbers(seed, env, ep)
+    theta = rng.integers(0, 1024, po.THETA_LEN).astype(np.uint16)
+    m = po.worldgen_theta(seed, env, ep, theta)
+    assert not np.array_equal(m, po.worldgen_theta(seed, env, ep, zero))
+    turned = (base.astype(np.uint32) + (theta.astype(np.uint32) << 6)).astype(np.uint16)
+    rock = {STONE, PATH, LAVA, COAL, IRON, DIAMOND}
+    checked = {"rock": 0, "water": 0, "land": 0}
+    for y in range(0, 64, 2):
+        for x in range(0, 64, 2):
+            if max(abs(x - 32), abs(y - 32)) < 10:
+                continue                                   # the start area lowers both fields
+            W, M = _fields(turned, x, y)
+            if M > 39500 + 300:
+                assert int(m[y, x]) in rock, (x, y)
+                checked["rock"] += 1
+            elif M < 39500 - 300 and W > 39500 + 300:
+                assert m[y, x] == WATER, (x, y)
+                checked["water"] += 1
+            elif M < 39500 - 300 and W < 37800 - 300:
+                assert m[y, x] in (GRASS, TREE), (x, y)
+                checked["land"] += 1
+    assert min(checked.values()) > 20, checked
+    # the unturned lattice does not explain this map: the angles really moved
+    wrong = 0
+    for y in range(0, 64, 2):
+        for x in range(0, 64, 2):
+            if max(abs(x - 32), abs(y - 32)) >= 10:
+                W, M = _fields(base, x, y)
+                wrong += (M > 39800 and int(m[y, x]) not in rock) or (M < 39200 and W > 39800 and m[y, x] != WATER)
+    assert wrong > 30
+
+
+def test_noise_mutation_draws_and_restart():
+    n, A, ms = 6, 37, 0xFEDCBA9876
+    cfg = po.default_config(worldgen=po.WORLDGEN_PERLIN, max_episode_steps=5)
+    o = po.Oracle(n, cfg)
+    seeds = synth.seeds_for(n, 3)
+    o.reset(seeds)
+    fresh0 = o.envs.copy()
+    for t in range(8):                                     # into episode 1, with some history
+        o.step(synth.actions(np.arange(n), t, "uniform", 2))
+    assert np.all(o.envs["episode"] == 1) and np.all(o.envs["t"] == 3)
+    theta = np.zeros((n, po.THETA_LEN), np.uint16)
+    o.mutate_noise(theta, ms, 4, 0)                        # amplitude 0: the level itself, episode restarted
+    assert not theta.any()
+    for i in range(n):
+        e = o.envs[i]
+        assert np.array_equal(e["map"].reshape(64, 64), po.worldgen(int(seeds[i]), i, 1, po.WORLDGEN_PERLIN))
+        want = fresh0[i].copy()
+        want["episode"] = 1
+        want["map"] = e["map"]
+        assert e.tobytes() == want.tobytes()               # everything but the map is the state of a fresh episode
+    # the draws: u16 number i of stream (round, 1) of the mutation domain, scaled to [-A, A]
+    o.mutate_noise(theta, ms, 4, A)
+    for i in range(n):
+        for k in (0, 1, 2, 7, 8, 100, 373):
+            w = po.philox([i, 4, 1, (4 << 16) | (k >> 3)], [ms & 0xFFFFFFFF, ms >> 32])[(k >> 1) & 3]
+            d = (w >> 16) if k & 1 else (w & 0xFFFF)
+            assert theta[i, k] == ((d * (2 * A + 1) >> 16) - A) % 1024
+        assert np.array_equal(o.envs[i]["map"].reshape(64, 64), po.worldgen_theta(int(seeds[i]), i, 1, theta[i]))
+    signed = ((theta.astype(np.int32) + 512) % 1024) - 512
+    assert signed.min() == -A and signed.max() == A and abs(signed.mean()) < 2.0
+    assert len(np.unique(signed)) == 2 * A + 1
+    assert not np.array_equal(theta[0], theta[1])
+    # mutations add up, modulo a full turn; another round draws other numbers
+    first = theta.copy()
+    o.mutate_noise(theta, ms, 5, 511)
+    step2 = ((theta.astype(np.int32) - first.astype(np.int32) + 512) % 1024) - 512
+    assert -511 <= step2.min() < -500 and 500 < step2.max() <= 511
+    again = first.copy()
+    o2 = po.Oracle(n, cfg)
+    o2.reset(seeds)
+    o2.envs[:] = o.envs
+    o2.mutate_noise(again, ms, 5, 511)
+    assert np.array_equal(again, theta) and o2.envs.tobytes() == o.envs.tobytes()
+    assert theta.max() < 1024
