@@ -243,6 +243,25 @@ int craftax_import_envs(void *state, int first, int count, const void *dumps, vo
 int craftax_mutate_swap(void *state, int first, int count, uint64_t mutation_seed, uint32_t round,
                         int restricted, int32_t *tries, void *stream);
 
+/* The third operator of the same section, "noise": a level is the vector of angles of the Perlin
+ * gradients its world is generated from, and the mutation adds a uniform random number to every
+ * element.  theta: DEVICE uint16[count][CRAFTAX_THETA_LEN], in and out, caller-owned (a level
+ * buffer keeps one row per level): element i is the offset, in 1024ths of a turn (0..1023), added
+ * to the angle of lattice number i of the world generation (the two spacing-16 lattices, then the
+ * four spacing-8 ones, each row by row); all zero = the level the seed alone gives.  The call adds
+ * to every element an integer uniform in [-amplitude, amplitude] (this library's reading of
+ * "uniform random number": ((d * (2 * amplitude + 1)) >> 16) - amplitude with d = u16 number i
+ * of Philox stream (env, round, 1, MUTATE << 16 | block) keyed by mutation_seed), modulo a full
+ * turn, generates the world of the current episode of each environment of [first, first+count)
+ * again from the new angles, and restarts that episode in it (fresh player, empty tables, same
+ * episode number; the per-cell draws for trees and ores stay those of the seed).  amplitude 0
+ * loads the level theta unchanged.  Needs variant CLASSIC with CRAFTAX_WORLDGEN_PERLIN
+ * (CRAFTAX_E_CONFIG otherwise); CRAFTAX_E_COUNT for a range outside the state or amplitude > 511;
+ * CRAFTAX_E_NULL for theta == NULL. */
+#define CRAFTAX_THETA_LEN 374
+int craftax_mutate_noise(void *state, int first, int count, uint16_t *theta, uint64_t mutation_seed,
+                         uint32_t round, uint32_t amplitude, void *stream);
+
 /* Fills actions (DEVICE int32[steps][n]) with the synthetic action stream used by the
  * benchmark: kind 0 = uniform over 17 actions, kind 1 = half of the draws restricted to
  * ids 1..5, kinds 2 and 3 = the same two over the 43 actions of full Craftax.  Input generation

@@ -22,8 +22,11 @@ EXPORTS = [
     "craftax_default_config", "craftax_default_config_for", "craftax_state_bytes", "craftax_obs_bytes",
     "craftax_env_dump_bytes", "craftax_env_dump_bytes_for",
     "craftax_state_init", "craftax_state_release", "craftax_reset", "craftax_step", "craftax_observe",
-    "craftax_rollout", "craftax_export_envs", "craftax_import_envs", "craftax_mutate_swap", "craftax_synth_actions", "craftax_last_error",
+    "craftax_rollout", "craftax_export_envs", "craftax_import_envs", "craftax_mutate_swap", "craftax_mutate_noise", "craftax_synth_actions", "craftax_last_error",
 ]
+
+
+THETA_LEN = 374      # angle offsets per Classic level (craftax_mutate_noise)
 
 
 class Config(ctypes.Structure):
@@ -98,6 +101,7 @@ def load() -> ctypes.CDLL:
     L.craftax_import_envs.argtypes = [vp, i32, i32, vp, vp]
     L.craftax_rollout.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp]
     L.craftax_mutate_swap.argtypes = [vp, i32, i32, u64, ctypes.c_uint32, i32, vp, vp]
+    L.craftax_mutate_noise.argtypes = [vp, i32, i32, vp, u64, ctypes.c_uint32, ctypes.c_uint32, vp]
     L.craftax_synth_actions.argtypes = [vp, i32, i32, i32, u64, i32, vp]
     L.craftax_last_error.argtypes = []
     L.craftax_last_error.restype = ctypes.c_char_p
@@ -179,6 +183,11 @@ def craftax_mutate_swap(state, first: int, count: int, mutation_seed: int, round
                                       None if tries is None else tries.data_ptr(), _stream_ptr(stream)), "craftax_mutate_swap")
 
 
+def craftax_mutate_noise(state, first: int, count: int, theta, mutation_seed: int, round_: int, amplitude: int, stream=None):
+    _check(load().craftax_mutate_noise(state.data_ptr(), first, count, None if theta is None else theta.data_ptr(), mutation_seed,
+                                       round_, amplitude, _stream_ptr(stream)), "craftax_mutate_noise")
+
+
 def craftax_synth_actions(actions, n: int, step0: int, steps: int, action_seed: int, kind: int, stream=None):
     _check(load().craftax_synth_actions(actions.data_ptr(), n, step0, steps, action_seed, kind, _stream_ptr(stream)),
            "craftax_synth_actions")
@@ -255,3 +264,8 @@ class Craftax:
         tries = self.torch.zeros(count, dtype=self.torch.int32, device=self.device)
         craftax_mutate_swap(self.state, first, count, mutation_seed, round_, restricted, tries, self.stream)
         return tries.cpu().numpy()
+
+    def mutate_noise(self, theta, mutation_seed: int, round_: int, amplitude: int, first: int = 0):
+        """Noise mutation; theta: device int16 tensor [count][THETA_LEN] holding the angle offsets, updated in place."""
+        assert theta.dtype == self.torch.int16 and theta.is_contiguous() and theta.shape[1] == THETA_LEN
+        craftax_mutate_noise(self.state, first, theta.shape[0], theta, mutation_seed, round_, amplitude, self.stream)

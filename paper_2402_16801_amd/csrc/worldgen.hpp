@@ -116,10 +116,12 @@ constexpr int WG_THREADS = 512;
 // first_run, runs: the part of the world this call generates (runs first_run .. first_run + runs - 1
 // of the 512; a world may be split over several blocks); runs <= NT.
 // PERLIN: the fields are Perlin noise over the same lattices (perlin_cs: the gradient table).
+// theta (may be null; LDS or global, LAT_TOTAL values): angle offsets of a mutated level.
 template <int NT = WG_THREADS, bool PERLIN = false>
 __device__ __forceinline__ void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat, uint32_t seed_lo, uint32_t seed_hi,
                                       uint32_t env, uint32_t episode, uint32_t* start_win = nullptr, int first_run = 0,
-                                      int runs = WG_THREADS, const uint32_t* __restrict__ perlin_cs = nullptr)
+                                      int runs = WG_THREADS, const uint32_t* __restrict__ perlin_cs = nullptr,
+                                      const uint16_t* theta = nullptr)
 {
     static_assert(WG_THREADS % NT == 0 && NT >= 64, "block size must divide 512");
     const int tid0 = threadIdx.x;
@@ -130,6 +132,15 @@ __device__ __forceinline__ void worldgen_block(uint8_t* __restrict__ map, uint16
         for (int w = 0; w < 4; ++w) {
             s_lat[tid * 8 + 2 * w] = (uint16_t)(r.w[w] & 0xFFFFu);
             s_lat[tid * 8 + 2 * w + 1] = (uint16_t)(r.w[w] >> 16);
+        }
+        // a mutated level (section "Craftax-1B: UED"): every gradient angle, the upper ten bits of its
+        // lattice number, turned by theta[i] 1024ths of a turn
+        if (theta != nullptr) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int i = tid * 8 + j;
+                if (i < LAT_TOTAL) s_lat[i] = (uint16_t)(s_lat[i] + ((theta[i] & 1023u) << 6));
+            }
         }
     }
     __syncthreads();

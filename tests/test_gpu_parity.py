@@ -435,6 +435,85 @@ def test_swap_mutation_matches_the_oracle(cx, restricted):
     sim.close()
 
 
+def test_noise_mutation_matches_the_oracle(cx):
+    """UED noise mutation: angle offsets, regenerated worlds and restarted episodes after play
+    across an episode boundary; repeated and partial mutations; the mutated levels played on
+    (single steps, auto-resets into unmutated worlds, a rollout)."""
+    import torch
+    n, ms = 70, 0x5EEDF00D1234
+    gcfg, ocfg = _cfgs(cx, po.OBS_SYM_U8_F32, worldgen=po.WORLDGEN_PERLIN, max_episode_steps=9)
+    sim = _make_sim(cx, n, gcfg)
+    orc = po.Oracle(n, ocfg, po.OBS_SYM_U8_F32)
+    seeds = synth.seeds_for(n, 21)
+    sim.reset(seeds); orc.reset(seeds)
+    t = 0
+
+    def play(k):
+        nonlocal t
+        for _ in range(k):
+            a = synth.actions(np.arange(n), t, "skewed", 2)
+            obs, rew, done = sim.step(torch.as_tensor(a, device=sim.device))
+            oobs, orew, odone = orc.step(a)
+            assert np.array_equal(done.cpu().numpy(), odone) and np.array_equal(obs.cpu().numpy(), oobs), f"step {t}"
+            t += 1
+
+    def same(what):
+        assert np.array_equal(d_theta.cpu().numpy().view(np.uint16), theta), f"theta after {what}"
+        assert sim.export_envs().tobytes() == orc.envs.tobytes(), f"state after {what}"
+        cx.craftax_observe(sim.state, sim.obs, n, sim.stream)
+        assert np.array_equal(sim.obs.cpu().numpy(), orc.observe()), f"observation after {what}"
+
+    play(12)
+    theta = np.zeros((n, po.THETA_LEN), np.uint16)
+    d_theta = torch.zeros((n, cx.THETA_LEN), dtype=torch.int16, device=sim.device)
+    sim.mutate_noise(d_theta, ms, 0, 0)                     # amplitude 0: the same levels, restarted
+    orc.mutate_noise(theta, ms, 0, 0)
+    same("amplitude 0")
+    assert not theta.any()
+    sim.mutate_noise(d_theta, ms, 1, 40)
+    orc.mutate_noise(theta, ms, 1, 40)
+    same("the first mutation")
+    assert theta.any()
+    play(5)
+    # a sub-range, the largest amplitude, on top of the first mutation
+    sim.mutate_noise(d_theta[5:25], ms, 2, 511, first=5)
+    before = orc.envs.copy()
+    part = theta[5:25].copy()
+    sub = po.Oracle(20, ocfg, po.OBS_SYM_U8_F32)
+    sub.envs[:] = before[5:25]
+    sub.mutate_noise(part, ms, 2, 511)
+    theta[5:25] = part
+    orc.envs[5:25] = sub.envs
+    same("a partial mutation")
+    play(14)                                               # past the end of the mutated episodes
+    steps = 12
+    acts = np.stack([synth.actions(np.arange(n), t + s, "skewed", 2) for s in range(steps)]).astype(np.int32)
+    sim.mutate_noise(d_theta, ms, 3, 100)
+    orc.mutate_noise(theta, ms, 3, 100)
+    d_rew = torch.zeros((steps, n), dtype=torch.float32, device=sim.device)
+    d_done = torch.zeros((steps, n), dtype=torch.uint8, device=sim.device)
+    cx.craftax_rollout(sim.state, torch.as_tensor(acts, device=sim.device), steps, sim.obs, d_rew, d_done, n, sim.stream)
+    for s in range(steps):
+        oobs, orew, odone = orc.step(acts[s])
+        assert np.array_equal(d_done[s].cpu().numpy(), odone), f"rollout step {s}"
+    assert np.array_equal(sim.obs.cpu().numpy(), oobs) and sim.export_envs().tobytes() == orc.envs.tobytes()
+    # errors: a range outside the state, an amplitude above half a turn, no theta, value-noise worlds, the other variant
+    with pytest.raises(cx.CraftaxError):
+        cx.craftax_mutate_noise(sim.state, 60, 11, d_theta, ms, 0, 5, sim.stream)
+    with pytest.raises(cx.CraftaxError):
+        cx.craftax_mutate_noise(sim.state, 0, n, d_theta, ms, 0, 512, sim.stream)
+    with pytest.raises(cx.CraftaxError):
+        cx.craftax_mutate_noise(sim.state, 0, n, None, ms, 0, 5, sim.stream)
+    assert sim.export_envs().tobytes() == orc.envs.tobytes()
+    sim.close()
+    for bad in (cx.default_config(), cx.default_config(cx.VARIANT_CRAFTAX)):
+        other = cx.Craftax(8, bad)
+        other.reset(synth.seeds_for(8))
+        with pytest.raises(cx.CraftaxError):
+            cx.craftax_mutate_noise(other.state, 0, 8, d_theta, ms, 0, 5, other.stream)
+        other.close()
+
+
 @pytest.mark.parametrize("lanes", [4, 8, 16])
 def test_perlin_worldgen_mode(cx, lanes):
     """The paper's Perlin-noise world generation: reset worlds, worlds regenerated one episode
