@@ -131,17 +131,22 @@ def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, varian
             "draw_s": draw_s}
 
 
-def rollout_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3):
+def rollout_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, variant: str = "classic"):
     """craftax_rollout: the same steps, actions and outputs as `steps` craftax_step calls, in one launch."""
     import torch
     from paper_2402_16801_amd import binding as cx, synth
 
-    cfg = cx.default_config(obs_mode=cx.OBS_SYM_U8_F32, max_episode_steps=10000)
+    if variant == "classic":
+        cfg = cx.default_config(obs_mode=cx.OBS_SYM_U8_F32, max_episode_steps=10000)
+        kind_id = {"uniform": 0, "skewed": 1}[kind]
+    else:
+        cfg = cx.default_config(cx.VARIANT_CRAFTAX, obs_mode=cx.OBS_SYM_U8_F32)
+        kind_id = {"uniform": 2, "skewed": 3}[kind]
     sim = cx.Craftax(n, cfg)
     sim.reset(synth.seeds_for(n))
     total = warmup + repeats * steps
     actions = torch.empty((total, n), dtype=torch.int32, device=sim.device)
-    cx.craftax_synth_actions(actions, n, 0, total, 0, {"uniform": 0, "skewed": 1}[kind], sim.stream)
+    cx.craftax_synth_actions(actions, n, 0, total, 0, kind_id, sim.stream)
     reward = torch.zeros((steps, n), dtype=torch.float32, device=sim.device)
     done = torch.zeros((steps, n), dtype=torch.uint8, device=sim.device)
     cx.craftax_rollout(sim.state, actions[:warmup], warmup, sim.obs, reward[:warmup], done[:warmup], n, sim.stream)
@@ -294,7 +299,9 @@ def main():
                                "roofline_frac": (alg["total"] - 256.0) * n / (roll / K) / 1e9 / HBM_PEAK_GBS}
         full = craftax_line(args, with_cpu=False)
         out["also_craftax"] = {"workload": full["config"]["workload"], "value": full["value"], "unit": "env_steps/s",
-                               "ms_per_step": full["ms_per_step"], "roofline": full["roofline"]}
+                               "ms_per_step": full["ms_per_step"], "roofline": full["roofline"],
+                               "rollout_value": full["also"]["rollout_value"],
+                               "rollout_ms_per_step": full["also"]["rollout_ms_per_step"]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(8192, min(K, 1000), args.kind)
     print(json.dumps(out))
@@ -381,6 +388,9 @@ def craftax_line(args, with_cpu: bool = True) -> dict:
             "avg_launch_us": launch_s * 1e6,
         },
     }
+    roll = rollout_run(n, K, W, kind, variant="craftax")
+    out["also"] = {"workload": f"the same {n} environments and action stream through craftax_rollout, {K} steps per launch",
+                   "rollout_value": n * K / roll, "rollout_ms_per_step": roll / K * 1e3, "unit": "env_steps/s"}
     if with_cpu and not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(1024, min(K, 1000), kind, variant="craftax")
     return out
