@@ -514,3 +514,36 @@ def test_rollout_without_observation_and_pixels_refused(cx):
     with pytest.raises(cx.CraftaxError):
         cx.craftax_rollout(pix.state, d_acts, 2, None, d_rew, d_done, 4, pix.stream)
     pix.close()
+
+
+def test_rollout_at_the_benchmark_size_sampled(cx):
+    """4,096 environments (the shape bench.py times), 400 steps in two rollouts with device-generated
+    uniform actions; a strided sample is followed by the oracle step by step."""
+    import torch
+    n, steps = 4096, 200
+    gcfg, ocfg = _cfgs(cx, 1)
+    sim = cx.Craftax(n, gcfg)
+    ids = np.unique(np.concatenate([np.arange(0, n, 64), [n - 1]]))
+    orc = po.FullOracle(len(ids), ocfg, ORACLE_MODE[1])
+    seeds = synth.seeds_for(n, 44)
+    sim.reset(seeds)
+    orc.reset(seeds[ids], env_ids=ids)
+    d_rew = torch.zeros((steps, n), dtype=torch.float32, device=sim.device)
+    d_done = torch.zeros((steps, n), dtype=torch.uint8, device=sim.device)
+    finished = 0
+    for part in range(2):
+        d_acts = torch.empty((steps, n), dtype=torch.int32, device=sim.device)
+        cx.craftax_synth_actions(d_acts, n, part * steps, steps, 6, 2, sim.stream)
+        cx.craftax_rollout(sim.state, d_acts, steps, sim.obs, d_rew, d_done, n, sim.stream)
+        torch.cuda.synchronize()
+        g_rew, g_done = d_rew.cpu().numpy()[:, ids], d_done.cpu().numpy()[:, ids]
+        for s in range(steps):
+            a = synth.actions(ids, part * steps + s, "uniform", 6, 43)
+            oobs, orew, odone = orc.step(a, render=(s == steps - 1))
+            assert np.array_equal(g_done[s], odone), f"done at step {part * steps + s}"
+            assert np.array_equal(g_rew[s].view(np.uint32), orew.view(np.uint32)), f"reward at step {part * steps + s}"
+            finished += int(odone.sum())
+        assert np.array_equal(sim.obs.cpu().numpy()[ids], oobs), f"observation after rollout {part}"
+        compare_state(sim, orc, ids, f"rollout {part}")
+    assert finished > 20
+    sim.close()
