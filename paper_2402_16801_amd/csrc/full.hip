@@ -24,7 +24,7 @@ using la::ENTRY_VOID;
 using la::NSUB;
 
 constexpr int RESET_SLOTS = 64;    // environments served at once by kf_reset_list (nine blocks each)
-constexpr int REGEN_BLOCKS = 1296; // regeneration blocks appended to the step grid: 3 worlds per sub-list at once, 27 blocks per world
+constexpr int REGEN_BLOCKS = 256;  // regeneration blocks at the head of the step grid: with 1,024 step blocks (4,096 environments) they fill the chip exactly
 
 __device__ inline uint32_t pack_regs(const MobRegs& m)
 {
@@ -61,58 +61,56 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ e
     const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
     worldgen_floor_block(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f);
     if (f == 0) publish_world(envs + (size_t)env * ENV_DWORDS, s_layout, lo, hi, ep, ep == 0u, s_words);
-    if (ep == 1u && threadIdx.x < FLOOR_PARTS) ls.tags[(size_t)env * NTAG + f * FLOOR_PARTS + threadIdx.x] = make_uint2(1u, 0u);
+    if (ep == 1u && threadIdx.x == 0) ls.tags[(size_t)env * NTAG + f] = make_uint2(1u, 0u);
 }
 
-// A regeneration block of the step grid: a third of one floor of the world after next of an
-// episode that ended in the previous launch (27 short blocks per world fit into the gaps the
-// step blocks leave; one long block per world would outlast them).
-__device__ __forceinline__ void regeneration_block(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, const Lists& ls,
-                                                   uint32_t seq, uint32_t count, uint32_t rb, uint32_t nrb, uint32_t* lds)
+// The regeneration blocks of the step grid: worlds after next for the episodes that ended in the
+// previous launch.  The blocks are persistent and serve the consumed list as one queue of work
+// units, one floor of one world each, drawn from a single counter: a step launch holds as many of
+// them as the chip has room for beside the step blocks, every unit starts as soon as a block is
+// free, and no unit waits for a block that is scheduled late.
+__device__ __forceinline__ void regeneration_queue(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, const Lists& ls,
+                                                   uint32_t seq, uint32_t* lds)
 {
     uint16_t* s_lat = reinterpret_cast<uint16_t*>(lds);
     GenLayout& L = *reinterpret_cast<GenLayout*>(lds + 128);
     uint32_t* s_words = lds + 512;
-    const uint4* list = la::consumed_sub_list(ls, seq, rb);
-    const uint32_t k = rb / NSUB, unit = k % NTAG, f = unit / FLOOR_PARTS, part = unit % FLOOR_PARTS;
-    for (uint32_t i = k / NTAG; i < count; i += nrb / NSUB / NTAG) {
-        const uint4 entry = list[i];
+    const uint32_t* s_prefix = lds + 528;
+    const uint32_t units = s_prefix[NSUB - 1] * (uint32_t)FLOORS;
+    for (;;) {
+        const uint32_t u = la::draw_unit(ls, seq, lds + 544);
+        if (u >= units) break;
+        const uint4 entry = la::queue_entry(ls, seq, s_prefix, u / FLOORS);
+        const int f = (int)(u % FLOORS);
         if (entry.x == ENTRY_VOID) continue;
-        worldgen_floor_block<BLOCK>(maps + map_offset(entry.x, entry.w), s_lat, L, entry.y, entry.z, entry.x, entry.w, (int)f,
-                                    nullptr, nullptr, (int)part * (GEN_THREADS / FLOOR_PARTS), GEN_THREADS / FLOOR_PARTS);
-        if (unit == 0) publish_world(envs + (size_t)entry.x * ENV_DWORDS, L, entry.y, entry.z, entry.w, false, s_words);
-        if (threadIdx.x == 0) ls.tags[(size_t)entry.x * NTAG + unit] = make_uint2(entry.w, seq);
-        __syncthreads();
+        worldgen_floor_block<BLOCK>(maps + map_offset(entry.x, entry.w), s_lat, L, entry.y, entry.z, entry.x, entry.w, f);
+        if (f == 0) publish_world(envs + (size_t)entry.x * ENV_DWORDS, L, entry.y, entry.z, entry.w, false, s_words);
+        if (threadIdx.x == 0) ls.tags[(size_t)entry.x * NTAG + f] = make_uint2(entry.w, seq);
     }
 }
-static_assert(LAT_TOTAL * 2 <= 128 * 4 && sizeof(GenLayout) <= (512 - 128) * 4, "regeneration scratch overlaps");
+static_assert(LAT_TOTAL * 2 <= 128 * 4 && sizeof(GenLayout) <= (512 - 128) * 4 && 545 <= ENVS_PER_BLOCK * L_ENV_DWORDS, "regeneration scratch overlaps");
 
 // ---------------------------------------------------------------------------------------------
-// step: one wavefront per environment, four environments per block, followed in the same grid by
-// the regeneration blocks for the episodes that ended in the previous launch.
+// step: one wavefront per environment, four environments per block; the grid starts with the
+// regeneration blocks for the episodes that ended in the previous launch.
 template <bool F32>
 __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
                                                 const Luts* __restrict__ luts, const int32_t* __restrict__ actions,
                                                 uint8_t* __restrict__ obs, float* __restrict__ reward,
-                                                uint8_t* __restrict__ done, Lists ls, Params p, int step_blocks)
+                                                uint8_t* __restrict__ done, Lists ls, Params p, int regen_blocks)
 {
     __shared__ uint32_t s_env[ENVS_PER_BLOCK * L_ENV_DWORDS];
-    __shared__ int s_ndone;
-    __shared__ uint32_t s_base;
-    __shared__ uint4 s_list[ENVS_PER_BLOCK];
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
-    const bool regen_role = (int)blockIdx.x >= step_blocks;
-    const uint32_t rb = blockIdx.x - (uint32_t)step_blocks, nrb = gridDim.x - (uint32_t)step_blocks;
-    const la::Ticket ticket = la::enter_launch(ls, regen_role, rb);
-    const uint32_t seq = ticket.seq;
-    if (regen_role) {
-        if (rb / NSUB / NTAG < ticket.regen_count) regeneration_block(envs, maps, ls, seq, ticket.regen_count, rb, nrb, s_env);
+    if ((int)blockIdx.x < regen_blocks) {
+        const la::Ticket ticket = la::enter_launch_queue(ls, s_env + 528);
+        regeneration_queue(envs, maps, ls, ticket.seq, s_env);
         la::leave_launch(ls, ticket);
         return;
     }
-    if (tid == 0) s_ndone = 0;
-    __syncthreads();
-    const int env = blockIdx.x * ENVS_PER_BLOCK + w;
+    const la::Ticket ticket = la::enter_launch(ls, false, 0u);
+    const uint32_t seq = ticket.seq;
+    const uint32_t step_block = blockIdx.x - (uint32_t)regen_blocks;
+    const int env = (int)step_block * ENVS_PER_BLOCK + w;
     if (env < p.n) {
         uint32_t* e = s_env + w * L_ENV_DWORDS;
         uint32_t* genv = envs + (size_t)env * ENV_DWORDS;
@@ -156,7 +154,8 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
         };
         StepOut o = step_env(l, (uint32_t)env, e, genv, maps + map_offset((uint32_t)env, ep), luts, action, p, m, qw, P, park);
         if (l == 0) { reward[env] = o.reward; done[env] = o.done ? 1 : 0; }
-        bool write_back = !o.done;
+        bool write_back = !o.done, queued = false;
+        uint32_t list_at = 0u;
         int floor_now = P.floor;
         if (!o.done) {
             if (l == 0) pack_player(e + L_REC, P);
@@ -183,7 +182,8 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
                 o.wx0 = W / 2 - WIN_COLS / 2; o.wy0 = W / 2 - WIN_ROWS / 2;
                 wave_sync();
                 write_back = true;
-                if (l == 0) s_list[atomicAdd(&s_ndone, 1)] = make_uint4((uint32_t)env, lo, hi, ep + 2u);
+                if (l == 0) list_at = la::claim_entry(ls, seq, step_block);   // the place on the list; the entry follows after the rendering
+                queued = true;
             } else if (l == 0) {
                 la::append_slow(ls, (uint32_t)p.n, make_uint4((uint32_t)env, lo, hi, ep + 1u));
             }
@@ -194,12 +194,9 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
             if (obs != nullptr)
                 render_env<F32>(l, e, o.wx0, o.wy0, m.alive, m.x, m.y, m.type, luts, obs + (size_t)env * (F32 ? STRIDE_F32 : STRIDE_U8));
         }
+        if (queued && l == 0) la::commit_entry(ls, seq, step_block, list_at, make_uint4((uint32_t)env, lo, hi, ep + 2u));
     }
-    __syncthreads();
     la::leave_launch(ls, ticket);
-    const int nd = s_ndone;
-    if (nd == 0) return;
-    la::append_block_entries(ls, seq, s_list, nd, &s_base);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -249,13 +246,11 @@ __global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ en
         const uint32_t wenv = (uint32_t)(blockIdx.x * ENVS_PER_BLOCK + ww), lo = ew[L_REC + R_SEED_LO], hi = ew[L_REC + R_SEED_HI];
         uint8_t* slot = maps + map_offset(wenv, ep);
 #pragma unroll 1
-        for (int unit = 0; unit < NTAG; ++unit) {
-            const int f = unit / FLOOR_PARTS, part = unit % FLOOR_PARTS;
+        for (int f = 0; f < FLOORS; ++f) {
             worldgen_floor_block<BLOCK>(slot, s_lat, s_layout, lo, hi, wenv, ep, f,
                                         start ? reinterpret_cast<uint8_t*>(ew + L_WB) : nullptr,
-                                        start ? reinterpret_cast<uint8_t*>(ew + L_WI) : nullptr,
-                                        part * (GEN_THREADS / FLOOR_PARTS), GEN_THREADS / FLOOR_PARTS);
-            if (unit == FLOOR_PARTS - 1) {            // floor 0 is complete: its layout describes the whole world
+                                        start ? reinterpret_cast<uint8_t*>(ew + L_WI) : nullptr);
+            if (f == 0) {                             // the layout of floor 0 describes the whole world
                 if (tid < FLOORS + 1) s_words[tid] = layout_word(s_layout, tid);
                 __syncthreads();
             }
@@ -415,7 +410,7 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_import_spare(uint32_t* __restr
     const uint32_t ep = genv[R_EPISODE] + 1u, lo = genv[R_SEED_LO], hi = genv[R_SEED_HI];
     worldgen_floor_block(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f);
     if (f == 0) publish_world(genv, s_layout, lo, hi, ep, false, s_words);
-    if (threadIdx.x < FLOOR_PARTS) ls.tags[(size_t)env * NTAG + f * FLOOR_PARTS + threadIdx.x] = make_uint2(ep, 0u);
+    if (threadIdx.x == 0) ls.tags[(size_t)env * NTAG + f] = make_uint2(ep, 0u);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -730,20 +725,19 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
     hipStream_t st = (hipStream_t)stream;
     uint8_t* o = static_cast<uint8_t*>(obs);
     const int sb = (n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK;
-    const int unit = NSUB * NTAG;                                            // regeneration blocks come in multiples of this
-    const int want = NTAG * n < REGEN_BLOCKS ? NTAG * n : REGEN_BLOCKS;
-    const dim3 grid((unsigned)(sb + (want + unit - 1) / unit * unit)), rgrid((unsigned)(n < RESET_SLOTS ? n : RESET_SLOTS) * FLOORS);
+    const int rb = FLOORS * n < REGEN_BLOCKS ? FLOORS * n : REGEN_BLOCKS;    // persistent blocks serving a queue: any number works
+    const dim3 grid((unsigned)(rb + sb)), rgrid((unsigned)(n < RESET_SLOTS ? n : RESET_SLOTS) * FLOORS);
     const bool slow = p.max_episode_steps == 1u;   // the only way an episode can end before its spare world exists
     if (cfg->obs_mode == CRAFTAX_OBS_PIXELS_F32) {
         // the step runs without rendering; the picture is drawn from the state it leaves
-        hipLaunchKernelGGL(kf_step<false>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, (uint8_t*)nullptr, reward, done, q.ls, p, sb);
+        hipLaunchKernelGGL(kf_step<false>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, (uint8_t*)nullptr, reward, done, q.ls, p, rb);
         if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, (uint8_t*)nullptr, q.ls);
         if (o != nullptr) hipLaunchKernelGGL(kf_pixels, dim3((unsigned)n), dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, o);
     } else if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) {
-        hipLaunchKernelGGL(kf_step<true>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, sb);
+        hipLaunchKernelGGL(kf_step<true>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb);
         if (slow) hipLaunchKernelGGL(kf_reset_list<true>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls);
     } else {
-        hipLaunchKernelGGL(kf_step<false>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, sb);
+        hipLaunchKernelGGL(kf_step<false>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb);
         if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls);
     }
     return check_launch("craftax_step", err);
@@ -757,12 +751,11 @@ int rollout(void* state, const craftax_config* cfg, int n, const int32_t* action
     const Params p = make_params(cfg, n);
     hipStream_t st = (hipStream_t)stream;
     uint8_t* o = static_cast<uint8_t*>(obs);
-    const int unit = NSUB * NTAG;
-    const int want = NTAG * n < REGEN_BLOCKS ? NTAG * n : REGEN_BLOCKS;
-    const dim3 drain((unsigned)((want + unit - 1) / unit * unit)), grid((unsigned)((n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK));
+    const int rb = FLOORS * n < REGEN_BLOCKS ? FLOORS * n : REGEN_BLOCKS;
+    const dim3 drain((unsigned)rb), grid((unsigned)((n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK));
     // a launch of regeneration blocks only empties the lists of the step kernel and completes every spare world
     hipLaunchKernelGGL(kf_step<false>, drain, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, (const int32_t*)nullptr, (uint8_t*)nullptr,
-                       (float*)nullptr, (uint8_t*)nullptr, q.ls, p, 0);
+                       (float*)nullptr, (uint8_t*)nullptr, q.ls, p, rb);
     if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32)
         hipLaunchKernelGGL(kf_rollout<true>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls.tags, p, steps);
     else

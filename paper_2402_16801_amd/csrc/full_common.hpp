@@ -145,8 +145,7 @@ __device__ inline bool inb(int x, int y) { return ((unsigned)x < (unsigned)W) & 
 // plant word: alive | x<<1 | y<<7 | age<<16
 constexpr int ENV_DWORDS = 256, REC_DWORDS = 64, MOBTAB_DWORDS = 16;
 constexpr int SPARE_LADDER = 208, SPARE_PERM = 217;   // dwords of the environment block describing the spare world
-constexpr int FLOOR_PARTS = 3;                        // a regenerated floor is split over this many blocks
-constexpr int NTAG = 9 * FLOOR_PARTS;                 // spare-world tags per environment: one per part of a floor
+constexpr int NTAG = 9;                               // spare-world tags per environment: one per floor
 constexpr int R_POS = 0, R_FLAGS = 1, R_ATTR = 2, R_INV = 3, R_POT = 6, R_VIT = 7, R_MANA = 8, R_CNT = 9, R_PERM = 10,
               R_KILLS = 11, R_LADDER = 14, R_ACH = 23, R_T = 26, R_EPISODE = 27, R_SEED_LO = 28, R_SEED_HI = 29, R_PLANT = 32;
 constexpr size_t MAP_BYTES = (size_t)FLOORS * 2 * CELLS;          // 41472 per map slot

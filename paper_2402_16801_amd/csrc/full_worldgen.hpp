@@ -30,21 +30,6 @@ __device__ inline int dungeon_index(int f) { return f == 1 ? 0 : (f == 3 ? 1 : 2
 __device__ inline bool is_dungeon(int f) { return f == 1 || f == 3 || f == 4; }
 __device__ inline bool is_cave(int f) { return f == 2 || f == 5 || f == 6 || f == 7; }
 
-__device__ inline uint32_t noise8(const uint16_t* lat, int x, int y)
-{
-    const int ix = x >> 3, iy = y >> 3;
-    const uint32_t wx = cx::smooth8(x & 7), wy = cx::smooth8(y & 7);
-    const uint32_t a = lat[iy * 7 + ix], b = lat[iy * 7 + ix + 1], c = lat[(iy + 1) * 7 + ix], d = lat[(iy + 1) * 7 + ix + 1];
-    return ((a * (256u - wx) + b * wx) * (256u - wy) + (c * (256u - wx) + d * wx) * wy) >> 16;
-}
-__device__ inline uint32_t noise16(const uint16_t* lat, int x, int y)
-{
-    const int ix = x >> 4, iy = y >> 4;
-    const uint32_t wx = cx::smooth16(x & 15), wy = cx::smooth16(y & 15);
-    const uint32_t a = lat[iy * 4 + ix], b = lat[iy * 4 + ix + 1], c = lat[(iy + 1) * 4 + ix], d = lat[(iy + 1) * 4 + ix + 1];
-    return ((a * (256u - wx) + b * wx) * (256u - wy) + (c * (256u - wx) + d * wx) * wy) >> 16;
-}
-
 __device__ inline bool on_corridor(int x, int y, int x0, int y0, int x1, int y1)
 {
     // horizontal along y0 from x0 to x1, then vertical along x1 from y0 to y1
@@ -53,13 +38,28 @@ __device__ inline bool on_corridor(int x, int y, int x0, int y0, int x1, int y1)
     return h | v;
 }
 
-// Cell functions, one per kind of floor: block id | item << 8.
-__device__ inline int cell_overworld(const GenLayout& L, const uint16_t* lat, int x, int y, int u)
+// Noise fields of a run of cells in one row: the two lattice rows are blended once per lattice
+// column (vertical weight), then every cell blends two columns (horizontal weight).  The integer
+// result equals the row-first bilinear formula ((a(256-wx)+b wx)(256-wy) + (c(256-wx)+d wx) wy) >> 16
+// because nothing is rounded before the final shift.  The callers'
+// runs of 4 cells start at a multiple of 4, so a run lies inside one lattice cell.
+struct Field8 { uint32_t l, r; };
+__device__ inline Field8 field8(const uint16_t* lat, int x0, int y)
 {
-    const uint16_t *w16 = lat, *m16 = lat + 16, *w8 = lat + 32, *m8 = w8 + 49, *c8 = m8 + 49, *f8 = c8 + 49;
-    int Wn = (int)((3u * noise16(w16, x, y) + noise8(w8, x, y)) >> 2);
-    int Mn = (int)((3u * noise16(m16, x, y) + noise8(m8, x, y)) >> 2);
-    const int Cn = (int)noise8(c8, x, y), Fn = (int)noise8(f8, x, y);
+    const uint32_t wy = cx::smooth8(y & 7);
+    return { cx::column(lat, 7, x0 >> 3, y >> 3, wy), cx::column(lat, 7, (x0 >> 3) + 1, y >> 3, wy) };
+}
+__device__ inline Field8 field16(const uint16_t* lat, int x0, int y)
+{
+    const uint32_t wy = cx::smooth16(y & 15);
+    return { cx::column(lat, 4, x0 >> 4, y >> 4, wy), cx::column(lat, 4, (x0 >> 4) + 1, y >> 4, wy) };
+}
+__device__ inline uint32_t at8(const Field8& f, int x) { return cx::across(f.l, f.r, cx::smooth8(x & 7)); }
+__device__ inline uint32_t at16(const Field8& f, int x) { return cx::across(f.l, f.r, cx::smooth16(x & 15)); }
+
+// Cell functions, one per kind of floor: block id | item << 8.
+__device__ inline int classify_overworld(const GenLayout& L, int Wn, int Mn, int Cn, int Fn, int x, int y, int u)
+{
     const int d = max(iabs(x - W / 2), iabs(y - W / 2));
     if (d < 10) { const int bias = (10 - d) * 2500; Wn = max(0, Wn - bias); Mn = max(0, Mn - bias); }
     int b;
@@ -110,10 +110,8 @@ __device__ inline int cell_graveyard(int x, int y)
     if (x == 24 && y == 42) return B_PATH | (IT_LADDER_UP << 8);
     return b;
 }
-__device__ inline int cell_cave(const GenLayout& L, const uint16_t* lat, int f, int x, int y, int u)
+__device__ inline int classify_cave(const GenLayout& L, int f, int Cn, int Fn, int x, int y, int u)
 {
-    const uint16_t *c8 = lat, *f8 = lat + 49;
-    const int Cn = (int)noise8(c8, x, y), Fn = (int)noise8(f8, x, y);
     const int open = f == 6 ? B_FIRE_GRASS : (f == 7 ? B_ICE_GRASS : B_PATH);
     int b;
     if (Cn > 31000) {
@@ -173,64 +171,75 @@ __device__ inline void make_cave_ladders(GenLayout& L, int f, const U4& r)
     L.down[f][0] = 32 + (int)choice(r.w[2], 6); L.down[f][1] = 32 + (int)choice(r.w[3], 6);
 }
 
-// Generates floor f of one environment with the GEN_THREADS threads of the calling block: thread
-// t owns the 4 cells [4t, 4t+4) of the floor (row t/12).  The block of floor 0 also derives the
+// Generates floor f of one environment with the NT threads of the calling block: run t (of 576)
+// is the 4 cells [4t, 4t+4) of the floor (row t/12).  The block of floor 0 also derives the
 // ladders of every floor and the potion permutation (whole_layout), which the fresh record
 // needs, and may drop the cells around the start position into an LDS window (start_wb /
 // start_wi, 11 x 16 bytes each) for the first observation.  maps: this environment's 41472
 // bytes.  s_lat, L: LDS scratch.  Ends with a block barrier.
-// first_run, runs: the part of the floor this call generates (a floor may be split over several
-// blocks); runs <= NT.
+// first_run, runs: the part of the floor this call generates (a block of fewer than `runs` threads
+// takes several passes).
 template <int NT = GEN_THREADS>
 __device__ __forceinline__ void worldgen_floor_block(uint8_t* __restrict__ maps, uint16_t* s_lat, GenLayout& L, uint32_t lo, uint32_t hi,
                                             uint32_t env, uint32_t episode, int f, uint8_t* start_wb = nullptr,
                                             uint8_t* start_wi = nullptr, int first_run = 0, int runs = GEN_THREADS)
 {
-    static_assert(NT >= 128, "the layout phase uses thread indices up to 101");
+    static_assert(NT >= 64, "the layout phase uses the first wavefront");
     const int tid0 = threadIdx.x;
-    { const int tid = tid0;
-    if (f == 0) {
-        if (tid < LAT0_BLOCKS) put_lattice(s_lat + tid * 8, wg_block(lo, hi, env, episode, 0u, (uint32_t)tid));
-        else if (tid >= 64 && tid < 88) {
-            const int d = (tid - 64) >> 3, i = (tid - 64) & 7, ff = d == 0 ? 1 : (d == 1 ? 3 : 4);
-            make_room(L, ff, i, wg_block(lo, hi, env, episode, (uint32_t)ff * 4u + 2u, (uint32_t)i));
-        } else if (tid >= 96 && tid < 100) {
-            const int c = tid - 96, ff = c == 0 ? 2 : (c == 1 ? 5 : (c == 2 ? 6 : 7));
-            make_cave_ladders(L, ff, wg_block(lo, hi, env, episode, (uint32_t)ff * 4u + 2u, 0u));
-        } else if (tid == 100) {
-            const U4 r = wg_block(lo, hi, env, episode, 2u, 0u);
-            int dx = (int)choice(r.w[0], 13) - 6;
-            const int dy = (int)choice(r.w[1], 13) - 6;
-            if (max(iabs(dx), iabs(dy)) < 3) dx = 3;
-            L.up[0][0] = 0; L.up[0][1] = 0; L.down[0][0] = W / 2 + dx; L.down[0][1] = W / 2 + dy;
-            L.up[8][0] = 24; L.up[8][1] = 42; L.down[8][0] = 0; L.down[8][1] = 0;
-        } else if (tid == 101) {
-            // section "Potions and Enchantments": a fresh colour -> effect permutation per episode
-            const U4 r0 = wg_block(lo, hi, env, episode, 63u, 0u), r1 = wg_block(lo, hi, env, episode, 63u, 1u);
-            const uint32_t draws[5] = { r0.w[0], r0.w[1], r0.w[2], r0.w[3], r1.w[0] };
-            uint32_t perm = 0u;
+    // Layout phase, all in the first wavefront and with one Philox call for the whole wave: every
+    // lane picks the (stream, block) of its role, then the roles unpack their words.
+    if (tid0 < 64) {
+        const int tid = tid0;
+        if (f == 0) {
+            // lanes 0..28 lattice blocks; 29..52 rooms of floors 1, 3, 4; 53..56 ladders of the caves 2, 5, 6, 7;
+            // 57 overworld ladder; 58, 59 potion permutation (section "Potions and Enchantments")
+            uint32_t stream = 0u, block = (uint32_t)tid;
+            int ff = 0;
+            if (tid >= 29 && tid < 53) { const int d = (tid - 29) >> 3; ff = d == 0 ? 1 : (d == 1 ? 3 : 4); stream = (uint32_t)ff * 4u + 2u; block = (uint32_t)((tid - 29) & 7); }
+            else if (tid >= 53 && tid < 57) { const int c = tid - 53; ff = c == 0 ? 2 : (c == 1 ? 5 : (c == 2 ? 6 : 7)); stream = (uint32_t)ff * 4u + 2u; block = 0u; }
+            else if (tid == 57) { stream = 2u; block = 0u; }
+            else if (tid >= 58) { stream = 63u; block = tid == 59 ? 1u : 0u; }
+            const U4 r = wg_block(lo, hi, env, episode, stream, block);
+            const uint32_t fifth = (uint32_t)__shfl((int)r.w[0], 59);
+            if (tid < LAT0_BLOCKS) put_lattice(s_lat + tid * 8, r);
+            else if (tid < 53) make_room(L, ff, (tid - 29) & 7, r);
+            else if (tid < 57) make_cave_ladders(L, ff, r);
+            else if (tid == 57) {
+                int dx = (int)choice(r.w[0], 13) - 6;
+                const int dy = (int)choice(r.w[1], 13) - 6;
+                if (max(iabs(dx), iabs(dy)) < 3) dx = 3;
+                L.up[0][0] = 0; L.up[0][1] = 0; L.down[0][0] = W / 2 + dx; L.down[0][1] = W / 2 + dy;
+                L.up[8][0] = 24; L.up[8][1] = 42; L.down[8][0] = 0; L.down[8][1] = 0;
+            } else if (tid == 58) {
+                // a fresh colour -> effect permutation per episode
+                const uint32_t draws[5] = { r.w[0], r.w[1], r.w[2], r.w[3], fifth };
+                uint32_t perm = 0u;
 #pragma unroll
-            for (int i = 0; i < 6; ++i) perm |= (uint32_t)i << (3 * i);
+                for (int i = 0; i < 6; ++i) perm |= (uint32_t)i << (3 * i);
 #pragma unroll
-            for (int i = 5; i >= 1; --i) {
-                const int j = (int)choice(draws[5 - i], (uint32_t)(i + 1));
-                const uint32_t a = (perm >> (3 * i)) & 7u, b = (perm >> (3 * j)) & 7u;
-                perm &= ~((7u << (3 * i)) | (7u << (3 * j)));
-                perm |= (b << (3 * i)) | (a << (3 * j));
+                for (int i = 5; i >= 1; --i) {
+                    const int j = (int)choice(draws[5 - i], (uint32_t)(i + 1));
+                    const uint32_t a = (perm >> (3 * i)) & 7u, b = (perm >> (3 * j)) & 7u;
+                    perm &= ~((7u << (3 * i)) | (7u << (3 * j)));
+                    perm |= (b << (3 * i)) | (a << (3 * j));
+                }
+                L.perm = perm;
             }
-            L.perm = perm;
+        } else if (is_dungeon(f)) {
+            if (tid < 8) make_room(L, f, tid, wg_block(lo, hi, env, episode, (uint32_t)f * 4u + 2u, (uint32_t)tid));
+        } else if (is_cave(f)) {
+            // lanes 0..12 lattice blocks, lane 13 the ladders
+            if (tid <= LATC_BLOCKS) {
+                const U4 r = wg_block(lo, hi, env, episode, (uint32_t)f * 4u + (tid == LATC_BLOCKS ? 2u : 0u), tid == LATC_BLOCKS ? 0u : (uint32_t)tid);
+                if (tid < LATC_BLOCKS) put_lattice(s_lat + tid * 8, r);
+                else make_cave_ladders(L, f, r);
+            }
         }
-    } else if (is_dungeon(f)) {
-        if (tid < 8) make_room(L, f, tid, wg_block(lo, hi, env, episode, (uint32_t)f * 4u + 2u, (uint32_t)tid));
-    } else if (is_cave(f)) {
-        if (tid < LATC_BLOCKS) put_lattice(s_lat + tid * 8, wg_block(lo, hi, env, episode, (uint32_t)f * 4u, (uint32_t)tid));
-        else if (tid == 32) make_cave_ladders(L, f, wg_block(lo, hi, env, episode, (uint32_t)f * 4u + 2u, 0u));
-    }
     }
     __syncthreads();
-    // one run of 4 cells per thread (the callers give a block no more runs than it has threads)
-    if (tid0 < runs) {
-    const int tid = first_run + tid0;
+    // runs of 4 cells, one per thread and pass
+#pragma unroll 1
+    for (int tid = first_run + tid0; tid < first_run + runs; tid += NT) {
     const int y = tid / 12, x = (tid - y * 12) * 4;
     const bool needs_u = !(f == 1 || f == 4 || f == 8);
     uint32_t rw0 = 0u, rw1 = 0u;
@@ -248,18 +257,27 @@ __device__ __forceinline__ void worldgen_floor_block(uint8_t* __restrict__ maps,
     };
     auto draw = [&](int j) { const uint32_t rw = j < 2 ? rw0 : rw1; return (int)((j & 1) ? (rw >> 16) : (rw & 0xFFFFu)); };
     // the floor is the same for the whole block: one kind of cell function per block
+    // (the cells of a run one after the other: side by side they are no faster where many blocks
+    // share a compute unit, and they cost the step kernel registers it does not have)
+    auto cells = [&](auto&& one) {
+#pragma unroll 1
+        for (int j = 0; j < 4; ++j) one(j);
+    };
     if (f == 0) {
-#pragma unroll 1
-        for (int j = 0; j < 4; ++j) put(j, cell_overworld(L, s_lat, x + j, y, draw(j)));
+        const Field8 w16 = field16(s_lat, x, y), m16 = field16(s_lat + 16, x, y);
+        const Field8 w8 = field8(s_lat + 32, x, y), m8 = field8(s_lat + 81, x, y), c8 = field8(s_lat + 130, x, y), f8 = field8(s_lat + 179, x, y);
+        cells([&](int j) {
+            const int Wn = (int)((3u * at16(w16, x + j) + at8(w8, x + j)) >> 2), Mn = (int)((3u * at16(m16, x + j) + at8(m8, x + j)) >> 2);
+            put(j, classify_overworld(L, Wn, Mn, (int)at8(c8, x + j), (int)at8(f8, x + j), x + j, y, draw(j)));
+        });
     } else if (is_dungeon(f)) {
-#pragma unroll 1
-        for (int j = 0; j < 4; ++j) put(j, cell_dungeon(L, f, x + j, y, draw(j)));
+        cells([&](int j) { put(j, cell_dungeon(L, f, x + j, y, draw(j))); });
     } else if (f == 8) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) put(j, cell_graveyard(x + j, y));
     } else {
-#pragma unroll 1
-        for (int j = 0; j < 4; ++j) put(j, cell_cave(L, s_lat, f, x + j, y, draw(j)));
+        const Field8 c8 = field8(s_lat, x, y), f8 = field8(s_lat + 49, x, y);
+        cells([&](int j) { put(j, classify_cave(L, f, (int)at8(c8, x + j), (int)at8(f8, x + j), x + j, y, draw(j))); });
     }
     *reinterpret_cast<uint32_t*>(maps + block_off(f, x, y)) = pb;
     *reinterpret_cast<uint32_t*>(maps + il_off(f, x, y)) = pi;

@@ -16,7 +16,7 @@
 // A list entry carries what world generation needs: (env, seed low, seed high, episode index);
 // env = ENTRY_VOID marks an entry cancelled by an import.  Each of the two regeneration lists
 // (filled and consumed in alternate launches) is cut into NSUB sub-lists with their own counters
-// (a step block appends to sub-list blockIdx mod NSUB), so that the appending atomics do not
+// (step block b appends to sub-list b mod NSUB), so that the appending atomics do not
 // queue up on one address.
 #pragma once
 
@@ -32,10 +32,11 @@ namespace la {
 //   SLOW    entries in the slow list; SLOW_FINISHED: slow-list blocks finished
 //   GROUP+g blocks of group g of the current step launch that have started
 //   REGEN+p*NSUB+s entries in sub-list s of regeneration list p
+//   UNIT+p  work units of regeneration list p handed out so far (kernels that serve the list as one queue)
 constexpr int CTR_STRIDE = 64;   // dwords between counters
 constexpr int NGROUP = 64, NSUB = 16;
 enum Counter : int { CT_SEQ = 0, CT_TOP = 1, CT_SLOW = 2, CT_SLOW_FINISHED = 3, CT_GROUP = 4, CT_REGEN = CT_GROUP + NGROUP,
-                     CT_COUNT = CT_REGEN + 2 * NSUB };
+                     CT_UNIT = CT_REGEN + 2 * NSUB, CT_COUNT = CT_UNIT + 2 };
 constexpr uint64_t COUNTER_BYTES = (uint64_t)CT_COUNT * CTR_STRIDE * 4;
 constexpr uint32_t TAG_NONE = 0xFFFFFFFFu, ENTRY_VOID = 0xFFFFFFFFu;
 
@@ -87,7 +88,51 @@ __device__ inline void leave_launch(const Lists& ls, const Ticket& t)
     if (atomicAdd(counter(ls, CT_TOP), 1u) != ngroups - 1u) return;
     *counter(ls, CT_TOP) = 0u;
     for (int sub = 0; sub < NSUB; ++sub) *counter(ls, CT_REGEN + (int)(((t.seq & 1u) ^ 1u) * NSUB) + sub) = 0u;
+    *counter(ls, CT_UNIT + (int)(t.seq & 1u)) = 0u;   // the queue counter of the list the NEXT launch consumes; blocks of this launch may still draw from the other one
     *counter(ls, CT_SEQ) = t.seq + 1u;
+}
+
+// The same for a block that serves the consumed list as ONE queue of work units (full game):
+// the lengths of all NSUB sub-lists, as running totals, go to s_prefix (LDS, NSUB words;
+// s_prefix[NSUB - 1] = all entries) before the block counts itself in.  All threads of the block
+// call; ends with a block barrier.
+__device__ inline Ticket enter_launch_queue(const Lists& ls, uint32_t* s_prefix)
+{
+    Ticket t;
+    t.seq = *counter(ls, CT_SEQ);
+    t.regen_count = 0u;
+    if (threadIdx.x < (unsigned)NSUB) {
+        uint32_t c = min(*counter(ls, CT_REGEN + (int)(((t.seq & 1u) ^ 1u) * NSUB + threadIdx.x)), ls.sub_cap);
+#pragma unroll
+        for (int d = 1; d < NSUB; d <<= 1) {
+            const uint32_t below = (uint32_t)__shfl_up((int)c, d, NSUB);
+            if ((int)threadIdx.x >= d) c += below;
+        }
+        s_prefix[threadIdx.x] = c;
+    }
+    __syncthreads();   // the lengths have arrived (they are in LDS) before this block counts itself in
+    t.gsize = (gridDim.x + NGROUP - 1) / NGROUP;
+    t.grp = blockIdx.x / t.gsize;
+    t.started = 0u;
+    asm volatile("" :: "v"(t.seq) : "memory");
+    if (threadIdx.x == 0) t.started = atomicAdd(counter(ls, CT_GROUP + (int)t.grp), 1u);
+    return t;
+}
+// Entry number g of the consumed list seen as one queue (g < s_prefix[NSUB - 1]).
+__device__ inline uint4 queue_entry(const Lists& ls, uint32_t seq, const uint32_t* s_prefix, uint32_t g)
+{
+    uint32_t sub = 0u, base = 0u;
+#pragma unroll
+    for (int k = 0; k < NSUB - 1; ++k) if (g >= s_prefix[k]) { sub = (uint32_t)k + 1u; base = s_prefix[k]; }
+    return ls.regen[(seq & 1u) ^ 1u][(size_t)sub * ls.sub_cap + (g - base)];
+}
+// Next unit of the queue: one atomic per block and turn.  All threads call; s_slot: one LDS word.
+__device__ inline uint32_t draw_unit(const Lists& ls, uint32_t seq, uint32_t* s_slot)
+{
+    __syncthreads();   // the previous value of *s_slot has been read by everyone
+    if (threadIdx.x == 0) *s_slot = atomicAdd(counter(ls, CT_UNIT + (int)((seq & 1u) ^ 1u)), 1u);
+    __syncthreads();
+    return *s_slot;
 }
 
 // the sub-list of the list consumed in this launch that regeneration block rb reads
@@ -96,13 +141,24 @@ __device__ inline const uint4* consumed_sub_list(const Lists& ls, uint32_t seq, 
     return ls.regen[(seq & 1u) ^ 1u] + (size_t)(rb % NSUB) * ls.sub_cap;
 }
 // Appends nd entries (staged in LDS by the block) to this launch's list; all threads of the block call.
-__device__ inline void append_block_entries(const Lists& ls, uint32_t seq, const uint4* s_list, int nd, uint32_t* s_base)
+// step_block: index of the block among the step blocks of the launch.
+__device__ inline void append_block_entries(const Lists& ls, uint32_t seq, const uint4* s_list, int nd, uint32_t* s_base, uint32_t step_block)
 {
-    const uint32_t sub = blockIdx.x % NSUB;
+    const uint32_t sub = step_block % NSUB;
     if (threadIdx.x == 0) *s_base = atomicAdd(counter(ls, CT_REGEN + (int)((seq & 1u) * NSUB + sub)), (uint32_t)nd);
     __syncthreads();
     if ((int)threadIdx.x < nd && *s_base + threadIdx.x < ls.sub_cap)   // always true: a sub-list holds every environment of its blocks
         ls.regen[seq & 1u][(size_t)sub * ls.sub_cap + *s_base + threadIdx.x] = s_list[threadIdx.x];
+}
+// The same for a single entry, in two halves so that the latency of the atomic hides behind whatever
+// the caller does in between: claim_entry reserves the place, commit_entry stores the entry there.
+__device__ inline uint32_t claim_entry(const Lists& ls, uint32_t seq, uint32_t step_block)
+{
+    return atomicAdd(counter(ls, CT_REGEN + (int)((seq & 1u) * NSUB + step_block % NSUB)), 1u);
+}
+__device__ inline void commit_entry(const Lists& ls, uint32_t seq, uint32_t step_block, uint32_t at, uint4 entry)
+{
+    if (at < ls.sub_cap) ls.regen[seq & 1u][(size_t)(step_block % NSUB) * ls.sub_cap + at] = entry;   // always true: a sub-list holds every environment of its blocks
 }
 // One entry for the list the NEXT launch consumes, from a kernel that runs after the step kernel
 // (which has already advanced the launch number); step_block = index of the step block that owns

@@ -65,9 +65,9 @@ def test_full_variant_sizes_and_defaults(lib):
         assert binding.craftax_obs_bytes(cfg) == 0 and binding.craftax_state_bytes(cfg, 8) == 0
     cfg.obs_mode = binding.OBS_SYM_U8_F32
     b1, b2 = binding.craftax_state_bytes(cfg, 1), binding.craftax_state_bytes(cfg, 1001)
-    # per environment: 1024-byte record + mob tables, two slots of 9 floors x 2 maps x 2304 bytes, 27 spare-world
+    # per environment: 1024-byte record + mob tables, two slots of 9 floors x 2 maps x 2304 bytes, 9 spare-world
     # tags, three list entries (the sub-lists round their capacity up)
-    assert abs((b2 - b1) - 1000 * (1024 + 2 * 9 * 2 * 2304 + 27 * 8 + 3 * 16)) < 8192 and b1 % 256 == 0
+    assert abs((b2 - b1) - 1000 * (1024 + 2 * 9 * 2 * 2304 + 9 * 8 + 3 * 16)) < 8192 and b1 % 256 == 0
     cfg.cap_skeleton = 3
     assert binding.craftax_state_bytes(cfg, 8) == 0
 
