@@ -107,26 +107,34 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
         la::leave_launch(ls, ticket);
         return;
     }
-    const la::Ticket ticket = la::enter_launch(ls, false, 0u);
-    const uint32_t seq = ticket.seq;
     const uint32_t step_block = blockIdx.x - (uint32_t)regen_blocks;
     const int env = (int)step_block * ENVS_PER_BLOCK + w;
-    if (env < p.n) {
+    const bool active = env < p.n;
+    uint32_t* genv = envs + (size_t)(active ? env : 0) * ENV_DWORDS;
+    // Everything that depends on the environment's number alone is fetched before the launch
+    // bookkeeping, whose own trip to memory then costs nothing extra: the record, the action, and
+    // what a finished episode needs from the spare world (its tags, its ladders and potion map).
+    uint32_t rec_word = 0u, hdr = 0u;
+    int action_raw = 0;
+    uint2 tag = make_uint2(0u, 0u);
+    if (active) {
+        rec_word = genv[l];
+        action_raw = actions[env];
+        if (l < NTAG) tag = ls.tags[(size_t)env * NTAG + l];
+        if (l < FLOORS + 1) hdr = genv[SPARE_LADDER + l];
+    }
+    const la::Ticket ticket = la::enter_launch(ls, false, 0u);
+    const uint32_t seq = ticket.seq;
+    if (active) {
         uint32_t* e = s_env + w * L_ENV_DWORDS;
-        uint32_t* genv = envs + (size_t)env * ENV_DWORDS;
-        e[L_REC + l] = genv[l];
-        const int action = uni(actions[env]);
+        e[L_REC + l] = rec_word;
+        const int action = uni(action_raw);
         wave_sync();
         const uint32_t ep = uniu(e[L_REC + R_EPISODE]), lo = uniu(e[L_REC + R_SEED_LO]), hi = uniu(e[L_REC + R_SEED_HI]);
         MobRegs m;
         uint32_t qw;
         Player P;
-        // What a finished episode needs from the spare world is fetched now, together with the
-        // current window, so that switching worlds costs no further trip to memory: its tags, its
-        // ladders and potion map, and the window of its start position.
-        uint2 tag = make_uint2(0u, 0u);
-        if (l < NTAG) tag = ls.tags[(size_t)env * NTAG + l];
-        const uint32_t hdr = l < FLOORS + 1 ? genv[SPARE_LADDER + l] : 0u;
+        // the window of the spare world's start position comes with the current window
         const uint8_t* spare = maps + map_offset((uint32_t)env, ep + 1u);
         uint32_t sw[3];
 #pragma unroll

@@ -162,10 +162,9 @@ __device__ __forceinline__ void render_env(const int l, uint32_t* e, const int w
                     const uint4 f = reinterpret_cast<const uint4*>(e + L_VEC)[j - VEC_OFFSET / 16];
                     v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
                 }
-                __builtin_nontemporal_store(v[0], &dst[j].x);
-                __builtin_nontemporal_store(v[1], &dst[j].y);
-                __builtin_nontemporal_store(v[2], &dst[j].z);
-                __builtin_nontemporal_store(v[3], &dst[j].w);
+                typedef uint32_t piece_t __attribute__((ext_vector_type(4)));
+                const piece_t piece = { v[0], v[1], v[2], v[3] };
+                __builtin_nontemporal_store(piece, reinterpret_cast<piece_t*>(dst + j));   // one 16-byte streaming store
             }
         }
     } else {
