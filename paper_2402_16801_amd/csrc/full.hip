@@ -65,21 +65,20 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ e
 }
 
 // The regeneration blocks of the step grid: worlds after next for the episodes that ended in the
-// previous launch.  The blocks are persistent and serve the consumed list as one queue of work
-// units, one floor of one world each, drawn from a single counter: a step launch holds as many of
-// them as the chip has room for beside the step blocks, every unit starts as soon as a block is
-// free, and no unit waits for a block that is scheduled late.
+// previous launch.  The consumed list is one dense queue of work units, one floor of one world
+// each; block rb of nrb takes units rb, rb + nrb, ...  The blocks stand at the head of the grid:
+// a step launch holds as many of them as the chip has room for beside the step blocks, so every
+// unit starts with the launch and none waits for a block that is scheduled late.
 __device__ __forceinline__ void regeneration_queue(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, const Lists& ls,
-                                                   uint32_t seq, uint32_t* lds)
+                                                   uint32_t seq, uint32_t* lds, int regen_blocks)
 {
     uint16_t* s_lat = reinterpret_cast<uint16_t*>(lds);
     GenLayout& L = *reinterpret_cast<GenLayout*>(lds + 128);
     uint32_t* s_words = lds + 512;
     const uint32_t* s_prefix = lds + 528;
     const uint32_t units = s_prefix[NSUB - 1] * (uint32_t)FLOORS;
-    for (;;) {
-        const uint32_t u = la::draw_unit(ls, seq, lds + 544);
-        if (u >= units) break;
+    for (uint32_t u = blockIdx.x; u < units; u += (uint32_t)regen_blocks) {
+        __syncthreads();   // the previous unit's scratch has been read by everyone
         const uint4 entry = la::queue_entry(ls, seq, s_prefix, u / FLOORS);
         const int f = (int)(u % FLOORS);
         if (entry.x == ENTRY_VOID) continue;
@@ -88,7 +87,7 @@ __device__ __forceinline__ void regeneration_queue(uint32_t* __restrict__ envs, 
         if (threadIdx.x == 0) ls.tags[(size_t)entry.x * NTAG + f] = make_uint2(entry.w, seq);
     }
 }
-static_assert(LAT_TOTAL * 2 <= 128 * 4 && sizeof(GenLayout) <= (512 - 128) * 4 && 545 <= ENVS_PER_BLOCK * L_ENV_DWORDS, "regeneration scratch overlaps");
+static_assert(LAT_TOTAL * 2 <= 128 * 4 && sizeof(GenLayout) <= (512 - 128) * 4 && 528 + NSUB <= ENVS_PER_BLOCK * L_ENV_DWORDS, "regeneration scratch overlaps");
 
 // ---------------------------------------------------------------------------------------------
 // step: one wavefront per environment, four environments per block; the grid starts with the
@@ -103,7 +102,7 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
     if ((int)blockIdx.x < regen_blocks) {
         const la::Ticket ticket = la::enter_launch_queue(ls, s_env + 528);
-        regeneration_queue(envs, maps, ls, ticket.seq, s_env);
+        regeneration_queue(envs, maps, ls, ticket.seq, s_env, regen_blocks);
         la::leave_launch(ls, ticket);
         return;
     }

@@ -32,11 +32,10 @@ namespace la {
 //   SLOW    entries in the slow list; SLOW_FINISHED: slow-list blocks finished
 //   GROUP+g blocks of group g of the current step launch that have started
 //   REGEN+p*NSUB+s entries in sub-list s of regeneration list p
-//   UNIT+p  work units of regeneration list p handed out so far (kernels that serve the list as one queue)
 constexpr int CTR_STRIDE = 64;   // dwords between counters
 constexpr int NGROUP = 64, NSUB = 16;
 enum Counter : int { CT_SEQ = 0, CT_TOP = 1, CT_SLOW = 2, CT_SLOW_FINISHED = 3, CT_GROUP = 4, CT_REGEN = CT_GROUP + NGROUP,
-                     CT_UNIT = CT_REGEN + 2 * NSUB, CT_COUNT = CT_UNIT + 2 };
+                     CT_COUNT = CT_REGEN + 2 * NSUB };
 constexpr uint64_t COUNTER_BYTES = (uint64_t)CT_COUNT * CTR_STRIDE * 4;
 constexpr uint32_t TAG_NONE = 0xFFFFFFFFu, ENTRY_VOID = 0xFFFFFFFFu;
 
@@ -88,14 +87,15 @@ __device__ inline void leave_launch(const Lists& ls, const Ticket& t)
     if (atomicAdd(counter(ls, CT_TOP), 1u) != ngroups - 1u) return;
     *counter(ls, CT_TOP) = 0u;
     for (int sub = 0; sub < NSUB; ++sub) *counter(ls, CT_REGEN + (int)(((t.seq & 1u) ^ 1u) * NSUB) + sub) = 0u;
-    *counter(ls, CT_UNIT + (int)(t.seq & 1u)) = 0u;   // the queue counter of the list the NEXT launch consumes; blocks of this launch may still draw from the other one
     *counter(ls, CT_SEQ) = t.seq + 1u;
 }
 
-// The same for a block that serves the consumed list as ONE queue of work units (full game):
-// the lengths of all NSUB sub-lists, as running totals, go to s_prefix (LDS, NSUB words;
-// s_prefix[NSUB - 1] = all entries) before the block counts itself in.  All threads of the block
-// call; ends with a block barrier.
+// The same for a block that sees the consumed list as ONE dense queue of entries (full game:
+// regeneration block b of B takes the work units b, b + B, ... of that queue, so the work sits on
+// the first blocks of the grid and no counter is shared: a few hundred atomics on one address
+// would take microseconds).  The lengths of all NSUB sub-lists, as running totals, go to s_prefix
+// (LDS, NSUB words; s_prefix[NSUB - 1] = all entries) before the block counts itself in.  All
+// threads of the block call; ends with a block barrier.
 __device__ inline Ticket enter_launch_queue(const Lists& ls, uint32_t* s_prefix)
 {
     Ticket t;
@@ -126,15 +126,6 @@ __device__ inline uint4 queue_entry(const Lists& ls, uint32_t seq, const uint32_
     for (int k = 0; k < NSUB - 1; ++k) if (g >= s_prefix[k]) { sub = (uint32_t)k + 1u; base = s_prefix[k]; }
     return ls.regen[(seq & 1u) ^ 1u][(size_t)sub * ls.sub_cap + (g - base)];
 }
-// Next unit of the queue: one atomic per block and turn.  All threads call; s_slot: one LDS word.
-__device__ inline uint32_t draw_unit(const Lists& ls, uint32_t seq, uint32_t* s_slot)
-{
-    __syncthreads();   // the previous value of *s_slot has been read by everyone
-    if (threadIdx.x == 0) *s_slot = atomicAdd(counter(ls, CT_UNIT + (int)((seq & 1u) ^ 1u)), 1u);
-    __syncthreads();
-    return *s_slot;
-}
-
 // the sub-list of the list consumed in this launch that regeneration block rb reads
 __device__ inline const uint4* consumed_sub_list(const Lists& ls, uint32_t seq, uint32_t rb)
 {
