@@ -3,7 +3,11 @@
 
 A "step" is one craftax_step call over all environments of the workload: rules, mob update,
 auto-reset of finished episodes and the symbolic observation write, with every input already
-resident in HBM.  Prints ONE JSON line (see the design doc for the field definitions).  The headline
+resident in HBM.  Prints ONE JSON line: metric / value / unit (environment steps per second),
+ms_per_step, config.workload, "roofline" (algorithmic bytes per launch over the launch time measured
+with HIP events on the library's stream, against the 8 TB/s HBM peak; "traffic" = HBM bytes per
+launch from the rocprofv3 counter runs summarised under profiles/) and "cpu_baseline" (the CPU
+oracle timed on a bounded sample of the same workload).  The headline
 workload is the 65,536-environment Craftax-Classic step; the 4,096-environment Classic step and
 the 4,096-environment full-Craftax step are measured next to it ("also", "also_craftax"), or
 alone with --workload craftax.
