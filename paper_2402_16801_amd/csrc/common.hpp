@@ -179,7 +179,21 @@ struct Grp {
         const uint32_t half = (lane & 32u) ? (uint32_t)(m >> 32) : (uint32_t)m;
         return __builtin_amdgcn_ubfe(half, lane & 31u & ~(uint32_t)(G - 1), (uint32_t)G);
     }
-    __device__ static inline int shfl(int v, int src_lane_in_group) { return __shfl(v, src_lane_in_group, G); }
+    // value of lane src_lane_in_group of this group.  Four lanes are a DPP quad: a lane number
+    // that the compiler knows (the unrolled loops over slots) turns into one quad-broadcast move
+    // instead of a trip through the LDS permute unit.
+    __device__ static inline int shfl(int v, int src_lane_in_group)
+    {
+        if (G == 4 && __builtin_constant_p(src_lane_in_group)) {
+            switch (src_lane_in_group) {
+            case 0: return __builtin_amdgcn_mov_dpp(v, 0x00, 0xF, 0xF, true);
+            case 1: return __builtin_amdgcn_mov_dpp(v, 0x55, 0xF, 0xF, true);
+            case 2: return __builtin_amdgcn_mov_dpp(v, 0xAA, 0xF, 0xF, true);
+            default: return __builtin_amdgcn_mov_dpp(v, 0xFF, 0xF, 0xF, true);
+            }
+        }
+        return __shfl(v, src_lane_in_group, G);
+    }
 };
 
 // LDS traffic inside one wave is executed in order, so a group only needs the compiler kept
