@@ -117,7 +117,7 @@ void orc_default_config(orc_config *cfg)
     cfg->cap_plant = 10;
     cfg->atlas_seed = 0;
     cfg->worldgen = ORC_WORLDGEN_VALUE;
-    cfg->reserved = 0;
+    cfg->reset_mode = ORC_RESET_EXACT;
 }
 
 size_t orc_env_bytes(void) { return sizeof(orc_env); }
@@ -849,6 +849,46 @@ void orc_step_batch(orc_env *envs, const orc_config *cfg, const int32_t *actions
         orc_step(&envs[i], cfg, actions[i], &reward[i], &done[i]);
         if (obs) orc_observe(&envs[i], cfg, mode, (uint8_t *)obs + stride * (size_t)i);
     }
+}
+
+/* ---- optimistic resets (appendix "Optimistic Environment Resets") ---------------------------------
+ * The paper: with N workers only M << N new worlds are generated per step (one per 16 workers);
+ * the environments that need a reset sample without replacement from those M, and only if more
+ * than M finish in one step do some get the same world.  Readings: world j of the pool of batch
+ * step T is the ordinary generator run for (seed of environment 0, environment number 2^31 + j,
+ * episode T); the finished environments are taken in increasing number, the r-th of them (r from
+ * 0) gets world (shift_T + r) mod M, where shift_T is one uniform draw per step -- distinct worlds
+ * for up to M resets, repeats beyond; the environment keeps its own seed and counts its episode
+ * up, so everything random after the reset still differs between environments that share a world. */
+uint32_t orc_pool_slot(uint64_t pool_seed, uint32_t step_index, uint32_t rank, uint32_t n)
+{
+    uint32_t m = (uint32_t)n / ORC_POOL_RATIO ? (uint32_t)n / ORC_POOL_RATIO : 1u;
+    uint32_t shift = choice(philox_word(pool_seed, 0xFFFFFFFFu, 2, step_index, DOM_WORLDGEN, 0, 0), m);
+    return (shift + rank) % m;
+}
+
+void orc_step_batch_pool(orc_env *envs, const orc_config *cfg, const int32_t *actions, int mode, void *obs,
+                         float *reward, uint8_t *done, int n, uint32_t step_index)
+{
+    size_t stride = orc_obs_bytes(mode);
+    uint64_t pool_seed = envs[0].seed;
+    for (int i = 0; i < n; i++) orc_step_rules(&envs[i], cfg, actions[i], &reward[i], &done[i]);
+    uint32_t rank = 0;
+    for (int i = 0; i < n; i++) {
+        if (!done[i]) continue;
+        orc_env *e = &envs[i];
+        uint32_t slot = orc_pool_slot(pool_seed, step_index, rank++, (uint32_t)n);
+        uint64_t seed = e->seed;
+        uint32_t env = e->env, episode = e->episode + 1;
+        memset(e, 0, sizeof(*e));
+        e->seed = seed; e->env = env; e->episode = episode;
+        orc_worldgen_mode(e->map, pool_seed, 0x80000000u | slot, step_index, cfg->worldgen);
+        e->px = ORC_MAP / 2; e->py = ORC_MAP / 2;
+        e->dir = DIR_DOWN;
+        e->vit[V_HEALTH] = e->vit[V_FOOD] = e->vit[V_DRINK] = e->vit[V_ENERGY] = MAX_COUNT;
+    }
+    if (obs)
+        for (int i = 0; i < n; i++) orc_observe(&envs[i], cfg, mode, (uint8_t *)obs + stride * (size_t)i);
 }
 
 /* ---- level mutations (section "Craftax-1B: UED") ------------------------------------------------

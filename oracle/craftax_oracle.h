@@ -46,7 +46,7 @@ typedef struct {
     uint32_t cap_plant;      /* 0..10 */
     uint64_t atlas_seed;     /* pixel observations only */
     uint32_t worldgen;       /* ORC_WORLDGEN_VALUE (benchmark configurations) or ORC_WORLDGEN_PERLIN (the paper's noise) */
-    uint32_t reserved;
+    uint32_t reset_mode;     /* ORC_RESET_EXACT or ORC_RESET_POOL (appendix "Optimistic Environment Resets") */
 } orc_config;
 enum { ORC_WORLDGEN_VALUE = 0, ORC_WORLDGEN_PERLIN = 1 };
 
@@ -105,6 +105,16 @@ void orc_observe(const orc_env *e, const orc_config *cfg, int obs_mode, void *ob
 /* Batched helpers: loop the above over n environments, serially. */
 void orc_reset_batch(orc_env *envs, const orc_config *cfg, const uint64_t *seeds,
                      const uint32_t *env_ids, int n);
+/* Optimistic resets (appendix "Optimistic Environment Resets"): every step M = max(1, n / 16) new
+ * worlds are generated, and the environments that finished take theirs from that pool, sampled
+ * without replacement (with repeats only when more than M finish at once).  step_index: number
+ * of batch steps taken since the reset; envs[0] must be environment 0 (its seed seeds the pool). */
+#define ORC_RESET_EXACT 0u
+#define ORC_RESET_POOL 1u
+#define ORC_POOL_RATIO 16u
+void orc_step_batch_pool(orc_env *envs, const orc_config *cfg, const int32_t *actions, int obs_mode,
+                         void *obs, float *reward, uint8_t *done, int n, uint32_t step_index);
+uint32_t orc_pool_slot(uint64_t pool_seed, uint32_t step_index, uint32_t rank, uint32_t n);
 void orc_step_batch(orc_env *envs, const orc_config *cfg, const int32_t *actions, int obs_mode,
                     void *obs, float *reward, uint8_t *done, int n);
 void orc_observe_batch(const orc_env *envs, const orc_config *cfg, int obs_mode, void *obs, int n);

@@ -80,7 +80,7 @@ class Config(ctypes.Structure):
                 ("cap_zombie", ctypes.c_uint32), ("cap_cow", ctypes.c_uint32),
                 ("cap_skeleton", ctypes.c_uint32), ("cap_arrow", ctypes.c_uint32),
                 ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64),
-                ("worldgen", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("worldgen", ctypes.c_uint32), ("reset_mode", ctypes.c_uint32)]
 
 
 WORLDGEN_VALUE, WORLDGEN_PERLIN = 0, 1
@@ -149,6 +149,8 @@ def worldgen(seed: int, env: int, episode: int = 0, mode: int = WORLDGEN_VALUE) 
     return m
 
 
+RESET_EXACT, RESET_POOL = 0, 1
+POOL_RATIO = 16
 THETA_LEN = 374      # Perlin gradient angles of one Classic world: 2 x 25 + 4 x 81
 
 
@@ -159,6 +161,12 @@ def worldgen_theta(seed: int, env: int, episode: int, theta: np.ndarray) -> np.n
     m = np.zeros((64, 64), np.uint8)
     lib().orc_worldgen_theta(_p(m), ctypes.c_uint64(seed), ctypes.c_uint32(env), ctypes.c_uint32(episode), _p(th))
     return m
+
+
+def pool_slot(pool_seed: int, step_index: int, rank: int, n: int) -> int:
+    L = lib()
+    L.orc_pool_slot.restype = ctypes.c_uint32
+    return int(L.orc_pool_slot(ctypes.c_uint64(pool_seed), ctypes.c_uint32(step_index), ctypes.c_uint32(rank), ctypes.c_uint32(n)))
 
 
 def perlin_noise(lattice: np.ndarray, spacing: int, x: int, y: int) -> int:
@@ -174,6 +182,7 @@ class Oracle:
         self.n = n
         self.cfg = cfg if cfg is not None else default_config()
         self.obs_mode = obs_mode
+        self.steps = 0
         self.envs = np.zeros(n, dtype=ENV_DTYPE)
         self.obs = np.zeros((n, OBS_BYTES[obs_mode]), np.uint8)
         self.reward = np.zeros(n, np.float32)
@@ -182,6 +191,7 @@ class Oracle:
     def reset(self, seeds, env_ids=None):
         seeds = np.ascontiguousarray(seeds, dtype=np.uint64)
         ids = None if env_ids is None else np.ascontiguousarray(env_ids, dtype=np.uint32)
+        self.steps = 0                      # batch steps since the reset (names the pool of the optimistic resets)
         lib().orc_reset_batch(_p(self.envs), ctypes.byref(self.cfg), _p(seeds),
                               None if ids is None else _p(ids), self.n)
         return self.observe()
@@ -193,8 +203,14 @@ class Oracle:
     def step(self, actions, render: bool = True):
         a = np.ascontiguousarray(actions, dtype=np.int32)
         assert a.shape == (self.n,)
-        lib().orc_step_batch(_p(self.envs), ctypes.byref(self.cfg), _p(a), self.obs_mode,
-                             _p(self.obs) if render else None, _p(self.reward), _p(self.done), self.n)
+        if self.cfg.reset_mode == RESET_POOL:
+            lib().orc_step_batch_pool(_p(self.envs), ctypes.byref(self.cfg), _p(a), self.obs_mode,
+                                      _p(self.obs) if render else None, _p(self.reward), _p(self.done), self.n,
+                                      ctypes.c_uint32(self.steps))
+        else:
+            lib().orc_step_batch(_p(self.envs), ctypes.byref(self.cfg), _p(a), self.obs_mode,
+                                 _p(self.obs) if render else None, _p(self.reward), _p(self.done), self.n)
+        self.steps += 1
         return self.obs, self.reward, self.done
 
     def step_rules_one(self, i: int, action: int):

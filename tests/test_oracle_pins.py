@@ -1148,3 +1148,77 @@ def test_noise_mutation_draws_and_restart():
     o2.mutate_noise(again, ms, 5, 511)
     assert np.array_equal(again, theta) and o2.envs.tobytes() == o.envs.tobytes()
     assert theta.max() < 1024
+
+
+# --------------------------------------------------- optimistic resets (appendix "Optimistic Environment Resets") ----
+def test_optimistic_reset_tail_bound_of_the_paper():
+    """The appendix's arithmetic: 1,024 workers, one new world per 16 of them (64 per step), an
+    episode ending every 200 steps on average: more resets than worlds with probability < 1e-10."""
+    from scipy.stats import binom
+    assert 1024 // po.POOL_RATIO == 64
+    tail = binom.sf(64, 1024, 1.0 / 200.0)
+    assert 0.0 < tail < 1e-10
+    # and the slots handed out in one step are distinct exactly up to the pool size
+    for n, t in [(1024, 0), (1024, 7), (4096, 3), (160, 11)]:
+        m = n // 16
+        slots = [po.pool_slot(0xABCDEF, t, r, n) for r in range(m + 3)]
+        assert len(set(slots[:m])) == m and max(slots) < m
+        assert slots[m:] == slots[:3]                                 # more resets than worlds: worlds repeat
+    assert [po.pool_slot(5, 0, r, 8) for r in range(3)] == [0, 0, 0]  # fewer than 16 workers: a pool of one
+    shifts = {po.pool_slot(0xABCDEF, t, 0, 1024) for t in range(200)}
+    assert len(shifts) > 50                                           # the starting slot is drawn anew every step
+
+
+def test_optimistic_resets_hand_out_pool_worlds_in_env_order():
+    n = 64
+    cfg = po.default_config(reset_mode=po.RESET_POOL, max_episode_steps=1000)
+    exact = po.default_config(max_episode_steps=1000)
+    o, x = po.Oracle(n, cfg), po.Oracle(n, exact)
+    seeds = synth.seeds_for(n, 12)
+    o.reset(seeds); x.reset(seeds)
+    pool_seed = int(seeds[0])
+    # no episode ends: the two modes are the same
+    for t in range(5):
+        a = synth.actions(np.arange(n), t, "uniform", 1)
+        oo, orr, od = o.step(a); xo, xr, xd = x.step(a)
+        assert not od.any() and np.array_equal(oo, xo) and o.envs.tobytes() == x.envs.tobytes()
+    # three environments die in this step (health 0 is reached by the rules' own bookkeeping: starved and parched)
+    victims = [50, 3, 17]
+    for v in victims:
+        o.envs[v]["vit"][:] = [1, 0, 0, 0]
+        o.envs[v]["cnt"][3] = -30                                   # the recover counter is about to cost a health point
+    before = o.envs.copy()
+    a = np.zeros(n, np.int32)
+    obs, rew, done = o.step(a)
+    assert sorted(np.nonzero(done)[0].tolist()) == sorted(victims)
+    T = 5
+    for rank, v in enumerate(sorted(victims)):
+        e = o.envs[v]
+        slot = po.pool_slot(pool_seed, T, rank, n)
+        assert np.array_equal(e["map"].reshape(64, 64), po.worldgen(pool_seed, 0x80000000 | slot, T))
+        assert e["episode"] == before[v]["episode"] + 1 and e["seed"] == seeds[v] and e["env"] == v and e["t"] == 0
+        assert list(e["vit"]) == [9, 9, 9, 9] and (e["px"], e["py"]) == (32, 32) and not e["inv"].any()
+        assert np.array_equal(obs[v], o.observe_one(v))
+    assert len({po.pool_slot(pool_seed, T, r, n) for r in range(3)}) == 3    # 3 resets, pool of 4: no world twice
+    # the others went on untouched by the resets
+    y = po.Oracle(n, exact); y.envs[:] = before; y.step(a)
+    rest = [i for i in range(n) if i not in victims]
+    assert o.envs[rest].tobytes() == y.envs[rest].tobytes()
+
+
+def test_optimistic_resets_repeat_worlds_when_the_pool_runs_out():
+    n = 48                                                           # pool of 3
+    cfg = po.default_config(reset_mode=po.RESET_POOL, max_episode_steps=1)
+    o = po.Oracle(n, cfg)
+    seeds = synth.seeds_for(n, 2)
+    o.reset(seeds)
+    o.step(np.zeros(n, np.int32))                                    # every episode ends at once
+    maps = o.envs["map"].reshape(n, -1)
+    assert len({m.tobytes() for m in maps}) == 3
+    # environment i has rank i: worlds repeat with period 3
+    assert all(np.array_equal(maps[i], maps[i + 3]) for i in range(n - 3))
+    # environments that share a world still differ afterwards: their own seeds drive everything random
+    for t in range(1, 4):
+        o.step(synth.actions(np.arange(n), t, "uniform", 0))
+    assert np.all(o.envs["episode"] == 4)
+    assert len({o.envs[i]["seed"].tobytes() for i in range(n)}) == n
