@@ -105,7 +105,7 @@ typedef struct craftax_config {
     uint32_t cap_plant;          /* 0..10 */
     uint64_t atlas_seed;         /* seed of the synthetic tile atlas (pixel observations) */
     uint32_t worldgen;           /* CRAFTAX_WORLDGEN_*: the noise behind the Classic terrain rule */
-    uint32_t reserved;           /* 0 */
+    uint32_t reset_mode;         /* CRAFTAX_RESET_*: where the world of a new episode comes from */
 } craftax_config;
 
 /* World generation of variant CLASSIC.  VALUE: seeded integer value noise (the benchmark
@@ -114,6 +114,19 @@ typedef struct craftax_config {
  * evaluated in integers: 1024 directions, gradients in Q14, fade weights in Q16, every division a
  * floor.  Both feed the same field mix and thresholds.  Variant CRAFTAX accepts VALUE only. */
 enum { CRAFTAX_WORLDGEN_VALUE = 0, CRAFTAX_WORLDGEN_PERLIN = 1 };
+
+/* Where the world of a new episode comes from.  EXACT (default): every environment gets a world
+ * of its own, a function of (its seed, its number, its episode index), generated one episode
+ * ahead.  POOL: the paper's optimistic resets (appendix "Optimistic Environment Resets"), kept as
+ * an option for comparison: batch step T (counted from craftax_reset) offers a pool of
+ * M = max(1, n / 16) new worlds, world j being the generator run for (seed of environment 0,
+ * environment number 2^31 + j, episode T); the environments that finish in that step are taken
+ * in increasing number and the r-th of them gets world (shift_T + r) mod M, shift_T being one
+ * uniform draw per step: no world twice unless more than M finish at once.  An environment keeps
+ * its own seed and counts its episode up, so everything random after the reset still differs
+ * between environments that share a world.  The library generates only the pool worlds that are
+ * taken.  Variant CLASSIC only; craftax_rollout is not available in this mode. */
+enum { CRAFTAX_RESET_EXACT = 0, CRAFTAX_RESET_POOL = 1 };
 
 /* One environment in canonical form, used by export/import (4304 bytes, little endian).
  * Dead mob and plant slots are all zero.  Mob slots: 0-2 zombie, 3-5 cow, 6-8 skeleton,

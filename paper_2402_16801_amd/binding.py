@@ -27,6 +27,7 @@ EXPORTS = [
 
 
 THETA_LEN = 374      # angle offsets per Classic level (craftax_mutate_noise)
+RESET_EXACT, RESET_POOL = 0, 1
 
 
 class Config(ctypes.Structure):
@@ -34,7 +35,7 @@ class Config(ctypes.Structure):
                 ("max_episode_steps", ctypes.c_uint32), ("day_length", ctypes.c_uint32),
                 ("cap_zombie", ctypes.c_uint32), ("cap_cow", ctypes.c_uint32), ("cap_skeleton", ctypes.c_uint32),
                 ("cap_arrow", ctypes.c_uint32), ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64),
-                ("worldgen", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("worldgen", ctypes.c_uint32), ("reset_mode", ctypes.c_uint32)]
 
 
 # numpy views of the canonical dumps declared in include/craftax.h

@@ -155,7 +155,9 @@ struct Params {
     uint32_t max_episode_steps, day_length;
     uint32_t cap_zombie, cap_cow, cap_skeleton, cap_arrow, cap_plant;
     uint32_t worldgen;              // CRAFTAX_WORLDGEN_*
+    uint32_t reset_mode;            // CRAFTAX_RESET_*
 };
+constexpr uint32_t POOL_RATIO = 16, POOL_ENV = 0x80000000u;   // optimistic resets: environments per pool world; numbering of the pool's worlds
 
 // ---- lane groups --------------------------------------------------------------------------------
 // An environment is owned by G consecutive lanes of a wavefront (G = 4, 8 or 16, so 16, 8 or

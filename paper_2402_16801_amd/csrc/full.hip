@@ -605,6 +605,7 @@ bool config_ok(const craftax_config* c, std::string* why)
     if (c->cap_zombie > 3 || c->cap_cow > 3 || c->cap_skeleton > 2) { *why = "caps: melee 0..3, passive 0..3, ranged 0..2"; return false; }
     if (c->cap_plant > (uint32_t)NPLANT) { *why = "cap_plant must be 0..10"; return false; }
     if (c->max_episode_steps == 0) { *why = "max_episode_steps must be positive"; return false; }
+    if (c->reset_mode != CRAFTAX_RESET_EXACT) { *why = "the Craftax variant has exact resets only (reset_mode must be EXACT)"; return false; }
     if (c->worldgen != CRAFTAX_WORLDGEN_VALUE) { *why = "the Craftax variant has one world generator (worldgen must be VALUE)"; return false; }
     return true;
 }

@@ -689,3 +689,47 @@ def test_rollout_at_scale_sampled(cx):
     dumps = np.concatenate([sim.export_envs(int(i), 1) for i in ids])
     assert dumps.tobytes() == orc.envs.tobytes()
     sim.close()
+
+
+@pytest.mark.parametrize("lanes", [4, 16])
+def test_optimistic_pool_resets_match_the_oracle(cx, lanes):
+    """The paper's optimistic resets as an option (reset_mode POOL): finished environments take
+    their worlds from the step's pool in the order of their numbers; state and observations are
+    compared with the oracle after every step."""
+    R = po.RESET_POOL
+    # short episodes: several resets per step, every pool position in use over time
+    finished = run_parity(cx, 200, 60, po.OBS_SYM_U8_F32, "skewed", state_every=1, max_episode_steps=7, lanes=lanes, reset_mode=R)
+    assert finished > 200 * 6
+    # every episode ends at every step: 48 environments share a pool of 3 worlds
+    run_parity(cx, 48, 12, po.OBS_SYM_U8_I8, "uniform", state_every=1, max_episode_steps=1, lanes=lanes, reset_mode=R)
+    # a pool of one, a single environment, a ragged count, the flat and pixel layouts, Perlin worlds
+    run_parity(cx, 9, 20, po.OBS_SYM_F32, "uniform", state_every=1, max_episode_steps=3, lanes=lanes, reset_mode=R)
+    run_parity(cx, 1, 12, po.OBS_SYM_U8_F32, "uniform", state_every=1, max_episode_steps=2, lanes=lanes, reset_mode=R)
+    run_parity(cx, 131, 30, po.OBS_PIXELS_F32, "uniform", state_every=5, obs_every=3, max_episode_steps=5, lanes=lanes, reset_mode=R)
+    run_parity(cx, 70, 30, po.OBS_SYM_U8_F32, "skewed", state_every=1, max_episode_steps=4, lanes=lanes, reset_mode=R,
+               worldgen=po.WORLDGEN_PERLIN)
+    # natural deaths only (long cap): resets are rare and come from the pool of their step
+    run_parity(cx, 600, 250, po.OBS_SYM_U8_F32, "skewed", state_every=50, lanes=lanes, reset_mode=R)
+
+
+def test_optimistic_pool_worlds_and_refusals(cx):
+    import torch
+    n = 64
+    gcfg, ocfg = _cfgs(cx, po.OBS_SYM_U8_F32, reset_mode=po.RESET_POOL, max_episode_steps=1)
+    sim = _make_sim(cx, n, gcfg)
+    seeds = synth.seeds_for(n, 8)
+    sim.reset(seeds)
+    sim.step(torch.zeros(n, dtype=torch.int32, device=sim.device))
+    maps = sim.export_envs().view(po.ENV_DTYPE)["map"].reshape(n, 64, 64)
+    for i in range(n):     # all 64 finished: environment i has rank i, the pool holds 4 worlds
+        slot = po.pool_slot(int(seeds[0]), 0, i, n)
+        assert np.array_equal(maps[i], po.worldgen(int(seeds[0]), 0x80000000 | slot, 0)), f"world of env {i}"
+    assert len({m.tobytes() for m in maps}) == 4
+    d_acts = torch.zeros((2, n), dtype=torch.int32, device=sim.device)
+    d_rew = torch.zeros((2, n), dtype=torch.float32, device=sim.device)
+    d_done = torch.zeros((2, n), dtype=torch.uint8, device=sim.device)
+    with pytest.raises(cx.CraftaxError):                              # rollouts need exact resets
+        cx.craftax_rollout(sim.state, d_acts, 2, sim.obs, d_rew, d_done, n, sim.stream)
+    sim.close()
+    assert cx.craftax_state_bytes(cx.default_config(reset_mode=2), 8) == 0
+    assert cx.craftax_state_bytes(cx.default_config(cx.VARIANT_CRAFTAX, reset_mode=po.RESET_POOL), 8) == 0
