@@ -733,3 +733,32 @@ def test_optimistic_pool_worlds_and_refusals(cx):
     sim.close()
     assert cx.craftax_state_bytes(cx.default_config(reset_mode=2), 8) == 0
     assert cx.craftax_state_bytes(cx.default_config(cx.VARIANT_CRAFTAX, reset_mode=po.RESET_POOL), 8) == 0
+
+
+def test_optimistic_pool_resets_at_the_benchmark_size(cx):
+    """65,536 environments with reset_mode POOL and a short episode cap: thousands of resets per
+    step, more than the pool of 4,096 holds at the cap steps (worlds repeat); the oracle follows
+    every environment (ranks need all of them), states are compared on a strided sample."""
+    import torch
+    n, T = 65536, 10
+    gcfg, ocfg = _cfgs(cx, po.OBS_SYM_U8_F32, reset_mode=po.RESET_POOL, max_episode_steps=5)
+    sim = _make_sim(cx, n, gcfg)
+    orc = po.Oracle(n, ocfg)
+    seeds = synth.seeds_for(n, 77)
+    sim.reset(seeds); orc.reset(seeds)
+    ids = np.unique(np.concatenate([np.arange(0, n, 997), [n - 1, 4095, 4096, 4097]]))
+    d_acts = torch.empty((T, n), dtype=torch.int32, device=sim.device)
+    cx.craftax_synth_actions(d_acts, n, 0, T, 9, 1, sim.stream)
+    most = 0
+    for s in range(T):
+        obs, rew, done = sim.step(d_acts[s])
+        oobs, orew, odone = orc.step(synth.actions(np.arange(n), s, "skewed", 9), render=(s % 4 == 3))
+        assert np.array_equal(done.cpu().numpy(), odone), f"done at step {s}"
+        assert np.array_equal(rew.cpu().numpy().view(np.uint32), orew.view(np.uint32)), f"reward at step {s}"
+        most = max(most, int(odone.sum()))
+        if s % 4 == 3:
+            assert np.array_equal(obs.cpu().numpy(), oobs), f"observation at step {s}"
+        dumps = np.concatenate([sim.export_envs(int(i), 1) for i in ids])
+        assert dumps.tobytes() == orc.envs[ids].tobytes(), f"state at step {s}"
+    assert most > n // 16                                            # the pool did run out at least once
+    sim.close()
