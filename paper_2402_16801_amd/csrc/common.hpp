@@ -247,5 +247,13 @@ constexpr int LDS_FLAG = 134;                    // 1 = this environment's stage
 constexpr int LDS_WINPOS = 135;                  // rollout: bit 31 | py << 8 | px of the position the window was loaded for, or 0
 constexpr int LDS_ENV_DWORDS = 142;
 static_assert(LDS_VEC + 24 <= LDS_ENV_DWORDS, "per-environment LDS area overflows");
+// The layout above keeps the record intact while the observation is staged (the rollout kernel
+// carries records from step to step).  The single-step kernel has written its record back before
+// it renders, so there the scalar vector takes the record's place: 118 dwords per environment
+// (again distinct even banks for the environments of a wave), which lets five blocks of 64
+// environments share a compute unit's 160 KB instead of four.
+struct KeepLayout { static constexpr int VEC = LDS_VEC, FLAG = LDS_FLAG, STRIDE = LDS_ENV_DWORDS; };
+struct StepLayout { static constexpr int VEC = LDS_REC, FLAG = 110, STRIDE = 118; };
+static_assert(StepLayout::FLAG >= LDS_BITS + 42 && StepLayout::FLAG < StepLayout::STRIDE && REC_DWORDS >= 24, "single-step LDS layout");
 
 }  // namespace cx

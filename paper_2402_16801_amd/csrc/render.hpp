@@ -32,7 +32,7 @@ __device__ inline uint32_t spread4(uint32_t nibble) { return (nibble * 0x0020408
 // and the staging costs 166 bytes of LDS per environment instead of 1323.
 // One 16-byte chunk of a staged observation (byte layouts): chunks 0..82 expand 16 staged bits
 // each, the next 2 or 6 hold the scalars, the rest of the stride is zero.
-template <int OBS_MODE>
+template <int OBS_MODE, class LY = KeepLayout>
 __device__ __forceinline__ uint4 staged_chunk(const uint32_t* e, int c)
 {
     constexpr int NV = OBS_MODE == 0 ? VEC_CHUNKS_I8 : VEC_CHUNKS_F32;
@@ -41,7 +41,7 @@ __device__ __forceinline__ uint4 staged_chunk(const uint32_t* e, int c)
         return make_uint4(spread4(h & 15u), spread4((h >> 4) & 15u), spread4((h >> 8) & 15u), spread4(h >> 12));
     }
     if (c < CELL_CHUNKS + NV) {
-        const uint32_t* v = e + LDS_VEC + (c - CELL_CHUNKS) * 4;
+        const uint32_t* v = e + LY::VEC + (c - CELL_CHUNKS) * 4;
         return make_uint4(v[0], v[1], v[2], v[3]);
     }
     return make_uint4(0u, 0u, 0u, 0u);
@@ -53,7 +53,7 @@ __device__ __forceinline__ uint4 staged_chunk(const uint32_t* e, int c)
 // against streaming (non-temporal) ones they are 5 % faster here, the observation buffer being
 // rewritten every step.  With G = 4 a run serves two environments in
 // turn.  wave_env: LDS area of the wave's first environment; wave_obs: its observation.
-template <int G, int OBS_MODE>
+template <int G, int OBS_MODE, class LY = KeepLayout>
 __device__ __forceinline__ void flush_wave_observations(uint32_t* wave_env, uint8_t* __restrict__ wave_obs)
 {
     constexpr int RUN = G < 8 ? 8 : G, PASSES = RUN / G, STRIDE = obs_stride(OBS_MODE), NCHUNK = STRIDE / 16;
@@ -61,14 +61,14 @@ __device__ __forceinline__ void flush_wave_observations(uint32_t* wave_env, uint
 #pragma unroll
     for (int pass = 0; pass < PASSES; ++pass) {
         const int ei = run * PASSES + pass;                       // environment within the wave
-        const uint32_t* e = wave_env + ei * LDS_ENV_DWORDS;
-        if (!e[LDS_FLAG]) continue;
+        const uint32_t* e = wave_env + ei * LY::STRIDE;
+        if (!e[LY::FLAG]) continue;
         uint32_t* out = reinterpret_cast<uint32_t*>(wave_obs + (size_t)ei * STRIDE);
 #pragma unroll
         for (int it = 0; it < (NCHUNK + RUN - 1) / RUN; ++it) {
             const int c = it * RUN + j;
             if (c >= NCHUNK) break;
-            const uint4 v = staged_chunk<OBS_MODE>(e, c);
+            const uint4 v = staged_chunk<OBS_MODE, LY>(e, c);
             *reinterpret_cast<uint4*>(out + 4 * c) = v;
         }
     }
@@ -77,14 +77,17 @@ __device__ __forceinline__ void flush_wave_observations(uint32_t* wave_env, uint
 // FILL_VEC = false: the caller has already put the 22 scalars into the LDS vector area.
 // FLUSH = false: stop after staging (bits and scalars in LDS); the caller writes them out with
 // flush_wave_observations.
-template <int G, int OBS_MODE, bool FILL_VEC = true, bool FLUSH = true>
+// LY: where the scalars are staged.  With StepLayout they overwrite the record, which is read
+// completely (position, tables, inventory, vitals) before the first of them is written.
+template <int G, int OBS_MODE, bool FILL_VEC = true, bool FLUSH = true, class LY = KeepLayout>
 __device__ __forceinline__ void render_symbolic(int l, uint32_t* e, int mvx, int mvy, int woff, const Luts* __restrict__ luts,
                                        uint8_t* __restrict__ obs_out)
 {
     const uint32_t* rec = e + LDS_REC;
     const uint8_t* win = reinterpret_cast<const uint8_t*>(e + LDS_WIN);
     uint32_t* bits = e + LDS_BITS;
-    uint32_t* vec = e + LDS_VEC;
+    static_assert(FILL_VEC || LY::VEC != LDS_REC, "scalars supplied by the caller need an area of their own");
+    uint32_t* vec = e + LY::VEC;
 #pragma unroll
     for (int it = 0; it < (42 + G - 1) / G; ++it) if (l + it * G < 42) bits[l + it * G] = 0u;
     group_sync();
@@ -158,7 +161,7 @@ __device__ __forceinline__ void render_symbolic(int l, uint32_t* e, int mvx, int
         for (int it_i = 0; it_i < ((obs_stride(OBS_MODE) / 16) + G - 1) / G; ++it_i) {
             const int i = l + it_i * G;
             if (i >= (obs_stride(OBS_MODE) / 16)) break;
-            out[i] = staged_chunk<OBS_MODE>(e, i);
+            out[i] = staged_chunk<OBS_MODE, LY>(e, i);
         }
     } else {
         // float[1345]: four values per 16-byte store
