@@ -209,13 +209,16 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
 // ---------------------------------------------------------------------------------------------
 // rollout: several steps in one launch (see craftax_rollout).  A block keeps the records of its
 // four environments in LDS for the whole launch, every wavefront walks its environment through
-// the steps, and the block meets at a barrier once per step.  When episodes end in a step, the
-// whole block generates their next worlds on the spot, floor by floor (the other environments of
-// the block wait those few dozen microseconds; nothing is exchanged between blocks, so blocks
-// drift apart and the memory traffic of some overlaps the arithmetic of others).  At the end the
-// block writes the records back and generates, for every environment whose episode changed, the
-// spare world that the step kernel expects, tagged as written by launch 0.  Before the launch the
-// regeneration lists of the step kernel must be empty (the host runs a list-only launch first).
+// the steps, and the block meets at a barrier once per step.  Worlds stay one episode ahead as in
+// the step kernel, but the block generates them itself: an environment whose episode ends moves
+// into the spare world in its other map slot (ladders and potion map from the header, the start
+// window from the map), and the whole block then generates the world after it into the slot that
+// was left, floor by floor (the other environments of the block wait those few hundred
+// microseconds; nothing is exchanged between blocks, so blocks drift apart and the memory traffic
+// of some overlaps the arithmetic of others).  At the end the block writes the records back and
+// tags the spare worlds it wrote as written by launch 0, which is what the step kernel expects.
+// Before the launch the regeneration lists of the step kernel must be empty (the host runs a
+// list-only launch first); a spare world that is missing nonetheless is generated on the spot.
 template <bool F32>
 __global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
                                                        const Luts* __restrict__ luts, const int32_t* __restrict__ actions,
@@ -227,14 +230,15 @@ __global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ en
     __shared__ GenLayout s_layout;
     __shared__ uint32_t s_words[FLOORS + 1];
     __shared__ int s_ended[ENVS_PER_BLOCK];          // this step ended the episode of environment w
-    __shared__ uint32_t s_first_ep[ENVS_PER_BLOCK];  // episode at the start of the launch, if its spare world was complete
+    __shared__ int s_spare_ok[ENVS_PER_BLOCK];       // the world of the next episode is complete in the other map slot
+    __shared__ int s_changed[ENVS_PER_BLOCK];        // this launch has written a spare world for environment w
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
     const int env = blockIdx.x * ENVS_PER_BLOCK + w;
     const bool active = env < p.n;
     uint32_t* e = s_env + w * L_ENV_DWORDS;
     uint32_t* genv = envs + (size_t)(active ? env : 0) * ENV_DWORDS;
     if (active) e[L_REC + l] = genv[l];
-    if (l == 0) { s_ended[w] = 0; s_first_ep[w] = 0xFFFFFFFFu; }
+    if (l == 0) { s_ended[w] = 0; s_spare_ok[w] = 0; s_changed[w] = 0; }
     __syncthreads();
     if (active) {
         const uint32_t ep = uniu(e[L_REC + R_EPISODE]);
@@ -242,7 +246,7 @@ __global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ en
         if (l < NTAG) tag = tags[(size_t)env * NTAG + l];
         constexpr uint64_t ALL = (1ull << NTAG) - 1ull;
         const bool complete = (__ballot(l < NTAG && tag.x == ep + 1u) & ALL) == ALL;
-        if (l == 0 && complete) s_first_ep[w] = ep;
+        if (l == 0 && complete) s_spare_ok[w] = 1;
     }
 
     // Generates the world of episode `ep` of block-local environment ww into its map slot, all threads
@@ -304,12 +308,34 @@ __global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ en
             if (!s_ended[ww]) continue;
             uint32_t* ew = s_env + ww * L_ENV_DWORDS;
             const uint32_t ep1 = ew[L_REC + R_EPISODE] + 1u, lo = ew[L_REC + R_SEED_LO], hi = ew[L_REC + R_SEED_HI];
-            uint32_t* wgenv = envs + (size_t)(blockIdx.x * ENVS_PER_BLOCK + ww) * ENV_DWORDS;
+            const uint32_t wenv = (uint32_t)(blockIdx.x * ENVS_PER_BLOCK + ww);
+            uint32_t* wgenv = envs + (size_t)wenv * ENV_DWORDS;
             __syncthreads();
-            generate(ww, ep1, true);
-            // fresh record in LDS, empty mob tables in memory
-            if (tid < REC_DWORDS) ew[L_REC + tid] = fresh_record_word(tid, s_words, lo, hi, ep1);
-            if (tid < FLOORS * MOBTAB_DWORDS) wgenv[REC_DWORDS + tid] = 0u;
+            const bool waiting = s_spare_ok[ww] != 0;
+            if (waiting) {
+                // the world is waiting in the other slot: its ladders and potion map from the header,
+                // the window of its start position from the map
+                if (tid < FLOORS + 1) s_words[tid] = wgenv[SPARE_LADDER + tid];
+                if (tid >= 64 && tid < 128)
+                    load_window(tid - 64, maps + map_offset(wenv, ep1), 0, W / 2, W / 2, reinterpret_cast<uint8_t*>(ew + L_WB),
+                                reinterpret_cast<uint8_t*>(ew + L_WI));
+                __syncthreads();
+            }
+            // turn 0 (only if no world was waiting): the world of the new episode, on the spot; turn 1:
+            // the world after it, into the slot that has just been left, so that the next end of an
+            // episode finds it (and the step kernel after this launch)
+#pragma unroll 1
+            for (int turn = waiting ? 1 : 0; turn < 2; ++turn) {
+                if (turn == 1) {
+                    // fresh record in LDS, empty mob tables in memory
+                    if (tid < REC_DWORDS) ew[L_REC + tid] = fresh_record_word(tid, s_words, lo, hi, ep1);
+                    if (tid < FLOORS * MOBTAB_DWORDS) wgenv[REC_DWORDS + tid] = 0u;
+                    __syncthreads();
+                }
+                generate(ww, ep1 + (uint32_t)turn, turn == 0);
+            }
+            if (tid < FLOORS + 1) wgenv[SPARE_LADDER + tid] = s_words[tid];
+            if (tid == 0) { s_spare_ok[ww] = 1; s_changed[ww] = 1; }
             __syncthreads();
         }
         if (active) {
@@ -333,11 +359,13 @@ __global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ en
         if (wenv >= p.n) continue;
         uint32_t* ew = s_env + ww * L_ENV_DWORDS;
         const uint32_t ep = ew[L_REC + R_EPISODE];
-        if (s_first_ep[ww] == ep) continue;                       // its spare world is still the right one
+        if (s_spare_ok[ww] && !s_changed[ww]) continue;           // its spare world and tags are as the launch found them
         __syncthreads();
-        generate(ww, ep + 1u, false);
-        uint32_t* wgenv = envs + (size_t)wenv * ENV_DWORDS;
-        if (tid < FLOORS + 1) wgenv[SPARE_LADDER + tid] = s_words[tid];
+        if (!s_spare_ok[ww]) {
+            generate(ww, ep + 1u, false);
+            uint32_t* wgenv = envs + (size_t)wenv * ENV_DWORDS;
+            if (tid < FLOORS + 1) wgenv[SPARE_LADDER + tid] = s_words[tid];
+        }
         if (tid < NTAG) tags[(size_t)wenv * NTAG + tid] = make_uint2(ep + 1u, 0u);
         __syncthreads();
     }
