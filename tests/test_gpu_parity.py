@@ -762,3 +762,49 @@ def test_optimistic_pool_resets_at_the_benchmark_size(cx):
         assert dumps.tobytes() == orc.envs[ids].tobytes(), f"state at step {s}"
     assert most > n // 16                                            # the pool did run out at least once
     sim.close()
+
+
+@pytest.mark.parametrize("what", ["rollout", "pool_step"])
+def test_rollout_and_pool_step_captured_in_a_graph(cx, what):
+    """craftax_rollout (two launches) and a step with optimistic resets (step + reset-list kernel)
+    captured in HIP graphs and replayed, the actions refilled between the replays, with eager work
+    and synchronisation in between; every replay is checked against the oracle."""
+    import torch
+    n, T = 300, 17
+    rollout = what == "rollout"
+    gcfg, ocfg = _cfgs(cx, po.OBS_SYM_U8_F32, max_episode_steps=11, reset_mode=po.RESET_EXACT if rollout else po.RESET_POOL)
+    sim = _make_sim(cx, n, gcfg, None)
+    orc = po.Oracle(n, ocfg)
+    seeds = synth.seeds_for(n, 33)
+    sim.reset(seeds); orc.reset(seeds)
+    steps = T if rollout else 1
+    a_buf = torch.zeros((steps, n), dtype=torch.int32, device=sim.device)
+    d_rew = torch.zeros((steps, n), dtype=torch.float32, device=sim.device)
+    d_done = torch.zeros((steps, n), dtype=torch.uint8, device=sim.device)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            if rollout:
+                cx.craftax_rollout(sim.state, a_buf, T, sim.obs, d_rew, d_done, n, torch.cuda.current_stream())
+            else:
+                cx.craftax_step(sim.state, a_buf[0], sim.obs, d_rew[0], d_done[0], n, torch.cuda.current_stream())
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    assert sim.export_envs().tobytes() == orc.envs.tobytes()          # capturing executes nothing
+    t = 0
+    for r in range(9 if rollout else 40):
+        acts = np.stack([synth.actions(np.arange(n), t + s, "skewed", 2) for s in range(steps)]).astype(np.int32)
+        a_buf.copy_(torch.as_tensor(acts, device=sim.device))
+        graph.replay()
+        torch.cuda.synchronize()
+        for s in range(steps):
+            oobs, orew, odone = orc.step(acts[s])
+            assert np.array_equal(d_done[s].cpu().numpy(), odone), (r, s)
+            assert np.array_equal(d_rew[s].cpu().numpy().view(np.uint32), orew.view(np.uint32)), (r, s)
+        t += steps
+        assert np.array_equal(sim.obs.cpu().numpy(), oobs), r
+        assert sim.export_envs().tobytes() == orc.envs.tobytes(), r
+    sim.close()
