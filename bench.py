@@ -30,6 +30,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+# The paper's own speed figures (its table of steps per second): whole PPO training runs, networks and
+# updates included, on another machine.  Context for a reader, not a baseline for vs_baseline.
+PAPER_CONTEXT = {
+    "note": "steps/s of complete PPO training runs (environment + learner), 1x RTX 4090, 4,096 workers; context only",
+    "craftax_classic_symbolic_ppo_sps": 405618,
+    "craftax_symbolic_ppo_sps": 266961,
+}
 OBS_ALG_BYTES = 1323 + 22 * 4  # uint8 cells + fp32 scalars actually produced per env-step
 
 
@@ -314,6 +321,7 @@ def main():
                                "rollout_ms_per_step": full["also"]["rollout_ms_per_step"]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(8192, min(K, 1000), args.kind)
+    out["paper_context"] = PAPER_CONTEXT
     print(json.dumps(out))
 
 
