@@ -213,7 +213,7 @@ constexpr int L_LIGHT = 512;                     // 28 dwords: light level per v
 constexpr int L_VEC = 540;                       // 52 dwords: the 51 scalars and a zero
 constexpr int L_SPARE_WB = 592;                  // 44 dwords: block window of the start position of the spare world
 constexpr int L_SPARE_WI = 636;                  // 44 dwords: its item/light window
-constexpr int L_SPARE_TAG = 680;                 // 54 dwords: the 27 (episode, launch) tags of the spare world
+constexpr int L_SPARE_TAG = 680;                 // 54 dwords reserved; the 9 (episode, launch) tags of the spare world use 18
 constexpr int L_SPARE_HDR = 734;                 // 10 dwords: ladders and potion map of the spare world
 constexpr int L_ENV_DWORDS = 744;
 constexpr int ENVS_PER_BLOCK = 4, BLOCK = 256;
