@@ -23,6 +23,7 @@ using la::counter;
 using la::ENTRY_VOID;
 using la::NSUB;
 
+constexpr int EAGER_SPARE_ENVS = 8192;   // up to here a step fetches the spare world's start window in advance (see kf_step)
 constexpr int RESET_SLOTS = 64;    // environments served at once by kf_reset_list (nine blocks each)
 constexpr int REGEN_BLOCKS = 256;  // regeneration blocks at the head of the step grid: with 1,024 step blocks (4,096 environments) they fill the chip exactly
 
@@ -92,7 +93,13 @@ static_assert(LAT_TOTAL * 2 <= 128 * 4 && sizeof(GenLayout) <= (512 - 128) * 4 &
 // ---------------------------------------------------------------------------------------------
 // step: one wavefront per environment, four environments per block; the grid starts with the
 // regeneration blocks for the episodes that ended in the previous launch.
-template <bool F32>
+// EAGER: the window of the spare world's start position is fetched in every step, with the current
+// window, so that an episode that ends switches worlds without a further trip to memory.  With a
+// few thousand environments the launch ends when its slowest block ends, and that trip would sit
+// on exactly those blocks (+0.7 us per launch at 4,096 environments); with tens of thousands the
+// kernel is bound by instruction issue and the hundred instructions per step cost more than the
+// rare trip (255 -> 216 us per launch at 65,536 environments).
+template <bool F32, bool EAGER>
 __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
                                                 const Luts* __restrict__ luts, const int32_t* __restrict__ actions,
                                                 uint8_t* __restrict__ obs, float* __restrict__ reward,
@@ -140,7 +147,7 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
         for (int it = 0; it < 3; ++it) {
             const int i = l + 64 * it;
             sw[it] = 0u;
-            if (i < WIN_ROWS * WIN_COLS) {
+            if (EAGER && i < WIN_ROWS * WIN_COLS) {
                 const int r = i / WIN_COLS, c = i - r * WIN_COLS;
                 const int x = W / 2 - WIN_COLS / 2 + c, y = W / 2 - WIN_ROWS / 2 + r;
                 sw[it] = (uint32_t)spare[block_off(0, x, y)] | ((uint32_t)spare[il_off(0, x, y)] << 8);
@@ -152,7 +159,7 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
 #pragma unroll
             for (int it = 0; it < 3; ++it) {
                 const int i = l + 64 * it;
-                if (i < WIN_ROWS * WIN_COLS) {
+                if (EAGER && i < WIN_ROWS * WIN_COLS) {
                     const int r = i / WIN_COLS, c = i - r * WIN_COLS;
                     reinterpret_cast<uint8_t*>(e + L_SPARE_WB)[r * WIN_PITCH + c] = (uint8_t)sw[it];
                     reinterpret_cast<uint8_t*>(e + L_SPARE_WI)[r * WIN_PITCH + c] = (uint8_t)(sw[it] >> 8);
@@ -178,7 +185,12 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
                 // potion map, all mob tables empty, window of the start position from the other slot
                 wave_sync();
                 e[L_REC + l] = fresh_record_word(l, e + L_SPARE_HDR, lo, hi, ep + 1u);
-                if (l < WIN_ROWS * WIN_PITCH / 4) { e[L_WB + l] = e[L_SPARE_WB + l]; e[L_WI + l] = e[L_SPARE_WI + l]; }
+                if (EAGER) {
+                    if (l < WIN_ROWS * WIN_PITCH / 4) { e[L_WB + l] = e[L_SPARE_WB + l]; e[L_WI + l] = e[L_SPARE_WI + l]; }
+                } else {
+                    load_window(l, maps + map_offset((uint32_t)env, ep + 1u), 0, W / 2, W / 2, reinterpret_cast<uint8_t*>(e + L_WB),
+                                reinterpret_cast<uint8_t*>(e + L_WI));
+                }
 #pragma unroll
                 for (int it = 0; it < (FLOORS * MOBTAB_DWORDS + 63) / 64; ++it) {
                     const int i = l + 64 * it;
@@ -764,16 +776,20 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
     const int rb = FLOORS * n < REGEN_BLOCKS ? FLOORS * n : REGEN_BLOCKS;    // persistent blocks serving a queue: any number works
     const dim3 grid((unsigned)(rb + sb)), rgrid((unsigned)(n < RESET_SLOTS ? n : RESET_SLOTS) * FLOORS);
     const bool slow = p.max_episode_steps == 1u;   // the only way an episode can end before its spare world exists
+    const bool eager = n <= EAGER_SPARE_ENVS;
     if (cfg->obs_mode == CRAFTAX_OBS_PIXELS_F32) {
         // the step runs without rendering; the picture is drawn from the state it leaves
-        hipLaunchKernelGGL(kf_step<false>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, (uint8_t*)nullptr, reward, done, q.ls, p, rb);
+        if (eager) hipLaunchKernelGGL((kf_step<false, true>), grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, (uint8_t*)nullptr, reward, done, q.ls, p, rb);
+        else hipLaunchKernelGGL((kf_step<false, false>), grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, (uint8_t*)nullptr, reward, done, q.ls, p, rb);
         if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, (uint8_t*)nullptr, q.ls);
         if (o != nullptr) hipLaunchKernelGGL(kf_pixels, dim3((unsigned)n), dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, o);
     } else if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) {
-        hipLaunchKernelGGL(kf_step<true>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb);
+        if (eager) hipLaunchKernelGGL((kf_step<true, true>), grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb);
+        else hipLaunchKernelGGL((kf_step<true, false>), grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb);
         if (slow) hipLaunchKernelGGL(kf_reset_list<true>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls);
     } else {
-        hipLaunchKernelGGL(kf_step<false>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb);
+        if (eager) hipLaunchKernelGGL((kf_step<false, true>), grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb);
+        else hipLaunchKernelGGL((kf_step<false, false>), grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb);
         if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls);
     }
     return check_launch("craftax_step", err);
@@ -790,7 +806,7 @@ int rollout(void* state, const craftax_config* cfg, int n, const int32_t* action
     const int rb = FLOORS * n < REGEN_BLOCKS ? FLOORS * n : REGEN_BLOCKS;
     const dim3 drain((unsigned)rb), grid((unsigned)((n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK));
     // a launch of regeneration blocks only empties the lists of the step kernel and completes every spare world
-    hipLaunchKernelGGL(kf_step<false>, drain, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, (const int32_t*)nullptr, (uint8_t*)nullptr,
+    hipLaunchKernelGGL((kf_step<false, false>), drain, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, (const int32_t*)nullptr, (uint8_t*)nullptr,
                        (float*)nullptr, (uint8_t*)nullptr, q.ls, p, rb);
     if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32)
         hipLaunchKernelGGL(kf_rollout<true>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls.tags, p, steps);
