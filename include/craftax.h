@@ -93,7 +93,7 @@ enum {
 
 typedef struct craftax_config {
     uint32_t abi_version;        /* CRAFTAX_ABI_VERSION */
-    uint32_t variant;            /* CRAFTAX_VARIANT_CLASSIC */
+    uint32_t variant;            /* CRAFTAX_VARIANT_* */
     uint32_t obs_mode;           /* CRAFTAX_OBS_* */
     uint32_t max_episode_steps;  /* episode is cut (done = 1) when this many steps were taken */
     uint32_t day_length;         /* even, 2..1024 */
@@ -227,7 +227,8 @@ int craftax_step(void *state, const int32_t *actions, void *obs, float *reward, 
  * written after every step into the same buffer obs (DEVICE, n strides; it ends up holding the
  * observation after the last step; NULL skips rendering).  A thread block keeps its environments
  * on chip for the whole launch and blocks advance independently.  Both variants, symbolic
- * observations only (CRAFTAX_E_CONFIG for a pixel mode).  Other errors as for craftax_step;
+ * observations and exact resets only (CRAFTAX_E_CONFIG for a pixel mode or reset_mode POOL).
+ * Other errors as for craftax_step;
  * CRAFTAX_E_COUNT also for steps <= 0. */
 int craftax_rollout(void *state, const int32_t *actions, int steps, void *obs, float *reward,
                     uint8_t *done, int n, void *stream);
