@@ -26,5 +26,22 @@ def build_library(verbose: bool = False) -> str:
     return OUT
 
 
+EXAMPLE_SRC = os.path.join(os.path.dirname(_PKG), "examples", "step_from_c.c")
+EXAMPLE_OUT = os.path.join(os.path.dirname(_PKG), "examples", "step_from_c")
+
+
+def build_example() -> str:
+    """The plain-C consumer of the ABI: gcc, the HIP runtime and the library, nothing else."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-O2", "-std=c11", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"), "-o", EXAMPLE_OUT, EXAMPLE_SRC,
+           "-L", _PKG, "-l:libcraftax_hip.so", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN/../paper_2402_16801_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("gcc failed:\n" + res.stderr)
+    return EXAMPLE_OUT
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_example())
