@@ -162,6 +162,8 @@ void cf_default_config(cf_config *cfg)
     cfg->cap_melee = 3; cfg->cap_ranged = 2; cfg->cap_passive = 3;
     cfg->cap_plant = 10;
     cfg->atlas_seed = 0;
+    cfg->worldgen = ORC_WORLDGEN_VALUE;
+    cfg->reserved = 0;
 }
 size_t cf_env_bytes(void) { return sizeof(cf_env); }
 size_t cf_obs_bytes(int mode)
@@ -219,17 +221,23 @@ static void set_ladders(cf_env *e, int f, int ux, int uy, int dx, int dy)
     }
 }
 
-static void gen_overworld(cf_env *e)
+/* The open floors take their fields from value noise (the benchmark configurations) or, as the
+ * paper's appendix "World Generation" has it, from Perlin noise over the same lattices. */
+typedef uint32_t (*noise_fn)(const uint16_t *, int, int, int, int);
+static noise_fn noise_of(uint32_t mode) { return mode == ORC_WORLDGEN_PERLIN ? orc_perlin_noise : orc_value_noise; }
+
+static void gen_overworld(cf_env *e, uint32_t mode)
 {
     const int f = 0;
+    const noise_fn noise = noise_of(mode);
     uint16_t lat[2 * 16 + 4 * 49];
     for (uint32_t i = 0; i < 2 * 16 + 4 * 49; i++) lat[i] = wg_u16(e, 0, i);
     const uint16_t *w16 = lat, *m16 = lat + 16, *w8 = lat + 32, *m8 = w8 + 49, *c8 = m8 + 49, *f8 = c8 + 49;
     for (int y = 0; y < CF_W; y++)
         for (int x = 0; x < CF_W; x++) {
-            int W = (int)((3u * orc_value_noise(w16, 4, 16, x, y) + orc_value_noise(w8, 7, 8, x, y)) >> 2);
-            int M = (int)((3u * orc_value_noise(m16, 4, 16, x, y) + orc_value_noise(m8, 7, 8, x, y)) >> 2);
-            int C = (int)orc_value_noise(c8, 7, 8, x, y), F = (int)orc_value_noise(f8, 7, 8, x, y);
+            int W = (int)((3u * noise(w16, 4, 16, x, y) + noise(w8, 7, 8, x, y)) >> 2);
+            int M = (int)((3u * noise(m16, 4, 16, x, y) + noise(m8, 7, 8, x, y)) >> 2);
+            int C = (int)noise(c8, 7, 8, x, y), F = (int)noise(f8, 7, 8, x, y);
             int u = wg_u16(e, 1, (uint32_t)cell(x, y));
             int d = imax(iabs(x - CF_W / 2), iabs(y - CF_W / 2));
             if (d < 10) { int bias = (10 - d) * 2500; W = imax(0, W - bias); M = imax(0, M - bias); }
@@ -288,15 +296,16 @@ static void gen_dungeon(cf_env *e, int f)
     set_ladders(e, f, cx[0], cy[0], cx[7], cy[7]);
 }
 
-static void gen_cave(cf_env *e, int f)
+static void gen_cave(cf_env *e, int f, uint32_t mode)
 {
+    const noise_fn noise = noise_of(mode);
     uint16_t lat[2 * 49];
     for (uint32_t i = 0; i < 2 * 49; i++) lat[i] = wg_u16(e, (uint32_t)f * 4, i);
     const uint16_t *c8 = lat, *f8 = lat + 49;
     const uint8_t open = f == 6 ? B_FIRE_GRASS : (f == 7 ? B_ICE_GRASS : B_PATH);
     for (int y = 0; y < CF_W; y++)
         for (int x = 0; x < CF_W; x++) {
-            int C = (int)orc_value_noise(c8, 7, 8, x, y), F = (int)orc_value_noise(f8, 7, 8, x, y);
+            int C = (int)noise(c8, 7, 8, x, y), F = (int)noise(f8, 7, 8, x, y);
             int u = wg_u16(e, (uint32_t)f * 4 + 1, (uint32_t)cell(x, y));
             uint8_t b;
             if (C > 31000) {            /* open cave */
@@ -338,22 +347,23 @@ static void gen_graveyard(cf_env *e)
     set_ladders(e, f, 24, 42, 0, 0);
 }
 
-void cf_worldgen_floor(cf_env *e, int f)
+void cf_worldgen_floor_mode(cf_env *e, int f, uint32_t mode)
 {
     memset(e->item[f], IT_NONE, CF_CELLS);
     memset(e->light[f], FLOOR_LIT[f] ? MAX_LIGHT : 0, CF_CELLS);
-    if (f == 0) gen_overworld(e);
+    if (f == 0) gen_overworld(e, mode);
     else if (f == 1 || f == 3 || f == 4) gen_dungeon(e, f);
     else if (f == 8) gen_graveyard(e);
-    else gen_cave(e, f);
+    else gen_cave(e, f, mode);
 }
+void cf_worldgen_floor(cf_env *e, int f) { cf_worldgen_floor_mode(e, f, ORC_WORLDGEN_VALUE); }
 
-static void reset_episode(cf_env *e, uint32_t episode)
+static void reset_episode(cf_env *e, const cf_config *cfg, uint32_t episode)
 {
     uint64_t seed = e->seed; uint32_t env = e->env;
     memset(e, 0, sizeof(*e));
     e->seed = seed; e->env = env; e->episode = episode;
-    for (int f = 0; f < CF_FLOORS; f++) cf_worldgen_floor(e, f);
+    for (int f = 0; f < CF_FLOORS; f++) cf_worldgen_floor_mode(e, f, cfg->worldgen);
     e->px = CF_W / 2; e->py = CF_W / 2; e->dir = 4;
     for (int i = 0; i < 5; i++) e->vit[i] = 9;
     e->dex = e->str = e->intel = 1;
@@ -368,10 +378,9 @@ static void reset_episode(cf_env *e, uint32_t episode)
 }
 void cf_reset(cf_env *e, const cf_config *cfg, uint64_t seed, uint32_t env)
 {
-    (void)cfg;
     memset(e, 0, sizeof(*e));
     e->seed = seed; e->env = env;
-    reset_episode(e, 0);
+    reset_episode(e, cfg, 0);
 }
 
 /* ---- helpers ------------------------------------------------------------------------------ */
@@ -873,7 +882,7 @@ void cf_step_rules(cf_env *e, const cf_config *cfg, int32_t action, float *rewar
 void cf_step(cf_env *e, const cf_config *cfg, int32_t action, float *reward, uint8_t *done)
 {
     cf_step_rules(e, cfg, action, reward, done);
-    if (*done) reset_episode(e, e->episode + 1);
+    if (*done) reset_episode(e, cfg, e->episode + 1);
 }
 
 /* ---- observation (appendix "Observation Space") -------------------------------------------------

@@ -47,6 +47,8 @@ typedef struct {
     uint32_t cap_melee, cap_ranged, cap_passive;   /* 3, 2, 3 */
     uint32_t cap_plant;
     uint64_t atlas_seed;          /* seed of the synthetic tile atlas (pixel observations) */
+    uint32_t worldgen;            /* ORC_WORLDGEN_VALUE or ORC_WORLDGEN_PERLIN: the noise behind the open floors */
+    uint32_t reserved;
 } cf_config;
 
 typedef struct {
@@ -93,6 +95,7 @@ size_t cf_obs_bytes(int mode);
 void cf_default_config(cf_config *cfg);
 int cf_achievement_reward(int id);
 void cf_worldgen_floor(cf_env *e, int floor);    /* uses e->seed, e->env, e->episode */
+void cf_worldgen_floor_mode(cf_env *e, int floor, uint32_t mode);   /* mode: ORC_WORLDGEN_VALUE or ORC_WORLDGEN_PERLIN */
 void cf_reset(cf_env *e, const cf_config *cfg, uint64_t seed, uint32_t env);
 void cf_step_rules(cf_env *e, const cf_config *cfg, int32_t action, float *reward, uint8_t *done);
 void cf_step(cf_env *e, const cf_config *cfg, int32_t action, float *reward, uint8_t *done);

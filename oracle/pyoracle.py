@@ -72,7 +72,8 @@ assert FULL_ENV_DTYPE.itemsize == 63432
 class FullConfig(ctypes.Structure):
     _fields_ = [("max_episode_steps", ctypes.c_uint32), ("day_length", ctypes.c_uint32),
                 ("cap_melee", ctypes.c_uint32), ("cap_ranged", ctypes.c_uint32),
-                ("cap_passive", ctypes.c_uint32), ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64)]
+                ("cap_passive", ctypes.c_uint32), ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64),
+                ("worldgen", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 class Config(ctypes.Structure):

@@ -5,6 +5,8 @@ from __future__ import annotations
 import collections
 import os
 
+import ctypes
+
 import numpy as np
 import pytest
 
@@ -219,9 +221,10 @@ def reachable(block, start):
     return seen
 
 
-def test_worldgen_floors_structure_and_ladder_connectivity():
+@pytest.mark.parametrize("mode", [po.WORLDGEN_VALUE, po.WORLDGEN_PERLIN])
+def test_worldgen_floors_structure_and_ladder_connectivity(mode):
     n = 48
-    o = fresh(n, seed=100)
+    o = fresh(n, seed=100, worldgen=mode)
     allowed = {
         0: {"GRASS", "WATER", "STONE", "TREE", "PATH", "COAL", "IRON", "DIAMOND", "SAND", "LAVA"},
         1: {"WALL", "PATH", "CHEST", "FOUNTAIN"},
@@ -260,6 +263,51 @@ def test_worldgen_floors_structure_and_ladder_connectivity():
         assert (e["block"][4] == B["ENCH_FIRE"]).sum() <= 1 and (e["block"][1] == B["CHEST"]).sum() >= 1
     for f in range(9):
         assert seen_blocks[f] == {B[k] for k in allowed[f]} - ({B["PATH"]} if f in (6, 7) and B["PATH"] not in seen_blocks[f] else set()), f
+
+
+def test_perlin_mode_changes_the_open_floors_only_and_follows_the_noise():
+    """worldgen = PERLIN (appendix "World Generation"): the overworld and the four cave floors take
+    their fields from Perlin noise over the same lattices, dungeons, vault and graveyard do not
+    change; auto-resets use the mode; the cave rule is checked against the noise function itself."""
+    n = 6
+    v, p = fresh(n, seed=31), fresh(n, seed=31, worldgen=po.WORLDGEN_PERLIN)
+    for i in range(n):
+        for f in range(9):
+            same = np.array_equal(v.envs[i]["block"][f], p.envs[i]["block"][f])
+            assert same == (f in (1, 3, 4, 8)), (i, f)
+        assert np.array_equal(v.envs[i]["ladder_down"][1:], p.envs[i]["ladder_down"][1:])       # layouts come from their own draws
+        assert np.array_equal(v.envs[i]["potion_effect"], p.envs[i]["potion_effect"])
+    # floor 2 (gnomish mines): open where the C field exceeds 31000, lattice = u16 numbers 0..48 of stream 8
+    seed, env = int(synth.seeds_for(n, 31)[2]), 2
+    nums = []
+    for block in range(7):
+        w = po.philox([env, 2 * 4, 0, (1 << 16) | block], [seed & 0xFFFFFFFF, seed >> 32])
+        for x in w:
+            nums += [x & 0xFFFF, x >> 16]
+    c8 = np.array(nums[:49], np.uint16).reshape(7, 7)
+    blk = p.envs[2]["block"][2]
+    ux, uy = (int(t) for t in p.envs[2]["ladder_up"][2]); dx, dy = (int(t) for t in p.envs[2]["ladder_down"][2])
+    checked = 0
+    for y in range(0, 48, 3):
+        for x in range(0, 48, 3):
+            if min(max(abs(x - ux), abs(y - uy)), max(abs(x - dx), abs(y - dy))) <= 1 or y == uy or x == dx:
+                continue                                   # ladder surroundings and the corridor between the ladders
+            C = po.perlin_noise(c8, 8, x, y)
+            if abs(C - 31000) > 200:
+                assert (blk[y, x] in (B["PATH"], B["STALAGMITE"])) == (C > 31000), (x, y, C)
+                checked += 1
+    assert checked > 150
+    # an episode that ends regenerates in the same mode
+    e = p.envs[0]
+    e["vit"][HEALTH] = 1; e["cnt"][3] = -30; e["vit"][FOOD] = 0
+    _, _, d = p.step(np.zeros(n, np.int32))
+    assert d[0] == 1 and e["episode"] == 1
+    q = po.FullOracle(1, po.full_default_config(worldgen=po.WORLDGEN_PERLIN))
+    q.reset(synth.seeds_for(n, 31)[:1])
+    q.envs[0]["episode"] = 1
+    for f in range(9):
+        po.lib().cf_worldgen_floor_mode(ctypes.c_void_p(q.envs.ctypes.data), f, po.WORLDGEN_PERLIN)
+    assert np.array_equal(q.envs[0]["block"], e["block"])
 
 
 def test_worldgen_is_a_pure_function_of_seed_env_episode():
