@@ -104,15 +104,17 @@ typedef struct craftax_config {
                                     (cap_skeleton, 0..2) creatures; projectiles are always 3+3 */
     uint32_t cap_plant;          /* 0..10 */
     uint64_t atlas_seed;         /* seed of the synthetic tile atlas (pixel observations) */
-    uint32_t worldgen;           /* CRAFTAX_WORLDGEN_*: the noise behind the Classic terrain rule */
+    uint32_t worldgen;           /* CRAFTAX_WORLDGEN_*: the noise behind the terrain rules */
     uint32_t reset_mode;         /* CRAFTAX_RESET_*: where the world of a new episode comes from */
 } craftax_config;
 
-/* World generation of variant CLASSIC.  VALUE: seeded integer value noise (the benchmark
+/* The noise of world generation.  VALUE: seeded integer value noise (the benchmark
  * configurations).  PERLIN: Perlin gradient noise as in the paper (appendix "World Generation":
  * unit gradients at random lattice angles, corner dot products blended with 6t^5 - 15t^4 + 10t^3),
  * evaluated in integers: 1024 directions, gradients in Q14, fade weights in Q16, every division a
- * floor.  Both feed the same field mix and thresholds.  Variant CRAFTAX accepts VALUE only. */
+ * floor.  Both feed the same field mix and thresholds.  In variant CRAFTAX the choice applies to the
+ * floors drawn from noise fields (the overworld and the four cave floors); the room floors and the
+ * boss floor use no noise and are the same in both. */
 enum { CRAFTAX_WORLDGEN_VALUE = 0, CRAFTAX_WORLDGEN_PERLIN = 1 };
 
 /* Where the world of a new episode comes from.  EXACT (default): every environment gets a world

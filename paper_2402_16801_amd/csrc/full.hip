@@ -50,7 +50,7 @@ __device__ inline void publish_world(uint32_t* __restrict__ genv, const GenLayou
 // ---------------------------------------------------------------------------------------------
 // reset of every environment: one block per (environment, episode 0 or 1, floor)
 __global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
-                                                       const uint64_t* __restrict__ seeds, Lists ls)
+                                                       const uint64_t* __restrict__ seeds, Lists ls, const uint32_t* __restrict__ perlin_cs)
 {
     if (blockIdx.x == 0) la::reset_counters(ls);
     __shared__ uint16_t s_lat[LAT_TOTAL];
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ e
     const int f = blockIdx.x % FLOORS;
     const uint64_t seed = seeds[env];
     const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
-    worldgen_floor_block(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f);
+    worldgen_floor_block<GEN_THREADS, true>(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f, nullptr, nullptr, 0, GEN_THREADS, perlin_cs);
     if (f == 0) publish_world(envs + (size_t)env * ENV_DWORDS, s_layout, lo, hi, ep, ep == 0u, s_words);
     if (ep == 1u && threadIdx.x == 0) ls.tags[(size_t)env * NTAG + f] = make_uint2(1u, 0u);
 }
@@ -70,8 +70,9 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ e
 // each; block rb of nrb takes units rb, rb + nrb, ...  The blocks stand at the head of the grid:
 // a step launch holds as many of them as the chip has room for beside the step blocks, so every
 // unit starts with the launch and none waits for a block that is scheduled late.
+template <bool PERLIN>
 __device__ __forceinline__ void regeneration_queue(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, const Lists& ls,
-                                                   uint32_t seq, uint32_t* lds, int regen_blocks)
+                                                   uint32_t seq, uint32_t* lds, int regen_blocks, const uint32_t* __restrict__ perlin_cs)
 {
     uint16_t* s_lat = reinterpret_cast<uint16_t*>(lds);
     GenLayout& L = *reinterpret_cast<GenLayout*>(lds + 128);
@@ -83,7 +84,8 @@ __device__ __forceinline__ void regeneration_queue(uint32_t* __restrict__ envs, 
         const uint4 entry = la::queue_entry(ls, seq, s_prefix, u / FLOORS);
         const int f = (int)(u % FLOORS);
         if (entry.x == ENTRY_VOID) continue;
-        worldgen_floor_block<BLOCK>(maps + map_offset(entry.x, entry.w), s_lat, L, entry.y, entry.z, entry.x, entry.w, f);
+        worldgen_floor_block<BLOCK, PERLIN>(maps + map_offset(entry.x, entry.w), s_lat, L, entry.y, entry.z, entry.x, entry.w, f, nullptr, nullptr,
+                                            0, GEN_THREADS, PERLIN ? perlin_cs : nullptr);
         if (f == 0) publish_world(envs + (size_t)entry.x * ENV_DWORDS, L, entry.y, entry.z, entry.w, false, s_words);
         if (threadIdx.x == 0) ls.tags[(size_t)entry.x * NTAG + f] = make_uint2(entry.w, seq);
     }
@@ -99,7 +101,9 @@ static_assert(LAT_TOTAL * 2 <= 128 * 4 && sizeof(GenLayout) <= (512 - 128) * 4 &
 // on exactly those blocks (+0.7 us per launch at 4,096 environments); with tens of thousands the
 // kernel is bound by instruction issue and the hundred instructions per step cost more than the
 // rare trip (255 -> 216 us per launch at 65,536 environments).
-template <bool F32, bool EAGER>
+// PERLIN: the regeneration blocks generate Perlin worlds (a kernel of its own, so that the value-noise
+// kernel carries none of that code).
+template <bool F32, bool EAGER, bool PERLIN>
 __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
                                                 const Luts* __restrict__ luts, const int32_t* __restrict__ actions,
                                                 uint8_t* __restrict__ obs, float* __restrict__ reward,
@@ -109,7 +113,7 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
     if ((int)blockIdx.x < regen_blocks) {
         const la::Ticket ticket = la::enter_launch_queue(ls, s_env + 528);
-        regeneration_queue(envs, maps, ls, ticket.seq, s_env, regen_blocks);
+        regeneration_queue<PERLIN>(envs, maps, ls, ticket.seq, s_env, regen_blocks, luts->perlin_cs);
         la::leave_launch(ls, ticket);
         return;
     }
@@ -231,7 +235,7 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
 // tags the spare worlds it wrote as written by launch 0, which is what the step kernel expects.
 // Before the launch the regeneration lists of the step kernel must be empty (the host runs a
 // list-only launch first); a spare world that is missing nonetheless is generated on the spot.
-template <bool F32>
+template <bool F32, bool PERLIN>
 __global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
                                                        const Luts* __restrict__ luts, const int32_t* __restrict__ actions,
                                                        uint8_t* __restrict__ obs, float* __restrict__ reward,
@@ -270,9 +274,10 @@ __global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ en
         uint8_t* slot = maps + map_offset(wenv, ep);
 #pragma unroll 1
         for (int f = 0; f < FLOORS; ++f) {
-            worldgen_floor_block<BLOCK>(slot, s_lat, s_layout, lo, hi, wenv, ep, f,
-                                        start ? reinterpret_cast<uint8_t*>(ew + L_WB) : nullptr,
-                                        start ? reinterpret_cast<uint8_t*>(ew + L_WI) : nullptr);
+            worldgen_floor_block<BLOCK, PERLIN>(slot, s_lat, s_layout, lo, hi, wenv, ep, f,
+                                                start ? reinterpret_cast<uint8_t*>(ew + L_WB) : nullptr,
+                                                start ? reinterpret_cast<uint8_t*>(ew + L_WI) : nullptr, 0, GEN_THREADS,
+                                                PERLIN ? luts->perlin_cs : nullptr);
             if (f == 0) {                             // the layout of floor 0 describes the whole world
                 if (tid < FLOORS + 1) s_words[tid] = layout_word(s_layout, tid);
                 __syncthreads();
@@ -389,7 +394,7 @@ __global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ en
 // kernel, and only when the episode cap is 1.
 template <bool F32>
 __global__ __launch_bounds__(GEN_THREADS) void kf_reset_list(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
-                                                            const Luts* __restrict__ luts, uint8_t* __restrict__ obs, Lists ls)
+                                                            const Luts* __restrict__ luts, uint8_t* __restrict__ obs, Lists ls, int perlin)
 {
     __shared__ uint16_t s_lat[LAT_TOTAL];
     __shared__ GenLayout s_layout;
@@ -404,8 +409,9 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_reset_list(uint32_t* __restric
         const uint4 entry = ls.slow[i];
         if (entry.x == ENTRY_VOID) continue;
         const uint32_t env = entry.x, lo = entry.y, hi = entry.z, ep = entry.w;
-        worldgen_floor_block(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f,
-                             reinterpret_cast<uint8_t*>(s_env + L_WB), reinterpret_cast<uint8_t*>(s_env + L_WI));
+        worldgen_floor_block<GEN_THREADS, true>(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f,
+                                                reinterpret_cast<uint8_t*>(s_env + L_WB), reinterpret_cast<uint8_t*>(s_env + L_WI), 0, GEN_THREADS,
+                                                perlin ? luts->perlin_cs : nullptr);
         if (f == 0) {
             publish_world(envs + (size_t)env * ENV_DWORDS, s_layout, lo, hi, ep, true, s_words);
             if (tid < REC_DWORDS) s_env[L_REC + tid] = fresh_record_word(tid, s_words, lo, hi, ep);
@@ -446,7 +452,8 @@ __global__ __launch_bounds__(BLOCK) void kf_observe(const uint32_t* __restrict__
 }
 
 // after an import: the world of the episode after the imported one, into the spare slot
-__global__ __launch_bounds__(GEN_THREADS) void kf_import_spare(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, Lists ls, int first)
+__global__ __launch_bounds__(GEN_THREADS) void kf_import_spare(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, Lists ls, int first,
+                                                                const uint32_t* __restrict__ perlin_cs)
 {
     __shared__ uint16_t s_lat[LAT_TOTAL];
     __shared__ GenLayout s_layout;
@@ -455,7 +462,7 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_import_spare(uint32_t* __restr
     const int f = blockIdx.x % FLOORS;
     uint32_t* genv = envs + (size_t)env * ENV_DWORDS;
     const uint32_t ep = genv[R_EPISODE] + 1u, lo = genv[R_SEED_LO], hi = genv[R_SEED_HI];
-    worldgen_floor_block(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f);
+    worldgen_floor_block<GEN_THREADS, true>(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f, nullptr, nullptr, 0, GEN_THREADS, perlin_cs);
     if (f == 0) publish_world(genv, s_layout, lo, hi, ep, false, s_words);
     if (threadIdx.x == 0) ls.tags[(size_t)env * NTAG + f] = make_uint2(ep, 0u);
 }
@@ -646,7 +653,7 @@ bool config_ok(const craftax_config* c, std::string* why)
     if (c->cap_plant > (uint32_t)NPLANT) { *why = "cap_plant must be 0..10"; return false; }
     if (c->max_episode_steps == 0) { *why = "max_episode_steps must be positive"; return false; }
     if (c->reset_mode != CRAFTAX_RESET_EXACT) { *why = "the Craftax variant has exact resets only (reset_mode must be EXACT)"; return false; }
-    if (c->worldgen != CRAFTAX_WORLDGEN_VALUE) { *why = "the Craftax variant has one world generator (worldgen must be VALUE)"; return false; }
+    if (c->worldgen > CRAFTAX_WORLDGEN_PERLIN) { *why = "unknown worldgen"; return false; }
     return true;
 }
 
@@ -685,6 +692,12 @@ static void build_luts(const craftax_config* c, Luts* L)
     for (int i = 0; i < 100; ++i) L->sqrt10[i] = (float)(std::sqrt((double)i) / 10.0);
     for (int i = 0; i < 32; ++i) L->tenth[i] = (float)((double)i / 10.0);
     for (int i = 0; i < 32; ++i) L->light20[i] = (float)((double)i / 20.0);
+    // unit gradients of the 1024 Perlin directions in Q14, rounded to nearest
+    for (int a = 0; a < 1024; ++a) {
+        const double turn = 6.283185307179586476925286766559 * (double)a / 1024.0;
+        const int16_t c16 = (int16_t)std::lround(std::cos(turn) * 16384.0), s16 = (int16_t)std::lround(std::sin(turn) * 16384.0);
+        L->perlin_cs[a] = (uint32_t)(uint16_t)c16 | ((uint32_t)(uint16_t)s16 << 16);
+    }
     if (c->obs_mode != CRAFTAX_OBS_PIXELS_F32) return;
     // tile atlas: word idx of stream s is word idx % 4 of Philox block (0, s, 0, ATLAS | idx / 4)
     // under the atlas seed; streams 8 blocks, 9 items, 10 creatures, 11 player, 12 icons, 13 masks
@@ -731,7 +744,13 @@ static Params make_params(const craftax_config* c, int n)
     Params p;
     p.n = n; p.max_episode_steps = c->max_episode_steps; p.day_length = c->day_length;
     p.cap_melee = c->cap_zombie; p.cap_ranged = c->cap_skeleton; p.cap_passive = c->cap_cow; p.cap_plant = c->cap_plant;
+    p.worldgen = c->worldgen;
     return p;
+}
+// the gradient table for the kernels that choose the noise at run time: null = value noise
+static const uint32_t* gradients(const craftax_config* c, const Ptrs& q)
+{
+    return c->worldgen == CRAFTAX_WORLDGEN_PERLIN ? q.luts->perlin_cs : nullptr;
 }
 static int check_launch(const char* what, std::string* err)
 {
@@ -761,8 +780,18 @@ int state_init(void* state, const craftax_config* cfg, int n, void* stream, std:
 int reset(void* state, const craftax_config* cfg, int n, const uint64_t* seeds, void* stream, std::string* err)
 {
     const Ptrs q = pointers(state, make_header(cfg, n));
-    hipLaunchKernelGGL(kf_reset, dim3((unsigned)n * 2 * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, seeds, q.ls);
+    hipLaunchKernelGGL(kf_reset, dim3((unsigned)n * 2 * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, seeds, q.ls, gradients(cfg, q));
     return check_launch("craftax_reset", err);
+}
+
+// one launch of the step kernel: the instance for this spare-world policy and this noise
+template <bool F32>
+static void launch_step(bool eager, bool perlin, dim3 grid, hipStream_t st, const Ptrs& q, const int32_t* actions, uint8_t* o, float* reward,
+                        uint8_t* done, const Params& p, int rb)
+{
+    auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb); };
+    if (perlin) { if (eager) go(kf_step<F32, true, true>); else go(kf_step<F32, false, true>); }
+    else { if (eager) go(kf_step<F32, true, false>); else go(kf_step<F32, false, false>); }
 }
 
 int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, void* obs, float* reward, uint8_t* done,
@@ -777,20 +806,18 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
     const dim3 grid((unsigned)(rb + sb)), rgrid((unsigned)(n < RESET_SLOTS ? n : RESET_SLOTS) * FLOORS);
     const bool slow = p.max_episode_steps == 1u;   // the only way an episode can end before its spare world exists
     const bool eager = n <= EAGER_SPARE_ENVS;
+    const int perlin = cfg->worldgen == CRAFTAX_WORLDGEN_PERLIN ? 1 : 0;
     if (cfg->obs_mode == CRAFTAX_OBS_PIXELS_F32) {
         // the step runs without rendering; the picture is drawn from the state it leaves
-        if (eager) hipLaunchKernelGGL((kf_step<false, true>), grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, (uint8_t*)nullptr, reward, done, q.ls, p, rb);
-        else hipLaunchKernelGGL((kf_step<false, false>), grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, (uint8_t*)nullptr, reward, done, q.ls, p, rb);
-        if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, (uint8_t*)nullptr, q.ls);
+        launch_step<false>(eager, perlin != 0, grid, st, q, actions, nullptr, reward, done, p, rb);
+        if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, (uint8_t*)nullptr, q.ls, perlin);
         if (o != nullptr) hipLaunchKernelGGL(kf_pixels, dim3((unsigned)n), dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, o);
     } else if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) {
-        if (eager) hipLaunchKernelGGL((kf_step<true, true>), grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb);
-        else hipLaunchKernelGGL((kf_step<true, false>), grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb);
-        if (slow) hipLaunchKernelGGL(kf_reset_list<true>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls);
+        launch_step<true>(eager, perlin != 0, grid, st, q, actions, o, reward, done, p, rb);
+        if (slow) hipLaunchKernelGGL(kf_reset_list<true>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls, perlin);
     } else {
-        if (eager) hipLaunchKernelGGL((kf_step<false, true>), grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb);
-        else hipLaunchKernelGGL((kf_step<false, false>), grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb);
-        if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls);
+        launch_step<false>(eager, perlin != 0, grid, st, q, actions, o, reward, done, p, rb);
+        if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls, perlin);
     }
     return check_launch("craftax_step", err);
 }
@@ -806,12 +833,11 @@ int rollout(void* state, const craftax_config* cfg, int n, const int32_t* action
     const int rb = FLOORS * n < REGEN_BLOCKS ? FLOORS * n : REGEN_BLOCKS;
     const dim3 drain((unsigned)rb), grid((unsigned)((n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK));
     // a launch of regeneration blocks only empties the lists of the step kernel and completes every spare world
-    hipLaunchKernelGGL((kf_step<false, false>), drain, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, (const int32_t*)nullptr, (uint8_t*)nullptr,
-                       (float*)nullptr, (uint8_t*)nullptr, q.ls, p, rb);
-    if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32)
-        hipLaunchKernelGGL(kf_rollout<true>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls.tags, p, steps);
-    else
-        hipLaunchKernelGGL(kf_rollout<false>, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls.tags, p, steps);
+    const bool perlin = cfg->worldgen == CRAFTAX_WORLDGEN_PERLIN;
+    launch_step<false>(false, perlin, drain, st, q, nullptr, nullptr, nullptr, nullptr, p, rb);
+    auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls.tags, p, steps); };
+    if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) { if (perlin) go(kf_rollout<true, true>); else go(kf_rollout<true, false>); }
+    else { if (perlin) go(kf_rollout<false, true>); else go(kf_rollout<false, false>); }
     return check_launch("craftax_rollout", err);
 }
 
@@ -839,7 +865,7 @@ int import_envs(void* state, const craftax_config* cfg, int n, int first, int co
     const Ptrs q = pointers(state, make_header(cfg, n));
     hipLaunchKernelGGL(kf_import, dim3(count), dim3(BLOCK), 0, (hipStream_t)stream, q.envs, q.maps, q.ls,
                        static_cast<const craftax_full_env_dump*>(dumps), first, make_params(cfg, n));
-    hipLaunchKernelGGL(kf_import_spare, dim3((unsigned)count * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, q.ls, first);
+    hipLaunchKernelGGL(kf_import_spare, dim3((unsigned)count * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, q.ls, first, gradients(cfg, q));
     return check_launch("craftax_import_envs", err);
 }
 

@@ -179,6 +179,7 @@ struct Luts {
     // (t: 0..4 items, 5..44 creatures, 45 the player).
     float atlas[127 * 300];
     uint16_t mask[46][10];
+    uint32_t perlin_cs[1024];       // unit gradient of direction a: cos (low half) and sin (high half) in Q14, as int16
 };
 constexpr int AT_ITEM = 37, AT_CRE = 42, AT_PLAYER = 82, AT_ICON = 83, AT_TILES = 127;
 constexpr int MASK_CRE = 5, MASK_PLAYER = 45;
@@ -197,6 +198,7 @@ struct Params {
     int n;
     uint32_t max_episode_steps, day_length;
     uint32_t cap_melee, cap_ranged, cap_passive, cap_plant;
+    uint32_t worldgen;              // CRAFTAX_WORLDGEN_*
 };
 
 // ---- per-environment LDS area (dword offsets) ----------------------------------------------------

@@ -179,11 +179,16 @@ __device__ inline void make_cave_ladders(GenLayout& L, int f, const U4& r)
 // bytes.  s_lat, L: LDS scratch.  Ends with a block barrier.
 // first_run, runs: the part of the floor this call generates (a block of fewer than `runs` threads
 // takes several passes).
-template <int NT = GEN_THREADS>
+// perlin_cs (with CAN_PERLIN): the gradient table; the fields of the overworld and of the caves are
+// then Perlin noise over the same lattices (appendix "World Generation") instead of value noise.
+// A kernel instantiated without CAN_PERLIN carries no code for it.
+template <int NT = GEN_THREADS, bool CAN_PERLIN = false>
 __device__ __forceinline__ void worldgen_floor_block(uint8_t* __restrict__ maps, uint16_t* s_lat, GenLayout& L, uint32_t lo, uint32_t hi,
                                             uint32_t env, uint32_t episode, int f, uint8_t* start_wb = nullptr,
-                                            uint8_t* start_wi = nullptr, int first_run = 0, int runs = GEN_THREADS)
+                                            uint8_t* start_wi = nullptr, int first_run = 0, int runs = GEN_THREADS,
+                                            const uint32_t* __restrict__ perlin_cs = nullptr)
 {
+    const bool perlin = CAN_PERLIN && perlin_cs != nullptr;
     static_assert(NT >= 64, "the layout phase uses the first wavefront");
     const int tid0 = threadIdx.x;
     // Layout phase, all in the first wavefront and with one Philox call for the whole wave: every
@@ -263,7 +268,19 @@ __device__ __forceinline__ void worldgen_floor_block(uint8_t* __restrict__ maps,
 #pragma unroll 1
         for (int j = 0; j < 4; ++j) one(j);
     };
-    if (f == 0) {
+    if (CAN_PERLIN && perlin && f == 0) {
+        cells([&](int j) {
+            const int Wn = (int)((3u * cx::perlin<16>(s_lat, 4, perlin_cs, x + j, y) + cx::perlin<8>(s_lat + 32, 7, perlin_cs, x + j, y)) >> 2);
+            const int Mn = (int)((3u * cx::perlin<16>(s_lat + 16, 4, perlin_cs, x + j, y) + cx::perlin<8>(s_lat + 81, 7, perlin_cs, x + j, y)) >> 2);
+            put(j, classify_overworld(L, Wn, Mn, (int)cx::perlin<8>(s_lat + 130, 7, perlin_cs, x + j, y),
+                                      (int)cx::perlin<8>(s_lat + 179, 7, perlin_cs, x + j, y), x + j, y, draw(j)));
+        });
+    } else if (CAN_PERLIN && perlin && is_cave(f)) {
+        cells([&](int j) {
+            put(j, classify_cave(L, f, (int)cx::perlin<8>(s_lat, 7, perlin_cs, x + j, y), (int)cx::perlin<8>(s_lat + 49, 7, perlin_cs, x + j, y),
+                                 x + j, y, draw(j)));
+        });
+    } else if (f == 0) {
         const Field8 w16 = field16(s_lat, x, y), m16 = field16(s_lat + 16, x, y);
         const Field8 w8 = field8(s_lat + 32, x, y), m8 = field8(s_lat + 81, x, y), c8 = field8(s_lat + 130, x, y), f8 = field8(s_lat + 179, x, y);
         cells([&](int j) {

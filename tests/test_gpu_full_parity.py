@@ -186,6 +186,53 @@ def test_full_float_layout(cx):
     run_full(cx, 16, 150, obs_mode=2, kind="uniform")
 
 
+def test_full_perlin_worlds(cx):
+    """The Perlin option for the open floors (appendix "World Generation"): 96 fresh worlds byte
+    for byte, and they are not the value-noise worlds."""
+    n = 96
+    seeds = synth.seeds_for(n, 77)
+    gcfg, ocfg = _cfgs(cx, 1, worldgen=po.WORLDGEN_PERLIN)
+    sim = cx.Craftax(n, gcfg)
+    orc = po.FullOracle(n, ocfg)
+    assert np.array_equal(sim.reset(seeds).cpu().numpy(), orc.reset(seeds))
+    compare_state(sim, orc, np.arange(n), "reset")
+    plain = po.FullOracle(n, po.full_default_config())
+    plain.reset(seeds)
+    differ = (plain.envs["block"] != orc.envs["block"]).reshape(n, 9, -1).any(axis=2)
+    assert differ[:, [0, 2, 5, 6, 7]].all() and not differ[:, [1, 3, 4, 8]].any()
+    sim.close()
+
+
+def test_full_perlin_episodes_every_generation_path(cx):
+    """Perlin worlds through every place a world is generated: the regeneration blocks of the step
+    kernel (short episodes), the slow path (one-step episodes), the rollout kernel and the spare
+    world made after an import of another episode index."""
+    import torch
+    P = po.WORLDGEN_PERLIN
+    finished, _, _ = run_full(cx, 40, 240, kind="skewed", max_episode_steps=23, state_every=23, worldgen=P)
+    assert finished >= 40 * 8
+    run_full(cx, 13, 12, kind="uniform", state_every=1, max_episode_steps=1, worldgen=P)
+    assert _rollout_full(cx, 37, 1, "skewed", pre=5, steps=50, post=8, max_episode_steps=11, worldgen=P) > 37 * 3
+    _rollout_full(cx, 6, 2, "uniform", pre=1, steps=5, post=2, max_episode_steps=1, worldgen=P)
+    n = 12
+    gcfg, ocfg = _cfgs(cx, 1, max_episode_steps=50, worldgen=P)
+    sim = cx.Craftax(n, gcfg)
+    orc = po.FullOracle(n, ocfg)
+    seeds = synth.seeds_for(n, 31)
+    sim.reset(seeds); orc.reset(seeds)
+    orc.envs["episode"] += np.arange(n, dtype=orc.envs["episode"].dtype) + 2
+    orc.envs["t"][:] = 49
+    sim.import_envs(orc.envs.copy())
+    for s in range(3):
+        a = synth.actions(np.arange(n), s, "uniform", 2, 43)
+        obs, rew, done = sim.step(torch.as_tensor(a, device=sim.device))
+        oobs, orew, odone = orc.step(a)
+        assert np.array_equal(done.cpu().numpy(), odone) and odone.all() == (s == 0)
+        assert np.array_equal(obs.cpu().numpy(), oobs)
+        compare_state(sim, orc, np.arange(n), f"step {s} after the import")
+    sim.close()
+
+
 @pytest.mark.parametrize("n", [1, 3, 5, 130])
 def test_full_ragged_counts(cx, n):
     run_full(cx, n, 120, kind="skewed", seed_base=50 + n)
