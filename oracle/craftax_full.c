@@ -226,12 +226,20 @@ static void set_ladders(cf_env *e, int f, int ux, int uy, int dx, int dy)
 typedef uint32_t (*noise_fn)(const uint16_t *, int, int, int, int);
 static noise_fn noise_of(uint32_t mode) { return mode == ORC_WORLDGEN_PERLIN ? orc_perlin_noise : orc_value_noise; }
 
-static void gen_overworld(cf_env *e, uint32_t mode)
+/* theta (may be NULL): the level's angle offsets for this floor's lattices, in 1024ths of a turn;
+ * the angle of a lattice point is the upper ten bits of its number (section "Craftax-1B: UED",
+ * noise mutation). */
+static uint16_t turned(uint16_t number, const uint16_t *theta, uint32_t i)
+{
+    return theta ? (uint16_t)(number + ((theta[i] & 1023u) << 6)) : number;
+}
+
+static void gen_overworld(cf_env *e, uint32_t mode, const uint16_t *theta)
 {
     const int f = 0;
     const noise_fn noise = noise_of(mode);
-    uint16_t lat[2 * 16 + 4 * 49];
-    for (uint32_t i = 0; i < 2 * 16 + 4 * 49; i++) lat[i] = wg_u16(e, 0, i);
+    uint16_t lat[CF_THETA_OVERWORLD];
+    for (uint32_t i = 0; i < CF_THETA_OVERWORLD; i++) lat[i] = turned(wg_u16(e, 0, i), theta, i);
     const uint16_t *w16 = lat, *m16 = lat + 16, *w8 = lat + 32, *m8 = w8 + 49, *c8 = m8 + 49, *f8 = c8 + 49;
     for (int y = 0; y < CF_W; y++)
         for (int x = 0; x < CF_W; x++) {
@@ -296,11 +304,11 @@ static void gen_dungeon(cf_env *e, int f)
     set_ladders(e, f, cx[0], cy[0], cx[7], cy[7]);
 }
 
-static void gen_cave(cf_env *e, int f, uint32_t mode)
+static void gen_cave(cf_env *e, int f, uint32_t mode, const uint16_t *theta)
 {
     const noise_fn noise = noise_of(mode);
-    uint16_t lat[2 * 49];
-    for (uint32_t i = 0; i < 2 * 49; i++) lat[i] = wg_u16(e, (uint32_t)f * 4, i);
+    uint16_t lat[CF_THETA_CAVE];
+    for (uint32_t i = 0; i < CF_THETA_CAVE; i++) lat[i] = turned(wg_u16(e, (uint32_t)f * 4, i), theta, i);
     const uint16_t *c8 = lat, *f8 = lat + 49;
     const uint8_t open = f == 6 ? B_FIRE_GRASS : (f == 7 ? B_ICE_GRASS : B_PATH);
     for (int y = 0; y < CF_W; y++)
@@ -347,23 +355,39 @@ static void gen_graveyard(cf_env *e)
     set_ladders(e, f, 24, 42, 0, 0);
 }
 
-void cf_worldgen_floor_mode(cf_env *e, int f, uint32_t mode)
+/* Where the angles of floor f stand in a level's vector: the overworld's six lattices first, then
+ * the two lattices of each cave floor in floor order; -1 for a floor without noise. */
+static int theta_offset(int f)
 {
+    switch (f) {
+    case 0: return 0;
+    case 2: return CF_THETA_OVERWORLD;
+    case 5: return CF_THETA_OVERWORLD + CF_THETA_CAVE;
+    case 6: return CF_THETA_OVERWORLD + 2 * CF_THETA_CAVE;
+    case 7: return CF_THETA_OVERWORLD + 3 * CF_THETA_CAVE;
+    default: return -1;
+    }
+}
+static void worldgen_floor(cf_env *e, int f, uint32_t mode, const uint16_t *theta)
+{
+    const uint16_t *th = theta && theta_offset(f) >= 0 ? theta + theta_offset(f) : NULL;
     memset(e->item[f], IT_NONE, CF_CELLS);
     memset(e->light[f], FLOOR_LIT[f] ? MAX_LIGHT : 0, CF_CELLS);
-    if (f == 0) gen_overworld(e, mode);
+    if (f == 0) gen_overworld(e, mode, th);
     else if (f == 1 || f == 3 || f == 4) gen_dungeon(e, f);
     else if (f == 8) gen_graveyard(e);
-    else gen_cave(e, f, mode);
+    else gen_cave(e, f, mode, th);
 }
-void cf_worldgen_floor(cf_env *e, int f) { cf_worldgen_floor_mode(e, f, ORC_WORLDGEN_VALUE); }
+void cf_worldgen_floor_mode(cf_env *e, int f, uint32_t mode) { worldgen_floor(e, f, mode, NULL); }
+void cf_worldgen_floor(cf_env *e, int f) { worldgen_floor(e, f, ORC_WORLDGEN_VALUE, NULL); }
+void cf_worldgen_floor_theta(cf_env *e, int f, const uint16_t *theta) { worldgen_floor(e, f, ORC_WORLDGEN_PERLIN, theta); }
 
-static void reset_episode(cf_env *e, const cf_config *cfg, uint32_t episode)
+static void start_episode(cf_env *e, const cf_config *cfg, uint32_t episode, const uint16_t *theta)
 {
     uint64_t seed = e->seed; uint32_t env = e->env;
     memset(e, 0, sizeof(*e));
     e->seed = seed; e->env = env; e->episode = episode;
-    for (int f = 0; f < CF_FLOORS; f++) cf_worldgen_floor_mode(e, f, cfg->worldgen);
+    for (int f = 0; f < CF_FLOORS; f++) worldgen_floor(e, f, cfg->worldgen, theta);
     e->px = CF_W / 2; e->py = CF_W / 2; e->dir = 4;
     for (int i = 0; i < 5; i++) e->vit[i] = 9;
     e->dex = e->str = e->intel = 1;
@@ -376,6 +400,7 @@ static void reset_episode(cf_env *e, const cf_config *cfg, uint32_t episode)
         uint8_t tmp = e->potion_effect[i]; e->potion_effect[i] = e->potion_effect[j]; e->potion_effect[j] = tmp;
     }
 }
+static void reset_episode(cf_env *e, const cf_config *cfg, uint32_t episode) { start_episode(e, cfg, episode, NULL); }
 void cf_reset(cf_env *e, const cf_config *cfg, uint64_t seed, uint32_t env)
 {
     memset(e, 0, sizeof(*e));
@@ -1074,4 +1099,21 @@ int cf_mutate_swap(cf_env *e, uint64_t mutation_seed, uint32_t round, int restri
         return (int)k + 1;
     }
     return 0;
+}
+
+/* Noise mutation (section "Craftax-1B: UED"), same reading as for Classic: the level is the vector
+ * of the Perlin angles of every noise lattice of the world (theta_offset above gives the order);
+ * element i gets a uniform integer offset in [-amplitude, amplitude] (1024ths of a turn) from u16
+ * number i of Philox stream (env, round, 1, MUTATE) under the mutation seed; all nine floors of
+ * the current episode are generated again from the new angles (the floors without noise come out
+ * as they were) and the episode starts over.  Needs cfg->worldgen == PERLIN. */
+void cf_mutate_noise(cf_env *e, const cf_config *cfg, uint16_t *theta, uint64_t mutation_seed, uint32_t round, uint32_t amplitude)
+{
+    for (uint32_t i = 0; i < CF_THETA_LEN; i++) {
+        uint32_t w = philox_word(mutation_seed, e->env, round, 1, DOM_MUTATE, i >> 3, (i >> 1) & 3u);
+        uint32_t d = (i & 1u) ? (w >> 16) : (w & 0xFFFFu);
+        int32_t u = (int32_t)((d * (2u * amplitude + 1u)) >> 16) - (int32_t)amplitude;
+        theta[i] = (uint16_t)(((int32_t)(theta[i] & 1023u) + u) & 1023);
+    }
+    start_episode(e, cfg, e->episode, theta);
 }

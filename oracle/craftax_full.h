@@ -96,6 +96,13 @@ void cf_default_config(cf_config *cfg);
 int cf_achievement_reward(int id);
 void cf_worldgen_floor(cf_env *e, int floor);    /* uses e->seed, e->env, e->episode */
 void cf_worldgen_floor_mode(cf_env *e, int floor, uint32_t mode);   /* mode: ORC_WORLDGEN_VALUE or ORC_WORLDGEN_PERLIN */
+/* A level as the noise mutation sees it: the angle offsets of every noise lattice, overworld
+ * (2 x 4x4 + 4 x 7x7 points) then cave floors 2, 5, 6, 7 (2 x 7x7 each). */
+#define CF_THETA_OVERWORLD (2 * 16 + 4 * 49)
+#define CF_THETA_CAVE (2 * 49)
+#define CF_THETA_LEN (CF_THETA_OVERWORLD + 4 * CF_THETA_CAVE)
+void cf_worldgen_floor_theta(cf_env *e, int floor, const uint16_t *theta);   /* Perlin floor of level theta[CF_THETA_LEN] */
+void cf_mutate_noise(cf_env *e, const cf_config *cfg, uint16_t *theta, uint64_t mutation_seed, uint32_t round, uint32_t amplitude);
 void cf_reset(cf_env *e, const cf_config *cfg, uint64_t seed, uint32_t env);
 void cf_step_rules(cf_env *e, const cf_config *cfg, int32_t action, float *reward, uint8_t *done);
 void cf_step(cf_env *e, const cf_config *cfg, int32_t action, float *reward, uint8_t *done);

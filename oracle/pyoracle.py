@@ -153,6 +153,8 @@ def worldgen(seed: int, env: int, episode: int = 0, mode: int = WORLDGEN_VALUE) 
 RESET_EXACT, RESET_POOL = 0, 1
 POOL_RATIO = 16
 THETA_LEN = 374      # Perlin gradient angles of one Classic world: 2 x 25 + 4 x 81
+FULL_THETA_LEN = 620  # of one full-Craftax world: overworld 2 x 16 + 4 x 49, then 2 x 49 for each of the cave floors 2, 5, 6, 7
+FULL_THETA_OFFSET = {0: 0, 2: 228, 5: 326, 6: 424, 7: 522}
 
 
 def worldgen_theta(seed: int, env: int, episode: int, theta: np.ndarray) -> np.ndarray:
@@ -306,6 +308,18 @@ class FullOracle:
 
     def draw(self, i: int, block: int, word: int) -> int:
         return int(lib().cf_step_draw(self._ptr(i), ctypes.c_uint32(block), ctypes.c_uint32(word)))
+
+    def mutate_noise(self, theta: np.ndarray, mutation_seed: int, round_: int, amplitude: int) -> None:
+        """Noise mutation on every environment; theta (uint16 [n][FULL_THETA_LEN]) is updated in place."""
+        assert theta.dtype == np.uint16 and theta.shape == (self.n, FULL_THETA_LEN) and theta.flags.c_contiguous
+        for i in range(self.n):
+            lib().cf_mutate_noise(self._ptr(i), ctypes.byref(self.cfg), ctypes.c_void_p(theta.ctypes.data + i * FULL_THETA_LEN * 2),
+                                  ctypes.c_uint64(mutation_seed), ctypes.c_uint32(round_), ctypes.c_uint32(amplitude))
+
+    def worldgen_floor_theta(self, i: int, f: int, theta: np.ndarray) -> None:
+        """Regenerates floor f of environment i as the Perlin floor of level theta."""
+        assert theta.dtype == np.uint16 and theta.shape == (FULL_THETA_LEN,) and theta.flags.c_contiguous
+        lib().cf_worldgen_floor_theta(self._ptr(i), f, _p(theta))
 
     def mutate_swap(self, mutation_seed: int, round_: int, restricted: bool) -> np.ndarray:
         """Swap mutation of the overworld of every environment; returns the accepted try + 1 per env."""

@@ -310,6 +310,131 @@ def test_perlin_mode_changes_the_open_floors_only_and_follows_the_noise():
     assert np.array_equal(q.envs[0]["block"], e["block"])
 
 
+def _full_lattice(seed, env, episode, floor, count):
+    """Lattice numbers of a floor straight from Philox: stream 4 * floor of the world generation
+    domain, two u16 per word, low half first."""
+    out = []
+    for block in range((count + 7) // 8):
+        w = po.philox([env, 4 * floor, episode, (1 << 16) | block], [seed & 0xFFFFFFFF, seed >> 32])
+        for x in w:
+            out += [x & 0xFFFF, x >> 16]
+    return np.array(out[:count], np.uint16)
+
+
+def _turn(lattice, theta):
+    return (lattice.astype(np.uint32) + (theta.astype(np.uint32) << 6)).astype(np.uint16)
+
+
+def test_noise_mutation_turns_the_angles_of_the_right_floor():
+    """Section "Craftax-1B: UED", noise mutation on the full game: the level is the angle vector of
+    all noise lattices, overworld first, then the cave floors 2, 5, 6, 7.  Each segment moves its
+    own floor only, and the moved floors follow the noise function called on the turned lattices."""
+    rng = np.random.default_rng(5)
+    n = 5
+    seeds = synth.seeds_for(n, 44)
+    plain = fresh(n, seed=44, worldgen=po.WORLDGEN_PERLIN)
+    assert po.FULL_THETA_LEN == 2 * 16 + 4 * 49 + 4 * 2 * 49
+    seg = dict(po.FULL_THETA_OFFSET)
+    ends = {0: 228, 2: 326, 5: 424, 6: 522, 7: 620}
+    for f in (0, 2, 5, 6, 7):
+        theta = np.zeros((n, po.FULL_THETA_LEN), np.uint16)
+        theta[:, seg[f]:ends[f]] = rng.integers(1, 1024, (n, ends[f] - seg[f]))
+        o = fresh(n, seed=44, worldgen=po.WORLDGEN_PERLIN)
+        before = theta.copy()
+        o.mutate_noise(theta, 99, 0, 0)                    # amplitude 0: the level as given
+        assert np.array_equal(theta, before)
+        for i in range(n):
+            for g in range(9):
+                assert np.array_equal(o.envs[i]["block"][g], plain.envs[i]["block"][g]) == (g != f), (f, i, g)
+            assert np.array_equal(o.envs[i]["ladder_down"], plain.envs[i]["ladder_down"])
+            assert np.array_equal(o.envs[i]["potion_effect"], plain.envs[i]["potion_effect"])
+    # all segments at once; floor 2 against its C field, the overworld against its M and W fields
+    theta = rng.integers(0, 1024, (n, po.FULL_THETA_LEN)).astype(np.uint16)
+    o = fresh(n, seed=44, worldgen=po.WORLDGEN_PERLIN)
+    o.mutate_noise(theta, 99, 0, 0)
+    i = 3
+    e = o.envs[i]
+    c8 = _turn(_full_lattice(int(seeds[i]), i, 0, 2, 98)[:49], theta[i, 228:277]).reshape(7, 7)
+    ux, uy = (int(t) for t in e["ladder_up"][2]); dx, dy = (int(t) for t in e["ladder_down"][2])
+    checked = 0
+    for y in range(0, 48, 2):
+        for x in range(0, 48, 2):
+            if min(max(abs(x - ux), abs(y - uy)), max(abs(x - dx), abs(y - dy))) <= 1 or y == uy or x == dx:
+                continue
+            C = po.perlin_noise(c8, 8, x, y)
+            if abs(C - 31000) > 200:
+                assert (e["block"][2][y, x] in (B["PATH"], B["STALAGMITE"])) == (C > 31000), (x, y, C)
+                checked += 1
+    assert checked > 300
+    base = _full_lattice(int(seeds[i]), i, 0, 0, 228)
+    rock = {B[k] for k in ("STONE", "PATH", "LAVA", "COAL", "IRON", "DIAMOND")}
+
+    def fields(lat, x, y):
+        W = (3 * po.perlin_noise(lat[0:16].reshape(4, 4), 16, x, y) + po.perlin_noise(lat[32:81].reshape(7, 7), 8, x, y)) >> 2
+        M = (3 * po.perlin_noise(lat[16:32].reshape(4, 4), 16, x, y) + po.perlin_noise(lat[81:130].reshape(7, 7), 8, x, y)) >> 2
+        return W, M
+
+    turned = _turn(base, theta[i, :228])
+    counts = {"rock": 0, "water": 0, "land": 0}
+    wrong = 0
+    for y in range(48):
+        for x in range(48):
+            if max(abs(x - 24), abs(y - 24)) < 10:
+                continue                                   # the start area lowers both fields and holds the ladder
+            b = int(e["block"][0][y, x])
+            W, M = fields(turned, x, y)
+            if M > 39500 + 300:
+                assert b in rock, (x, y); counts["rock"] += 1
+            elif M < 39500 - 300 and W > 39500 + 300:
+                assert b == B["WATER"], (x, y); counts["water"] += 1
+            elif M < 39500 - 300 and W < 37800 - 300:
+                assert b in (B["GRASS"], B["TREE"]), (x, y); counts["land"] += 1
+            W0, M0 = fields(base, x, y)
+            wrong += (M0 > 39800 and b not in rock) or (M0 < 39200 and W0 > 39800 and b != B["WATER"])
+    assert min(counts.values()) > 20, counts
+    assert wrong > 30                                      # the unturned lattice does not explain this map
+    # the single-floor entry point gives the same floors
+    q = fresh(n, seed=44, worldgen=po.WORLDGEN_PERLIN)
+    for f in range(9):
+        q.worldgen_floor_theta(i, f, theta[i])
+    assert np.array_equal(q.envs[i]["block"], e["block"]) and np.array_equal(q.envs[i]["item"], e["item"])
+
+
+def test_noise_mutation_draws_and_restart_in_the_full_game():
+    n, A, ms = 4, 29, 0x13572468ACE
+    o = fresh(n, seed=9, worldgen=po.WORLDGEN_PERLIN, max_episode_steps=5)
+    for t in range(5):
+        o.step(synth.actions(np.arange(n), t, "uniform", 2, 43))
+    assert np.all(o.envs["episode"] == 1) and np.all(o.envs["t"] == 0)
+    fresh1 = o.envs.copy()                                 # the start of episode 1, as the auto-reset leaves it
+    for t in range(5, 8):
+        o.step(synth.actions(np.arange(n), t, "uniform", 2, 43))
+    assert np.all(o.envs["t"] == 3) and o.envs.tobytes() != fresh1.tobytes()
+    theta = np.zeros((n, po.FULL_THETA_LEN), np.uint16)
+    o.mutate_noise(theta, ms, 6, 0)
+    assert not theta.any() and o.envs.tobytes() == fresh1.tobytes()
+    o.mutate_noise(theta, ms, 6, A)
+    for i in range(n):
+        for k in (0, 1, 2, 7, 8, 227, 228, 325, 326, 619):
+            w = po.philox([i, 6, 1, (4 << 16) | (k >> 3)], [ms & 0xFFFFFFFF, ms >> 32])[(k >> 1) & 3]
+            d = (w >> 16) if k & 1 else (w & 0xFFFF)
+            assert theta[i, k] == ((d * (2 * A + 1) >> 16) - A) % 1024
+    signed = ((theta.astype(np.int32) + 512) % 1024) - 512
+    assert signed.min() == -A and signed.max() == A and abs(signed.mean()) < 2.0 and len(np.unique(signed)) == 2 * A + 1
+    # everything but the maps is the fresh episode; the maps are the level's
+    for i in range(n):
+        want = fresh1[i].copy()
+        for name in ("block", "item", "light"):
+            want[name] = o.envs[i][name]
+        assert o.envs[i].tobytes() == want.tobytes()
+        assert not np.array_equal(o.envs[i]["block"][0], fresh1[i]["block"][0])
+        assert np.array_equal(o.envs[i]["item"], fresh1[i]["item"]) and np.array_equal(o.envs[i]["light"], fresh1[i]["light"])
+    first = theta.copy()
+    o.mutate_noise(theta, ms, 7, 511)                      # mutations add up, modulo a full turn
+    step2 = ((theta.astype(np.int32) - first.astype(np.int32) + 512) % 1024) - 512
+    assert -511 <= step2.min() < -495 and 495 < step2.max() <= 511 and theta.max() < 1024
+
+
 def test_worldgen_is_a_pure_function_of_seed_env_episode():
     o = fresh(4, seed=5)
     p = fresh(4, seed=5)
