@@ -271,10 +271,15 @@ int craftax_mutate_swap(void *state, int first, int count, uint64_t mutation_see
  * turn, generates the world of the current episode of each environment of [first, first+count)
  * again from the new angles, and restarts that episode in it (fresh player, empty tables, same
  * episode number; the per-cell draws for trees and ores stay those of the seed).  amplitude 0
- * loads the level theta unchanged.  Needs variant CLASSIC with CRAFTAX_WORLDGEN_PERLIN
- * (CRAFTAX_E_CONFIG otherwise); CRAFTAX_E_COUNT for a range outside the state or amplitude > 511;
- * CRAFTAX_E_NULL for theta == NULL. */
+ * loads the level theta unchanged.  Variant CRAFTAX: a row has CRAFTAX_FULL_THETA_LEN elements,
+ * the lattices of every floor generated from noise: the overworld's two spacing-16 lattices (4x4
+ * points) and four spacing-8 ones (7x7), then the two 7x7 lattices of each of the cave floors 2,
+ * 5, 6 and 7; the draws count i over the whole row; all nine floors of the current episode are
+ * generated again (the room floors and the boss floor come out as they were).  Needs
+ * CRAFTAX_WORLDGEN_PERLIN (CRAFTAX_E_CONFIG otherwise); CRAFTAX_E_COUNT for a range outside the
+ * state or amplitude > 511; CRAFTAX_E_NULL for theta == NULL. */
 #define CRAFTAX_THETA_LEN 374
+#define CRAFTAX_FULL_THETA_LEN 620
 int craftax_mutate_noise(void *state, int first, int count, uint16_t *theta, uint64_t mutation_seed,
                          uint32_t round, uint32_t amplitude, void *stream);
 

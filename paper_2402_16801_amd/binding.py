@@ -27,6 +27,7 @@ EXPORTS = [
 
 
 THETA_LEN = 374      # angle offsets per Classic level (craftax_mutate_noise)
+FULL_THETA_LEN = 620  # per full-Craftax level
 RESET_EXACT, RESET_POOL = 0, 1
 
 
@@ -267,6 +268,8 @@ class Craftax:
         return tries.cpu().numpy()
 
     def mutate_noise(self, theta, mutation_seed: int, round_: int, amplitude: int, first: int = 0):
-        """Noise mutation; theta: device int16 tensor [count][THETA_LEN] holding the angle offsets, updated in place."""
-        assert theta.dtype == self.torch.int16 and theta.is_contiguous() and theta.shape[1] == THETA_LEN
+        """Noise mutation; theta: device int16 tensor [count][THETA_LEN] (FULL_THETA_LEN for the full game)
+        holding the angle offsets, updated in place."""
+        row = FULL_THETA_LEN if self.cfg.variant == VARIANT_CRAFTAX else THETA_LEN
+        assert theta.dtype == self.torch.int16 and theta.is_contiguous() and theta.shape[1] == row
         craftax_mutate_noise(self.state, first, theta.shape[0], theta, mutation_seed, round_, amplitude, self.stream)

@@ -467,6 +467,51 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_import_spare(uint32_t* __restr
     if (threadIdx.x == 0) ls.tags[(size_t)env * NTAG + f] = make_uint2(ep, 0u);
 }
 
+// Noise mutation (section "Craftax-1B: UED"): one block per (environment, floor) of the floors
+// f0 .. f0 + nf - 1.  The level is the vector of the Perlin angles of every noise lattice: the
+// overworld's 228, then 98 for each of the cave floors 2, 5, 6, 7.  The block of a floor adds to its
+// own segment a uniform offset in [-amplitude, amplitude] per element (u16 number i of stream
+// (round, 1) of the mutation domain, i counted over the whole vector) and generates the floor of
+// the current episode again from the turned lattice; the block of floor 0 then starts the episode
+// over.  Floor 0 runs in a launch of its own after the others: its block rewrites the record the
+// others read their seed and episode from.
+__device__ inline int theta_offset(int f)
+{
+    return f == 0 ? 0 : LAT0_U16 + LATC_U16 * (f == 2 ? 0 : (f == 5 ? 1 : (f == 6 ? 2 : 3)));
+}
+__global__ __launch_bounds__(GEN_THREADS) void kf_mutate_noise(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, const Luts* __restrict__ luts,
+                                                                uint16_t* __restrict__ theta, int first, int f0, int nf, uint32_t k0, uint32_t k1,
+                                                                uint32_t round, uint32_t amplitude)
+{
+    __shared__ uint16_t s_lat[LAT_TOTAL];
+    __shared__ uint16_t s_theta[LAT_TOTAL];
+    __shared__ GenLayout s_layout;
+    __shared__ uint32_t s_words[FLOORS + 1];
+    const int tid = threadIdx.x, slot = blockIdx.x / nf, f = f0 + blockIdx.x % nf;
+    const uint32_t env = (uint32_t)first + (uint32_t)slot;
+    uint32_t* genv = envs + (size_t)env * ENV_DWORDS;
+    const uint32_t ep = genv[R_EPISODE], lo = genv[R_SEED_LO], hi = genv[R_SEED_HI];
+    const bool noisy = f == 0 || is_cave(f);
+    if (tid < LAT_TOTAL) {
+        uint16_t v = 0;
+        const int len = f == 0 ? LAT0_U16 : LATC_U16;
+        if (noisy && tid < len) {
+            const int i = theta_offset(f) + tid;
+            uint16_t* th = theta + (size_t)slot * CRAFTAX_FULL_THETA_LEN + i;
+            const cx::U4 d = cx::philox4x32_10(env, round, 1u, (cx::DOM_MUTATE << 16) | (uint32_t)(i >> 3), k0, k1);
+            const uint32_t w = d.w[(i >> 1) & 3], d16 = (i & 1) ? (w >> 16) : (w & 0xFFFFu);
+            const int u = (int)((d16 * (2u * amplitude + 1u)) >> 16) - (int)amplitude;
+            v = (uint16_t)(((int)(*th & 1023u) + u) & 1023);
+            *th = v;
+        }
+        s_theta[tid] = v;
+    }
+    __syncthreads();
+    worldgen_floor_block<GEN_THREADS, true>(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f, nullptr, nullptr, 0, GEN_THREADS,
+                                            luts->perlin_cs, noisy ? s_theta : nullptr);
+    if (f == 0) publish_world(genv, s_layout, lo, hi, ep, true, s_words);
+}
+
 // ---------------------------------------------------------------------------------------------
 // canonical dumps: one block per environment
 __global__ __launch_bounds__(BLOCK) void kf_export(const uint32_t* __restrict__ envs, const uint8_t* __restrict__ maps,
@@ -876,6 +921,18 @@ int mutate_swap(void* state, const craftax_config* cfg, int n, int first, int co
     hipLaunchKernelGGL(kf_mutate_swap, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, (hipStream_t)stream, q.envs, q.maps, first,
                        count, (uint32_t)mutation_seed, (uint32_t)(mutation_seed >> 32), round, restricted != 0 ? 1 : 0, tries);
     return check_launch("craftax_mutate_swap", err);
+}
+
+int mutate_noise(void* state, const craftax_config* cfg, int n, int first, int count, uint16_t* theta, uint64_t mutation_seed, uint32_t round,
+                 uint32_t amplitude, void* stream, std::string* err)
+{
+    const Ptrs q = pointers(state, make_header(cfg, n));
+    const uint32_t k0 = (uint32_t)mutation_seed, k1 = (uint32_t)(mutation_seed >> 32);
+    hipLaunchKernelGGL(kf_mutate_noise, dim3((unsigned)count * (FLOORS - 1)), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, q.luts, theta,
+                       first, 1, FLOORS - 1, k0, k1, round, amplitude);
+    hipLaunchKernelGGL(kf_mutate_noise, dim3((unsigned)count), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, q.luts, theta, first, 0, 1,
+                       k0, k1, round, amplitude);
+    return check_launch("craftax_mutate_noise", err);
 }
 
 }  // namespace host

@@ -26,6 +26,8 @@ int export_envs(const void* state, const craftax_config* cfg, int n, int first, 
 int import_envs(void* state, const craftax_config* cfg, int n, int first, int count, const void* dumps, void* stream, std::string* err);
 int mutate_swap(void* state, const craftax_config* cfg, int n, int first, int count, uint64_t mutation_seed, uint32_t round,
                 int restricted, int32_t* tries, void* stream, std::string* err);
+int mutate_noise(void* state, const craftax_config* cfg, int n, int first, int count, uint16_t* theta, uint64_t mutation_seed, uint32_t round,
+                 uint32_t amplitude, void* stream, std::string* err);
 
 }  // namespace host
 }  // namespace cf

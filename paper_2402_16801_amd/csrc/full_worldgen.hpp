@@ -182,11 +182,14 @@ __device__ inline void make_cave_ladders(GenLayout& L, int f, const U4& r)
 // perlin_cs (with CAN_PERLIN): the gradient table; the fields of the overworld and of the caves are
 // then Perlin noise over the same lattices (appendix "World Generation") instead of value noise.
 // A kernel instantiated without CAN_PERLIN carries no code for it.
+// theta_f (with CAN_PERLIN; LDS, LAT_TOTAL entries, the same for the whole block): angle offsets in
+// 1024ths of a turn added to the upper ten bits of this floor's lattice numbers, the level of the
+// noise mutation (section "Craftax-1B: UED").
 template <int NT = GEN_THREADS, bool CAN_PERLIN = false>
 __device__ __forceinline__ void worldgen_floor_block(uint8_t* __restrict__ maps, uint16_t* s_lat, GenLayout& L, uint32_t lo, uint32_t hi,
                                             uint32_t env, uint32_t episode, int f, uint8_t* start_wb = nullptr,
                                             uint8_t* start_wi = nullptr, int first_run = 0, int runs = GEN_THREADS,
-                                            const uint32_t* __restrict__ perlin_cs = nullptr)
+                                            const uint32_t* __restrict__ perlin_cs = nullptr, const uint16_t* theta_f = nullptr)
 {
     const bool perlin = CAN_PERLIN && perlin_cs != nullptr;
     static_assert(NT >= 64, "the layout phase uses the first wavefront");
@@ -242,6 +245,10 @@ __device__ __forceinline__ void worldgen_floor_block(uint8_t* __restrict__ maps,
         }
     }
     __syncthreads();
+    if (CAN_PERLIN && theta_f != nullptr) {
+        for (int i = tid0; i < LAT_TOTAL; i += NT) s_lat[i] = (uint16_t)(s_lat[i] + ((theta_f[i] & 1023u) << 6));
+        __syncthreads();
+    }
     // runs of 4 cells, one per thread and pass
 #pragma unroll 1
     for (int tid = first_run + tid0; tid < first_run + runs; tid += NT) {

@@ -233,6 +233,90 @@ def test_full_perlin_episodes_every_generation_path(cx):
     sim.close()
 
 
+def test_full_noise_mutation_matches_the_oracle(cx):
+    """Section "Craftax-1B: UED", noise mutation on the full game: angle vectors, the nine floors
+    generated again and the restarted episodes after play across an episode boundary; repeated and
+    partial mutations; the mutated levels played on through auto-resets and a rollout."""
+    import torch
+    n, ms = 45, 0xBEEF5EED77
+    gcfg, ocfg = _cfgs(cx, 1, worldgen=po.WORLDGEN_PERLIN, max_episode_steps=9)
+    sim = cx.Craftax(n, gcfg)
+    orc = po.FullOracle(n, ocfg)
+    seeds = synth.seeds_for(n, 21)
+    sim.reset(seeds); orc.reset(seeds)
+    ids = np.arange(n)
+    t = 0
+
+    def play(k):
+        nonlocal t
+        for _ in range(k):
+            a = synth.actions(ids, t, "skewed", 2, 43)
+            obs, rew, done = sim.step(torch.as_tensor(a, device=sim.device))
+            oobs, orew, odone = orc.step(a)
+            assert np.array_equal(done.cpu().numpy(), odone) and np.array_equal(obs.cpu().numpy(), oobs), f"step {t}"
+            t += 1
+
+    def same(what):
+        assert np.array_equal(d_theta.cpu().numpy().view(np.uint16), theta), f"theta after {what}"
+        compare_state(sim, orc, ids, what)
+        cx.craftax_observe(sim.state, sim.obs, n, sim.stream)
+        assert np.array_equal(sim.obs.cpu().numpy(), orc.observe()), f"observation after {what}"
+
+    play(12)
+    theta = np.zeros((n, po.FULL_THETA_LEN), np.uint16)
+    d_theta = torch.zeros((n, cx.FULL_THETA_LEN), dtype=torch.int16, device=sim.device)
+    sim.mutate_noise(d_theta, ms, 0, 0)                     # amplitude 0: the same levels, restarted
+    orc.mutate_noise(theta, ms, 0, 0)
+    same("amplitude 0")
+    assert not theta.any()
+    sim.mutate_noise(d_theta, ms, 1, 40)
+    orc.mutate_noise(theta, ms, 1, 40)
+    same("the first mutation")
+    assert theta[:, :228].any() and theta[:, 522:].any()
+    play(5)
+    # a sub-range, the largest amplitude, on top of the first mutation
+    sim.mutate_noise(d_theta[5:25], ms, 2, 511, first=5)
+    part = theta[5:25].copy()
+    sub = po.FullOracle(20, ocfg)
+    sub.envs[:] = orc.envs[5:25]
+    sub.mutate_noise(part, ms, 2, 511)
+    theta[5:25] = part
+    orc.envs[5:25] = sub.envs
+    same("a partial mutation")
+    play(14)                                               # past the end of the mutated episodes
+    # a level put on every floor's ladder: the mutated caves under the player's feet
+    sim.mutate_noise(d_theta, ms, 3, 100)
+    orc.mutate_noise(theta, ms, 3, 100)
+    rich_scene(orc.envs)
+    sim.import_envs(orc.envs.copy())
+    same("mutated levels with the player on every floor")
+    steps = 12
+    acts = np.stack([synth.actions(ids, t + s, "skewed", 2, 43) for s in range(steps)]).astype(np.int32)
+    d_rew = torch.zeros((steps, n), dtype=torch.float32, device=sim.device)
+    d_done = torch.zeros((steps, n), dtype=torch.uint8, device=sim.device)
+    cx.craftax_rollout(sim.state, torch.as_tensor(acts, device=sim.device), steps, sim.obs, d_rew, d_done, n, sim.stream)
+    for s in range(steps):
+        oobs, orew, odone = orc.step(acts[s])
+        assert np.array_equal(d_done[s].cpu().numpy(), odone), f"rollout step {s}"
+        assert np.array_equal(d_rew[s].cpu().numpy().view(np.uint32), orew.view(np.uint32)), f"rollout step {s}"
+    assert np.array_equal(sim.obs.cpu().numpy(), oobs)
+    compare_state(sim, orc, ids, "the rollout")
+    # errors: a range outside the state, an amplitude above half a turn, no theta, value-noise worlds
+    with pytest.raises(cx.CraftaxError):
+        cx.craftax_mutate_noise(sim.state, 40, 6, d_theta, ms, 0, 5, sim.stream)
+    with pytest.raises(cx.CraftaxError):
+        cx.craftax_mutate_noise(sim.state, 0, n, d_theta, ms, 0, 512, sim.stream)
+    with pytest.raises(cx.CraftaxError):
+        cx.craftax_mutate_noise(sim.state, 0, n, None, ms, 0, 5, sim.stream)
+    compare_state(sim, orc, ids, "the refused calls")
+    sim.close()
+    other = cx.Craftax(8, cx.default_config(cx.VARIANT_CRAFTAX))
+    other.reset(synth.seeds_for(8))
+    with pytest.raises(cx.CraftaxError):
+        cx.craftax_mutate_noise(other.state, 0, 8, d_theta, ms, 0, 5, other.stream)
+    other.close()
+
+
 @pytest.mark.parametrize("n", [1, 3, 5, 130])
 def test_full_ragged_counts(cx, n):
     run_full(cx, n, 120, kind="skewed", seed_base=50 + n)
