@@ -163,7 +163,7 @@ void cf_default_config(cf_config *cfg)
     cfg->cap_plant = 10;
     cfg->atlas_seed = 0;
     cfg->worldgen = ORC_WORLDGEN_VALUE;
-    cfg->reserved = 0;
+    cfg->reset_mode = ORC_RESET_EXACT;
 }
 size_t cf_env_bytes(void) { return sizeof(cf_env); }
 size_t cf_obs_bytes(int mode)
@@ -1066,6 +1066,33 @@ void cf_step_batch(cf_env *envs, const cf_config *cfg, const int32_t *actions, i
         cf_step(&envs[i], cfg, actions[i], &reward[i], &done[i]);
         if (obs) cf_observe(&envs[i], cfg, mode, (uint8_t *)obs + stride * (size_t)i);
     }
+}
+
+/* Optimistic resets (appendix "Optimistic Environment Resets"), the reading of the Classic oracle
+ * applied to the full game: all environments take the step's rules first; the r-th finished
+ * environment (by environment number) then starts its next episode in pool world orc_pool_slot(seed
+ * of environment 0, step index, r, n) -- all nine floors, the ladders and the potion map of world
+ * (seed of environment 0, environment 2^31 + slot, episode = step index) -- while it keeps its own
+ * seed and number and counts its episode up, so every later draw is its own. */
+void cf_step_batch_pool(cf_env *envs, const cf_config *cfg, const int32_t *actions, int mode, void *obs, float *reward, uint8_t *done,
+                        int n, uint32_t step_index)
+{
+    size_t stride = cf_obs_bytes(mode);
+    uint64_t pool_seed = envs[0].seed;
+    for (int i = 0; i < n; i++) cf_step_rules(&envs[i], cfg, actions[i], &reward[i], &done[i]);
+    uint32_t rank = 0;
+    for (int i = 0; i < n; i++) {
+        if (!done[i]) continue;
+        cf_env *e = &envs[i];
+        uint32_t slot = orc_pool_slot(pool_seed, step_index, rank++, (uint32_t)n);
+        uint64_t seed = e->seed;
+        uint32_t env = e->env, episode = e->episode + 1;
+        e->seed = pool_seed; e->env = 0x80000000u | slot;
+        start_episode(e, cfg, step_index, NULL);
+        e->seed = seed; e->env = env; e->episode = episode;
+    }
+    if (obs)
+        for (int i = 0; i < n; i++) cf_observe(&envs[i], cfg, mode, (uint8_t *)obs + stride * (size_t)i);
 }
 
 /* ---- level mutations (section "Craftax-1B: UED": applied to the overworld) ----------------------

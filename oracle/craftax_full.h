@@ -48,7 +48,7 @@ typedef struct {
     uint32_t cap_plant;
     uint64_t atlas_seed;          /* seed of the synthetic tile atlas (pixel observations) */
     uint32_t worldgen;            /* ORC_WORLDGEN_VALUE or ORC_WORLDGEN_PERLIN: the noise behind the open floors */
-    uint32_t reserved;
+    uint32_t reset_mode;          /* ORC_RESET_EXACT (cf_step_batch) or ORC_RESET_POOL (cf_step_batch_pool) */
 } cf_config;
 
 typedef struct {
@@ -94,6 +94,8 @@ size_t cf_env_bytes(void);
 size_t cf_obs_bytes(int mode);
 void cf_default_config(cf_config *cfg);
 int cf_achievement_reward(int id);
+void cf_step_batch_pool(cf_env *envs, const cf_config *cfg, const int32_t *actions, int mode, void *obs, float *reward, uint8_t *done,
+                        int n, uint32_t step_index);   /* optimistic resets; step_index = steps since the reset */
 void cf_worldgen_floor(cf_env *e, int floor);    /* uses e->seed, e->env, e->episode */
 void cf_worldgen_floor_mode(cf_env *e, int floor, uint32_t mode);   /* mode: ORC_WORLDGEN_VALUE or ORC_WORLDGEN_PERLIN */
 /* A level as the noise mutation sees it: the angle offsets of every noise lattice, overworld

@@ -73,7 +73,7 @@ class FullConfig(ctypes.Structure):
     _fields_ = [("max_episode_steps", ctypes.c_uint32), ("day_length", ctypes.c_uint32),
                 ("cap_melee", ctypes.c_uint32), ("cap_ranged", ctypes.c_uint32),
                 ("cap_passive", ctypes.c_uint32), ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64),
-                ("worldgen", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("worldgen", ctypes.c_uint32), ("reset_mode", ctypes.c_uint32)]
 
 
 class Config(ctypes.Structure):
@@ -268,6 +268,7 @@ class FullOracle:
         self.cfg = cfg if cfg is not None else full_default_config()
         self.obs_mode = obs_mode
         self.envs = np.zeros(n, dtype=FULL_ENV_DTYPE)
+        self.steps = 0                      # batch steps since the reset (names the pool of the optimistic resets)
         self.obs = np.zeros((n, FULL_OBS_BYTES[obs_mode]), np.uint8)
         self.reward = np.zeros(n, np.float32)
         self.done = np.zeros(n, np.uint8)
@@ -280,6 +281,7 @@ class FullOracle:
         ids = None if env_ids is None else np.ascontiguousarray(env_ids, dtype=np.uint32)
         lib().cf_reset_batch(_p(self.envs), ctypes.byref(self.cfg), _p(seeds),
                              None if ids is None else _p(ids), self.n)
+        self.steps = 0
         return self.observe()
 
     def observe(self):
@@ -289,8 +291,14 @@ class FullOracle:
     def step(self, actions, render: bool = True):
         a = np.ascontiguousarray(actions, dtype=np.int32)
         assert a.shape == (self.n,)
-        lib().cf_step_batch(_p(self.envs), ctypes.byref(self.cfg), _p(a), self.obs_mode,
-                            _p(self.obs) if render else None, _p(self.reward), _p(self.done), self.n)
+        if self.cfg.reset_mode == RESET_POOL:
+            lib().cf_step_batch_pool(_p(self.envs), ctypes.byref(self.cfg), _p(a), self.obs_mode,
+                                     _p(self.obs) if render else None, _p(self.reward), _p(self.done), self.n,
+                                     ctypes.c_uint32(self.steps))
+        else:
+            lib().cf_step_batch(_p(self.envs), ctypes.byref(self.cfg), _p(a), self.obs_mode,
+                                _p(self.obs) if render else None, _p(self.reward), _p(self.done), self.n)
+        self.steps += 1
         return self.obs, self.reward, self.done
 
     def step_rules_one(self, i: int, action: int):

@@ -435,6 +435,67 @@ def test_noise_mutation_draws_and_restart_in_the_full_game():
     assert -511 <= step2.min() < -495 and 495 < step2.max() <= 511 and theta.max() < 1024
 
 
+def test_optimistic_resets_of_the_full_game_hand_out_pool_worlds_in_env_order():
+    """Appendix "Optimistic Environment Resets" on the full game: the r-th finished environment of
+    step T gets all nine floors, the ladders and the potion map of pool world (seed of environment
+    0, 2^31 + slot(T, r), T) and keeps its own seed, number and episode count."""
+    n = 64
+    o = fresh(n, seed=12, reset_mode=po.RESET_POOL, max_episode_steps=1000)
+    x = fresh(n, seed=12, max_episode_steps=1000)
+    seeds = synth.seeds_for(n, 12)
+    pool_seed = int(seeds[0])
+    for t in range(4):                                     # no episode ends: the two modes are the same
+        a = synth.actions(np.arange(n), t, "uniform", 1, 43)
+        oo, _, od = o.step(a); xo, _, _ = x.step(a)
+        assert not od.any() and np.array_equal(oo, xo) and o.envs.tobytes() == x.envs.tobytes()
+    victims = [50, 3, 17]
+    for v in victims:
+        o.envs[v]["vit"][HEALTH] = 1; o.envs[v]["vit"][FOOD] = 0; o.envs[v]["cnt"][3] = -30
+    before = o.envs.copy()
+    a = np.zeros(n, np.int32)
+    obs, rew, done = o.step(a)
+    assert sorted(np.nonzero(done)[0].tolist()) == sorted(victims)
+    T = 4
+    slots = []
+    for rank, v in enumerate(sorted(victims)):
+        e = o.envs[v]
+        slot = po.pool_slot(pool_seed, T, rank, n)
+        slots.append(slot)
+        w = po.FullOracle(1, po.full_default_config())     # the pool world through the plain reset of that identity
+        w.reset(np.array([pool_seed], np.uint64), env_ids=np.array([0x80000000 | slot], np.uint32))
+        w.envs[0]["episode"] = T
+        for f in range(9):
+            po.lib().cf_worldgen_floor(ctypes.c_void_p(w.envs.ctypes.data), f)
+        for name in ("block", "item", "light", "ladder_up", "ladder_down"):
+            assert np.array_equal(e[name], w.envs[0][name]), (v, name)
+        assert sorted(e["potion_effect"].tolist()) == list(range(6))
+        assert e["episode"] == before[v]["episode"] + 1 and e["seed"] == seeds[v] and e["env"] == v and e["t"] == 0
+        assert list(e["vit"]) == [9] * 5 and (e["px"], e["py"], e["floor"]) == (24, 24, 0) and not e["mob"]["alive"].any()
+        assert np.array_equal(obs[v], o.observe_one(v))
+    assert len(set(slots)) == 3                            # 3 resets, pool of 4: no world twice
+    y = po.FullOracle(n, po.full_default_config(max_episode_steps=1000)); y.envs[:] = before; y.step(a)
+    rest = [i for i in range(n) if i not in victims]
+    assert o.envs[rest].tobytes() == y.envs[rest].tobytes()
+
+
+def test_optimistic_resets_of_the_full_game_repeat_worlds_and_keep_envs_apart():
+    n = 48                                                 # pool of 3
+    o = fresh(n, seed=2, reset_mode=po.RESET_POOL, max_episode_steps=1)
+    o.step(np.zeros(n, np.int32))                          # every episode ends at once
+    maps = o.envs["block"].reshape(n, -1)
+    assert len({m.tobytes() for m in maps}) == 3
+    assert all(np.array_equal(maps[i], maps[i + 3]) for i in range(n - 3))      # environment i has rank i
+    assert all(np.array_equal(o.envs[i]["potion_effect"], o.envs[i + 3]["potion_effect"]) for i in range(n - 3))
+    assert len({o.envs[i]["potion_effect"].tobytes() for i in range(3)}) > 1    # the potion map belongs to the world
+    # the step after: another pool
+    first = maps.copy()
+    o.step(np.zeros(n, np.int32))
+    assert not any(np.array_equal(o.envs["block"].reshape(n, -1)[i], first[j]) for i in range(3) for j in range(3))
+    assert np.all(o.envs["episode"] == 2)
+    # environments that share a world draw their own numbers afterwards
+    assert o.draw(0, 0, 0) != o.draw(3, 0, 0)
+
+
 def test_worldgen_is_a_pure_function_of_seed_env_episode():
     o = fresh(4, seed=5)
     p = fresh(4, seed=5)
