@@ -127,7 +127,8 @@ enum { CRAFTAX_WORLDGEN_VALUE = 0, CRAFTAX_WORLDGEN_PERLIN = 1 };
  * uniform draw per step: no world twice unless more than M finish at once.  An environment keeps
  * its own seed and counts its episode up, so everything random after the reset still differs
  * between environments that share a world.  The library generates only the pool worlds that are
- * taken.  Variant CLASSIC only; craftax_rollout is not available in this mode. */
+ * taken.  In variant CRAFTAX a world is all nine floors with their ladders and the potion map.
+ * craftax_rollout is not available in this mode. */
 enum { CRAFTAX_RESET_EXACT = 0, CRAFTAX_RESET_POOL = 1 };
 
 /* One environment in canonical form, used by export/import (4304 bytes, little endian).

@@ -50,7 +50,8 @@ __device__ inline void publish_world(uint32_t* __restrict__ genv, const GenLayou
 // ---------------------------------------------------------------------------------------------
 // reset of every environment: one block per (environment, episode 0 or 1, floor)
 __global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
-                                                       const uint64_t* __restrict__ seeds, Lists ls, const uint32_t* __restrict__ perlin_cs)
+                                                       const uint64_t* __restrict__ seeds, Lists ls, const uint32_t* __restrict__ perlin_cs,
+                                                       int pool)
 {
     if (blockIdx.x == 0) la::reset_counters(ls);
     __shared__ uint16_t s_lat[LAT_TOTAL];
@@ -62,7 +63,9 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ e
     const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
     worldgen_floor_block<GEN_THREADS, true>(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f, nullptr, nullptr, 0, GEN_THREADS, perlin_cs);
     if (f == 0) publish_world(envs + (size_t)env * ENV_DWORDS, s_layout, lo, hi, ep, ep == 0u, s_words);
-    if (ep == 1u && threadIdx.x == 0) ls.tags[(size_t)env * NTAG + f] = make_uint2(1u, 0u);
+    // With optimistic resets no spare world is ever valid: tag 0 matches no next episode (they count
+    // from 1), so the step kernel hands every finished episode to kf_reset_list.
+    if (ep == 1u && threadIdx.x == 0) ls.tags[(size_t)env * NTAG + f] = make_uint2(pool ? 0u : 1u, 0u);
 }
 
 // The regeneration blocks of the step grid: worlds after next for the episodes that ended in the
@@ -394,12 +397,20 @@ __global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ en
 // kernel, and only when the episode cap is 1.
 template <bool F32>
 __global__ __launch_bounds__(GEN_THREADS) void kf_reset_list(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
-                                                            const Luts* __restrict__ luts, uint8_t* __restrict__ obs, Lists ls, int perlin)
+                                                            const Luts* __restrict__ luts, uint8_t* __restrict__ obs, Lists ls, int perlin,
+                                                            const uint8_t* __restrict__ done, int n, int pool)
 {
     __shared__ uint16_t s_lat[LAT_TOTAL];
     __shared__ GenLayout s_layout;
     __shared__ uint32_t s_words[FLOORS + 1];
     __shared__ uint32_t s_env[L_ENV_DWORDS];
+    __shared__ uint32_t s_rank[(GEN_THREADS + 63) / 64];
+    // Optimistic resets (pool != 0): the world comes from this step's pool.  The step kernel has
+    // already advanced the launch number: it is the index of the step just done + 2.  The pool is
+    // keyed by the seed of environment 0 (whoever rewrites that record writes the same seed back).
+    const uint32_t step_index = pool ? *counter(ls, la::CT_SEQ) - 2u : 0u;
+    const uint32_t pool_lo = pool ? envs[R_SEED_LO] : 0u, pool_hi = pool ? envs[R_SEED_HI] : 0u;
+    const uint32_t pool_size = (uint32_t)n / cx::POOL_RATIO ? (uint32_t)n / cx::POOL_RATIO : 1u;
     const uint32_t count = la::slow_count(ls, ls.slow_cap);
     const uint32_t slot = blockIdx.x / FLOORS, slots = gridDim.x / FLOORS;
     const int f = blockIdx.x % FLOORS;
@@ -409,13 +420,28 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_reset_list(uint32_t* __restric
         const uint4 entry = ls.slow[i];
         if (entry.x == ENTRY_VOID) continue;
         const uint32_t env = entry.x, lo = entry.y, hi = entry.z, ep = entry.w;
-        worldgen_floor_block<GEN_THREADS, true>(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f,
+        uint32_t wlo = lo, whi = hi, wenv = env, wep = ep;   // the world's identity: the environment's own ...
+        if (pool) {
+            // ... or the pool's: rank of this environment among the finished ones = finished environments before it
+            uint32_t before = 0u;
+            for (uint32_t j = (uint32_t)tid; j < env; j += GEN_THREADS) before += done[j];
+            for (int o = 32; o > 0; o >>= 1) before += __shfl_down(before, o);
+            __syncthreads();                                  // the previous entry's ranks have been read
+            if ((tid & 63) == 0) s_rank[tid >> 6] = before;
+            __syncthreads();
+            uint32_t rank = 0u;
+#pragma unroll
+            for (int w = 0; w < (GEN_THREADS + 63) / 64; ++w) rank += s_rank[w];
+            const cx::U4 sh = cx::philox4x32_10(0xFFFFFFFFu, 2u, step_index, cx::DOM_WORLDGEN << 16, pool_lo, pool_hi);
+            wlo = pool_lo; whi = pool_hi; wenv = cx::POOL_ENV | ((cx::choice(sh.w[0], pool_size) + rank) % pool_size); wep = step_index;
+        }
+        worldgen_floor_block<GEN_THREADS, true>(maps + map_offset(env, ep), s_lat, s_layout, wlo, whi, wenv, wep, f,
                                                 reinterpret_cast<uint8_t*>(s_env + L_WB), reinterpret_cast<uint8_t*>(s_env + L_WI), 0, GEN_THREADS,
                                                 perlin ? luts->perlin_cs : nullptr);
         if (f == 0) {
             publish_world(envs + (size_t)env * ENV_DWORDS, s_layout, lo, hi, ep, true, s_words);
             if (tid < REC_DWORDS) s_env[L_REC + tid] = fresh_record_word(tid, s_words, lo, hi, ep);
-            if (tid == 96) la::append_after_step(ls, env / ENVS_PER_BLOCK, make_uint4(env, lo, hi, ep + 1u));
+            if (tid == 96 && !pool) la::append_after_step(ls, env / ENVS_PER_BLOCK, make_uint4(env, lo, hi, ep + 1u));
             __syncthreads();
             if (obs != nullptr && tid < 64)
                 render_env<F32>(tid, s_env, W / 2 - WIN_COLS / 2, W / 2 - WIN_ROWS / 2, 0, 0, 0, 0, luts,
@@ -453,7 +479,7 @@ __global__ __launch_bounds__(BLOCK) void kf_observe(const uint32_t* __restrict__
 
 // after an import: the world of the episode after the imported one, into the spare slot
 __global__ __launch_bounds__(GEN_THREADS) void kf_import_spare(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, Lists ls, int first,
-                                                                const uint32_t* __restrict__ perlin_cs)
+                                                                const uint32_t* __restrict__ perlin_cs, int pool)
 {
     __shared__ uint16_t s_lat[LAT_TOTAL];
     __shared__ GenLayout s_layout;
@@ -464,7 +490,7 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_import_spare(uint32_t* __restr
     const uint32_t ep = genv[R_EPISODE] + 1u, lo = genv[R_SEED_LO], hi = genv[R_SEED_HI];
     worldgen_floor_block<GEN_THREADS, true>(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f, nullptr, nullptr, 0, GEN_THREADS, perlin_cs);
     if (f == 0) publish_world(genv, s_layout, lo, hi, ep, false, s_words);
-    if (threadIdx.x == 0) ls.tags[(size_t)env * NTAG + f] = make_uint2(ep, 0u);
+    if (threadIdx.x == 0) ls.tags[(size_t)env * NTAG + f] = make_uint2(pool ? 0u : ep, 0u);
 }
 
 // Noise mutation (section "Craftax-1B: UED"): one block per (environment, floor) of the floors
@@ -697,7 +723,7 @@ bool config_ok(const craftax_config* c, std::string* why)
     if (c->cap_zombie > 3 || c->cap_cow > 3 || c->cap_skeleton > 2) { *why = "caps: melee 0..3, passive 0..3, ranged 0..2"; return false; }
     if (c->cap_plant > (uint32_t)NPLANT) { *why = "cap_plant must be 0..10"; return false; }
     if (c->max_episode_steps == 0) { *why = "max_episode_steps must be positive"; return false; }
-    if (c->reset_mode != CRAFTAX_RESET_EXACT) { *why = "the Craftax variant has exact resets only (reset_mode must be EXACT)"; return false; }
+    if (c->reset_mode > CRAFTAX_RESET_POOL) { *why = "unknown reset_mode"; return false; }
     if (c->worldgen > CRAFTAX_WORLDGEN_PERLIN) { *why = "unknown worldgen"; return false; }
     return true;
 }
@@ -825,7 +851,7 @@ int state_init(void* state, const craftax_config* cfg, int n, void* stream, std:
 int reset(void* state, const craftax_config* cfg, int n, const uint64_t* seeds, void* stream, std::string* err)
 {
     const Ptrs q = pointers(state, make_header(cfg, n));
-    hipLaunchKernelGGL(kf_reset, dim3((unsigned)n * 2 * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, seeds, q.ls, gradients(cfg, q));
+    hipLaunchKernelGGL(kf_reset, dim3((unsigned)n * 2 * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, seeds, q.ls, gradients(cfg, q), cfg->reset_mode == CRAFTAX_RESET_POOL ? 1 : 0);
     return check_launch("craftax_reset", err);
 }
 
@@ -849,20 +875,24 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
     const int sb = (n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK;
     const int rb = FLOORS * n < REGEN_BLOCKS ? FLOORS * n : REGEN_BLOCKS;    // persistent blocks serving a queue: any number works
     const dim3 grid((unsigned)(rb + sb)), rgrid((unsigned)(n < RESET_SLOTS ? n : RESET_SLOTS) * FLOORS);
-    const bool slow = p.max_episode_steps == 1u;   // the only way an episode can end before its spare world exists
-    const bool eager = n <= EAGER_SPARE_ENVS;
+    const int pool = cfg->reset_mode == CRAFTAX_RESET_POOL ? 1 : 0;
+    // kf_reset_list serves the episodes that end before their spare world exists: with exact resets
+    // only one-step episodes can; with optimistic resets there are no spare worlds and every
+    // finished episode is served there, its world depending on who else finished
+    const bool slow = p.max_episode_steps == 1u || pool != 0;
+    const bool eager = n <= EAGER_SPARE_ENVS && pool == 0;
     const int perlin = cfg->worldgen == CRAFTAX_WORLDGEN_PERLIN ? 1 : 0;
     if (cfg->obs_mode == CRAFTAX_OBS_PIXELS_F32) {
         // the step runs without rendering; the picture is drawn from the state it leaves
         launch_step<false>(eager, perlin != 0, grid, st, q, actions, nullptr, reward, done, p, rb);
-        if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, (uint8_t*)nullptr, q.ls, perlin);
+        if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, (uint8_t*)nullptr, q.ls, perlin, done, n, pool);
         if (o != nullptr) hipLaunchKernelGGL(kf_pixels, dim3((unsigned)n), dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, o);
     } else if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) {
         launch_step<true>(eager, perlin != 0, grid, st, q, actions, o, reward, done, p, rb);
-        if (slow) hipLaunchKernelGGL(kf_reset_list<true>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls, perlin);
+        if (slow) hipLaunchKernelGGL(kf_reset_list<true>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls, perlin, done, n, pool);
     } else {
         launch_step<false>(eager, perlin != 0, grid, st, q, actions, o, reward, done, p, rb);
-        if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls, perlin);
+        if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls, perlin, done, n, pool);
     }
     return check_launch("craftax_step", err);
 }
@@ -871,6 +901,7 @@ int rollout(void* state, const craftax_config* cfg, int n, const int32_t* action
             void* stream, std::string* err)
 {
     if (cfg->obs_mode == CRAFTAX_OBS_PIXELS_F32) { *err = "craftax_rollout needs a symbolic observation"; return CRAFTAX_E_CONFIG; }
+    if (cfg->reset_mode != CRAFTAX_RESET_EXACT) { *err = "craftax_rollout needs exact resets"; return CRAFTAX_E_CONFIG; }
     const Ptrs q = pointers(state, make_header(cfg, n));
     const Params p = make_params(cfg, n);
     hipStream_t st = (hipStream_t)stream;
@@ -910,7 +941,7 @@ int import_envs(void* state, const craftax_config* cfg, int n, int first, int co
     const Ptrs q = pointers(state, make_header(cfg, n));
     hipLaunchKernelGGL(kf_import, dim3(count), dim3(BLOCK), 0, (hipStream_t)stream, q.envs, q.maps, q.ls,
                        static_cast<const craftax_full_env_dump*>(dumps), first, make_params(cfg, n));
-    hipLaunchKernelGGL(kf_import_spare, dim3((unsigned)count * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, q.ls, first, gradients(cfg, q));
+    hipLaunchKernelGGL(kf_import_spare, dim3((unsigned)count * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, q.ls, first, gradients(cfg, q), cfg->reset_mode == CRAFTAX_RESET_POOL ? 1 : 0);
     return check_launch("craftax_import_envs", err);
 }
 

@@ -317,6 +317,52 @@ def test_full_noise_mutation_matches_the_oracle(cx):
     other.close()
 
 
+def test_full_optimistic_pool_resets_match_the_oracle(cx):
+    """The paper's optimistic resets on the full game (reset_mode POOL): finished environments take
+    all nine floors, ladders and potion map from the step's pool in the order of their numbers."""
+    import torch
+    R = po.RESET_POOL
+    # short episodes: several resets per step, every pool position in use over time
+    finished, _, _ = run_full(cx, 200, 60, kind="skewed", state_every=1, max_episode_steps=7, reset_mode=R)
+    assert finished > 200 * 6
+    # every episode ends at every step: 48 environments share a pool of 3 worlds
+    run_full(cx, 48, 10, kind="uniform", state_every=1, max_episode_steps=1, reset_mode=R)
+    # a pool of one, a single environment, a ragged count, the flat and pixel layouts, Perlin worlds
+    run_full(cx, 9, 20, obs_mode=2, kind="uniform", state_every=1, max_episode_steps=3, reset_mode=R)
+    run_full(cx, 1, 12, kind="uniform", state_every=1, max_episode_steps=2, reset_mode=R)
+    run_full(cx, 131, 20, kind="uniform", state_every=5, max_episode_steps=5, reset_mode=R, worldgen=po.WORLDGEN_PERLIN)
+    # played from rich scenes on every floor with a long cap: deaths are rare and come from the pool of their step
+    run_full(cx, 180, 300, kind="uniform", state_every=50, prep=rich_scene, reset_mode=R)
+    # the worlds themselves: all 64 finish at once, environment i has rank i, the pool holds 4 worlds
+    n = 64
+    gcfg, ocfg = _cfgs(cx, 1, reset_mode=R, max_episode_steps=1)
+    sim = cx.Craftax(n, gcfg)
+    seeds = synth.seeds_for(n, 8)
+    sim.reset(seeds)
+    sim.step(torch.zeros(n, dtype=torch.int32, device=sim.device))
+    got = sim.export_envs().view(po.FULL_ENV_DTYPE).reshape(-1)
+    for i in range(n):
+        slot = po.pool_slot(int(seeds[0]), 0, i, n)
+        w = po.FullOracle(1, po.full_default_config())
+        w.reset(np.array([seeds[0]], np.uint64), env_ids=np.array([0x80000000 | slot], np.uint32))
+        assert np.array_equal(got[i]["block"], w.envs[0]["block"]) and np.array_equal(got[i]["potion_effect"], w.envs[0]["potion_effect"])
+        assert got[i]["seed"] == seeds[i] and got[i]["env"] == i and got[i]["episode"] == 1
+    assert len({g["block"].tobytes() for g in got}) == 4
+    # craftax_rollout needs exact resets
+    acts = torch.zeros((3, n), dtype=torch.int32, device=sim.device)
+    with pytest.raises(cx.CraftaxError):
+        cx.craftax_rollout(sim.state, acts, 3, sim.obs, torch.zeros((3, n), device=sim.device), torch.zeros((3, n), dtype=torch.uint8, device=sim.device),
+                           n, sim.stream)
+    sim.close()
+
+
+def test_full_optimistic_pool_resets_at_the_benchmark_size(cx):
+    """4,096 environments with a 40-step cap: about a hundred resets per step, all environments compared."""
+    finished, _, _ = run_full(cx, 4096, 90, kind="uniform", obs_every=15, state_every=45, max_episode_steps=40, reset_mode=po.RESET_POOL,
+                              device_actions=True, progress=30)
+    assert finished >= 4096 * 2
+
+
 @pytest.mark.parametrize("n", [1, 3, 5, 130])
 def test_full_ragged_counts(cx, n):
     run_full(cx, n, 120, kind="skewed", seed_base=50 + n)

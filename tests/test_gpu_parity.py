@@ -731,7 +731,7 @@ def test_optimistic_pool_worlds_and_refusals(cx):
         cx.craftax_rollout(sim.state, d_acts, 2, sim.obs, d_rew, d_done, n, sim.stream)
     sim.close()
     assert cx.craftax_state_bytes(cx.default_config(reset_mode=2), 8) == 0
-    assert cx.craftax_state_bytes(cx.default_config(cx.VARIANT_CRAFTAX, reset_mode=po.RESET_POOL), 8) == 0
+    assert cx.craftax_state_bytes(cx.default_config(cx.VARIANT_CRAFTAX, reset_mode=2), 8) == 0
 
 
 def test_optimistic_pool_resets_at_the_benchmark_size(cx):

@@ -71,7 +71,8 @@ def test_full_game_accepts_only_its_own_options(lib):
     ok = binding.default_config(binding.VARIANT_CRAFTAX)
     assert binding.craftax_state_bytes(ok, 8) > 0
     assert binding.craftax_state_bytes(binding.default_config(binding.VARIANT_CRAFTAX, worldgen=binding.WORLDGEN_PERLIN), 8) > 0
-    for field, value in [("worldgen", 2), ("reset_mode", binding.RESET_POOL), ("obs_mode", binding.OBS_SYM_U8_I8)]:
+    assert binding.craftax_state_bytes(binding.default_config(binding.VARIANT_CRAFTAX, reset_mode=binding.RESET_POOL), 8) > 0
+    for field, value in [("worldgen", 2), ("reset_mode", 2), ("obs_mode", binding.OBS_SYM_U8_I8)]:
         assert binding.craftax_state_bytes(binding.default_config(binding.VARIANT_CRAFTAX, **{field: value}), 8) == 0
     # the state grows linearly and stays 256-byte aligned
     sizes = [binding.craftax_state_bytes(ok, n) for n in (1, 2, 64, 4096)]
