@@ -79,3 +79,20 @@ def test_host_side_argument_errors(lib):
     assert lib.craftax_step(ctypes.c_void_p(4096), None, None, None, None, 4, None) == -4
     assert lib.craftax_last_error() != b""
     assert lib.craftax_state_release(ctypes.c_void_p(4096)) == -4
+
+
+def test_header_constants_match_their_python_mirrors():
+    """The binding (and, separately, the oracle's wrapper) restate the header's numbers; a change on
+    one side only would shift every array row."""
+    from oracle import pyoracle as po
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    text = open(os.path.join(root, "include", "craftax.h")).read()
+    defines = {k: int(v) for k, v in re.findall(r"#define\s+(CRAFTAX_\w+)\s+(\d+)\s*$", text, re.M)}
+    enums = {k: int(v) for k, v in re.findall(r"(CRAFTAX_\w+)\s*=\s*(\d+)", text)}
+    assert defines["CRAFTAX_THETA_LEN"] == binding.THETA_LEN == po.THETA_LEN == 2 * 25 + 4 * 81
+    assert defines["CRAFTAX_FULL_THETA_LEN"] == binding.FULL_THETA_LEN == po.FULL_THETA_LEN == 2 * 16 + 4 * 49 + 4 * 2 * 49
+    assert enums["CRAFTAX_WORLDGEN_VALUE"] == binding.WORLDGEN_VALUE == po.WORLDGEN_VALUE
+    assert enums["CRAFTAX_WORLDGEN_PERLIN"] == binding.WORLDGEN_PERLIN == po.WORLDGEN_PERLIN
+    assert enums["CRAFTAX_RESET_EXACT"] == binding.RESET_EXACT == po.RESET_EXACT
+    assert enums["CRAFTAX_RESET_POOL"] == binding.RESET_POOL == po.RESET_POOL
+    assert enums["CRAFTAX_VARIANT_CLASSIC"] == binding.VARIANT_CLASSIC and enums["CRAFTAX_VARIANT_CRAFTAX"] == binding.VARIANT_CRAFTAX
