@@ -169,6 +169,80 @@ def test_worldgen_histogram_and_start_area():
     assert frac[DIAMOND] < frac[IRON] < frac[COAL] < frac[STONE]
 
 
+def _world_numbers(seed, env, episode, stream, count):
+    """u16 numbers 0..count-1 of a world-generation stream, straight from the known-answer-tested
+    Philox: counter (env, stream, episode, WORLDGEN << 16 | block), two numbers per word, low half first."""
+    out = []
+    for block in range((count + 7) // 8):
+        for w in po.philox([env, stream, episode, (1 << 16) | block], [seed & 0xFFFFFFFF, seed >> 32]):
+            out += [w & 0xFFFF, w >> 16]
+    return np.array(out[:count], np.int64)
+
+
+def _value_field(lat, width, spacing):
+    return np.array([[_noise(lat, width, spacing, x, y) for x in range(64)] for y in range(64)], np.int64)
+
+
+@pytest.mark.parametrize("seed,env,episode", [(0, 0, 0), (0x1234567890AB, 11, 2), (77, 65535, 1)])
+def test_value_worldgen_rebuilt_from_the_lattice_numbers(seed, env, episode):
+    """The whole value-noise map recomputed here, cell for cell: lattice numbers and per-cell
+    uniforms from Philox, the six fields from the (separately pinned) noise function, then the
+    terrain rule painted layer by layer from the least to the most specific case.  Which lattice
+    feeds which field, the 3:1 mix, the start-area bias and the order of the thresholds all show."""
+    lat = _world_numbers(seed, env, episode, 0, po.THETA_LEN).astype(np.uint16)
+    u = _world_numbers(seed, env, episode, 1, 64 * 64).reshape(64, 64)
+    n16 = [_value_field(lat[25 * i:25 * i + 25].reshape(5, 5), 5, 16) for i in range(2)]
+    n8 = [_value_field(lat[50 + 81 * i:50 + 81 * i + 81].reshape(9, 9), 9, 8) for i in range(4)]
+    W = (3 * n16[0] + n8[0]) >> 2
+    M = (3 * n16[1] + n8[1]) >> 2
+    C, F = n8[2], n8[3]
+    yy, xx = np.mgrid[0:64, 0:64]
+    d = np.maximum(abs(xx - 32), abs(yy - 32))
+    bias = np.where(d < 10, (10 - d) * 2500, 0)
+    W = np.maximum(0, W - bias)
+    M = np.maximum(0, M - bias)
+    # lowlands, least specific first
+    m = np.full((64, 64), GRASS)
+    m[u < 1300] = TREE
+    m[(F > 33500) & (u < 26000)] = TREE
+    m[W > 37800] = SAND
+    m[W > 39500] = WATER
+    # mountains, again from the fallback up to the first rule
+    rock = M > 39500
+    m[rock] = STONE
+    m[rock & (u >= 3000) & (u < 8000)] = COAL
+    m[rock & (F < 33000) & (u >= 500) & (u < 3000)] = IRON
+    m[rock & (M > 42000) & (u < 500)] = DIAMOND
+    m[rock & (M > 43000) & (F > 44000)] = LAVA
+    m[rock & (abs(C - 30000) < 1300)] = PATH
+    m[rock & (C > 43000) & (M > 41000)] = PATH
+    m[d <= 2] = GRASS
+    got = po.worldgen(seed, env, episode)
+    assert np.array_equal(got, m), np.argwhere(got != m)[:5]
+    # the pin bites: with the cave and forest lattices exchanged the map would differ
+    swapped = m.copy()
+    swapped[rock & (abs(F - 30000) < 1300)] = PATH
+    assert not np.array_equal(swapped, m)
+
+
+def test_value_noise_is_smoothstep_bilinear_interpolation():
+    """orc_value_noise against the definition in exact rationals: bilinear blend of the four
+    surrounding lattice numbers with weights smoothstep(k/S) = 3t^2 - 2t^3 (rounded to 1/256)."""
+    from fractions import Fraction
+    rng = np.random.default_rng(12)
+    for spacing, width in ((8, 9), (16, 5)):
+        lat = rng.integers(0, 65536, size=(width, width)).astype(np.uint16)
+        for y in range(0, 64, 3):
+            for x in range(0, 64, 5):
+                i, j = x // spacing, y // spacing
+                tx, ty = Fraction(x % spacing, spacing), Fraction(y % spacing, spacing)
+                sx, sy = 3 * tx ** 2 - 2 * tx ** 3, 3 * ty ** 2 - 2 * ty ** 3
+                a, b, c, dd = (int(lat[j, i]), int(lat[j, i + 1]), int(lat[j + 1, i]), int(lat[j + 1, i + 1]))
+                exact = (a * (1 - sx) + b * sx) * (1 - sy) + (c * (1 - sx) + dd * sx) * sy
+                # weights are kept in 1/256 units (error < 1/512 each) and the result is floored
+                assert abs(_noise(lat, width, spacing, x, y) - exact) <= 1 + 65535 * Fraction(2, 512)
+
+
 # ------------------------------------------------------------ helpers ----
 def blank(n=1, block=GRASS, caps=0, **cfgkw):
     """Environments with a uniform map and, by default, spawning switched off."""
@@ -791,6 +865,59 @@ def test_pixel_observation_structure():
     # another atlas seed gives another picture
     o.cfg.atlas_seed = 1
     assert not np.array_equal(o.observe_one(0, po.OBS_PIXELS_F32), img1.tobytes())
+
+
+def _atlas_numbers(atlas_seed, stream, count):
+    """Words 0..count-1 of an atlas stream from the known-answer-tested Philox: counter
+    (0, stream, 0, ATLAS << 16 | block), key = the atlas seed."""
+    out = []
+    for block in range((count + 3) // 4):
+        out += po.philox([0, stream, 0, (3 << 16) | block], [atlas_seed & 0xFFFFFFFF, atlas_seed >> 32])
+    return np.array(out[:count], np.uint32)
+
+
+@pytest.mark.parametrize("atlas_seed", [0, 0xABCDEF0123])
+def test_pixel_observation_rebuilt_from_philox(atlas_seed):
+    """The 63 x 63 x 3 picture rebuilt here from Philox words alone: block tiles [16][7][7][3]
+    (stream 0, index block id - 1), entity tiles [5][7][7][3] (stream 1: player, zombie, cow,
+    skeleton, arrow), one-bit masks [5][7][7] (stream 2, top bit), texel = (word >> 8) / 2^24, one
+    multiply by the daylight value.  The scene sits at the map edge and holds every entity type."""
+    tile = ((_atlas_numbers(atlas_seed, 0, 16 * 147) >> 8).astype(np.float32) * np.float32(2.0 ** -24)).reshape(16, 7, 7, 3)
+    ent = ((_atlas_numbers(atlas_seed, 1, 5 * 147) >> 8).astype(np.float32) * np.float32(2.0 ** -24)).reshape(5, 7, 7, 3)
+    mask = (_atlas_numbers(atlas_seed, 2, 5 * 49) >> 31).astype(bool).reshape(5, 7, 7)
+    assert 0.3 < mask.mean() < 0.7
+    o = blank(atlas_seed=atlas_seed)
+    e = o.envs[0]
+    rng = np.random.default_rng(4)
+    e["map"][:] = rng.integers(2, 17, size=(64, 64))        # every block id somewhere
+    e["px"], e["py"] = 2, 62                                 # two columns and one row from the edges
+    e["t"] = 40
+    e["mob"][1] = (1, 4, 60, 0, 5, 0, (0, 0))                # zombie
+    e["mob"][3] = (1, 0, 63, 0, 3, 0, (0, 0))                # cow in the map corner
+    e["mob"][8] = (1, 6, 59, 0, 3, 0, (0, 0))                # skeleton
+    e["mob"][11] = (1, 1, 62, 2, 0, 0, (0, 0))               # arrow next to the player
+    e["mob"][4] = (1, 7, 62, 0, 3, 0, (0, 0))                # cow one column outside the 9 x 9 view
+    who = {(2, 62): 0, (4, 60): 1, (0, 63): 2, (6, 59): 3, (1, 62): 4}
+    light = np.float32(L.orc_daylight(ctypes.byref(o.cfg), ctypes.c_uint32(40)))
+    assert 0 < light < 1
+    want = np.zeros((63, 63, 3), np.float32)
+    for tr in range(9):
+        for tc in range(9):
+            x, y = 2 + tc - 4, 62 + tr - 4
+            inside = 0 <= x < 64 and 0 <= y < 64
+            block = int(e["map"][y, x]) if inside else 1
+            texels = tile[block - 1].copy()
+            if inside and (x, y) in who:
+                k = who[(x, y)]
+                texels[mask[k]] = ent[k][mask[k]]
+            want[tr * 7:tr * 7 + 7, tc * 7:tc * 7 + 7] = texels * light
+    raw = o.observe_one(0, po.OBS_PIXELS_F32)
+    got = raw[:63 * 63 * 3 * 4].view(np.float32).reshape(63, 63, 3)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), np.argwhere(got != want)[:5]
+    assert not raw[63 * 63 * 3 * 4:].any()                   # the stride's padding is zero
+    # the pin bites: a tile transposed within itself, or rows and columns of tiles exchanged, differ
+    assert not np.array_equal(want, want.reshape(9, 7, 9, 7, 3).transpose(0, 3, 2, 1, 4).reshape(63, 63, 3))
+    assert not np.array_equal(want, want.transpose(1, 0, 2))
 
 
 # --------------------------------------------------- invariants on rollouts ----
