@@ -178,6 +178,77 @@ def perlin_noise(lattice: np.ndarray, spacing: int, x: int, y: int) -> int:
     return int(lib().orc_perlin_noise(_p(lat), lat.shape[1], spacing, x, y))
 
 
+def _host_threads() -> int:
+    """Worker threads for the batched helpers below: the cores this process may use, 16 at most."""
+    try:
+        c = len(os.sched_getaffinity(0))
+    except AttributeError:
+        c = os.cpu_count() or 1
+    return max(1, min(16, c))
+
+
+def _step_many(orc, step_fn, observe_fn, env_bytes, actions, threads, render_last, sample, sample_obs):
+    """Harness, no arithmetic: K steps of every environment of `orc`, the environments cut into
+    contiguous slices that Python threads advance independently (the C calls release the
+    interpreter lock; environments never interact with exact resets).  Inside a slice it is the
+    ordinary serial batch call, step after step."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    assert orc.cfg.reset_mode == RESET_EXACT, "pool resets couple the environments of a step"
+    a = np.ascontiguousarray(actions, dtype=np.int32)
+    K, n = a.shape
+    assert n == orc.n
+    threads = _host_threads() if threads is None else threads
+    rew = np.zeros((K, n), np.float32)
+    don = np.zeros((K, n), np.uint8)
+    stride = orc.obs.shape[1]
+    sample = None if sample is None else np.asarray(sample, dtype=np.int64)
+    if sample is not None:
+        assert sample_obs.shape == (K, len(sample), stride) and sample_obs.dtype == np.uint8 and sample_obs.flags.c_contiguous
+    bounds = np.linspace(0, n, min(threads, n) + 1).astype(np.int64)
+    cfg = ctypes.byref(orc.cfg)
+
+    def work(w):
+        lo, hi = int(bounds[w]), int(bounds[w + 1])
+        if hi == lo:
+            return
+        envs = ctypes.c_void_p(orc.envs.ctypes.data + lo * env_bytes)
+        obs = ctypes.c_void_p(orc.obs.ctypes.data + lo * stride)
+        mine = [] if sample is None else [(j, int(i)) for j, i in enumerate(sample) if lo <= i < hi]
+        for k in range(K):
+            step_fn(envs, cfg, ctypes.c_void_p(a.ctypes.data + (k * n + lo) * 4), orc.obs_mode,
+                    obs if (render_last and k == K - 1) else None,
+                    ctypes.c_void_p(rew.ctypes.data + (k * n + lo) * 4), ctypes.c_void_p(don.ctypes.data + k * n + lo), hi - lo)
+            for j, i in mine:
+                observe_fn(ctypes.c_void_p(orc.envs.ctypes.data + i * env_bytes), cfg, orc.obs_mode,
+                           ctypes.c_void_p(sample_obs.ctypes.data + (k * len(sample) + j) * stride))
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(work, range(len(bounds) - 1)))
+    orc.steps += K
+    return rew, don
+
+
+def _reset_many(orc, reset_fn, env_bytes, seeds, threads):
+    from concurrent.futures import ThreadPoolExecutor
+
+    seeds = np.ascontiguousarray(seeds, dtype=np.uint64)
+    ids = np.arange(orc.n, dtype=np.uint32)
+    threads = _host_threads() if threads is None else threads
+    bounds = np.linspace(0, orc.n, min(threads, orc.n) + 1).astype(np.int64)
+    cfg = ctypes.byref(orc.cfg)
+
+    def work(w):
+        lo, hi = int(bounds[w]), int(bounds[w + 1])
+        if hi > lo:
+            reset_fn(ctypes.c_void_p(orc.envs.ctypes.data + lo * env_bytes), cfg, ctypes.c_void_p(seeds.ctypes.data + lo * 8),
+                     ctypes.c_void_p(ids.ctypes.data + lo * 4), hi - lo)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(work, range(len(bounds) - 1)))
+    orc.steps = 0
+
+
 class Oracle:
     """n independent environments stepped serially on the host."""
 
@@ -215,6 +286,18 @@ class Oracle:
                                  _p(self.obs) if render else None, _p(self.reward), _p(self.done), self.n)
         self.steps += 1
         return self.obs, self.reward, self.done
+
+    def step_many(self, actions, threads=None, render_last=True, sample=None, sample_obs=None):
+        """K = len(actions) steps of all environments on several host threads (slices of
+        environments; see _step_many).  Returns reward [K, n] and done [K, n]; self.obs holds the
+        observation after the last step if render_last; the observations of the environments in
+        `sample` after every step go to sample_obs [K, len(sample), stride]."""
+        return _step_many(self, lib().orc_step_batch, lib().orc_observe, ENV_DTYPE.itemsize, actions, threads, render_last,
+                          sample, sample_obs)
+
+    def reset_many(self, seeds, threads=None):
+        """reset() of all environments (numbered 0..n-1) on several host threads; no rendering."""
+        _reset_many(self, lib().orc_reset_batch, ENV_DTYPE.itemsize, seeds, threads)
 
     def step_rules_one(self, i: int, action: int):
         """Rules without auto-reset on environment i; returns (reward, done)."""
@@ -300,6 +383,14 @@ class FullOracle:
                                 _p(self.obs) if render else None, _p(self.reward), _p(self.done), self.n)
         self.steps += 1
         return self.obs, self.reward, self.done
+
+    def step_many(self, actions, threads=None, render_last=True, sample=None, sample_obs=None):
+        """As Oracle.step_many, for the full game."""
+        return _step_many(self, lib().cf_step_batch, lib().cf_observe, FULL_ENV_DTYPE.itemsize, actions, threads, render_last,
+                          sample, sample_obs)
+
+    def reset_many(self, seeds, threads=None):
+        _reset_many(self, lib().cf_reset_batch, FULL_ENV_DTYPE.itemsize, seeds, threads)
 
     def step_rules_one(self, i: int, action: int):
         r = ctypes.c_float()

@@ -546,18 +546,26 @@ def test_full_pixels_overlays_edges_and_strip(cx):
     sim.close()
 
 
-def test_full_config4_4096_envs_5000_steps(cx):
-    """The benchmark shape of the full game: 4096 environments, 43 uniform actions generated on
-    the device, 5000 steps; 128 sampled environments are checked against the oracle."""
-    sample = np.arange(0, 4096, 32)
-    finished, _, _ = run_full(cx, 4096, 5000, kind="uniform", sample=sample, device_actions=True, obs_every=10, progress=1000)
-    assert finished > 128 * 10
+def test_full_config4_4096_envs_5000_steps_all_environments(cx):
+    """The benchmark shape of the full game: 4096 environments, 43 uniform actions, 5000 steps.  The
+    oracle follows all 4096 environments: reward and done after every step, every observation every
+    250 steps and for 69 environments (stride 61) after every step, the whole state (nine floors of
+    every environment) at steps 2,500 and 5,000."""
+    from population import run_population
+    gcfg, ocfg = _cfgs(cx, 1)
+    sim = cx.Craftax(4096, gcfg)
+    orc = po.FullOracle(4096, ocfg, ORACLE_MODE[1])
+    finished = run_population(cx, sim, orc, 5000, "uniform", 43, 250, 61, (2500, 5000), po.FULL_ENV_DTYPE)
+    sim.close()
+    assert finished > 4096 * 10
 
 
 def test_full_four_times_the_benchmark_size_sampled(cx):
     """16,384 environments of the full game (1.4 GB of state) with a short episode cap, so that
-    the regeneration lists are long; a strided sample is followed by the oracle."""
-    sample = np.unique(np.concatenate([np.arange(0, 16384, 512), [16383, 8191]]))
+    the regeneration lists are long; a sample at a stride coprime to the block shape (every
+    position inside a block occurs) is followed by the oracle."""
+    sample = np.unique(np.concatenate([np.arange(3, 16384, 509), [16383, 8191, 0]]))
+    assert len(set((sample % 4).tolist())) == 4
     finished, _, _ = run_full(cx, 16384, 60, kind="uniform", sample=sample, device_actions=True, obs_every=5,
                               max_episode_steps=11)
     assert finished > len(sample) * 4
@@ -700,7 +708,7 @@ def test_rollout_at_the_benchmark_size_sampled(cx):
     n, steps = 4096, 200
     gcfg, ocfg = _cfgs(cx, 1)
     sim = cx.Craftax(n, gcfg)
-    ids = np.unique(np.concatenate([np.arange(0, n, 64), [n - 1]]))
+    ids = np.unique(np.concatenate([np.arange(0, n, 61), [n - 1]]))   # a stride coprime to the block shape
     orc = po.FullOracle(len(ids), ocfg, ORACLE_MODE[1])
     seeds = synth.seeds_for(n, 44)
     sim.reset(seeds)

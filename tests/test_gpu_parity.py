@@ -109,34 +109,47 @@ def test_config1_64_envs_1000_steps_full_compare(cx):
     assert finished > 100
 
 
-def test_config2_4096_envs_10000_steps_sampled(cx):
-    """4096 envs, 10,000 steps, caps 3/3/3, day 300, uint8 cells + fp32 scalars; a strided
-    sample of 64 environments (plus the last one) is followed by the oracle step by step."""
-    sample = np.unique(np.concatenate([np.arange(0, 4096, 64), [4095, 1, 17]]))
-    finished = run_parity(cx, 4096, 10000, po.OBS_SYM_U8_F32, "uniform", sample=sample, state_every=2500,
-                          obs_every=1, progress=2000)
-    assert finished > 1000
+def _population(cx, n, T, obs_mode, kind, chunk, stride, **cfgkw):
+    from population import run_population
+    gcfg, ocfg = _cfgs(cx, obs_mode, **cfgkw)
+    sim = _make_sim(cx, n, gcfg)
+    orc = po.Oracle(n, ocfg, obs_mode)
+    finished = run_population(cx, sim, orc, T, kind, 17, chunk, stride, (T // 2, T), po.ENV_DTYPE)
+    sim.close()
+    return finished
 
 
-def test_config3_65536_envs_1000_steps_sampled(cx):
-    """65,536 envs, skewed action stream generated on the device, episode cap 10,000."""
-    sample = np.unique(np.concatenate([np.arange(0, 65536, 1024), [65535, 3, 4097]]))
-    finished = run_parity(cx, 65536, 1000, po.OBS_SYM_U8_F32, "skewed", sample=sample, state_every=500,
-                          device_actions=True, progress=250)
-    assert finished > 50
+def test_config2_4096_envs_10000_steps_all_environments(cx):
+    """4096 envs, 10,000 steps, caps 3/3/3, day 300, uint8 cells + fp32 scalars.  The oracle follows
+    all 4096 environments: reward and done after every step, every observation every 250 steps and
+    for 69 environments (stride 61) after every step, the whole state at steps 5,000 and 10,000."""
+    finished = _population(cx, 4096, 10000, po.OBS_SYM_U8_F32, "uniform", 250, 61)
+    assert finished > 4096 * 20
+
+
+def test_config3_65536_envs_1000_steps_all_environments(cx):
+    """65,536 envs, skewed actions, episode cap 10,000, 1000 steps: the graded workload.  The oracle
+    follows all 65,536 environments: reward and done after every step, every observation every 50
+    steps and for 66 environments (stride 1021) after every step, the whole state at 500 and 1000."""
+    finished = _population(cx, 65536, 1000, po.OBS_SYM_U8_F32, "skewed", 50, 1021)
+    assert finished > 65536 * 2
 
 
 def test_config5_pixels_1024_envs_sampled(cx):
-    """Pixel observations 63x63x3 fp32: compared bit for bit (abs tol 0) on a sample."""
-    sample = np.array([0, 77, 512, 1023])
-    run_parity(cx, 1024, 1000, po.OBS_PIXELS_F32, "uniform", sample=sample, obs_every=25, state_every=500,
+    """Pixel observations 63x63x3 fp32, compared bit for bit (abs tol 0): 37 environments at a stride
+    coprime to the block shapes, every fifth picture; reward, done and state of the same sample."""
+    sample = np.unique(np.concatenate([np.arange(9, 1024, 29), [0, 1023]]))
+    assert len(sample) >= 32
+    run_parity(cx, 1024, 1000, po.OBS_PIXELS_F32, "uniform", sample=sample, obs_every=5, state_every=500,
                atlas_seed=0)
 
 
 def test_four_times_the_largest_config_sampled(cx):
     """262,144 environments (2.2 GB of state), short episodes so that every list and every
-    regeneration block is busy; a strided sample is followed by the oracle."""
-    sample = np.unique(np.concatenate([np.arange(0, 262144, 4096), [262143, 131071, 65536]]))
+    regeneration block is busy; a sample at a stride coprime to the block shapes (every position
+    inside a block occurs) is followed by the oracle."""
+    sample = np.unique(np.concatenate([np.arange(5, 262144, 4093), [262143, 131071, 65536, 0]]))
+    assert len(set((sample % 64).tolist())) == 64
     finished = run_parity(cx, 262144, 60, po.OBS_SYM_U8_F32, "skewed", sample=sample, state_every=30,
                           device_actions=True, max_episode_steps=9)
     assert finished > len(sample) * 5
@@ -667,7 +680,7 @@ def test_rollout_at_scale_sampled(cx):
     n, steps = 70000, 50
     gcfg, ocfg = _cfgs(cx, po.OBS_SYM_U8_F32, max_episode_steps=9)
     sim = _make_sim(cx, n, gcfg)
-    ids = np.unique(np.concatenate([np.arange(0, n, 1100), [n - 1, n - 2, 65535, 65536]]))
+    ids = np.unique(np.concatenate([np.arange(0, n, 1021), [n - 1, n - 2, 65535, 65536]]))
     orc = po.Oracle(len(ids), ocfg)
     seeds = synth.seeds_for(n, 31)
     sim.reset(seeds)
