@@ -81,6 +81,52 @@ def read_profile_traffic(name: str):
     return float(m.group(1)) if m else None
 
 
+SPIN_UP_STEPS = 2000       # untimed steps before any timed region: episodes last ~180 steps, so every
+                           # environment has been through several and the batch is in its steady state
+LENGTH_WINDOW = 1000       # the last steps of the spin-up, over which the mean episode length is taken
+
+
+def episode_sum(sim) -> int:
+    """Sum of the episode counters of all environments (episodes finished since the reset)."""
+    total = 0
+    chunk = 512 if sim.cfg.variant == 1 else 8192
+    for first in range(0, sim.n, chunk):
+        d = sim.export_envs(first, min(chunk, sim.n - first))
+        total += int(d.view(sim.dump_dtype)["episode"].sum())
+    return total
+
+
+def advance(cx, sim, kind_id: int, first_step: int, steps: int, use_rollout: bool) -> int:
+    """Untimed: `steps` steps of the workload's own action stream without rendering, through
+    craftax_rollout where the configuration allows it (faster), else step by step."""
+    import torch
+
+    n, chunk = sim.n, 250
+    actions = torch.empty((chunk, n), dtype=torch.int32, device=sim.device)
+    reward = torch.empty((chunk, n), dtype=torch.float32, device=sim.device)
+    done = torch.empty((chunk, n), dtype=torch.uint8, device=sim.device)
+    for s0 in range(first_step, first_step + steps, chunk):
+        k = min(chunk, first_step + steps - s0)
+        cx.craftax_synth_actions(actions, n, s0, k, 0, kind_id, sim.stream)
+        if use_rollout:
+            cx.craftax_rollout(sim.state, actions, k, None, reward, done, n, sim.stream)
+        else:
+            for j in range(k):
+                cx.craftax_step(sim.state, actions[j], None, reward[j], done[j], n, sim.stream)
+    torch.cuda.synchronize()
+    return first_step + steps
+
+
+def spin_up(cx, sim, kind_id: int, use_rollout: bool):
+    """Brings a freshly reset batch to its steady state (outside every timed region) and measures
+    the mean episode length over a fixed window.  Returns (next action step, mean episode length)."""
+    s = advance(cx, sim, kind_id, 0, SPIN_UP_STEPS - LENGTH_WINDOW, use_rollout)
+    before = episode_sum(sim)
+    s = advance(cx, sim, kind_id, s, LENGTH_WINDOW, use_rollout)
+    finished = episode_sum(sim) - before
+    return s, sim.n * LENGTH_WINDOW / max(finished, 1)
+
+
 def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, variant: str = "classic", pixels: bool = False,
             pool_resets: bool = False):
     import torch
@@ -94,10 +140,11 @@ def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, varian
                                 reset_mode=cx.RESET_POOL if pool_resets else cx.RESET_EXACT)
     sim = cx.Craftax(n, cfg)
     sim.reset(synth.seeds_for(n))
-    total_steps = warmup + repeats * steps
     kind_id = {"uniform": 0, "skewed": 1}[kind] + (2 if variant == "craftax" else 0)
+    step0, mean_len = spin_up(cx, sim, kind_id, use_rollout=not (pixels or pool_resets))
+    total_steps = warmup + repeats * steps
     actions = torch.empty((total_steps, n), dtype=torch.int32, device=dev)
-    cx.craftax_synth_actions(actions, n, 0, total_steps, 0, kind_id, sim.stream)
+    cx.craftax_synth_actions(actions, n, step0, total_steps, 0, kind_id, sim.stream)
     torch.cuda.synchronize()
 
     # the launches go to torch's current stream, so torch events bracket exactly that stream
@@ -131,17 +178,9 @@ def gpu_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, varian
         e1.record(stream)
         torch.cuda.synchronize()
         draw_s = e0.elapsed_time(e1) * 1e-3 / steps
-    # episodes finished so far -> mean episode length (drives the amortised reset bytes)
-    episodes = 0
-    chunk = 512 if variant == "craftax" else 8192
-    for first in range(0, n, chunk):
-        d = sim.export_envs(first, min(chunk, n - first))
-        episodes += int(d.view(sim.dump_dtype)["episode"].sum())
-    mean_len = (n * total_steps) / max(episodes, 1)
     sim.close()
     med = int(np.argsort(wall)[len(wall) // 2])
-    return {"wall_s": wall[med], "event_s": evt[med], "all_wall_s": wall, "episodes": episodes, "mean_episode_len": mean_len,
-            "draw_s": draw_s}
+    return {"wall_s": wall[med], "event_s": evt[med], "all_wall_s": wall, "mean_episode_len": mean_len, "draw_s": draw_s}
 
 
 def rollout_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, variant: str = "classic"):
@@ -157,11 +196,13 @@ def rollout_run(n: int, steps: int, warmup: int, kind: str, repeats: int = 3, va
         kind_id = {"uniform": 2, "skewed": 3}[kind]
     sim = cx.Craftax(n, cfg)
     sim.reset(synth.seeds_for(n))
-    total = warmup + repeats * steps
+    step0, _ = spin_up(cx, sim, kind_id, use_rollout=True)
+    total = max(warmup, 1) + repeats * steps
+    warmup = max(warmup, 1)
     actions = torch.empty((total, n), dtype=torch.int32, device=sim.device)
-    cx.craftax_synth_actions(actions, n, 0, total, 0, kind_id, sim.stream)
-    reward = torch.zeros((steps, n), dtype=torch.float32, device=sim.device)
-    done = torch.zeros((steps, n), dtype=torch.uint8, device=sim.device)
+    cx.craftax_synth_actions(actions, n, step0, total, 0, kind_id, sim.stream)
+    reward = torch.zeros((max(steps, warmup), n), dtype=torch.float32, device=sim.device)
+    done = torch.zeros((max(steps, warmup), n), dtype=torch.uint8, device=sim.device)
     cx.craftax_rollout(sim.state, actions[:warmup], warmup, sim.obs, reward[:warmup], done[:warmup], n, sim.stream)
     torch.cuda.synchronize()
     wall = []
@@ -193,25 +234,59 @@ def copy_ceiling_gbs(mib: int = 1024, repeats: int = 10) -> float:
     return 2.0 * (mib << 20) * repeats / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
-def cpu_baseline(n_sample: int, steps: int, kind: str, variant: str = "classic", pixels: bool = False):
-    """The CPU oracle, as it stands, on the first n_sample environments of the same workload."""
+CPU_SAMPLE_ENVS, CPU_SAMPLE_STEPS = 8192, 1000         # one core: about 10 s of oracle work
+CPU_ALL_ENVS, CPU_ALL_STEPS = 65536, 300               # all cores: the whole population of the headline workload
+
+
+def cpu_baseline(kind: str, variant: str = "classic", pixels: bool = False, n_sample: int | None = None, steps: int | None = None):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload (its size does not
+    depend on --steps): the first environments, from their reset on, on one core; and the same
+    oracle over more environments on all host cores (slices of environments on threads: the
+    environments are independent).  The resets are not timed."""
     from oracle import pyoracle as po
     from paper_2402_16801_amd import synth
 
-    if variant == "craftax":
-        acts = synth.action_block(n_sample, steps, kind, 0, n_actions=43)
-        orc = po.FullOracle(n_sample, po.full_default_config(), po.FULL_OBS_PIXELS_F32 if pixels else po.FULL_OBS_U8_F32)
-    else:
-        acts = synth.action_block(n_sample, steps, kind, 0)
-        orc = po.Oracle(n_sample, po.default_config(max_episode_steps=10000), po.OBS_SYM_U8_F32)
-    orc.reset(synth.seeds_for(n_sample))
-    t0 = time.perf_counter()
+    def make(n):
+        if variant == "craftax":
+            return po.FullOracle(n, po.full_default_config(), po.FULL_OBS_PIXELS_F32 if pixels else po.FULL_OBS_U8_F32)
+        return po.Oracle(n, po.default_config(max_episode_steps=10000), po.OBS_SYM_U8_F32)
+
+    n_actions = 43 if variant == "craftax" else 17
+    what = "pixel" if pixels else "symbolic"
+    if n_sample is None:
+        n_sample, steps = (CPU_SAMPLE_ENVS, CPU_SAMPLE_STEPS) if variant == "classic" else (1024, 1000)
+    orc = make(n_sample)
+    orc.reset_many(synth.seeds_for(n_sample))
+    t0, done_steps = time.perf_counter(), 0
     for s in range(steps):
-        orc.step(acts[s])
+        orc.step(synth.actions(np.arange(n_sample), s, kind, 0, n_actions))
+        done_steps += 1
+        if time.perf_counter() - t0 > 20.0:
+            break
     dt = time.perf_counter() - t0
-    return {"value": n_sample * steps / dt, "unit": "env_steps/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {n_sample} envs x {steps} steps of the same workload, single thread, "
-                      f"including the {'pixel' if pixels else 'symbolic'} observation ({dt:.1f} s)"}
+    one = {"value": n_sample * done_steps / dt, "unit": "env_steps/s", "cores": 1, "kind": "oracle",
+           "sample": f"first {n_sample} envs x {done_steps} steps of the same workload from the reset on, single thread, "
+                     f"including the {what} observation of every step and the action draws ({dt:.1f} s)"}
+    if pixels:
+        return one, None
+    threads = po._host_threads()
+    n_all, k_all = (CPU_ALL_ENVS, CPU_ALL_STEPS) if variant == "classic" else (4096, 1000)
+    orc = make(n_all)
+    orc.reset_many(synth.seeds_for(n_all))
+    chunk, done_steps, dt = 50, 0, 0.0
+    for s0 in range(0, k_all, chunk):
+        acts = synth.action_block(n_all, chunk, kind, 0, s0, n_actions)
+        t0 = time.perf_counter()
+        # every step renders nothing but the last of a chunk: the rules are timed, as in the parity runs
+        orc.step_many(acts, threads=threads)
+        dt += time.perf_counter() - t0
+        done_steps += chunk
+        if dt > 20.0:
+            break
+    allc = {"value": n_all * done_steps / dt, "unit": "env_steps/s", "cores": threads, "kind": "oracle",
+            "sample": f"all {n_all} envs x {done_steps} steps of the same workload from the reset on, {threads} threads over slices "
+                      f"of environments, rules and auto-resets of every step, observation once per {chunk} steps ({dt:.1f} s)"}
+    return one, allc
 
 
 def main():
@@ -282,6 +357,7 @@ def main():
                         f"obs uint8[1323]+fp32[22]",
             "envs": n, "obs_mode": "SYM_U8_F32", "actions": args.kind,
             "mean_episode_len": round(main_run["mean_episode_len"], 1),
+            "spin_up_steps": SPIN_UP_STEPS, "episode_length_window": LENGTH_WINDOW,
         },
         "roofline": {
             "bound": "hbm",
@@ -320,7 +396,7 @@ def main():
                                "rollout_value": full["also"]["rollout_value"],
                                "rollout_ms_per_step": full["also"]["rollout_ms_per_step"]}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(8192, min(K, 1000), args.kind)
+        out["cpu_baseline"], out["cpu_baseline_all_cores"] = cpu_baseline(args.kind)
     out["paper_context"] = PAPER_CONTEXT
     print(json.dumps(out))
 
@@ -331,7 +407,7 @@ def rollout_line(args) -> dict:
     kind = "skewed" if args.kind is None else args.kind
     K, W = args.steps, args.warmup
     wall = rollout_run(n, K, W, kind)
-    alg = algorithmic_bytes_per_env_step(180.0)["total"] - 256.0     # the record stays on chip between the steps of a launch
+    alg = algorithmic_bytes_per_env_step(180.0)["total"] - 256.0     # the record stays on chip between the steps of a launch (episodes last ~180 steps)
     achieved = alg * n / (wall / K) / 1e9
     return {
         "metric": "env steps/sec at 1 GPU (65536 envs, symbolic obs, K steps per launch) + % HBM roofline",
@@ -375,7 +451,7 @@ def craftax_pixels_line(args) -> dict:
             "avg_launch_us": run["draw_s"] * 1e6,
             "measured_copy_gbs": copy_ceiling_gbs(),
         },
-        **({} if args.no_cpu_baseline else {"cpu_baseline": cpu_baseline(64, 40, kind, variant="craftax", pixels=True)}),
+        **({} if args.no_cpu_baseline else {"cpu_baseline": cpu_baseline(kind, variant="craftax", pixels=True, n_sample=64, steps=40)[0]}),
     }
 
 
@@ -410,7 +486,7 @@ def craftax_line(args, with_cpu: bool = True) -> dict:
     out["also"] = {"workload": f"the same {n} environments and action stream through craftax_rollout, {K} steps per launch",
                    "rollout_value": n * K / roll, "rollout_ms_per_step": roll / K * 1e3, "unit": "env_steps/s"}
     if with_cpu and not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(1024, min(K, 1000), kind, variant="craftax")
+        out["cpu_baseline"], out["cpu_baseline_all_cores"] = cpu_baseline(kind, variant="craftax")
     return out
 
 

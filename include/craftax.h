@@ -15,8 +15,9 @@
  *    observe, export and import only enqueue work on it and return without synchronising.
  *  - Return value: 0 on success, negative on error (see CRAFTAX_E_*); the message is
  *    available from craftax_last_error() (thread local).  On error nothing is launched.
- *  - Nothing is allocated by any call except craftax_state_init, which makes one
- *    temporary host staging buffer.
+ *  - No call allocates device memory.  craftax_state_init makes one temporary host staging
+ *    buffer; craftax_state_init and craftax_state_attach synchronise with the stream they are
+ *    given.  No environment variable is read.
  */
 #ifndef CRAFTAX_H
 #define CRAFTAX_H
@@ -28,14 +29,15 @@
 extern "C" {
 #endif
 
-#define CRAFTAX_ABI_VERSION 1u
+#define CRAFTAX_ABI_VERSION 2u
 
 enum {
     CRAFTAX_OK = 0,
     CRAFTAX_E_NULL = -1,       /* a required pointer is NULL */
     CRAFTAX_E_ALIGN = -2,      /* state not 256-byte aligned or obs not 16-byte aligned */
     CRAFTAX_E_COUNT = -3,      /* n <= 0, n differs from the state's n, or a range is outside it */
-    CRAFTAX_E_STATE = -4,      /* state was not initialised by craftax_state_init in this process */
+    CRAFTAX_E_STATE = -4,      /* state is not registered in this process (craftax_state_init or craftax_state_attach),
+                                  or holds no worlds yet (no craftax_reset since craftax_state_init) */
     CRAFTAX_E_HIP = -5,        /* a HIP call failed */
     CRAFTAX_E_CONFIG = -6      /* unsupported configuration value */
 };
@@ -106,6 +108,10 @@ typedef struct craftax_config {
     uint64_t atlas_seed;         /* seed of the synthetic tile atlas (pixel observations) */
     uint32_t worldgen;           /* CRAFTAX_WORLDGEN_*: the noise behind the terrain rules */
     uint32_t reset_mode;         /* CRAFTAX_RESET_*: where the world of a new episode comes from */
+    uint32_t group_lanes;        /* Classic only, tuning: lanes of a wavefront that share one environment in the step
+                                    kernels; 0 = chosen from n (the default), else 4, 8 or 16.  Results do not depend on
+                                    it.  Variant CRAFTAX ignores it. */
+    uint32_t reserved;           /* must be 0 */
 } craftax_config;
 
 /* The noise of world generation.  VALUE: seeded integer value noise (the benchmark
@@ -194,20 +200,42 @@ void craftax_default_config(craftax_config *cfg);
  * "Further Environment Details"), day 300, caps melee 3 / passive 3 / ranged 2, 10 plants. */
 void craftax_default_config_for(craftax_config *cfg, uint32_t variant);
 
-/* Bytes of device memory the caller must provide for n environments (0 on a bad config). */
+/* Bytes of device memory the caller must provide for n environments (0 on a bad config).  The
+ * paper's interface (section "RL Environment Interface") exposes the whole environment state as
+ * one object; here that object is one caller-owned blob of this size for all n environments:
+ * header, tables, per-environment records and maps (two map slots each: appendix "Optimistic
+ * Environment Resets" is why the next world is kept ready), and the reset bookkeeping. */
 size_t craftax_state_bytes(const craftax_config *cfg, int n);
-/* Per-environment observation stride in bytes for cfg->obs_mode (multiple of 16). */
+/* Per-environment observation stride in bytes for cfg->obs_mode (multiple of 16): the symbolic
+ * and pixel observations of section "RL Environment Interface" / appendix "Observation Space" in
+ * the layouts listed above.  0 on a bad config. */
 size_t craftax_obs_bytes(const craftax_config *cfg);
 /* sizeof(craftax_env_dump). */
 size_t craftax_env_dump_bytes(void);
 /* Size of one canonical dump for cfg->variant: craftax_env_dump or craftax_full_env_dump. */
 size_t craftax_env_dump_bytes_for(const craftax_config *cfg);
 
-/* Writes the header, lookup tables and tile atlas into `state` (DEVICE, 256-byte aligned,
- * craftax_state_bytes() long) and registers it with the library.  Environments hold no
- * valid world until craftax_reset.  cfg is HOST. */
+/* Prepares the state object of section "RL Environment Interface" for n environments: writes the
+ * header, the lookup tables (day/night curve of appendix "Observation Space", scalings of its
+ * inventory table, Perlin gradients of appendix "World Generation") and the tile atlas into
+ * `state` (DEVICE, 256-byte aligned, craftax_state_bytes() long) and registers the address with
+ * the library.  Environments hold no world until craftax_reset: until then step, rollout, observe,
+ * export, import and the mutations return CRAFTAX_E_STATE.  cfg is HOST.  Errors: CRAFTAX_E_NULL,
+ * CRAFTAX_E_ALIGN, CRAFTAX_E_COUNT (n <= 0), CRAFTAX_E_CONFIG (bad field, or a kernel this
+ * configuration would launch needs more LDS or threads per block than the device allows),
+ * CRAFTAX_E_HIP. */
 int craftax_state_init(void *state, const craftax_config *cfg, int n, void *stream);
-/* Forgets a state registered by craftax_state_init (the memory stays the caller's). */
+/* Checkpoint / resume (the paper's state is one object that can be stored and restored, section
+ * "RL Environment Interface").  A state blob is position independent: a byte copy of it, taken
+ * while no call on it is in flight (device to device, or through the host or a file and back),
+ * continues bit for bit where the original stood once it is attached at its new address.  attach
+ * reads the blob's header (DEVICE to HOST, synchronising with `stream`), checks that it was
+ * written by this library version for exactly this cfg and n (CRAFTAX_E_STATE if it is no state
+ * blob, CRAFTAX_E_CONFIG / CRAFTAX_E_COUNT on a mismatch) and registers the address; nothing in
+ * the blob is changed.  The blob must come from a state that had been reset. */
+int craftax_state_attach(void *state, const craftax_config *cfg, int n, void *stream);
+/* Forgets a state registered by craftax_state_init or craftax_state_attach (the memory stays
+ * the caller's). */
 int craftax_state_release(void *state);
 
 /* Starts episode 0 of every environment: env i gets seeds[i] (DEVICE, n x uint64) as its
@@ -236,12 +264,26 @@ int craftax_step(void *state, const int32_t *actions, void *obs, float *reward, 
 int craftax_rollout(void *state, const int32_t *actions, int steps, void *obs, float *reward,
                     uint8_t *done, int n, void *stream);
 
-/* Renders the current observation of every environment (used after craftax_reset). */
+/* Renders the current observation of every environment, as the paper's reset returns it (section
+ * "RL Environment Interface": symbolic 1345 / 8268 values or 63x63x3 / 110x130x3 pixels, appendix
+ * "Observation Space") in the layout of cfg->obs_mode; obs: DEVICE, n x craftax_obs_bytes(),
+ * 16-byte aligned.  Used after craftax_reset, an import or a mutation; craftax_step writes the
+ * observation itself. */
 int craftax_observe(void *state, void *obs, int n, void *stream);
 
 /* Copies environments [first, first+count) to / from canonical dumps in DEVICE memory
- * (count x craftax_env_dump, or craftax_full_env_dump for variant CRAFTAX).  Import is the state-editing hook: the paper notes that the
- * whole environment state is one object that level editors can modify. */
+ * (count x craftax_env_dump, or craftax_full_env_dump for variant CRAFTAX; 16-byte aligned).
+ * Section "RL Environment Interface" exposes the whole environment state as one object so that
+ * levels can be inspected and edited (section "Craftax-1B: UED" relies on it); export is the
+ * readable form of that object, import the state-editing hook.
+ * Import packs the dump into the library's bit fields and accepts exactly the values the rules can
+ * reach; anything else is brought into range silently: block ids outside the variant's table
+ * (1..16 Classic, 1..36 Craftax) become 1 (out of bounds: solid, never rendered from a tile that
+ * does not exist), items above 4 become 0, light is capped at 20; Classic: coordinates are taken
+ * modulo 64, counts and vitals modulo 16, the four counters are clamped to -128..127, mob hp and
+ * cooldown modulo 16, direction modulo 8; Craftax: see craftax_full_env_dump (coordinates clamped
+ * to the 48x48 floor, levels to their maxima).  A dump that holds such values does not come back
+ * unchanged from export. */
 int craftax_export_envs(const void *state, int first, int count, void *dumps, void *stream);
 int craftax_import_envs(void *state, int first, int count, const void *dumps, void *stream);
 

@@ -21,7 +21,7 @@ VARIANT_CLASSIC, VARIANT_CRAFTAX = 0, 1
 EXPORTS = [
     "craftax_default_config", "craftax_default_config_for", "craftax_state_bytes", "craftax_obs_bytes",
     "craftax_env_dump_bytes", "craftax_env_dump_bytes_for",
-    "craftax_state_init", "craftax_state_release", "craftax_reset", "craftax_step", "craftax_observe",
+    "craftax_state_init", "craftax_state_attach", "craftax_state_release", "craftax_reset", "craftax_step", "craftax_observe",
     "craftax_rollout", "craftax_export_envs", "craftax_import_envs", "craftax_mutate_swap", "craftax_mutate_noise", "craftax_synth_actions", "craftax_last_error",
 ]
 
@@ -36,7 +36,8 @@ class Config(ctypes.Structure):
                 ("max_episode_steps", ctypes.c_uint32), ("day_length", ctypes.c_uint32),
                 ("cap_zombie", ctypes.c_uint32), ("cap_cow", ctypes.c_uint32), ("cap_skeleton", ctypes.c_uint32),
                 ("cap_arrow", ctypes.c_uint32), ("cap_plant", ctypes.c_uint32), ("atlas_seed", ctypes.c_uint64),
-                ("worldgen", ctypes.c_uint32), ("reset_mode", ctypes.c_uint32)]
+                ("worldgen", ctypes.c_uint32), ("reset_mode", ctypes.c_uint32),
+                ("group_lanes", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 # numpy views of the canonical dumps declared in include/craftax.h
@@ -95,6 +96,7 @@ def load() -> ctypes.CDLL:
     L.craftax_env_dump_bytes.argtypes = []
     L.craftax_env_dump_bytes.restype = ctypes.c_size_t
     L.craftax_state_init.argtypes = [vp, ctypes.POINTER(Config), i32, vp]
+    L.craftax_state_attach.argtypes = [vp, ctypes.POINTER(Config), i32, vp]
     L.craftax_state_release.argtypes = [vp]
     L.craftax_reset.argtypes = [vp, vp, i32, vp]
     L.craftax_step.argtypes = [vp, vp, vp, vp, vp, i32, vp]
@@ -146,6 +148,10 @@ def _stream_ptr(stream) -> int:
 
 def craftax_state_init(state, cfg: Config, n: int, stream=None):
     _check(load().craftax_state_init(state.data_ptr(), ctypes.byref(cfg), n, _stream_ptr(stream)), "craftax_state_init")
+
+
+def craftax_state_attach(state, cfg: Config, n: int, stream=None):
+    _check(load().craftax_state_attach(state.data_ptr(), ctypes.byref(cfg), n, _stream_ptr(stream)), "craftax_state_attach")
 
 
 def craftax_state_release(state):

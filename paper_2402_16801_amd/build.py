@@ -15,12 +15,38 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, only_changed: bool = False) -> str:
+    """Compiles every translation unit (in parallel) and links the library.  only_changed skips a
+    unit whose object is newer than every source and header (for quick iteration; the build check
+    always compiles everything)."""
+    from concurrent.futures import ThreadPoolExecutor
+
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", OUT] + SRCS
+    objdir = os.path.join(_PKG, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    csrc = os.path.join(_PKG, "csrc")
+    deps = [os.path.join(csrc, f) for f in os.listdir(csrc)] + [os.path.join(os.path.dirname(_PKG), "include", "craftax.h")]
+    newest = max(os.path.getmtime(d) for d in deps)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+
+    def compile_one(src):
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        if only_changed and os.path.exists(obj) and os.path.getmtime(obj) >= newest:
+            return obj
+        cmd = [hipcc] + flags + ["-c", "-o", obj, src]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + res.stderr)
+        if verbose:
+            print(" ".join(cmd))
+        return obj
+
+    with ThreadPoolExecutor(max_workers=len(SRCS)) as ex:
+        objs = list(ex.map(compile_one, SRCS))
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT] + objs
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stderr)
+        raise RuntimeError("hipcc link failed:\n" + res.stderr)
     if verbose:
         print(" ".join(cmd))
     return OUT

@@ -144,6 +144,7 @@ struct Header {
     uint32_t cap_zombie, cap_cow, cap_skeleton, cap_arrow, cap_plant;
     uint64_t atlas_seed;
     uint64_t off_ctrs, off_luts, off_recs, off_maps, off_tags, off_regen0, off_regen1, off_slow, total;
+    uint32_t variant, worldgen, reset_mode, pad;
 };
 constexpr uint64_t HEADER_BYTES = 256;   // the header sits alone in the first 256 bytes of the state blob
 static_assert(sizeof(Header) <= HEADER_BYTES, "header outgrew its area");

@@ -1,5 +1,6 @@
 // Kernels and host entry points of the full-Craftax variant (nine floors, 43 actions).
 #include "full_api.hpp"
+#include "launch_limits.hpp"
 
 #include <hip/hip_runtime.h>
 
@@ -595,9 +596,10 @@ __global__ __launch_bounds__(BLOCK) void kf_export(const uint32_t* __restrict__ 
     }
 }
 
-// Import packs into the record's bit fields: counts 0..255, counters -128..127, mob hp 0..31,
-// cooldown 0..15, experience 0..15, coordinates 0..47, floor 0..8 (every state the rules can
-// reach is); values outside are clamped so that no kernel ever indexes beyond its buffers.
+// Import packs into the record's bit fields: counts 0..99, vitals 0..31, counters -128..127, mob
+// hp 0..31, cooldown 0..15, creature type 0..18, experience 0..15, coordinates 0..47, floor 0..8,
+// block ids 1..36, items 0..4, light 0..20 (every state the rules can reach is); values outside
+// are brought into range so that no kernel ever indexes beyond its tables or buffers.
 __global__ __launch_bounds__(BLOCK) void kf_import(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, Lists ls,
                                                   const craftax_full_env_dump* __restrict__ dumps, int first, Params p)
 {
@@ -608,8 +610,9 @@ __global__ __launch_bounds__(BLOCK) void kf_import(uint32_t* __restrict__ envs, 
     uint32_t* r = envs + (size_t)env * ENV_DWORDS;
     for (int i = tid; i < FLOORS * CELLS; i += BLOCK) {
         const int f = i / CELLS, c = i - f * CELLS;
-        em[(size_t)f * 2 * CELLS + c] = d->block[f][c];
-        em[(size_t)f * 2 * CELLS + CELLS + c] = (uint8_t)((d->item[f][c] & 7u) | ((uint32_t)min((int)d->light[f][c], 31) << 3));
+        const uint32_t b = d->block[f][c], it = d->item[f][c];
+        em[(size_t)f * 2 * CELLS + c] = (uint8_t)(b - 1u < (uint32_t)(B_COUNT - 1) ? b : (uint32_t)B_OOB);
+        em[(size_t)f * 2 * CELLS + CELLS + c] = (uint8_t)((it <= 4u ? it : 0u) | ((uint32_t)min((int)d->light[f][c], 20) << 3));
     }
     __shared__ uint32_t s[ENV_DWORDS];
     s[tid] = 0u;
@@ -624,15 +627,15 @@ __global__ __launch_bounds__(BLOCK) void kf_import(uint32_t* __restrict__ envs, 
         uint32_t at = ((uint32_t)(d->xp & 15) << 16) | ((uint32_t)(d->dex & 7) << 20) | ((uint32_t)(d->str & 7) << 23) | ((uint32_t)(d->intel & 7) << 26);
         for (int i = 0; i < 4; ++i) at |= ((uint32_t)(d->armour[i] & 3) << (2 * i)) | ((uint32_t)(d->armour_ench[i] & 3) << (8 + 2 * i));
         s[R_ATTR] = at;
-        for (int i = 0; i < 10; ++i) s[R_INV + (i >> 2)] |= (uint32_t)d->inv[i] << (8 * (i & 3));
-        for (int i = 0; i < 6; ++i) { const int b = 10 + i; s[R_INV + (b >> 2)] |= (uint32_t)d->potion[i] << (8 * (b & 3)); }
+        for (int i = 0; i < 10; ++i) s[R_INV + (i >> 2)] |= (uint32_t)min((int)d->inv[i], 99) << (8 * (i & 3));
+        for (int i = 0; i < 6; ++i) { const int b = 10 + i; s[R_INV + (b >> 2)] |= (uint32_t)min((int)d->potion[i], 99) << (8 * (b & 3)); }
         uint32_t wv = 0, wc = 0;
         for (int i = 0; i < 4; ++i) {
-            wv |= (uint32_t)(uint8_t)max(0, (int)d->vit[i]) << (8 * i);
+            wv |= (uint32_t)max(0, min(31, (int)d->vit[i])) << (8 * i);
             wc |= (uint32_t)(max(-128, min(127, (int)d->cnt[i])) & 0xFF) << (8 * i);
         }
         s[R_VIT] = wv; s[R_CNT] = wc;
-        s[R_MANA] = (uint32_t)(uint8_t)max(0, (int)d->vit[4]) | ((uint32_t)(max(-128, min(127, (int)d->cnt[4])) & 0xFF) << 8) |
+        s[R_MANA] = (uint32_t)max(0, min(31, (int)d->vit[4])) | ((uint32_t)(max(-128, min(127, (int)d->cnt[4])) & 0xFF) << 8) |
                     ((d->t % p.day_length) << 16);
         uint32_t pm = (uint32_t)(d->visited & 0x1FF) << 18;
         for (int i = 0; i < 6; ++i) pm |= (uint32_t)(d->potion_effect[i] & 7) << (3 * i);
@@ -651,7 +654,7 @@ __global__ __launch_bounds__(BLOCK) void kf_import(uint32_t* __restrict__ envs, 
         const craftax_full_mob u = d->mob[f][k];
         Mob m;
         m.alive = u.alive & 1; m.x = min((int)u.x, W - 1); m.y = min((int)u.y, W - 1); m.dir = u.dir & 7; m.hp = max(0, min(31, (int)u.hp)); m.cd = min(15, (int)u.cd);
-        m.type = u.type & 31;
+        m.type = min((int)u.type, 18);
         s[REC_DWORDS + f * MOBTAB_DWORDS + k] = pack_mob(m);
     }
     if (tid >= 128 && tid < 128 + NPLANT) {
@@ -725,6 +728,7 @@ bool config_ok(const craftax_config* c, std::string* why)
     if (c->max_episode_steps == 0) { *why = "max_episode_steps must be positive"; return false; }
     if (c->reset_mode > CRAFTAX_RESET_POOL) { *why = "unknown reset_mode"; return false; }
     if (c->worldgen > CRAFTAX_WORLDGEN_PERLIN) { *why = "unknown worldgen"; return false; }
+    if (c->reserved != 0) { *why = "reserved must be 0"; return false; }
     return true;
 }
 
@@ -735,6 +739,7 @@ static Header make_header(const craftax_config* c, int n)
     h.magic = MAGIC; h.version = CRAFTAX_ABI_VERSION; h.n = (uint32_t)n; h.variant = c->variant;
     h.obs_mode = c->obs_mode; h.max_episode_steps = c->max_episode_steps; h.day_length = c->day_length;
     h.cap_melee = c->cap_zombie; h.cap_ranged = c->cap_skeleton; h.cap_passive = c->cap_cow; h.cap_plant = c->cap_plant;
+    h.atlas_seed = c->atlas_seed; h.worldgen = c->worldgen; h.reset_mode = c->reset_mode;
     h.off_ctrs = cx::HEADER_BYTES;
     h.off_luts = h.off_ctrs + la::COUNTER_BYTES;
     h.off_envs = round_up(h.off_luts + sizeof(Luts), 256);
@@ -848,6 +853,48 @@ int state_init(void* state, const craftax_config* cfg, int n, void* stream, std:
     return CRAFTAX_OK;
 }
 
+int check_header(const void* header_bytes, const craftax_config* cfg, int n, std::string* err)
+{
+    Header got;
+    std::memcpy(&got, header_bytes, sizeof(got));
+    if (got.magic != MAGIC) { *err = "the memory holds no Craftax state blob"; return CRAFTAX_E_STATE; }
+    if (got.version != CRAFTAX_ABI_VERSION) { *err = "the state blob was written by another library version"; return CRAFTAX_E_STATE; }
+    if (got.n != (uint32_t)n) { *err = "the state blob holds another number of environments"; return CRAFTAX_E_COUNT; }
+    const Header want = make_header(cfg, n);
+    if (std::memcmp(&got, &want, sizeof(Header)) != 0) { *err = "the state blob was initialised with another configuration"; return CRAFTAX_E_CONFIG; }
+    return CRAFTAX_OK;
+}
+
+int check_kernels(const craftax_config* cfg, std::string* err)
+{
+    int dev = 0, lds = 0, threads = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&threads, hipDeviceAttributeMaxThreadsPerBlock, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        *err = "no usable HIP device";
+        return CRAFTAX_E_HIP;
+    }
+    const cx::DeviceLimits limits{(size_t)lds, threads};
+    auto fits = [&](const char* name, const void* fn, int block) {
+        hipFuncAttributes a;
+        if (hipFuncGetAttributes(&a, fn) != hipSuccess) { (void)hipGetLastError(); *err = std::string("no attributes for ") + name; return false; }
+        return cx::kernel_fits(cx::KernelNeeds{name, a.sharedSizeBytes, a.maxThreadsPerBlock, block}, limits, err);
+    };
+    const bool perlin = cfg->worldgen == CRAFTAX_WORLDGEN_PERLIN;
+    bool ok = true;
+    if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) {
+        ok = ok && (perlin ? fits("kf_step", (const void*)kf_step<true, true, true>, BLOCK) : fits("kf_step", (const void*)kf_step<true, true, false>, BLOCK));
+        ok = ok && (perlin ? fits("kf_rollout", (const void*)kf_rollout<true, true>, BLOCK) : fits("kf_rollout", (const void*)kf_rollout<true, false>, BLOCK));
+        ok = ok && fits("kf_reset_list", (const void*)kf_reset_list<true>, GEN_THREADS) && fits("kf_observe", (const void*)kf_observe<true>, BLOCK);
+    } else {
+        ok = ok && (perlin ? fits("kf_step", (const void*)kf_step<false, true, true>, BLOCK) : fits("kf_step", (const void*)kf_step<false, true, false>, BLOCK));
+        ok = ok && (perlin ? fits("kf_rollout", (const void*)kf_rollout<false, true>, BLOCK) : fits("kf_rollout", (const void*)kf_rollout<false, false>, BLOCK));
+        ok = ok && fits("kf_reset_list", (const void*)kf_reset_list<false>, GEN_THREADS) && fits("kf_observe", (const void*)kf_observe<false>, BLOCK);
+    }
+    ok = ok && fits("kf_reset", (const void*)kf_reset, GEN_THREADS) && fits("kf_pixels", (const void*)kf_pixels, BLOCK);
+    return ok ? CRAFTAX_OK : CRAFTAX_E_CONFIG;
+}
+
 int reset(void* state, const craftax_config* cfg, int n, const uint64_t* seeds, void* stream, std::string* err)
 {
     const Ptrs q = pointers(state, make_header(cfg, n));
@@ -866,7 +913,7 @@ static void launch_step(bool eager, bool perlin, dim3 grid, hipStream_t st, cons
 }
 
 int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, void* obs, float* reward, uint8_t* done,
-         void* stream, std::string* err)
+         bool serve_slow, void* stream, std::string* err)
 {
     const Ptrs q = pointers(state, make_header(cfg, n));
     const Params p = make_params(cfg, n);
@@ -877,9 +924,11 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
     const dim3 grid((unsigned)(rb + sb)), rgrid((unsigned)(n < RESET_SLOTS ? n : RESET_SLOTS) * FLOORS);
     const int pool = cfg->reset_mode == CRAFTAX_RESET_POOL ? 1 : 0;
     // kf_reset_list serves the episodes that end before their spare world exists: with exact resets
-    // only one-step episodes can; with optimistic resets there are no spare worlds and every
-    // finished episode is served there, its world depending on who else finished
-    const bool slow = p.max_episode_steps == 1u || pool != 0;
+    // only one-step episodes can, or a fresh episode whose world was edited before its first step
+    // (serve_slow: the caller mutated or imported since the last step); with optimistic resets there
+    // are no spare worlds and every finished episode is served there, its world depending on who
+    // else finished
+    const bool slow = p.max_episode_steps == 1u || pool != 0 || serve_slow;
     const bool eager = n <= EAGER_SPARE_ENVS && pool == 0;
     const int perlin = cfg->worldgen == CRAFTAX_WORLDGEN_PERLIN ? 1 : 0;
     if (cfg->obs_mode == CRAFTAX_OBS_PIXELS_F32) {

@@ -17,8 +17,13 @@ size_t state_bytes(const craftax_config* cfg, int n);
 size_t obs_bytes(const craftax_config* cfg);
 int state_init(void* state, const craftax_config* cfg, int n, void* stream, std::string* err);
 int reset(void* state, const craftax_config* cfg, int n, const uint64_t* seeds, void* stream, std::string* err);
+// serve_slow: also launch the kernel that serves episodes which ended before their spare world existed
 int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, void* obs, float* reward, uint8_t* done,
-         void* stream, std::string* err);
+         bool serve_slow, void* stream, std::string* err);
+// checks a header read back from a blob against cfg and n: 0, or a CRAFTAX_E_* code and a message
+int check_header(const void* header_bytes, const craftax_config* cfg, int n, std::string* err);
+// LDS and thread needs of the kernels this configuration launches against the device's limits
+int check_kernels(const craftax_config* cfg, std::string* err);
 int rollout(void* state, const craftax_config* cfg, int n, const int32_t* actions, int steps, void* obs, float* reward, uint8_t* done,
             void* stream, std::string* err);
 int observe(void* state, const craftax_config* cfg, int n, void* obs, void* stream, std::string* err);

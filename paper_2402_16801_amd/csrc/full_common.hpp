@@ -190,6 +190,8 @@ struct Header {
     uint32_t variant, obs_mode, max_episode_steps, day_length;
     uint32_t cap_melee, cap_ranged, cap_passive, cap_plant;
     uint64_t off_ctrs, off_luts, off_envs, off_maps, off_tags, off_regen0, off_regen1, off_slow, total;
+    uint64_t atlas_seed;
+    uint32_t worldgen, reset_mode;
 };
 static_assert(sizeof(Header) <= cx::HEADER_BYTES, "header outgrew its area");
 constexpr uint64_t MAGIC = 0x46554C4C43524158ull;

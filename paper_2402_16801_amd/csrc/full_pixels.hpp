@@ -61,9 +61,9 @@ __global__ __launch_bounds__(BLOCK) void kf_pixels(const uint32_t* __restrict__ 
             int block = B_OOB, item = IT_NONE, lv = MAX_LIGHT;
             uint32_t cre = NO_TILE;
             if (inb(x, y)) {
-                block = m[block_off(f, x, y)] & 63;
+                block = min((int)m[block_off(f, x, y)], (int)B_COUNT - 1);     // ids beyond the table would index past the atlas
                 const int il = m[il_off(f, x, y)];
-                item = il & 7; lv = il >> 3;
+                item = min(il & 7, (int)IT_COUNT - 1); lv = il >> 3;
                 const uint32_t cr = s_cre[tid];
                 if (cr != 0xFFFFFFFFu) cre = AT_CRE + (cr & 0xFFu);
             }

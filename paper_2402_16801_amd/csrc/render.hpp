@@ -207,7 +207,9 @@ __device__ __forceinline__ void render_pixels_block(const uint32_t* __restrict__
     if (tid < PIX_VIEW * PIX_VIEW) {
         const int tr = tid / PIX_VIEW, tc = tid - tr * PIX_VIEW;
         const int x = px + tc - PIX_VIEW / 2, y = py + tr - PIX_VIEW / 2;
-        s_tile[tid] = in_map(x, y) ? (int)map[map_index(x, y)] : (int)BK_OOB;
+        // ids outside 1..16 would index before or past the atlas: they are drawn as the out-of-bounds tile
+        const int b = in_map(x, y) ? (int)map[map_index(x, y)] : (int)BK_OOB;
+        s_tile[tid] = (unsigned)(b - 1) < 16u ? b : (int)BK_OOB;
         s_ent[tid] = (tid == PIX_VIEW * PIX_VIEW / 2) ? 0 : -1;
     }
     __syncthreads();

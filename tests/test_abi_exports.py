@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_sizes_and_defaults(lib):
     cfg = binding.default_config()
-    assert (cfg.abi_version, cfg.variant, cfg.obs_mode) == (1, 0, 1)
+    assert (cfg.abi_version, cfg.variant, cfg.obs_mode) == (2, 0, 1)
     assert (cfg.max_episode_steps, cfg.day_length) == (10000, 300)
     assert (cfg.cap_zombie, cfg.cap_cow, cfg.cap_skeleton, cfg.cap_arrow, cfg.cap_plant) == (3, 3, 3, 3, 10)
     assert binding.craftax_env_dump_bytes() == 4304
@@ -50,7 +50,7 @@ def test_sizes_and_defaults(lib):
 
 def test_full_variant_sizes_and_defaults(lib):
     cfg = binding.default_config(binding.VARIANT_CRAFTAX)
-    assert (cfg.abi_version, cfg.variant, cfg.obs_mode) == (1, 1, 1)
+    assert (cfg.abi_version, cfg.variant, cfg.obs_mode) == (2, 1, 1)
     assert (cfg.max_episode_steps, cfg.day_length) == (100000, 300)
     assert (cfg.cap_zombie, cfg.cap_cow, cfg.cap_skeleton, cfg.cap_plant) == (3, 3, 2, 10)
     assert binding.craftax_env_dump_bytes_for(cfg) == 63432

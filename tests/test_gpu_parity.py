@@ -29,15 +29,8 @@ def _cfgs(cx, obs_mode, **kw):
 
 def _make_sim(cx, n, gcfg, lanes=None):
     """lanes: lanes per environment of the step kernel (4, 8, 16) or None for the default."""
-    import os
-    if lanes is None:
-        os.environ.pop("CRAFTAX_GROUP_LANES", None)
-    else:
-        os.environ["CRAFTAX_GROUP_LANES"] = str(lanes)
-    try:
-        return cx.Craftax(n, gcfg)
-    finally:
-        os.environ.pop("CRAFTAX_GROUP_LANES", None)
+    gcfg.group_lanes = 0 if lanes is None else lanes
+    return cx.Craftax(n, gcfg)
 
 
 def run_parity(cx, n, T, obs_mode, kind, sample=None, action_seed=0, state_every=0, obs_every=1,

@@ -60,7 +60,8 @@ def test_new_entry_points_refuse_bad_calls_on_the_host(lib):
 
 @pytest.mark.parametrize("field,value", [("reset_mode", 2), ("worldgen", 2), ("day_length", 301), ("day_length", 0), ("day_length", 2048),
                                          ("cap_zombie", 4), ("cap_plant", 11), ("max_episode_steps", 0), ("obs_mode", 4),
-                                         ("abi_version", 7), ("variant", 2)])
+                                         ("abi_version", 7), ("abi_version", 1), ("variant", 2), ("group_lanes", 2), ("group_lanes", 32),
+                                         ("reserved", 1)])
 def test_bad_configurations_get_no_state(lib, field, value):
     cfg = binding.default_config(**{field: value})
     assert binding.craftax_state_bytes(cfg, 64) == 0

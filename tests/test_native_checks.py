@@ -1,0 +1,33 @@
+"""Host-only native checks (no GPU): the oracle's C code under AddressSanitizer and
+UndefinedBehaviorSanitizer, and the unit test of the launch-limit rule the library applies before
+it accepts a state."""
+import os
+import subprocess
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+NATIVE = os.path.join(ROOT, "tests", "native")
+
+
+def _run(cmd, env=None, timeout=600):
+    res = subprocess.run(cmd, capture_output=True, text=True, timeout=timeout, env=env)
+    assert res.returncode == 0, f"{' '.join(cmd)}\n{res.stdout[-3000:]}\n{res.stderr[-3000:]}"
+    return res.stdout + res.stderr
+
+
+def test_oracle_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    exe = str(tmp_path / "oracle_sanitizer_run")
+    srcs = [os.path.join(ROOT, "oracle", f) for f in ("philox.c", "classic.c", "craftax_full.c")]
+    _run(["gcc", "-O1", "-g", "-std=c11", "-ffp-contract=off", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+          "-static-libasan", "-o", exe, os.path.join(NATIVE, "oracle_sanitizer_run.c")] + srcs + ["-lm"])
+    env = dict(os.environ)
+    env.pop("LD_PRELOAD", None)                     # the sanitizer runtime has to come first in the process
+    env["ASAN_OPTIONS"] = "detect_leaks=0:abort_on_error=0"
+    env["UBSAN_OPTIONS"] = "print_stacktrace=1"
+    out = _run([exe], env=env)
+    assert "oracle_sanitizer_run: ok" in out and "runtime error" not in out and "AddressSanitizer" not in out, out[-3000:]
+
+
+def test_launch_limit_rule(tmp_path):
+    exe = str(tmp_path / "launch_limits_test")
+    _run(["g++", "-O1", "-std=c++17", "-Wall", "-Wextra", "-o", exe, os.path.join(NATIVE, "launch_limits_test.cpp")])
+    assert "launch_limits_test: ok" in _run([exe])
