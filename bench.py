@@ -87,13 +87,8 @@ LENGTH_WINDOW = 1000       # the last steps of the spin-up, over which the mean 
 
 
 def episode_sum(sim) -> int:
-    """Sum of the episode counters of all environments (episodes finished since the reset)."""
-    total = 0
-    chunk = 512 if sim.cfg.variant == 1 else 8192
-    for first in range(0, sim.n, chunk):
-        d = sim.export_envs(first, min(chunk, sim.n - first))
-        total += int(d.view(sim.dump_dtype)["episode"].sum())
-    return total
+    """Episodes finished since the reset, summed over all environments (craftax_stats)."""
+    return int(sim.stats()["episodes"])
 
 
 def advance(cx, sim, kind_id: int, first_step: int, steps: int, use_rollout: bool) -> int:

@@ -333,6 +333,30 @@ int craftax_mutate_noise(void *state, int first, int count, uint16_t *theta, uin
 int craftax_synth_actions(int32_t *actions, int n, int step0, int steps, uint64_t action_seed,
                           int kind, void *stream);
 
+/* Per-run metrics (the paper reports achievement success rates and reward as a share of the
+ * maximum, section "Craftax-1B"; its appendix "Optimistic Environment Resets" argues from the mean
+ * episode length): a snapshot over the n environments as they stand.
+ *   episodes        episodes finished since craftax_reset, summed over the environments
+ *   steps           steps taken so far in the current episodes (sum of t)
+ *   achievements[i] environments whose current episode has unlocked achievement i (appendix
+ *                   "Achievements": 22 ids for Classic, 67 for Craftax; the rest stay 0)
+ * Mean episode length over a window = n * window / (episodes after - episodes before).
+ * out: DEVICE, one craftax_metrics, 8-byte aligned.  workspace: DEVICE scratch of at least
+ * craftax_stats_workspace_bytes(n) bytes, 16-byte aligned, contents irrelevant before and after
+ * (each 256 environments leave one partial result there, a second kernel adds them up, so the
+ * result does not depend on any order of execution).  Errors: CRAFTAX_E_NULL, CRAFTAX_E_ALIGN,
+ * CRAFTAX_E_COUNT (n differs from the state's, or the workspace is too small), CRAFTAX_E_STATE. */
+#define CRAFTAX_STATS_ACHIEVEMENTS 96
+typedef struct craftax_metrics {
+    uint64_t episodes;
+    uint64_t steps;
+    uint32_t achievements[CRAFTAX_STATS_ACHIEVEMENTS];
+    uint32_t n;
+    uint32_t pad;
+} craftax_metrics;
+size_t craftax_stats_workspace_bytes(int n);
+int craftax_stats(const void *state, craftax_metrics *out, void *workspace, size_t workspace_bytes, int n, void *stream);
+
 const char *craftax_last_error(void);
 
 #ifdef __cplusplus

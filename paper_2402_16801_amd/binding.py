@@ -23,6 +23,7 @@ EXPORTS = [
     "craftax_env_dump_bytes", "craftax_env_dump_bytes_for",
     "craftax_state_init", "craftax_state_attach", "craftax_state_release", "craftax_reset", "craftax_step", "craftax_observe",
     "craftax_rollout", "craftax_export_envs", "craftax_import_envs", "craftax_mutate_swap", "craftax_mutate_noise", "craftax_synth_actions", "craftax_last_error",
+    "craftax_stats_workspace_bytes", "craftax_stats",
 ]
 
 
@@ -61,6 +62,11 @@ FULL_ENV_DUMP_DTYPE = np.dtype([
     ("ach", "<u4", (3,)), ("t", "<u4"), ("episode", "<u4"), ("env", "<u4"), ("pad0", "<u4"), ("seed", "<u8"),
     ("mob", _FULL_MOB, (9, 14)), ("plant", _PLANT, (10,)), ("pad1", "u1", (4,))])
 assert ENV_DUMP_DTYPE.itemsize == 4304 and FULL_ENV_DUMP_DTYPE.itemsize == 63432
+
+
+STATS_ACHIEVEMENTS = 96
+STATS_DTYPE = np.dtype([("episodes", "<u8"), ("steps", "<u8"), ("achievements", "<u4", (STATS_ACHIEVEMENTS,)), ("n", "<u4"), ("pad", "<u4")])
+assert STATS_DTYPE.itemsize == 408
 
 
 class CraftaxError(RuntimeError):
@@ -107,6 +113,9 @@ def load() -> ctypes.CDLL:
     L.craftax_mutate_swap.argtypes = [vp, i32, i32, u64, ctypes.c_uint32, i32, vp, vp]
     L.craftax_mutate_noise.argtypes = [vp, i32, i32, vp, u64, ctypes.c_uint32, ctypes.c_uint32, vp]
     L.craftax_synth_actions.argtypes = [vp, i32, i32, i32, u64, i32, vp]
+    L.craftax_stats_workspace_bytes.argtypes = [i32]
+    L.craftax_stats_workspace_bytes.restype = ctypes.c_size_t
+    L.craftax_stats.argtypes = [vp, vp, vp, ctypes.c_size_t, i32, vp]
     L.craftax_last_error.argtypes = []
     L.craftax_last_error.restype = ctypes.c_char_p
     _lib = L
@@ -196,6 +205,15 @@ def craftax_mutate_noise(state, first: int, count: int, theta, mutation_seed: in
                                        round_, amplitude, _stream_ptr(stream)), "craftax_mutate_noise")
 
 
+def craftax_stats_workspace_bytes(n: int) -> int:
+    return int(load().craftax_stats_workspace_bytes(n))
+
+
+def craftax_stats(state, out, workspace, n: int, stream=None):
+    _check(load().craftax_stats(state.data_ptr(), out.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                n, _stream_ptr(stream)), "craftax_stats")
+
+
 def craftax_synth_actions(actions, n: int, step0: int, steps: int, action_seed: int, kind: int, stream=None):
     _check(load().craftax_synth_actions(actions.data_ptr(), n, step0, steps, action_seed, kind, _stream_ptr(stream)),
            "craftax_synth_actions")
@@ -265,6 +283,14 @@ class Craftax:
         buf = torch.as_tensor(raw, device=self.device)
         craftax_import_envs(self.state, first, raw.shape[0], buf, self.stream)
         self.torch.cuda.synchronize(self.device)
+
+    def stats(self) -> np.ndarray:
+        """Metrics snapshot (craftax_stats) as a numpy record of STATS_DTYPE."""
+        torch = self.torch
+        out = torch.zeros(STATS_DTYPE.itemsize, dtype=torch.uint8, device=self.device)
+        work = torch.empty(craftax_stats_workspace_bytes(self.n), dtype=torch.uint8, device=self.device)
+        craftax_stats(self.state, out, work, self.n, self.stream)
+        return out.cpu().numpy().view(STATS_DTYPE)[0]
 
     def mutate_swap(self, mutation_seed: int, round_: int, restricted: bool, first: int = 0, count: int | None = None) -> np.ndarray:
         """Swap mutation of the current maps; returns the accepted try + 1 (0: none) per environment."""

@@ -865,6 +865,12 @@ int check_header(const void* header_bytes, const craftax_config* cfg, int n, std
     return CRAFTAX_OK;
 }
 
+RecordLayout record_layout(const void* state, const craftax_config* cfg, int n)
+{
+    const Ptrs q = pointers(state, make_header(cfg, n));
+    return RecordLayout{q.envs, ENV_DWORDS, R_ACH, 3, R_T, R_EPISODE};
+}
+
 int check_kernels(const craftax_config* cfg, std::string* err)
 {
     int dev = 0, lds = 0, threads = 0;

@@ -22,6 +22,9 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
          bool serve_slow, void* stream, std::string* err);
 // checks a header read back from a blob against cfg and n: 0, or a CRAFTAX_E_* code and a message
 int check_header(const void* header_bytes, const craftax_config* cfg, int n, std::string* err);
+// where the metrics kernel finds achievements, t and episode: records as dwords
+struct RecordLayout { const uint32_t* recs; int stride, ach, ach_words, t, episode; };
+RecordLayout record_layout(const void* state, const craftax_config* cfg, int n);
 // LDS and thread needs of the kernels this configuration launches against the device's limits
 int check_kernels(const craftax_config* cfg, std::string* err);
 int rollout(void* state, const craftax_config* cfg, int n, const int32_t* actions, int steps, void* obs, float* reward, uint8_t* done,

@@ -266,3 +266,33 @@ def test_death_on_the_first_step_after_an_auto_reset_and_a_swap(cx, variant, n, 
         _step_both(sim, orc, synth.actions(np.arange(n), s, "uniform", 3, n_actions), f"step {s}")
     assert sim.export_envs().tobytes() == orc.envs.tobytes()
     sim.close()
+
+
+def _oracle_stats(orc, n_ach):
+    e = orc.envs
+    ach = e["ach"].reshape(len(e), -1).astype(np.uint64)
+    bits = np.zeros(96, np.int64)
+    for i in range(n_ach):
+        bits[i] = int(((ach[:, i // 32] >> np.uint64(i % 32)) & np.uint64(1)).sum())
+    return int(e["episode"].astype(np.int64).sum()), int(e["t"].astype(np.int64).sum()), bits
+
+
+@pytest.mark.parametrize("variant,n", [("classic", 1000), ("classic", 257), ("craftax", 300)])
+def test_metrics_snapshot_matches_the_oracle(cx, variant, n):
+    """craftax_stats (episodes finished, steps into the current episodes, achievement counts)
+    against the same sums over the oracle's environments, at several points of a run."""
+    sim, orc, n_actions = _pair(cx, variant, n, max_episode_steps=60)
+    seeds = synth.seeds_for(n, 21)
+    sim.reset(seeds); orc.reset(seeds)
+    n_ach = 22 if variant == "classic" else 67
+    seen = np.zeros(96, np.int64)
+    for s in range(150):
+        _step_both(sim, orc, synth.actions(np.arange(n), s, "skewed", 2, n_actions), f"step {s}")
+        if s % 30 == 29 or s < 2:
+            got = sim.stats()
+            episodes, steps, bits = _oracle_stats(orc, n_ach)
+            assert (int(got["episodes"]), int(got["steps"]), int(got["n"])) == (episodes, steps, n)
+            assert np.array_equal(got["achievements"].astype(np.int64), bits)
+            seen = np.maximum(seen, bits)
+    assert int(got["episodes"]) >= 2 * n and (seen > 0).sum() >= 3, "the run was to finish episodes and unlock achievements"
+    sim.close()
