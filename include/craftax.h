@@ -357,6 +357,17 @@ typedef struct craftax_metrics {
 size_t craftax_stats_workspace_bytes(int n);
 int craftax_stats(const void *state, craftax_metrics *out, void *workspace, size_t workspace_bytes, int n, void *stream);
 
+/* craftax_stats for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The partial
+ * results go to a buffer inside the library's own device image (1 MiB per GPU, held until the
+ * process ends) instead of a workspace; nothing is allocated, by this call or behind it.  Same
+ * result as craftax_stats.  Limits: n <= CRAFTAX_STATS_STATIC_MAX_ENVS (CRAFTAX_E_COUNT beyond).
+ * All calls on one GPU share that buffer: calls that overlap in time on one GPU (different
+ * streams, different states) race and give wrong sums; calls on one stream, or ordered by events,
+ * are safe.  The GPU that is current at the call must be the one that holds `state`. */
+#define CRAFTAX_STATS_STATIC_MAX_ENVS 524288
+int craftax_stats_static(const void *state, craftax_metrics *out, int n, void *stream);
+
 const char *craftax_last_error(void);
 
 #ifdef __cplusplus

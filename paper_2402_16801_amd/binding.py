@@ -23,7 +23,7 @@ EXPORTS = [
     "craftax_env_dump_bytes", "craftax_env_dump_bytes_for",
     "craftax_state_init", "craftax_state_attach", "craftax_state_release", "craftax_reset", "craftax_step", "craftax_observe",
     "craftax_rollout", "craftax_export_envs", "craftax_import_envs", "craftax_mutate_swap", "craftax_mutate_noise", "craftax_synth_actions", "craftax_last_error",
-    "craftax_stats_workspace_bytes", "craftax_stats",
+    "craftax_stats_workspace_bytes", "craftax_stats", "craftax_stats_static",
 ]
 
 
@@ -116,6 +116,7 @@ def load() -> ctypes.CDLL:
     L.craftax_stats_workspace_bytes.argtypes = [i32]
     L.craftax_stats_workspace_bytes.restype = ctypes.c_size_t
     L.craftax_stats.argtypes = [vp, vp, vp, ctypes.c_size_t, i32, vp]
+    L.craftax_stats_static.argtypes = [vp, vp, i32, vp]
     L.craftax_last_error.argtypes = []
     L.craftax_last_error.restype = ctypes.c_char_p
     _lib = L
@@ -212,6 +213,13 @@ def craftax_stats_workspace_bytes(n: int) -> int:
 def craftax_stats(state, out, workspace, n: int, stream=None):
     _check(load().craftax_stats(state.data_ptr(), out.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                 n, _stream_ptr(stream)), "craftax_stats")
+
+
+def craftax_stats_static(state, out, n: int, stream=None):
+    _check(load().craftax_stats_static(state.data_ptr(), out.data_ptr(), n, _stream_ptr(stream)), "craftax_stats_static")
+
+
+STATS_STATIC_MAX_ENVS = 524288
 
 
 def craftax_synth_actions(actions, n: int, step0: int, steps: int, action_seed: int, kind: int, stream=None):

@@ -97,6 +97,7 @@ def test_header_constants_match_their_python_mirrors():
     assert enums["CRAFTAX_RESET_POOL"] == binding.RESET_POOL == po.RESET_POOL
     assert enums["CRAFTAX_VARIANT_CLASSIC"] == binding.VARIANT_CLASSIC and enums["CRAFTAX_VARIANT_CRAFTAX"] == binding.VARIANT_CRAFTAX
     assert defines["CRAFTAX_STATS_ACHIEVEMENTS"] == binding.STATS_ACHIEVEMENTS >= 67
+    assert defines["CRAFTAX_STATS_STATIC_MAX_ENVS"] == binding.STATS_STATIC_MAX_ENVS and binding.STATS_STATIC_MAX_ENVS % 256 == 0
     assert binding.STATS_DTYPE.itemsize == 8 + 8 + 4 * 96 + 8
     assert binding.craftax_stats_workspace_bytes(1) == 512 and binding.craftax_stats_workspace_bytes(257) == 1024
     assert binding.craftax_stats_workspace_bytes(0) == 0
