@@ -93,14 +93,22 @@ __device__ __forceinline__ void render_symbolic(int l, uint32_t* e, int mvx, int
     group_sync();
     const uint32_t w_pos = rec[RW_POS];
     const int px = w_pos & 0xFF, py = (w_pos >> 8) & 0xFF;
+    // view cells: lane l takes the columns l, l + G, ... of every row, so that the row and the
+    // column group are compile-time constants and a cell costs one LDS read at a fixed offset from
+    // the lane's base, one add for its bit number, and the OR
+    {
+        const uint8_t* cell0 = win + (1 + mvy) * WIN_PITCH + woff + 1 + mvx + l;
+        const int bit0 = l * NCHAN;
 #pragma unroll
-    for (int it_c = 0; it_c < ((VIEW_ROWS * VIEW_COLS) + G - 1) / G; ++it_c) {
-        const int c = l + it_c * G;
-        if (c >= (VIEW_ROWS * VIEW_COLS)) break;
-        const int row = c / VIEW_COLS, col = c - row * VIEW_COLS;
-        const int b = win[(row + 1 + mvy) * WIN_PITCH + woff + col + 1 + mvx];
-        const int bit = c * NCHAN + b;
-        atomicOr(&bits[bit >> 5], 1u << (bit & 31));
+        for (int row = 0; row < VIEW_ROWS; ++row) {
+#pragma unroll
+            for (int j = 0; j < (VIEW_COLS + G - 1) / G; ++j) {
+                if (G * j + G > VIEW_COLS && l + G * j >= VIEW_COLS) continue;
+                const int b = cell0[row * WIN_PITCH + G * j];
+                const int bit = bit0 + (row * VIEW_COLS + G * j) * NCHAN + b;
+                atomicOr(&bits[bit >> 5], 1u << (bit & 31));
+            }
+        }
     }
 #pragma unroll
     for (int it_k = 0; it_k < ((NMOB) + G - 1) / G; ++it_k) {

@@ -27,30 +27,57 @@ enum Intent : int { K_NONE = 0, K_MOVE = 1, K_MOVE_PATH = 2, K_ATTACK = 3, K_SHO
 
 struct StepOut { bool done; float reward; int mvx, mvy, woff; };
 
+// The part of the window a step can touch, in window rows and columns (inclusive): the 7 x 9 view
+// around the player, widened by one row or column on the side the player may move to.  Nothing
+// else of the window is read by the rules or the renderer, so nothing else is fetched: nine rows
+// always straddle two map tiles (cache lines), seven or eight often do not.
+struct WinRect { int r0, r1, c0, c1; };
+__device__ inline WinRect full_window() { return WinRect{0, WIN_ROWS - 1, 0, WIN_COLS - 1}; }
+__device__ inline WinRect window_for_action(int a)
+{
+    WinRect w{1, WIN_ROWS - 2, 1, WIN_COLS - 2};
+    if (a == AC_LEFT) w.c0 = 0;
+    if (a == AC_RIGHT) w.c1 = WIN_COLS - 1;
+    if (a == AC_UP) w.r0 = 0;
+    if (a == AC_DOWN) w.r1 = WIN_ROWS - 1;
+    return w;
+}
+__device__ inline bool in_rect(const WinRect& w, int wr, int wc) { return wr >= w.r0 && wr <= w.r1 && wc >= w.c0 && wc <= w.c1; }
+
 // Loads the map window around (px, py) into LDS with aligned dword loads: lane l takes dwords
 // l, l+G, ... of the 36 (four per window row).  A dword never straddles a map tile, and the
-// whole window lies in at most four tiles (cache lines).
+// whole window lies in at most four tiles (cache lines).  Only the dwords that hold a cell of
+// `need` are fetched; the others are left as they are.
+template <int G>
+__device__ __forceinline__ void load_window(int l, int px, int py, const uint8_t* __restrict__ map, uint32_t* win, const WinRect need)
+{
+    constexpr int NIT = (WIN_DWORDS + G - 1) / G;
+    const int x0 = px - WIN_COLS / 2, xa = x0 & ~3, y0 = py - WIN_ROWS / 2, woff = x0 & 3;
+    const int d0 = (woff + need.c0) >> 2, d1 = (woff + need.c1) >> 2;     // first and last dword of a row that is needed
+    uint32_t v[NIT];
+    bool inside[NIT], wanted[NIT];
+    // all loads are issued unconditionally (cells outside the map, and dwords that are not needed,
+    // read the player's own dword, whose cache line is fetched anyway), so they go out back to back
+    // and are waited for once
+    const int idle = map_index(px, py) & ~3;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int d = l + it * G;
+        const int r = d >> 2, j = d & 3, x = xa + (j << 2), y = y0 + r;
+        wanted[it] = d < WIN_DWORDS && r >= need.r0 && r <= need.r1 && j >= d0 && j <= d1;
+        inside[it] = wanted[it] && (unsigned)y < (unsigned)MAPW && (unsigned)x < (unsigned)MAPW;
+        v[it] = *reinterpret_cast<const uint32_t*>(map + (inside[it] ? map_index(x, y) : idle));
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int d = l + it * G;
+        if (wanted[it]) win[d] = inside[it] ? v[it] : 0x01010101u * (uint32_t)BK_OOB;
+    }
+}
 template <int G>
 __device__ __forceinline__ void load_window(int l, int px, int py, const uint8_t* __restrict__ map, uint32_t* win)
 {
-    constexpr int NIT = (WIN_DWORDS + G - 1) / G;
-    const int xa = (px - WIN_COLS / 2) & ~3, y0 = py - WIN_ROWS / 2;
-    uint32_t v[NIT];
-    bool inside[NIT];
-    // all loads are issued unconditionally (outside cells read offset 0 and are replaced
-    // afterwards), so they go out back to back and are waited for once
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const int d = l + it * G;
-        const int r = d >> 2, x = xa + ((d & 3) << 2), y = y0 + r;
-        inside[it] = d < WIN_DWORDS && (unsigned)y < (unsigned)MAPW && (unsigned)x < (unsigned)MAPW;
-        v[it] = *reinterpret_cast<const uint32_t*>(map + (inside[it] ? map_index(x, y) : 0));
-    }
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const int d = l + it * G;
-        if (d < WIN_DWORDS) win[d] = inside[it] ? v[it] : 0x01010101u * (uint32_t)BK_OOB;
-    }
+    load_window<G>(l, px, py, map, win, full_window());
 }
 
 // Mob and plant slots stay in their packed record form while the step runs: bit 0 alive,
@@ -95,7 +122,11 @@ __device__ __forceinline__ StepOut step_env(int l, uint32_t env, uint32_t* e, ui
     const int px0 = w_pos & 0xFF, py0 = (w_pos >> 8) & 0xFF;
     int px = px0, py = py0, dir = (w_pos >> 16) & 0xFF, sleeping = (w_pos >> 24) & 0xFF;
     const uint32_t win_key = 0x80000000u | (w_pos & 0xFFFFu);
-    if (!KEEP_WIN || e[LDS_WINPOS] != win_key) load_window<G>(l, px0, py0, map, e + LDS_WIN);
+    int a = ((unsigned)action < (unsigned)AC_COUNT) ? action : (int)AC_NOOP;
+    if (sleeping) a = AC_NOOP;
+    // a kept window serves later steps with other actions: it is always loaded whole
+    const WinRect loaded = KEEP_WIN ? full_window() : window_for_action(a);
+    if (!KEEP_WIN || e[LDS_WINPOS] != win_key) load_window<G>(l, px0, py0, map, e + LDS_WIN, loaded);
     // where a lane with nothing to read points its load: the player's own cell, whose cache line
     // the window load fetches anyway (any other fixed cell would cost a line of its own)
     const int idle_cell = map_index(px0, py0);
@@ -130,8 +161,6 @@ __device__ __forceinline__ StepOut step_env(int l, uint32_t env, uint32_t* e, ui
     const uint32_t ach0 = ach;
     const uint32_t sapling_draw = (uint32_t)Gr::shfl((int)dr.w[3], 3);
 
-    int a = ((unsigned)action < (unsigned)AC_COUNT) ? action : (int)AC_NOOP;
-    if (sleeping) a = AC_NOOP;
     group_sync();   // the window is in LDS
     if (KEEP_WIN && l == 0) e[LDS_WINPOS] = win_key;
 
