@@ -368,6 +368,18 @@ int craftax_stats(const void *state, craftax_metrics *out, void *workspace, size
 #define CRAFTAX_STATS_STATIC_MAX_ENVS 524288
 int craftax_stats_static(const void *state, craftax_metrics *out, int n, void *stream);
 
+/* Debug build with bounds checks (a build of the same sources with -DCRAFTAX_DEBUG_BOUNDS, shipped
+ * as libcraftax_hip_debug.so): every index the kernels form into a map, an LDS window or a staging
+ * area is checked on the device; an index outside its range is counted (and replaced by 0, so that
+ * nothing faults) instead of being used.  craftax_debug_bounds waits for the device, copies the
+ * record to report (HOST: violations so far, then source line, index and limit of the first one),
+ * clears it, and returns 1; in the release library it returns 0 and zeroes report.
+ * craftax_debug_bounds_selftest runs a kernel that forms one out-of-range index on purpose (it is
+ * caught and replaced, nothing faults) and returns 1 if the record then shows exactly that
+ * violation, 0 in the release library, a negative CRAFTAX_E_* code on a HIP error. */
+int craftax_debug_bounds(uint32_t report[4]);
+int craftax_debug_bounds_selftest(void);
+
 const char *craftax_last_error(void);
 
 #ifdef __cplusplus

@@ -13,6 +13,7 @@ import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libcraftax_hip.so")
+DEBUG_LIB_PATH = os.path.join(_PKG, "libcraftax_hip_debug.so")     # the same sources built with bounds checks
 
 OBS_SYM_U8_I8, OBS_SYM_U8_F32, OBS_SYM_F32, OBS_PIXELS_F32 = 0, 1, 2, 3
 WORLDGEN_VALUE, WORLDGEN_PERLIN = 0, 1
@@ -24,6 +25,7 @@ EXPORTS = [
     "craftax_state_init", "craftax_state_attach", "craftax_state_release", "craftax_reset", "craftax_step", "craftax_observe",
     "craftax_rollout", "craftax_export_envs", "craftax_import_envs", "craftax_mutate_swap", "craftax_mutate_noise", "craftax_synth_actions", "craftax_last_error",
     "craftax_stats_workspace_bytes", "craftax_stats", "craftax_stats_static",
+    "craftax_debug_bounds", "craftax_debug_bounds_selftest",
 ]
 
 
@@ -76,6 +78,23 @@ class CraftaxError(RuntimeError):
 _lib = None
 
 
+def use_library(path: str):
+    """Switches every later call of this module to the library at `path` (LIB_PATH or
+    DEBUG_LIB_PATH).  States made with one library are not known to the other."""
+    global _lib, LIB_PATH
+    LIB_PATH = path
+    _lib = None
+
+
+def craftax_debug_bounds():
+    """(checks built in, [violations, line, index, limit]) of the loaded library; clears the record."""
+    rep = (ctypes.c_uint32 * 4)()
+    rc = load().craftax_debug_bounds(rep)
+    if rc < 0:
+        raise CraftaxError(f"craftax_debug_bounds failed ({rc}): {load().craftax_last_error().decode()}")
+    return bool(rc), [int(x) for x in rep]
+
+
 def load() -> ctypes.CDLL:
     """Loads the built library; raises if it has not been built (run __graft_entry__.build())."""
     global _lib
@@ -117,6 +136,8 @@ def load() -> ctypes.CDLL:
     L.craftax_stats_workspace_bytes.restype = ctypes.c_size_t
     L.craftax_stats.argtypes = [vp, vp, vp, ctypes.c_size_t, i32, vp]
     L.craftax_stats_static.argtypes = [vp, vp, i32, vp]
+    L.craftax_debug_bounds.argtypes = [ctypes.POINTER(ctypes.c_uint32 * 4)]
+    L.craftax_debug_bounds_selftest.argtypes = []
     L.craftax_last_error.argtypes = []
     L.craftax_last_error.restype = ctypes.c_char_p
     _lib = L

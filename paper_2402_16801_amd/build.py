@@ -15,19 +15,23 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False, only_changed: bool = False) -> str:
+DEBUG_OUT = os.path.join(_PKG, "libcraftax_hip_debug.so")
+
+
+def build_library(verbose: bool = False, only_changed: bool = False, debug_bounds: bool = False) -> str:
     """Compiles every translation unit (in parallel) and links the library.  only_changed skips a
     unit whose object is newer than every source and header (for quick iteration; the build check
     always compiles everything)."""
     from concurrent.futures import ThreadPoolExecutor
 
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objdir = os.path.join(_PKG, "_build")
+    objdir = os.path.join(_PKG, "_build_debug" if debug_bounds else "_build")
     os.makedirs(objdir, exist_ok=True)
     csrc = os.path.join(_PKG, "csrc")
     deps = [os.path.join(csrc, f) for f in os.listdir(csrc)] + [os.path.join(os.path.dirname(_PKG), "include", "craftax.h")]
     newest = max(os.path.getmtime(d) for d in deps)
-    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"] + (["-DCRAFTAX_DEBUG_BOUNDS"] if debug_bounds else [])
+    out = DEBUG_OUT if debug_bounds else OUT
 
     def compile_one(src):
         obj = os.path.join(objdir, os.path.basename(src) + ".o")
@@ -43,13 +47,23 @@ def build_library(verbose: bool = False, only_changed: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=len(SRCS)) as ex:
         objs = list(ex.map(compile_one, SRCS))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT] + objs
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + objs
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc link failed:\n" + res.stderr)
     if verbose:
         print(" ".join(cmd))
-    return OUT
+    return out
+
+
+def build_all(only_changed: bool = False):
+    """The release library and the bounds-checking debug library, side by side."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    with ThreadPoolExecutor(max_workers=2) as ex:
+        a = ex.submit(build_library, False, only_changed, False)
+        b = ex.submit(build_library, False, only_changed, True)
+        return a.result(), b.result()
 
 
 EXAMPLE_SRC = os.path.join(os.path.dirname(_PKG), "examples", "step_from_c.c")
@@ -69,5 +83,5 @@ def build_example() -> str:
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    print(build_all())
     print(build_example())

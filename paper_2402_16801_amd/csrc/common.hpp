@@ -7,6 +7,25 @@
 
 namespace cx {
 
+// ---- bounds checks of the debug build ------------------------------------------------------------
+// Built with -DCRAFTAX_DEBUG_BOUNDS, every index into a map, an LDS window or a staging area that
+// goes through CX_IDX(index, limit) is checked: an index outside [0, limit) is counted in a
+// device-side record (with the source line, the index and the limit of the first one) and 0 is used
+// in its place, so that a wrong index is reported without a memory fault.  The release build
+// compiles CX_IDX to the bare index.  The record is per translation unit; the host adds them up.
+#ifdef CRAFTAX_DEBUG_BOUNDS
+static __device__ uint32_t g_bounds[4];   // violations, then line / index / limit of the first one
+__device__ inline long long bounds_checked(long long i, long long limit, int line)
+{
+    if (i >= 0 && i < limit) return i;
+    if (atomicAdd(&g_bounds[0], 1u) == 0u) { g_bounds[1] = (uint32_t)line; g_bounds[2] = (uint32_t)i; g_bounds[3] = (uint32_t)limit; }
+    return 0;
+}
+#define CX_IDX(i, limit) ((int)cx::bounds_checked((long long)(i), (long long)(limit), __LINE__))
+#else
+#define CX_IDX(i, limit) (i)
+#endif
+
 // ---- ids fixed by the paper (appendices "Block Types", "Action Space", "Achievements") ----
 enum Block : int { BK_INVALID = 0, BK_OOB = 1, BK_GRASS = 2, BK_WATER = 3, BK_STONE = 4, BK_TREE = 5,
                    BK_WOOD = 6, BK_PATH = 7, BK_COAL = 8, BK_IRON = 9, BK_DIAMOND = 10, BK_TABLE = 11,
@@ -213,6 +232,7 @@ __device__ inline void group_sync()
 // window the step reads every time then touches 2 to 4 lines instead of 5 to 9.
 __device__ inline int map_index(int x, int y)
 {
+    x = CX_IDX(x, MAPW); y = CX_IDX(y, MAPW);
     return (((y >> 3) << 2) + (x >> 4)) * 128 + ((y & 7) << 4) + (x & 15);
 }
 

@@ -865,6 +865,22 @@ int check_header(const void* header_bytes, const craftax_config* cfg, int n, std
     return CRAFTAX_OK;
 }
 
+int debug_bounds(uint32_t report[4], std::string* err)
+{
+#ifdef CRAFTAX_DEBUG_BOUNDS
+    uint32_t mine[4] = {0u, 0u, 0u, 0u};
+    const uint32_t zero[4] = {0u, 0u, 0u, 0u};
+    hipError_t e = hipMemcpyFromSymbol(mine, HIP_SYMBOL(cx::g_bounds), sizeof(mine));
+    if (e == hipSuccess) e = hipMemcpyToSymbol(HIP_SYMBOL(cx::g_bounds), zero, sizeof(zero));
+    if (e != hipSuccess) { *err = std::string("debug_bounds: ") + hipGetErrorString(e); return CRAFTAX_E_HIP; }
+    if (report[0] == 0u && mine[0] != 0u) { report[1] = mine[1]; report[2] = mine[2]; report[3] = mine[3]; }
+    report[0] += mine[0];
+#else
+    (void)report; (void)err;
+#endif
+    return CRAFTAX_OK;
+}
+
 RecordLayout record_layout(const void* state, const craftax_config* cfg, int n)
 {
     const Ptrs q = pointers(state, make_header(cfg, n));

@@ -25,6 +25,8 @@ int check_header(const void* header_bytes, const craftax_config* cfg, int n, std
 // where the metrics kernel finds achievements, t and episode: records as dwords
 struct RecordLayout { const uint32_t* recs; int stride, ach, ach_words, t, episode; };
 RecordLayout record_layout(const void* state, const craftax_config* cfg, int n);
+// debug build: adds this translation unit's bounds record to report[4] and clears it
+int debug_bounds(uint32_t report[4], std::string* err);
 // LDS and thread needs of the kernels this configuration launches against the device's limits
 int check_kernels(const craftax_config* cfg, std::string* err);
 int rollout(void* state, const craftax_config* cfg, int n, const int32_t* actions, int steps, void* obs, float* reward, uint8_t* done,

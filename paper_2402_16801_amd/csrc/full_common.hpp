@@ -150,8 +150,16 @@ constexpr int R_POS = 0, R_FLAGS = 1, R_ATTR = 2, R_INV = 3, R_POT = 6, R_VIT = 
               R_KILLS = 11, R_LADDER = 14, R_ACH = 23, R_T = 26, R_EPISODE = 27, R_SEED_LO = 28, R_SEED_HI = 29, R_PLANT = 32;
 constexpr size_t MAP_BYTES = (size_t)FLOORS * 2 * CELLS;          // 41472 per map slot
 __host__ __device__ inline size_t map_offset(uint32_t env, uint32_t episode) { return ((size_t)env * 2 + (episode & 1u)) * MAP_BYTES; }
-__device__ inline size_t block_off(int f, int x, int y) { return (size_t)f * (2 * CELLS) + (size_t)(y * W + x); }
-__device__ inline size_t il_off(int f, int x, int y) { return (size_t)f * (2 * CELLS) + CELLS + (size_t)(y * W + x); }
+__device__ inline size_t block_off(int f, int x, int y)
+{
+    f = CX_IDX(f, FLOORS); x = CX_IDX(x, W); y = CX_IDX(y, W);
+    return (size_t)f * (2 * CELLS) + (size_t)(y * W + x);
+}
+__device__ inline size_t il_off(int f, int x, int y)
+{
+    f = CX_IDX(f, FLOORS); x = CX_IDX(x, W); y = CX_IDX(y, W);
+    return (size_t)f * (2 * CELLS) + CELLS + (size_t)(y * W + x);
+}
 
 struct Mob { int alive, x, y, dir, hp, cd, type; };
 __host__ __device__ inline Mob unpack_mob(uint32_t w)

@@ -110,7 +110,7 @@ __device__ __forceinline__ void render_env(const int l, uint32_t* e, const int w
     }
     if (l < NVEC + 1) vec[l] = l < NVEC ? scalar_value(l, rec, luts) : 0.0f;
     wave_sync();
-    auto set_bit = [&](int i) { atomicOr(&bits[i >> 5], 1u << (i & 31)); };
+    auto set_bit = [&](int i) { atomicOr(&bits[CX_IDX(i >> 5, 260)], 1u << (i & 31)); };
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const int cell = l + 64 * it;
@@ -121,10 +121,10 @@ __device__ __forceinline__ void render_env(const int l, uint32_t* e, const int w
             if (!inb(x, y)) {   // beyond the edge of the map: always visible
                 set_bit(cell * NCHAN + B_OOB); set_bit(cell * NCHAN + 37 + IT_NONE); lv = MAX_LIGHT;
             } else {
-                const int il = wi[(y - wy0) * WIN_PITCH + (x - wx0)];
+                const int il = wi[CX_IDX((y - wy0) * WIN_PITCH + (x - wx0), WIN_ROWS * WIN_PITCH)];
                 lv = il >> 3;
                 if (lv != 0) {      // cells darker than 0.05 stay blank
-                    set_bit(cell * NCHAN + (wb[(y - wy0) * WIN_PITCH + (x - wx0)] & 63));
+                    set_bit(cell * NCHAN + (wb[CX_IDX((y - wy0) * WIN_PITCH + (x - wx0), WIN_ROWS * WIN_PITCH)] & 63));
                     set_bit(cell * NCHAN + 37 + (il & 7));
                     const uint32_t cr = cre[cell];
                     if (cr != 0xFFFFFFFFu) set_bit(cell * NCHAN + (int)(cr & 0xFFu));

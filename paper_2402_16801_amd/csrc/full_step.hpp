@@ -111,8 +111,8 @@ __device__ __forceinline__ void load_window(int l, const uint8_t* __restrict__ m
             const int x = cx_ - WIN_COLS / 2 + c, y = cy_ - WIN_ROWS / 2 + r;
             int b = B_OOB, il = MAX_LIGHT << 3;
             if (inb(x, y)) { b = maps[block_off(f, x, y)]; il = maps[il_off(f, x, y)]; }
-            wb[r * WIN_PITCH + c] = (uint8_t)b;
-            wi[r * WIN_PITCH + c] = (uint8_t)il;
+            wb[CX_IDX(r * WIN_PITCH + c, WIN_ROWS * WIN_PITCH)] = (uint8_t)b;
+            wi[CX_IDX(r * WIN_PITCH + c, WIN_ROWS * WIN_PITCH)] = (uint8_t)il;
         }
     }
 }
@@ -161,8 +161,8 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
     after_load();
     wave_sync();
 
-    auto win_b = [&](int x, int y) { return uni((int)wb[(y - wy0) * WIN_PITCH + (x - wx0)]); };
-    auto win_i = [&](int x, int y) { return uni((int)wi[(y - wy0) * WIN_PITCH + (x - wx0)]); };
+    auto win_b = [&](int x, int y) { return uni((int)wb[CX_IDX((y - wy0) * WIN_PITCH + (x - wx0), WIN_ROWS * WIN_PITCH)]); };
+    auto win_i = [&](int x, int y) { return uni((int)wi[CX_IDX((y - wy0) * WIN_PITCH + (x - wx0), WIN_ROWS * WIN_PITCH)]); };
     auto in_win = [&](int x, int y) { return (unsigned)(x - wx0) < (unsigned)WIN_COLS && (unsigned)(y - wy0) < (unsigned)WIN_ROWS; };
     auto occ_mask = [&](int x, int y) -> uint32_t { return (uint32_t)__ballot(m.alive && m.x == x && m.y == y); };
     // the one block cell the player may change this step; mobs read their terrain from HBM and
@@ -171,7 +171,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
     auto set_block = [&](int x, int y, int b) {
         if (l == 0) {
             maps[block_off(P.floor, x, y)] = (uint8_t)b;
-            if (in_win(x, y)) wb[(y - wy0) * WIN_PITCH + (x - wx0)] = (uint8_t)b;
+            if (in_win(x, y)) wb[CX_IDX((y - wy0) * WIN_PITCH + (x - wx0), WIN_ROWS * WIN_PITCH)] = (uint8_t)b;
         }
         wave_sync();
     };
@@ -214,7 +214,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
                     const int nil = (il & ~7) | IT_LADDER_DOWN;
                     if (l == 0) {
                         maps[il_off(f, lx, ly)] = (uint8_t)nil;
-                        if (in_win(lx, ly)) wi[(ly - wy0) * WIN_PITCH + (lx - wx0)] = (uint8_t)nil;
+                        if (in_win(lx, ly)) wi[CX_IDX((ly - wy0) * WIN_PITCH + (lx - wx0), WIN_ROWS * WIN_PITCH)] = (uint8_t)nil;
                     }
                     wave_sync();
                 }
@@ -239,7 +239,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
     bool near_table, near_furnace;
     {
         int b = B_INVALID;
-        if (l < 9) b = wb[(P.py - wy0 - 1 + l / 3) * WIN_PITCH + (P.px - wx0 - 1 + l % 3)];
+        if (l < 9) b = wb[CX_IDX((P.py - wy0 - 1 + l / 3) * WIN_PITCH + (P.px - wx0 - 1 + l % 3), WIN_ROWS * WIN_PITCH)];
         near_table = __ballot(b == B_TABLE) != 0;
         near_furnace = __ballot(b == B_FURNACE) != 0;
     }
@@ -399,7 +399,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
             } else {
                 if (P.inv[I_TORCH] < 1 || !in_set(WALKABLE, b)) break;
                 --P.inv[I_TORCH];
-                if (l == 0) wi[(ty - wy0) * WIN_PITCH + (tx - wx0)] = (uint8_t)((il & ~7) | IT_TORCH);
+                if (l == 0) wi[CX_IDX((ty - wy0) * WIN_PITCH + (tx - wx0), WIN_ROWS * WIN_PITCH)] = (uint8_t)((il & ~7) | IT_TORCH);
                 wave_sync();
                 // light falls off by 4 per cell of Chebyshev distance; the centre cell also carries the item
 #pragma unroll
@@ -408,12 +408,12 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
                     if (i < 81) {
                         const int ddy = i / 9 - 4, ddx = i % 9 - 4, x = tx + ddx, y = ty + ddy;
                         if (inb(x, y) && in_win(x, y)) {
-                            const int old = wi[(y - wy0) * WIN_PITCH + (x - wx0)];
+                            const int old = wi[CX_IDX((y - wy0) * WIN_PITCH + (x - wx0), WIN_ROWS * WIN_PITCH)];
                             const int nl = MAX_LIGHT - 4 * max(iabs(ddx), iabs(ddy));
                             const bool centre = ddx == 0 && ddy == 0;
                             if (nl > (old >> 3) || centre) {
                                 const int nv = (old & 7) | (max(nl, old >> 3) << 3);
-                                wi[(y - wy0) * WIN_PITCH + (x - wx0)] = (uint8_t)nv;
+                                wi[CX_IDX((y - wy0) * WIN_PITCH + (x - wx0), WIN_ROWS * WIN_PITCH)] = (uint8_t)nv;
                                 maps[il_off(f, x, y)] = (uint8_t)nv;
                             }
                         }
@@ -690,7 +690,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
             if ((beside(z0) || beside(z1) || beside(z2)) && rnd.w[2] < P_PLANT_EATEN) { nb = B_GRASS; q_alive = 0; q_x = q_y = q_age = 0; }
             if (nb >= 0) {
                 maps[block_off(0, x, y)] = (uint8_t)nb;
-                if (in_win(x, y)) wb[(y - wy0) * WIN_PITCH + (x - wx0)] = (uint8_t)nb;
+                if (in_win(x, y)) wb[CX_IDX((y - wy0) * WIN_PITCH + (x - wx0), WIN_ROWS * WIN_PITCH)] = (uint8_t)nb;
             }
         }
         wave_sync();

@@ -104,9 +104,9 @@ __device__ __forceinline__ void render_symbolic(int l, uint32_t* e, int mvx, int
 #pragma unroll
             for (int j = 0; j < (VIEW_COLS + G - 1) / G; ++j) {
                 if (G * j + G > VIEW_COLS && l + G * j >= VIEW_COLS) continue;
-                const int b = cell0[row * WIN_PITCH + G * j];
+                const int b = win[CX_IDX((int)(cell0 - win) + row * WIN_PITCH + G * j, WIN_ROWS * WIN_PITCH)];
                 const int bit = bit0 + (row * VIEW_COLS + G * j) * NCHAN + b;
-                atomicOr(&bits[bit >> 5], 1u << (bit & 31));
+                atomicOr(&bits[CX_IDX(bit >> 5, 42)], 1u << (bit & 31));
             }
         }
     }
@@ -118,7 +118,7 @@ __device__ __forceinline__ void render_symbolic(int l, uint32_t* e, int mvx, int
         const int col = m.x - px + VIEW_COLS / 2, row = m.y - py + VIEW_ROWS / 2;
         if (m.alive && (unsigned)col < (unsigned)VIEW_COLS && (unsigned)row < (unsigned)VIEW_ROWS) {
             const int bit = (row * VIEW_COLS + col) * NCHAN + 17 + ((k * 11) >> 5);
-            atomicOr(&bits[bit >> 5], 1u << (bit & 31));
+            atomicOr(&bits[CX_IDX(bit >> 5, 42)], 1u << (bit & 31));
         }
     }
     // the 22 scalars; int8 flavour packs four per dword
@@ -241,10 +241,10 @@ __device__ __forceinline__ void render_pixels_block(const uint32_t* __restrict__
             const bool valid = y < PIX_SIDE;
             const int yy = valid ? y : 0;
             const int tr = yy / PIX_TILE, iy = yy - tr * PIX_TILE, tc = x / PIX_TILE, ix = x - tc * PIX_TILE;
-            const int tile = s_tile[tr * PIX_VIEW + tc], ent = s_ent[tr * PIX_VIEW + tc];
+            const int tile = s_tile[CX_IDX(tr * PIX_VIEW + tc, PIX_VIEW * PIX_VIEW)], ent = s_ent[CX_IDX(tr * PIX_VIEW + tc, PIX_VIEW * PIX_VIEW)];
             const int in_tile = (iy * PIX_TILE + ix) * 3;
-            const float* src = luts->tile + (tile - 1) * PIX_TILE_FLOATS + in_tile;
-            if (ent >= 0 && luts->ent_mask[ent * (PIX_TILE * PIX_TILE) + iy * PIX_TILE + ix]) src = luts->ent + ent * PIX_TILE_FLOATS + in_tile;
+            const float* src = luts->tile + CX_IDX((tile - 1) * PIX_TILE_FLOATS + in_tile, 16 * PIX_TILE_FLOATS - 2);
+            if (ent >= 0 && luts->ent_mask[CX_IDX(ent * (PIX_TILE * PIX_TILE) + iy * PIX_TILE + ix, 5 * PIX_TILE * PIX_TILE)]) src = luts->ent + CX_IDX(ent * PIX_TILE_FLOATS + in_tile, 5 * PIX_TILE_FLOATS - 2);
             v[u][0] = src[0]; v[u][1] = src[1]; v[u][2] = src[2];
             scale[u] = valid ? light : 0.0f;
             x += 64;

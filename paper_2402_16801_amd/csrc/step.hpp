@@ -71,7 +71,7 @@ __device__ __forceinline__ void load_window(int l, int px, int py, const uint8_t
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
         const int d = l + it * G;
-        if (wanted[it]) win[d] = inside[it] ? v[it] : 0x01010101u * (uint32_t)BK_OOB;
+        if (wanted[it]) win[CX_IDX(d, WIN_DWORDS)] = inside[it] ? v[it] : 0x01010101u * (uint32_t)BK_OOB;
     }
 }
 template <int G>
@@ -170,7 +170,7 @@ __device__ __forceinline__ StepOut step_env(int l, uint32_t env, uint32_t* e, ui
     for (int it = 0; it < (9 + G - 1) / G; ++it) {
         const int j = l + it * G;
         if (j >= 9) break;
-        const int b = win[(3 + j / 3) * WIN_PITCH + woff + 4 + j % 3];
+        const int b = win[CX_IDX((3 + j / 3) * WIN_PITCH + woff + 4 + j % 3, WIN_ROWS * WIN_PITCH)];
         l_table = l_table || b == BK_TABLE;
         l_furnace = l_furnace || b == BK_FURNACE;
     }
@@ -181,7 +181,7 @@ __device__ __forceinline__ StepOut step_env(int l, uint32_t env, uint32_t* e, ui
     const bool f_in = in_map(fx, fy);
     const uint32_t fkey = cell_key(fx, fy);
     const int f_win = (WIN_ROWS / 2 + ddy) * WIN_PITCH + woff + WIN_COLS / 2 + ddx;
-    const int fb = win[f_win];
+    const int fb = win[CX_IDX(f_win, WIN_ROWS * WIN_PITCH)];
     // which mob (if any) stands on the facing cell: owner lane, sub-slot and hp
     int my_hit = -1;
     uint32_t plant_alive = 0;
@@ -281,7 +281,7 @@ __device__ __forceinline__ StepOut step_env(int l, uint32_t env, uint32_t* e, ui
     }
     const int modcell = modval >= 0 ? fy * MAPW + fx : -1;
     if (modval >= 0) {
-        if (l == 0) { map[map_index(fx, fy)] = (uint8_t)modval; win[f_win] = (uint8_t)modval; }
+        if (l == 0) { map[map_index(fx, fy)] = (uint8_t)modval; win[CX_IDX(f_win, WIN_ROWS * WIN_PITCH)] = (uint8_t)modval; }
 #pragma unroll
         for (int s = 0; s < NSP; ++s) {
             const int k = l + s * G;
@@ -463,7 +463,7 @@ __device__ __forceinline__ StepOut step_env(int l, uint32_t env, uint32_t* e, ui
             if (nb != q_block[s]) {
                 map[map_index(qx, qy)] = (uint8_t)nb;
                 const int wx = qx - (px0 - WIN_COLS / 2), wy = qy - (py0 - WIN_ROWS / 2);
-                if ((unsigned)wx < (unsigned)WIN_COLS && (unsigned)wy < (unsigned)WIN_ROWS) win[wy * WIN_PITCH + woff + wx] = (uint8_t)nb;
+                if ((unsigned)wx < (unsigned)WIN_COLS && (unsigned)wy < (unsigned)WIN_ROWS) win[CX_IDX(wy * WIN_PITCH + woff + wx, WIN_ROWS * WIN_PITCH)] = (uint8_t)nb;
             }
             if (nb == BK_GRASS) qw[s] = 0u;
         }

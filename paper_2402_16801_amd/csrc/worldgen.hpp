@@ -34,7 +34,7 @@ __device__ inline uint32_t smooth16(int k) { return (uint32_t)((24 * k * k - k *
 // the final shift and every intermediate fits in 32 bits.
 __device__ inline uint32_t column(const uint16_t* lat, int width, int ix, int iy, uint32_t wy)
 {
-    return (uint32_t)lat[iy * width + ix] * (256u - wy) + (uint32_t)lat[(iy + 1) * width + ix] * wy;
+    return (uint32_t)lat[CX_IDX(iy * width + ix, width * width)] * (256u - wy) + (uint32_t)lat[CX_IDX((iy + 1) * width + ix, width * width)] * wy;
 }
 __device__ inline uint32_t across(uint32_t left, uint32_t right, uint32_t wx)
 {
@@ -67,7 +67,7 @@ __device__ inline uint32_t perlin(const uint16_t* lat, int width, const uint32_t
     for (int cy = 0; cy < 2; ++cy)
 #pragma unroll
         for (int cx = 0; cx < 2; ++cx) {
-            const uint32_t g = cs[lat[(iy + cy) * width + ix + cx] >> 6];
+            const uint32_t g = cs[lat[CX_IDX((iy + cy) * width + ix + cx, width * width)] >> 6];
             dot[cy][cx] = (int64_t)((int)(int16_t)(g & 0xFFFFu) * (kx - cx * S) + (int)(int16_t)(g >> 16) * (ky - cy * S));
         }
     const int64_t wx = perlin_fade<S>(kx), wy = perlin_fade<S>(ky);
@@ -190,8 +190,8 @@ __device__ __forceinline__ void worldgen_block(uint8_t* __restrict__ map, uint16
         constexpr int WY0 = MAPW / 2 - WIN_ROWS / 2, WX0 = (MAPW / 2 - WIN_COLS / 2) & ~3;
         const int wr = y - WY0, wc = x0 - WX0;
         if (start_win != nullptr && (unsigned)wr < (unsigned)WIN_ROWS && (unsigned)wc < (unsigned)WIN_PITCH) {
-            start_win[wr * (WIN_PITCH / 4) + wc / 4] = packed[0];
-            start_win[wr * (WIN_PITCH / 4) + wc / 4 + 1] = packed[1];
+            start_win[CX_IDX(wr * (WIN_PITCH / 4) + wc / 4, WIN_DWORDS)] = packed[0];
+            start_win[CX_IDX(wr * (WIN_PITCH / 4) + wc / 4 + 1, WIN_DWORDS)] = packed[1];
         }
     }
     }
