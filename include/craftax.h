@@ -108,9 +108,9 @@ typedef struct craftax_config {
     uint64_t atlas_seed;         /* seed of the synthetic tile atlas (pixel observations) */
     uint32_t worldgen;           /* CRAFTAX_WORLDGEN_*: the noise behind the terrain rules */
     uint32_t reset_mode;         /* CRAFTAX_RESET_*: where the world of a new episode comes from */
-    uint32_t group_lanes;        /* Classic only, tuning: lanes of a wavefront that share one environment in the step
-                                    kernels; 0 = chosen from n (the default), else 4, 8 or 16.  Results do not depend on
-                                    it.  Variant CRAFTAX ignores it. */
+    uint32_t group_lanes;        /* tuning: lanes of a wavefront that share one environment in the step kernel; 0 = chosen
+                                    from n (the default), else 4, 8 or 16 (Classic), 16 or 64 (CRAFTAX).  Results do not
+                                    depend on it. */
     uint32_t reserved;           /* must be 0 */
 } craftax_config;
 

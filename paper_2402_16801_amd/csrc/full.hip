@@ -26,6 +26,7 @@ using la::NSUB;
 
 constexpr int EAGER_SPARE_ENVS = 8192;   // up to here a step fetches the spare world's start window in advance (see kf_step)
 constexpr int RESET_SLOTS = 64;    // environments served at once by kf_reset_list (nine blocks each)
+constexpr int MAX_ENVS_PER_STEP_BLOCK = 16;   // a step block holds 4 environments (a wavefront each) or 16 (16 lanes each)
 constexpr int REGEN_BLOCKS = 256;  // regeneration blocks at the head of the step grid: with 1,024 step blocks (4,096 environments) they fill the chip exactly
 
 __device__ inline uint32_t pack_regs(const MobRegs& m)
@@ -107,14 +108,23 @@ static_assert(LAT_TOTAL * 2 <= 128 * 4 && sizeof(GenLayout) <= (512 - 128) * 4 &
 // rare trip (255 -> 216 us per launch at 65,536 environments).
 // PERLIN: the regeneration blocks generate Perlin worlds (a kernel of its own, so that the value-noise
 // kernel carries none of that code).
-template <bool F32, bool EAGER, bool PERLIN>
-__global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
+// GW: lanes per environment (see Lanes): 64 = one wavefront per environment, four environments per
+// block; 16 = four environments per wavefront, sixteen per block.
+template <bool F32, bool EAGER, bool PERLIN, int GW>
+__global__ __launch_bounds__(BLOCK, GW == 64 ? 5 : 2) void kf_step(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
                                                 const Luts* __restrict__ luts, const int32_t* __restrict__ actions,
                                                 uint8_t* __restrict__ obs, float* __restrict__ reward,
                                                 uint8_t* __restrict__ done, Lists ls, Params p, int regen_blocks)
 {
-    __shared__ uint32_t s_env[ENVS_PER_BLOCK * L_ENV_DWORDS];
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+    using G = Lanes<GW>;
+    constexpr int EPB = BLOCK / GW;                          // environments per block
+    constexpr int REC_IT = REC_DWORDS / GW > 0 ? REC_DWORDS / GW : 1;
+    constexpr int WIN_IT = (WIN_ROWS * WIN_COLS + GW - 1) / GW;
+    static_assert(REC_DWORDS % GW == 0 || GW > REC_DWORDS, "the record is moved in whole turns of the group");
+    static_assert(GW >= MOBTAB_DWORDS && GW >= NTAG && GW >= FLOORS + 1, "a group holds a mob table, the tags and the header in one turn");
+    __shared__ uint32_t s_env[EPB * L_ENV_DWORDS];
+    __shared__ float s_lut[LUT_FLOATS];
+    const int tid = threadIdx.x, w = tid / GW, l = tid % GW;
     if ((int)blockIdx.x < regen_blocks) {
         const la::Ticket ticket = la::enter_launch_queue(ls, s_env + 528);
         regeneration_queue<PERLIN>(envs, maps, ls, ticket.seq, s_env, regen_blocks, luts->perlin_cs);
@@ -122,38 +132,51 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
         return;
     }
     const uint32_t step_block = blockIdx.x - (uint32_t)regen_blocks;
-    const int env = (int)step_block * ENVS_PER_BLOCK + w;
+    const int env = (int)step_block * EPB + w;
     const bool active = env < p.n;
     uint32_t* genv = envs + (size_t)(active ? env : 0) * ENV_DWORDS;
     // Everything that depends on the environment's number alone is fetched before the launch
     // bookkeeping, whose own trip to memory then costs nothing extra: the record, the action, and
     // what a finished episode needs from the spare world (its tags, its ladders and potion map).
-    uint32_t rec_word = 0u, hdr = 0u;
+    uint32_t rec_word[REC_IT], hdr = 0u;
     int action_raw = 0;
     uint2 tag = make_uint2(0u, 0u);
+#pragma unroll
+    for (int it = 0; it < REC_IT; ++it) rec_word[it] = 0u;
+    // what the renderer looks up in tables: asked for now, used at the end of the step
+    RenderAux<GW> aux;
+    fetch_scalar_specs<GW>(l, aux);
+    aux.lut = s_lut;
+    if (tid < LUT_FLOATS) s_lut[tid] = luts->sqrt10[tid];     // sqrt10, tenth and light20 lie one after the other
     if (active) {
-        rec_word = genv[l];
+#pragma unroll
+        for (int it = 0; it < REC_IT; ++it) if (l + GW * it < REC_DWORDS) rec_word[it] = genv[l + GW * it];
         action_raw = actions[env];
         if (l < NTAG) tag = ls.tags[(size_t)env * NTAG + l];
         if (l < FLOORS + 1) hdr = genv[SPARE_LADDER + l];
     }
     const la::Ticket ticket = la::enter_launch(ls, false, 0u);
     const uint32_t seq = ticket.seq;
+    __syncthreads();                                          // the conversion tables are in LDS
     if (active) {
         uint32_t* e = s_env + w * L_ENV_DWORDS;
-        e[L_REC + l] = rec_word;
-        const int action = uni(action_raw);
+#pragma unroll
+        for (int it = 0; it < REC_IT; ++it) if (l + GW * it < REC_DWORDS) e[L_REC + l + GW * it] = rec_word[it];
+        const int action = G::uni(action_raw);
         wave_sync();
-        const uint32_t ep = uniu(e[L_REC + R_EPISODE]), lo = uniu(e[L_REC + R_SEED_LO]), hi = uniu(e[L_REC + R_SEED_HI]);
+        const uint32_t ep = G::uniu(e[L_REC + R_EPISODE]), lo = G::uniu(e[L_REC + R_SEED_LO]), hi = G::uniu(e[L_REC + R_SEED_HI]);
+        // daylight of the state that will be rendered: the next phase, or phase 0 of a fresh episode
+        const uint32_t phase_now = G::uniu(e[L_REC + R_MANA]) >> 16;
+        const float day_next = luts->daylight[phase_now + 1u == p.day_length ? 0u : phase_now + 1u], day_fresh = luts->daylight[0];
         MobRegs m;
         uint32_t qw;
         Player P;
         // the window of the spare world's start position comes with the current window
         const uint8_t* spare = maps + map_offset((uint32_t)env, ep + 1u);
-        uint32_t sw[3];
+        uint32_t sw[WIN_IT];
 #pragma unroll
-        for (int it = 0; it < 3; ++it) {
-            const int i = l + 64 * it;
+        for (int it = 0; it < WIN_IT; ++it) {
+            const int i = l + GW * it;
             sw[it] = 0u;
             if (EAGER && i < WIN_ROWS * WIN_COLS) {
                 const int r = i / WIN_COLS, c = i - r * WIN_COLS;
@@ -165,8 +188,8 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
             if (l < NTAG) { e[L_SPARE_TAG + 2 * l] = tag.x; e[L_SPARE_TAG + 2 * l + 1] = tag.y; }
             if (l < FLOORS + 1) e[L_SPARE_HDR + l] = hdr;
 #pragma unroll
-            for (int it = 0; it < 3; ++it) {
-                const int i = l + 64 * it;
+            for (int it = 0; it < WIN_IT; ++it) {
+                const int i = l + GW * it;
                 if (EAGER && i < WIN_ROWS * WIN_COLS) {
                     const int r = i / WIN_COLS, c = i - r * WIN_COLS;
                     reinterpret_cast<uint8_t*>(e + L_SPARE_WB)[r * WIN_PITCH + c] = (uint8_t)sw[it];
@@ -174,7 +197,7 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
                 }
             }
         };
-        StepOut o = step_env(l, (uint32_t)env, e, genv, maps + map_offset((uint32_t)env, ep), luts, action, p, m, qw, P, park);
+        StepOut o = step_env<GW>(l, (uint32_t)env, e, genv, maps + map_offset((uint32_t)env, ep), luts, action, p, m, qw, P, park);
         if (l == 0) { reward[env] = o.reward; done[env] = o.done ? 1 : 0; }
         bool write_back = !o.done, queued = false;
         uint32_t list_at = 0u;
@@ -185,23 +208,29 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
             wave_sync();
         } else {
             // every part of the next world must have been written by an earlier launch
-            constexpr uint64_t ALL = (1ull << NTAG) - 1ull;
-            const bool ready = (__ballot(l < NTAG && e[L_SPARE_TAG + 2 * (l < NTAG ? l : 0)] == ep + 1u &&
-                                         e[L_SPARE_TAG + 2 * (l < NTAG ? l : 0) + 1] < seq) & ALL) == ALL;
+            constexpr uint32_t ALL = (1u << NTAG) - 1u;
+            const bool ready = (G::ballot(l < NTAG && e[L_SPARE_TAG + 2 * (l < NTAG ? l : 0)] == ep + 1u &&
+                                          e[L_SPARE_TAG + 2 * (l < NTAG ? l : 0) + 1] < seq) & ALL) == ALL;
             if (ready) {
                 // start the new episode right here: fresh record from the spare world's ladders and
                 // potion map, all mob tables empty, window of the start position from the other slot
                 wave_sync();
-                e[L_REC + l] = fresh_record_word(l, e + L_SPARE_HDR, lo, hi, ep + 1u);
+#pragma unroll
+                for (int it = 0; it < REC_IT; ++it)
+                    if (l + GW * it < REC_DWORDS) e[L_REC + l + GW * it] = fresh_record_word(l + GW * it, e + L_SPARE_HDR, lo, hi, ep + 1u);
                 if (EAGER) {
-                    if (l < WIN_ROWS * WIN_PITCH / 4) { e[L_WB + l] = e[L_SPARE_WB + l]; e[L_WI + l] = e[L_SPARE_WI + l]; }
+#pragma unroll
+                    for (int it = 0; it < (WIN_ROWS * WIN_PITCH / 4 + GW - 1) / GW; ++it) {
+                        const int i = l + GW * it;
+                        if (i < WIN_ROWS * WIN_PITCH / 4) { e[L_WB + i] = e[L_SPARE_WB + i]; e[L_WI + i] = e[L_SPARE_WI + i]; }
+                    }
                 } else {
-                    load_window(l, maps + map_offset((uint32_t)env, ep + 1u), 0, W / 2, W / 2, reinterpret_cast<uint8_t*>(e + L_WB),
-                                reinterpret_cast<uint8_t*>(e + L_WI));
+                    load_window<GW>(l, maps + map_offset((uint32_t)env, ep + 1u), 0, W / 2, W / 2, reinterpret_cast<uint8_t*>(e + L_WB),
+                                    reinterpret_cast<uint8_t*>(e + L_WI));
                 }
 #pragma unroll
-                for (int it = 0; it < (FLOORS * MOBTAB_DWORDS + 63) / 64; ++it) {
-                    const int i = l + 64 * it;
+                for (int it = 0; it < (FLOORS * MOBTAB_DWORDS + GW - 1) / GW; ++it) {
+                    const int i = l + GW * it;
                     if (i < FLOORS * MOBTAB_DWORDS) genv[REC_DWORDS + i] = 0u;
                 }
                 clear_mob(m);
@@ -216,10 +245,13 @@ __global__ __launch_bounds__(BLOCK, 5) void kf_step(uint32_t* __restrict__ envs,
             }
         }
         if (write_back) {
-            genv[l] = e[L_REC + l];
+#pragma unroll
+            for (int it = 0; it < REC_IT; ++it) if (l + GW * it < REC_DWORDS) genv[l + GW * it] = e[L_REC + l + GW * it];
             if (l < MOBTAB_DWORDS) genv[REC_DWORDS + floor_now * MOBTAB_DWORDS + l] = l < NSLOT ? pack_regs(m) : 0u;
-            if (obs != nullptr)
-                render_env<F32>(l, e, o.wx0, o.wy0, m.alive, m.x, m.y, m.type, luts, obs + (size_t)env * (F32 ? STRIDE_F32 : STRIDE_U8));
+            if (obs != nullptr) {
+                aux.day = o.done ? day_fresh : day_next;
+                render_env<F32, GW>(l, e, o.wx0, o.wy0, m.alive, m.x, m.y, m.type, luts, obs + (size_t)env * (F32 ? STRIDE_F32 : STRIDE_U8), &aux);
+            }
         }
         if (queued && l == 0) la::commit_entry(ls, seq, step_block, list_at, make_uint4((uint32_t)env, lo, hi, ep + 2u));
     }
@@ -729,6 +761,7 @@ bool config_ok(const craftax_config* c, std::string* why)
     if (c->reset_mode > CRAFTAX_RESET_POOL) { *why = "unknown reset_mode"; return false; }
     if (c->worldgen > CRAFTAX_WORLDGEN_PERLIN) { *why = "unknown worldgen"; return false; }
     if (c->reserved != 0) { *why = "reserved must be 0"; return false; }
+    if (c->group_lanes != 0 && c->group_lanes != 16 && c->group_lanes != 64) { *why = "group_lanes must be 0, 16 or 64"; return false; }
     return true;
 }
 
@@ -746,7 +779,7 @@ static Header make_header(const craftax_config* c, int n)
     h.off_maps = h.off_envs + (uint64_t)n * (ENV_DWORDS * 4);
     h.off_tags = round_up(h.off_maps + (uint64_t)n * 2 * MAP_BYTES, 256);     // two map slots per environment
     h.off_regen0 = round_up(h.off_tags + (uint64_t)n * NTAG * 8, 256);
-    const uint64_t list_bytes = (uint64_t)NSUB * la::sub_list_capacity((uint64_t)n, ENVS_PER_BLOCK) * 16;
+    const uint64_t list_bytes = (uint64_t)NSUB * la::sub_list_capacity((uint64_t)n, MAX_ENVS_PER_STEP_BLOCK) * 16;
     h.off_regen1 = h.off_regen0 + list_bytes;
     h.off_slow = h.off_regen1 + list_bytes;
     h.total = round_up(h.off_slow + (uint64_t)n * 16, 256);
@@ -811,7 +844,7 @@ static Ptrs pointers(const void* state, const Header& h)
     q.ls.regen[1] = reinterpret_cast<uint4*>(base + h.off_regen1);
     q.ls.slow = reinterpret_cast<uint4*>(base + h.off_slow);
     q.ls.tags = reinterpret_cast<uint2*>(base + h.off_tags);
-    q.ls.sub_cap = (uint32_t)la::sub_list_capacity((uint64_t)h.n, ENVS_PER_BLOCK);
+    q.ls.sub_cap = (uint32_t)la::sub_list_capacity((uint64_t)h.n, MAX_ENVS_PER_STEP_BLOCK);
     q.ls.slow_cap = h.n;
     return q;
 }
@@ -905,11 +938,13 @@ int check_kernels(const craftax_config* cfg, std::string* err)
     const bool perlin = cfg->worldgen == CRAFTAX_WORLDGEN_PERLIN;
     bool ok = true;
     if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) {
-        ok = ok && (perlin ? fits("kf_step", (const void*)kf_step<true, true, true>, BLOCK) : fits("kf_step", (const void*)kf_step<true, true, false>, BLOCK));
+        ok = ok && (perlin ? fits("kf_step", (const void*)kf_step<true, true, true, 64>, BLOCK) : fits("kf_step", (const void*)kf_step<true, true, false, 64>, BLOCK));
+        ok = ok && (perlin ? fits("kf_step (16 lanes)", (const void*)kf_step<true, true, true, 16>, BLOCK) : fits("kf_step (16 lanes)", (const void*)kf_step<true, true, false, 16>, BLOCK));
         ok = ok && (perlin ? fits("kf_rollout", (const void*)kf_rollout<true, true>, BLOCK) : fits("kf_rollout", (const void*)kf_rollout<true, false>, BLOCK));
         ok = ok && fits("kf_reset_list", (const void*)kf_reset_list<true>, GEN_THREADS) && fits("kf_observe", (const void*)kf_observe<true>, BLOCK);
     } else {
-        ok = ok && (perlin ? fits("kf_step", (const void*)kf_step<false, true, true>, BLOCK) : fits("kf_step", (const void*)kf_step<false, true, false>, BLOCK));
+        ok = ok && (perlin ? fits("kf_step", (const void*)kf_step<false, true, true, 64>, BLOCK) : fits("kf_step", (const void*)kf_step<false, true, false, 64>, BLOCK));
+        ok = ok && (perlin ? fits("kf_step (16 lanes)", (const void*)kf_step<false, true, true, 16>, BLOCK) : fits("kf_step (16 lanes)", (const void*)kf_step<false, true, false, 16>, BLOCK));
         ok = ok && (perlin ? fits("kf_rollout", (const void*)kf_rollout<false, true>, BLOCK) : fits("kf_rollout", (const void*)kf_rollout<false, false>, BLOCK));
         ok = ok && fits("kf_reset_list", (const void*)kf_reset_list<false>, GEN_THREADS) && fits("kf_observe", (const void*)kf_observe<false>, BLOCK);
     }
@@ -924,14 +959,33 @@ int reset(void* state, const craftax_config* cfg, int n, const uint64_t* seeds, 
     return check_launch("craftax_reset", err);
 }
 
-// one launch of the step kernel: the instance for this spare-world policy and this noise
+// Lanes per environment of the step kernel.  A whole wavefront (the default at every batch size)
+// keeps the player's state and the 43-action code on the scalar unit, which works beside the vector
+// unit.  Sixteen lanes put four environments in a wavefront and fill 14 of 16 lanes with mob slots
+// instead of 14 of 64, but the player's code then runs on the vector unit, the kernel needs 210
+// vector registers (two wavefronts per SIMD instead of five), and a wavefront renders four
+// observations one after the other: measured slower at every size (22.5 against 18.8 us per step at
+// 4,096 environments, 243 against 207 us at 65,536).  It stays selectable (cfg->group_lanes = 16)
+// and is tested like the default.
+static int group_lanes(const craftax_config* cfg, int n)
+{
+    (void)n;
+    return cfg->group_lanes == 16 ? 16 : 64;
+}
+
+// one launch of the step kernel: the instance for this spare-world policy, this noise and this group width
 template <bool F32>
-static void launch_step(bool eager, bool perlin, dim3 grid, hipStream_t st, const Ptrs& q, const int32_t* actions, uint8_t* o, float* reward,
+static void launch_step(int gw, bool eager, bool perlin, dim3 grid, hipStream_t st, const Ptrs& q, const int32_t* actions, uint8_t* o, float* reward,
                         uint8_t* done, const Params& p, int rb)
 {
     auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls, p, rb); };
-    if (perlin) { if (eager) go(kf_step<F32, true, true>); else go(kf_step<F32, false, true>); }
-    else { if (eager) go(kf_step<F32, true, false>); else go(kf_step<F32, false, false>); }
+    if (gw == 16) {
+        if (perlin) { if (eager) go(kf_step<F32, true, true, 16>); else go(kf_step<F32, false, true, 16>); }
+        else { if (eager) go(kf_step<F32, true, false, 16>); else go(kf_step<F32, false, false, 16>); }
+    } else {
+        if (perlin) { if (eager) go(kf_step<F32, true, true, 64>); else go(kf_step<F32, false, true, 64>); }
+        else { if (eager) go(kf_step<F32, true, false, 64>); else go(kf_step<F32, false, false, 64>); }
+    }
 }
 
 int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, void* obs, float* reward, uint8_t* done,
@@ -941,7 +995,8 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
     const Params p = make_params(cfg, n);
     hipStream_t st = (hipStream_t)stream;
     uint8_t* o = static_cast<uint8_t*>(obs);
-    const int sb = (n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK;
+    const int gw = group_lanes(cfg, n), epb = BLOCK / gw;
+    const int sb = (n + epb - 1) / epb;
     const int rb = FLOORS * n < REGEN_BLOCKS ? FLOORS * n : REGEN_BLOCKS;    // persistent blocks serving a queue: any number works
     const dim3 grid((unsigned)(rb + sb)), rgrid((unsigned)(n < RESET_SLOTS ? n : RESET_SLOTS) * FLOORS);
     const int pool = cfg->reset_mode == CRAFTAX_RESET_POOL ? 1 : 0;
@@ -955,14 +1010,14 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
     const int perlin = cfg->worldgen == CRAFTAX_WORLDGEN_PERLIN ? 1 : 0;
     if (cfg->obs_mode == CRAFTAX_OBS_PIXELS_F32) {
         // the step runs without rendering; the picture is drawn from the state it leaves
-        launch_step<false>(eager, perlin != 0, grid, st, q, actions, nullptr, reward, done, p, rb);
+        launch_step<false>(gw, eager, perlin != 0, grid, st, q, actions, nullptr, reward, done, p, rb);
         if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, (uint8_t*)nullptr, q.ls, perlin, done, n, pool);
         if (o != nullptr) hipLaunchKernelGGL(kf_pixels, dim3((unsigned)n), dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, o);
     } else if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) {
-        launch_step<true>(eager, perlin != 0, grid, st, q, actions, o, reward, done, p, rb);
+        launch_step<true>(gw, eager, perlin != 0, grid, st, q, actions, o, reward, done, p, rb);
         if (slow) hipLaunchKernelGGL(kf_reset_list<true>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls, perlin, done, n, pool);
     } else {
-        launch_step<false>(eager, perlin != 0, grid, st, q, actions, o, reward, done, p, rb);
+        launch_step<false>(gw, eager, perlin != 0, grid, st, q, actions, o, reward, done, p, rb);
         if (slow) hipLaunchKernelGGL(kf_reset_list<false>, rgrid, dim3(GEN_THREADS), 0, st, q.envs, q.maps, q.luts, o, q.ls, perlin, done, n, pool);
     }
     return check_launch("craftax_step", err);
@@ -981,7 +1036,7 @@ int rollout(void* state, const craftax_config* cfg, int n, const int32_t* action
     const dim3 drain((unsigned)rb), grid((unsigned)((n + ENVS_PER_BLOCK - 1) / ENVS_PER_BLOCK));
     // a launch of regeneration blocks only empties the lists of the step kernel and completes every spare world
     const bool perlin = cfg->worldgen == CRAFTAX_WORLDGEN_PERLIN;
-    launch_step<false>(false, perlin, drain, st, q, nullptr, nullptr, nullptr, nullptr, p, rb);
+    launch_step<false>(64, false, perlin, drain, st, q, nullptr, nullptr, nullptr, nullptr, p, rb);
     auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, dim3(BLOCK), 0, st, q.envs, q.maps, q.luts, actions, o, reward, done, q.ls.tags, p, steps); };
     if (cfg->obs_mode == CRAFTAX_OBS_SYM_F32) { if (perlin) go(kf_rollout<true, true>); else go(kf_rollout<true, false>); }
     else { if (perlin) go(kf_rollout<false, true>); else go(kf_rollout<false, false>); }

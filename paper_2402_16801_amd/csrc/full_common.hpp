@@ -3,6 +3,8 @@
 // scalar registers), lane k < 14 owns mob slot k of the current floor, lane k < 10 plant k.
 #pragma once
 
+#include <cstddef>
+
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -84,9 +86,13 @@ constexpr uint32_t P_SAPLING = 429496730u, P_CHASE = 3435973836u, P_SHOOT = 0x80
                    P_SKELETON_SPAWN = 0x19999999u;
 
 // Creature table (appendix "Creatures"): health, damage physical/fire/ice, defence % physical/
-// fire/ice, collision type, achievement for defeating (eating) it.
-struct CreatureRow { int8_t hp, dp, df, di; int8_t Dp, Df, Di; int8_t col; int8_t ach; };
-__device__ __constant__ const CreatureRow CREATURE[32] = {
+// fire/ice, collision type, achievement for defeating (eating) it.  The rows are written out once,
+// here; the device reads them from 64-bit constants packed at compile time (creature(type) is a few
+// shifts), not from memory: a lookup in memory sat in the middle of every step's chain of
+// dependent round trips.
+struct CreatureRow { int hp, dp, df, di; int Dp, Df, Di; int col; int ach; };
+constexpr int N_CREATURE = 19;
+constexpr CreatureRow CREATURE_ROWS[N_CREATURE] = {
     { 5, 2, 0, 0, 0, 0, 0, COL_GROUND, H_DEFEAT_ZOMBIE },          { 3, 2, 0, 0, 0, 0, 0, COL_GROUND, H_DEFEAT_SKELETON },
     { 3, 0, 0, 0, 0, 0, 0, COL_GROUND, H_EAT_COW },                { 7, 3, 0, 0, 0, 0, 0, COL_GROUND, H_DEFEAT_ORC_SOLIDER },
     { 5, 3, 0, 0, 0, 0, 0, COL_GROUND, H_DEFEAT_ORC_MAGE },        { 6, 0, 0, 0, 0, 0, 0, COL_GROUND, H_EAT_SNAIL },
@@ -98,16 +104,93 @@ __device__ __constant__ const CreatureRow CREATURE[32] = {
     { 14, 3, 5, 0, 90, 100, 0, COL_FLYING, H_DEFEAT_FIRE_ELEMENTAL }, { 24, 4, 0, 5, 90, 0, 100, COL_GROUND, H_DEFEAT_FROST_TROLL },
     { 16, 4, 0, 4, 90, 0, 100, COL_FLYING, H_DEFEAT_ICE_ELEMENTAL },
 };
+// field f of a row: 0 hp, 1..3 damage, 4 physical defence as a code (0, 20, 50, 90 -> 0..3), 5 and 6 fire
+// and ice defence as a flag (0 or 100), 7 collision, 8 achievement
+constexpr int creature_field(const CreatureRow& r, int f)
+{
+    return f == 0 ? r.hp : f == 1 ? r.dp : f == 2 ? r.df : f == 3 ? r.di
+         : f == 4 ? (r.Dp == 0 ? 0 : r.Dp == 20 ? 1 : r.Dp == 50 ? 2 : 3) : f == 5 ? (r.Df != 0) : f == 6 ? (r.Di != 0) : f == 7 ? r.col : r.ach;
+}
+// `count` values of `bits` bits each, from row `first` on
+constexpr uint64_t pack_creatures(int f, int bits, int first, int count)
+{
+    uint64_t v = 0;
+    for (int i = 0; i < count && first + i < N_CREATURE; ++i) v |= (uint64_t)creature_field(CREATURE_ROWS[first + i], f) << (bits * i);
+    return v;
+}
+constexpr uint64_t CR_HP[2] = { pack_creatures(0, 5, 0, 12), pack_creatures(0, 5, 12, 12) };
+constexpr uint64_t CR_DP = pack_creatures(1, 3, 0, 19), CR_DF = pack_creatures(2, 3, 0, 19), CR_DI = pack_creatures(3, 3, 0, 19);
+constexpr uint64_t CR_DEFP = pack_creatures(4, 2, 0, 19), CR_DEFF = pack_creatures(5, 1, 0, 19), CR_DEFI = pack_creatures(6, 1, 0, 19);
+constexpr uint64_t CR_COL = pack_creatures(7, 2, 0, 19);
+constexpr uint64_t CR_ACH[3] = { pack_creatures(8, 7, 0, 9), pack_creatures(8, 7, 9, 9), pack_creatures(8, 7, 18, 9) };
+__host__ __device__ constexpr CreatureRow creature(int type)
+{
+    const int t = type < N_CREATURE ? type : N_CREATURE - 1;      // a mob word has five bits of type; rows end at 18
+    CreatureRow c{};
+    c.hp = (int)((t < 12 ? CR_HP[0] >> (5 * t) : CR_HP[1] >> (5 * (t - 12))) & 31u);
+    c.dp = (int)((CR_DP >> (3 * t)) & 7u); c.df = (int)((CR_DF >> (3 * t)) & 7u); c.di = (int)((CR_DI >> (3 * t)) & 7u);
+    c.Dp = (int)((0x5A321400u >> (8 * (int)((CR_DEFP >> (2 * t)) & 3u))) & 0xFFu);
+    c.Df = 100 * (int)((CR_DEFF >> t) & 1u); c.Di = 100 * (int)((CR_DEFI >> t) & 1u);
+    c.col = (int)((CR_COL >> (2 * t)) & 3u);
+    c.ach = (int)((t < 9 ? CR_ACH[0] >> (7 * t) : t < 18 ? CR_ACH[1] >> (7 * (t - 9)) : CR_ACH[2] >> (7 * (t - 18))) & 127u);
+    return c;
+}
+constexpr bool creature_table_round_trips()
+{
+    for (int t = 0; t < N_CREATURE; ++t) {
+        const CreatureRow a = CREATURE_ROWS[t], b = creature(t);
+        if (a.hp != b.hp || a.dp != b.dp || a.df != b.df || a.di != b.di || a.Dp != b.Dp || a.Df != b.Df || a.Di != b.Di || a.col != b.col || a.ach != b.ach)
+            return false;
+    }
+    return true;
+}
+static_assert(creature_table_round_trips(), "the packed creature table does not decode to its rows");
+
+// Small per-floor and per-type tables, packed the same way (five bits per entry, 31 = none).
+template <int N>
+constexpr uint64_t pack5(const int (&a)[N])
+{
+    uint64_t v = 0;
+    for (int i = 0; i < N; ++i) v |= (uint64_t)(a[i] < 0 ? 31 : a[i]) << (5 * i);
+    return v;
+}
+constexpr int unpack5(uint64_t packed, int i) { const int v = (int)((packed >> (5 * i)) & 31u); return v == 31 ? -1 : v; }
 // who lives on which floor (appendix "Creatures", column Floor); the boss floor calls them as waves
-__device__ __constant__ const int8_t MELEE_OF_FLOOR[8] = { C_ZOMBIE, C_ORC_SOLDIER, C_GNOME_WARRIOR, C_LIZARD, C_KNIGHT, C_TROLL, C_PIGMAN, C_FROST_TROLL };
-__device__ __constant__ const int8_t RANGED_OF_FLOOR[8] = { C_SKELETON, C_ORC_MAGE, C_GNOME_ARCHER, C_KOBOLD, C_ARCHER, C_DEEP_THING, C_FIRE_ELEMENTAL, C_ICE_ELEMENTAL };
-__device__ __constant__ const int8_t PASSIVE_OF_FLOOR[8] = { C_COW, C_SNAIL, C_BAT, C_SNAIL, C_SNAIL, C_BAT, C_BAT, -1 };
-__device__ __constant__ const int8_t ENTER_ACH[FLOORS] = { -1, H_ENTER_DUNGEON, H_ENTER_GNOMISH_MINES, H_ENTER_SEWERS, H_ENTER_VAULT,
-                                                          H_ENTER_TROLL_MINES, H_ENTER_FIRE_REALM, H_ENTER_ICE_REALM, H_ENTER_GRAVEYARD };
+constexpr int MELEE_ROWS[8] = { C_ZOMBIE, C_ORC_SOLDIER, C_GNOME_WARRIOR, C_LIZARD, C_KNIGHT, C_TROLL, C_PIGMAN, C_FROST_TROLL };
+constexpr int RANGED_ROWS[8] = { C_SKELETON, C_ORC_MAGE, C_GNOME_ARCHER, C_KOBOLD, C_ARCHER, C_DEEP_THING, C_FIRE_ELEMENTAL, C_ICE_ELEMENTAL };
+constexpr int PASSIVE_ROWS[8] = { C_COW, C_SNAIL, C_BAT, C_SNAIL, C_SNAIL, C_BAT, C_BAT, -1 };
+__host__ __device__ constexpr int melee_of_floor(int f) { return unpack5(pack5(MELEE_ROWS), f); }
+__host__ __device__ constexpr int ranged_of_floor(int f) { return unpack5(pack5(RANGED_ROWS), f); }
+__host__ __device__ constexpr int passive_of_floor(int f) { return unpack5(pack5(PASSIVE_ROWS), f); }
+static_assert(melee_of_floor(3) == C_LIZARD && ranged_of_floor(7) == C_ICE_ELEMENTAL && passive_of_floor(7) == -1 && passive_of_floor(2) == C_BAT, "floor tables");
+// achievement for entering floor f (seven bits per entry, 127 = none)
+constexpr int ENTER_ROWS[FLOORS] = { -1, H_ENTER_DUNGEON, H_ENTER_GNOMISH_MINES, H_ENTER_SEWERS, H_ENTER_VAULT,
+                                     H_ENTER_TROLL_MINES, H_ENTER_FIRE_REALM, H_ENTER_ICE_REALM, H_ENTER_GRAVEYARD };
+constexpr uint64_t pack_enter()
+{
+    uint64_t v = 0;
+    for (int i = 0; i < FLOORS; ++i) v |= (uint64_t)(ENTER_ROWS[i] < 0 ? 127 : ENTER_ROWS[i]) << (7 * i);
+    return v;
+}
+__host__ __device__ constexpr int enter_ach(int f) { const int v = (int)((pack_enter() >> (7 * f)) & 127u); return v == 127 ? -1 : v; }
+static_assert(enter_ach(0) == -1 && enter_ach(8) == H_ENTER_GRAVEYARD && enter_ach(4) == H_ENTER_VAULT, "floor achievements");
 // Observation channel (42..81) of a creature by slot class: 8 type slots per class, classes in
-// the order melee, passive, ranged, mob projectile, player projectile.
-__device__ __constant__ const int8_t MELEE_TYPE_SLOT[32] = { 0, 0, 0, 1, 0, 0, 2, 0, 0, 3, 0, 4, 0, 5, 0, 6, 0, 7 };
-__device__ __constant__ const int8_t RANGED_TYPE_SLOT[32] = { 0, 0, 0, 0, 1, 0, 0, 2, 0, 0, 3, 0, 4, 0, 5, 0, 6, 0, 7 };
+// the order melee, passive, ranged, mob projectile, player projectile.  The type slot of a melee or
+// ranged creature is the floor it lives on.
+constexpr int type_slot_of(const int (&rows)[8], int type)
+{
+    for (int f = 0; f < 8; ++f) if (rows[f] == type) return f;
+    return 0;
+}
+constexpr uint64_t pack_type_slots(const int (&rows)[8])
+{
+    uint64_t v = 0;
+    for (int t = 0; t < N_CREATURE; ++t) v |= (uint64_t)type_slot_of(rows, t) << (3 * t);
+    return v;
+}
+__host__ __device__ constexpr int melee_type_slot(int type) { return (int)((pack_type_slots(MELEE_ROWS) >> (3 * (type < N_CREATURE ? type : 0))) & 7u); }
+__host__ __device__ constexpr int ranged_type_slot(int type) { return (int)((pack_type_slots(RANGED_ROWS) >> (3 * (type < N_CREATURE ? type : 0))) & 7u); }
+static_assert(melee_type_slot(C_KNIGHT) == 4 && melee_type_slot(C_FROST_TROLL) == 7 && ranged_type_slot(C_ORC_MAGE) == 1 && ranged_type_slot(C_SKELETON) == 0, "type slots");
 
 __device__ inline bool lit_floor(int f) { return (0x05Bu >> f) & 1u; }    // floors 0, 1, 3, 4, 6; dark: 2, 5, 7, 8
 
@@ -189,6 +272,8 @@ struct Luts {
     uint16_t mask[46][10];
     uint32_t perlin_cs[1024];       // unit gradient of direction a: cos (low half) and sin (high half) in Q14, as int16
 };
+static_assert(offsetof(Luts, tenth) == offsetof(Luts, sqrt10) + 400 && offsetof(Luts, light20) == offsetof(Luts, tenth) + 128,
+              "sqrt10, tenth and light20 are copied to LDS as one run of floats");
 constexpr int AT_ITEM = 37, AT_CRE = 42, AT_PLAYER = 82, AT_ICON = 83, AT_TILES = 127;
 constexpr int MASK_CRE = 5, MASK_PLAYER = 45;
 
@@ -240,5 +325,33 @@ __device__ inline void wave_sync()
 __device__ inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ inline uint32_t uniu(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
 __device__ inline int lane_get(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+
+// An environment is stepped by GW consecutive lanes of a wavefront: the whole wavefront (GW = 64:
+// the player's state lives in scalar registers and the 43-action code runs on the scalar unit), or
+// a group of 16 lanes, four environments per wavefront (GW = 16: the player's state is a vector
+// register per value, equal in the lanes of a group; the action code runs once per wavefront for
+// four environments, and the 14 mob slots fill 14 of 16 lanes instead of 14 of 64).  The step and
+// the renderer are written once against these primitives; `lane` below is a lane of the group.
+template <int GW> struct Lanes;
+template <> struct Lanes<64> {
+    __device__ static inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+    __device__ static inline uint32_t uniu(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+    __device__ static inline int get(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+    __device__ static inline uint32_t ballot(bool pred) { return (uint32_t)__ballot(pred); }      // bit i = lane i, i < 32
+};
+template <> struct Lanes<16> {
+    __device__ static inline int uni(int v) { return v; }
+    __device__ static inline uint32_t uniu(uint32_t v) { return v; }
+    // value of lane `lane` of the calling lane's group (every lane of the group must be active)
+    __device__ static inline int get(int v, int lane) { return __shfl(v, (int)(threadIdx.x & 48u) | lane, 64); }
+    // bit i = predicate of lane i of the calling lane's group
+    __device__ static inline uint32_t ballot(bool pred)
+    {
+        const uint64_t m = __ballot(pred);
+        const uint32_t lane = threadIdx.x & 63u;
+        const uint32_t half = (lane & 32u) ? (uint32_t)(m >> 32) : (uint32_t)m;
+        return __builtin_amdgcn_ubfe(half, lane & 16u, 16u);
+    }
+};
 
 }  // namespace cf

@@ -60,14 +60,51 @@ __device__ __forceinline__ float scalar_value(int i, const uint32_t* rec, const 
     return (f == 0 || kills >= KILLS_TO_CLEAR) ? 1.0f : 0.0f;
 }
 
+// What the step kernels fetch ahead of the renderer, so that it waits for no table in memory: the
+// specification of the scalars this lane writes (scalar l, l + GW, ...), the small conversion tables
+// (sqrt10, tenth, light20, as they lie in Luts) copied to LDS, and the daylight value of the
+// observation's phase.
+constexpr int LUT_FLOATS = 100 + 32 + 32;
+template <int GW>
+struct RenderAux {
+    uint32_t spec[(NVEC + 1 + GW - 1) / GW];    // ScalarSpec of scalar l + GW * it, as four bytes
+    const float* lut;                           // LDS: sqrt10[100], tenth[32], light20[32]
+    float day;                                  // daylight[phase of the rendered state]
+};
+template <int GW>
+__device__ __forceinline__ void fetch_scalar_specs(int l, RenderAux<GW>& aux)
+{
+#pragma unroll
+    for (int it = 0; it < (NVEC + 1 + GW - 1) / GW; ++it) {
+        const int i = l + GW * it;
+        aux.spec[it] = i < NVEC ? *reinterpret_cast<const uint32_t*>(&SCALARS[i]) : 0u;
+    }
+}
+static_assert(sizeof(ScalarSpec) == 4, "a scalar specification travels as one dword");
+__device__ __forceinline__ float scalar_value_fast(int i, uint32_t spec, const uint32_t* rec, const float* lut, float day)
+{
+    const uint32_t word = spec & 0xFFu, shift = (spec >> 8) & 0xFFu, mask = (spec >> 16) & 0xFFu, conv = spec >> 24;
+    const uint32_t raw = (rec[word] >> shift) & mask;
+    if (conv == CV_SQRT10) return lut[min(raw, 99u)];
+    if (conv == CV_TENTH) return lut[100 + min(raw, 31u)];
+    if (conv == CV_HALF) return (float)raw * 0.5f;
+    if (conv == CV_QUARTER) return (float)raw * 0.25f;
+    if (conv == CV_RAW) return (float)raw;
+    if (i >= 39 && i < 43) return (int)raw == i - 38 ? 1.0f : 0.0f;
+    if (i == 43) return day;
+    const int f = (int)raw;
+    const int kills = (int)((rec[R_KILLS + (f >> 2)] >> (8 * (f & 3))) & 0xFFu);
+    return (f == 0 || kills >= KILLS_TO_CLEAR) ? 1.0f : 0.0f;
+}
+
 // Observation channel of the creature in slot k (class by slot range, type slot by creature).
 __device__ inline int creature_channel(int k, int type)
 {
-    if (k < S_RANGED0) return 42 + MELEE_TYPE_SLOT[type];
-    if (k < S_PASSIVE0) return 42 + 16 + RANGED_TYPE_SLOT[type];
+    if (k < S_RANGED0) return 42 + melee_type_slot(type);
+    if (k < S_PASSIVE0) return 42 + 16 + ranged_type_slot(type);
     if (k < S_MPROJ0) return 42 + 8 + (type == C_COW ? 0 : (type == C_SNAIL ? 1 : 2));
     if (k < S_PPROJ0) {
-        const CreatureRow c = CREATURE[type];
+        const CreatureRow c = creature(type);
         return 42 + 24 + (c.df > 0 ? (c.di > 0 ? 3 : 1) : (c.di > 0 ? 2 : 0));
     }
     return 42 + 32 + type;
@@ -82,10 +119,13 @@ __device__ inline uint32_t spread4(uint32_t nibble) { return (nibble * 0x0020408
 // The one-hot bytes are staged as single bits (a few LDS atomics per cell) next to a light level
 // per cell; every lane then expands 16 bits at a time into one 16-byte piece of the output, so
 // that a wavefront writes whole cache lines.
-template <bool F32>
+// GW: lanes that render this environment (see Lanes); l: the calling lane's number among them.
+template <bool F32, int GW = 64>
 __device__ __forceinline__ void render_env(const int l, uint32_t* e, const int wx0, const int wy0, const int m_alive, const int m_x,
-                                  const int m_y, const int m_type, const Luts* __restrict__ luts, uint8_t* __restrict__ out)
+                                  const int m_y, const int m_type, const Luts* __restrict__ luts, uint8_t* __restrict__ out,
+                                  const RenderAux<GW>* aux = nullptr)
 {
+    using G = Lanes<GW>;
     const uint32_t* rec = e + L_REC;
     const uint8_t* wb = reinterpret_cast<const uint8_t*>(e + L_WB);
     const uint8_t* wi = reinterpret_cast<const uint8_t*>(e + L_WI);
@@ -93,27 +133,34 @@ __device__ __forceinline__ void render_env(const int l, uint32_t* e, const int w
     uint32_t* bits = e + L_BITS;
     uint8_t* light = reinterpret_cast<uint8_t*>(e + L_LIGHT);
     float* vec = reinterpret_cast<float*>(e + L_VEC);
-    const uint32_t pos = uniu(rec[R_POS]);
+    const uint32_t pos = G::uniu(rec[R_POS]);
     const int px = pos & 0xFF, py = (pos >> 8) & 0xFF;
 #pragma unroll
-    for (int it = 0; it < 5; ++it) {
-        const int i = l + 64 * it;
+    for (int it = 0; it < (260 + GW - 1) / GW; ++it) {
+        const int i = l + GW * it;
         if (i < 260) bits[i] = 0u;
     }
-    cre[l] = 0xFFFFFFFFu;
-    if (l + 64 < NCELL + 1) cre[l + 64] = 0xFFFFFFFFu;
+#pragma unroll
+    for (int it = 0; it < (NCELL + 1 + GW - 1) / GW; ++it) {
+        const int i = l + GW * it;
+        if (i < NCELL + 1) cre[i] = 0xFFFFFFFFu;
+    }
     wave_sync();
     if (l < NSLOT && m_alive) {
         const int vr = m_y - (py - VROWS / 2), vc = m_x - (px - VCOLS / 2);
         if ((unsigned)vr < (unsigned)VROWS && (unsigned)vc < (unsigned)VCOLS)
             atomicMin(&cre[vr * VCOLS + vc], ((uint32_t)l << 8) | (uint32_t)creature_channel(l, m_type));   // lowest slot wins
     }
-    if (l < NVEC + 1) vec[l] = l < NVEC ? scalar_value(l, rec, luts) : 0.0f;
+#pragma unroll
+    for (int it = 0; it < (NVEC + 1 + GW - 1) / GW; ++it) {
+        const int i = l + GW * it;
+        if (i < NVEC + 1) vec[i] = i >= NVEC ? 0.0f : (aux != nullptr ? scalar_value_fast(i, aux->spec[it], rec, aux->lut, aux->day) : scalar_value(i, rec, luts));
+    }
     wave_sync();
     auto set_bit = [&](int i) { atomicOr(&bits[CX_IDX(i >> 5, 260)], 1u << (i & 31)); };
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-        const int cell = l + 64 * it;
+    for (int it = 0; it < (NCELL + GW - 1) / GW; ++it) {
+        const int cell = l + GW * it;
         if (cell < NCELL) {
             const int r = cell / VCOLS, c = cell - r * VCOLS;
             const int x = px - VCOLS / 2 + c, y = py - VROWS / 2 + r;
@@ -144,10 +191,11 @@ __device__ __forceinline__ void render_env(const int l, uint32_t* e, const int w
         }
     };
     if (!F32) {
+        constexpr int PIECE_UNROLL = GW == 64 ? 9 : 3;
         uint4* dst = reinterpret_cast<uint4*>(out);
-#pragma unroll
-        for (int it = 0; it < 9; ++it) {
-            const int j = l + 64 * it;
+#pragma unroll PIECE_UNROLL
+        for (int it = 0; it < (STRIDE_U8 / 16 + GW - 1) / GW; ++it) {
+            const int j = l + GW * it;
             if (j < STRIDE_U8 / 16) {
                 uint32_t v[4] = { 0u, 0u, 0u, 0u };
                 if (j < VEC_OFFSET / 16) {
@@ -170,11 +218,11 @@ __device__ __forceinline__ void render_env(const int l, uint32_t* e, const int w
     } else {
         float4* dst = reinterpret_cast<float4*>(out);
 #pragma unroll 1
-        for (int j = l; j < STRIDE_F32 / 64; j += 64) {   // 16 floats per piece
+        for (int j = l; j < STRIDE_F32 / 64; j += GW) {   // 16 floats per piece
             const uint32_t b16 = j < 520 ? (bits[j >> 1] >> ((j & 1) * 16)) & 0xFFFFu : 0u;
             int at, lv;
             light_in_piece(j, &at, &lv);
-            const float lf = luts->light20[lv];
+            const float lf = aux != nullptr ? aux->lut[132 + lv] : luts->light20[lv];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 float v[4];

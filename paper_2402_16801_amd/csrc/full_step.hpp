@@ -33,31 +33,33 @@ struct Player {
 
 __device__ inline int sext8(uint32_t v) { return (int)(int8_t)(v & 0xFFu); }
 
+template <int GW = 64>
 __device__ __forceinline__ void unpack_player(const uint32_t* rec, Player& P)
 {
-    const uint32_t r0 = uniu(rec[R_POS]), r1 = uniu(rec[R_FLAGS]), r2 = uniu(rec[R_ATTR]);
+    using G = Lanes<GW>;
+    const uint32_t r0 = G::uniu(rec[R_POS]), r1 = G::uniu(rec[R_FLAGS]), r2 = G::uniu(rec[R_ATTR]);
     P.px = r0 & 0xFF; P.py = (r0 >> 8) & 0xFF; P.dir = (r0 >> 16) & 0xFF; P.floor = (r0 >> 24) & 0xF;
     P.sleeping = r1 & 1; P.resting = (r1 >> 1) & 1; P.fireball = (r1 >> 2) & 1; P.iceball = (r1 >> 3) & 1;
     P.book = (r1 >> 4) & 3; P.pickaxe = (r1 >> 6) & 7; P.sword = (r1 >> 9) & 7; P.sword_ench = (r1 >> 12) & 3;
     P.bow = (r1 >> 14) & 1; P.bow_ench = (r1 >> 15) & 3; P.boss_vulnerable = (r1 >> 17) & 1; P.boss_hits = (r1 >> 18) & 15;
     P.armour = r2 & 0xFF; P.armour_ench = (r2 >> 8) & 0xFF;
     P.xp = (r2 >> 16) & 15; P.dex = (r2 >> 20) & 7; P.str = (r2 >> 23) & 7; P.intel = (r2 >> 26) & 7;
-    const uint32_t i0 = uniu(rec[R_INV]), i1 = uniu(rec[R_INV + 1]), i2 = uniu(rec[R_INV + 2]), i3 = uniu(rec[R_POT]);
+    const uint32_t i0 = G::uniu(rec[R_INV]), i1 = G::uniu(rec[R_INV + 1]), i2 = G::uniu(rec[R_INV + 2]), i3 = G::uniu(rec[R_POT]);
 #pragma unroll
     for (int i = 0; i < 4; ++i) { P.inv[i] = (i0 >> (8 * i)) & 0xFF; P.inv[4 + i] = (i1 >> (8 * i)) & 0xFF; }
     P.inv[8] = i2 & 0xFF; P.inv[9] = (i2 >> 8) & 0xFF;
     P.potion = (uint64_t)(i2 >> 16) | ((uint64_t)i3 << 16);
-    const uint32_t v0 = uniu(rec[R_VIT]), v1 = uniu(rec[R_MANA]), c0 = uniu(rec[R_CNT]);
+    const uint32_t v0 = G::uniu(rec[R_VIT]), v1 = G::uniu(rec[R_MANA]), c0 = G::uniu(rec[R_CNT]);
 #pragma unroll
     for (int i = 0; i < 4; ++i) { P.vit[i] = (v0 >> (8 * i)) & 0xFF; P.cnt[i] = sext8(c0 >> (8 * i)); }
     P.vit[V_MANA] = v1 & 0xFF; P.cnt[K_MANA] = sext8(v1 >> 8); P.phase = (int)(v1 >> 16);
-    const uint32_t pm = uniu(rec[R_PERM]);
+    const uint32_t pm = G::uniu(rec[R_PERM]);
     P.perm = pm & 0x3FFFFu; P.visited = (pm >> 18) & 0x1FF;
-    P.kills07 = (uint64_t)uniu(rec[R_KILLS]) | ((uint64_t)uniu(rec[R_KILLS + 1]) << 32);
-    P.kills8 = uniu(rec[R_KILLS + 2]) & 0xFF;
+    P.kills07 = (uint64_t)G::uniu(rec[R_KILLS]) | ((uint64_t)G::uniu(rec[R_KILLS + 1]) << 32);
+    P.kills8 = G::uniu(rec[R_KILLS + 2]) & 0xFF;
 #pragma unroll
-    for (int i = 0; i < 3; ++i) P.ach[i] = uniu(rec[R_ACH + i]);
-    P.t = uniu(rec[R_T]); P.episode = uniu(rec[R_EPISODE]);
+    for (int i = 0; i < 3; ++i) P.ach[i] = G::uniu(rec[R_ACH + i]);
+    P.t = G::uniu(rec[R_T]); P.episode = G::uniu(rec[R_EPISODE]);
 }
 
 // packs everything that can change back into the LDS copy of the record (one lane writes)
@@ -101,11 +103,12 @@ __device__ inline int through(int ap, int af, int ai, int dp, int df, int di)
 }
 
 // Loads the 11 x 13 window of floor f centred on (cx, cy) into LDS (both maps).
+template <int GW = 64>
 __device__ __forceinline__ void load_window(int l, const uint8_t* __restrict__ maps, int f, int cx_, int cy_, uint8_t* wb, uint8_t* wi)
 {
 #pragma unroll
-    for (int it = 0; it < 3; ++it) {
-        const int i = l + 64 * it;
+    for (int it = 0; it < (WIN_ROWS * WIN_COLS + GW - 1) / GW; ++it) {
+        const int i = l + GW * it;
         if (i < WIN_ROWS * WIN_COLS) {
             const int r = i / WIN_COLS, c = i - r * WIN_COLS;
             const int x = cx_ - WIN_COLS / 2 + c, y = cy_ - WIN_ROWS / 2 + r;
@@ -128,22 +131,25 @@ enum Intent : int { N_NONE = 0, N_DAMAGE, N_DAMAGE_DIE, N_DIE, N_MOVE, N_SHOOT, 
 // HBM.  maps: its floors.  m, qw: this lane's mob slot (current floor) and plant word.
 // after_load: called once the loads of the current window have been issued and stored, before the
 // wave waits for them (the caller parks data it fetched earlier there).
-template <typename AfterLoad>
+template <int GW = 64, typename AfterLoad>
 __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uint32_t* e, uint32_t* __restrict__ genv,
                                    uint8_t* __restrict__ maps, const Luts* __restrict__ luts, const int action_in,
                                    const Params& p, MobRegs& m, uint32_t& qw, Player& P, AfterLoad&& after_load)
 {
+    using G = Lanes<GW>;
     uint32_t* rec = e + L_REC;
     uint8_t* wb = reinterpret_cast<uint8_t*>(e + L_WB);
     uint8_t* wi = reinterpret_cast<uint8_t*>(e + L_WI);
-    unpack_player(rec, P);
-    const uint32_t seed_lo = uniu(rec[R_SEED_LO]), seed_hi = uniu(rec[R_SEED_HI]);
+    unpack_player<GW>(rec, P);
+    // asked for now, needed in the spawn phase: by then it has long arrived
+    const uint32_t zombie_thr = luts->zombie_thr[P.phase];
+    const uint32_t seed_lo = G::uniu(rec[R_SEED_LO]), seed_hi = G::uniu(rec[R_SEED_HI]);
 
     // this step's draws: lane k computes Philox block k = (move k, decision k, plant-eaten k, misc k)
     const U4 rnd = philox4x32_10(env, P.t, P.episode, (cx::DOM_STEP << 16) | (uint32_t)(l < NSLOT ? l : 0), seed_lo, seed_hi);
     uint32_t misc[12];
 #pragma unroll
-    for (int i = 0; i < 12; ++i) misc[i] = (uint32_t)lane_get((int)rnd.w[3], i);
+    for (int i = 0; i < 12; ++i) misc[i] = (uint32_t)G::get((int)rnd.w[3], i);
 
     // mob table of the current floor and the window around the player
     {
@@ -157,14 +163,14 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
     int q_block = B_INVALID;
     if (q_alive) q_block = maps[block_off(0, q_x, q_y)];
     int wx0 = P.px - WIN_COLS / 2, wy0 = P.py - WIN_ROWS / 2;
-    load_window(l, maps, P.floor, P.px, P.py, wb, wi);
+    load_window<GW>(l, maps, P.floor, P.px, P.py, wb, wi);
     after_load();
     wave_sync();
 
-    auto win_b = [&](int x, int y) { return uni((int)wb[CX_IDX((y - wy0) * WIN_PITCH + (x - wx0), WIN_ROWS * WIN_PITCH)]); };
-    auto win_i = [&](int x, int y) { return uni((int)wi[CX_IDX((y - wy0) * WIN_PITCH + (x - wx0), WIN_ROWS * WIN_PITCH)]); };
+    auto win_b = [&](int x, int y) { return G::uni((int)wb[CX_IDX((y - wy0) * WIN_PITCH + (x - wx0), WIN_ROWS * WIN_PITCH)]); };
+    auto win_i = [&](int x, int y) { return G::uni((int)wi[CX_IDX((y - wy0) * WIN_PITCH + (x - wx0), WIN_ROWS * WIN_PITCH)]); };
     auto in_win = [&](int x, int y) { return (unsigned)(x - wx0) < (unsigned)WIN_COLS && (unsigned)(y - wy0) < (unsigned)WIN_ROWS; };
-    auto occ_mask = [&](int x, int y) -> uint32_t { return (uint32_t)__ballot(m.alive && m.x == x && m.y == y); };
+    auto occ_mask = [&](int x, int y) -> uint32_t { return (uint32_t)G::ballot(m.alive && m.x == x && m.y == y); };
     // the one block cell the player may change this step; mobs read their terrain from HBM and
     // take this cell from here instead
     int patch_f = -1, patch_x = -1, patch_y = -1, patch_b = 0;
@@ -185,8 +191,8 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
     // the player hurts mob slot k; returns true when it died
     auto hurt_mob = [&](int k, int ap, int af, int ai) -> bool {
         if (k >= S_MPROJ0) return false;                       // projectiles cannot be hit
-        const int type = lane_get(m.type, k), hp = lane_get(m.hp, k);
-        const CreatureRow c = CREATURE[type];
+        const int type = G::get(m.type, k), hp = G::get(m.hp, k);
+        const CreatureRow c = creature(type);
         const int nhp = hp - through(ap, af, ai, c.Dp, c.Df, c.Di);
         if (nhp > 0) { if (l == k) m.hp = nhp; return false; }
         if (l == k) clear_mob(m);
@@ -202,13 +208,13 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
             }
             // the way down opens once enough enemies of this floor are gone
             if (f >= 1 && f < FLOORS - 1 && kf >= KILLS_TO_CLEAR) {
-                const uint32_t lw = uniu(rec[R_LADDER + f]);
+                const uint32_t lw = G::uniu(rec[R_LADDER + f]);
                 const int lx = (lw >> 16) & 0xFF, ly = (lw >> 24) & 0xFF;
                 int il;
                 if (in_win(lx, ly)) il = win_i(lx, ly);
                 else {
                     __threadfence();                           // a torch placed this step may have lit that cell
-                    il = uni((int)__hip_atomic_load(maps + il_off(f, lx, ly), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                    il = G::uni((int)__hip_atomic_load(maps + il_off(f, lx, ly), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
                 }
                 if ((il & 7) == IT_LADDER_DOWN_BLOCKED) {
                     const int nil = (il & ~7) | IT_LADDER_DOWN;
@@ -240,8 +246,8 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
     {
         int b = B_INVALID;
         if (l < 9) b = wb[CX_IDX((P.py - wy0 - 1 + l / 3) * WIN_PITCH + (P.px - wx0 - 1 + l % 3), WIN_ROWS * WIN_PITCH)];
-        near_table = __ballot(b == B_TABLE) != 0;
-        near_furnace = __ballot(b == B_FURNACE) != 0;
+        near_table = G::ballot(b == B_TABLE) != 0;
+        near_furnace = G::ballot(b == B_FURNACE) != 0;
     }
     auto try_craft = [&](bool need_furnace, int wood, int stone, int coal, int iron, int diamond) -> bool {
         if (!near_table || (need_furnace && !near_furnace)) return false;
@@ -252,7 +258,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
     auto change_floor = [&](int nf, int x, int y) {
         const uint32_t nw = l < NSLOT ? genv[REC_DWORDS + nf * MOBTAB_DWORDS + l] : 0u;
         const Mob u = unpack_mob(nw);
-        if (__ballot(u.alive && u.x == x && u.y == y)) return;           // the far end of the ladder must be free
+        if (G::ballot(u.alive && u.x == x && u.y == y)) return;           // the far end of the ladder must be free
         if (l < NSLOT) {
             Mob o; o.alive = m.alive; o.x = m.x; o.y = m.y; o.dir = m.dir; o.hp = m.hp; o.cd = m.cd; o.type = m.type;
             genv[REC_DWORDS + P.floor * MOBTAB_DWORDS + l] = pack_mob(o);
@@ -262,12 +268,12 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
         if (!((P.visited >> nf) & 1)) {
             P.visited |= 1 << nf;
             if (P.xp < 15) ++P.xp;                                       // section "Attributes": a point per new floor
-            const int ea = ENTER_ACH[nf];
+            const int ea = enter_ach(nf);
             if (ea >= 0) unlock(P, ea);
         }
         wave_sync();
         wx0 = x - WIN_COLS / 2; wy0 = y - WIN_ROWS / 2;
-        load_window(l, maps, nf, x, y, wb, wi);
+        load_window<GW>(l, maps, nf, x, y, wb, wi);
         wave_sync();
     };
     // a projectile of the player leaves the facing cell
@@ -282,7 +288,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
             hurt_mob(k, ap, af, ai);
             return true;
         }
-        const uint32_t free_slots = ~(uint32_t)__ballot(m.alive) & (7u << S_PPROJ0);
+        const uint32_t free_slots = ~(uint32_t)G::ballot(m.alive) & (7u << S_PPROJ0);
         if (!free_slots || !in_set(FLYABLE, win_b(tx, ty))) return false;
         spawn_mob(__builtin_ctz(free_slots), tx, ty, P.dir, kind, 0);
         return true;
@@ -357,13 +363,13 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
                 if (P.boss_hits >= BOSS_HITS) { unlock(P, H_DEFEAT_NECROMANCER); set_facing_block(tx, ty, B_PATH); break; }
                 set_facing_block(tx, ty, B_NECROMANCER);
                 const int wv = P.boss_hits - 1;
-                const int mt = MELEE_OF_FLOOR[wv], rt = RANGED_OF_FLOOR[wv];
+                const int mt = melee_of_floor(wv), rt = ranged_of_floor(wv);
 #pragma unroll
                 for (int s = 0; s < 5; ++s) {
                     const int x = s < 3 ? 20 + 4 * s : 22 + 4 * (s - 3), y = s < 3 ? 10 : 8;
                     const int type = s < 3 ? mt : rt;
                     const bool taken = occ_mask(x, y) != 0 || (P.px == x && P.py == y);
-                    if (!lane_get(m.alive, s) && !taken) spawn_mob(s, x, y, 0, type, CREATURE[type].hp);
+                    if (!G::get(m.alive, s) && !taken) spawn_mob(s, x, y, 0, type, creature(type).hp);
                 }
                 break;
             }
@@ -390,7 +396,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
             } else if (a == A_PLACE_PLANT) {
                 if (f != 0 || P.inv[I_SAPLING] < 1 || b != B_GRASS) break;
                 const uint32_t cap = min(p.cap_plant, (uint32_t)NPLANT);
-                const uint32_t free_slots = ~(uint32_t)__ballot(q_alive != 0) & ((1u << cap) - 1u);
+                const uint32_t free_slots = ~(uint32_t)G::ballot(q_alive != 0) & ((1u << cap) - 1u);
                 if (!free_slots) break;
                 const int s = __builtin_ctz(free_slots);
                 --P.inv[I_SAPLING]; set_facing_block(tx, ty, B_PLANT);
@@ -403,8 +409,8 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
                 wave_sync();
                 // light falls off by 4 per cell of Chebyshev distance; the centre cell also carries the item
 #pragma unroll
-                for (int it = 0; it < 2; ++it) {
-                    const int i = l + 64 * it;
+                for (int it = 0; it < (81 + GW - 1) / GW; ++it) {
+                    const int i = l + GW * it;
                     if (i < 81) {
                         const int ddy = i / 9 - 4, ddx = i % 9 - 4, x = tx + ddx, y = ty + ddy;
                         if (inb(x, y) && in_win(x, y)) {
@@ -452,13 +458,13 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
         case A_CAST_ICEBALL: if (P.iceball && P.vit[V_MANA] >= 2 && shoot(PP_ICEBALL, tx, ty, t_ok)) { P.vit[V_MANA] -= 2; unlock(P, H_CAST_ICEBALL); } break;
         case A_DESCEND:
             if (f < FLOORS - 1 && (win_i(P.px, P.py) & 7) == IT_LADDER_DOWN) {
-                const uint32_t lw = uniu(rec[R_LADDER + f + 1]);
+                const uint32_t lw = G::uniu(rec[R_LADDER + f + 1]);
                 change_floor(f + 1, lw & 0xFF, (lw >> 8) & 0xFF);
             }
             break;
         case A_ASCEND:
             if (f > 0 && (win_i(P.px, P.py) & 7) == IT_LADDER_UP) {
-                const uint32_t lw = uniu(rec[R_LADDER + f - 1]);
+                const uint32_t lw = G::uniu(rec[R_LADDER + f - 1]);
                 change_floor(f - 1, (lw >> 16) & 0xFF, (lw >> 24) & 0xFF);
             }
             break;
@@ -532,7 +538,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
             const uint32_t m8 = choice(rnd.w[0], 8);
             const int wander = m8 < 4 ? (int)m8 + 1 : 0;
             if (l < S_MPROJ0) {
-                const CreatureRow c = CREATURE[m.type];
+                const CreatureRow c = creature(m.type);
                 dmg = idle_factor * through(c.dp, c.df, c.di, pdp, pdf, pdi);
                 col = c.col;
                 if (l < S_RANGED0) {
@@ -553,7 +559,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
             } else {
                 tdir = m.dir;
                 if (l < S_PPROJ0) {
-                    const CreatureRow c = CREATURE[m.type];
+                    const CreatureRow c = creature(m.type);
                     dmg = idle_factor * through(c.dp, c.df, c.di, pdp, pdf, pdi);
                     kind = N_FLY;
                 } else kind = N_PPROJ;
@@ -592,13 +598,13 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
         const int iwv = kind | ((tx & 63) << 4) | ((ty & 63) << 10) | ((ok ? 1 : 0) << 16) | (dmg << 17) | (tdir << 25);
 
         // the slots act one after the other, each seeing what the earlier ones did
-        uint32_t alive_bits = (uint32_t)__ballot(m.alive != 0);
+        uint32_t alive_bits = (uint32_t)G::ballot(m.alive != 0);
         constexpr int ORDER[NSLOT] = { 0, 1, 2, 5, 6, 7, 8, 9, 10, 11, 12, 13, 3, 4 };
 #pragma unroll
         for (int i = 0; i < NSLOT; ++i) {
             const int k = ORDER[i];
             if (!((alive_bits >> k) & 1u)) continue;
-            const int iw = lane_get(iwv, k);
+            const int iw = G::get(iwv, k);
             const int kd = iw & 15, kx = (iw >> 4) & 63, ky = (iw >> 10) & 63, kdir = (iw >> 25) & 7;
             const bool kok = (iw >> 16) & 1;
             const int kdmg = (iw >> 17) & 255;
@@ -617,7 +623,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
                 const uint32_t free_slots = ~alive_bits & (7u << S_MPROJ0);
                 if (free_slots && kok && om == 0) {
                     const int s = __builtin_ctz(free_slots);
-                    const int type = lane_get(m.type, k);
+                    const int type = G::get(m.type, k);
                     if (l == s) { m.alive = 1; m.x = kx; m.y = ky; m.dir = kdir; m.hp = 0; m.cd = 0; m.type = type; }
                     alive_bits |= 1u << s;
                 }
@@ -628,7 +634,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
                 if (om) {
                     const int hit = __builtin_ctz(om);
                     int ap, af, ai;
-                    shot_attack(lane_get(m.type, k), ap, af, ai);
+                    shot_attack(G::get(m.type, k), ap, af, ai);
                     if (hurt_mob(hit, ap, af, ai)) alive_bits &= ~(1u << hit);
                     if (l == k) clear_mob(m);
                     alive_bits &= ~(1u << k);
@@ -640,7 +646,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
 
         // ---- despawn far away, spawn near (section "Creatures": fixed slots, masked when empty) ----
         if (m.alive && max(iabs(m.x - P.px), iabs(m.y - P.py)) > DESPAWN_DIST) clear_mob(m);
-        alive_bits = (uint32_t)__ballot(m.alive != 0);
+        alive_bits = (uint32_t)G::ballot(m.alive != 0);
         if (f == 8) {
             // the necromancer can be hit again once its wave is gone
             if (!P.boss_vulnerable && P.boss_hits < BOSS_HITS && !(alive_bits & 0x1Fu)) {
@@ -650,7 +656,7 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
         } else {
             const int first[3] = { S_MELEE0, S_RANGED0, S_PASSIVE0 }, count[3] = { 3, 2, 3 };
             const uint32_t caps[3] = { p.cap_melee, p.cap_ranged, p.cap_passive };
-            const int type[3] = { MELEE_OF_FLOOR[f], RANGED_OF_FLOOR[f], PASSIVE_OF_FLOOR[f] };
+            const int type[3] = { melee_of_floor(f), ranged_of_floor(f), passive_of_floor(f) };
 #pragma unroll
             for (int j = 0; j < 3; ++j) {
                 const int x = sx[j], y = sy[j];
@@ -658,18 +664,18 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
                 const uint32_t free_slots = ~alive_bits & (((1u << n) - 1u) << first[j]);
                 if (type[j] < 0 || !free_slots || max(iabs(x - P.px), iabs(y - P.py)) < SPAWN_MIN_DIST || !inb(x, y)) continue;
                 if (occ_mask(x, y) != 0 || (x == P.px && y == P.py)) continue;
-                const int b = lane_get(probe_b, j);
+                const int b = G::get(probe_b, j);
                 uint32_t thr; bool okb;
                 if (f == 0) {   // overworld: zombies on grass by darkness, skeletons on paths, cows on grass
-                    thr = j == 0 ? luts->zombie_thr[P.phase] : (j == 1 ? P_SKELETON_SPAWN : P_PASSIVE_SPAWN);
+                    thr = j == 0 ? zombie_thr : (j == 1 ? P_SKELETON_SPAWN : P_PASSIVE_SPAWN);
                     okb = j == 1 ? b == B_PATH : b == B_GRASS;
                 } else {
                     thr = j == 0 ? P_MELEE_SPAWN : (j == 1 ? P_RANGED_SPAWN : P_PASSIVE_SPAWN);
-                    okb = passable_for(CREATURE[type[j]].col, b);
+                    okb = passable_for(creature(type[j]).col, b);
                 }
                 if (!okb || misc[3 * j + 2] >= thr) continue;
                 const int s = __builtin_ctz(free_slots);
-                spawn_mob(s, x, y, 0, type[j], CREATURE[type[j]].hp);
+                spawn_mob(s, x, y, 0, type[j], creature(type[j]).hp);
                 alive_bits |= 1u << s;
             }
         }
@@ -678,9 +684,9 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
     // ---- plants: they only grow while the player is in the overworld ---------------------------
     if (f == 0) {
         if (patch_f == 0 && patch_x == q_x && patch_y == q_y) q_block = patch_b;
-        const int z0 = lane_get(m.alive, 0) ? (lane_get(m.x, 0) | (lane_get(m.y, 0) << 8)) : -1;
-        const int z1 = lane_get(m.alive, 1) ? (lane_get(m.x, 1) | (lane_get(m.y, 1) << 8)) : -1;
-        const int z2 = lane_get(m.alive, 2) ? (lane_get(m.x, 2) | (lane_get(m.y, 2) << 8)) : -1;
+        const int z0 = G::get(m.alive, 0) ? (G::get(m.x, 0) | (G::get(m.y, 0) << 8)) : -1;
+        const int z1 = G::get(m.alive, 1) ? (G::get(m.x, 1) | (G::get(m.y, 1) << 8)) : -1;
+        const int z2 = G::get(m.alive, 2) ? (G::get(m.x, 2) | (G::get(m.y, 2) << 8)) : -1;
         if (l < NPLANT && q_alive) {
             if (q_age < 65535) ++q_age;
             const int x = q_x, y = q_y;

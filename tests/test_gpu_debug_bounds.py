@@ -101,13 +101,14 @@ def test_classic_perlin_pool_and_noise_without_an_index_out_of_range(dbg):
     _clean(cx, "Classic, Perlin worlds, pool resets, noise mutation")
 
 
-def test_full_game_runs_without_an_index_out_of_range(dbg):
+@pytest.mark.parametrize("lanes", [64, 16])
+def test_full_game_runs_without_an_index_out_of_range(dbg, lanes):
     import torch
     from test_gpu_full_parity import rich_scene
     cx = dbg
     n, cap = 72, 60
     for obs_mode, omode in ((cx.OBS_SYM_U8_F32, po.FULL_OBS_U8_F32), (cx.OBS_PIXELS_F32, po.FULL_OBS_PIXELS_F32)):
-        sim = cx.Craftax(n, cx.default_config(cx.VARIANT_CRAFTAX, obs_mode=obs_mode, max_episode_steps=cap))
+        sim = cx.Craftax(n, cx.default_config(cx.VARIANT_CRAFTAX, obs_mode=obs_mode, max_episode_steps=cap, group_lanes=lanes))
         orc = po.FullOracle(n, po.full_default_config(max_episode_steps=cap), omode)
         seeds = synth.seeds_for(n, 17)
         sim.reset(seeds); orc.reset(seeds)
@@ -137,4 +138,4 @@ def test_full_game_runs_without_an_index_out_of_range(dbg):
             sim.mutate_swap(3, 1, True); orc.mutate_swap(3, 1, True)
         assert sim.export_envs().tobytes() == orc.envs.tobytes()
         sim.close()
-        _clean(cx, f"Craftax, observation layout {obs_mode}")
+        _clean(cx, f"Craftax, {lanes} lanes, observation layout {obs_mode}")

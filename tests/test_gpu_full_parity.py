@@ -26,8 +26,21 @@ def cx():
     return binding
 
 
+# Every test of this file runs twice: with the step kernel's default shape (a wavefront per
+# environment) and with 16 lanes per environment, four environments per wavefront.
+FORCED_LANES = 0
+
+
+@pytest.fixture(autouse=True, params=[0, 16], ids=["auto", "lanes16"])
+def _group_lanes(request):
+    global FORCED_LANES
+    FORCED_LANES = request.param
+    yield
+    FORCED_LANES = 0
+
+
 def _cfgs(cx, obs_mode, **kw):
-    g = cx.default_config(cx.VARIANT_CRAFTAX, obs_mode=obs_mode)
+    g = cx.default_config(cx.VARIANT_CRAFTAX, obs_mode=obs_mode, group_lanes=FORCED_LANES)
     o = po.full_default_config()
     for k, v in kw.items():
         setattr(o, k, v)
