@@ -388,6 +388,27 @@ def test_full_caps_and_short_episodes(cx):
     assert finished >= 40 * 6
 
 
+def test_full_randomly_drawn_configurations(cx):
+    """Ten configurations drawn from a fixed seed: batch size (ragged), observation layout, mob
+    and plant caps, day length, episode cap, world generator, action mix, seeds, fresh worlds or
+    edited scenes on every floor.  Every step's outputs and, every few steps, the whole state
+    are compared."""
+    rng = np.random.default_rng(20240301)
+    for case in range(10):
+        n = int(rng.integers(1, 120))
+        kw = dict(cap_melee=int(rng.integers(0, 4)), cap_ranged=int(rng.integers(0, 3)), cap_passive=int(rng.integers(0, 4)),
+                  cap_plant=int(rng.integers(0, 11)), day_length=2 * int(rng.integers(1, 200)),
+                  max_episode_steps=int(rng.choice([1, 2, 5, 40, 10000])), worldgen=int(rng.integers(0, 2)))
+        mode = int(rng.integers(1, 3))
+        kind = ["uniform", "skewed"][int(rng.integers(0, 2))]
+        seed_base, action_seed = int(rng.integers(0, 2**63)), int(rng.integers(0, 2**40))
+        scenes = bool(rng.integers(0, 2))
+        T = 12 if kw["max_episode_steps"] <= 5 else 80
+        print(f"case {case}: n={n} mode={mode} kind={kind} T={T} scenes={scenes} {kw}", flush=True)
+        run_full(cx, n, T, obs_mode=mode, kind=kind, state_every=4 if T == 12 else 20, seed_base=seed_base, action_seed=action_seed,
+                 prep=rich_scene if scenes else None, **kw)
+
+
 def test_full_out_of_range_actions_are_noops(cx):
     import torch
     gcfg, ocfg = _cfgs(cx, 1)

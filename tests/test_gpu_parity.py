@@ -185,6 +185,27 @@ def test_paper_caps_and_other_day_length(cx):
     run_parity(cx, 32, 300, po.OBS_SYM_U8_F32, "skewed", state_every=50, cap_zombie=0, cap_cow=1, cap_arrow=0)
 
 
+def test_randomly_drawn_configurations(cx):
+    """Sixteen configurations drawn from a fixed seed: batch size (ragged), lanes per environment,
+    observation layout, mob and plant caps, day length, episode cap, world generator, action
+    mix and seeds.  Every step's outputs and, every few steps, the whole state are compared."""
+    rng = np.random.default_rng(20240229)
+    modes = [po.OBS_SYM_U8_I8, po.OBS_SYM_U8_F32, po.OBS_SYM_F32]
+    for case in range(16):
+        n = int(rng.integers(1, 300))
+        kw = dict(cap_zombie=int(rng.integers(0, 4)), cap_cow=int(rng.integers(0, 4)), cap_skeleton=int(rng.integers(0, 3)),
+                  cap_arrow=int(rng.integers(0, 4)), cap_plant=int(rng.integers(0, 11)), day_length=2 * int(rng.integers(1, 200)),
+                  max_episode_steps=int(rng.choice([1, 2, 3, 7, 30, 90, 10000])), worldgen=int(rng.integers(0, 2)))
+        lanes = [None, 4, 8, 16][int(rng.integers(0, 4))]
+        mode = modes[int(rng.integers(0, 3))]
+        kind = ["uniform", "skewed"][int(rng.integers(0, 2))]
+        seed_base, action_seed = int(rng.integers(0, 2**63)), int(rng.integers(0, 2**40))
+        T = 25 if kw["max_episode_steps"] <= 3 else 120
+        print(f"case {case}: n={n} lanes={lanes} mode={mode} kind={kind} T={T} {kw}", flush=True)
+        run_parity(cx, n, T, mode, kind, state_every=5 if T == 25 else 20, seed_base=seed_base, action_seed=action_seed,
+                   lanes=lanes, **kw)
+
+
 def test_seeds_with_high_bits_and_other_action_seed(cx):
     run_parity(cx, 32, 300, po.OBS_SYM_U8_F32, "skewed", state_every=100, seed_base=0xDEADBEEF12345678,
                action_seed=0x1234567890, max_episode_steps=150)
