@@ -335,12 +335,19 @@ int craftax_synth_actions(int32_t *actions, int n, int step0, int steps, uint64_
 
 /* Per-run metrics (the paper reports achievement success rates and reward as a share of the
  * maximum, section "Craftax-1B"; its appendix "Optimistic Environment Resets" argues from the mean
- * episode length): a snapshot over the n environments as they stand.
- *   episodes        episodes finished since craftax_reset, summed over the environments
- *   steps           steps taken so far in the current episodes (sum of t)
- *   achievements[i] environments whose current episode has unlocked achievement i (appendix
+ * episode length): sums over the n environments.
+ *   episodes        episodes finished since craftax_reset
+ *   steps           steps taken so far in the episodes now running (sum of t)
+ *   achievements[i] environments whose running episode has unlocked achievement i (appendix
  *                   "Achievements": 22 ids for Classic, 67 for Craftax; the rest stay 0)
- * Mean episode length over a window = n * window / (episodes after - episodes before).
+ *   unlocks[i]      how often achievement i has been unlocked since craftax_reset, counted by the
+ *                   step kernels as it happens (an achievement unlocks at most once per episode)
+ * Success rate of achievement i over the finished episodes = (unlocks[i] - achievements[i]) /
+ * episodes; over a window of steps, the same with the differences of two snapshots.  Mean episode
+ * length over a window = n * window / (episodes after - episodes before).  The counters belong to
+ * the run, not to the environments: craftax_reset clears them, craftax_import_envs and the
+ * mutations leave them alone (an episode restarted by craftax_mutate_noise can unlock again), and
+ * they travel with a copy of the state blob.
  * out: DEVICE, one craftax_metrics, 8-byte aligned.  workspace: DEVICE scratch of at least
  * craftax_stats_workspace_bytes(n) bytes, 16-byte aligned, contents irrelevant before and after
  * (each 256 environments leave one partial result there, a second kernel adds them up, so the
@@ -353,13 +360,14 @@ typedef struct craftax_metrics {
     uint32_t achievements[CRAFTAX_STATS_ACHIEVEMENTS];
     uint32_t n;
     uint32_t pad;
+    uint64_t unlocks[CRAFTAX_STATS_ACHIEVEMENTS];
 } craftax_metrics;
 size_t craftax_stats_workspace_bytes(int n);
 int craftax_stats(const void *state, craftax_metrics *out, void *workspace, size_t workspace_bytes, int n, void *stream);
 
 /* craftax_stats for callers that cannot allocate device memory or hand over a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The partial
- * results go to a buffer inside the library's own device image (1 MiB per GPU, held until the
+ * results go to a buffer inside the library's own device image (2 MiB per GPU, held until the
  * process ends) instead of a workspace; nothing is allocated, by this call or behind it.  Same
  * result as craftax_stats.  Limits: n <= CRAFTAX_STATS_STATIC_MAX_ENVS (CRAFTAX_E_COUNT beyond).
  * All calls on one GPU share that buffer: calls that overlap in time on one GPU (different

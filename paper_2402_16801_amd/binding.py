@@ -67,8 +67,9 @@ assert ENV_DUMP_DTYPE.itemsize == 4304 and FULL_ENV_DUMP_DTYPE.itemsize == 63432
 
 
 STATS_ACHIEVEMENTS = 96
-STATS_DTYPE = np.dtype([("episodes", "<u8"), ("steps", "<u8"), ("achievements", "<u4", (STATS_ACHIEVEMENTS,)), ("n", "<u4"), ("pad", "<u4")])
-assert STATS_DTYPE.itemsize == 408
+STATS_DTYPE = np.dtype([("episodes", "<u8"), ("steps", "<u8"), ("achievements", "<u4", (STATS_ACHIEVEMENTS,)), ("n", "<u4"), ("pad", "<u4"),
+                        ("unlocks", "<u8", (STATS_ACHIEVEMENTS,))])
+assert STATS_DTYPE.itemsize == 408 + 8 * STATS_ACHIEVEMENTS
 
 
 class CraftaxError(RuntimeError):

@@ -162,7 +162,7 @@ struct Header {
     uint32_t obs_mode, max_episode_steps, day_length;
     uint32_t cap_zombie, cap_cow, cap_skeleton, cap_arrow, cap_plant;
     uint64_t atlas_seed;
-    uint64_t off_ctrs, off_luts, off_recs, off_maps, off_tags, off_regen0, off_regen1, off_slow, total;
+    uint64_t off_ctrs, off_luts, off_recs, off_maps, off_tags, off_regen0, off_regen1, off_slow, off_unlocks, total;
     uint32_t variant, worldgen, reset_mode, pad;
 };
 constexpr uint64_t HEADER_BYTES = 256;   // the header sits alone in the first 256 bytes of the state blob
@@ -176,8 +176,29 @@ struct Params {
     uint32_t cap_zombie, cap_cow, cap_skeleton, cap_arrow, cap_plant;
     uint32_t worldgen;              // CRAFTAX_WORLDGEN_*
     uint32_t reset_mode;            // CRAFTAX_RESET_*
+    uint32_t* unlocks;              // UNLOCK_STRIDE counters per environment (see count_unlocks); null in kernels that do not step
 };
 constexpr uint32_t POOL_RATIO = 16, POOL_ENV = 0x80000000u;   // optimistic resets: environments per pool world; numbering of the pool's worlds
+
+// Unlock counters (the paper reports achievement success rates, section "Craftax-1B": the share of
+// episodes in which an achievement was unlocked): counts[k] = how often achievement k has been
+// unlocked in this environment since craftax_reset.  An achievement unlocks at most once per
+// episode, so the sum over the environments, less the episodes still running that hold it, is the
+// number of finished episodes that reached it.  Counted where it happens, in the step: `unlocked`
+// = the bits that are new after this step.  The G lanes of the environment's group take the
+// achievements l, l + G, ...; the adds return nothing, so no wavefront waits for them, and only
+// this group ever touches these words.
+constexpr int N_ACHIEVEMENTS = 22, UNLOCK_STRIDE = 24;   // dwords per environment (96 bytes)
+template <int G>
+__device__ __forceinline__ void count_unlocks(int l, uint32_t* __restrict__ counts, uint32_t unlocked)
+{
+    if (unlocked == 0u) return;
+#pragma unroll
+    for (int k0 = 0; k0 < N_ACHIEVEMENTS; k0 += G) {
+        const int k = k0 + l;
+        if (k < N_ACHIEVEMENTS && ((unlocked >> k) & 1u)) atomicAdd(counts + k, 1u);
+    }
+}
 
 // ---- lane groups --------------------------------------------------------------------------------
 // An environment is owned by G consecutive lanes of a wavefront (G = 4, 8 or 16, so 16, 8 or

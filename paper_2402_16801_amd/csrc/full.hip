@@ -53,7 +53,7 @@ __device__ inline void publish_world(uint32_t* __restrict__ genv, const GenLayou
 // reset of every environment: one block per (environment, episode 0 or 1, floor)
 __global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps,
                                                        const uint64_t* __restrict__ seeds, Lists ls, const uint32_t* __restrict__ perlin_cs,
-                                                       int pool)
+                                                       int pool, uint32_t* __restrict__ unlocks)
 {
     if (blockIdx.x == 0) la::reset_counters(ls);
     __shared__ uint16_t s_lat[LAT_TOTAL];
@@ -65,6 +65,7 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ e
     const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
     worldgen_floor_block<GEN_THREADS, true>(maps + map_offset(env, ep), s_lat, s_layout, lo, hi, env, ep, f, nullptr, nullptr, 0, GEN_THREADS, perlin_cs);
     if (f == 0) publish_world(envs + (size_t)env * ENV_DWORDS, s_layout, lo, hi, ep, ep == 0u, s_words);
+    if (f == 0 && ep == 0u && threadIdx.x < UNLOCK_STRIDE) unlocks[(size_t)env * UNLOCK_STRIDE + threadIdx.x] = 0u;
     // With optimistic resets no spare world is ever valid: tag 0 matches no next episode (they count
     // from 1), so the step kernel hands every finished episode to kf_reset_list.
     if (ep == 1u && threadIdx.x == 0) ls.tags[(size_t)env * NTAG + f] = make_uint2(pool ? 0u : 1u, 0u);
@@ -199,6 +200,8 @@ __global__ __launch_bounds__(BLOCK, GW == 64 ? 5 : 2) void kf_step(uint32_t* __r
         };
         StepOut o = step_env<GW>(l, (uint32_t)env, e, genv, maps + map_offset((uint32_t)env, ep), luts, action, p, m, qw, P, park);
         if (l == 0) { reward[env] = o.reward; done[env] = o.done ? 1 : 0; }
+#pragma unroll
+        for (int aw = 0; aw < 3; ++aw) count_unlocks<GW>(l, p.unlocks + (size_t)env * UNLOCK_STRIDE, aw, o.unlocked[aw]);
         bool write_back = !o.done, queued = false;
         uint32_t list_at = 0u;
         int floor_now = P.floor;
@@ -338,7 +341,7 @@ __global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ en
         MobRegs m;
         clear_mob(m);
         StepOut o;
-        o.done = false; o.reward = 0.0f; o.wx0 = 0; o.wy0 = 0;
+        o.done = false; o.reward = 0.0f; o.wx0 = 0; o.wy0 = 0; o.unlocked[0] = o.unlocked[1] = o.unlocked[2] = 0u;
         int floor_now = 0;
         if (active) {
             const int action = uni(actions[(size_t)t * p.n + env]);
@@ -347,6 +350,8 @@ __global__ __launch_bounds__(BLOCK, 4) void kf_rollout(uint32_t* __restrict__ en
             Player P;
             o = step_env(l, (uint32_t)env, e, genv, maps + map_offset((uint32_t)env, ep), luts, action, p, m, qw, P, []() {});
             if (l == 0) { reward[(size_t)t * p.n + env] = o.reward; done[(size_t)t * p.n + env] = o.done ? 1 : 0; }
+#pragma unroll
+            for (int aw = 0; aw < 3; ++aw) count_unlocks<64>(l, p.unlocks + (size_t)env * UNLOCK_STRIDE, aw, o.unlocked[aw]);
             floor_now = P.floor;
             if (!o.done) {
                 if (l == 0) pack_player(e + L_REC, P);
@@ -782,7 +787,8 @@ static Header make_header(const craftax_config* c, int n)
     const uint64_t list_bytes = (uint64_t)NSUB * la::sub_list_capacity((uint64_t)n, MAX_ENVS_PER_STEP_BLOCK) * 16;
     h.off_regen1 = h.off_regen0 + list_bytes;
     h.off_slow = h.off_regen1 + list_bytes;
-    h.total = round_up(h.off_slow + (uint64_t)n * 16, 256);
+    h.off_unlocks = round_up(h.off_slow + (uint64_t)n * 16, 256);
+    h.total = round_up(h.off_unlocks + (uint64_t)n * UNLOCK_STRIDE * 4, 256);
     return h;
 }
 
@@ -848,9 +854,10 @@ static Ptrs pointers(const void* state, const Header& h)
     q.ls.slow_cap = h.n;
     return q;
 }
-static Params make_params(const craftax_config* c, int n)
+static Params make_params(const void* state, const craftax_config* c, int n)
 {
     Params p;
+    p.unlocks = reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(static_cast<const uint8_t*>(state)) + make_header(c, n).off_unlocks);
     p.n = n; p.max_episode_steps = c->max_episode_steps; p.day_length = c->day_length;
     p.cap_melee = c->cap_zombie; p.cap_ranged = c->cap_skeleton; p.cap_passive = c->cap_cow; p.cap_plant = c->cap_plant;
     p.worldgen = c->worldgen;
@@ -917,7 +924,7 @@ int debug_bounds(uint32_t report[4], std::string* err)
 RecordLayout record_layout(const void* state, const craftax_config* cfg, int n)
 {
     const Ptrs q = pointers(state, make_header(cfg, n));
-    return RecordLayout{q.envs, ENV_DWORDS, R_ACH, 3, R_T, R_EPISODE};
+    return RecordLayout{q.envs, ENV_DWORDS, R_ACH, 3, R_T, R_EPISODE, make_params(state, cfg, n).unlocks, UNLOCK_STRIDE};
 }
 
 int check_kernels(const craftax_config* cfg, std::string* err)
@@ -955,7 +962,8 @@ int check_kernels(const craftax_config* cfg, std::string* err)
 int reset(void* state, const craftax_config* cfg, int n, const uint64_t* seeds, void* stream, std::string* err)
 {
     const Ptrs q = pointers(state, make_header(cfg, n));
-    hipLaunchKernelGGL(kf_reset, dim3((unsigned)n * 2 * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, seeds, q.ls, gradients(cfg, q), cfg->reset_mode == CRAFTAX_RESET_POOL ? 1 : 0);
+    hipLaunchKernelGGL(kf_reset, dim3((unsigned)n * 2 * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, seeds, q.ls, gradients(cfg, q), cfg->reset_mode == CRAFTAX_RESET_POOL ? 1 : 0,
+                       make_params(state, cfg, n).unlocks);
     return check_launch("craftax_reset", err);
 }
 
@@ -992,7 +1000,7 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
          bool serve_slow, void* stream, std::string* err)
 {
     const Ptrs q = pointers(state, make_header(cfg, n));
-    const Params p = make_params(cfg, n);
+    const Params p = make_params(state, cfg, n);
     hipStream_t st = (hipStream_t)stream;
     uint8_t* o = static_cast<uint8_t*>(obs);
     const int gw = group_lanes(cfg, n), epb = BLOCK / gw;
@@ -1029,7 +1037,7 @@ int rollout(void* state, const craftax_config* cfg, int n, const int32_t* action
     if (cfg->obs_mode == CRAFTAX_OBS_PIXELS_F32) { *err = "craftax_rollout needs a symbolic observation"; return CRAFTAX_E_CONFIG; }
     if (cfg->reset_mode != CRAFTAX_RESET_EXACT) { *err = "craftax_rollout needs exact resets"; return CRAFTAX_E_CONFIG; }
     const Ptrs q = pointers(state, make_header(cfg, n));
-    const Params p = make_params(cfg, n);
+    const Params p = make_params(state, cfg, n);
     hipStream_t st = (hipStream_t)stream;
     uint8_t* o = static_cast<uint8_t*>(obs);
     const int rb = FLOORS * n < REGEN_BLOCKS ? FLOORS * n : REGEN_BLOCKS;
@@ -1066,7 +1074,7 @@ int import_envs(void* state, const craftax_config* cfg, int n, int first, int co
 {
     const Ptrs q = pointers(state, make_header(cfg, n));
     hipLaunchKernelGGL(kf_import, dim3(count), dim3(BLOCK), 0, (hipStream_t)stream, q.envs, q.maps, q.ls,
-                       static_cast<const craftax_full_env_dump*>(dumps), first, make_params(cfg, n));
+                       static_cast<const craftax_full_env_dump*>(dumps), first, make_params(state, cfg, n));
     hipLaunchKernelGGL(kf_import_spare, dim3((unsigned)count * FLOORS), dim3(GEN_THREADS), 0, (hipStream_t)stream, q.envs, q.maps, q.ls, first, gradients(cfg, q), cfg->reset_mode == CRAFTAX_RESET_POOL ? 1 : 0);
     return check_launch("craftax_import_envs", err);
 }

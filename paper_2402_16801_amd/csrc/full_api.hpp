@@ -22,8 +22,8 @@ int step(void* state, const craftax_config* cfg, int n, const int32_t* actions, 
          bool serve_slow, void* stream, std::string* err);
 // checks a header read back from a blob against cfg and n: 0, or a CRAFTAX_E_* code and a message
 int check_header(const void* header_bytes, const craftax_config* cfg, int n, std::string* err);
-// where the metrics kernel finds achievements, t and episode: records as dwords
-struct RecordLayout { const uint32_t* recs; int stride, ach, ach_words, t, episode; };
+// where the metrics kernel finds achievements, t and episode (records as dwords) and the unlock counters
+struct RecordLayout { const uint32_t* recs; int stride, ach, ach_words, t, episode; const uint32_t* unlocks; int unlock_stride; };
 RecordLayout record_layout(const void* state, const craftax_config* cfg, int n);
 // debug build: adds this translation unit's bounds record to report[4] and clears it
 int debug_bounds(uint32_t report[4], std::string* err);

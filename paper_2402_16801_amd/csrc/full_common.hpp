@@ -282,7 +282,7 @@ struct Header {
     uint32_t version, n;
     uint32_t variant, obs_mode, max_episode_steps, day_length;
     uint32_t cap_melee, cap_ranged, cap_passive, cap_plant;
-    uint64_t off_ctrs, off_luts, off_envs, off_maps, off_tags, off_regen0, off_regen1, off_slow, total;
+    uint64_t off_ctrs, off_luts, off_envs, off_maps, off_tags, off_regen0, off_regen1, off_slow, off_unlocks, total;
     uint64_t atlas_seed;
     uint32_t worldgen, reset_mode;
 };
@@ -294,7 +294,26 @@ struct Params {
     uint32_t max_episode_steps, day_length;
     uint32_t cap_melee, cap_ranged, cap_passive, cap_plant;
     uint32_t worldgen;              // CRAFTAX_WORLDGEN_*
+    uint32_t* unlocks;              // UNLOCK_STRIDE counters per environment (see count_unlocks); null in kernels that do not step
 };
+
+// Unlock counters (the paper reports achievement success rates, section "Craftax-1B"): counts[k] =
+// how often achievement k has been unlocked in this environment since craftax_reset; an
+// achievement unlocks at most once per episode, so the sum over the environments, less the
+// running episodes that hold it, is the number of finished episodes that reached it.  Counted in
+// the step, from the bits of achievement word w that are new after it; lane l of the environment's
+// group takes bits l, l + GW, ...; the adds return nothing, so no wavefront waits for them.
+constexpr int UNLOCK_STRIDE = 72;   // dwords per environment: 67 achievements, padded to 288 bytes
+template <int GW>
+__device__ __forceinline__ void count_unlocks(int l, uint32_t* __restrict__ counts, int w, uint32_t unlocked)
+{
+    if (unlocked == 0u) return;
+#pragma unroll
+    for (int b0 = 0; b0 < 32; b0 += GW) {
+        const int b = b0 + l;
+        if (b < 32 && 32 * w + b < H_COUNT && ((unlocked >> b) & 1u)) atomicAdd(counts + 32 * w + b, 1u);
+    }
+}
 
 // ---- per-environment LDS area (dword offsets) ----------------------------------------------------
 // Window: 11 rows x 13 columns (pitch 16 bytes) of the block map and of the item/light map

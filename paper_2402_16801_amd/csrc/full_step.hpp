@@ -123,7 +123,7 @@ __device__ __forceinline__ void load_window(int l, const uint8_t* __restrict__ m
 struct MobRegs { int alive, x, y, dir, hp, cd, type; };
 __device__ inline void clear_mob(MobRegs& m) { m.alive = m.x = m.y = m.dir = m.hp = m.cd = m.type = 0; }
 
-struct StepOut { bool done; float reward; int wx0, wy0; };
+struct StepOut { bool done; float reward; int wx0, wy0; uint32_t unlocked[3]; };   // unlocked: achievement bits new after this step
 
 enum Intent : int { N_NONE = 0, N_DAMAGE, N_DAMAGE_DIE, N_DIE, N_MOVE, N_SHOOT, N_FLY, N_PPROJ };
 
@@ -732,13 +732,14 @@ __device__ __forceinline__ StepOut step_env(const int l, const uint32_t env, uin
 
     // ---- reward, time, done (section "RL Environment Interface") ------------------------------
     int gained = 0;
+    StepOut o;
 #pragma unroll
     for (int w = 0; w < 3; ++w) {
         const uint32_t nw = P.ach[w] & ~ach0[w];
+        o.unlocked[w] = nw;
         gained += __builtin_popcount(nw & CAT1[w]) + 3 * __builtin_popcount(nw & CAT3[w]) +
                   5 * __builtin_popcount(nw & CAT5[w]) + 8 * __builtin_popcount(nw & CAT8[w]);
     }
-    StepOut o;
     o.reward = (float)(10 * gained + (P.vit[V_HEALTH] - health0)) * 0.1f;
     ++P.t;
     P.phase = P.phase + 1 == (int)p.day_length ? 0 : P.phase + 1;

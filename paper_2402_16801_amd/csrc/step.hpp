@@ -25,7 +25,7 @@ namespace cx {
 
 enum Intent : int { K_NONE = 0, K_MOVE = 1, K_MOVE_PATH = 2, K_ATTACK = 3, K_SHOOT = 4, K_FLY = 5 };
 
-struct StepOut { bool done; float reward; int mvx, mvy, woff; };
+struct StepOut { bool done; float reward; int mvx, mvy, woff; uint32_t unlocked; };   // unlocked: achievement bits new after this step
 
 // The part of the window a step can touch, in window rows and columns (inclusive): the 7 x 9 view
 // around the player, widened by one row or column on the side the player may move to.  Nothing
@@ -495,7 +495,8 @@ __device__ __forceinline__ StepOut step_env(int l, uint32_t env, uint32_t* e, ui
     // ---- reward, time, done ---------------------------------------------------------------------------
     StepOut out;
     out.mvx = mvx; out.mvy = mvy; out.woff = woff;
-    const int gained = __popc(ach & ~ach0);
+    out.unlocked = ach & ~ach0;
+    const int gained = __popc(out.unlocked);
     out.reward = (float)(10 * gained + (vit[0] - health0)) * 0.1f;
     const uint32_t t1 = t + 1;
     phase = phase + 1 == p.day_length ? 0u : phase + 1;

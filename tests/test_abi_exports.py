@@ -66,8 +66,8 @@ def test_full_variant_sizes_and_defaults(lib):
     cfg.obs_mode = binding.OBS_SYM_U8_F32
     b1, b2 = binding.craftax_state_bytes(cfg, 1), binding.craftax_state_bytes(cfg, 1001)
     # per environment: 1024-byte record + mob tables, two slots of 9 floors x 2 maps x 2304 bytes, 9 spare-world
-    # tags, three list entries (the sub-lists round their capacity up)
-    assert abs((b2 - b1) - 1000 * (1024 + 2 * 9 * 2 * 2304 + 9 * 8 + 3 * 16)) < 8192 and b1 % 256 == 0
+    # tags, three list entries (the sub-lists round their capacity up), 72 unlock counters
+    assert abs((b2 - b1) - 1000 * (1024 + 2 * 9 * 2 * 2304 + 9 * 8 + 3 * 16 + 72 * 4)) < 8192 and b1 % 256 == 0
     cfg.cap_skeleton = 3
     assert binding.craftax_state_bytes(cfg, 8) == 0
 
@@ -98,6 +98,6 @@ def test_header_constants_match_their_python_mirrors():
     assert enums["CRAFTAX_VARIANT_CLASSIC"] == binding.VARIANT_CLASSIC and enums["CRAFTAX_VARIANT_CRAFTAX"] == binding.VARIANT_CRAFTAX
     assert defines["CRAFTAX_STATS_ACHIEVEMENTS"] == binding.STATS_ACHIEVEMENTS >= 67
     assert defines["CRAFTAX_STATS_STATIC_MAX_ENVS"] == binding.STATS_STATIC_MAX_ENVS and binding.STATS_STATIC_MAX_ENVS % 256 == 0
-    assert binding.STATS_DTYPE.itemsize == 8 + 8 + 4 * 96 + 8
-    assert binding.craftax_stats_workspace_bytes(1) == 512 and binding.craftax_stats_workspace_bytes(257) == 1024
+    assert binding.STATS_DTYPE.itemsize == 8 + 8 + 4 * 96 + 8 + 8 * 96
+    assert binding.craftax_stats_workspace_bytes(1) == 1024 and binding.craftax_stats_workspace_bytes(257) == 2048
     assert binding.craftax_stats_workspace_bytes(0) == 0

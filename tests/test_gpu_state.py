@@ -268,31 +268,86 @@ def test_death_on_the_first_step_after_an_auto_reset_and_a_swap(cx, variant, n, 
     sim.close()
 
 
-def _oracle_stats(orc, n_ach):
-    e = orc.envs
-    ach = e["ach"].reshape(len(e), -1).astype(np.uint64)
-    bits = np.zeros(96, np.int64)
+def _bit_counts(words, n_ach):
+    """How many rows of the achievement words (n x W uint32) have bit i set, for i < n_ach, in 96 slots."""
+    w = words.reshape(len(words), -1).astype(np.uint64)
+    out = np.zeros(96, np.int64)
     for i in range(n_ach):
-        bits[i] = int(((ach[:, i // 32] >> np.uint64(i % 32)) & np.uint64(1)).sum())
-    return int(e["episode"].astype(np.int64).sum()), int(e["t"].astype(np.int64).sum()), bits
+        out[i] = int(((w[:, i // 32] >> np.uint64(i % 32)) & np.uint64(1)).sum())
+    return out
 
 
-@pytest.mark.parametrize("variant,n", [("classic", 1000), ("classic", 257), ("craftax", 300)])
-def test_metrics_snapshot_matches_the_oracle(cx, variant, n):
-    """craftax_stats (episodes finished, steps into the current episodes, achievement counts)
-    against the same sums over the oracle's environments, at several points of a run."""
+def _unlocked_this_step(orc, before, actions, odone, n_ach):
+    """Achievement bits that the step just taken by `orc` switched on, counted per achievement.  For an
+    environment whose episode went on they are the difference of its achievement words; one whose
+    episode ended has been reset already, so its last step is taken again from the copy made before
+    the step, by the oracle's rules alone (no reset)."""
+    after = orc.envs["ach"].reshape(orc.n, -1)
+    prev = before["ach"].reshape(orc.n, -1)
+    new = np.where(odone[:, None] == 1, 0, after & ~prev).astype(np.uint32)
+    ended = np.nonzero(odone)[0]
+    if len(ended):
+        shadow = type(orc)(len(ended), orc.cfg, orc.obs_mode)
+        shadow.envs[:] = before[ended]
+        for j, i in enumerate(ended):
+            shadow.step_rules_one(j, int(actions[i]))
+        new[ended] = shadow.envs["ach"].reshape(len(ended), -1) & ~prev[ended]
+    return _bit_counts(new, n_ach)
+
+
+@pytest.mark.parametrize("variant,n,lanes", [("classic", 1000, 0), ("classic", 257, 4), ("classic", 70, 8), ("craftax", 300, 0), ("craftax", 70, 16)])
+def test_metrics_match_the_oracle(cx, variant, n, lanes):
+    """craftax_stats (episodes finished, steps into the running episodes, achievements held by the
+    running episodes, unlock events since the reset) against the same sums over the oracle's
+    environments, at several points of a run of single steps and rollouts; then the success rates
+    over the finished episodes that follow from them, and a reset that clears the counters."""
+    import torch
     sim, orc, n_actions = _pair(cx, variant, n, max_episode_steps=60)
+    if lanes:                                   # another shape of the step kernel
+        sim.close()
+        cfg = cx.default_config(cx.VARIANT_CRAFTAX if variant == "craftax" else cx.VARIANT_CLASSIC, obs_mode=cx.OBS_SYM_U8_F32,
+                                max_episode_steps=60, group_lanes=lanes)
+        sim = cx.Craftax(n, cfg)
     seeds = synth.seeds_for(n, 21)
     sim.reset(seeds); orc.reset(seeds)
     n_ach = 22 if variant == "classic" else 67
     seen = np.zeros(96, np.int64)
-    for s in range(150):
-        _step_both(sim, orc, synth.actions(np.arange(n), s, "skewed", 2, n_actions), f"step {s}")
-        if s % 30 == 29 or s < 2:
+    unlocks = np.zeros(96, np.int64)
+    finished_with = np.zeros(96, np.int64)      # finished episodes that had unlocked achievement i
+    s = 0
+    while s < 170:
+        if s in (40, 100):                      # a rollout of 25 steps in between: the same counters
+            T = 25
+            acts = np.stack([synth.actions(np.arange(n), s + k, "skewed", 2, n_actions) for k in range(T)])
+            rew = torch.empty((T, n), dtype=torch.float32, device=sim.device)
+            dn = torch.empty((T, n), dtype=torch.uint8, device=sim.device)
+            cx.craftax_rollout(sim.state, torch.as_tensor(acts, device=sim.device), T, None, rew, dn, n, sim.stream)
+            for k in range(T):
+                before = orc.envs.copy()
+                _, _, odone = orc.step(acts[k], render=False)
+                step_new = _unlocked_this_step(orc, before, acts[k], odone, n_ach)
+                unlocks += step_new
+                assert np.array_equal(dn[k].cpu().numpy(), odone)
+            s += T
+        else:
+            a = synth.actions(np.arange(n), s, "skewed", 2, n_actions)
+            before = orc.envs.copy()
+            odone = _step_both(sim, orc, a, f"step {s}")
+            unlocks += _unlocked_this_step(orc, before, a, odone, n_ach)
+            s += 1
+        if s % 30 == 0 or s < 3:
             got = sim.stats()
-            episodes, steps, bits = _oracle_stats(orc, n_ach)
-            assert (int(got["episodes"]), int(got["steps"]), int(got["n"])) == (episodes, steps, n)
-            assert np.array_equal(got["achievements"].astype(np.int64), bits)
+            e = orc.envs
+            bits = _bit_counts(e["ach"], n_ach)
+            assert (int(got["episodes"]), int(got["steps"]), int(got["n"])) == (int(e["episode"].astype(np.int64).sum()), int(e["t"].astype(np.int64).sum()), n)
+            assert np.array_equal(got["achievements"].astype(np.int64), bits), f"running episodes, step {s}"
+            assert np.array_equal(got["unlocks"].astype(np.int64), unlocks), f"unlock events, step {s}"
             seen = np.maximum(seen, bits)
     assert int(got["episodes"]) >= 2 * n and (seen > 0).sum() >= 3, "the run was to finish episodes and unlock achievements"
+    # success rate over the finished episodes: every unlock belongs to a finished or to a running episode
+    finished_with = got["unlocks"].astype(np.int64) - got["achievements"].astype(np.int64)
+    assert (finished_with >= 0).all() and (finished_with <= int(got["episodes"])).all() and finished_with.sum() > 0
+    sim.reset(seeds)
+    again = sim.stats()
+    assert int(again["episodes"]) == 0 and not again["unlocks"].any() and not again["achievements"].any()
     sim.close()
