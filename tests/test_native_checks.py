@@ -19,12 +19,18 @@ def test_oracle_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_pa
     srcs = [os.path.join(ROOT, "oracle", f) for f in ("philox.c", "classic.c", "craftax_full.c")]
     _run(["gcc", "-O1", "-g", "-std=c11", "-ffp-contract=off", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
           "-static-libasan", "-o", exe, os.path.join(NATIVE, "oracle_sanitizer_run.c")] + srcs + ["-lm"])
-    env = dict(os.environ)
-    env.pop("LD_PRELOAD", None)                     # the sanitizer runtime has to come first in the process
+    env = dict(os.environ)                          # the sanitizer runtime is linked statically: whatever is preloaded stays
     env["ASAN_OPTIONS"] = "detect_leaks=0:abort_on_error=0"
     env["UBSAN_OPTIONS"] = "print_stacktrace=1"
     out = _run([exe], env=env)
     assert "oracle_sanitizer_run: ok" in out and "runtime error" not in out and "AddressSanitizer" not in out, out[-3000:]
+
+
+def test_regeneration_units_are_dealt_out_exactly_once(tmp_path):
+    """The walk that shares the regeneration units of a step launch between its blocks (csrc/regen_units.hpp)."""
+    exe = str(tmp_path / "regen_units_test")
+    _run(["g++", "-O1", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-o", exe, os.path.join(NATIVE, "regen_units_test.cpp")])
+    assert "regen_units_test: ok" in _run([exe])
 
 
 def test_launch_limit_rule(tmp_path):
