@@ -76,14 +76,16 @@ __global__ __launch_bounds__(GEN_THREADS) void kf_reset(uint32_t* __restrict__ e
 // each; block rb of nrb takes units rb, rb + nrb, ...  The blocks stand at the head of the grid:
 // a step launch holds as many of them as the chip has room for beside the step blocks, so every
 // unit starts with the launch and none waits for a block that is scheduled late.
+// where a regeneration block keeps its scratch in the step kernel's LDS area (dwords): lattice numbers at 0, the layout at 128
+constexpr int REGEN_WORDS_AT = 832, REGEN_PREFIX_AT = 848;
 template <bool PERLIN>
 __device__ __forceinline__ void regeneration_queue(uint32_t* __restrict__ envs, uint8_t* __restrict__ maps, const Lists& ls,
                                                    uint32_t seq, uint32_t* lds, int regen_blocks, const uint32_t* __restrict__ perlin_cs)
 {
     uint16_t* s_lat = reinterpret_cast<uint16_t*>(lds);
     GenLayout& L = *reinterpret_cast<GenLayout*>(lds + 128);
-    uint32_t* s_words = lds + 512;
-    const uint32_t* s_prefix = lds + 528;
+    uint32_t* s_words = lds + REGEN_WORDS_AT;
+    const uint32_t* s_prefix = lds + REGEN_PREFIX_AT;
     const uint32_t units = s_prefix[NSUB - 1] * (uint32_t)FLOORS;
     for (uint32_t u = blockIdx.x; u < units; u += (uint32_t)regen_blocks) {
         __syncthreads();   // the previous unit's scratch has been read by everyone
@@ -96,7 +98,8 @@ __device__ __forceinline__ void regeneration_queue(uint32_t* __restrict__ envs, 
         if (threadIdx.x == 0) ls.tags[(size_t)entry.x * NTAG + f] = make_uint2(entry.w, seq);
     }
 }
-static_assert(LAT_TOTAL * 2 <= 128 * 4 && sizeof(GenLayout) <= (512 - 128) * 4 && 528 + NSUB <= ENVS_PER_BLOCK * L_ENV_DWORDS, "regeneration scratch overlaps");
+static_assert(LAT_TOTAL * 2 <= 128 * 4 && sizeof(GenLayout) <= (REGEN_WORDS_AT - 128) * 4 && REGEN_WORDS_AT + FLOORS + 1 <= REGEN_PREFIX_AT &&
+              REGEN_PREFIX_AT + NSUB <= ENVS_PER_BLOCK * L_ENV_DWORDS, "regeneration scratch overlaps");
 
 // ---------------------------------------------------------------------------------------------
 // step: one wavefront per environment, four environments per block; the grid starts with the
@@ -127,7 +130,7 @@ __global__ __launch_bounds__(BLOCK, GW == 64 ? 5 : 2) void kf_step(uint32_t* __r
     __shared__ float s_lut[LUT_FLOATS];
     const int tid = threadIdx.x, w = tid / GW, l = tid % GW;
     if ((int)blockIdx.x < regen_blocks) {
-        const la::Ticket ticket = la::enter_launch_queue(ls, s_env + 528);
+        const la::Ticket ticket = la::enter_launch_queue(ls, s_env + REGEN_PREFIX_AT);
         regeneration_queue<PERLIN>(envs, maps, ls, ticket.seq, s_env, regen_blocks, luts->perlin_cs);
         la::leave_launch(ls, ticket);
         return;

@@ -23,6 +23,12 @@ struct GenLayout {
     Room room[3][8];          // dungeon (floor 1), sewers (3), vault (4)
     int up[FLOORS][2], down[FLOORS][2];
     uint32_t perm;            // potion colour -> effect, 6 x 3 bits
+    // The built floor being generated, row by row (bit x = column x), see dungeon_row_masks: cells
+    // inside rooms 0..3 and 4..7, cells on corridors 0..3 and 4..6, chest cells; and the five single
+    // cells of a floor as x | y << 8: fountain, the two enchantment tables, ladder up, ladder down
+    // (0xFFFF: this floor has none).
+    uint64_t row_mask[5][W];
+    uint32_t spot[5];
 };
 
 __device__ inline int cave_index(int f) { return f == 2 ? 0 : (f == 5 ? 1 : (f == 6 ? 2 : 3)); }
@@ -80,6 +86,8 @@ __device__ inline int classify_overworld(const GenLayout& L, int Wn, int Mn, int
     if (x == L.down[0][0] && y == L.down[0][1]) return B_PATH | (IT_LADDER_DOWN << 8);
     return b;
 }
+// The cell of a built floor written out test by test.  The generator uses cell_dungeon_masked below, which
+// takes `inside`, `corridor` and the chest test from per-row bit masks; this is what those masks mean.
 __device__ inline int cell_dungeon(const GenLayout& L, int f, int x, int y, int u)
 {
     const Room* R = L.room[dungeon_index(f)];
@@ -100,6 +108,68 @@ __device__ inline int cell_dungeon(const GenLayout& L, int f, int x, int y, int 
     int it = IT_NONE;
     if (x == R[0].cx && y == R[0].cy) { b = B_PATH; it = IT_LADDER_UP; }
     if (x == R[7].cx && y == R[7].cy) { b = B_PATH; it = IT_LADDER_DOWN_BLOCKED; }
+    return b | (it << 8);
+}
+// A built floor as bit masks per row, so that a cell costs a few shifts and tests instead of eight
+// room tests, seven corridor tests and nine single-cell tests.  Part p of row y (five parts, so
+// that 240 threads share the work): rooms 0..3, rooms 4..7 (`inside` of cell_dungeon), corridors
+// 0..3, corridors 4..6 (`corridor`), chests.  The few single cells go to L.spot.
+constexpr int M_ROOMS_A = 0, M_ROOMS_B = 1, M_PATH_A = 2, M_PATH_B = 3, M_CHEST = 4, MASK_PARTS = 5;
+constexpr int SPOT_FOUNTAIN = 0, SPOT_FIRE = 1, SPOT_ICE = 2, SPOT_UP = 3, SPOT_DOWN = 4;
+__device__ inline void dungeon_row_mask(GenLayout& L, int f, int y, int part)
+{
+    const Room* R = L.room[dungeon_index(f)];
+    auto span = [](int a, int b) -> uint64_t { return (~0ull >> (63 - (b - a))) << a; };   // bits a..b, 0 <= a <= b < 64
+    uint64_t m = 0ull;
+    if (part == M_ROOMS_A || part == M_ROOMS_B) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const Room r = R[4 * (part - M_ROOMS_A) + k];
+            if ((unsigned)(y - r.y) < (unsigned)r.h) m |= span(r.x, r.x + r.w - 1);
+        }
+    } else if (part == M_PATH_A || part == M_PATH_B) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int i = 4 * (part - M_PATH_A) + k;
+            if (i < 7) {
+                const int x0 = R[i].cx, y0 = R[i].cy, x1 = R[i + 1].cx, y1 = R[i + 1].cy;
+                if (y == y0) m |= span(min(x0, x1), max(x0, x1));
+                if (y >= min(y0, y1) && y <= max(y0, y1)) m |= 1ull << x1;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 1; i <= 6; ++i) if (y == R[i].cy + 1) m |= 1ull << (R[i].cx + 1);
+    }
+    L.row_mask[CX_IDX(part, MASK_PARTS)][CX_IDX(y, W)] = m;
+}
+__device__ inline void dungeon_spot(GenLayout& L, int f, int k)
+{
+    const Room* R = L.room[dungeon_index(f)];
+    auto at = [](int x, int y) { return (uint32_t)x | ((uint32_t)y << 8); };
+    uint32_t v = 0xFFFFu;
+    if (k == SPOT_FOUNTAIN && f == 1) v = at(R[2].cx - 1, R[2].cy - 1);
+    if (k == SPOT_FIRE && f == 4) v = at(R[3].cx - 1, R[3].cy - 1);
+    if (k == SPOT_ICE && f == 4) v = at(R[4].cx - 1, R[4].cy - 1);
+    if (k == SPOT_UP) v = at(R[0].cx, R[0].cy);
+    if (k == SPOT_DOWN) v = at(R[7].cx, R[7].cy);
+    L.spot[k] = v;
+}
+// cell_dungeon from the masks of its row (shifted so that bit 0 is this cell) and the single cells:
+// the same tests in the same order of precedence.
+__device__ inline int cell_dungeon_masked(const GenLayout& L, int f, int x, int y, int u, bool inside, bool corridor, bool chest)
+{
+    const uint32_t here = (uint32_t)x | ((uint32_t)y << 8);
+    int b = f == 3 ? B_WALL_MOSS : B_WALL;
+    if (inside) b = (f == 3 && u < 12000) ? B_WATER : B_PATH;
+    if (chest) b = B_CHEST;
+    if (here == L.spot[SPOT_FOUNTAIN]) b = B_FOUNTAIN;
+    if (here == L.spot[SPOT_FIRE]) b = B_ENCH_FIRE;
+    if (here == L.spot[SPOT_ICE]) b = B_ENCH_ICE;
+    if (corridor) b = B_PATH;
+    int it = IT_NONE;
+    if (here == L.spot[SPOT_UP]) { b = B_PATH; it = IT_LADDER_UP; }
+    if (here == L.spot[SPOT_DOWN]) { b = B_PATH; it = IT_LADDER_DOWN_BLOCKED; }
     return b | (it << 8);
 }
 __device__ inline int cell_graveyard(int x, int y)
@@ -245,6 +315,11 @@ __device__ __forceinline__ void worldgen_floor_block(uint8_t* __restrict__ maps,
         }
     }
     __syncthreads();
+    if (is_dungeon(f)) {                       // the same floor for the whole block
+        for (int i = tid0; i < MASK_PARTS * W; i += NT) dungeon_row_mask(L, f, i % W, i / W);
+        if (tid0 < 5) dungeon_spot(L, f, tid0);
+        __syncthreads();
+    }
     if (CAN_PERLIN && theta_f != nullptr) {
         for (int i = tid0; i < LAT_TOTAL; i += NT) s_lat[i] = (uint16_t)(s_lat[i] + ((theta_f[i] & 1023u) << 6));
         __syncthreads();
@@ -295,7 +370,10 @@ __device__ __forceinline__ void worldgen_floor_block(uint8_t* __restrict__ maps,
             put(j, classify_overworld(L, Wn, Mn, (int)at8(c8, x + j), (int)at8(f8, x + j), x + j, y, draw(j)));
         });
     } else if (is_dungeon(f)) {
-        cells([&](int j) { put(j, cell_dungeon(L, f, x + j, y, draw(j))); });
+        const int yr = CX_IDX(y, W);                                             // the run lies in one row
+        const uint64_t in = (L.row_mask[M_ROOMS_A][yr] | L.row_mask[M_ROOMS_B][yr]) >> x, path = (L.row_mask[M_PATH_A][yr] | L.row_mask[M_PATH_B][yr]) >> x,
+                       chest = L.row_mask[M_CHEST][yr] >> x;
+        cells([&](int j) { put(j, cell_dungeon_masked(L, f, x + j, y, draw(j), (in >> j) & 1ull, (path >> j) & 1ull, (chest >> j) & 1ull)); });
     } else if (f == 8) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) put(j, cell_graveyard(x + j, y));
