@@ -124,6 +124,7 @@ __device__ __forceinline__ void worldgen_block(uint8_t* __restrict__ map, uint16
                                       const uint16_t* theta = nullptr)
 {
     static_assert(WG_THREADS % NT == 0 && NT >= 64, "block size must divide 512");
+    // runs is 512 (a world) or 256 (half of one): whole wavefronts, and a number of them that divides the eight runs of a row
     const int tid0 = threadIdx.x;
     const int tid = tid0;
     if (tid < LAT_BLOCKS) {
@@ -146,7 +147,13 @@ __device__ __forceinline__ void worldgen_block(uint8_t* __restrict__ map, uint16
     __syncthreads();
     // one run of 8 cells per thread (the callers give a block no more runs than it has threads)
     if (tid0 < runs) {
-    const int tid = first_run + tid0;
+    // Which run a thread takes: a wavefront owns a strip of columns over all rows of the part (one
+    // run wide when the part is the whole world, two when it is half of it) rather than eight whole
+    // rows.  A strip is all plain or all mountain more often than eight rows across the world, so
+    // the terrain rule's branches are skipped more often, and the 16 lanes that fill a map tile are
+    // neighbours.  Only the assignment changes: run `tid` is the same cells and draws as ever.
+    const int waves = runs >> 6, strip = 8 / waves, wl = tid0 & 63, ww = tid0 >> 6;
+    const int tid = first_run + (wl / strip) * 8 + ww * strip + (wl % strip);
     const U4 r = philox4x32_10(env, 1u, episode, (DOM_WORLDGEN << 16) | (uint32_t)tid, seed_lo, seed_hi);
     const int y = tid >> 3, x0 = (tid & 7) << 3;
     const uint16_t* w16 = s_lat;
