@@ -78,3 +78,11 @@ def test_full_game_accepts_only_its_own_options(lib):
     # the state grows linearly and stays 256-byte aligned
     sizes = [binding.craftax_state_bytes(ok, n) for n in (1, 2, 64, 4096)]
     assert all(s % 256 == 0 for s in sizes) and sizes == sorted(sizes)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU is all this build measures: any other count ends with a message, before anything touches a GPU."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0 and "ONE GPU" in (res.stderr + res.stdout) and "{" not in res.stdout

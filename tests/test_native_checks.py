@@ -33,6 +33,17 @@ def test_regeneration_units_are_dealt_out_exactly_once(tmp_path):
     assert "regen_units_test: ok" in _run([exe])
 
 
+def test_public_header_compiles_as_c_and_as_cpp(tmp_path):
+    """include/craftax.h on its own, with warnings as errors, as C11 and as C++17: no HIP or torch type
+    in any signature, every struct complete."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    body = '#include "craftax.h"\nint main(void) { craftax_config c; craftax_metrics m; (void)c; (void)m; return (int)sizeof(craftax_metrics) == 0; }\n'
+    for name, cc, std in (("use.c", "gcc", "-std=c11"), ("use.cpp", "g++", "-std=c++17")):
+        src = tmp_path / name
+        src.write_text(body)
+        _run([cc, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"), "-c", "-o", str(tmp_path / (name + ".o")), str(src)])
+
+
 def test_launch_limit_rule(tmp_path):
     exe = str(tmp_path / "launch_limits_test")
     _run(["g++", "-O1", "-std=c++17", "-Wall", "-Wextra", "-o", exe, os.path.join(NATIVE, "launch_limits_test.cpp")])
