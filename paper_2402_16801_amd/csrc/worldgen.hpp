@@ -117,7 +117,9 @@ constexpr int WG_THREADS = 512;
 // of the 512; a world may be split over several blocks); runs <= NT.
 // PERLIN: the fields are Perlin noise over the same lattices (perlin_cs: the gradient table).
 // theta (may be null; LDS or global, LAT_TOTAL values): angle offsets of a mutated level.
-template <int NT = WG_THREADS, bool PERLIN = false>
+// STRIPS: how the runs are dealt to the wavefronts (see below); the rollout kernel, which is short of
+// registers, keeps the plain order.
+template <int NT = WG_THREADS, bool PERLIN = false, bool STRIPS = true>
 __device__ __forceinline__ void worldgen_block(uint8_t* __restrict__ map, uint16_t* s_lat, uint32_t seed_lo, uint32_t seed_hi,
                                       uint32_t env, uint32_t episode, uint32_t* start_win = nullptr, int first_run = 0,
                                       int runs = WG_THREADS, const uint32_t* __restrict__ perlin_cs = nullptr,
@@ -153,7 +155,7 @@ __device__ __forceinline__ void worldgen_block(uint8_t* __restrict__ map, uint16
     // the terrain rule's branches are skipped more often, and the 16 lanes that fill a map tile are
     // neighbours.  Only the assignment changes: run `tid` is the same cells and draws as ever.
     const int waves = runs >> 6, strip = 8 / waves, wl = tid0 & 63, ww = tid0 >> 6;
-    const int tid = first_run + (wl / strip) * 8 + ww * strip + (wl % strip);
+    const int tid = first_run + (STRIPS ? (wl / strip) * 8 + ww * strip + (wl % strip) : tid0);
     const U4 r = philox4x32_10(env, 1u, episode, (DOM_WORLDGEN << 16) | (uint32_t)tid, seed_lo, seed_hi);
     const int y = tid >> 3, x0 = (tid & 7) << 3;
     const uint16_t* w16 = s_lat;
