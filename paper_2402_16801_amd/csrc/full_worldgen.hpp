@@ -180,6 +180,8 @@ __device__ inline int cell_graveyard(int x, int y)
     if (x == 24 && y == 42) return B_PATH | (IT_LADDER_UP << 8);
     return b;
 }
+// The cell of a cave floor written out test by test.  The generator uses classify_cave_masked below, which takes
+// the clearings and the corridor from a per-row bit mask; this is what that mask means.
 __device__ inline int classify_cave(const GenLayout& L, int f, int Cn, int Fn, int x, int y, int u)
 {
     const int open = f == 6 ? B_FIRE_GRASS : (f == 7 ? B_ICE_GRASS : B_PATH);
@@ -207,6 +209,55 @@ __device__ inline int classify_cave(const GenLayout& L, int f, int Cn, int Fn, i
     int it = IT_NONE;
     if (x == ux && y == uy) { b = B_PATH; it = IT_LADDER_UP; }
     if (x == dx && y == dy) { b = B_PATH; it = IT_LADDER_DOWN_BLOCKED; }
+    return b | (it << 8);
+}
+
+// Row y of a cave floor as one bit mask (L.row_mask[M_CAVE_OPEN]): the cells classify_cave opens whatever
+// the noise says, i.e. the 3 x 3 clearings around the two ladders and the L-shaped corridor between
+// them; the ladders themselves go to L.spot.  classify_cave_masked is classify_cave with those
+// tests taken from the mask: the same rules in the same order.
+constexpr int M_CAVE_OPEN = 0;
+__device__ inline void cave_row_mask(GenLayout& L, int f, int y)
+{
+    const int ux = L.up[f][0], uy = L.up[f][1], dx = L.down[f][0], dy = L.down[f][1];
+    auto span = [](int a, int b) -> uint64_t { return (~0ull >> (63 - (b - a))) << a; };   // bits a..b, 0 <= a <= b < 64
+    uint64_t m = 0ull;
+    if (iabs(y - uy) <= 1) m |= span(ux - 1, ux + 1);
+    if (iabs(y - dy) <= 1) m |= span(dx - 1, dx + 1);
+    if (y == uy) m |= span(min(ux, dx), max(ux, dx));                 // on_corridor: along row uy from ux to dx,
+    if (y >= min(uy, dy) && y <= max(uy, dy)) m |= 1ull << dx;        // then along column dx from uy to dy
+    L.row_mask[M_CAVE_OPEN][CX_IDX(y, W)] = m;
+    if (y == 0) {
+        L.spot[SPOT_UP] = (uint32_t)ux | ((uint32_t)uy << 8);
+        L.spot[SPOT_DOWN] = (uint32_t)dx | ((uint32_t)dy << 8);
+    }
+}
+__device__ inline int classify_cave_masked(const GenLayout& L, int f, int Cn, int Fn, int x, int y, int u, bool opened)
+{
+    const int open = f == 6 ? B_FIRE_GRASS : (f == 7 ? B_ICE_GRASS : B_PATH);
+    int b;
+    if (Cn > 31000) {
+        b = open;
+        if (f == 2 && u < 1500) b = B_STALAGMITE;
+        if (f == 5 && Fn > 44000) b = B_WATER;
+        if (f == 6) { if (Fn > 43000) b = B_LAVA; else if (u < 3000) b = B_FIRE_TREE; }
+        if (f == 7) { if (Fn > 43000) b = B_WATER; else if (u < 3000) b = B_ICE_SHRUB; }
+    } else {
+        b = B_STONE;
+        if (f == 2 || f == 5) {
+            if (u < 5000) b = B_COAL;
+            else if (u < 7500) b = B_IRON;
+            else if (u < 8000) b = B_DIAMOND;
+            else if (u < (f == 2 ? 8600 : 9000)) b = B_SAPPHIRE;
+            else if (u < (f == 2 ? 9200 : 10000)) b = B_RUBY;
+        } else if (f == 6) { if (u < 2500) b = B_RUBY; else if (u < 6000) b = B_COAL; }
+        else { if (u < 2500) b = B_SAPPHIRE; else if (u < 5000) b = B_DIAMOND; }
+    }
+    if (opened) b = open;
+    const uint32_t here = (uint32_t)x | ((uint32_t)y << 8);
+    int it = IT_NONE;
+    if (here == L.spot[SPOT_UP]) { b = B_PATH; it = IT_LADDER_UP; }
+    if (here == L.spot[SPOT_DOWN]) { b = B_PATH; it = IT_LADDER_DOWN_BLOCKED; }
     return b | (it << 8);
 }
 
@@ -319,6 +370,9 @@ __device__ __forceinline__ void worldgen_floor_block(uint8_t* __restrict__ maps,
         for (int i = tid0; i < MASK_PARTS * W; i += NT) dungeon_row_mask(L, f, i % W, i / W);
         if (tid0 < 5) dungeon_spot(L, f, tid0);
         __syncthreads();
+    } else if (is_cave(f)) {
+        if (tid0 < W) cave_row_mask(L, f, tid0);
+        __syncthreads();
     }
     if (CAN_PERLIN && theta_f != nullptr) {
         for (int i = tid0; i < LAT_TOTAL; i += NT) s_lat[i] = (uint16_t)(s_lat[i] + ((theta_f[i] & 1023u) << 6));
@@ -358,9 +412,10 @@ __device__ __forceinline__ void worldgen_floor_block(uint8_t* __restrict__ maps,
                                       (int)cx::perlin<8>(s_lat + 179, 7, perlin_cs, x + j, y), x + j, y, draw(j)));
         });
     } else if (CAN_PERLIN && perlin && is_cave(f)) {
+        const uint64_t opened = L.row_mask[M_CAVE_OPEN][CX_IDX(y, W)] >> x;   // the run lies in one row
         cells([&](int j) {
-            put(j, classify_cave(L, f, (int)cx::perlin<8>(s_lat, 7, perlin_cs, x + j, y), (int)cx::perlin<8>(s_lat + 49, 7, perlin_cs, x + j, y),
-                                 x + j, y, draw(j)));
+            put(j, classify_cave_masked(L, f, (int)cx::perlin<8>(s_lat, 7, perlin_cs, x + j, y), (int)cx::perlin<8>(s_lat + 49, 7, perlin_cs, x + j, y),
+                                        x + j, y, draw(j), (opened >> j) & 1ull));
         });
     } else if (f == 0) {
         const Field8 w16 = field16(s_lat, x, y), m16 = field16(s_lat + 16, x, y);
@@ -379,7 +434,8 @@ __device__ __forceinline__ void worldgen_floor_block(uint8_t* __restrict__ maps,
         for (int j = 0; j < 4; ++j) put(j, cell_graveyard(x + j, y));
     } else {
         const Field8 c8 = field8(s_lat, x, y), f8 = field8(s_lat + 49, x, y);
-        cells([&](int j) { put(j, classify_cave(L, f, (int)at8(c8, x + j), (int)at8(f8, x + j), x + j, y, draw(j))); });
+        const uint64_t opened = L.row_mask[M_CAVE_OPEN][CX_IDX(y, W)] >> x;   // the run lies in one row
+        cells([&](int j) { put(j, classify_cave_masked(L, f, (int)at8(c8, x + j), (int)at8(f8, x + j), x + j, y, draw(j), (opened >> j) & 1ull)); });
     }
     *reinterpret_cast<uint32_t*>(maps + block_off(f, x, y)) = pb;
     *reinterpret_cast<uint32_t*>(maps + il_off(f, x, y)) = pi;
